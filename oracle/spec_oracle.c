@@ -1,0 +1,436 @@
+/*
+ * CPU oracle for the verify pass of speculative sampling with KV caching.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what the hot path
+ * computes.  Only the test-suite, the smoke check and the bench's cpu_baseline leg may call it;
+ * the GPU library never does, and the two share no code.
+ *
+ * What it follows (paper sections):
+ *   - Section 3, Eq. (1): autoregressive sampling p(x_{n+1} | x_1..x_n), token by argmax or sampling.
+ *   - Sections 2 and 4.2: KV caching - per-token keys/values are stored once and reused.
+ *   - Sections 3 and 4.3: speculative sampling - a draft model proposes K tokens, the target model
+ *     scores them in one K+1-row pass and accepts or rejects them so that the target distribution
+ *     is recovered (the rule of Chen et al. that Section 3 credits: accept with probability
+ *     min(1, p/q); on the first rejection resample from norm(max(0, p - q)); bonus token from
+ *     the last row when nothing was rejected).
+ *   - Section 4.4: two caches of different size; truncation of the stale tail is a length write.
+ *
+ * The paper names no architecture beyond a Llama-2 model id (Section 4.1), so the decoder is the
+ * Llama-style one of the synthetic workloads: RMSNorm -> QKV -> rotary embedding (split-half
+ * pairing) -> causal attention over the cache -> O projection + residual -> RMSNorm ->
+ * SwiGLU FFN + residual; final RMSNorm -> LM head.  No biases, untied embedding, MHA.
+ *
+ * Precision: activations are fp32; every dot product, sum and transcendental is evaluated in fp64
+ * in a fixed sequential order and rounded once to fp32; each output row is computed on its own,
+ * so a result never depends on how many rows share a call.  With bf16 storage the only roundings
+ * to bf16 (nearest-even) are the ones storage mandates: weights (given as bf16) and KV entries.
+ *
+ * Parity pins: every exported function is pinned by tests/test_oracle_*.py (library routines,
+ * closed forms, invariants, brute force); none is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------ storage types */
+
+static inline float bf16_to_f32(uint16_t b) {
+    uint32_t u = ((uint32_t)b) << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+/* round-to-nearest-even fp32 -> bf16 (NaN kept quiet) */
+uint16_t orc_f32_to_bf16(float f) {
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    uint32_t lsb = (u >> 16) & 1u;
+    u += 0x7fffu + lsb;
+    return (uint16_t)(u >> 16);
+}
+
+float orc_bf16_to_f32(uint16_t b) { return bf16_to_f32(b); }
+
+/* element idx of a weight / cache array held in the storage type */
+static inline double st_get(const void *a, int is_bf16, size_t idx) {
+    return is_bf16 ? (double)bf16_to_f32(((const uint16_t *)a)[idx]) : (double)((const float *)a)[idx];
+}
+
+static inline void st_put(void *a, int is_bf16, size_t idx, float v) {
+    if (is_bf16) ((uint16_t *)a)[idx] = orc_f32_to_bf16(v);
+    else ((float *)a)[idx] = v;
+}
+
+int orc_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ------------------------------------------------------------------ decoder pieces */
+
+/* RMSNorm: out_i = x_i * g_i / sqrt(mean(x^2) + eps) */
+void orc_rmsnorm(const float *x, const float *g, int n, double eps, float *out) {
+    double ss = 0.0;
+    for (int i = 0; i < n; ++i) ss += (double)x[i] * (double)x[i];
+    double r = 1.0 / sqrt(ss / (double)n + eps);
+    for (int i = 0; i < n; ++i) out[i] = (float)((double)x[i] * r * (double)g[i]);
+}
+
+/* y_n = sum_k W[n][k] x_k, W row-major [N][K] in the storage type ("linear layers", Section 3) */
+void orc_linear(const void *W, int is_bf16, const float *x, int N, int K, float *y) {
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        double acc = 0.0;
+        size_t base = (size_t)n * (size_t)K;
+        for (int k = 0; k < K; ++k) acc += st_get(W, is_bf16, base + k) * (double)x[k];
+        y[n] = (float)acc;
+    }
+}
+
+/* Rotary embedding of one head vector at absolute position pos, split-half pairing:
+ * (v_j, v_{j+hd/2}) rotated by angle pos * base^(-2j/hd), j = 0..hd/2-1. */
+void orc_rope(float *v, int hd, int64_t pos, double base) {
+    int half = hd / 2;
+    for (int j = 0; j < half; ++j) {
+        double ang = (double)pos * pow(base, -2.0 * (double)j / (double)hd);
+        double c = cos(ang), s = sin(ang);
+        double a = v[j], b = v[j + half];
+        v[j] = (float)(a * c - b * s);
+        v[j + half] = (float)(a * s + b * c);
+    }
+}
+
+static inline double silu(double x) { return x / (1.0 + exp(-x)); }
+
+/* softmax(logits / T) in fp64, rounded once to fp32 */
+void orc_softmax(const float *logits, int V, double T, float *out) {
+    double m = -INFINITY;
+    for (int v = 0; v < V; ++v) {
+        double x = (double)logits[v] / T;
+        if (x > m) m = x;
+    }
+    double Z = 0.0;
+    for (int v = 0; v < V; ++v) Z += exp((double)logits[v] / T - m);
+    for (int v = 0; v < V; ++v) out[v] = (float)(exp((double)logits[v] / T - m) / Z);
+}
+
+/* index of the largest element, lowest index on ties */
+int orc_argmax(const float *x, int V) {
+    int best = 0;
+    for (int v = 1; v < V; ++v)
+        if (x[v] > x[best]) best = v;
+    return best;
+}
+
+/* ------------------------------------------------------------------ model + cache */
+
+typedef struct {
+    const void *wq, *wk, *wv, *wo, *wg, *wu, *wd;
+    const float *g1, *g2;
+} orc_layer;
+
+typedef struct {
+    int n_layers, d_model, n_heads, head_dim, d_ff, vocab, is_bf16;
+    double rope_base, rms_eps;
+    orc_layer *layers;
+    const void *embed, *lm_head;
+    const float *gf;
+} orc_model;
+
+/* KV cache of ONE sequence (Sections 2, 4.2): per layer, keys (already rotated) and values of
+ * every past position, row-major [max_seq][n_heads*head_dim], in the storage type. */
+typedef struct {
+    int n_layers, max_seq, width, is_bf16;
+    int len;
+    void **k, **v;
+} orc_kv;
+
+orc_model *orc_model_new(int n_layers, int d_model, int n_heads, int head_dim, int d_ff, int vocab,
+                         double rope_base, double rms_eps, int is_bf16) {
+    orc_model *m = (orc_model *)calloc(1, sizeof(orc_model));
+    m->n_layers = n_layers; m->d_model = d_model; m->n_heads = n_heads; m->head_dim = head_dim;
+    m->d_ff = d_ff; m->vocab = vocab; m->rope_base = rope_base; m->rms_eps = rms_eps;
+    m->is_bf16 = is_bf16;
+    m->layers = (orc_layer *)calloc((size_t)n_layers, sizeof(orc_layer));
+    return m;
+}
+
+void orc_model_set_layer(orc_model *m, int l, const void *wq, const void *wk, const void *wv,
+                         const void *wo, const void *wg, const void *wu, const void *wd,
+                         const float *g1, const float *g2) {
+    orc_layer *L = &m->layers[l];
+    L->wq = wq; L->wk = wk; L->wv = wv; L->wo = wo; L->wg = wg; L->wu = wu; L->wd = wd;
+    L->g1 = g1; L->g2 = g2;
+}
+
+void orc_model_set_io(orc_model *m, const void *embed, const float *gf, const void *lm_head) {
+    m->embed = embed; m->gf = gf; m->lm_head = lm_head;
+}
+
+void orc_model_free(orc_model *m) {
+    if (!m) return;
+    free(m->layers);
+    free(m);
+}
+
+orc_kv *orc_kv_new(const orc_model *m, int max_seq) {
+    orc_kv *c = (orc_kv *)calloc(1, sizeof(orc_kv));
+    c->n_layers = m->n_layers; c->max_seq = max_seq; c->width = m->n_heads * m->head_dim;
+    c->is_bf16 = m->is_bf16; c->len = 0;
+    c->k = (void **)calloc((size_t)m->n_layers, sizeof(void *));
+    c->v = (void **)calloc((size_t)m->n_layers, sizeof(void *));
+    size_t esz = m->is_bf16 ? 2 : 4;
+    for (int l = 0; l < m->n_layers; ++l) {
+        c->k[l] = calloc((size_t)max_seq * (size_t)c->width, esz);
+        c->v[l] = calloc((size_t)max_seq * (size_t)c->width, esz);
+    }
+    return c;
+}
+
+void orc_kv_free(orc_kv *c) {
+    if (!c) return;
+    for (int l = 0; l < c->n_layers; ++l) { free(c->k[l]); free(c->v[l]); }
+    free(c->k); free(c->v); free(c);
+}
+
+int orc_kv_len(const orc_kv *c) { return c->len; }
+
+/* Truncation (Section 4.4): the stale tail is dropped by moving the length; no data moves. */
+int orc_kv_set_len(orc_kv *c, int len) {
+    if (len < 0 || len > c->len) return -1;
+    c->len = len;
+    return 0;
+}
+
+/* Raw append of n_rows already-rotated K rows and V rows (storage type) to one layer at
+ * positions pos0..pos0+n_rows-1.  The length moves only through orc_kv_advance. */
+int orc_kv_write(orc_kv *c, int layer, int pos0, const void *k_rows, const void *v_rows, int n_rows) {
+    if (layer < 0 || layer >= c->n_layers || pos0 < 0 || pos0 + n_rows > c->max_seq) return -1;
+    size_t esz = c->is_bf16 ? 2 : 4;
+    size_t off = (size_t)pos0 * (size_t)c->width * esz, n = (size_t)n_rows * (size_t)c->width * esz;
+    memcpy((char *)c->k[layer] + off, k_rows, n);
+    memcpy((char *)c->v[layer] + off, v_rows, n);
+    return 0;
+}
+
+int orc_kv_advance(orc_kv *c, int n_rows) {
+    if (c->len + n_rows > c->max_seq) return -1;
+    c->len += n_rows;
+    return 0;
+}
+
+/* Causal attention of one query row (all heads) at absolute position pos over cache positions
+ * 0..pos of one layer: s_j = q.k_j / sqrt(hd), P = softmax_j(s), o = sum_j P_j v_j. */
+static void attention_row(const orc_model *m, const orc_kv *c, int layer, const float *q, int pos,
+                          float *o) {
+    int H = m->n_heads, hd = m->head_dim, W = c->width;
+    double scale = 1.0 / sqrt((double)hd);
+#pragma omp parallel for schedule(static)
+    for (int h = 0; h < H; ++h) {
+        int n = pos + 1;
+        double *s = (double *)malloc((size_t)n * sizeof(double));
+        double mx = -INFINITY;
+        for (int j = 0; j < n; ++j) {
+            double acc = 0.0;
+            for (int e = 0; e < hd; ++e)
+                acc += (double)q[h * hd + e] * st_get(c->k[layer], c->is_bf16, (size_t)j * W + h * hd + e);
+            s[j] = acc * scale;
+            if (s[j] > mx) mx = s[j];
+        }
+        double Z = 0.0;
+        for (int j = 0; j < n; ++j) { s[j] = exp(s[j] - mx); Z += s[j]; }
+        for (int e = 0; e < hd; ++e) {
+            double acc = 0.0;
+            for (int j = 0; j < n; ++j)
+                acc += s[j] * st_get(c->v[layer], c->is_bf16, (size_t)j * W + h * hd + e);
+            o[h * hd + e] = (float)(acc / Z);
+        }
+        free(s);
+    }
+}
+
+/* All decoder layers over M new rows of hidden state h [M][d] (in place) at positions
+ * len..len+M-1: appends the rows' K/V to the cache and advances its length by M.
+ * This is the K+1-row pass of Section 3 when h holds [last committed token, d_1..d_K]. */
+int orc_layers_forward(const orc_model *m, orc_kv *c, float *h, int M) {
+    int d = m->d_model, H = m->n_heads, hd = m->head_dim, F = m->d_ff, W = H * hd;
+    int bf = m->is_bf16;
+    if (c->len + M > c->max_seq) return -1;
+    float *a = (float *)malloc(sizeof(float) * (size_t)d);
+    float *q = (float *)malloc(sizeof(float) * (size_t)W * (size_t)M);
+    float *kk = (float *)malloc(sizeof(float) * (size_t)W);
+    float *vv = (float *)malloc(sizeof(float) * (size_t)W);
+    float *o = (float *)malloc(sizeof(float) * (size_t)W);
+    float *t = (float *)malloc(sizeof(float) * (size_t)d);
+    float *gg = (float *)malloc(sizeof(float) * (size_t)F);
+    float *uu = (float *)malloc(sizeof(float) * (size_t)F);
+    for (int l = 0; l < m->n_layers; ++l) {
+        const orc_layer *L = &m->layers[l];
+        /* projections + rotary + cache append, row by row */
+        for (int i = 0; i < M; ++i) {
+            int pos = c->len + i;
+            orc_rmsnorm(h + (size_t)i * d, L->g1, d, m->rms_eps, a);
+            orc_linear(L->wq, bf, a, W, d, q + (size_t)i * W);
+            orc_linear(L->wk, bf, a, W, d, kk);
+            orc_linear(L->wv, bf, a, W, d, vv);
+            for (int hh = 0; hh < H; ++hh) {
+                orc_rope(q + (size_t)i * W + hh * hd, hd, pos, m->rope_base);
+                orc_rope(kk + hh * hd, hd, pos, m->rope_base);
+            }
+            for (int e = 0; e < W; ++e) {
+                st_put(c->k[l], bf, (size_t)pos * W + e, kk[e]);
+                st_put(c->v[l], bf, (size_t)pos * W + e, vv[e]);
+            }
+        }
+        /* attention reads every key/value, the row's own included, back from the cache */
+        for (int i = 0; i < M; ++i) {
+            float *hi = h + (size_t)i * d;
+            attention_row(m, c, l, q + (size_t)i * W, c->len + i, o);
+            orc_linear(L->wo, bf, o, d, W, t);
+            for (int e = 0; e < d; ++e) hi[e] = hi[e] + t[e];
+            orc_rmsnorm(hi, L->g2, d, m->rms_eps, a);
+            orc_linear(L->wg, bf, a, F, d, gg);
+            orc_linear(L->wu, bf, a, F, d, uu);
+            for (int e = 0; e < F; ++e) gg[e] = (float)(silu((double)gg[e]) * (double)uu[e]);
+            orc_linear(L->wd, bf, gg, d, F, t);
+            for (int e = 0; e < d; ++e) hi[e] = hi[e] + t[e];
+        }
+    }
+    c->len += M;
+    free(a); free(q); free(kk); free(vv); free(o); free(t); free(gg); free(uu);
+    return 0;
+}
+
+/* h_i = E[token_i] */
+int orc_embed(const orc_model *m, const int32_t *tokens, int M, float *h) {
+    for (int i = 0; i < M; ++i) {
+        if (tokens[i] < 0 || tokens[i] >= m->vocab) return -1;
+        for (int e = 0; e < m->d_model; ++e)
+            h[(size_t)i * m->d_model + e] = (float)st_get(m->embed, m->is_bf16, (size_t)tokens[i] * m->d_model + e);
+    }
+    return 0;
+}
+
+/* logits_i = RMSNorm(h_i, gf) . W_lm^T */
+void orc_head(const orc_model *m, const float *h, int M, float *logits) {
+    float *a = (float *)malloc(sizeof(float) * (size_t)m->d_model);
+    for (int i = 0; i < M; ++i) {
+        orc_rmsnorm(h + (size_t)i * m->d_model, m->gf, m->d_model, m->rms_eps, a);
+        orc_linear(m->lm_head, m->is_bf16, a, m->vocab, m->d_model, logits + (size_t)i * m->vocab);
+    }
+    free(a);
+}
+
+/* Forward over M token rows against the cache -> logits [M][vocab] (may be NULL to skip the head). */
+int orc_forward(const orc_model *m, orc_kv *c, const int32_t *tokens, int M, float *logits) {
+    float *h = (float *)malloc(sizeof(float) * (size_t)M * (size_t)m->d_model);
+    int rc = orc_embed(m, tokens, M, h);
+    if (rc == 0) rc = orc_layers_forward(m, c, h, M);
+    if (rc == 0 && logits) orc_head(m, h, M, logits);
+    free(h);
+    return rc;
+}
+
+/* ------------------------------------------------------------------ accept / resample */
+
+/* Bernoulli(min(1, p/q)) realised without a division, in fp32:
+ * accept <=> p >= q  or  fl32(u * q) < p.   q = 0 accepts (p >= q). */
+int orc_accept(float u, float p, float q) {
+    if (p >= q) return 1;
+    volatile float t = u * q; /* one IEEE fp32 multiply, round-to-nearest-even, never fused */
+    return t < p;
+}
+
+/* fixed-point weight of a probability-like fp32 value r in [0, 1]: trunc(r * 2^32) */
+static inline uint64_t fx_weight(float r) {
+    if (!(r > 0.0f)) return 0;
+    return (uint64_t)((double)r * 4294967296.0);
+}
+
+static inline float residual(float p, float q) {
+    volatile float r = p - q; /* one fp32 subtract */
+    return r > 0.0f ? r : 0.0f;
+}
+
+/* Integer inverse CDF.  Weights w_v are given by the callback-free form below: kind 0 uses
+ * w_v = fx(p_v), kind 1 uses w_v = fx(max(0, p_v - q_v)).  u is a multiple of 2^-24 in [0,1).
+ * S = sum w_v; threshold T = floor(m * S / 2^24) with m = u * 2^24; the result is the smallest v
+ * whose inclusive prefix sum exceeds T.  Returns -1 when S = 0. */
+static int inv_cdf(const float *p, const float *q, int V, float u) {
+    uint64_t S = 0;
+    for (int v = 0; v < V; ++v) S += q ? fx_weight(residual(p[v], q[v])) : fx_weight(p[v]);
+    if (S == 0) return -1;
+    uint64_t mant = (uint64_t)((double)u * 16777216.0);
+    unsigned __int128 prod = (unsigned __int128)mant * (unsigned __int128)S;
+    uint64_t T = (uint64_t)(prod >> 24);
+    uint64_t C = 0;
+    for (int v = 0; v < V; ++v) {
+        C += q ? fx_weight(residual(p[v], q[v])) : fx_weight(p[v]);
+        if (C > T) return v;
+    }
+    return V - 1; /* unreachable: T < S */
+}
+
+/* token ~ p by the integer inverse CDF; argmax (lowest index) when every weight quantises to 0 */
+int orc_sample(const float *p, int V, float u) {
+    int t = inv_cdf(p, NULL, V, u);
+    return t >= 0 ? t : orc_argmax(p, V);
+}
+
+/* token ~ norm(max(0, p - q)); falls back to orc_sample(p) when the residual quantises to 0 */
+int orc_sample_residual(const float *p, const float *q, int V, float u) {
+    int t = inv_cdf(p, q, V, u);
+    return t >= 0 ? t : orc_sample(p, V, u);
+}
+
+/* The modified rejection step (Sections 3, 4.3) for a batch of sequences.
+ * p [B][K+1][V], q [B][K][V] probabilities; draft [B][K]; u [B][K+1]: u[b][i<K] decides draft
+ * token i, u[b][K] drives the one sampling that happens (residual resample or bonus).
+ * n_accepted[b] = number of leading accepted draft tokens, next[b] = the token that follows. */
+int orc_speculative_accept(const float *p, const float *q, const int32_t *draft, const float *u,
+                           int B, int K, int V, int32_t *n_accepted, int32_t *next) {
+    for (int b = 0; b < B; ++b) {
+        const float *pb = p + (size_t)b * (K + 1) * V;
+        const float *qb = q + (size_t)b * K * V;
+        int a = 0;
+        for (int i = 0; i < K; ++i) {
+            int d = draft[b * K + i];
+            if (d < 0 || d >= V) return -1;
+            if (!orc_accept(u[b * (K + 1) + i], pb[(size_t)i * V + d], qb[(size_t)i * V + d])) break;
+            ++a;
+        }
+        float us = u[b * (K + 1) + K];
+        n_accepted[b] = a;
+        if (a < K) next[b] = orc_sample_residual(pb + (size_t)a * V, qb + (size_t)a * V, V, us);
+        else next[b] = orc_sample(pb + (size_t)K * V, V, us);
+    }
+    return 0;
+}
+
+/* Greedy (argmax) mode: p and q are one-hot at their argmax, so a draft token is accepted iff it
+ * is the target's argmax, and the next token is the target's argmax at the first mismatch (or of
+ * the bonus row).  p_logits [B][K+1][V]. */
+int orc_greedy_accept(const float *p_logits, const int32_t *draft, int B, int K, int V,
+                      int32_t *n_accepted, int32_t *next) {
+    for (int b = 0; b < B; ++b) {
+        const float *pb = p_logits + (size_t)b * (K + 1) * V;
+        int a = 0;
+        for (int i = 0; i < K; ++i) {
+            if (draft[b * K + i] != orc_argmax(pb + (size_t)i * V, V)) break;
+            ++a;
+        }
+        n_accepted[b] = a;
+        next[b] = orc_argmax(pb + (size_t)a * V, V);
+    }
+    return 0;
+}
