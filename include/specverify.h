@@ -1,0 +1,187 @@
+/*
+ * specverify - the verify pass of speculative sampling with KV caching on one MI355X (gfx950).
+ *
+ * C ABI of the GPU library.  Every pointer marked "dev" is device memory owned by the caller
+ * (for instance a PyTorch allocation); everything marked "host" is host memory.  The library
+ * never frees caller memory.  `stream` is a hipStream_t passed as void* (NULL = the null
+ * stream); all work of a call is enqueued on it and, unless a call says otherwise, nothing
+ * synchronises with the host.  Handles are not thread-safe: one stream per handle at a time.
+ *
+ * Return value of every call: SS_OK (0) or a negative code.  Arguments are validated on the
+ * host before anything is launched, so SS_EINVAL / SS_ECAPACITY never leave partial device
+ * state behind.  ss_last_error() returns a message for the calling thread's last failure.
+ * Values that only the device sees (token ids) are clamped into range by the kernels and the
+ * event is recorded in a device status word readable through ss_device_status().
+ *
+ * Method references are to the paper's sections: Section 3 (autoregressive vs speculative
+ * sampling, the K-rows-for-the-price-of-one premise, recovery of the target distribution),
+ * Sections 2/4.2 (KV caching), Section 4.3 (draft proposes, target accepts or rejects),
+ * Section 4.4 (two caches of different size; the target cache goes stale and is rolled back).
+ */
+#ifndef SPECVERIFY_H
+#define SPECVERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SS_OK 0
+#define SS_EINVAL (-1)    /* NULL pointer, bad shape, unsupported size */
+#define SS_ECAPACITY (-2) /* KV cache or workspace too small for the request */
+#define SS_EHIP (-3)      /* a HIP runtime call failed; see ss_last_error() */
+
+#define SS_DTYPE_F32 0
+#define SS_DTYPE_BF16 1
+
+#define SS_MAX_ROWS_PER_SEQ 16 /* M = K + 1 query rows per sequence in one call */
+
+typedef void *ss_stream; /* hipStream_t */
+
+/* Decoder shape (Llama style: RMSNorm, rotary embedding with split-half pairing, MHA, SwiGLU,
+ * no biases, untied LM head).  head_dim must be a multiple of 32, d_model and d_ff multiples of
+ * 8 (bf16) or 4 (f32).  dtype is the storage type of weights and of the KV cache. */
+typedef struct {
+    int32_t n_layers, d_model, n_heads, head_dim, d_ff, vocab;
+    float rope_base, rms_eps;
+    int32_t dtype;    /* SS_DTYPE_F32 | SS_DTYPE_BF16 */
+    int32_t max_rows; /* largest batch * M any call on this model will pass */
+    int32_t max_pos;  /* rotary table length: positions 0..max_pos-1 */
+} ss_model_cfg;
+
+/* One layer's weights, dev pointers, row-major [out_features][in_features] in the storage type:
+ *   wqkv [3*H*hd][d]  rows 0..H*hd-1 = W_q, then W_k, then W_v
+ *   wo   [d][H*hd]
+ *   wgu  [2*F][d]     rows 0..F-1 = W_gate, rows F..2F-1 = W_up
+ *   wd   [d][F]
+ *   g1, g2 [d] fp32   RMSNorm gains before attention / before the FFN */
+typedef struct {
+    const void *wqkv, *wo, *wgu, *wd;
+    const float *g1, *g2;
+} ss_layer_weights;
+
+typedef struct {
+    const void *embed;              /* dev [vocab][d], storage type */
+    const ss_layer_weights *layers; /* host array [n_layers] of dev pointers */
+    const float *gf;                /* dev [d] fp32 final RMSNorm gain */
+    const void *lm_head;            /* dev [vocab][d], storage type */
+} ss_weights;
+
+typedef struct ss_model ss_model;
+typedef struct ss_kv_cache ss_kv_cache;
+
+const char *ss_last_error(void);
+
+/* Reads and clears the device status word of `model` (synchronises `stream`).
+ * bit 0: a token id outside [0, vocab) reached a kernel and was clamped. */
+int ss_device_status(ss_model *model, ss_stream stream, int32_t *status_host);
+
+/* ---- model -------------------------------------------------------------------------------
+ * Creates a handle over caller-owned weights (which must outlive it) and allocates the
+ * model's activation workspace and rotary table on the current device (the only allocations
+ * the forward path ever makes).  A draft that reuses the target's first layers is simply a
+ * second model whose pointers alias the target's. */
+int ss_model_create(const ss_model_cfg *cfg, const ss_weights *weights, ss_model **out);
+int ss_model_destroy(ss_model *model);
+
+/* ---- KV cache (Sections 2, 4.2, 4.4) --------------------------------------------------------
+ * kv_cache_alloc: a contiguous, page-free cache for `batch` sequences of up to `max_seq`
+ * positions in the model's storage type, allocated (and zero-filled) by the library together
+ * with a device array len[batch] of current lengths (all 0).
+ * Device layout per layer l, sequence b, head h (S = max_seq rounded up to 64):
+ *   K[l][b][h][S][hd]           keys, already rotated, one row per position
+ *   V[l][b][h][S/64][hd][64]    values, transposed inside blocks of 64 positions */
+int ss_kv_cache_alloc(const ss_model *model, int32_t batch, int32_t max_seq, ss_kv_cache **out);
+int ss_kv_cache_free(ss_kv_cache *kv);
+size_t ss_kv_cache_bytes(const ss_model *model, int32_t batch, int32_t max_seq);
+
+/* kv_cache_append: raw append for one sequence and one layer of n_rows rows of already-rotated
+ * keys and of values, dev [n_rows][H*hd] in the storage type, at positions pos0..pos0+n_rows-1.
+ * Lengths do not move; call ss_kv_cache_set_len once all layers are written.  Used to build an
+ * existing context; ss_verify_forward / ss_draft_step append their own rows. */
+int ss_kv_cache_append(ss_kv_cache *kv, int32_t layer, int32_t seq, int32_t pos0, const void *k_dev,
+                       const void *v_dev, int32_t n_rows, ss_stream stream);
+
+/* Sets every sequence's length from a host array [batch] (0 <= len <= max_seq).  Rows past a
+ * length are dead and get overwritten by later appends: truncation moves no data. */
+int ss_kv_cache_set_len(ss_kv_cache *kv, const int32_t *len_host, ss_stream stream);
+/* Copies the device lengths to a host array [batch]; synchronises `stream`. */
+int ss_kv_cache_get_len(ss_kv_cache *kv, int32_t *len_host, ss_stream stream);
+
+/* Roll-back after the rejection step, entirely on the device: a verify call appended M rows per
+ * sequence, of which only the first n_accepted[b] + 1 (the last committed token and the accepted
+ * draft tokens) stay:  len[b] -= M - 1 - n_accepted[b].  n_accepted_dev is dev int32 [batch]
+ * with 0 <= n_accepted[b] <= M - 1 (values outside are clamped).  The library keeps a host-side upper
+ * bound of every length for its capacity checks; n_accepted_host (host int32 [batch], may be NULL)
+ * lets it keep that bound exact, otherwise the bound stays at the unrolled length until the next
+ * ss_kv_cache_get_len / ss_kv_cache_set_len. */
+int ss_kv_cache_rollback(ss_kv_cache *kv, const int32_t *n_accepted_dev, const int32_t *n_accepted_host,
+                         int32_t M, ss_stream stream);
+
+/* ---- target verify pass (Section 3: K draft tokens + 1 bonus row in one pass) ---------------
+ * tokens_dev int32 [batch][M] = [last committed token, d_1..d_K] per sequence, 1 <= M <= 16.
+ * Runs the decoder over the batch*M rows at positions len[b]..len[b]+M-1, appends their keys
+ * and values to the cache (len[b] += M) and writes logits_dev fp32 [batch][M][vocab].
+ * Also serves prefill in chunks of <= 16 rows. logits_dev may be NULL (cache fill only). */
+int ss_verify_forward(ss_model *model, ss_kv_cache *kv, const int32_t *tokens_dev, int32_t batch,
+                      int32_t M, float *logits_dev, ss_stream stream);
+
+/* The decoder layers alone over given hidden rows h_dev fp32 [batch*M][d] (updated in place):
+ * everything ss_verify_forward does between the embedding and the final norm. */
+int ss_decoder_layers_forward(ss_model *model, ss_kv_cache *kv, float *h_dev, int32_t batch, int32_t M,
+                              ss_stream stream);
+
+/* ---- draft step (Section 4.3: the draft model proposes one token per call) ------------------
+ * tokens_dev int32 [batch][m], m in {1..16} (m = 2 is the catch-up after a fully accepted step).
+ * Runs `draft` over the rows, takes the last row's logits of each sequence, and
+ *   temperature > 0 : q = softmax(logits / temperature) written to q_rows_dev + b*ldq (fp32
+ *                     [vocab]); token ~ q by the integer inverse CDF with uniform u_dev[b]
+ *   temperature == 0: token = argmax (lowest index on ties); q_rows_dev and u_dev may be NULL.
+ * token_out_dev int32 [batch].  Calling it on the target model is an autoregressive decode step. */
+int ss_draft_step(ss_model *draft, ss_kv_cache *draft_kv, const int32_t *tokens_dev, int32_t batch,
+                  int32_t m, float temperature, const float *u_dev, float *q_rows_dev, int64_t ldq,
+                  int32_t *token_out_dev, ss_stream stream);
+
+/* ---- softmax (per-row statistics by wavefront reductions over the vocabulary) ---------------
+ * probs_dev[r][v] = exp(logits[r][v]/T - max_r) / sum_v exp(...), fp32 [rows][vocab]. */
+int ss_softmax(const float *logits_dev, int32_t rows, int32_t vocab, float temperature, float *probs_dev,
+               ss_stream stream);
+
+/* ---- modified rejection step (Sections 3, 4.3) -----------------------------------------------
+ * p_dev fp32 [batch][K+1][vocab] target probabilities, q_dev fp32 [batch][K][vocab] draft
+ * probabilities, draft_tokens_dev int32 [batch][K], uniforms_dev fp32 [batch][K+1] (multiples of
+ * 2^-24 in [0,1)).  For i = 0..K-1 in order, draft token d_i is accepted iff
+ *     p_i(d_i) >= q_i(d_i)  or  fl32(u_i * q_i(d_i)) < p_i(d_i)         (probability min(1, p/q))
+ * stopping at the first rejection; n_accepted[b] = a.  Then with u = uniforms[b][K]:
+ *     a < K : next ~ norm(max(0, p_a - q_a));  a = K : next ~ p_K
+ * by an integer inverse CDF: w_v = trunc(r_v * 2^32), S = sum w_v, threshold = (u*2^24 * S) >> 24,
+ * token = smallest v whose inclusive prefix sum exceeds the threshold.  If the residual weights
+ * are all 0 the target row itself is sampled; if those are all 0 too, its argmax.  The result is
+ * a pure function of the input bits.  K may be 0.  n_accepted_dev, next_token_dev: int32 [batch]. */
+int ss_speculative_accept(const float *p_dev, const float *q_dev, const int32_t *draft_tokens_dev,
+                          const float *uniforms_dev, int32_t batch, int32_t K, int32_t vocab,
+                          int32_t *n_accepted_dev, int32_t *next_token_dev, ss_stream stream);
+
+/* Same step straight from logits: p = softmax(p_logits/T), q = softmax(q_logits/T) are never
+ * materialised (one read of all logits for the row statistics, then a re-read of the one or two
+ * rows the sampling needs).  Returns exactly what ss_speculative_accept returns on the
+ * probabilities ss_softmax would produce.  p_out_dev / q_out_dev, if not NULL, receive those
+ * probabilities ([batch][K+1][vocab] / [batch][K][vocab]).  temperature > 0. */
+int ss_speculative_accept_logits(const float *p_logits_dev, const float *q_logits_dev, float temperature,
+                                 const int32_t *draft_tokens_dev, const float *uniforms_dev,
+                                 int32_t batch, int32_t K, int32_t vocab, int32_t *n_accepted_dev,
+                                 int32_t *next_token_dev, float *p_out_dev, float *q_out_dev,
+                                 ss_stream stream);
+
+/* Greedy mode (argmax selection, Section 3): a draft token is accepted iff it equals the argmax
+ * of its target row (lowest index on ties); next = argmax of the first mismatching row, or of the
+ * bonus row.  p_logits_dev fp32 [batch][K+1][vocab]. */
+int ss_greedy_accept(const float *p_logits_dev, const int32_t *draft_tokens_dev, int32_t batch, int32_t K,
+                     int32_t vocab, int32_t *n_accepted_dev, int32_t *next_token_dev, ss_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECVERIFY_H */

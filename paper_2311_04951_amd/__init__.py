@@ -1,0 +1,294 @@
+"""Python binding of libspecverify.so (C ABI in include/specverify.h).
+
+Argument marshalling only: every function here has the name of the C entry point it calls, takes
+torch tensors (device memory) where the C call takes device pointers, and raises SpecVerifyError
+on a negative return code.  PyTorch is used for device memory and streams, nothing else; there is
+no CPU fallback - importing works without a GPU, calling does not.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libspecverify.so")
+
+SS_OK, SS_EINVAL, SS_ECAPACITY, SS_EHIP = 0, -1, -2, -3
+SS_DTYPE_F32, SS_DTYPE_BF16 = 0, 1
+SS_MAX_ROWS_PER_SEQ = 16
+
+EXPORTS = [
+    "ss_last_error", "ss_device_status", "ss_model_create", "ss_model_destroy", "ss_kv_cache_alloc",
+    "ss_kv_cache_free", "ss_kv_cache_bytes", "ss_kv_cache_append", "ss_kv_cache_set_len",
+    "ss_kv_cache_get_len", "ss_kv_cache_rollback", "ss_verify_forward", "ss_decoder_layers_forward",
+    "ss_draft_step", "ss_softmax", "ss_speculative_accept", "ss_speculative_accept_logits",
+    "ss_greedy_accept",
+]
+
+
+class SpecVerifyError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"specverify error {code}: {msg}")
+        self.code = code
+
+
+class _Cfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "head_dim", "d_ff", "vocab")] + \
+               [("rope_base", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int32),
+                ("max_rows", C.c_int32), ("max_pos", C.c_int32)]
+
+
+class _LayerW(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("wqkv", "wo", "wgu", "wd", "g1", "g2")]
+
+
+class _Weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("layers", C.POINTER(_LayerW)), ("gf", C.c_void_p), ("lm_head", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """Loads the built library; fails loudly when it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                              "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+        L.ss_last_error.restype = C.c_char_p
+        L.ss_kv_cache_bytes.restype = C.c_size_t
+        sig = {
+            "ss_device_status": [vp, vp, vp],
+            "ss_model_create": [C.POINTER(_Cfg), C.POINTER(_Weights), C.POINTER(vp)],
+            "ss_model_destroy": [vp],
+            "ss_kv_cache_alloc": [vp, i32, i32, C.POINTER(vp)],
+            "ss_kv_cache_free": [vp],
+            "ss_kv_cache_bytes": [vp, i32, i32],
+            "ss_kv_cache_append": [vp, i32, i32, i32, vp, vp, i32, vp],
+            "ss_kv_cache_set_len": [vp, vp, vp],
+            "ss_kv_cache_get_len": [vp, vp, vp],
+            "ss_kv_cache_rollback": [vp, vp, vp, i32, vp],
+            "ss_verify_forward": [vp, vp, vp, i32, i32, vp, vp],
+            "ss_decoder_layers_forward": [vp, vp, vp, i32, i32, vp],
+            "ss_draft_step": [vp, vp, vp, i32, i32, f32, vp, vp, i64, vp, vp],
+            "ss_softmax": [vp, i32, i32, f32, vp, vp],
+            "ss_speculative_accept": [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp],
+            "ss_speculative_accept_logits": [vp, vp, f32, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp],
+            "ss_greedy_accept": [vp, vp, i32, i32, i32, vp, vp, vp],
+        }
+        for name, args in sig.items():
+            getattr(L, name).argtypes = args
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise SpecVerifyError(rc, lib().ss_last_error().decode())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _dev(t, dtype=None):
+    """Device pointer of a contiguous CUDA tensor (None -> NULL)."""
+    if t is None:
+        return C.c_void_p(0)
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected dtype {dtype}, got {t.dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _host_i32(seq):
+    import numpy as np
+    a = np.ascontiguousarray(seq, dtype=np.int32)
+    return a, a.ctypes.data_as(C.c_void_p)
+
+
+# ---------------------------------------------------------------------------------- handles
+
+class Model:
+    """Owner of an ss_model handle.  `shape` carries n_layers, d_model, n_heads, head_dim, d_ff, vocab,
+    rope_base, rms_eps, dtype ("bf16" | "f32"); `weights` is a dict
+    {embed, layers: [{wq, wk, wv, wo, wg, wu, wd, g1, g2}], gf, lm_head} of device tensors.  Packing
+    q|k|v and gate|up into the fused matrices the library streams is a one-off copy done here
+    (memory plumbing; pass `packed_layers` = [{wqkv, wo, wgu, wd, g1, g2}] to skip it)."""
+
+    def __init__(self, shape, weights=None, max_rows=16, max_pos=4096, packed_layers=None):
+        self.shape = shape
+        st = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+        if packed_layers is None:
+            packed_layers = []
+            for lw in weights["layers"]:
+                packed_layers.append({
+                    "wqkv": torch.cat([lw["wq"], lw["wk"], lw["wv"]], 0).contiguous(),
+                    "wo": lw["wo"].contiguous(),
+                    "wgu": torch.cat([lw["wg"], lw["wu"]], 0).contiguous(),
+                    "wd": lw["wd"].contiguous(), "g1": lw["g1"].contiguous(), "g2": lw["g2"].contiguous()})
+        self.layers = packed_layers
+        self.embed = weights.get("embed") if weights else None
+        self.gf = weights.get("gf") if weights else None
+        self.lm_head = weights.get("lm_head") if weights else None
+        arr = (_LayerW * max(1, len(packed_layers)))()
+        for i, pl in enumerate(packed_layers):
+            for n in ("wqkv", "wo", "wgu", "wd"):
+                setattr(arr[i], n, _dev(pl[n], st).value)
+            for n in ("g1", "g2"):
+                setattr(arr[i], n, _dev(pl[n], torch.float32).value)
+        w = _Weights(_dev(self.embed, st if self.embed is not None else None), arr,
+                     _dev(self.gf, torch.float32 if self.gf is not None else None),
+                     _dev(self.lm_head, st if self.lm_head is not None else None))
+        cfg = _Cfg(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ff, shape.vocab,
+                   shape.rope_base, shape.rms_eps, SS_DTYPE_BF16 if shape.dtype == "bf16" else SS_DTYPE_F32,
+                   max_rows, max_pos)
+        h = C.c_void_p()
+        _check(lib().ss_model_create(C.byref(cfg), C.byref(w), C.byref(h)))
+        self.handle = h
+
+    def close(self):
+        if getattr(self, "handle", None):
+            lib().ss_model_destroy(self.handle)
+            self.handle = None
+
+    __del__ = close
+
+
+class KVCache:
+    def __init__(self, model: Model, batch: int, max_seq: int):
+        self.model, self.batch, self.max_seq = model, batch, max_seq
+        h = C.c_void_p()
+        _check(lib().ss_kv_cache_alloc(model.handle, batch, max_seq, C.byref(h)))
+        self.handle = h
+
+    def close(self):
+        if getattr(self, "handle", None):
+            lib().ss_kv_cache_free(self.handle)
+            self.handle = None
+
+    __del__ = close
+
+
+# ---------------------------------------------------------------------------------- entry points
+
+def ss_kv_cache_alloc(model: Model, batch: int, max_seq: int) -> KVCache:
+    return KVCache(model, batch, max_seq)
+
+
+def ss_kv_cache_bytes(model: Model, batch: int, max_seq: int) -> int:
+    return lib().ss_kv_cache_bytes(model.handle, batch, max_seq)
+
+
+def ss_kv_cache_append(kv: KVCache, layer: int, seq: int, pos0: int, k, v, stream=None):
+    _check(lib().ss_kv_cache_append(kv.handle, layer, seq, pos0, _dev(k), _dev(v), k.shape[0], _stream(stream)))
+
+
+def ss_kv_cache_set_len(kv: KVCache, lens, stream=None):
+    a, p = _host_i32(lens)
+    if a.size != kv.batch:
+        raise ValueError("one length per sequence")
+    _check(lib().ss_kv_cache_set_len(kv.handle, p, _stream(stream)))
+
+
+def ss_kv_cache_get_len(kv: KVCache, stream=None):
+    import numpy as np
+    a = np.zeros(kv.batch, dtype=np.int32)
+    _check(lib().ss_kv_cache_get_len(kv.handle, a.ctypes.data_as(C.c_void_p), _stream(stream)))
+    return a
+
+
+def ss_kv_cache_rollback(kv: KVCache, n_accepted, M: int, n_accepted_host=None, stream=None):
+    hp = C.c_void_p(0)
+    if n_accepted_host is not None:
+        keep, hp = _host_i32(n_accepted_host)
+    _check(lib().ss_kv_cache_rollback(kv.handle, _dev(n_accepted, torch.int32), hp, M, _stream(stream)))
+
+
+def ss_verify_forward(model: Model, kv: KVCache, tokens, M: int, logits=None, stream=None):
+    """tokens int32 [batch, M] -> logits fp32 [batch, M, vocab] (allocated when not given; pass
+    logits=False to skip the LM head)."""
+    batch = tokens.numel() // M
+    if logits is None:
+        logits = torch.empty((batch, M, model.shape.vocab), dtype=torch.float32, device=tokens.device)
+    lp = None if logits is False else logits
+    _check(lib().ss_verify_forward(model.handle, kv.handle, _dev(tokens, torch.int32), batch, M,
+                                   _dev(lp, torch.float32 if lp is not None else None), _stream(stream)))
+    return lp
+
+
+def ss_decoder_layers_forward(model: Model, kv: KVCache, h, batch: int, M: int, stream=None):
+    _check(lib().ss_decoder_layers_forward(model.handle, kv.handle, _dev(h, torch.float32), batch, M, _stream(stream)))
+    return h
+
+
+def ss_draft_step(draft: Model, kv: KVCache, tokens, m: int, temperature: float, u, q_rows, ldq: int,
+                  token_out, stream=None):
+    batch = tokens.numel() // m
+    qp = C.c_void_p(0) if q_rows is None else C.c_void_p(q_rows.data_ptr())
+    _check(lib().ss_draft_step(draft.handle, kv.handle, _dev(tokens, torch.int32), batch, m, float(temperature),
+                               _dev(u, torch.float32 if u is not None else None), qp, int(ldq),
+                               _dev(token_out, torch.int32), _stream(stream)))
+    return token_out
+
+
+def ss_softmax(logits, temperature: float, probs=None, stream=None):
+    V = logits.shape[-1]
+    rows = logits.numel() // V
+    if probs is None:
+        probs = torch.empty_like(logits)
+    _check(lib().ss_softmax(_dev(logits, torch.float32), rows, V, float(temperature), _dev(probs, torch.float32),
+                            _stream(stream)))
+    return probs
+
+
+def _accept_out(batch, device, n_accepted, next_token):
+    if n_accepted is None:
+        n_accepted = torch.empty(batch, dtype=torch.int32, device=device)
+    if next_token is None:
+        next_token = torch.empty(batch, dtype=torch.int32, device=device)
+    return n_accepted, next_token
+
+
+def ss_speculative_accept(p, q, draft_tokens, uniforms, n_accepted=None, next_token=None, stream=None):
+    B, K1, V = p.shape
+    n_accepted, next_token = _accept_out(B, p.device, n_accepted, next_token)
+    _check(lib().ss_speculative_accept(_dev(p, torch.float32), _dev(q, torch.float32) if K1 > 1 else C.c_void_p(0),
+                                       _dev(draft_tokens, torch.int32) if K1 > 1 else C.c_void_p(0),
+                                       _dev(uniforms, torch.float32), B, K1 - 1, V, _dev(n_accepted), _dev(next_token),
+                                       _stream(stream)))
+    return n_accepted, next_token
+
+
+def ss_speculative_accept_logits(p_logits, q_logits, temperature, draft_tokens, uniforms, n_accepted=None,
+                                 next_token=None, p_out=None, q_out=None, stream=None):
+    B, K1, V = p_logits.shape
+    n_accepted, next_token = _accept_out(B, p_logits.device, n_accepted, next_token)
+    _check(lib().ss_speculative_accept_logits(
+        _dev(p_logits, torch.float32), _dev(q_logits, torch.float32) if K1 > 1 else C.c_void_p(0), float(temperature),
+        _dev(draft_tokens, torch.int32) if K1 > 1 else C.c_void_p(0), _dev(uniforms, torch.float32), B, K1 - 1, V,
+        _dev(n_accepted), _dev(next_token), _dev(p_out), _dev(q_out), _stream(stream)))
+    return n_accepted, next_token
+
+
+def ss_greedy_accept(p_logits, draft_tokens, n_accepted=None, next_token=None, stream=None):
+    B, K1, V = p_logits.shape
+    n_accepted, next_token = _accept_out(B, p_logits.device, n_accepted, next_token)
+    _check(lib().ss_greedy_accept(_dev(p_logits, torch.float32),
+                                  _dev(draft_tokens, torch.int32) if K1 > 1 else C.c_void_p(0), B, K1 - 1, V,
+                                  _dev(n_accepted), _dev(next_token), _stream(stream)))
+    return n_accepted, next_token
+
+
+def ss_device_status(model: Model, stream=None) -> int:
+    out = C.c_int32(0)
+    _check(lib().ss_device_status(model.handle, _stream(stream), C.byref(out)))
+    return out.value

@@ -1,0 +1,407 @@
+// Per-row softmax statistics and the modified rejection step of speculative sampling
+// (Sections 3 and 4.3: the target accepts or rejects the draft's tokens so that the target
+// distribution is recovered).
+//
+//   accept d_i  <=>  p_i(d_i) >= q_i(d_i)  or  fl32(u_i * q_i(d_i)) < p_i(d_i)      (prob. min(1, p/q))
+//   on the first rejection: next ~ norm(max(0, p - q));  nothing rejected: next ~ p_{K+1}
+//
+// Sampling is an integer inverse CDF so that a parallel reduction and a sequential loop pick the same
+// token: w_v = trunc(r_v * 2^32) (uint64), S = sum w_v, threshold = (u*2^24 * S) >> 24, token = the
+// smallest v whose inclusive prefix exceeds the threshold.  Integer sums are associative, so the
+// wavefront reductions below cannot change the answer.
+//
+// Row statistics (max, Z) use one pass over the vocabulary (online softmax) with wavefront shuffles;
+// probabilities are defined by one fixed instruction sequence (prob_from_logit) so that the fused
+// logits path and the materialised softmax produce identical bits.
+#include "ss_device.h"
+#include "ss_kernels.h"
+
+namespace ss {
+
+__device__ __forceinline__ float scaled_logit(float l, float inv_t) { return __fmul_rn(l, inv_t); }
+__device__ __forceinline__ float prob_from_logit(float l, float inv_t, float mx, float Z) {
+    return __fdiv_rn(expf(__fsub_rn(scaled_logit(l, inv_t), mx)), Z);
+}
+
+// ------------------------------------------------------------------ row statistics
+
+__device__ __forceinline__ void online_add(float &m, float &s, float x) {
+    if (x > m) {
+        s = s * expf(m - x) + 1.0f;
+        m = x;
+    } else {
+        s += expf(x - m);
+    }
+}
+__device__ __forceinline__ void online_merge(float &m, float &s, float m2, float s2) {
+    const float mm = fmaxf(m, m2);
+    s = s * expf(m - mm) + s2 * expf(m2 - mm);
+    m = mm;
+}
+
+// one workgroup per row: stats[row] = (max_v x_v, sum_v exp(x_v - max)), x = logit * inv_t
+__global__ __launch_bounds__(256) void row_stats_kernel(const float *logits, int V, float inv_t, float2 *stats) {
+    const int row = blockIdx.x;
+    const float *x = logits + (size_t)row * V;
+    float m = -INFINITY, s = 0.f;
+    const bool vec = (V % 4 == 0) && ((reinterpret_cast<uintptr_t>(x) & 15) == 0);
+    if (vec) {
+        const f32x4 *x4 = reinterpret_cast<const f32x4 *>(x);
+        for (int i = threadIdx.x; i < V / 4; i += 256) {
+            const f32x4 t = __builtin_nontemporal_load(x4 + i);
+            const float a0 = scaled_logit(t[0], inv_t), a1 = scaled_logit(t[1], inv_t);
+            const float a2 = scaled_logit(t[2], inv_t), a3 = scaled_logit(t[3], inv_t);
+            const float mx = fmaxf(fmaxf(a0, a1), fmaxf(a2, a3));
+            if (mx == -INFINITY) continue;
+            if (mx > m) {
+                s *= expf(m - mx);
+                m = mx;
+            }
+            s += (expf(a0 - m) + expf(a1 - m)) + (expf(a2 - m) + expf(a3 - m));
+        }
+    } else {
+        for (int i = threadIdx.x; i < V; i += 256) online_add(m, s, scaled_logit(x[i], inv_t));
+    }
+    if (m == -INFINITY) s = 0.f; // a thread that saw nothing: exp(-inf - -inf) must not appear
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float m2 = __shfl_xor(m, o), s2 = __shfl_xor(s, o);
+        if (m2 != -INFINITY) {
+            if (m == -INFINITY) {
+                m = m2;
+                s = s2;
+            } else {
+                online_merge(m, s, m2, s2);
+            }
+        }
+    }
+    __shared__ float sm[4], ss_[4];
+    if ((threadIdx.x & 63) == 0) {
+        sm[threadIdx.x >> 6] = m;
+        ss_[threadIdx.x >> 6] = s;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float M = sm[0], S = ss_[0];
+        for (int w = 1; w < 4; ++w)
+            if (sm[w] != -INFINITY) {
+                if (M == -INFINITY) {
+                    M = sm[w];
+                    S = ss_[w];
+                } else {
+                    online_merge(M, S, sm[w], ss_[w]);
+                }
+            }
+        stats[row] = make_float2(M, S);
+    }
+}
+
+void launch_row_stats(const float *logits, int rows, int V, float inv_t, float2 *stats, hipStream_t st) {
+    if (rows <= 0) return;
+    hipLaunchKernelGGL(row_stats_kernel, dim3(rows), dim3(256), 0, st, logits, V, inv_t, stats);
+}
+
+__global__ __launch_bounds__(256) void softmax_write_kernel(const float *logits, int V, float inv_t, const float2 *stats,
+                                                            float *probs, int64_t ld) {
+    const int row = blockIdx.y;
+    const float2 st = stats[row];
+    const size_t base = (size_t)row * V, obase = (size_t)row * ld;
+    for (int v = blockIdx.x * 256 + threadIdx.x; v < V; v += gridDim.x * 256)
+        probs[obase + v] = prob_from_logit(logits[base + v], inv_t, st.x, st.y);
+}
+
+void launch_softmax_write(const float *logits, int rows, int V, float inv_t, const float2 *stats, float *probs,
+                          int64_t probs_ld, hipStream_t st) {
+    if (rows <= 0) return;
+    int gx = (V + 256 * 8 - 1) / (256 * 8);
+    hipLaunchKernelGGL(softmax_write_kernel, dim3(gx, rows), dim3(256), 0, st, logits, V, inv_t, stats, probs, probs_ld);
+}
+
+// ------------------------------------------------------------------ a row of probabilities
+
+struct RowSrc {
+    const float *row;
+    int from_logits;
+    float inv_t, mx, Z;
+    __device__ __forceinline__ float conv(float x) const { return from_logits ? prob_from_logit(x, inv_t, mx, Z) : x; }
+    __device__ __forceinline__ float at(int v) const { return conv(row[v]); }
+    // probabilities of v..v+3 (0 beyond V); v is a multiple of 4
+    __device__ __forceinline__ void load4(int v, int V, bool vec, float (&out)[4]) const {
+        if (vec && v + 3 < V) {
+            const float4 t = *reinterpret_cast<const float4 *>(row + v);
+            out[0] = conv(t.x);
+            out[1] = conv(t.y);
+            out[2] = conv(t.z);
+            out[3] = conv(t.w);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) out[e] = (v + e < V) ? conv(row[v + e]) : 0.f;
+        }
+    }
+};
+
+__device__ __forceinline__ unsigned long long fx_weight(float r) {
+    return r > 0.f ? (unsigned long long)(r * 4294967296.0f) : 0ull;
+}
+
+template <bool RESID>
+__device__ __forceinline__ void weights4(const RowSrc &P, const RowSrc &Q, int v, int V, bool vec,
+                                         unsigned long long (&w)[4]) {
+    float p[4];
+    P.load4(v, V, vec, p);
+    if (RESID) {
+        float q[4];
+        Q.load4(v, V, vec, q);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = fx_weight(fmaxf(__fsub_rn(p[e], q[e]), 0.f));
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = fx_weight(p[e]);
+    }
+}
+
+__device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long x, int o) {
+    const unsigned lo = __shfl_xor((unsigned)x, o), hi = __shfl_xor((unsigned)(x >> 32), o);
+    return ((unsigned long long)hi << 32) | lo;
+}
+__device__ __forceinline__ unsigned long long shfl_up_u64(unsigned long long x, int o) {
+    const unsigned lo = __shfl_up((unsigned)x, o), hi = __shfl_up((unsigned)(x >> 32), o);
+    return ((unsigned long long)hi << 32) | lo;
+}
+__device__ __forceinline__ unsigned long long shfl_u64(unsigned long long x, int src) {
+    const unsigned lo = __shfl((unsigned)x, src), hi = __shfl((unsigned)(x >> 32), src);
+    return ((unsigned long long)hi << 32) | lo;
+}
+
+constexpr int SAMPLE_THREADS = 1024, SAMPLE_WAVES = SAMPLE_THREADS / 64;
+
+// Integer inverse CDF of one row by a 1024-thread workgroup.  Wave w owns the contiguous segment
+// [w*seg, (w+1)*seg); pass A sums every segment, pass B rescans the one segment that holds the
+// threshold.  Returns the token to every thread, or -1 when all weights are 0.
+template <bool RESID>
+__device__ int block_inv_cdf(const RowSrc &P, const RowSrc &Q, int V, float u, unsigned long long *sm_wave,
+                             int *sm_tok) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool vec = (V % 4 == 0) && ((reinterpret_cast<uintptr_t>(P.row) & 15) == 0) &&
+                     (!RESID || (reinterpret_cast<uintptr_t>(Q.row) & 15) == 0);
+    int seg = (V + SAMPLE_WAVES - 1) / SAMPLE_WAVES;
+    seg = (seg + 255) & ~255;
+    const int v_begin = wave * seg, v_end = min(v_begin + seg, V);
+
+    unsigned long long sum = 0;
+    for (int v = v_begin + 4 * lane; v < v_end; v += 256) {
+        unsigned long long w[4];
+        weights4<RESID>(P, Q, v, V, vec, w);
+        sum += (w[0] + w[1]) + (w[2] + w[3]);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sum += shfl_xor_u64(sum, o);
+    __syncthreads(); // protects sm_wave / sm_tok against a previous call in the same kernel
+    if (lane == 0) sm_wave[wave] = sum;
+    if (threadIdx.x == 0) *sm_tok = -1;
+    __syncthreads();
+    unsigned long long S = 0;
+    for (int w = 0; w < SAMPLE_WAVES; ++w) S += sm_wave[w];
+    if (S == 0) return -1;
+    const unsigned long long mant = (unsigned long long)(u * 16777216.0f);
+    const unsigned long long T = (__umul64hi(mant, S) << 40) | ((mant * S) >> 24);
+    unsigned long long C = 0; // weight of all segments before mine
+    for (int w = 0; w < wave; ++w) C += sm_wave[w];
+    if (C <= T && T < C + sm_wave[wave]) { // wave-uniform: exactly one wave rescans its segment
+        for (int v0 = v_begin; v0 < v_end; v0 += 256) {
+            const int v = v0 + 4 * lane;
+            unsigned long long w[4] = {0, 0, 0, 0};
+            if (v < v_end) weights4<RESID>(P, Q, v, V, vec, w);
+            const unsigned long long mine = (w[0] + w[1]) + (w[2] + w[3]);
+            unsigned long long incl = mine;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const unsigned long long t = shfl_up_u64(incl, o);
+                if (lane >= o) incl += t;
+            }
+            const unsigned long long total = shfl_u64(incl, 63);
+            if (C + total > T) {
+                unsigned long long run = C + incl - mine;
+                if (run <= T && T < run + mine) {
+                    int tok = v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        run += w[e];
+                        if (run > T) {
+                            tok = v + e;
+                            break;
+                        }
+                    }
+                    *sm_tok = tok;
+                }
+                break;
+            }
+            C += total;
+        }
+    }
+    __syncthreads();
+    return *sm_tok;
+}
+
+// (value, index) argmax of one row by the workgroup, lowest index on ties
+__device__ int block_argmax(const RowSrc &P, int V, float *sm_val, int *sm_idx) {
+    float best = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int v = threadIdx.x; v < V; v += blockDim.x) {
+        const float x = P.at(v);
+        if (x > best || bi == 0x7fffffff) {
+            best = x;
+            bi = v;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float b2 = __shfl_xor(best, o);
+        const int i2 = __shfl_xor(bi, o);
+        if (b2 > best || (b2 == best && i2 < bi)) {
+            best = b2;
+            bi = i2;
+        }
+    }
+    const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) {
+        sm_val[wave] = best;
+        sm_idx[wave] = bi;
+    }
+    __syncthreads();
+    best = sm_val[0];
+    bi = sm_idx[0];
+    for (int w = 1; w < nw; ++w)
+        if (sm_val[w] > best || (sm_val[w] == best && sm_idx[w] < bi)) {
+            best = sm_val[w];
+            bi = sm_idx[w];
+        }
+    return bi;
+}
+
+// ------------------------------------------------------------------ the rejection step
+
+__device__ __forceinline__ RowSrc make_row(const float *base, const float2 *stats, size_t row, int V, int from_logits,
+                                           float inv_t) {
+    RowSrc r;
+    r.row = base + row * (size_t)V;
+    r.from_logits = from_logits;
+    r.inv_t = inv_t;
+    r.mx = 0.f;
+    r.Z = 1.f;
+    if (from_logits) {
+        const float2 s = stats[row];
+        r.mx = s.x;
+        r.Z = s.y;
+    }
+    return r;
+}
+
+// one thread per sequence: leading accepted draft tokens
+__global__ void accept_scan_kernel(AcceptArgs a) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= a.B) return;
+    int n = 0;
+    for (int i = 0; i < a.K; ++i) {
+        const int d = a.draft[b * a.K + i];
+        if (d < 0 || d >= a.V) { // cannot be validated on the host: flagged, treated as rejected
+            atomicOr(a.status, 1);
+            break;
+        }
+        const RowSrc P = make_row(a.p, a.p_stats, (size_t)b * (a.K + 1) + i, a.V, a.from_logits, a.inv_t);
+        const RowSrc Q = make_row(a.q, a.q_stats, (size_t)b * a.K + i, a.V, a.from_logits, a.inv_t);
+        const float pi = P.at(d), qi = Q.at(d);
+        const bool acc = (pi >= qi) || (__fmul_rn(a.u[b * (a.K + 1) + i], qi) < pi);
+        if (!acc) break;
+        ++n;
+    }
+    a.n_accepted[b] = n;
+}
+
+// one workgroup per sequence: residual resample at the first rejection, or the bonus token
+__global__ __launch_bounds__(SAMPLE_THREADS) void accept_sample_kernel(AcceptArgs a) {
+    __shared__ unsigned long long sm_wave[SAMPLE_WAVES];
+    __shared__ int sm_tok;
+    __shared__ float sm_val[SAMPLE_WAVES];
+    __shared__ int sm_idx[SAMPLE_WAVES];
+    const int b = blockIdx.x;
+    const int n = a.n_accepted[b];
+    const float u = a.u[b * (a.K + 1) + a.K];
+    const RowSrc P = make_row(a.p, a.p_stats, (size_t)b * (a.K + 1) + n, a.V, a.from_logits, a.inv_t);
+    int tok = -1;
+    if (n < a.K) {
+        const RowSrc Q = make_row(a.q, a.q_stats, (size_t)b * a.K + n, a.V, a.from_logits, a.inv_t);
+        tok = block_inv_cdf<true>(P, Q, a.V, u, sm_wave, &sm_tok);
+    }
+    if (tok < 0) tok = block_inv_cdf<false>(P, P, a.V, u, sm_wave, &sm_tok);
+    if (tok < 0) tok = block_argmax(P, a.V, sm_val, sm_idx);
+    if (threadIdx.x == 0) a.next_token[b] = tok;
+}
+
+void launch_accept(const AcceptArgs &a, hipStream_t st) {
+    if (a.B <= 0) return;
+    hipLaunchKernelGGL(accept_scan_kernel, dim3((a.B + 63) / 64), dim3(64), 0, st, a);
+    hipLaunchKernelGGL(accept_sample_kernel, dim3(a.B), dim3(SAMPLE_THREADS), 0, st, a);
+}
+
+// ------------------------------------------------------------------ sampling / argmax of plain rows
+
+__global__ __launch_bounds__(SAMPLE_THREADS) void sample_rows_kernel(const float *probs, int64_t ld, int V, const float *u,
+                                                                     int32_t *token_out) {
+    __shared__ unsigned long long sm_wave[SAMPLE_WAVES];
+    __shared__ int sm_tok;
+    __shared__ float sm_val[SAMPLE_WAVES];
+    __shared__ int sm_idx[SAMPLE_WAVES];
+    const int b = blockIdx.x;
+    RowSrc P;
+    P.row = probs + (size_t)b * ld;
+    P.from_logits = 0;
+    P.inv_t = 1.f;
+    P.mx = 0.f;
+    P.Z = 1.f;
+    int tok = block_inv_cdf<false>(P, P, V, u[b], sm_wave, &sm_tok);
+    if (tok < 0) tok = block_argmax(P, V, sm_val, sm_idx);
+    if (threadIdx.x == 0) token_out[b] = tok;
+}
+void launch_sample_rows(const float *probs, int64_t ld, int B, int V, const float *u, int32_t *token_out,
+                        hipStream_t st) {
+    if (B <= 0) return;
+    hipLaunchKernelGGL(sample_rows_kernel, dim3(B), dim3(SAMPLE_THREADS), 0, st, probs, ld, V, u, token_out);
+}
+
+__global__ __launch_bounds__(SAMPLE_THREADS) void argmax_rows_kernel(const float *x, int64_t ld, int V, int32_t *out) {
+    __shared__ float sm_val[SAMPLE_WAVES];
+    __shared__ int sm_idx[SAMPLE_WAVES];
+    RowSrc P;
+    P.row = x + (size_t)blockIdx.x * ld;
+    P.from_logits = 0;
+    P.inv_t = 1.f;
+    P.mx = 0.f;
+    P.Z = 1.f;
+    const int t = block_argmax(P, V, sm_val, sm_idx);
+    if (threadIdx.x == 0) out[blockIdx.x] = t;
+}
+void launch_argmax_rows(const float *logits, int64_t ld, int B, int V, int32_t *token_out, hipStream_t st) {
+    if (B <= 0) return;
+    hipLaunchKernelGGL(argmax_rows_kernel, dim3(B), dim3(SAMPLE_THREADS), 0, st, logits, ld, V, token_out);
+}
+
+// greedy: accept while the draft token is the target row's argmax; next = argmax at the first mismatch
+__global__ void greedy_scan_kernel(const int32_t *row_argmax, const int32_t *draft, int B, int K, int32_t *n_accepted,
+                                   int32_t *next_token) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int n = 0;
+    while (n < K && draft[b * K + n] == row_argmax[b * (K + 1) + n]) ++n;
+    n_accepted[b] = n;
+    next_token[b] = row_argmax[b * (K + 1) + n];
+}
+void launch_greedy_accept(const float *p_logits, const int32_t *draft, int B, int K, int V, int32_t *row_argmax,
+                          int32_t *n_accepted, int32_t *next_token, hipStream_t st) {
+    if (B <= 0) return;
+    launch_argmax_rows(p_logits, V, B * (K + 1), V, row_argmax, st);
+    hipLaunchKernelGGL(greedy_scan_kernel, dim3((B + 63) / 64), dim3(64), 0, st, row_argmax, draft, B, K, n_accepted, next_token);
+}
+
+} // namespace ss

@@ -1,0 +1,501 @@
+// C ABI of the library (declared in include/specverify.h): argument validation, handle bookkeeping
+// and the order in which the kernels of one verify pass / draft step / rejection step are enqueued.
+// No arithmetic of the method lives here.
+#include "../../include/specverify.h"
+#include "ss_kernels.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <string>
+#include <vector>
+
+using namespace ss;
+
+static thread_local std::string g_err;
+
+static int fail(int code, const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                              \
+    do {                                                                                           \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess) return fail(SS_EHIP, "%s: %s", #expr, hipGetErrorString(e_));        \
+    } while (0)
+
+static int check_launch() {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(SS_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    return SS_OK;
+}
+
+static inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+struct ss_model {
+    ss_model_cfg cfg;
+    std::vector<ss_layer_weights> layers;
+    const void *embed, *lm_head;
+    const float *gf;
+    int planes, esz, W; // activation planes, storage element size, H*hd
+    int R16;            // max_rows rounded up to 16
+    float *h;           // [max_rows][d] residual stream
+    void *act_a;        // planes [R16][d]   normalised hidden rows
+    void *act_q;        // planes [R16][W]   rotated queries
+    void *act_o;        // planes [R16][W]   attention output
+    void *act_z;        // planes [R16][F]   SwiGLU output
+    float *part_o, *part_m, *part_l;
+    float *logits_ws; // [max_rows][vocab] (draft step)
+    float2 *stats_ws; // [max_rows]
+    float2 *rope;     // [max_pos][hd/2]
+    int32_t *status;
+    std::vector<void *> owned;
+};
+
+struct ss_kv_cache {
+    int n_layers, H, hd, dtype, esz;
+    int B, max_seq, S;
+    void *k, *v; // [n_layers][B][H][S][hd] each (V block-transposed)
+    int32_t *len_dev;
+    std::vector<int32_t> len_ub; // host upper bound of every length
+    size_t layer_elems;
+};
+
+static const int MAX_SPLITS = 16;
+
+extern "C" const char *ss_last_error(void) { return g_err.c_str(); }
+
+// ------------------------------------------------------------------------------------------ model
+
+static int dev_alloc(ss_model *m, void **p, size_t bytes, bool zero) {
+    HIP_TRY(hipMalloc(p, bytes ? bytes : 16));
+    m->owned.push_back(*p);
+    if (zero) HIP_TRY(hipMemset(*p, 0, bytes ? bytes : 16));
+    return SS_OK;
+}
+
+extern "C" int ss_model_destroy(ss_model *m) {
+    if (!m) return SS_OK;
+    for (void *p : m->owned) (void)hipFree(p);
+    delete m;
+    return SS_OK;
+}
+
+extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_model **out) {
+    if (!cfg || !w || !out) return fail(SS_EINVAL, "ss_model_create: NULL argument");
+    const ss_model_cfg &c = *cfg;
+    if (c.dtype != SS_DTYPE_F32 && c.dtype != SS_DTYPE_BF16) return fail(SS_EINVAL, "dtype must be f32 or bf16");
+    const int E = c.dtype == SS_DTYPE_BF16 ? 8 : 4;
+    if (c.n_layers < 0 || c.d_model <= 0 || c.n_heads <= 0 || c.d_ff <= 0 || c.vocab <= 0 || c.max_rows <= 0 || c.max_pos <= 0)
+        return fail(SS_EINVAL, "non-positive shape");
+    if (c.head_dim != 32 && c.head_dim != 64 && c.head_dim != 128) return fail(SS_EINVAL, "head_dim must be 32, 64 or 128");
+    if (c.d_model % E || c.d_ff % E) return fail(SS_EINVAL, "d_model and d_ff must be multiples of %d", E);
+    if (!w->layers && c.n_layers) return fail(SS_EINVAL, "weights->layers is NULL");
+    for (int l = 0; l < c.n_layers; ++l) {
+        const ss_layer_weights &L = w->layers[l];
+        if (!L.wqkv || !L.wo || !L.wgu || !L.wd || !L.g1 || !L.g2) return fail(SS_EINVAL, "layer %d has a NULL weight", l);
+    }
+    ss_model *m = new ss_model();
+    m->cfg = c;
+    m->layers.assign(w->layers, w->layers + c.n_layers);
+    m->embed = w->embed;
+    m->lm_head = w->lm_head;
+    m->gf = w->gf;
+    m->planes = c.dtype == SS_DTYPE_BF16 ? 2 : 1;
+    m->esz = c.dtype == SS_DTYPE_BF16 ? 2 : 4;
+    m->W = c.n_heads * c.head_dim;
+    m->R16 = round_up(c.max_rows, 16);
+    const size_t pe = (size_t)m->planes * m->esz * m->R16;
+    int rc = SS_OK;
+    auto A = [&](void **p, size_t bytes, bool zero) {
+        if (rc == SS_OK) rc = dev_alloc(m, p, bytes, zero);
+    };
+    A((void **)&m->h, sizeof(float) * (size_t)c.max_rows * c.d_model, true);
+    A(&m->act_a, pe * c.d_model, true);
+    A(&m->act_q, pe * m->W, true);
+    A(&m->act_o, pe * m->W, true);
+    A(&m->act_z, pe * c.d_ff, true);
+    A((void **)&m->part_o, sizeof(float) * (size_t)MAX_SPLITS * c.max_rows * m->W, true);
+    A((void **)&m->part_m, sizeof(float) * (size_t)MAX_SPLITS * c.max_rows * c.n_heads, true);
+    A((void **)&m->part_l, sizeof(float) * (size_t)MAX_SPLITS * c.max_rows * c.n_heads, true);
+    A((void **)&m->logits_ws, sizeof(float) * (size_t)c.max_rows * c.vocab, true);
+    A((void **)&m->stats_ws, sizeof(float2) * (size_t)c.max_rows, true);
+    A((void **)&m->rope, sizeof(float2) * (size_t)c.max_pos * (c.head_dim / 2), false);
+    A((void **)&m->status, sizeof(int32_t), true);
+    if (rc != SS_OK) {
+        ss_model_destroy(m);
+        return rc;
+    }
+    // rotary table: angle(pos, j) = pos * base^(-2j/hd), evaluated in double, stored as fp32 (cos, sin)
+    {
+        const int half = c.head_dim / 2;
+        std::vector<float2> tab((size_t)c.max_pos * half);
+        for (int j = 0; j < half; ++j) {
+            const double inv = std::pow((double)c.rope_base, -2.0 * j / (double)c.head_dim);
+            for (int p = 0; p < c.max_pos; ++p) {
+                const double ang = (double)p * inv;
+                tab[(size_t)p * half + j] = make_float2((float)std::cos(ang), (float)std::sin(ang));
+            }
+        }
+        hipError_t e = hipMemcpy(m->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            ss_model_destroy(m);
+            return fail(SS_EHIP, "rope table upload: %s", hipGetErrorString(e));
+        }
+    }
+    *out = m;
+    return SS_OK;
+}
+
+extern "C" int ss_device_status(ss_model *m, ss_stream stream, int32_t *status_host) {
+    if (!m || !status_host) return fail(SS_EINVAL, "ss_device_status: NULL argument");
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(hipMemcpyAsync(status_host, m->status, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    HIP_TRY(hipMemsetAsync(m->status, 0, sizeof(int32_t), st));
+    return SS_OK;
+}
+
+// ------------------------------------------------------------------------------------------ cache
+
+extern "C" size_t ss_kv_cache_bytes(const ss_model *m, int32_t batch, int32_t max_seq) {
+    if (!m || batch <= 0 || max_seq <= 0) return 0;
+    const size_t S = round_up(max_seq, 64);
+    return 2 * (size_t)m->cfg.n_layers * batch * m->W * S * m->esz;
+}
+
+extern "C" int ss_kv_cache_free(ss_kv_cache *kv) {
+    if (!kv) return SS_OK;
+    if (kv->k) (void)hipFree(kv->k);
+    if (kv->v) (void)hipFree(kv->v);
+    if (kv->len_dev) (void)hipFree(kv->len_dev);
+    delete kv;
+    return SS_OK;
+}
+
+extern "C" int ss_kv_cache_alloc(const ss_model *m, int32_t batch, int32_t max_seq, ss_kv_cache **out) {
+    if (!m || !out) return fail(SS_EINVAL, "ss_kv_cache_alloc: NULL argument");
+    if (batch <= 0 || max_seq <= 0) return fail(SS_EINVAL, "batch and max_seq must be positive");
+    if (max_seq > m->cfg.max_pos) return fail(SS_EINVAL, "max_seq %d exceeds the model's rotary table (%d)", max_seq, m->cfg.max_pos);
+    ss_kv_cache *kv = new ss_kv_cache();
+    kv->n_layers = m->cfg.n_layers;
+    kv->H = m->cfg.n_heads;
+    kv->hd = m->cfg.head_dim;
+    kv->dtype = m->cfg.dtype;
+    kv->esz = m->esz;
+    kv->B = batch;
+    kv->max_seq = max_seq;
+    kv->S = round_up(max_seq, 64);
+    kv->layer_elems = (size_t)batch * kv->H * kv->S * kv->hd;
+    kv->k = kv->v = nullptr;
+    kv->len_dev = nullptr;
+    kv->len_ub.assign(batch, 0);
+    const size_t bytes = kv->layer_elems * kv->n_layers * kv->esz;
+    hipError_t e = hipMalloc(&kv->k, bytes ? bytes : 16);
+    if (e == hipSuccess) e = hipMalloc(&kv->v, bytes ? bytes : 16);
+    if (e == hipSuccess) e = hipMalloc((void **)&kv->len_dev, sizeof(int32_t) * batch);
+    // zero fill: attention may touch (masked) positions past a length, which must hold finite values
+    if (e == hipSuccess) e = hipMemset(kv->k, 0, bytes ? bytes : 16);
+    if (e == hipSuccess) e = hipMemset(kv->v, 0, bytes ? bytes : 16);
+    if (e == hipSuccess) e = hipMemset(kv->len_dev, 0, sizeof(int32_t) * batch);
+    if (e != hipSuccess) {
+        ss_kv_cache_free(kv);
+        return fail(SS_EHIP, "ss_kv_cache_alloc: %s", hipGetErrorString(e));
+    }
+    *out = kv;
+    return SS_OK;
+}
+
+extern "C" int ss_kv_cache_append(ss_kv_cache *kv, int32_t layer, int32_t seq, int32_t pos0, const void *k_dev,
+                                  const void *v_dev, int32_t n_rows, ss_stream stream) {
+    if (!kv || !k_dev || !v_dev) return fail(SS_EINVAL, "ss_kv_cache_append: NULL argument");
+    if (layer < 0 || layer >= kv->n_layers || seq < 0 || seq >= kv->B || n_rows < 0 || pos0 < 0)
+        return fail(SS_EINVAL, "ss_kv_cache_append: layer/seq/rows out of range");
+    if ((int64_t)pos0 + n_rows > kv->max_seq) return fail(SS_ECAPACITY, "append of %d rows at %d exceeds max_seq %d", n_rows, pos0, kv->max_seq);
+    char *kc = (char *)kv->k + kv->layer_elems * layer * kv->esz;
+    char *vc = (char *)kv->v + kv->layer_elems * layer * kv->esz;
+    launch_kv_append(kv->dtype, kc, vc, k_dev, v_dev, seq, pos0, n_rows, kv->H, kv->hd, kv->S, (hipStream_t)stream);
+    return check_launch();
+}
+
+extern "C" int ss_kv_cache_set_len(ss_kv_cache *kv, const int32_t *len_host, ss_stream stream) {
+    if (!kv || !len_host) return fail(SS_EINVAL, "ss_kv_cache_set_len: NULL argument");
+    for (int b = 0; b < kv->B; ++b)
+        if (len_host[b] < 0 || len_host[b] > kv->max_seq) return fail(SS_EINVAL, "length %d of sequence %d outside [0, %d]", len_host[b], b, kv->max_seq);
+    hipStream_t st = (hipStream_t)stream;
+    // the source must stay valid until the copy ran: synchronise (this call is off the hot path)
+    HIP_TRY(hipMemcpyAsync(kv->len_dev, len_host, sizeof(int32_t) * kv->B, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    kv->len_ub.assign(len_host, len_host + kv->B);
+    return SS_OK;
+}
+
+extern "C" int ss_kv_cache_get_len(ss_kv_cache *kv, int32_t *len_host, ss_stream stream) {
+    if (!kv || !len_host) return fail(SS_EINVAL, "ss_kv_cache_get_len: NULL argument");
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(hipMemcpyAsync(len_host, kv->len_dev, sizeof(int32_t) * kv->B, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    kv->len_ub.assign(len_host, len_host + kv->B);
+    return SS_OK;
+}
+
+extern "C" int ss_kv_cache_rollback(ss_kv_cache *kv, const int32_t *n_accepted_dev, const int32_t *n_accepted_host,
+                                    int32_t M, ss_stream stream) {
+    if (!kv || !n_accepted_dev) return fail(SS_EINVAL, "ss_kv_cache_rollback: NULL argument");
+    if (M < 1 || M > SS_MAX_ROWS_PER_SEQ) return fail(SS_EINVAL, "M must be in [1, %d]", SS_MAX_ROWS_PER_SEQ);
+    for (int b = 0; b < kv->B; ++b)
+        if (kv->len_ub[b] < M) return fail(SS_EINVAL, "sequence %d is shorter than the %d rows to roll back over", b, M);
+    launch_len_rollback(kv->len_dev, n_accepted_dev, kv->B, M, (hipStream_t)stream);
+    // without the host copy the bound keeps the unrolled length; ss_kv_cache_get_len tightens it
+    if (n_accepted_host)
+        for (int b = 0; b < kv->B; ++b) {
+            const int a = std::min(std::max(n_accepted_host[b], 0), M - 1);
+            kv->len_ub[b] -= M - 1 - a;
+        }
+    return check_launch();
+}
+
+// ------------------------------------------------------------------------------------------ forward
+
+static int check_pair(const ss_model *m, const ss_kv_cache *kv, int batch, int M, const char *who) {
+    if (!m || !kv) return fail(SS_EINVAL, "%s: NULL handle", who);
+    if (kv->n_layers != m->cfg.n_layers || kv->H != m->cfg.n_heads || kv->hd != m->cfg.head_dim || kv->dtype != m->cfg.dtype)
+        return fail(SS_EINVAL, "%s: cache was allocated for a different model shape", who);
+    if (batch != kv->B) return fail(SS_EINVAL, "%s: batch %d != cache batch %d", who, batch, kv->B);
+    if (M < 1 || M > SS_MAX_ROWS_PER_SEQ) return fail(SS_EINVAL, "%s: rows per sequence must be in [1, %d]", who, SS_MAX_ROWS_PER_SEQ);
+    if ((int64_t)batch * M > m->cfg.max_rows) return fail(SS_EINVAL, "%s: %d rows exceed the model's max_rows %d", who, batch * M, m->cfg.max_rows);
+    for (int b = 0; b < batch; ++b)
+        if (kv->len_ub[b] + M > kv->max_seq || kv->len_ub[b] + M > m->cfg.max_pos)
+            return fail(SS_ECAPACITY, "%s: sequence %d at length <= %d has no room for %d rows (max_seq %d)", who, b, kv->len_ub[b], M, kv->max_seq);
+    return SS_OK;
+}
+
+// all layers over the R = batch*M rows in m->h
+static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream_t st) {
+    const ss_model_cfg &c = m->cfg;
+    const int R = batch * M, d = c.d_model, W = m->W, F = c.d_ff;
+    const size_t pl = (size_t)m->R16;
+    int Lmax = 0;
+    for (int b = 0; b < batch; ++b) Lmax = std::max(Lmax, kv->len_ub[b] + M);
+    int want = (512 + batch * c.n_heads - 1) / (batch * c.n_heads);
+    int nsplit = std::max(1, std::min(std::min(want, (Lmax + 63) / 64), MAX_SPLITS));
+    const int chunk = round_up((Lmax + nsplit - 1) / nsplit, 64);
+    nsplit = (Lmax + chunk - 1) / chunk;
+
+    for (int l = 0; l < c.n_layers; ++l) {
+        const ss_layer_weights &L = m->layers[l];
+        char *kc = (char *)kv->k + kv->layer_elems * l * kv->esz;
+        char *vc = (char *)kv->v + kv->layer_elems * l * kv->esz;
+        launch_rmsnorm_pack(c.dtype, m->h, L.g1, R, d, c.rms_eps, m->act_a, pl * d, d, st);
+        GemmArgs g{};
+        g.W = L.wqkv; g.N = 3 * W; g.K = d;
+        g.act = m->act_a; g.act_plane = pl * d; g.ld_act = d; g.R = R;
+        g.act_out = m->act_q; g.act_out_plane = pl * W; g.ld_act_out = W;
+        g.H = c.n_heads; g.hd = c.head_dim; g.M = M; g.S = kv->S; g.max_pos = c.max_pos;
+        g.len = kv->len_dev; g.rope = m->rope; g.kcache = kc; g.vcache = vc;
+        launch_gemm(c.dtype, EPI_QKV, g, st);
+
+        AttnArgs a{};
+        a.q = m->act_q; a.q_plane = pl * W; a.ldq = W;
+        a.kcache = kc; a.vcache = vc; a.len = kv->len_dev;
+        a.B = batch; a.M = M; a.H = c.n_heads; a.hd = c.head_dim; a.S = kv->S; a.R = R;
+        a.nsplit = nsplit; a.chunk = chunk;
+        a.part_o = m->part_o; a.part_m = m->part_m; a.part_l = m->part_l;
+        a.act_out = m->act_o; a.act_out_plane = pl * W; a.ld_out = W;
+        a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)c.head_dim));
+        launch_attention(c.dtype, a, st);
+
+        GemmArgs o{};
+        o.W = L.wo; o.N = d; o.K = W;
+        o.act = m->act_o; o.act_plane = pl * W; o.ld_act = W; o.R = R;
+        o.out = m->h; o.resid = m->h; o.ldo = d;
+        launch_gemm(c.dtype, EPI_RESID, o, st);
+
+        launch_rmsnorm_pack(c.dtype, m->h, L.g2, R, d, c.rms_eps, m->act_a, pl * d, d, st);
+        GemmArgs u{};
+        u.W = L.wgu; u.N = F; u.K = d;
+        u.act = m->act_a; u.act_plane = pl * d; u.ld_act = d; u.R = R;
+        u.act_out = m->act_z; u.act_out_plane = pl * F; u.ld_act_out = F;
+        launch_gemm(c.dtype, EPI_SWIGLU, u, st);
+
+        GemmArgs dn{};
+        dn.W = L.wd; dn.N = d; dn.K = F;
+        dn.act = m->act_z; dn.act_plane = pl * F; dn.ld_act = F; dn.R = R;
+        dn.out = m->h; dn.resid = m->h; dn.ldo = d;
+        launch_gemm(c.dtype, EPI_RESID, dn, st);
+    }
+    launch_len_add(kv->len_dev, batch, M, st);
+    for (int b = 0; b < batch; ++b) kv->len_ub[b] += M;
+}
+
+// logits[r][:] = RMSNorm(h[row0 + r*stride], gf) . W_lm^T for r < nrows
+static void run_head(ss_model *m, int nrows, int row0, int stride, float *logits, hipStream_t st) {
+    const ss_model_cfg &c = m->cfg;
+    const size_t pl = (size_t)m->R16;
+    launch_rmsnorm_pack_rows(c.dtype, m->h, m->gf, nrows, row0, stride, c.d_model, c.rms_eps, m->act_a, pl * c.d_model, c.d_model, st);
+    GemmArgs g{};
+    g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model;
+    g.act = m->act_a; g.act_plane = pl * c.d_model; g.ld_act = c.d_model; g.R = nrows;
+    g.out = logits; g.ldo = c.vocab;
+    launch_gemm(c.dtype, EPI_STORE, g, st);
+}
+
+extern "C" int ss_decoder_layers_forward(ss_model *m, ss_kv_cache *kv, float *h_dev, int32_t batch, int32_t M, ss_stream stream) {
+    int rc = check_pair(m, kv, batch, M, "ss_decoder_layers_forward");
+    if (rc) return rc;
+    if (!h_dev) return fail(SS_EINVAL, "ss_decoder_layers_forward: h_dev is NULL");
+    hipStream_t st = (hipStream_t)stream;
+    const size_t bytes = sizeof(float) * (size_t)batch * M * m->cfg.d_model;
+    HIP_TRY(hipMemcpyAsync(m->h, h_dev, bytes, hipMemcpyDeviceToDevice, st));
+    run_layers(m, kv, batch, M, st);
+    HIP_TRY(hipMemcpyAsync(h_dev, m->h, bytes, hipMemcpyDeviceToDevice, st));
+    return check_launch();
+}
+
+extern "C" int ss_verify_forward(ss_model *m, ss_kv_cache *kv, const int32_t *tokens_dev, int32_t batch, int32_t M,
+                                 float *logits_dev, ss_stream stream) {
+    int rc = check_pair(m, kv, batch, M, "ss_verify_forward");
+    if (rc) return rc;
+    if (!tokens_dev) return fail(SS_EINVAL, "ss_verify_forward: tokens_dev is NULL");
+    if (!m->embed || (logits_dev && (!m->lm_head || !m->gf))) return fail(SS_EINVAL, "ss_verify_forward: model has no embedding / LM head");
+    hipStream_t st = (hipStream_t)stream;
+    launch_embed(m->cfg.dtype, m->embed, tokens_dev, batch * M, m->cfg.d_model, m->cfg.vocab, m->h, m->status, st);
+    run_layers(m, kv, batch, M, st);
+    if (logits_dev) run_head(m, batch * M, 0, 1, logits_dev, st);
+    return check_launch();
+}
+
+extern "C" int ss_draft_step(ss_model *m, ss_kv_cache *kv, const int32_t *tokens_dev, int32_t batch, int32_t mrows,
+                             float temperature, const float *u_dev, float *q_rows_dev, int64_t ldq,
+                             int32_t *token_out_dev, ss_stream stream) {
+    int rc = check_pair(m, kv, batch, mrows, "ss_draft_step");
+    if (rc) return rc;
+    if (!tokens_dev || !token_out_dev) return fail(SS_EINVAL, "ss_draft_step: NULL argument");
+    if (!m->embed || !m->lm_head || !m->gf) return fail(SS_EINVAL, "ss_draft_step: model has no embedding / LM head");
+    if (!(temperature >= 0.f)) return fail(SS_EINVAL, "ss_draft_step: temperature must be >= 0");
+    if (temperature > 0.f && (!u_dev || !q_rows_dev || ldq < m->cfg.vocab)) return fail(SS_EINVAL, "ss_draft_step: sampling needs u_dev, q_rows_dev and ldq >= vocab");
+    hipStream_t st = (hipStream_t)stream;
+    const int V = m->cfg.vocab;
+    launch_embed(m->cfg.dtype, m->embed, tokens_dev, batch * mrows, m->cfg.d_model, V, m->h, m->status, st);
+    run_layers(m, kv, batch, mrows, st);
+    run_head(m, batch, mrows - 1, mrows, m->logits_ws, st);
+    if (temperature > 0.f) {
+        const float inv_t = 1.0f / temperature;
+        launch_row_stats(m->logits_ws, batch, V, inv_t, m->stats_ws, st);
+        launch_softmax_write(m->logits_ws, batch, V, inv_t, m->stats_ws, q_rows_dev, ldq, st);
+        launch_sample_rows(q_rows_dev, ldq, batch, V, u_dev, token_out_dev, st);
+    } else {
+        launch_argmax_rows(m->logits_ws, V, batch, V, token_out_dev, st);
+    }
+    return check_launch();
+}
+
+// ------------------------------------------------------------------------------------------ softmax / accept
+
+// Library scratch for the standalone softmax / accept entry points (row statistics, row argmax,
+// status word): one buffer per process, grown on demand, so steady-state calls allocate nothing.
+static std::mutex g_scratch_mu;
+static void *g_scratch = nullptr;
+static size_t g_scratch_bytes = 0;
+
+static int scratch(size_t bytes, void **out) {
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    bytes += 256;
+    if (bytes > g_scratch_bytes) {
+        if (g_scratch) {
+            HIP_TRY(hipDeviceSynchronize());
+            HIP_TRY(hipFree(g_scratch));
+            g_scratch = nullptr;
+            g_scratch_bytes = 0;
+        }
+        size_t n = std::max(bytes, (size_t)1 << 20);
+        HIP_TRY(hipMalloc(&g_scratch, n));
+        HIP_TRY(hipMemset(g_scratch, 0, n));
+        g_scratch_bytes = n;
+    }
+    *out = g_scratch;
+    return SS_OK;
+}
+
+extern "C" int ss_softmax(const float *logits_dev, int32_t rows, int32_t vocab, float temperature, float *probs_dev,
+                          ss_stream stream) {
+    if (!logits_dev || !probs_dev) return fail(SS_EINVAL, "ss_softmax: NULL argument");
+    if (rows < 0 || vocab <= 0 || !(temperature > 0.f)) return fail(SS_EINVAL, "ss_softmax: bad rows/vocab/temperature");
+    void *ws;
+    int rc = scratch(sizeof(float2) * (size_t)rows, &ws);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const float inv_t = 1.0f / temperature;
+    launch_row_stats(logits_dev, rows, vocab, inv_t, (float2 *)((char *)ws + 256), st);
+    launch_softmax_write(logits_dev, rows, vocab, inv_t, (float2 *)((char *)ws + 256), probs_dev, vocab, st);
+    return check_launch();
+}
+
+static int check_accept(const void *p, const void *q, const void *d, const void *u, int B, int K, int V, const void *na,
+                        const void *nx, const char *who) {
+    if (B < 0 || K < 0 || V <= 0) return fail(SS_EINVAL, "%s: bad batch/K/vocab", who);
+    if (K > SS_MAX_ROWS_PER_SEQ - 1) return fail(SS_EINVAL, "%s: K must be <= %d", who, SS_MAX_ROWS_PER_SEQ - 1);
+    if (!p || !u || !na || !nx || (K > 0 && (!q || !d))) return fail(SS_EINVAL, "%s: NULL argument", who);
+    return SS_OK;
+}
+
+extern "C" int ss_speculative_accept(const float *p_dev, const float *q_dev, const int32_t *draft_tokens_dev,
+                                     const float *uniforms_dev, int32_t batch, int32_t K, int32_t vocab,
+                                     int32_t *n_accepted_dev, int32_t *next_token_dev, ss_stream stream) {
+    int rc = check_accept(p_dev, q_dev, draft_tokens_dev, uniforms_dev, batch, K, vocab, n_accepted_dev, next_token_dev, "ss_speculative_accept");
+    if (rc) return rc;
+    void *ws;
+    rc = scratch(0, &ws);
+    if (rc) return rc;
+    AcceptArgs a{};
+    a.p = p_dev; a.q = q_dev; a.from_logits = 0; a.inv_t = 1.f;
+    a.draft = draft_tokens_dev; a.u = uniforms_dev; a.B = batch; a.K = K; a.V = vocab;
+    a.n_accepted = n_accepted_dev; a.next_token = next_token_dev; a.status = (int32_t *)ws;
+    launch_accept(a, (hipStream_t)stream);
+    return check_launch();
+}
+
+extern "C" int ss_speculative_accept_logits(const float *p_logits_dev, const float *q_logits_dev, float temperature,
+                                            const int32_t *draft_tokens_dev, const float *uniforms_dev, int32_t batch,
+                                            int32_t K, int32_t vocab, int32_t *n_accepted_dev, int32_t *next_token_dev,
+                                            float *p_out_dev, float *q_out_dev, ss_stream stream) {
+    int rc = check_accept(p_logits_dev, q_logits_dev, draft_tokens_dev, uniforms_dev, batch, K, vocab, n_accepted_dev, next_token_dev, "ss_speculative_accept_logits");
+    if (rc) return rc;
+    if (!(temperature > 0.f)) return fail(SS_EINVAL, "ss_speculative_accept_logits: temperature must be > 0");
+    const size_t np = (size_t)batch * (K + 1), nq = (size_t)batch * K;
+    void *ws;
+    rc = scratch(sizeof(float2) * (np + nq), &ws);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    float2 *ps = (float2 *)((char *)ws + 256), *qs = ps + np;
+    const float inv_t = 1.0f / temperature;
+    launch_row_stats(p_logits_dev, (int)np, vocab, inv_t, ps, st);
+    launch_row_stats(q_logits_dev, (int)nq, vocab, inv_t, qs, st);
+    AcceptArgs a{};
+    a.p = p_logits_dev; a.q = q_logits_dev; a.p_stats = ps; a.q_stats = qs; a.from_logits = 1; a.inv_t = inv_t;
+    a.draft = draft_tokens_dev; a.u = uniforms_dev; a.B = batch; a.K = K; a.V = vocab;
+    a.n_accepted = n_accepted_dev; a.next_token = next_token_dev; a.status = (int32_t *)ws;
+    launch_accept(a, st);
+    if (p_out_dev) launch_softmax_write(p_logits_dev, (int)np, vocab, inv_t, ps, p_out_dev, vocab, st);
+    if (q_out_dev) launch_softmax_write(q_logits_dev, (int)nq, vocab, inv_t, qs, q_out_dev, vocab, st);
+    return check_launch();
+}
+
+extern "C" int ss_greedy_accept(const float *p_logits_dev, const int32_t *draft_tokens_dev, int32_t batch, int32_t K,
+                                int32_t vocab, int32_t *n_accepted_dev, int32_t *next_token_dev, ss_stream stream) {
+    if (batch < 0 || K < 0 || K > SS_MAX_ROWS_PER_SEQ - 1 || vocab <= 0) return fail(SS_EINVAL, "ss_greedy_accept: bad batch/K/vocab");
+    if (!p_logits_dev || !n_accepted_dev || !next_token_dev || (K > 0 && !draft_tokens_dev)) return fail(SS_EINVAL, "ss_greedy_accept: NULL argument");
+    void *ws;
+    int rc = scratch(sizeof(int32_t) * (size_t)batch * (K + 1), &ws);
+    if (rc) return rc;
+    launch_greedy_accept(p_logits_dev, draft_tokens_dev, batch, K, vocab, (int32_t *)((char *)ws + 256), n_accepted_dev, next_token_dev, (hipStream_t)stream);
+    return check_launch();
+}

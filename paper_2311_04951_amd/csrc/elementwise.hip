@@ -1,0 +1,101 @@
+// Small row-wise kernels of the verify pass: embedding gather, RMSNorm (+ packing of the result as
+// the activation planes the next GEMM reads), cache-length bookkeeping (Section 4.4: truncation is a
+// length write) and the raw cache append used to build an existing context.
+#include "ss_device.h"
+#include "ss_kernels.h"
+
+namespace ss {
+
+// h[r][:] = E[token[r]][:]
+template <typename T>
+__global__ void embed_kernel(const T *embed, const int32_t *tokens, int d, int vocab, float *h, int32_t *status) {
+    const int r = blockIdx.x;
+    int tok = tokens[r];
+    if (tok < 0 || tok >= vocab) {
+        if (threadIdx.x == 0) atomicOr(status, 1);
+        tok = tok < 0 ? 0 : vocab - 1;
+    }
+    const T *src = embed + (size_t)tok * d;
+    for (int e = threadIdx.x; e < d; e += blockDim.x) h[(size_t)r * d + e] = to_f32(src[e]);
+}
+
+void launch_embed(int dtype, const void *embed, const int32_t *tokens, int R, int d, int vocab, float *h,
+                  int32_t *status, hipStream_t st) {
+    if (dtype) hipLaunchKernelGGL((embed_kernel<bf16_t>), dim3(R), dim3(256), 0, st, (const bf16_t *)embed, tokens, d, vocab, h, status);
+    else hipLaunchKernelGGL((embed_kernel<float>), dim3(R), dim3(256), 0, st, (const float *)embed, tokens, d, vocab, h, status);
+}
+
+// act[r][:] = h[src][:] * gain / sqrt(mean(h[src]^2) + eps) with src = row0 + r*row_stride
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_pack_kernel(const float *h, const float *gain, int row0, int row_stride,
+                                                           int d, float eps, ActPlanes<T> act) {
+    const int r = blockIdx.x;
+    const float *x = h + (size_t)(row0 + r * row_stride) * d;
+    float ss = 0.f;
+    for (int e = threadIdx.x; e < d; e += 256) ss += x[e] * x[e];
+    ss = wave_sum(ss);
+    __shared__ float part[4];
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float tot = (part[0] + part[1]) + (part[2] + part[3]);
+    const float scale = 1.0f / sqrtf(tot / (float)d + eps);
+    for (int e = threadIdx.x; e < d; e += 256) store_act(act, (size_t)r * act.ld + e, x[e] * scale * gain[e]);
+}
+
+void launch_rmsnorm_pack_rows(int dtype, const float *h, const float *gain, int nrows, int row0, int row_stride,
+                              int d, float eps, void *act, size_t act_plane, int ld_act, hipStream_t st) {
+    if (dtype) {
+        ActPlanes<bf16_t> ap{(bf16_t *)act, act_plane, ld_act};
+        hipLaunchKernelGGL((rmsnorm_pack_kernel<bf16_t>), dim3(nrows), dim3(256), 0, st, h, gain, row0, row_stride, d, eps, ap);
+    } else {
+        ActPlanes<float> ap{(float *)act, act_plane, ld_act};
+        hipLaunchKernelGGL((rmsnorm_pack_kernel<float>), dim3(nrows), dim3(256), 0, st, h, gain, row0, row_stride, d, eps, ap);
+    }
+}
+
+void launch_rmsnorm_pack(int dtype, const float *h, const float *gain, int R, int d, float eps, void *act,
+                         size_t act_plane, int ld_act, hipStream_t st) {
+    launch_rmsnorm_pack_rows(dtype, h, gain, R, 0, 1, d, eps, act, act_plane, ld_act, st);
+}
+
+__global__ void len_add_kernel(int32_t *len, int batch, int delta) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < batch) len[b] += delta;
+}
+void launch_len_add(int32_t *len, int batch, int delta, hipStream_t st) {
+    hipLaunchKernelGGL(len_add_kernel, dim3((batch + 63) / 64), dim3(64), 0, st, len, batch, delta);
+}
+
+// after the rejection step only the first n_accepted + 1 of the M appended rows stay
+__global__ void len_rollback_kernel(int32_t *len, const int32_t *n_accepted, int batch, int M) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < batch) {
+        int a = n_accepted[b];
+        a = a < 0 ? 0 : (a > M - 1 ? M - 1 : a);
+        len[b] -= M - 1 - a;
+    }
+}
+void launch_len_rollback(int32_t *len, const int32_t *n_accepted, int batch, int M, hipStream_t st) {
+    hipLaunchKernelGGL(len_rollback_kernel, dim3((batch + 63) / 64), dim3(64), 0, st, len, n_accepted, batch, M);
+}
+
+// raw append: rows [n_rows][H*hd] of rotated keys / values into sequence `seq` at pos0..
+template <typename T>
+__global__ void kv_append_kernel(T *kc, T *vc, const T *k, const T *v, int seq, int pos0, int H, int hd, int S) {
+    const int r = blockIdx.x, pos = pos0 + r;
+    const int W = H * hd;
+    for (int e = threadIdx.x; e < W; e += blockDim.x) {
+        const int h = e / hd, j = e - h * hd;
+        const size_t head = ((size_t)seq * H + h) * S * hd;
+        kc[head + (size_t)pos * hd + j] = k[(size_t)r * W + e];
+        vc[head + ((size_t)(pos >> 6) * hd + j) * 64 + (pos & 63)] = v[(size_t)r * W + e];
+    }
+}
+void launch_kv_append(int dtype, void *kc, void *vc, const void *k, const void *v, int seq, int pos0, int n_rows,
+                      int H, int hd, int S, hipStream_t st) {
+    if (n_rows <= 0) return;
+    if (dtype) hipLaunchKernelGGL((kv_append_kernel<bf16_t>), dim3(n_rows), dim3(256), 0, st, (bf16_t *)kc, (bf16_t *)vc, (const bf16_t *)k, (const bf16_t *)v, seq, pos0, H, hd, S);
+    else hipLaunchKernelGGL((kv_append_kernel<float>), dim3(n_rows), dim3(256), 0, st, (float *)kc, (float *)vc, (const float *)k, (const float *)v, seq, pos0, H, hd, S);
+}
+
+} // namespace ss

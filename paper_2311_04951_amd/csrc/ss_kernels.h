@@ -1,0 +1,94 @@
+// Host-side declarations of the kernel launchers (defined in the .hip files) and the argument
+// structs they take.  Everything here is plain data; the C ABI in include/specverify.h sits on top.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace ss {
+
+enum Epilogue : int {
+    EPI_STORE = 0,  // out[m][n] = acc
+    EPI_RESID = 1,  // out[m][n] = resid[m][n] + acc
+    EPI_SWIGLU = 2, // z[m][n] = silu(gate) * up, written as activation planes
+    EPI_QKV = 3     // rotary embedding on q, k; q -> activation planes, k, v -> KV cache
+};
+
+// Skinny GEMM  out[R][N] = act[R][K] . W[N][K]^T  for a handful of rows R (weights streamed once).
+struct GemmArgs {
+    const void *W; // [N][K] storage type, row-major
+    int N, K;
+    const void *act; // activation planes [planes][R16][ld_act]
+    size_t act_plane;
+    int ld_act;
+    int R; // valid rows
+    // EPI_STORE / EPI_RESID
+    float *out;
+    const float *resid;
+    int ldo;
+    // EPI_SWIGLU (N = F; up rows start at W row F) and EPI_QKV (q rows): activation planes written
+    void *act_out;
+    size_t act_out_plane;
+    int ld_act_out;
+    // EPI_QKV
+    int H, hd, M, S, max_pos;
+    const int32_t *len;  // [batch] lengths before this call's append
+    const float2 *rope;  // [max_pos][hd/2] (cos, sin)
+    void *kcache, *vcache; // this layer's K and V
+};
+void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st);
+
+struct AttnArgs {
+    const void *q; // activation planes [planes][R16][ldq], rotated queries
+    size_t q_plane;
+    int ldq;
+    const void *kcache, *vcache; // this layer
+    const int32_t *len;          // [batch] lengths before this call's append
+    int B, M, H, hd, S, R;
+    int nsplit, chunk;  // positions per split (multiple of 64)
+    float *part_o;      // [nsplit][R][H][hd] unnormalised
+    float *part_m;      // [nsplit][R][H] running max (log2 domain)
+    float *part_l;      // [nsplit][R][H] sum of weights
+    void *act_out;      // merged, normalised output as activation planes [planes][R16][ld_out]
+    size_t act_out_plane;
+    int ld_out;
+    float scale_log2e;
+};
+void launch_attention(int dtype, const AttnArgs &a, hipStream_t st);
+
+void launch_embed(int dtype, const void *embed, const int32_t *tokens, int R, int d, int vocab, float *h,
+                  int32_t *status, hipStream_t st);
+void launch_rmsnorm_pack(int dtype, const float *h, const float *gain, int R, int d, float eps, void *act,
+                         size_t act_plane, int ld_act, hipStream_t st);
+// gathers the last row of every sequence: rows b*M + M-1 -> compact rows b (norm + pack)
+void launch_rmsnorm_pack_rows(int dtype, const float *h, const float *gain, int nrows, int row0, int row_stride,
+                              int d, float eps, void *act, size_t act_plane, int ld_act, hipStream_t st);
+void launch_len_add(int32_t *len, int batch, int delta, hipStream_t st);
+void launch_len_rollback(int32_t *len, const int32_t *n_accepted, int batch, int M, hipStream_t st);
+void launch_kv_append(int dtype, void *kc, void *vc, const void *k, const void *v, int seq, int pos0, int n_rows,
+                      int H, int hd, int S, hipStream_t st);
+
+// softmax / accept
+void launch_row_stats(const float *logits, int rows, int V, float inv_t, float2 *stats, hipStream_t st);
+void launch_softmax_write(const float *logits, int rows, int V, float inv_t, const float2 *stats, float *probs,
+                          int64_t probs_ld, hipStream_t st);
+struct AcceptArgs {
+    const float *p, *q;          // probabilities, or logits when from_logits
+    const float2 *p_stats, *q_stats; // (max, Z) per row when from_logits
+    int from_logits;
+    float inv_t;
+    const int32_t *draft;
+    const float *u;
+    int B, K, V;
+    int32_t *n_accepted, *next_token;
+    int32_t *status;
+};
+void launch_accept(const AcceptArgs &a, hipStream_t st);
+void launch_greedy_accept(const float *p_logits, const int32_t *draft, int B, int K, int V, int32_t *row_argmax,
+                          int32_t *n_accepted, int32_t *next_token, hipStream_t st);
+// token ~ row by the integer inverse CDF (rows are probabilities), or argmax when greedy
+void launch_sample_rows(const float *probs, int64_t ld, int B, int V, const float *u, int32_t *token_out,
+                        hipStream_t st);
+void launch_argmax_rows(const float *logits, int64_t ld, int B, int V, int32_t *token_out, hipStream_t st);
+
+} // namespace ss

@@ -1,0 +1,101 @@
+"""Host loops over the C-ABI calls: autoregressive decoding (Section 3, Eq. 1) and speculative
+sampling with two KV caches (Sections 3, 4.3, 4.4).  Control flow and buffer plumbing only - every
+number is produced by the library's kernels.
+
+Cache bookkeeping of the speculative loop (the answer to Section 4.4's two-caches question): with n
+committed tokens both caches hold the first n-1 positions.  K draft calls bring the draft cache to
+n-1+K, one verify call brings the target cache to n+K, and after a tokens are accepted both are
+rolled back (a length write on the device) to n+a.  When all K are accepted the draft cache is one
+row short, so its next call feeds two tokens.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import (KVCache, Model, ss_draft_step, ss_greedy_accept, ss_kv_cache_rollback, ss_softmax,
+               ss_speculative_accept, ss_verify_forward)
+
+
+def prefill(model: Model, kv: KVCache, tokens, chunk: int = 16):
+    """Feeds `tokens` (list of ids, one sequence, batch 1) through the model in chunks of <= 16 rows."""
+    dev = torch.device("cuda")
+    for i in range(0, len(tokens), chunk):
+        t = torch.tensor([tokens[i:i + chunk]], dtype=torch.int32, device=dev)
+        ss_verify_forward(model, kv, t, t.shape[1], logits=False)
+
+
+def autoregressive_generate(target: Model, prompt, n_new: int, temperature: float, u=None, max_seq=None):
+    """One target call per token; the sampled token never leaves the device between steps."""
+    dev = torch.device("cuda")
+    V = target.shape.vocab
+    kv = KVCache(target, 1, max_seq or (len(prompt) + n_new + 1))
+    prefill(target, kv, list(prompt[:-1]))
+    buf = torch.empty(n_new + 1, dtype=torch.int32, device=dev)
+    buf[0] = int(prompt[-1])
+    q = torch.empty(V, dtype=torch.float32, device=dev) if temperature > 0 else None
+    ud = None
+    if temperature > 0:
+        ud = torch.as_tensor(u, dtype=torch.float32).to(dev)
+    for i in range(n_new):
+        ss_draft_step(target, kv, buf[i:i + 1], 1, temperature, ud[i:i + 1] if ud is not None else None, q, V,
+                      buf[i + 1:i + 2])
+    out = buf[1:].tolist()
+    kv.close()
+    return out
+
+
+def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int, temperature: float,
+                         u_draft=None, u_accept=None, max_seq=None, observer=None):
+    """Returns (tokens[n_new], stats).  u_draft [steps, K], u_accept [steps, K+1] (temperature > 0).
+    `observer(dict)` (optional) sees each step's device tensors: draft tokens, q rows, target logits,
+    n_accepted, next token."""
+    dev = torch.device("cuda")
+    V = target.shape.vocab
+    M = K + 1
+    greedy = temperature == 0
+    cap = max_seq or (len(prompt) + n_new + K + 2)
+    tkv, dkv = KVCache(target, 1, cap), KVCache(draft, 1, cap)
+    prefill(target, tkv, list(prompt[:-1]))
+    prefill(draft, dkv, list(prompt[:-1]))
+    x = [int(t) for t in prompt]
+    n0 = len(x)
+    pending = [x[-1]]
+    vt = torch.empty((1, M), dtype=torch.int32, device=dev)       # verify rows [x_n, d_1..d_K]
+    q = torch.zeros((1, K, V), dtype=torch.float32, device=dev)
+    logits = torch.empty((1, M, V), dtype=torch.float32, device=dev)
+    p = torch.empty_like(logits)
+    na = torch.empty(1, dtype=torch.int32, device=dev)
+    nx = torch.empty(1, dtype=torch.int32, device=dev)
+    if not greedy:
+        ud_all = torch.as_tensor(u_draft, dtype=torch.float32).to(dev)
+        ua_all = torch.as_tensor(u_accept, dtype=torch.float32).to(dev)
+    accepted = []
+    step = 0
+    while len(x) - n0 < n_new:
+        feed = torch.tensor([pending], dtype=torch.int32, device=dev)
+        for i in range(K):
+            ss_draft_step(draft, dkv, feed, feed.shape[1], temperature,
+                          None if greedy else ud_all[step, i:i + 1], None if greedy else q[0, i], K * V,
+                          vt[0, i + 1:i + 2])
+            feed = vt[:, i + 1:i + 2]
+        vt[0, 0] = x[-1]
+        ss_verify_forward(target, tkv, vt, M, logits)
+        d = vt[:, 1:].contiguous()
+        if greedy:
+            ss_greedy_accept(logits, d, na, nx)
+        else:
+            ss_softmax(logits, temperature, p)
+            ss_speculative_accept(p, q, d, ua_all[step:step + 1].contiguous(), na, nx)
+        if observer is not None:
+            observer({"step": step, "draft": d, "q": q, "logits": logits, "p": p, "n_accepted": na, "next": nx})
+        a, y = int(na.item()), int(nx.item())
+        dl = d[0].tolist()
+        ss_kv_cache_rollback(tkv, na, M, n_accepted_host=[a])
+        ss_kv_cache_rollback(dkv, na, K, n_accepted_host=[a])   # a = K leaves the draft cache one row short
+        x += dl[:a] + [y]
+        pending = [y] if a < K else [dl[K - 1], y]
+        accepted.append(a)
+        step += 1
+    tkv.close()
+    dkv.close()
+    return x[n0:n0 + n_new], {"steps": step, "accepted": accepted}

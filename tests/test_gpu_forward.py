@@ -1,0 +1,144 @@
+"""GPU parity of the verify pass (decoder forward against the KV cache) with the CPU oracle.
+
+Tolerance on logits / hidden rows: max-abs 1e-4 with fp32 storage, 2e-2 with bf16 storage
+(the contract of this repository's target; the fp32 figure is ~100x the fp32 accumulation noise of
+these shapes, the bf16 figure covers a flipped bf16 rounding of a cache entry)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2311_04951_amd as sv
+import seeded_inputs as si
+from gpu_util import dev, maxabs, model_pair, tol, weights_to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def _gpu_forward_chunks(gm, gkv, toks, chunks):
+    outs, i = [], 0
+    for c in chunks:
+        t = torch.tensor(toks[i:i + c][None].astype(np.int32), device=dev())
+        outs.append(sv.ss_verify_forward(gm, gkv, t, c)[0].cpu().numpy())
+        i += c
+    return np.concatenate(outs)
+
+
+@pytest.mark.parametrize("shape", [si.TINY_TARGET, si.TINY_DRAFT,
+                                   si.DecoderShape(2, 64, 2, 32, 96, 50, rope_base=500.0, rms_eps=1e-6, dtype="f32"),
+                                   si.DecoderShape(2, 256, 2, 128, 344, 300, dtype="f32")])
+def test_fp32_verify_logits_match_oracle(shape):
+    om, gm, _ = model_pair(shape, seed=3)
+    toks = si.token_ids(3, "toks", (70,), shape.vocab).numpy()
+    chunks = [16, 16, 1, 5, 5, 2, 9, 16]            # prefill chunks, single rows, K+1-row verify passes
+    gkv = sv.KVCache(gm, 1, 100)
+    got = _gpu_forward_chunks(gm, gkv, toks, chunks)
+    ref = om.forward(om.new_kv(100), toks)
+    assert maxabs(got, ref) < tol(shape)
+    assert sv.ss_kv_cache_get_len(gkv).tolist() == [70]
+    assert sv.ss_device_status(gm) == 0
+
+
+@pytest.mark.parametrize("shape", [si.DecoderShape(2, 128, 2, 64, 344, 512, dtype="bf16"),
+                                   si.DecoderShape(1, 512, 4, 128, 1376, 1000, dtype="bf16"),
+                                   si.DecoderShape(3, 256, 8, 32, 688, 333, dtype="bf16")])
+def test_bf16_verify_logits_match_oracle(shape):
+    om, gm, _ = model_pair(shape, seed=4)
+    toks = si.token_ids(4, "toks", (150,), shape.vocab).numpy()
+    chunks = [16] * 8 + [5, 1, 9, 7]                # crosses the 64- and 128-position cache blocks
+    gkv = sv.KVCache(gm, 1, 160)
+    got = _gpu_forward_chunks(gm, gkv, toks, chunks)
+    ref = om.forward(om.new_kv(160), toks)
+    assert maxabs(got, ref) < tol(shape)
+    # the bf16 path keeps fp32 activations (hi + lo split), so it is in fact far inside the bar
+    assert maxabs(got, ref) < 2e-3
+
+
+def test_rollback_then_reverify_matches_oracle():
+    """Rejected rows are dropped by a length write and overwritten by the next pass (Section 4.4)."""
+    shape = si.TINY_TARGET
+    om, gm, _ = model_pair(shape, seed=5)
+    toks = si.token_ids(5, "toks", (40,), shape.vocab).numpy()
+    gkv = sv.KVCache(gm, 1, 64)
+    _gpu_forward_chunks(gm, gkv, toks[:20], [16, 4])
+    junk = torch.tensor([[7, 8, 9, 10, 11]], dtype=torch.int32, device=dev())
+    sv.ss_verify_forward(gm, gkv, junk, 5)
+    na = torch.tensor([1], dtype=torch.int32, device=dev())          # keep x_n and one draft token
+    sv.ss_kv_cache_rollback(gkv, na, 5, n_accepted_host=[1])
+    assert sv.ss_kv_cache_get_len(gkv).tolist() == [22]
+    sv.ss_kv_cache_set_len(gkv, [20])                                # and drop those two as well
+    got = _gpu_forward_chunks(gm, gkv, toks[20:], [5, 15])
+    okv = om.new_kv(64)
+    om.forward(okv, toks[:20], want_logits=False)
+    ref = om.forward(okv, toks[20:])
+    assert maxabs(got, ref) < tol(shape)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_batched_ragged_lengths_match_per_sequence_oracle(dtype):
+    """Three sequences with different context lengths verified in one call; each must equal the
+    oracle run on that sequence alone.  Contexts are built with the raw append."""
+    shape = si.DecoderShape(2, 128, 2, 64, 344, 512, dtype=dtype)
+    w = si.decoder_weights(shape, seed=6)
+    om = oracle.Model(shape, w)
+    gm = sv.Model(shape, weights_to_device(w), max_rows=48, max_pos=512)
+    B, M = 3, 9
+    lens = [70, 3, 129]
+    gkv = sv.KVCache(gm, B, 200)
+    toks = si.token_ids(6, "toks", (B, M), shape.vocab)
+    refs = []
+    for b in range(B):
+        ctx = si.kv_context(shape, 6, f"ctx{b}", lens[b])
+        for l, (k, v) in enumerate(ctx):
+            sv.ss_kv_cache_append(gkv, l, b, 0, k.to(dev()), v.to(dev()))
+        okv = om.new_kv(200)
+        okv.append_raw(ctx)
+        refs.append(om.forward(okv, toks[b].numpy()))
+    sv.ss_kv_cache_set_len(gkv, lens)
+    got = sv.ss_verify_forward(gm, gkv, toks.to(dev()), M).cpu().numpy()
+    for b in range(B):
+        assert maxabs(got[b], refs[b]) < tol(shape), b
+    assert sv.ss_kv_cache_get_len(gkv).tolist() == [l + M for l in lens]
+    # ragged roll-back: different accept counts per sequence
+    na = torch.tensor([0, 8, 3], dtype=torch.int32, device=dev())
+    sv.ss_kv_cache_rollback(gkv, na, M)
+    assert sv.ss_kv_cache_get_len(gkv).tolist() == [lens[0] + 1, lens[1] + 9, lens[2] + 4]
+
+
+def test_single_7b_layer_verify_matches_oracle():
+    """One 7B-shaped bf16 layer, 5 query rows against 1024 cached positions (the microbench shape):
+    hidden rows out of the layer vs the oracle, max-abs 2e-2."""
+    shape = si.LAYER_7B
+    lw = si.layer_weights(shape, seed=0, layer=0)
+    w = {"embed": None, "gf": None, "lm_head": None, "layers": [lw]}
+    om = oracle.Model(shape, w)
+    gm = sv.Model(shape, weights_to_device(w), max_rows=16, max_pos=2048)
+    L, M = 1024, 5
+    ctx = si.kv_context(shape, 0, "ctx", L)
+    gkv = sv.KVCache(gm, 1, L + 64)
+    sv.ss_kv_cache_append(gkv, 0, 0, 0, ctx[0][0].to(dev()), ctx[0][1].to(dev()))
+    sv.ss_kv_cache_set_len(gkv, [L])
+    okv = om.new_kv(L + 64)
+    okv.append_raw(ctx)
+    h = si.normal(0, "h", (M, shape.d_model), 1.0)
+    got = sv.ss_decoder_layers_forward(gm, gkv, h.to(dev()).clone(), 1, M).cpu().numpy()
+    ref = om.layers_forward(okv, h.numpy())
+    assert maxabs(got, ref) < 2e-2
+    assert maxabs(got, ref) < 1e-3
+
+
+def test_capacity_and_shape_errors_come_from_the_host():
+    shape = si.TINY_DRAFT
+    _, gm, _ = model_pair(shape, seed=7, max_rows=8)
+    gkv = sv.KVCache(gm, 1, 10)
+    t = torch.zeros((1, 8), dtype=torch.int32, device=dev())
+    sv.ss_verify_forward(gm, gkv, t, 8, logits=False)
+    with pytest.raises(sv.SpecVerifyError) as e:
+        sv.ss_verify_forward(gm, gkv, t, 8, logits=False)           # 8 + 8 > 10
+    assert e.value.code == sv.SS_ECAPACITY
+    with pytest.raises(sv.SpecVerifyError) as e:
+        sv.ss_verify_forward(gm, sv.KVCache(gm, 2, 10), torch.zeros((2, 8), dtype=torch.int32, device=dev()), 8)
+    assert e.value.code == sv.SS_EINVAL                              # 16 rows > max_rows 8
+    bad = torch.full((1, 1), shape.vocab + 5, dtype=torch.int32, device=dev())
+    sv.ss_verify_forward(gm, gkv, bad, 1, logits=False)
+    assert sv.ss_device_status(gm) == 1 and sv.ss_device_status(gm) == 0   # clamped, flagged, cleared

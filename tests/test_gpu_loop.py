@@ -1,0 +1,103 @@
+"""The whole speculative loop on the GPU path (tiny fp32 pair): greedy speculative == greedy
+autoregressive token for token, draft steps equal oracle draft steps, and a lock-step comparison of a
+sampled run with the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2311_04951_amd as sv
+import seeded_inputs as si
+from paper_2311_04951_amd import generate as gen
+from gpu_util import dev, maxabs, weights_to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def _pair(seed, early=False):
+    tw = si.decoder_weights(si.TINY_TARGET, seed)
+    if early:
+        dshape, dw = si.early_exit_draft(si.TINY_TARGET, tw, 1)
+    else:
+        dshape, dw = si.TINY_DRAFT, si.decoder_weights(si.TINY_DRAFT, seed + 100)
+    gt = sv.Model(si.TINY_TARGET, weights_to_device(tw), max_rows=16, max_pos=256)
+    gd = sv.Model(dshape, weights_to_device(dw), max_rows=16, max_pos=256)
+    return (oracle.Model(si.TINY_TARGET, tw), oracle.Model(dshape, dw)), (gt, gd)
+
+
+@pytest.mark.parametrize("K,early", [(4, False), (2, True), (8, True)])
+def test_greedy_speculative_equals_greedy_autoregressive_on_gpu(K, early):
+    (ot, od), (gt, gd) = _pair(0, early)
+    prompt = si.token_ids(0, "prompt", (32,), 1024).numpy().tolist()
+    ar = gen.autoregressive_generate(gt, prompt, 64, 0.0)
+    sp, stats = gen.speculative_generate(gt, gd, prompt, 64, K, 0.0)
+    assert sp == ar
+    # and the GPU's greedy stream is the oracle's (argmax gaps of this model are far above 1e-4)
+    assert ar == oracle.autoregressive_generate(ot, prompt, 64, 0.0)
+    assert all(0 <= a <= K for a in stats["accepted"])
+
+
+def test_greedy_with_draft_equal_to_target_accepts_everything_on_gpu():
+    """Every draft token is accepted, so every step after the first takes the two-token draft
+    catch-up; the stream must still be the autoregressive one."""
+    (ot, _), (gt, _) = _pair(3)
+    prompt = si.token_ids(3, "prompt", (9,), 1024).numpy().tolist()
+    ar = gen.autoregressive_generate(gt, prompt, 30, 0.0)
+    sp, stats = gen.speculative_generate(gt, gt, prompt, 30, 3, 0.0)
+    assert sp == ar and all(a == 3 for a in stats["accepted"])
+
+
+def test_sampled_run_in_lock_step_with_the_oracle():
+    """Temperature 1, K = 4, 64 tokens.  Each step the oracle is run on the GPU's history: logits by
+    tolerance, draft sampling and accept/resample decisions bit-exact on the GPU's own q and p."""
+    K, n_new, T = 4, 64, 1.0
+    (ot, od), (gt, gd) = _pair(1, early=True)
+    prompt = si.token_ids(1, "prompt", (32,), 1024).numpy().tolist()
+    ud = si.uniforms(1, "ud", (n_new, K)).numpy()
+    ua = si.uniforms(1, "ua", (n_new, K + 1)).numpy()
+    seen = []
+
+    def obs(s):
+        seen.append({k: (v.detach().cpu().numpy().copy() if hasattr(v, "detach") else v) for k, v in s.items()})
+
+    sp, stats = gen.speculative_generate(gt, gd, prompt, n_new, K, T, ud, ua, observer=obs)
+    assert len(sp) == n_new and stats["steps"] == len(seen)
+    # replay on the oracle, following the GPU's committed history
+    x = list(prompt)
+    otkv, odkv = ot.new_kv(256), od.new_kv(256)
+    ot.forward(otkv, x[:-1], want_logits=False)
+    od.forward(odkv, x[:-1], want_logits=False)
+    pending = [x[-1]]
+    for s in seen:
+        n, st = len(x), s["step"]
+        d = s["draft"][0].tolist()
+        feed = pending
+        for i in range(K):
+            ql = od.forward(odkv, feed)[-1]
+            assert maxabs(s["q"][0, i], oracle.softmax(ql, T)) < 1e-5
+            assert d[i] == oracle.sample(s["q"][0, i], ud[st][i])        # draft sampling: bit-exact on GPU q
+            feed = [d[i]]
+        pl = ot.forward(otkv, [x[-1]] + d)
+        assert maxabs(s["logits"][0], pl) < 1e-4
+        ona, onx = oracle.speculative_accept(s["p"], s["q"], s["draft"], ua[st][None])
+        assert ona.tolist() == s["n_accepted"].tolist() and onx.tolist() == s["next"].tolist()
+        a, y = int(ona[0]), int(onx[0])
+        x += d[:a] + [y]
+        otkv.set_len(n + a)
+        if a < K:
+            odkv.set_len(n + a)
+            pending = [y]
+        else:
+            pending = [d[K - 1], y]
+    assert x[len(prompt):len(prompt) + n_new] == sp
+    assert 0 < sum(stats["accepted"]) < K * stats["steps"]      # both accepts and rejections occurred
+
+
+def test_sampled_autoregressive_matches_oracle_stream():
+    (ot, _), (gt, _) = _pair(2)
+    prompt = si.token_ids(2, "prompt", (16,), 1024).numpy().tolist()
+    u = si.uniforms(2, "u", (24,)).numpy()
+    got = gen.autoregressive_generate(gt, prompt, 24, 1.0, u)
+    ref = oracle.autoregressive_generate(ot, prompt, 24, 1.0, u)
+    # identical unless a uniform falls within float noise of a CDF edge (probability ~1e-5 per token)
+    assert got == ref
