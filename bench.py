@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark of the verify pass of speculative sampling on one MI355X.
+
+Workload (default): the full 7B-shaped bf16 target (32 layers, d 4096, 32 heads x 128, FFN 11008,
+vocab 32000, random init), batch 1, K = 4 draft tokens (5 query rows), prompt of 128 random ids.
+A timed "step" is one verify pass: ss_verify_forward over the 5 rows against the KV cache, softmax
+of the 5 logit rows, the modified rejection step against the draft's q rows, and the device-side
+cache roll-back.  Inputs (weights, cache, draft rows) are resident in HBM before timing starts.
+The same run also times the end-to-end speculative loop (K draft steps + verify + accept per
+step, draft = the target's first 2 layers + shared norm and head), an autoregressive baseline, a
+per-kernel-class event profile for the roofline figure, and the CPU oracle on a bounded sample.
+
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12  # B/s, MI355X published peak
+
+
+def build_7b(si, sv, torch, seed, n_layers, dev):
+    """Random-init weights generated on the GPU, packed once into the library's fused matrices."""
+    shape = si.DecoderShape(**{**si.FULL_7B.as_dict(), "n_layers": n_layers})
+    packed = []
+    for l in range(n_layers):
+        lw = si.layer_weights(shape, seed, l, device=dev)
+        packed.append({"wqkv": torch.cat([lw["wq"], lw["wk"], lw["wv"]], 0), "wo": lw["wo"],
+                       "wgu": torch.cat([lw["wg"], lw["wu"]], 0), "wd": lw["wd"], "g1": lw["g1"], "g2": lw["g2"]})
+        del lw
+    dt = si.storage_dtype(shape)
+    io = {"embed": si.normal(seed, "embed", (shape.vocab, shape.d_model), 0.02, device=dev, dtype=dt),
+          "gf": si.normal(seed, "gf", (shape.d_model,), 0.02, mean=1.0, device=dev),
+          "lm_head": si.normal(seed, "lm_head", (shape.vocab, shape.d_model), 0.02, device=dev, dtype=dt)}
+    return shape, packed, io
+
+
+def layer_bytes(shape):
+    d, F, W = shape.d_model, shape.d_ff, shape.n_heads * shape.head_dim
+    return 2 * (3 * W * d + d * W + 3 * d * F)
+
+
+def verify_pass_bytes(shape, L, M):
+    """Algorithmic HBM bytes of one verify pass: every weight once, the KV context once, the new K/V
+    rows, the logits."""
+    W = shape.n_heads * shape.head_dim
+    kv_read = shape.n_layers * 2 * (L + M) * W * 2
+    kv_write = shape.n_layers * 2 * M * W * 2
+    head = shape.vocab * shape.d_model * 2
+    return shape.n_layers * layer_bytes(shape) + head + kv_read + kv_write + M * shape.vocab * 4
+
+
+def cpu_baseline(si, torch, shape, packed, io, prompt_len, M, seconds_target=15.0):
+    """The oracle, as it stands, on a bounded sample: the first n layers + LM head of one M-row
+    verify pass against a synthetic context of prompt_len rows; extrapolated by weight bytes."""
+    import numpy as np
+    import oracle
+    d, W = shape.d_model, shape.n_heads * shape.head_dim
+
+    def unpack(p):
+        return {"wq": p["wqkv"][:W].cpu(), "wk": p["wqkv"][W:2 * W].cpu(), "wv": p["wqkv"][2 * W:].cpu(),
+                "wo": p["wo"].cpu(), "wg": p["wgu"][:shape.d_ff].cpu(), "wu": p["wgu"][shape.d_ff:].cpu(),
+                "wd": p["wd"].cpu(), "g1": p["g1"].cpu(), "g2": p["g2"].cpu()}
+
+    def run(n_layers):
+        s = si.DecoderShape(**{**shape.as_dict(), "n_layers": n_layers})
+        w = {"embed": io["embed"].cpu(), "gf": io["gf"].cpu(), "lm_head": io["lm_head"].cpu(),
+             "layers": [unpack(packed[l]) for l in range(n_layers)]}
+        om = oracle.Model(s, w)
+        kv = om.new_kv(prompt_len + M + 1)
+        kv.append_raw(si.kv_context(s, 1, "cpu_ctx", prompt_len))
+        toks = si.token_ids(1, "cpu_toks", (M,), s.vocab).numpy()
+        t0 = time.perf_counter()
+        om.forward(kv, toks)
+        return time.perf_counter() - t0
+
+    t1 = run(1)
+    head_b = shape.vocab * d * 2
+    n = int(max(1, min(shape.n_layers, round(seconds_target / max(t1, 1e-3)))))
+    t = run(n) if n > 1 else t1
+    frac = (n * layer_bytes(shape) + head_b) / (shape.n_layers * layer_bytes(shape) + head_b)
+    t_full = t / frac
+    return {"value": M / t_full, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"first {n} of {shape.n_layers} layers + LM head of one {M}-row verify pass against "
+                      f"{prompt_len} cached positions ({t:.1f} s), extrapolated by weight bytes to the full pass"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--K", type=int, default=4)
+    ap.add_argument("--layers", type=int, default=32, help="decoder layers (32 = the named workload)")
+    ap.add_argument("--gen-tokens", type=int, default=256)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-e2e", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2311_04951_amd as sv
+    import seeded_inputs as si
+    from paper_2311_04951_amd import generate as gen
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K, M, T = args.K, args.K + 1, 1.0
+    prompt_len = 128
+    shape, packed, io = build_7b(si, sv, torch, 0, args.layers, dev)
+    max_pos = 4096
+    target = sv.Model(shape, io, max_rows=16, max_pos=max_pos, packed_layers=packed)
+    dshape = si.DecoderShape(**{**shape.as_dict(), "n_layers": min(2, args.layers)})
+    draft = sv.Model(dshape, io, max_rows=16, max_pos=max_pos, packed_layers=packed[:dshape.n_layers])
+    V = shape.vocab
+    prompt = si.token_ids(0, "prompt", (prompt_len,), V).tolist()
+
+    # ---- end-to-end speculative loop and autoregressive baseline (also warms everything up)
+    e2e = None
+    if not args.no_e2e:
+        n_new = args.gen_tokens
+        ud = si.uniforms(0, "ud", (n_new, K))
+        ua = si.uniforms(0, "ua", (n_new, K + 1))
+        toks, st = gen.speculative_generate(target, draft, prompt, n_new, K, T, ud, ua)
+        ar_stats = {}
+        n_ar = min(64, n_new)
+        gen.autoregressive_generate(target, prompt, n_ar, T, si.uniforms(0, "uar", (n_ar,)), stats=ar_stats)
+        e2e = {"accepted_tokens_per_s": st["generated"] / st["loop_seconds"], "generated": st["generated"],
+               "steps": st["steps"], "mean_accepted_per_step": sum(st["accepted"]) / max(1, st["steps"]),
+               "ms_per_step": 1e3 * st["loop_seconds"] / max(1, st["steps"]),
+               "autoregressive_tokens_per_s": n_ar / ar_stats["loop_seconds"],
+               "speedup_vs_autoregressive": (st["generated"] / st["loop_seconds"]) / (n_ar / ar_stats["loop_seconds"]),
+               "temperature": T, "K": K, "draft": f"first {dshape.n_layers} target layers + shared norm and LM head"}
+
+    # ---- state for the verify-pass legs: prompt in the cache, real draft rows from the draft model
+    total_steps = args.warmup + 2 * args.steps + 4
+    tkv = sv.KVCache(target, 1, prompt_len + M * total_steps + 16)
+    dkv = sv.KVCache(draft, 1, prompt_len + K + 16)
+    gen.prefill(target, tkv, prompt[:-1])
+    gen.prefill(draft, dkv, prompt[:-1])
+    vt = torch.empty((1, M), dtype=torch.int32, device=dev)
+    vt[0, 0] = prompt[-1]
+    q = torch.zeros((1, K, V), dtype=torch.float32, device=dev)
+    udd = si.uniforms(0, "bench_ud", (K,)).to(dev)
+    feed = vt[:, 0:1]
+    for i in range(K):
+        sv.ss_draft_step(draft, dkv, feed, 1, T, udd[i:i + 1], q[0, i], K * V, vt[0, i + 1:i + 2])
+        feed = vt[:, i + 1:i + 2]
+    d = vt[:, 1:].contiguous()
+    u = si.uniforms(0, "bench_ua", (total_steps, K + 1)).to(dev)
+    logits = torch.empty((1, M, V), dtype=torch.float32, device=dev)
+    p = torch.empty_like(logits)
+    na = torch.empty(1, dtype=torch.int32, device=dev)
+    nx = torch.empty(1, dtype=torch.int32, device=dev)
+    counter = [0]
+
+    def verify_step():
+        i = counter[0]
+        counter[0] += 1
+        sv.ss_verify_forward(target, tkv, vt, M, logits)
+        sv.ss_softmax(logits, T, p)
+        sv.ss_speculative_accept(p, q, d, u[i:i + 1], na, nx)
+        sv.ss_kv_cache_rollback(tkv, na, M)
+
+    for _ in range(args.warmup):
+        verify_step()
+    torch.cuda.synchronize()
+    L_start = int(sv.ss_kv_cache_get_len(tkv)[0])
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        verify_step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    L_end = int(sv.ss_kv_cache_get_len(tkv)[0])
+    ms_per_step = 1e3 * dt / args.steps
+    value = M * args.steps / dt
+    L_mean = 0.5 * (L_start + L_end)
+    pass_bytes = verify_pass_bytes(shape, L_mean, M)
+
+    # ---- the same steps again with an event pair around every forward-path launch
+    sv.ss_profile_enable(target, True)
+    for _ in range(args.steps):
+        verify_step()
+    torch.cuda.synchronize()
+    prof = sv.ss_profile_read(target)
+    sv.ss_profile_enable(target, False)
+    classes = {k: {"avg_us": 1e3 * ms / max(1, n), "launches_per_step": n / args.steps} for k, (ms, n) in prof.items() if n}
+    gu = classes["gateup_gemm"]
+    gu_bytes = 2 * shape.d_ff * shape.d_model * 2          # W_gate | W_up streamed once per launch
+    achieved = gu_bytes / (gu["avg_us"] * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": "gemm_kernel<bf16, SWIGLU> (gate/up projection, 42.8% of the pass's bytes)",
+                "achieved": achieved, "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": achieved / (HBM_PEAK / 1e9),
+                "traffic": None, "algorithmic_bytes_per_launch": gu_bytes}
+
+    out = {
+        "metric": "verify-pass tokens/s", "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"full 7B-shaped target ({shape.n_layers} layers, d 4096, 32x128 heads, FFN 11008, vocab 32000), "
+                               f"bf16, batch 1, K={K} ({M} query rows), KV context {L_start}..{L_end}, random init",
+                   "step": "ss_verify_forward + ss_softmax + ss_speculative_accept + ss_kv_cache_rollback"},
+        "verify_pass": {"algorithmic_bytes": pass_bytes, "hbm_frac_of_peak": pass_bytes / (dt / args.steps) / HBM_PEAK,
+                        "hbm_GBps": pass_bytes / (dt / args.steps) / 1e9, "kernel_classes": classes},
+        "roofline": roofline,
+        "end_to_end": e2e,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(si, torch, shape, packed, io, prompt_len, M)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -78,6 +78,17 @@ const char *ss_last_error(void);
  * bit 0: a token id outside [0, vocab) reached a kernel and was clamped. */
 int ss_device_status(ss_model *model, ss_stream stream, int32_t *status_host);
 
+/* ---- measurement ----------------------------------------------------------------------------
+ * With profiling on, every kernel launch of the forward path on `model` is bracketed by a HIP
+ * event pair recorded on the call's stream.  ss_profile_read waits for the recorded events, adds
+ * the elapsed times up per kernel class and clears the record.  Classes (n_classes >= 8):
+ * 0 RMSNorm, 1 QKV GEMM (+rotary, +cache append), 2 attention (+merge), 3 O-projection GEMM,
+ * 4 gate/up GEMM (+SwiGLU), 5 down-projection GEMM, 6 LM-head GEMM, 7 other.
+ * total_ms_host / launches_host: host arrays [n_classes].  Event recording perturbs the pass a
+ * little, so timed throughput runs keep it off. */
+int ss_profile_enable(ss_model *model, int32_t on);
+int ss_profile_read(ss_model *model, int32_t n_classes, double *total_ms_host, int64_t *launches_host);
+
 /* ---- model -------------------------------------------------------------------------------
  * Creates a handle over caller-owned weights (which must outlive it) and allocates the
  * model's activation workspace and rotary table on the current device (the only allocations

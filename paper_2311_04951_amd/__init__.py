@@ -24,8 +24,10 @@ EXPORTS = [
     "ss_kv_cache_free", "ss_kv_cache_bytes", "ss_kv_cache_append", "ss_kv_cache_set_len",
     "ss_kv_cache_get_len", "ss_kv_cache_rollback", "ss_verify_forward", "ss_decoder_layers_forward",
     "ss_draft_step", "ss_softmax", "ss_speculative_accept", "ss_speculative_accept_logits",
-    "ss_greedy_accept",
+    "ss_greedy_accept", "ss_profile_enable", "ss_profile_read",
 ]
+
+PROFILE_CLASSES = ["rmsnorm", "qkv_gemm", "attention", "oproj_gemm", "gateup_gemm", "down_gemm", "head_gemm", "other"]
 
 
 class SpecVerifyError(RuntimeError):
@@ -80,6 +82,8 @@ def lib():
             "ss_speculative_accept": [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp],
             "ss_speculative_accept_logits": [vp, vp, f32, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp],
             "ss_greedy_accept": [vp, vp, i32, i32, i32, vp, vp, vp],
+            "ss_profile_enable": [vp, i32],
+            "ss_profile_read": [vp, i32, vp, vp],
         }
         for name, args in sig.items():
             getattr(L, name).argtypes = args
@@ -292,3 +296,16 @@ def ss_device_status(model: Model, stream=None) -> int:
     out = C.c_int32(0)
     _check(lib().ss_device_status(model.handle, _stream(stream), C.byref(out)))
     return out.value
+
+
+def ss_profile_enable(model: Model, on: bool):
+    _check(lib().ss_profile_enable(model.handle, int(bool(on))))
+
+
+def ss_profile_read(model: Model):
+    """-> {class name: (total_ms, launches)} for the launches recorded since profiling was enabled."""
+    n = len(PROFILE_CLASSES)
+    ms = (C.c_double * n)()
+    cnt = (C.c_int64 * n)()
+    _check(lib().ss_profile_read(model.handle, n, ms, cnt))
+    return {PROFILE_CLASSES[i]: (ms[i], cnt[i]) for i in range(n)}

@@ -58,6 +58,38 @@ struct ss_model {
     float2 *rope;     // [max_pos][hd/2]
     int32_t *status;
     std::vector<void *> owned;
+    // optional per-kernel-class timing (ss_profile_*): event pairs recorded around launches
+    bool prof = false;
+    std::vector<hipEvent_t> ev;
+    std::vector<int> ev_tag;
+    size_t ev_used = 0;
+};
+
+enum ProfTag { PT_NORM = 0, PT_QKV, PT_ATTN, PT_OPROJ, PT_GATEUP, PT_DOWN, PT_HEAD, PT_OTHER, PT_COUNT };
+
+// records an event pair around the launches issued while it is alive (only when profiling is on)
+struct ProfScope {
+    ss_model *m;
+    hipStream_t st;
+    bool on;
+    ProfScope(ss_model *m_, int tag, hipStream_t st_) : m(m_), st(st_), on(m_->prof) {
+        if (!on) return;
+        if (m->ev_used + 2 > m->ev.size()) {
+            for (int i = 0; i < 2; ++i) {
+                hipEvent_t e;
+                if (hipEventCreate(&e) != hipSuccess) { on = false; return; }
+                m->ev.push_back(e);
+            }
+        }
+        m->ev_tag.resize(m->ev.size() / 2);
+        m->ev_tag[m->ev_used / 2] = tag;
+        (void)hipEventRecord(m->ev[m->ev_used], st);
+    }
+    ~ProfScope() {
+        if (!on) return;
+        (void)hipEventRecord(m->ev[m->ev_used + 1], st);
+        m->ev_used += 2;
+    }
 };
 
 struct ss_kv_cache {
@@ -85,6 +117,7 @@ static int dev_alloc(ss_model *m, void **p, size_t bytes, bool zero) {
 extern "C" int ss_model_destroy(ss_model *m) {
     if (!m) return SS_OK;
     for (void *p : m->owned) (void)hipFree(p);
+    for (hipEvent_t e : m->ev) (void)hipEventDestroy(e);
     delete m;
     return SS_OK;
 }
@@ -161,6 +194,30 @@ extern "C" int ss_device_status(ss_model *m, ss_stream stream, int32_t *status_h
     HIP_TRY(hipMemcpyAsync(status_host, m->status, sizeof(int32_t), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     HIP_TRY(hipMemsetAsync(m->status, 0, sizeof(int32_t), st));
+    return SS_OK;
+}
+
+extern "C" int ss_profile_enable(ss_model *m, int32_t on) {
+    if (!m) return fail(SS_EINVAL, "ss_profile_enable: NULL model");
+    m->prof = on != 0;
+    m->ev_used = 0;
+    return SS_OK;
+}
+
+extern "C" int ss_profile_read(ss_model *m, int32_t n_classes, double *total_ms_host, int64_t *launches_host) {
+    if (!m || !total_ms_host || !launches_host || n_classes < PT_COUNT) return fail(SS_EINVAL, "ss_profile_read: bad argument (need %d classes)", (int)PT_COUNT);
+    for (int i = 0; i < n_classes; ++i) {
+        total_ms_host[i] = 0.0;
+        launches_host[i] = 0;
+    }
+    for (size_t i = 0; i + 1 < m->ev_used; i += 2) {
+        HIP_TRY(hipEventSynchronize(m->ev[i + 1]));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, m->ev[i], m->ev[i + 1]));
+        total_ms_host[m->ev_tag[i / 2]] += ms;
+        launches_host[m->ev_tag[i / 2]] += 1;
+    }
+    m->ev_used = 0;
     return SS_OK;
 }
 
@@ -294,14 +351,20 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
         const ss_layer_weights &L = m->layers[l];
         char *kc = (char *)kv->k + kv->layer_elems * l * kv->esz;
         char *vc = (char *)kv->v + kv->layer_elems * l * kv->esz;
-        launch_rmsnorm_pack(c.dtype, m->h, L.g1, R, d, c.rms_eps, m->act_a, pl * d, d, st);
+        {
+            ProfScope ps(m, PT_NORM, st);
+            launch_rmsnorm_pack(c.dtype, m->h, L.g1, R, d, c.rms_eps, m->act_a, pl * d, d, st);
+        }
         GemmArgs g{};
         g.W = L.wqkv; g.N = 3 * W; g.K = d;
         g.act = m->act_a; g.act_plane = pl * d; g.ld_act = d; g.R = R;
         g.act_out = m->act_q; g.act_out_plane = pl * W; g.ld_act_out = W;
         g.H = c.n_heads; g.hd = c.head_dim; g.M = M; g.S = kv->S; g.max_pos = c.max_pos;
         g.len = kv->len_dev; g.rope = m->rope; g.kcache = kc; g.vcache = vc;
-        launch_gemm(c.dtype, EPI_QKV, g, st);
+        {
+            ProfScope ps(m, PT_QKV, st);
+            launch_gemm(c.dtype, EPI_QKV, g, st);
+        }
 
         AttnArgs a{};
         a.q = m->act_q; a.q_plane = pl * W; a.ldq = W;
@@ -311,26 +374,40 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
         a.part_o = m->part_o; a.part_m = m->part_m; a.part_l = m->part_l;
         a.act_out = m->act_o; a.act_out_plane = pl * W; a.ld_out = W;
         a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)c.head_dim));
-        launch_attention(c.dtype, a, st);
+        {
+            ProfScope ps(m, PT_ATTN, st);
+            launch_attention(c.dtype, a, st);
+        }
 
         GemmArgs o{};
         o.W = L.wo; o.N = d; o.K = W;
         o.act = m->act_o; o.act_plane = pl * W; o.ld_act = W; o.R = R;
         o.out = m->h; o.resid = m->h; o.ldo = d;
-        launch_gemm(c.dtype, EPI_RESID, o, st);
-
-        launch_rmsnorm_pack(c.dtype, m->h, L.g2, R, d, c.rms_eps, m->act_a, pl * d, d, st);
+        {
+            ProfScope ps(m, PT_OPROJ, st);
+            launch_gemm(c.dtype, EPI_RESID, o, st);
+        }
+        {
+            ProfScope ps(m, PT_NORM, st);
+            launch_rmsnorm_pack(c.dtype, m->h, L.g2, R, d, c.rms_eps, m->act_a, pl * d, d, st);
+        }
         GemmArgs u{};
         u.W = L.wgu; u.N = F; u.K = d;
         u.act = m->act_a; u.act_plane = pl * d; u.ld_act = d; u.R = R;
         u.act_out = m->act_z; u.act_out_plane = pl * F; u.ld_act_out = F;
-        launch_gemm(c.dtype, EPI_SWIGLU, u, st);
+        {
+            ProfScope ps(m, PT_GATEUP, st);
+            launch_gemm(c.dtype, EPI_SWIGLU, u, st);
+        }
 
         GemmArgs dn{};
         dn.W = L.wd; dn.N = d; dn.K = F;
         dn.act = m->act_z; dn.act_plane = pl * F; dn.ld_act = F; dn.R = R;
         dn.out = m->h; dn.resid = m->h; dn.ldo = d;
-        launch_gemm(c.dtype, EPI_RESID, dn, st);
+        {
+            ProfScope ps(m, PT_DOWN, st);
+            launch_gemm(c.dtype, EPI_RESID, dn, st);
+        }
     }
     launch_len_add(kv->len_dev, batch, M, st);
     for (int b = 0; b < batch; ++b) kv->len_ub[b] += M;
@@ -340,7 +417,11 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
 static void run_head(ss_model *m, int nrows, int row0, int stride, float *logits, hipStream_t st) {
     const ss_model_cfg &c = m->cfg;
     const size_t pl = (size_t)m->R16;
-    launch_rmsnorm_pack_rows(c.dtype, m->h, m->gf, nrows, row0, stride, c.d_model, c.rms_eps, m->act_a, pl * c.d_model, c.d_model, st);
+    {
+        ProfScope ps(m, PT_NORM, st);
+        launch_rmsnorm_pack_rows(c.dtype, m->h, m->gf, nrows, row0, stride, c.d_model, c.rms_eps, m->act_a, pl * c.d_model, c.d_model, st);
+    }
+    ProfScope ps(m, PT_HEAD, st);
     GemmArgs g{};
     g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model;
     g.act = m->act_a; g.act_plane = pl * c.d_model; g.ld_act = c.d_model; g.R = nrows;

@@ -10,6 +10,8 @@ row short, so its next call feeds two tokens.
 """
 from __future__ import annotations
 
+import time
+
 import torch
 
 from . import (KVCache, Model, ss_draft_step, ss_greedy_accept, ss_kv_cache_rollback, ss_softmax,
@@ -24,8 +26,10 @@ def prefill(model: Model, kv: KVCache, tokens, chunk: int = 16):
         ss_verify_forward(model, kv, t, t.shape[1], logits=False)
 
 
-def autoregressive_generate(target: Model, prompt, n_new: int, temperature: float, u=None, max_seq=None):
-    """One target call per token; the sampled token never leaves the device between steps."""
+def autoregressive_generate(target: Model, prompt, n_new: int, temperature: float, u=None, max_seq=None,
+                            stats=None):
+    """One target call per token; the sampled token never leaves the device between steps.  `stats`
+    (a dict, optional) receives loop_seconds: the wall time of the decode loop without the prefill."""
     dev = torch.device("cuda")
     V = target.shape.vocab
     kv = KVCache(target, 1, max_seq or (len(prompt) + n_new + 1))
@@ -36,9 +40,14 @@ def autoregressive_generate(target: Model, prompt, n_new: int, temperature: floa
     ud = None
     if temperature > 0:
         ud = torch.as_tensor(u, dtype=torch.float32).to(dev)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
     for i in range(n_new):
         ss_draft_step(target, kv, buf[i:i + 1], 1, temperature, ud[i:i + 1] if ud is not None else None, q, V,
                       buf[i + 1:i + 2])
+    torch.cuda.synchronize()
+    if stats is not None:
+        stats["loop_seconds"] = time.perf_counter() - t0
     out = buf[1:].tolist()
     kv.close()
     return out
@@ -71,6 +80,8 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
         ua_all = torch.as_tensor(u_accept, dtype=torch.float32).to(dev)
     accepted = []
     step = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
     while len(x) - n0 < n_new:
         feed = torch.tensor([pending], dtype=torch.int32, device=dev)
         for i in range(K):
@@ -96,6 +107,9 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
         pending = [y] if a < K else [dl[K - 1], y]
         accepted.append(a)
         step += 1
+    torch.cuda.synchronize()
+    loop_s = time.perf_counter() - t0
     tkv.close()
     dkv.close()
-    return x[n0:n0 + n_new], {"steps": step, "accepted": accepted}
+    return x[n0:n0 + n_new], {"steps": step, "accepted": accepted, "loop_seconds": loop_s,
+                              "generated": len(x) - n0}
