@@ -75,15 +75,18 @@ typedef struct ss_kv_cache ss_kv_cache;
 const char *ss_last_error(void);
 
 /* Reads and clears the device status word of `model` (synchronises `stream`).
- * bit 0: a token id outside [0, vocab) reached a kernel and was clamped. */
+ * bit 0: a token id outside [0, vocab) reached a kernel and was clamped.
+ * bit 1: a device-wide barrier of the persistent verify kernel gave up waiting (its spin is bounded);
+ *        the results of that call are invalid and the barrier state has been reset. */
 int ss_device_status(ss_model *model, ss_stream stream, int32_t *status_host);
 
 /* ---- measurement ----------------------------------------------------------------------------
  * With profiling on, every kernel launch of the forward path on `model` is bracketed by a HIP
  * event pair recorded on the call's stream.  ss_profile_read waits for the recorded events, adds
- * the elapsed times up per kernel class and clears the record.  Classes (n_classes >= 8):
+ * the elapsed times up per kernel class and clears the record.  Classes (n_classes >= 9):
  * 0 RMSNorm, 1 QKV GEMM (+rotary, +cache append), 2 attention (+merge), 3 O-projection GEMM,
- * 4 gate/up GEMM (+SwiGLU), 5 down-projection GEMM, 6 LM-head GEMM, 7 other.
+ * 4 gate/up GEMM (+SwiGLU), 5 down-projection GEMM, 6 LM-head GEMM, 7 other, 8 the persistent
+ * verify kernel (the whole forward of a call with at most 16 rows is one launch of it).
  * total_ms_host / launches_host: host arrays [n_classes].  Event recording perturbs the pass a
  * little, so timed throughput runs keep it off. */
 int ss_profile_enable(ss_model *model, int32_t on);
@@ -96,6 +99,14 @@ int ss_profile_read(ss_model *model, int32_t n_classes, double *total_ms_host, i
  * second model whose pointers alias the target's. */
 int ss_model_create(const ss_model_cfg *cfg, const ss_weights *weights, ss_model **out);
 int ss_model_destroy(ss_model *model);
+
+/* Selects how the forward path of `model` is launched.  0 (default): one kernel per phase (RMSNorm,
+ * QKV GEMM, attention, O projection, gate/up GEMM, down projection ...).  1: calls with at most 16
+ * rows run as ONE persistent cooperative kernel (one workgroup per compute unit, device-wide
+ * barriers between phases, weight loads of the next phase in flight across the barrier); larger
+ * calls keep the per-phase launches.  Both paths produce results within the same tolerance of the
+ * method; SS_EINVAL if the persistent kernel cannot be co-resident on this device. */
+int ss_model_set_persistent(ss_model *model, int32_t on);
 
 /* ---- KV cache (Sections 2, 4.2, 4.4) --------------------------------------------------------
  * kv_cache_alloc: a contiguous, page-free cache for `batch` sequences of up to `max_seq`

@@ -24,10 +24,11 @@ EXPORTS = [
     "ss_kv_cache_free", "ss_kv_cache_bytes", "ss_kv_cache_append", "ss_kv_cache_set_len",
     "ss_kv_cache_get_len", "ss_kv_cache_rollback", "ss_verify_forward", "ss_decoder_layers_forward",
     "ss_draft_step", "ss_softmax", "ss_speculative_accept", "ss_speculative_accept_logits",
-    "ss_greedy_accept", "ss_profile_enable", "ss_profile_read",
+    "ss_greedy_accept", "ss_profile_enable", "ss_profile_read", "ss_model_set_persistent",
 ]
 
-PROFILE_CLASSES = ["rmsnorm", "qkv_gemm", "attention", "oproj_gemm", "gateup_gemm", "down_gemm", "head_gemm", "other"]
+PROFILE_CLASSES = ["rmsnorm", "qkv_gemm", "attention", "oproj_gemm", "gateup_gemm", "down_gemm", "head_gemm", "other",
+                   "verify_persistent"]
 
 
 class SpecVerifyError(RuntimeError):
@@ -83,6 +84,7 @@ def lib():
             "ss_speculative_accept_logits": [vp, vp, f32, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp],
             "ss_greedy_accept": [vp, vp, i32, i32, i32, vp, vp, vp],
             "ss_profile_enable": [vp, i32],
+            "ss_model_set_persistent": [vp, i32],
             "ss_profile_read": [vp, i32, vp, vp],
         }
         for name, args in sig.items():
@@ -160,8 +162,8 @@ class Model:
         self.handle = h
 
     def close(self):
-        if getattr(self, "handle", None):
-            lib().ss_model_destroy(self.handle)
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.ss_model_destroy(self.handle)
             self.handle = None
 
     __del__ = close
@@ -175,8 +177,8 @@ class KVCache:
         self.handle = h
 
     def close(self):
-        if getattr(self, "handle", None):
-            lib().ss_kv_cache_free(self.handle)
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.ss_kv_cache_free(self.handle)
             self.handle = None
 
     __del__ = close
@@ -296,6 +298,10 @@ def ss_device_status(model: Model, stream=None) -> int:
     out = C.c_int32(0)
     _check(lib().ss_device_status(model.handle, _stream(stream), C.byref(out)))
     return out.value
+
+
+def ss_model_set_persistent(model: Model, on: bool):
+    _check(lib().ss_model_set_persistent(model.handle, int(bool(on))))
 
 
 def ss_profile_enable(model: Model, on: bool):

@@ -3,10 +3,12 @@
 // No arithmetic of the method lives here.
 #include "../../include/specverify.h"
 #include "ss_kernels.h"
+#include "ss_mega.h"
 
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <string>
@@ -58,6 +60,15 @@ struct ss_model {
     float2 *rope;     // [max_pos][hd/2]
     int32_t *status;
     std::vector<void *> owned;
+    // persistent verify kernel: phase programs (device), barrier state, norm partials
+    int mega_G = 0;                 // workgroups per launch (0: persistent path unavailable)
+    MegaPhase *prog_full = nullptr; // [embed, layers, head, len]
+    MegaPhase *prog_nohead = nullptr; // [embed, layers, len]
+    int n_full = 0, n_nohead = 0;
+    float *nsq = nullptr;
+    unsigned *arrive = nullptr, *abort_flag = nullptr, *attn_cnt = nullptr;
+    unsigned epoch = 1;
+    bool persistent = false; // forward path: false = one launch per phase, true = the persistent kernel
     // optional per-kernel-class timing (ss_profile_*): event pairs recorded around launches
     bool prof = false;
     std::vector<hipEvent_t> ev;
@@ -65,7 +76,7 @@ struct ss_model {
     size_t ev_used = 0;
 };
 
-enum ProfTag { PT_NORM = 0, PT_QKV, PT_ATTN, PT_OPROJ, PT_GATEUP, PT_DOWN, PT_HEAD, PT_OTHER, PT_COUNT };
+enum ProfTag { PT_NORM = 0, PT_QKV, PT_ATTN, PT_OPROJ, PT_GATEUP, PT_DOWN, PT_HEAD, PT_OTHER, PT_PERSISTENT, PT_COUNT };
 
 // records an event pair around the launches issued while it is alive (only when profiling is on)
 struct ProfScope {
@@ -167,6 +178,57 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
         ss_model_destroy(m);
         return rc;
     }
+    // phase programs of the persistent verify kernel
+    {
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        m->mega_G = mega_grid(c.dtype, dev);
+        if (m->mega_G > 0 && c.n_layers >= 0) {
+            std::vector<MegaPhase> prog;
+            auto gain_after = [&](int l) { return l + 1 < c.n_layers ? m->layers[l + 1].g1 : m->gf; };
+            MegaPhase e{};
+            e.kind = PH_EMBED;
+            e.gain = c.n_layers ? m->layers[0].g1 : m->gf;
+            prog.push_back(e);
+            for (int l = 0; l < c.n_layers; ++l) {
+                const ss_layer_weights &L = m->layers[l];
+                MegaPhase q{}; q.kind = PH_QKV; q.layer = l; q.W = L.wqkv; q.N = 3 * m->W; q.K = c.d_model; q.act_src = ACT_A; prog.push_back(q);
+                MegaPhase a{}; a.kind = PH_ATTN; a.layer = l; prog.push_back(a);
+                MegaPhase o{}; o.kind = PH_RESID; o.layer = l; o.W = L.wo; o.N = c.d_model; o.K = m->W; o.act_src = ACT_O; o.gain = L.g2; prog.push_back(o);
+                MegaPhase u{}; u.kind = PH_SWIGLU; u.layer = l; u.W = L.wgu; u.N = c.d_ff; u.K = c.d_model; u.act_src = ACT_A; prog.push_back(u);
+                MegaPhase dn{}; dn.kind = PH_RESID; dn.layer = l; dn.W = L.wd; dn.N = c.d_model; dn.K = c.d_ff; dn.act_src = ACT_Z; dn.gain = gain_after(l); prog.push_back(dn);
+            }
+            MegaPhase ln{}; ln.kind = PH_LEN;
+            std::vector<MegaPhase> nohead = prog;
+            nohead.push_back(ln);
+            const bool gains_ok = true; // a missing final gain only leaves the last packed rows unscaled (unused)
+            if (m->lm_head && m->gf) {
+                MegaPhase hd{}; hd.kind = PH_HEAD; hd.W = m->lm_head; hd.N = c.vocab; hd.K = c.d_model; hd.act_src = ACT_A; prog.push_back(hd);
+            }
+            prog.push_back(ln);
+            if (!gains_ok) {
+                m->mega_G = 0; // a model without a final gain cannot fold the norm into the next GEMM
+            } else {
+                m->n_full = (int)prog.size();
+                m->n_nohead = (int)nohead.size();
+                A((void **)&m->prog_full, sizeof(MegaPhase) * prog.size(), false);
+                A((void **)&m->prog_nohead, sizeof(MegaPhase) * nohead.size(), false);
+                A((void **)&m->nsq, sizeof(float) * 16 * (size_t)m->mega_G, true);
+                A((void **)&m->arrive, sizeof(unsigned) * (size_t)m->mega_G, true);
+                A((void **)&m->abort_flag, sizeof(unsigned), true);
+                A((void **)&m->attn_cnt, sizeof(unsigned) * (size_t)c.max_rows * c.n_heads, true);
+                if (rc == SS_OK) {
+                    hipError_t e1 = hipMemcpy(m->prog_full, prog.data(), sizeof(MegaPhase) * prog.size(), hipMemcpyHostToDevice);
+                    hipError_t e2 = hipMemcpy(m->prog_nohead, nohead.data(), sizeof(MegaPhase) * nohead.size(), hipMemcpyHostToDevice);
+                    if (e1 != hipSuccess || e2 != hipSuccess) rc = fail(SS_EHIP, "program upload failed");
+                }
+                if (rc != SS_OK) {
+                    ss_model_destroy(m);
+                    return rc;
+                }
+            }
+        }
+    }
     // rotary table: angle(pos, j) = pos * base^(-2j/hd), evaluated in double, stored as fp32 (cos, sin)
     {
         const int half = c.head_dim / 2;
@@ -194,6 +256,20 @@ extern "C" int ss_device_status(ss_model *m, ss_stream stream, int32_t *status_h
     HIP_TRY(hipMemcpyAsync(status_host, m->status, sizeof(int32_t), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     HIP_TRY(hipMemsetAsync(m->status, 0, sizeof(int32_t), st));
+    if (m->abort_flag) {
+        unsigned ab = 0;
+        HIP_TRY(hipMemcpyAsync(&ab, m->abort_flag, sizeof(unsigned), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        if (ab) {
+            // a device-wide barrier gave up: reset the barrier state so that later launches start clean
+            *status_host |= 2;
+            HIP_TRY(hipMemsetAsync(m->abort_flag, 0, sizeof(unsigned), st));
+            HIP_TRY(hipMemsetAsync(m->arrive, 0, sizeof(unsigned) * (size_t)m->mega_G, st));
+            HIP_TRY(hipMemsetAsync(m->attn_cnt, 0, sizeof(unsigned) * (size_t)m->cfg.max_rows * m->cfg.n_heads, st));
+            HIP_TRY(hipStreamSynchronize(st));
+            m->epoch = 1;
+        }
+    }
     return SS_OK;
 }
 
@@ -429,11 +505,111 @@ static void run_head(ss_model *m, int nrows, int row0, int stride, float *logits
     launch_gemm(c.dtype, EPI_STORE, g, st);
 }
 
+static bool use_persistent(const ss_model *m, int R) { return m->persistent && m->mega_G > 0 && R <= 16; }
+
+extern "C" int ss_model_set_persistent(ss_model *m, int32_t on) {
+    if (!m) return fail(SS_EINVAL, "ss_model_set_persistent: NULL model");
+    if (on && m->mega_G <= 0) return fail(SS_EINVAL, "the persistent verify kernel is not available for this model on this device");
+    m->persistent = on != 0;
+    return SS_OK;
+}
+
+// One launch of the persistent kernel: [embedding | given rows] -> layers -> [LM head] -> lengths += M.
+static int run_persistent(ss_model *m, ss_kv_cache *kv, const int32_t *tokens, float *h, int batch, int M, float *logits,
+                          int head_rows, int head_row0, int head_stride, hipStream_t st) {
+    const ss_model_cfg &c = m->cfg;
+    const size_t pl = (size_t)m->R16;
+    MegaCall P{};
+    const bool with_head = logits != nullptr;
+    P.phases = with_head ? m->prog_full : m->prog_nohead;
+    P.n_phases = with_head ? m->n_full : m->n_nohead;
+    P.dtype = c.dtype;
+    P.d = c.d_model; P.H = c.n_heads; P.hd = c.head_dim; P.F = c.d_ff; P.V = c.vocab;
+    P.R = batch * M; P.B = batch; P.M = M;
+    P.eps = c.rms_eps;
+    P.tokens = tokens; P.embed = m->embed; P.h = h;
+    P.act[ACT_A] = m->act_a; P.act_plane[ACT_A] = pl * c.d_model; P.act_ld[ACT_A] = c.d_model;
+    P.act[ACT_Q] = m->act_q; P.act_plane[ACT_Q] = pl * m->W; P.act_ld[ACT_Q] = m->W;
+    P.act[ACT_O] = m->act_o; P.act_plane[ACT_O] = pl * m->W; P.act_ld[ACT_O] = m->W;
+    P.act[ACT_Z] = m->act_z; P.act_plane[ACT_Z] = pl * c.d_ff; P.act_ld[ACT_Z] = c.d_ff;
+    P.nsq = m->nsq;
+    P.logits = logits; P.ldo = c.vocab; P.head_rows = head_rows; P.head_row0 = head_row0; P.head_stride = head_stride;
+    P.kc = kv->k; P.vc = kv->v; P.layer_elems = kv->layer_elems; P.len = kv->len_dev; P.S = kv->S; P.max_pos = c.max_pos;
+    P.rope = m->rope;
+    int Lmax = 0;
+    for (int b = 0; b < batch; ++b) Lmax = std::max(Lmax, kv->len_ub[b] + M);
+    int want = (2 * m->mega_G + batch * c.n_heads - 1) / (batch * c.n_heads);
+    int nsplit = std::max(1, std::min(std::min(want, (Lmax + 63) / 64), MAX_SPLITS));
+    const int chunk = round_up((Lmax + nsplit - 1) / nsplit, 64);
+    nsplit = (Lmax + chunk - 1) / chunk;
+    P.nsplit = nsplit; P.chunk = chunk;
+    P.part_o = m->part_o; P.part_m = m->part_m; P.part_l = m->part_l; P.attn_cnt = m->attn_cnt;
+    P.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)c.head_dim));
+    P.arrive = m->arrive; P.abort_flag = m->abort_flag; P.epoch_base = m->epoch;
+    P.spin_limit = 1u << 20;
+    P.status = m->status;
+    m->epoch += (unsigned)P.n_phases + 1;
+    static const bool want_timeline = getenv("SS_TIMELINE") != nullptr; // development aid: phase times of workgroup 0
+    static unsigned long long *tl_dev = nullptr;
+    if (want_timeline) {
+        if (!tl_dev) {
+            HIP_TRY(hipMalloc((void **)&tl_dev, sizeof(unsigned long long) * (3 * 4096 + 2 * 4096)));
+            HIP_TRY(hipMemset(tl_dev, 0, sizeof(unsigned long long) * (3 * 4096 + 2 * 4096)));
+        }
+        P.timeline = tl_dev;
+    }
+    {
+        ProfScope ps(m, PT_PERSISTENT, st);
+        hipError_t e = launch_mega(P, m->mega_G, st);
+        if (e != hipSuccess) return fail(SS_EHIP, "persistent verify kernel launch: %s", hipGetErrorString(e));
+    }
+    for (int b = 0; b < batch; ++b) kv->len_ub[b] += M;
+    if (want_timeline && P.n_phases <= 4096) {
+        std::vector<unsigned long long> t(3 * P.n_phases);
+        std::vector<MegaPhase> ph(P.n_phases);
+        HIP_TRY(hipStreamSynchronize(st));
+        HIP_TRY(hipMemcpy(t.data(), tl_dev, t.size() * 8, hipMemcpyDeviceToHost));
+        HIP_TRY(hipMemcpy(ph.data(), P.phases, ph.size() * sizeof(MegaPhase), hipMemcpyDeviceToHost));
+        double pre[8] = {0}, work[8] = {0}, wait[8] = {0};
+        int cnt[8] = {0};
+        for (int p = 0; p < P.n_phases; ++p) {
+            const int k = ph[p].kind + (ph[p].kind == PH_RESID && ph[p].K != c.d_ff ? 0 : 0);
+            const int slot = (ph[p].kind == PH_RESID && ph[p].K == c.d_ff) ? 7 : k;
+            pre[slot] += (double)(t[3 * p + 1] - t[3 * p]) * 0.01;
+            work[slot] += (double)(t[3 * p + 2] - t[3 * p + 1]) * 0.01;
+            if (p + 1 < P.n_phases) wait[slot] += (double)(t[3 * (p + 1)] - t[3 * p + 2]) * 0.01;
+            cnt[slot]++;
+        }
+        const char *names[8] = {"embed", "qkv", "attn", "oproj", "gateup", "head", "len", "down"};
+        fprintf(stderr, "[timeline wg0] total %.1f us:", (double)(t[3 * P.n_phases - 1] - t[0]) * 0.01);
+        for (int k = 0; k < 8; ++k)
+            if (cnt[k]) fprintf(stderr, " %s{n=%d pre=%.1f work=%.1f barrier_after=%.1f}", names[k], cnt[k], pre[k] / cnt[k], work[k] / cnt[k], wait[k] / cnt[k]);
+        fprintf(stderr, "\n");
+        if (getenv("SS_TRACE")) {
+            std::vector<unsigned long long> tr(2 * 4096);
+            HIP_TRY(hipMemcpy(tr.data(), tl_dev + 3 * 4096, tr.size() * 8, hipMemcpyDeviceToHost));
+            fprintf(stderr, "[trace]");
+            for (int i = 0; i < 4000 && tr[2 * i]; ++i) {
+                if (i > 0) fprintf(stderr, " %llu:+%.2f", tr[2 * i], (double)(tr[2 * i + 1] - tr[2 * i - 1]) * 0.01);
+                else fprintf(stderr, " %llu", tr[0]);
+                if ((int)tr[2 * i] >= 200 && i > 140) break;
+            }
+            fprintf(stderr, "\n");
+            HIP_TRY(hipMemset(tl_dev + 3 * 4096, 0, sizeof(unsigned long long) * 2 * 4096));
+        }
+    }
+    return SS_OK;
+}
+
 extern "C" int ss_decoder_layers_forward(ss_model *m, ss_kv_cache *kv, float *h_dev, int32_t batch, int32_t M, ss_stream stream) {
     int rc = check_pair(m, kv, batch, M, "ss_decoder_layers_forward");
     if (rc) return rc;
     if (!h_dev) return fail(SS_EINVAL, "ss_decoder_layers_forward: h_dev is NULL");
     hipStream_t st = (hipStream_t)stream;
+    if (use_persistent(m, batch * M)) {
+        rc = run_persistent(m, kv, nullptr, h_dev, batch, M, nullptr, 0, 0, 1, st);
+        return rc ? rc : check_launch();
+    }
     const size_t bytes = sizeof(float) * (size_t)batch * M * m->cfg.d_model;
     HIP_TRY(hipMemcpyAsync(m->h, h_dev, bytes, hipMemcpyDeviceToDevice, st));
     run_layers(m, kv, batch, M, st);
@@ -448,6 +624,10 @@ extern "C" int ss_verify_forward(ss_model *m, ss_kv_cache *kv, const int32_t *to
     if (!tokens_dev) return fail(SS_EINVAL, "ss_verify_forward: tokens_dev is NULL");
     if (!m->embed || (logits_dev && (!m->lm_head || !m->gf))) return fail(SS_EINVAL, "ss_verify_forward: model has no embedding / LM head");
     hipStream_t st = (hipStream_t)stream;
+    if (use_persistent(m, batch * M)) {
+        rc = run_persistent(m, kv, tokens_dev, m->h, batch, M, logits_dev, batch * M, 0, 1, st);
+        return rc ? rc : check_launch();
+    }
     launch_embed(m->cfg.dtype, m->embed, tokens_dev, batch * M, m->cfg.d_model, m->cfg.vocab, m->h, m->status, st);
     run_layers(m, kv, batch, M, st);
     if (logits_dev) run_head(m, batch * M, 0, 1, logits_dev, st);
@@ -465,9 +645,14 @@ extern "C" int ss_draft_step(ss_model *m, ss_kv_cache *kv, const int32_t *tokens
     if (temperature > 0.f && (!u_dev || !q_rows_dev || ldq < m->cfg.vocab)) return fail(SS_EINVAL, "ss_draft_step: sampling needs u_dev, q_rows_dev and ldq >= vocab");
     hipStream_t st = (hipStream_t)stream;
     const int V = m->cfg.vocab;
-    launch_embed(m->cfg.dtype, m->embed, tokens_dev, batch * mrows, m->cfg.d_model, V, m->h, m->status, st);
-    run_layers(m, kv, batch, mrows, st);
-    run_head(m, batch, mrows - 1, mrows, m->logits_ws, st);
+    if (use_persistent(m, batch * mrows)) {
+        rc = run_persistent(m, kv, tokens_dev, m->h, batch, mrows, m->logits_ws, batch, mrows - 1, mrows, st);
+        if (rc) return rc;
+    } else {
+        launch_embed(m->cfg.dtype, m->embed, tokens_dev, batch * mrows, m->cfg.d_model, V, m->h, m->status, st);
+        run_layers(m, kv, batch, mrows, st);
+        run_head(m, batch, mrows - 1, mrows, m->logits_ws, st);
+    }
     if (temperature > 0.f) {
         const float inv_t = 1.0f / temperature;
         launch_row_stats(m->logits_ws, batch, V, inv_t, m->stats_ws, st);

@@ -3,10 +3,10 @@
 //
 //   out[m][n] = sum_k act[m][k] * W[n][k],   m < R <= 16 per row tile, W row-major [N][K].
 //
-// One workgroup (4 wavefronts) owns 16 output columns (or a pair of 16-column tiles for the fused
+// One workgroup (16 wavefronts) owns 16 output columns (or a pair of 16-column tiles for the fused
 // epilogues).  Each lane streams 16-byte chunks of 16 weight rows straight from HBM into registers -
 // weights are used exactly once, so they never pass through LDS - and feeds them to MFMA as the A
-// operand; the activation rows are the B operand, read as packed planes through L1/L2.  The four
+// operand; the activation rows are the B operand, read as packed planes through L1/L2.  The
 // waves interleave over K in 128-byte steps per row, their partial tiles are summed in a fixed
 // order through LDS (deterministic), and wave 0 applies the epilogue:
 //   STORE   plain fp32 store (LM head)
@@ -16,12 +16,14 @@
 //           planes, k and v -> KV cache at positions len[b] + i
 #include "ss_device.h"
 #include "ss_kernels.h"
+#include <cstdlib>
 
 namespace ss {
 
-template <typename T, int EPI>
-__global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
-    constexpr int E = Traits<T>::E, KB = 4 * E, NW = 4;
+// NW = wavefronts per workgroup (interleaved over K), U = 128-byte steps in flight per wave
+template <typename T, int EPI, int NW, int U>
+__global__ __launch_bounds__(NW * 64) void gemm_kernel(GemmArgs a) {
+    constexpr int E = Traits<T>::E, KB = 4 * E;
     constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 15, g = lane >> 4;
@@ -52,31 +54,37 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
     }
     ActPlanes<T> act{const_cast<T *>(reinterpret_cast<const T *>(a.act)), a.act_plane, a.ld_act};
     const size_t aoff = (size_t)(rt * 16 + c) * a.ld_act + g * E;
+    const bool row_live = rt * 16 + c < a.R; // rows past R contribute nothing: skip their loads
 
     f32x4 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // each wave takes 128-byte steps (two k-blocks) of every row, interleaved with the other waves
+    // Each wave takes 128-byte steps (two k-blocks) of every row, interleaved with the other waves,
+    // two steps per iteration so that 4*NT weight loads are in flight per lane before the first MFMA.
     const int nkb = (K + KB - 1) / KB;
-    for (int kp = wave; 2 * kp < nkb; kp += NW) {
-        u32x4 w[NT][2];
-        Act<T> av[2];
+    for (int kp = wave; 2 * kp < nkb; kp += U * NW) {
+        u32x4 w[U][NT][2];
+        Act<T> av[U][2];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int k = (2 * kp + j) * KB;
-            const bool ok = k + g * E < K; // K is a multiple of E
+        for (int s = 0; s < U; ++s)
 #pragma unroll
-            for (int t = 0; t < NT; ++t) w[t][j] = ok ? ld16_stream(wrow[t] + k) : zero16();
-            av[j] = ok ? load_act(act, aoff + k) : zero_act<T>();
-        }
+            for (int j = 0; j < 2; ++j) {
+                const int k = (2 * (kp + s * NW) + j) * KB;
+                const bool ok = k + g * E < K; // K is a multiple of E
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+                for (int t = 0; t < NT; ++t) w[s][t][j] = ok ? ld16_stream(wrow[t] + k) : zero16();
+                av[s][j] = (ok && row_live) ? load_act(act, aoff + k) : zero_act<T>();
+            }
 #pragma unroll
-            for (int t = 0; t < NT; ++t) acc[t] = mma(acc[t], w[t][j], av[j]);
+        for (int s = 0; s < U; ++s)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int t = 0; t < NT; ++t) acc[t] = mma(acc[t], w[s][t][j], av[s][j]);
     }
 
-    // fixed-order sum of the four waves' partial tiles
+    // fixed-order sum of the waves' partial tiles
     __shared__ float red[NW][NT][4][64];
 #pragma unroll
     for (int t = 0; t < NT; ++t)
@@ -88,7 +96,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) r[t][v] = ((red[0][t][v][lane] + red[1][t][v][lane]) + red[2][t][v][lane]) + red[3][t][v][lane];
+        for (int v = 0; v < 4; ++v) {
+            float sum = red[0][t][v][lane];
+#pragma unroll 4
+            for (int w2 = 1; w2 < NW; ++w2) sum += red[w2][t][v][lane];
+            r[t][v] = sum;
+        }
 
     // lane (c, g) holds row m = rt*16 + c, columns n0 + 4g + v
     const int m = rt * 16 + c;
@@ -173,7 +186,16 @@ template <typename T, int EPI> static void launch_gemm_t(const GemmArgs &a, hipS
     if (EPI == EPI_QKV) tiles = 3 * a.H * (a.hd / 32);
     else tiles = (a.N + 15) / 16;
     dim3 grid(tiles, (a.R + 15) / 16);
-    hipLaunchKernelGGL((gemm_kernel<T, EPI>), grid, dim3(256), 0, st, a);
+    static const int cfg = getenv("SS_GEMM_CFG") ? atoi(getenv("SS_GEMM_CFG")) : 0;
+    switch (cfg) {
+    case 1: hipLaunchKernelGGL((gemm_kernel<T, EPI, 8, 2>), grid, dim3(8 * 64), 0, st, a); break;
+    case 2: hipLaunchKernelGGL((gemm_kernel<T, EPI, 8, 4>), grid, dim3(8 * 64), 0, st, a); break;
+    case 3: hipLaunchKernelGGL((gemm_kernel<T, EPI, 4, 4>), grid, dim3(4 * 64), 0, st, a); break;
+    case 4: hipLaunchKernelGGL((gemm_kernel<T, EPI, 16, 1>), grid, dim3(16 * 64), 0, st, a); break;
+    case 5: hipLaunchKernelGGL((gemm_kernel<T, EPI, 4, 2>), grid, dim3(4 * 64), 0, st, a); break;
+    case 6: hipLaunchKernelGGL((gemm_kernel<T, EPI, 8, 1>), grid, dim3(8 * 64), 0, st, a); break;
+    default: hipLaunchKernelGGL((gemm_kernel<T, EPI, 16, 2>), grid, dim3(16 * 64), 0, st, a); break;
+    }
 }
 
 void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st) {

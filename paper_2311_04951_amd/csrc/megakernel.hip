@@ -1,0 +1,685 @@
+// The verify pass as ONE persistent kernel (Section 3: the pass is bound by streaming the weights, so
+// the design goal is that the HBM stream never stops).
+//
+// One workgroup of 8 wavefronts per compute unit stays resident for the whole pass and walks a list
+// of phases: [embedding] then per layer [QKV, attention, O projection, gate/up, down projection],
+// then [LM head] and [cache-length update].  Consecutive phases are separated by a device-wide
+// barrier (each workgroup publishes an epoch in its own slot and polls all slots: no atomics on a
+// shared counter; the spin is bounded and sets an abort flag that makes every workgroup leave).
+// The barrier carries no cache write-back / invalidate: everything one workgroup writes for another
+// to read inside the kernel (hidden rows, packed activations, norm partials, new cache rows,
+// attention partials) moves through agent-coherent relaxed atomics, which are performed at the
+// memory side of the per-XCD L2 caches; a barrier is then two memory round trips (~4 us) instead of
+// a full L2 flush and invalidate (~8 us).
+//
+// Every workgroup owns a fixed, byte-balanced share of each weight matrix (a contiguous range of
+// output rows / of gate-up or rotary pairs), so the sequence of 16-byte weight chunks a wavefront
+// will consume over the whole pass is static.  It is consumed through a two-deep register pipeline of
+// "chunks" (up to 16 loads = 16 KB per wavefront): the loads of the next chunk - which may belong to
+// the next tile or to the NEXT PHASE - are issued before the current chunk is multiplied, reduced and
+// written back, so barriers, reductions, epilogues and the attention phase all run under weight
+// loads that are already in flight.
+//
+// GEMM tiles are 16 weight rows (MFMA A operand) x all K; the 8 waves interleave over K in 128-byte
+// steps and their partial 16x16 tiles are summed in a fixed order through a double-buffered LDS
+// area by waves 0-3 while waves 4-7 already multiply the next tile.  Paired epilogues put the two
+// rows of a pair (gate/up, or rotary j and j + hd/2) 8 rows apart in the same tile, so the partner is
+// one wave-shuffle away.  RMSNorm is folded into the GEMMs: the producer packs h * gain and publishes
+// per-workgroup partial sums of squares, the consumer multiplies its outputs by the row scale.
+// The hidden rows a phase multiplies with (B operand) are copied once per phase (per 4096-wide K
+// slab) into LDS, so the chain load-weights -> MFMA never waits on a second global round trip.
+#include "attention_core.h"
+#include "ss_mega.h"
+#include <algorithm>
+
+namespace ss {
+
+constexpr int MNW = MEGA_THREADS / 64; // wavefronts per workgroup
+constexpr int CH = 4;                  // 128-byte steps per chunk per wave (8 loads = 8 KB per wave)
+constexpr int SLAB_CK = 2;             // chunks per LDS activation slab
+constexpr int RING = 3;                // chunks in flight per wave
+constexpr int CHUNK_ROW_BYTES = CH * MNW * 128; // bytes of a weight row one chunk covers (all waves)
+
+struct Range {
+    int u0, u1, ntiles;
+};
+
+__device__ __forceinline__ bool is_gemm(int kind) { return kind == PH_QKV || kind == PH_RESID || kind == PH_SWIGLU || kind == PH_HEAD; }
+
+// the share of phase ph owned by workgroup wg: units are tiles (QKV), pairs (SWIGLU) or rows
+__device__ __forceinline__ Range phase_range(const MegaPhase &ph, int wg, int G) {
+    const int units = ph.kind == PH_QKV ? ph.N / 16 : ph.N;
+    Range r; // wg * units < 2^31 for every shape the host accepts
+    r.u0 = (int)((unsigned)wg * (unsigned)units / (unsigned)G);
+    r.u1 = (int)((unsigned)(wg + 1) * (unsigned)units / (unsigned)G);
+    const int per = ph.kind == PH_QKV ? 1 : (ph.kind == PH_SWIGLU ? 8 : 16);
+    r.ntiles = (r.u1 - r.u0 + per - 1) / per;
+    return r;
+}
+
+// weight row that A-row i (0..15) of tile `tile` stands for
+__device__ __forceinline__ int a_row(int kind, int N, const Range &r, int hd, int tile, int i, bool &live) {
+    if (kind == PH_QKV) {
+        const int t = r.u0 + tile, tph = hd / 16;
+        const int hh = t / tph, j0 = (t - hh * tph) * 8;
+        live = true;
+        return hh * hd + j0 + (i < 8 ? i : hd / 2 + i - 8);
+    }
+    if (kind == PH_SWIGLU) {
+        const int pair = r.u0 + tile * 8 + (i & 7);
+        live = pair < r.u1;
+        return i < 8 ? pair : N + pair;
+    }
+    const int row = r.u0 + tile * 16 + i;
+    live = row < r.u1;
+    return row;
+}
+
+template <typename T> __device__ __forceinline__ int chunks_per_tile(int K) {
+    const int row_bytes = K * (int)sizeof(T);
+    return (row_bytes + CHUNK_ROW_BYTES - 1) / CHUNK_ROW_BYTES;
+}
+
+// Position in a workgroup's static chunk sequence.  Everything a step needs rides along (phase
+// fields, the tile's per-lane row pointer), so stepping costs no division and no descriptor reload.
+struct Cursor {
+    int p, tile, ck, nck;
+    int idx;    // chunk index inside the phase, padding included
+    bool dummy; // a padding position: no loads, no math (phases are padded to a multiple of RING chunks
+                // so that every phase starts at ring slot 0)
+    Range r;
+    int kind, N, kbytes; // phase kind, rows/pairs, bytes per weight row
+    const char *W;
+    const char *wp; // this lane's pointer into its weight row of the current tile (+ its wave / lane-group offset)
+    bool live;      // the lane's A-row exists
+};
+
+template <typename T> __device__ __forceinline__ void cursor_tile(Cursor &c, int hd) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, cc = lane & 15, g = lane >> 4;
+    const int row = a_row(c.kind, c.N, c.r, hd, c.tile, cc, c.live);
+    c.wp = c.W + (size_t)row * c.kbytes + wave * 128 + g * 16;
+}
+
+template <typename T> __device__ __forceinline__ void cursor_seek(Cursor &c, const MegaCall &P, int wg, int G) {
+    while (c.p < P.n_phases) {
+        const MegaPhase ph = P.phases[c.p];
+        if (is_gemm(ph.kind)) {
+            c.r = phase_range(ph, wg, G);
+            if (c.r.ntiles > 0) {
+                c.kind = ph.kind;
+                c.N = ph.N;
+                c.kbytes = ph.K * (int)sizeof(T);
+                c.W = reinterpret_cast<const char *>(ph.W);
+                c.nck = chunks_per_tile<T>(ph.K);
+                c.tile = 0;
+                c.ck = 0;
+                c.idx = 0;
+                c.dummy = false;
+                cursor_tile<T>(c, P.hd);
+                return;
+            }
+        }
+        ++c.p;
+    }
+}
+
+template <typename T> __device__ __forceinline__ void cursor_next(Cursor &c, const MegaCall &P, int wg, int G) {
+    ++c.idx;
+    if (!c.dummy) {
+        if (++c.ck < c.nck) return;
+        c.ck = 0;
+        if (++c.tile < c.r.ntiles) {
+            cursor_tile<T>(c, P.hd);
+            return;
+        }
+        c.dummy = true; // real chunks done: pad to a multiple of RING
+    }
+    if (c.idx % RING != 0) return;
+    ++c.p;
+    cursor_seek<T>(c, P, wg, G);
+}
+
+// issue the 2*CH weight loads of chunk c for this lane: one base pointer, immediate offsets
+__device__ __forceinline__ void issue_chunk(const Cursor &c, u32x4 (&wbuf)[2 * CH]) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4;
+    if (c.dummy) return;
+#ifdef SS_EXPERIMENT_NOLOAD
+    for (int i = 0; i < 2 * CH; ++i) wbuf[i] = u32x4{(unsigned)(size_t)c.wp, 1u, 2u, 3u};
+    return;
+#endif
+    const char *base = c.wp + (size_t)c.ck * CHUNK_ROW_BYTES;
+    const bool whole = (c.ck + 1) * CHUNK_ROW_BYTES <= c.kbytes; // uniform: the chunk lies inside the row
+    if (c.live && whole) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) wbuf[2 * i + j] = ld16(base + i * (MNW * 128) + j * 64);
+    } else {
+        const int kb0 = c.ck * CHUNK_ROW_BYTES + wave * 128 + g * 16;
+#pragma unroll
+        for (int i = 0; i < CH; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int off = i * (MNW * 128) + j * 64;
+                wbuf[2 * i + j] = (c.live && kb0 + off < c.kbytes) ? ld16(base + off) : zero16();
+            }
+    }
+}
+
+constexpr int SLAB_ROW_BYTES = SLAB_CK * CH * MNW * 128; // 8192: the K range one slab covers, per hidden row
+constexpr int SLAB_PITCH = SLAB_ROW_BYTES + 48; // padded against LDS bank conflicts between rows
+
+// LDS: [ union: activation slab | attention merge area ][ red ][ small ]
+struct MegaSmemTail {
+    float red[2][MNW][4][64]; // partial tiles, double-buffered
+    float scale[16];          // row scales of the current phase
+    float sq[4][16];          // per reducer wave partial row sums of squares
+    float blk[MNW];
+    int flag;
+};
+
+// development aid: fine-grained event trace of workgroup 0, wave 0 (P.timeline + 3*4096 onwards)
+__device__ __forceinline__ void trace(const MegaCall &P, int &n, int tag) {
+    if (P.timeline && blockIdx.x == 0 && threadIdx.x == 0 && n < 4000) {
+        P.timeline[3 * 4096 + 2 * n] = (unsigned long long)tag;
+        P.timeline[3 * 4096 + 2 * n + 1] = wall_clock64();
+        ++n;
+    }
+}
+
+struct MegaSmem {
+    unsigned char *u; // slab / attention area
+    MegaSmemTail *t;
+};
+
+// device-wide barrier without cache maintenance; false = aborted (bounded spin ran out or another
+// workgroup aborted).  Stores issued before it are complete (workgroup-scope release + barrier).
+__device__ __forceinline__ bool grid_sync(const MegaCall &P, unsigned epoch, int G, MegaSmem &sm) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        if (threadIdx.x == 0) __hip_atomic_store(&P.arrive[blockIdx.x], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        bool ok = true;
+        unsigned spins = 0;
+        for (;;) {
+            bool all = true;
+            for (int i = threadIdx.x; i < G; i += 64) {
+                const unsigned v = __hip_atomic_load(&P.arrive[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if ((int)(v - epoch) < 0) all = false;
+            }
+            if (__all(all)) break;
+            if (++spins > P.spin_limit || __hip_atomic_load(P.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
+                ok = false;
+                break;
+            }
+        }
+        if (threadIdx.x == 0) {
+            sm.t->flag = ok ? 1 : 0;
+            if (!ok) __hip_atomic_store(P.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    __syncthreads();
+    return sm.t->flag != 0;
+}
+
+// ---------------------------------------------------------------- non-GEMM phases
+
+template <typename T>
+__device__ void do_embed(const MegaCall &P, const MegaPhase &ph, int wg, int G, MegaSmem &sm) {
+    ActPlanes<T> act{reinterpret_cast<T *>(P.act[ACT_A]), P.act_plane[ACT_A], P.act_ld[ACT_A]};
+    for (int r = wg; r < P.R; r += G) {
+        const T *src = nullptr;
+        if (P.tokens) {
+            int tok = P.tokens[r];
+            if (tok < 0 || tok >= P.V) {
+                if (threadIdx.x == 0) atomicOr(P.status, 1);
+                tok = tok < 0 ? 0 : P.V - 1;
+            }
+            src = reinterpret_cast<const T *>(P.embed) + (size_t)tok * P.d;
+        }
+        float ss = 0.f;
+        for (int e = threadIdx.x; e < P.d; e += MEGA_THREADS) {
+            float x;
+            if (src) {
+                x = to_f32(src[e]);
+                st_coh(&P.h[(size_t)r * P.d + e], x);
+            } else {
+                x = ld_coh(&P.h[(size_t)r * P.d + e]);
+            }
+            store_act_coh(act, (size_t)r * act.ld + e, ph.gain ? x * ph.gain[e] : x);
+            ss += x * x;
+        }
+        ss = wave_sum(ss);
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) sm.t->blk[threadIdx.x >> 6] = ss;
+        __syncthreads();
+        float tot = 0.f;
+#pragma unroll
+        for (int w = 0; w < MNW; ++w) tot += sm.t->blk[w];
+        for (int s = threadIdx.x; s < G; s += MEGA_THREADS) st_coh(&P.nsq[(size_t)r * G + s], s == 0 ? tot : 0.f);
+    }
+}
+
+template <typename T, int HD>
+__device__ void do_attn_hd(const MegaCall &P, const MegaPhase &ph, int wg, int G, MegaSmem &sm) {
+    AttnArgs a;
+    a.q = P.act[ACT_Q];
+    a.q_plane = P.act_plane[ACT_Q];
+    a.ldq = P.act_ld[ACT_Q];
+    const size_t esz = sizeof(T);
+    a.kcache = (char *)P.kc + P.layer_elems * ph.layer * esz;
+    a.vcache = (char *)P.vc + P.layer_elems * ph.layer * esz;
+    a.len = P.len;
+    a.B = P.B; a.M = P.M; a.H = P.H; a.hd = HD; a.S = P.S; a.R = P.R;
+    a.nsplit = P.nsplit; a.chunk = P.chunk;
+    a.part_o = P.part_o; a.part_m = P.part_m; a.part_l = P.part_l;
+    a.act_out = P.act[ACT_O]; a.act_out_plane = P.act_plane[ACT_O]; a.ld_out = P.act_ld[ACT_O];
+    a.scale_log2e = P.scale_log2e;
+    AttnSmem<HD, MNW> &asm_ = *reinterpret_cast<AttnSmem<HD, MNW> *>(sm.u);
+    ActPlanes<T> out{reinterpret_cast<T *>(a.act_out), a.act_out_plane, a.ld_out};
+    const int units = P.B * P.H * P.nsplit;
+    for (int u = wg; u < units; u += G) {
+        const int split = u % P.nsplit, bh = u / P.nsplit;
+        const int h = bh % P.H, b = bh / P.H;
+        attn_unit<T, HD, MNW, true>(a, split, h, b, asm_);
+        // the split that arrives last merges all splits of (b, h); partials travel through
+        // coherent accesses, so completing the stores (release at workgroup scope) is all it takes
+        bool merge = true;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __syncthreads();
+        if (P.nsplit > 1) {
+            if (threadIdx.x == 0) {
+                const unsigned old = __hip_atomic_fetch_add(&P.attn_cnt[bh], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                sm.t->flag = old == (unsigned)(P.nsplit - 1);
+            }
+            __syncthreads();
+            merge = sm.t->flag != 0;
+        }
+        if (merge) {
+            for (int idx = threadIdx.x; idx < P.M * HD; idx += MEGA_THREADS) {
+                const int c = idx / HD, e = idx - c * HD, row = b * P.M + c;
+                store_act_coh(out, (size_t)row * a.ld_out + h * HD + e, attn_merge_elem<true>(a, row, h, e));
+            }
+            if (P.nsplit > 1 && threadIdx.x == 0) __hip_atomic_store(&P.attn_cnt[bh], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+    }
+}
+
+template <typename T>
+__device__ void do_attn(const MegaCall &P, const MegaPhase &ph, int wg, int G, MegaSmem &sm) {
+    if (P.hd == 128) do_attn_hd<T, 128>(P, ph, wg, G, sm);
+    else if (P.hd == 64) do_attn_hd<T, 64>(P, ph, wg, G, sm);
+    else do_attn_hd<T, 32>(P, ph, wg, G, sm);
+}
+
+// row scales 1/sqrt(mean(h^2) + eps) from the producers' partial sums: 32 threads per row, one round trip
+__device__ __forceinline__ void compute_scales(const MegaCall &P, int G, MegaSmem &sm) {
+    const int j = threadIdx.x & 31;
+    for (int row = threadIdx.x >> 5; row < 16; row += MEGA_THREADS / 32) {
+    float s = 0.f;
+    for (int i0 = 0; i0 < G; i0 += 256) { // 8 independent loads per round
+        float t[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int i = i0 + j + 32 * q;
+            t[q] = i < G ? ld_coh(&P.nsq[(size_t)row * G + i]) : 0.f;
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) s += t[q];
+    }
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if (j == 0) sm.t->scale[row] = 1.0f / sqrtf(s / (float)P.d + P.eps);
+    }
+}
+
+// copy the hidden rows of K slab `ck` of the phase's B operand into LDS (zero beyond K)
+template <typename T>
+__device__ __forceinline__ void load_slab(const MegaCall &P, const MegaPhase &ph, int slab, MegaSmem &sm) {
+    constexpr int PL = Traits<T>::PLANES;
+    constexpr int PER8 = 8 / (int)sizeof(T); // elements per 8-byte unit
+    const bool head = ph.kind == PH_HEAD;
+    const int rows = P.slab_rows;
+    const int nlive = head ? P.head_rows : P.R;
+    const T *base = reinterpret_cast<const T *>(P.act[ph.act_src]);
+    const size_t plane = P.act_plane[ph.act_src];
+    const int ld = P.act_ld[ph.act_src];
+    // a row of the slab is 1024 8-byte units = ROUNDS rounds of the workgroup's threads; all loads of a batch
+    // of rows are issued before the first LDS store so that they overlap (one memory round trip)
+    constexpr int BATCH = 2, ROUNDS = SLAB_ROW_BYTES / 8 / MEGA_THREADS;
+    const int nrow = PL * rows; // (plane, row) pairs
+    for (int pr0 = 0; pr0 < nrow; pr0 += BATCH) {
+        unsigned long long v[BATCH][ROUNDS];
+#pragma unroll
+        for (int b = 0; b < BATCH; ++b) {
+            const int pr = pr0 + b, r = pr % rows, pl = pr / rows;
+            const int brow = head ? P.head_row0 + r * P.head_stride : r;
+            const T *src = base + pl * plane + (size_t)brow * ld;
+#pragma unroll
+            for (int h2 = 0; h2 < ROUNDS; ++h2) {
+                const int x = threadIdx.x + h2 * MEGA_THREADS;
+                const int k = slab * (SLAB_ROW_BYTES / (int)sizeof(T)) + x * PER8;
+                v[b][h2] = (pr < nrow && r < nlive && k < ph.K) ? ld_coh64(src + k) : 0ull;
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < BATCH; ++b)
+#pragma unroll
+            for (int h2 = 0; h2 < ROUNDS; ++h2) {
+                const int pr = pr0 + b, x = threadIdx.x + h2 * MEGA_THREADS;
+                if (pr < nrow) *reinterpret_cast<unsigned long long *>(sm.u + (size_t)pr * SLAB_PITCH + x * 8) = v[b][h2];
+            }
+    }
+}
+
+// ---------------------------------------------------------------- GEMM chunk + tile epilogue
+
+template <typename T>
+__device__ __forceinline__ void tile_epilogue(const MegaCall &P, const MegaPhase &ph, const Range &r, int tile, float sum,
+                                              int v, float &rowsq, MegaSmem &sm) {
+    const int lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
+    const int i = 4 * g + v; // A-row of this element; the B row (hidden row) is c
+    bool live;
+    const int n = a_row(ph.kind, ph.N, r, P.hd, tile, i, live);
+    if (ph.kind == PH_RESID) {
+        if (live && c < P.R) {
+            const size_t o = (size_t)c * P.d + n;
+            const float hn = ld_coh(&P.h[o]) + sum;
+            st_coh(&P.h[o], hn);
+            ActPlanes<T> act{reinterpret_cast<T *>(P.act[ACT_A]), P.act_plane[ACT_A], P.act_ld[ACT_A]};
+            store_act_coh(act, (size_t)c * act.ld + n, ph.gain ? hn * ph.gain[n] : hn); // no gain: nothing normalises these rows
+            rowsq += hn * hn;
+        }
+        return;
+    }
+    if (ph.kind == PH_HEAD) {
+        if (live && c < P.head_rows) P.logits[(size_t)c * P.ldo + n] = sum * sm.t->scale[P.head_row0 + c * P.head_stride];
+        return;
+    }
+    // paired epilogues: lanes g < 2 hold the first row of a pair, lane + 32 holds its partner
+    const float partner = __shfl_down(sum, 32);
+    if (g >= 2 || !live || c >= P.R) return;
+    const float sc = sm.t->scale[c];
+    const float x0s = sum * sc, x1s = partner * sc;
+    if (ph.kind == PH_SWIGLU) {
+        ActPlanes<T> z{reinterpret_cast<T *>(P.act[ACT_Z]), P.act_plane[ACT_Z], P.act_ld[ACT_Z]};
+        const float s = x0s / (1.0f + expf(-x0s));
+        store_act_coh(z, (size_t)c * z.ld + n, s * x1s); // n = pair index = column of z
+        return;
+    }
+    // PH_QKV: n = hh*hd + j, j in the first half of head hh (heads ordered q | k | v)
+    const int hh = n / P.hd, j = n - hh * P.hd;
+    const int region = hh / P.H, h = hh - region * P.H;
+    const int b = c / P.M, ii = c - b * P.M;
+    int pos = P.len[b] + ii;
+    if (pos > P.max_pos - 1) pos = P.max_pos - 1; // host validation keeps these from happening
+    if (pos > P.S - 1) pos = P.S - 1;
+    float x0 = x0s, x1 = x1s;
+    if (region < 2) {
+        const float2 cs = P.rope[(size_t)pos * (P.hd / 2) + j];
+        x0 = x0s * cs.x - x1s * cs.y;
+        x1 = x0s * cs.y + x1s * cs.x;
+    }
+    if (region == 0) {
+        ActPlanes<T> q{reinterpret_cast<T *>(P.act[ACT_Q]), P.act_plane[ACT_Q], P.act_ld[ACT_Q]};
+        const size_t o = (size_t)c * q.ld + h * P.hd + j;
+        store_act_coh(q, o, x0);
+        store_act_coh(q, o + P.hd / 2, x1);
+    } else if (region == 1) {
+        T *kc = reinterpret_cast<T *>(P.kc) + P.layer_elems * ph.layer + (((size_t)b * P.H + h) * P.S + pos) * P.hd + j;
+        st_coh(kc, to_storage<T>(x0));
+        st_coh(kc + P.hd / 2, to_storage<T>(x1));
+    } else {
+        T *vc = reinterpret_cast<T *>(P.vc) + P.layer_elems * ph.layer + ((size_t)b * P.H + h) * P.S * P.hd +
+                ((size_t)(pos >> 6) * P.hd) * 64 + (pos & 63);
+        st_coh(vc + (size_t)j * 64, to_storage<T>(x0));
+        st_coh(vc + (size_t)(j + P.hd / 2) * 64, to_storage<T>(x1));
+    }
+}
+
+// acc0 / acc1 += chunk: the hi and lo planes (bf16) or alternate k-blocks (f32) go to different
+// accumulators so that consecutive MFMAs do not wait on each other
+__device__ __forceinline__ void mma2(f32x4 &acc0, f32x4 &acc1, u32x4 w, const Act<bf16_t> &b, int) {
+    bf16x8 av = __builtin_bit_cast(bf16x8, w);
+    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, b.p[0]), acc0, 0, 0, 0);
+    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, b.p[1]), acc1, 0, 0, 0);
+}
+__device__ __forceinline__ void mma2(f32x4 &acc0, f32x4 &acc1, u32x4 w, const Act<float> &b, int j) {
+    if (j & 1) acc1 = mma(acc1, w, b);
+    else acc0 = mma(acc0, w, b);
+}
+
+// multiply chunk c (weights in wbuf) into the tile accumulators
+template <typename T>
+__device__ __forceinline__ void mma_chunk(const Cursor &c, const MegaCall &P, const MegaPhase &ph, const u32x4 (&wbuf)[2 * CH],
+                                          f32x4 &acc0, f32x4 &acc1, int &slab_tag, MegaSmem &sm, int &ntr) {
+    constexpr int E = Traits<T>::E, KB = 4 * E, PL = Traits<T>::PLANES;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, cc = lane & 15, g = lane >> 4;
+    if (c.ck == 0) {
+        acc0 = f32x4{0.f, 0.f, 0.f, 0.f};
+        acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    if (P.slab_rows > 0) {
+        // B operand from the LDS slab of (phase, K slab); reloaded only when that pair changes
+        const int tag = (c.p << 8) | (c.ck / SLAB_CK);
+        if (slab_tag != tag) {
+            __syncthreads(); // every wave is done with the previous slab
+            load_slab<T>(P, ph, c.ck / SLAB_CK, sm);
+            __syncthreads();
+            slab_tag = tag;
+            trace(P, ntr, 100 + ph.kind);
+        }
+        const bool blive = cc < P.slab_rows;
+        const unsigned char *lb = sm.u + (size_t)cc * SLAB_PITCH + (c.ck % SLAB_CK) * CHUNK_ROW_BYTES + wave * 128 + g * 16;
+        const size_t plane_off = (size_t)P.slab_rows * SLAB_PITCH;
+#pragma unroll
+        for (int i = 0; i < CH; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                Act<T> av;
+#pragma unroll
+                for (int pl = 0; pl < PL; ++pl)
+                    av.p[pl] = blive ? *reinterpret_cast<const u32x4 *>(lb + pl * plane_off + i * (MNW * 128) + j * 64) : zero16();
+                mma2(acc0, acc1, wbuf[2 * i + j], av, j);
+            }
+    } else {
+        // too many rows for the slab: coherent loads straight from memory
+        const bool head = ph.kind == PH_HEAD;
+        const int brow = head ? P.head_row0 + cc * P.head_stride : cc;
+        const bool blive = cc < (head ? P.head_rows : P.R);
+        ActPlanes<T> act{reinterpret_cast<T *>(P.act[ph.act_src]), P.act_plane[ph.act_src], P.act_ld[ph.act_src]};
+        const size_t aoff = (size_t)brow * act.ld + g * E;
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int s = wave + MNW * (c.ck * CH + i);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int k = (2 * s + j) * KB;
+                const Act<T> av = (blive && k + g * E < ph.K) ? load_act_coh(act, aoff + k) : zero_act<T>();
+                mma2(acc0, acc1, wbuf[2 * i + j], av, j);
+            }
+        }
+    }
+    trace(P, ntr, 4);
+}
+
+// tile complete: fixed-order sum of the waves' partial tiles by waves 0-3 (register v = wave), epilogue
+template <typename T>
+__device__ __forceinline__ void finish_tile(const Cursor &c, const MegaCall &P, const MegaPhase &ph, const f32x4 &acc0,
+                                            const f32x4 &acc1, int &tile_seq, float &rowsq, MegaSmem &sm, int &ntr) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int par = tile_seq & 1;
+    ++tile_seq;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) sm.t->red[par][wave][v][lane] = acc0[v] + acc1[v];
+    __syncthreads();
+    trace(P, ntr, 5);
+    if (wave < 4) {
+        float sum = sm.t->red[par][0][wave][lane];
+#pragma unroll
+        for (int w2 = 1; w2 < MNW; ++w2) sum += sm.t->red[par][w2][wave][lane];
+        tile_epilogue<T>(P, ph, c.r, c.tile, sum, wave, rowsq, sm);
+    }
+    trace(P, ntr, 6);
+}
+
+// ---------------------------------------------------------------- the kernel
+
+template <typename T>
+__global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCall P) {
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    MegaSmem sm;
+    sm.u = smem_raw;
+    sm.t = reinterpret_cast<MegaSmemTail *>(smem_raw + P.u_bytes);
+    const int wg = blockIdx.x, G = gridDim.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    // Weight pipeline: `la` runs RING chunks ahead of `cc` (the next chunk to multiply); the loads of
+    // those chunks are in flight into the ring slots r0, r1, r2.  A step multiplies straight out of its
+    // slot (which waits for that slot's loads only - later slots stay in flight), then refills the slot
+    // with the chunk RING ahead, which may belong to the next phase: barriers, phase prologues and
+    // epilogues run under weight loads that are already in flight.  Every workgroup's chunk count per
+    // phase is padded to a multiple of RING, so each phase starts at slot r0 and the code below exists
+    // once.  The attention phase needs most of the register file: the look-ahead does not cross it,
+    // and the ring is refilled right after it (before the barrier that follows).
+    struct State {
+        Cursor cc, la;
+        f32x4 acc0, acc1;
+        int tile_seq, slab_tag;
+        float rowsq;
+    } st;
+    st.cc.p = 0;
+    cursor_seek<T>(st.cc, P, wg, G);
+    st.la = st.cc;
+    st.acc0 = f32x4{0.f, 0.f, 0.f, 0.f};
+    st.acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
+    st.tile_seq = 0;
+    st.slab_tag = -1;
+    st.rowsq = 0.f;
+    int ntr = 0;
+
+    auto next_attn = [&](int from) {
+        int q = from;
+        while (q < P.n_phases && P.phases[q].kind != PH_ATTN) ++q;
+        return q;
+    };
+    int la_limit = next_attn(0);
+
+    u32x4 r0[2 * CH], r1[2 * CH], r2[2 * CH];
+    static_assert(RING == 3, "the loops below are written for three ring slots");
+    static_assert(MNW >= 4, "waves 0-3 reduce one accumulator register each");
+
+    auto fill = [&](u32x4(&slot)[2 * CH]) {
+        if (st.la.p < la_limit) {
+            issue_chunk(st.la, slot);
+            cursor_next<T>(st.la, P, wg, G);
+        }
+    };
+    fill(r0);
+    fill(r1);
+    fill(r2);
+
+    for (int p = 0; p < P.n_phases; ++p) {
+        const MegaPhase ph = P.phases[p];
+        if (p > 0 && !grid_sync(P, P.epoch_base + (unsigned)p, G, sm)) return;
+        if (P.timeline && wg == 0 && threadIdx.x == 0) P.timeline[3 * p] = wall_clock64();
+        st.rowsq = 0.f;
+        switch (ph.kind) {
+        case PH_EMBED: do_embed<T>(P, ph, wg, G, sm); break;
+        case PH_ATTN:
+            do_attn<T>(P, ph, wg, G, sm);
+            st.slab_tag = -1; // the attention area aliases the slab
+            la_limit = next_attn(p + 1);
+            fill(r0); // the ring was empty: start the weights of the phases after attention
+            fill(r1);
+            fill(r2);
+            break;
+        case PH_LEN:
+            if (wg == 0 && (int)threadIdx.x < P.B) P.len[threadIdx.x] += P.M;
+            break;
+        case PH_QKV:
+        case PH_SWIGLU:
+        case PH_HEAD: compute_scales(P, G, sm); break; // read after a later __syncthreads
+        default: break;
+        }
+        if (P.timeline && wg == 0 && threadIdx.x == 0) P.timeline[3 * p + 1] = wall_clock64();
+        trace(P, ntr, 200 + ph.kind);
+
+        auto step = [&](u32x4(&slot)[2 * CH]) {
+            const Cursor c = st.cc;
+            cursor_next<T>(st.cc, P, wg, G);
+            if (!c.dummy) mma_chunk<T>(c, P, ph, slot, st.acc0, st.acc1, st.slab_tag, sm, ntr);
+            fill(slot);
+            trace(P, ntr, 3);
+            if (!c.dummy && c.ck + 1 == c.nck) finish_tile<T>(c, P, ph, st.acc0, st.acc1, st.tile_seq, st.rowsq, sm, ntr);
+        };
+        while (st.cc.p == p) { // RING chunks (padding included) per round
+            step(r0);
+            step(r1);
+            step(r2);
+        }
+
+        if (ph.kind == PH_RESID) {
+            // publish this workgroup's partial sums of squares of the new hidden rows
+            float rs = st.rowsq;
+            rs += __shfl_xor(rs, 16);
+            rs += __shfl_xor(rs, 32);
+            if (wave < 4 && lane < 16) sm.t->sq[wave][lane] = rs;
+            __syncthreads();
+            if (threadIdx.x < 16)
+                st_coh(&P.nsq[(size_t)threadIdx.x * G + wg],
+                       (sm.t->sq[0][threadIdx.x] + sm.t->sq[1][threadIdx.x]) + (sm.t->sq[2][threadIdx.x] + sm.t->sq[3][threadIdx.x]));
+        }
+        if (P.timeline && wg == 0 && threadIdx.x == 0) P.timeline[3 * p + 2] = wall_clock64();
+    }
+}
+
+constexpr size_t LDS_BYTES = 160 * 1024;
+constexpr size_t ATTN_BYTES = sizeof(AttnSmem<128, MNW>);
+
+// rows the LDS slab can hold (0: use the direct path) and the size of the slab / attention area
+static void smem_plan(int dtype, int rows, int &slab_rows, size_t &u_bytes) {
+    const size_t planes = dtype ? 2 : 1;
+    const size_t avail = LDS_BYTES - sizeof(MegaSmemTail) - 256;
+    const int max_rows = (int)(avail / (planes * SLAB_PITCH));
+    slab_rows = rows <= max_rows ? rows : 0;
+    u_bytes = std::max(ATTN_BYTES, (size_t)slab_rows * planes * SLAB_PITCH);
+    u_bytes = (u_bytes + 255) & ~(size_t)255;
+}
+
+static hipError_t ensure_smem_attr(int dtype) {
+    static bool attr_set[2] = {false, false};
+    const int i = dtype ? 1 : 0;
+    if (attr_set[i]) return hipSuccess;
+    const void *fn = dtype ? (const void *)verify_persistent_kernel<bf16_t> : (const void *)verify_persistent_kernel<float>;
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
+    if (e == hipSuccess) attr_set[i] = true;
+    return e;
+}
+
+int mega_grid(int dtype, int device) {
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) return 0;
+    if (ensure_smem_attr(dtype) != hipSuccess) return 0;
+    int per_cu = 0;
+    const size_t smem = LDS_BYTES - 1024;
+    hipError_t e = dtype ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, verify_persistent_kernel<bf16_t>, MEGA_THREADS, smem)
+                         : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, verify_persistent_kernel<float>, MEGA_THREADS, smem);
+    if (e != hipSuccess || per_cu < 1) return 0;
+    return prop.multiProcessorCount; // one workgroup per compute unit
+}
+
+hipError_t launch_mega(const MegaCall &call, int grid, hipStream_t st) {
+    MegaCall c = call;
+    size_t u_bytes;
+    smem_plan(c.dtype, std::max(c.R, c.head_rows), c.slab_rows, u_bytes);
+    c.u_bytes = (int)u_bytes;
+    void *args[] = {&c};
+    const void *fn = call.dtype ? (const void *)verify_persistent_kernel<bf16_t> : (const void *)verify_persistent_kernel<float>;
+    hipError_t e = ensure_smem_attr(call.dtype);
+    if (e != hipSuccess) return e;
+    return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(MEGA_THREADS), args, u_bytes + sizeof(MegaSmemTail), st);
+}
+
+} // namespace ss

@@ -127,6 +127,37 @@ __device__ __forceinline__ f32x4 mma(f32x4 acc, u32x4 a, const Act<float> &b) {
     return acc;
 }
 
+// ---- agent-coherent accesses ------------------------------------------------------------------
+// Data that one workgroup writes and another reads INSIDE one kernel (persistent verify kernel) is
+// moved with relaxed agent-scope atomics: they are performed at the memory side, so no cache
+// write-back / invalidate is needed at the device-wide barriers (the L2 of each XCD is private).
+__device__ __forceinline__ float ld_coh(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_coh(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_coh(bf16_t *p, bf16_t v) {
+    __hip_atomic_store(reinterpret_cast<uint16_t *>(p), v.bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long ld_coh64(const void *p) {
+    return __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// 16-byte chunk as two coherent 8-byte loads
+__device__ __forceinline__ u32x4 ld16_coh(const void *p) {
+    const unsigned long long a = ld_coh64(p), b = ld_coh64(reinterpret_cast<const char *>(p) + 8);
+    return u32x4{(uint32_t)a, (uint32_t)(a >> 32), (uint32_t)b, (uint32_t)(b >> 32)};
+}
+template <typename T> __device__ __forceinline__ Act<T> load_act_coh(const ActPlanes<T> &a, size_t off) {
+    Act<T> r;
+#pragma unroll
+    for (int pl = 0; pl < Traits<T>::PLANES; ++pl) r.p[pl] = ld16_coh(a.base + pl * a.plane + off);
+    return r;
+}
+__device__ __forceinline__ void store_act_coh(const ActPlanes<bf16_t> &a, size_t off, float x) {
+    uint32_t hi = bf16_rne(x);
+    uint32_t lo = bf16_rne(x - bf16_bits_to_f32(hi));
+    st_coh(a.base + off, bf16_t{(uint16_t)hi});
+    st_coh(a.base + a.plane + off, bf16_t{(uint16_t)lo});
+}
+__device__ __forceinline__ void store_act_coh(const ActPlanes<float> &a, size_t off, float x) { st_coh(a.base + off, x); }
+
 __device__ __forceinline__ float wave_max(float x) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));

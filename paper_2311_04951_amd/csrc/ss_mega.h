@@ -1,0 +1,76 @@
+// Program description of the persistent verify kernel: a list of phases (built once per model) and
+// the per-call parameters.  Plain data shared by the host API and the kernel.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace ss {
+
+enum PhaseKind : int {
+    PH_EMBED = 0, // hidden rows from the embedding table (or from given rows), packed for the first norm
+    PH_QKV,       // QKV projection + row scale + rotary + cache append
+    PH_ATTN,      // multi-row decode attention (+ merge by the last split to finish)
+    PH_RESID,     // O projection / down projection: h += ..., repack for the next norm
+    PH_SWIGLU,    // gate/up projection + row scale + SwiGLU
+    PH_HEAD,      // LM head + row scale
+    PH_LEN        // cache lengths += M
+};
+
+enum ActBuf : int { ACT_A = 0, ACT_Q = 1, ACT_O = 2, ACT_Z = 3, ACT_COUNT = 4 };
+
+struct MegaPhase {
+    int kind, layer;
+    const void *W;     // weights of a GEMM phase, row-major [rows][K]
+    int N;             // QKV: 3*H*hd rows; SWIGLU: F (pairs of gate/up rows); RESID, HEAD: rows
+    int K;
+    int act_src;       // activation planes read (B operand)
+    const float *gain; // EMBED / RESID: gain of the NEXT RMSNorm, folded in when the new rows are packed
+};
+
+struct MegaCall {
+    const MegaPhase *phases;
+    int n_phases;
+    int dtype;
+    int d, H, hd, F, V;
+    int R, B, M;
+    float eps;
+    // embedding / residual stream
+    const int32_t *tokens; // NULL: rows are taken from h as given
+    const void *embed;
+    float *h;              // [R][d] residual stream (in/out)
+    void *act[ACT_COUNT];  // activation planes
+    size_t act_plane[ACT_COUNT];
+    int act_ld[ACT_COUNT];
+    float *nsq;            // [16][G] per-workgroup partial sums of squares of the rows of h
+    // LM head: output row r reads activation row head_row0 + r*head_stride
+    float *logits;
+    int ldo, head_rows, head_row0, head_stride;
+    // cache
+    void *kc, *vc;
+    size_t layer_elems;
+    int32_t *len;
+    int S, max_pos;
+    const float2 *rope;
+    // attention
+    int nsplit, chunk;
+    float *part_o, *part_m, *part_l;
+    unsigned *attn_cnt; // [B*H] arrival counters (zero between launches)
+    float scale_log2e;
+    // device-wide barrier: arrive[G] slots hold the last epoch each workgroup reached
+    unsigned *arrive;
+    unsigned *abort_flag;
+    unsigned epoch_base;
+    unsigned spin_limit;
+    int32_t *status;
+    int slab_rows, u_bytes;       // set by launch_mega: rows held in the LDS slab (0: none), size of the slab area
+    unsigned long long *timeline; // optional [3*n_phases] device clock samples of workgroup 0 (NULL: off)
+};
+
+constexpr int MEGA_THREADS = 512;
+
+// number of workgroups a launch may use (all resident at once), and the launch itself
+int mega_grid(int dtype, int device);
+hipError_t launch_mega(const MegaCall &call, int grid, hipStream_t st);
+
+} // namespace ss

@@ -18,10 +18,15 @@ def weights_to_device(w):
     return out
 
 
-def model_pair(shape, seed, max_rows=16, max_pos=256):
+def model_pair(shape, seed, max_rows=16, max_pos=256, persistent=False):
     """(oracle model, GPU model, host weights) over identical seeded weights."""
     w = si.decoder_weights(shape, seed)
-    return oracle.Model(shape, w), sv.Model(shape, weights_to_device(w), max_rows=max_rows, max_pos=max_pos), w
+    gm = sv.Model(shape, weights_to_device(w), max_rows=max_rows, max_pos=max_pos)
+    sv.ss_model_set_persistent(gm, persistent)
+    return oracle.Model(shape, w), gm, w
+
+
+PATHS = [False, True]   # per-phase launches, persistent kernel
 
 
 def tol(shape):

@@ -10,7 +10,7 @@ import torch
 import oracle
 import paper_2311_04951_amd as sv
 import seeded_inputs as si
-from gpu_util import dev, maxabs, model_pair, tol, weights_to_device
+from gpu_util import PATHS, dev, maxabs, model_pair, tol, weights_to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -27,8 +27,9 @@ def _gpu_forward_chunks(gm, gkv, toks, chunks):
 @pytest.mark.parametrize("shape", [si.TINY_TARGET, si.TINY_DRAFT,
                                    si.DecoderShape(2, 64, 2, 32, 96, 50, rope_base=500.0, rms_eps=1e-6, dtype="f32"),
                                    si.DecoderShape(2, 256, 2, 128, 344, 300, dtype="f32")])
-def test_fp32_verify_logits_match_oracle(shape):
-    om, gm, _ = model_pair(shape, seed=3)
+@pytest.mark.parametrize("persistent", PATHS)
+def test_fp32_verify_logits_match_oracle(shape, persistent):
+    om, gm, _ = model_pair(shape, seed=3, persistent=persistent)
     toks = si.token_ids(3, "toks", (70,), shape.vocab).numpy()
     chunks = [16, 16, 1, 5, 5, 2, 9, 16]            # prefill chunks, single rows, K+1-row verify passes
     gkv = sv.KVCache(gm, 1, 100)
@@ -42,8 +43,9 @@ def test_fp32_verify_logits_match_oracle(shape):
 @pytest.mark.parametrize("shape", [si.DecoderShape(2, 128, 2, 64, 344, 512, dtype="bf16"),
                                    si.DecoderShape(1, 512, 4, 128, 1376, 1000, dtype="bf16"),
                                    si.DecoderShape(3, 256, 8, 32, 688, 333, dtype="bf16")])
-def test_bf16_verify_logits_match_oracle(shape):
-    om, gm, _ = model_pair(shape, seed=4)
+@pytest.mark.parametrize("persistent", PATHS)
+def test_bf16_verify_logits_match_oracle(shape, persistent):
+    om, gm, _ = model_pair(shape, seed=4, persistent=persistent)
     toks = si.token_ids(4, "toks", (150,), shape.vocab).numpy()
     chunks = [16] * 8 + [5, 1, 9, 7]                # crosses the 64- and 128-position cache blocks
     gkv = sv.KVCache(gm, 1, 160)
@@ -54,10 +56,11 @@ def test_bf16_verify_logits_match_oracle(shape):
     assert maxabs(got, ref) < 2e-3
 
 
-def test_rollback_then_reverify_matches_oracle():
+@pytest.mark.parametrize("persistent", PATHS)
+def test_rollback_then_reverify_matches_oracle(persistent):
     """Rejected rows are dropped by a length write and overwritten by the next pass (Section 4.4)."""
     shape = si.TINY_TARGET
-    om, gm, _ = model_pair(shape, seed=5)
+    om, gm, _ = model_pair(shape, seed=5, persistent=persistent)
     toks = si.token_ids(5, "toks", (40,), shape.vocab).numpy()
     gkv = sv.KVCache(gm, 1, 64)
     _gpu_forward_chunks(gm, gkv, toks[:20], [16, 4])
@@ -74,15 +77,16 @@ def test_rollback_then_reverify_matches_oracle():
     assert maxabs(got, ref) < tol(shape)
 
 
+@pytest.mark.parametrize("B,M,persistent", [(3, 9, False), (3, 5, True), (3, 5, False)])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_batched_ragged_lengths_match_per_sequence_oracle(dtype):
+def test_batched_ragged_lengths_match_per_sequence_oracle(dtype, B, M, persistent):
     """Three sequences with different context lengths verified in one call; each must equal the
     oracle run on that sequence alone.  Contexts are built with the raw append."""
     shape = si.DecoderShape(2, 128, 2, 64, 344, 512, dtype=dtype)
     w = si.decoder_weights(shape, seed=6)
     om = oracle.Model(shape, w)
     gm = sv.Model(shape, weights_to_device(w), max_rows=48, max_pos=512)
-    B, M = 3, 9
+    sv.ss_model_set_persistent(gm, persistent)
     lens = [70, 3, 129]
     gkv = sv.KVCache(gm, B, 200)
     toks = si.token_ids(6, "toks", (B, M), shape.vocab)
@@ -100,12 +104,13 @@ def test_batched_ragged_lengths_match_per_sequence_oracle(dtype):
         assert maxabs(got[b], refs[b]) < tol(shape), b
     assert sv.ss_kv_cache_get_len(gkv).tolist() == [l + M for l in lens]
     # ragged roll-back: different accept counts per sequence
-    na = torch.tensor([0, 8, 3], dtype=torch.int32, device=dev())
+    na = torch.tensor([0, M - 1, 3], dtype=torch.int32, device=dev())
     sv.ss_kv_cache_rollback(gkv, na, M)
-    assert sv.ss_kv_cache_get_len(gkv).tolist() == [lens[0] + 1, lens[1] + 9, lens[2] + 4]
+    assert sv.ss_kv_cache_get_len(gkv).tolist() == [lens[0] + 1, lens[1] + M, lens[2] + 4]
 
 
-def test_single_7b_layer_verify_matches_oracle():
+@pytest.mark.parametrize("persistent", PATHS)
+def test_single_7b_layer_verify_matches_oracle(persistent):
     """One 7B-shaped bf16 layer, 5 query rows against 1024 cached positions (the microbench shape):
     hidden rows out of the layer vs the oracle, max-abs 2e-2."""
     shape = si.LAYER_7B
@@ -113,6 +118,7 @@ def test_single_7b_layer_verify_matches_oracle():
     w = {"embed": None, "gf": None, "lm_head": None, "layers": [lw]}
     om = oracle.Model(shape, w)
     gm = sv.Model(shape, weights_to_device(w), max_rows=16, max_pos=2048)
+    sv.ss_model_set_persistent(gm, persistent)
     L, M = 1024, 5
     ctx = si.kv_context(shape, 0, "ctx", L)
     gkv = sv.KVCache(gm, 1, L + 64)

@@ -9,12 +9,12 @@ import oracle
 import paper_2311_04951_amd as sv
 import seeded_inputs as si
 from paper_2311_04951_amd import generate as gen
-from gpu_util import dev, maxabs, weights_to_device
+from gpu_util import PATHS, dev, maxabs, weights_to_device
 
 pytestmark = pytest.mark.gpu
 
 
-def _pair(seed, early=False):
+def _pair(seed, early=False, persistent=False):
     tw = si.decoder_weights(si.TINY_TARGET, seed)
     if early:
         dshape, dw = si.early_exit_draft(si.TINY_TARGET, tw, 1)
@@ -22,12 +22,15 @@ def _pair(seed, early=False):
         dshape, dw = si.TINY_DRAFT, si.decoder_weights(si.TINY_DRAFT, seed + 100)
     gt = sv.Model(si.TINY_TARGET, weights_to_device(tw), max_rows=16, max_pos=256)
     gd = sv.Model(dshape, weights_to_device(dw), max_rows=16, max_pos=256)
+    sv.ss_model_set_persistent(gt, persistent)
+    sv.ss_model_set_persistent(gd, persistent)
     return (oracle.Model(si.TINY_TARGET, tw), oracle.Model(dshape, dw)), (gt, gd)
 
 
+@pytest.mark.parametrize("persistent", PATHS)
 @pytest.mark.parametrize("K,early", [(4, False), (2, True), (8, True)])
-def test_greedy_speculative_equals_greedy_autoregressive_on_gpu(K, early):
-    (ot, od), (gt, gd) = _pair(0, early)
+def test_greedy_speculative_equals_greedy_autoregressive_on_gpu(K, early, persistent):
+    (ot, od), (gt, gd) = _pair(0, early, persistent)
     prompt = si.token_ids(0, "prompt", (32,), 1024).numpy().tolist()
     ar = gen.autoregressive_generate(gt, prompt, 64, 0.0)
     sp, stats = gen.speculative_generate(gt, gd, prompt, 64, K, 0.0)
@@ -37,21 +40,23 @@ def test_greedy_speculative_equals_greedy_autoregressive_on_gpu(K, early):
     assert all(0 <= a <= K for a in stats["accepted"])
 
 
-def test_greedy_with_draft_equal_to_target_accepts_everything_on_gpu():
+@pytest.mark.parametrize("persistent", PATHS)
+def test_greedy_with_draft_equal_to_target_accepts_everything_on_gpu(persistent):
     """Every draft token is accepted, so every step after the first takes the two-token draft
     catch-up; the stream must still be the autoregressive one."""
-    (ot, _), (gt, _) = _pair(3)
+    (ot, _), (gt, _) = _pair(3, persistent=persistent)
     prompt = si.token_ids(3, "prompt", (9,), 1024).numpy().tolist()
     ar = gen.autoregressive_generate(gt, prompt, 30, 0.0)
     sp, stats = gen.speculative_generate(gt, gt, prompt, 30, 3, 0.0)
     assert sp == ar and all(a == 3 for a in stats["accepted"])
 
 
-def test_sampled_run_in_lock_step_with_the_oracle():
+@pytest.mark.parametrize("persistent", PATHS)
+def test_sampled_run_in_lock_step_with_the_oracle(persistent):
     """Temperature 1, K = 4, 64 tokens.  Each step the oracle is run on the GPU's history: logits by
     tolerance, draft sampling and accept/resample decisions bit-exact on the GPU's own q and p."""
     K, n_new, T = 4, 64, 1.0
-    (ot, od), (gt, gd) = _pair(1, early=True)
+    (ot, od), (gt, gd) = _pair(1, early=True, persistent=persistent)
     prompt = si.token_ids(1, "prompt", (32,), 1024).numpy().tolist()
     ud = si.uniforms(1, "ud", (n_new, K)).numpy()
     ua = si.uniforms(1, "ua", (n_new, K + 1)).numpy()
