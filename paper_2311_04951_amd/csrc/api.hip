@@ -12,6 +12,7 @@
 #include <cstring>
 #include <mutex>
 #include <string>
+#include <algorithm>
 #include <vector>
 
 using namespace ss;
@@ -67,6 +68,7 @@ struct ss_model {
     int n_full = 0, n_nohead = 0;
     float *nsq = nullptr;
     unsigned *arrive = nullptr, *abort_flag = nullptr, *attn_cnt = nullptr;
+    void *zeros = nullptr;
     unsigned epoch = 1;
     bool persistent = false; // forward path: false = one launch per phase, true = the persistent kernel
     // optional per-kernel-class timing (ss_profile_*): event pairs recorded around launches
@@ -216,6 +218,7 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
                 A((void **)&m->nsq, sizeof(float) * 16 * (size_t)m->mega_G, true);
                 A((void **)&m->arrive, sizeof(unsigned) * (size_t)m->mega_G, true);
                 A((void **)&m->abort_flag, sizeof(unsigned), true);
+                A(&m->zeros, 256, true);
                 A((void **)&m->attn_cnt, sizeof(unsigned) * (size_t)c.max_rows * c.n_heads, true);
                 if (rc == SS_OK) {
                     hipError_t e1 = hipMemcpy(m->prog_full, prog.data(), sizeof(MegaPhase) * prog.size(), hipMemcpyHostToDevice);
@@ -538,8 +541,10 @@ static int run_persistent(ss_model *m, ss_kv_cache *kv, const int32_t *tokens, f
     P.rope = m->rope;
     int Lmax = 0;
     for (int b = 0; b < batch; ++b) Lmax = std::max(Lmax, kv->len_ub[b] + M);
-    int want = (2 * m->mega_G + batch * c.n_heads - 1) / (batch * c.n_heads);
-    int nsplit = std::max(1, std::min(std::min(want, (Lmax + 63) / 64), MAX_SPLITS));
+    // one (sequence, head, split) unit per workgroup when possible; a split is worth its merge only once
+    // a unit would otherwise walk more than ~1024 positions (4 blocks per wave)
+    const int fit = std::max(1, m->mega_G / (batch * c.n_heads));
+    int nsplit = std::max(1, std::min(std::min((Lmax + 1023) / 1024, fit), MAX_SPLITS));
     const int chunk = round_up((Lmax + nsplit - 1) / nsplit, 64);
     nsplit = (Lmax + chunk - 1) / chunk;
     P.nsplit = nsplit; P.chunk = chunk;
@@ -548,13 +553,19 @@ static int run_persistent(ss_model *m, ss_kv_cache *kv, const int32_t *tokens, f
     P.arrive = m->arrive; P.abort_flag = m->abort_flag; P.epoch_base = m->epoch;
     P.spin_limit = 1u << 20;
     P.status = m->status;
+    P.zeros = m->zeros;
     m->epoch += (unsigned)P.n_phases + 1;
-    static const bool want_timeline = getenv("SS_TIMELINE") != nullptr; // development aid: phase times of workgroup 0
+    // development aid (SS_TIMELINE=1): device clock samples of every workgroup at each phase's start,
+    // after its prologue and at its end, summarised per phase kind on stderr after the launch
+    static const bool want_timeline = getenv("SS_TIMELINE") != nullptr;
     static unsigned long long *tl_dev = nullptr;
+    static size_t tl_cap = 0;
+    const size_t tl_need = (size_t)3 * P.n_phases * m->mega_G;
     if (want_timeline) {
-        if (!tl_dev) {
-            HIP_TRY(hipMalloc((void **)&tl_dev, sizeof(unsigned long long) * (3 * 4096 + 2 * 4096)));
-            HIP_TRY(hipMemset(tl_dev, 0, sizeof(unsigned long long) * (3 * 4096 + 2 * 4096)));
+        if (tl_cap < tl_need) {
+            if (tl_dev) HIP_TRY(hipFree(tl_dev));
+            HIP_TRY(hipMalloc((void **)&tl_dev, sizeof(unsigned long long) * tl_need));
+            tl_cap = tl_need;
         }
         P.timeline = tl_dev;
     }
@@ -564,39 +575,37 @@ static int run_persistent(ss_model *m, ss_kv_cache *kv, const int32_t *tokens, f
         if (e != hipSuccess) return fail(SS_EHIP, "persistent verify kernel launch: %s", hipGetErrorString(e));
     }
     for (int b = 0; b < batch; ++b) kv->len_ub[b] += M;
-    if (want_timeline && P.n_phases <= 4096) {
-        std::vector<unsigned long long> t(3 * P.n_phases);
-        std::vector<MegaPhase> ph(P.n_phases);
+    if (want_timeline) {
+        const int G = m->mega_G, NP = P.n_phases;
+        std::vector<unsigned long long> t(tl_need);
+        std::vector<MegaPhase> ph(NP);
         HIP_TRY(hipStreamSynchronize(st));
         HIP_TRY(hipMemcpy(t.data(), tl_dev, t.size() * 8, hipMemcpyDeviceToHost));
         HIP_TRY(hipMemcpy(ph.data(), P.phases, ph.size() * sizeof(MegaPhase), hipMemcpyDeviceToHost));
-        double pre[8] = {0}, work[8] = {0}, wait[8] = {0};
+        auto at = [&](int p, int k, int wg) { return (double)t[((size_t)3 * p + k) * G + wg] * 0.01; }; // 100 MHz clock
+        double pre[8] = {0}, wmed[8] = {0}, wmax[8] = {0}, wall[8] = {0}, sync[8] = {0}, skew[8] = {0};
         int cnt[8] = {0};
-        for (int p = 0; p < P.n_phases; ++p) {
-            const int k = ph[p].kind + (ph[p].kind == PH_RESID && ph[p].K != c.d_ff ? 0 : 0);
-            const int slot = (ph[p].kind == PH_RESID && ph[p].K == c.d_ff) ? 7 : k;
-            pre[slot] += (double)(t[3 * p + 1] - t[3 * p]) * 0.01;
-            work[slot] += (double)(t[3 * p + 2] - t[3 * p + 1]) * 0.01;
-            if (p + 1 < P.n_phases) wait[slot] += (double)(t[3 * (p + 1)] - t[3 * p + 2]) * 0.01;
+        std::vector<double> w(G);
+        for (int p = 0; p < NP; ++p) {
+            const int slot = (ph[p].kind == PH_RESID && ph[p].K == c.d_ff) ? 7 : ph[p].kind;
+            double s0 = 1e300, s1 = 0, e1 = 0, n0 = 1e300, pr = 0;
+            for (int g = 0; g < G; ++g) {
+                s0 = std::min(s0, at(p, 0, g)); s1 = std::max(s1, at(p, 0, g)); e1 = std::max(e1, at(p, 2, g));
+                if (p + 1 < NP) n0 = std::min(n0, at(p + 1, 0, g));
+                w[g] = at(p, 2, g) - at(p, 0, g);
+                pr += at(p, 1, g) - at(p, 0, g);
+            }
+            std::sort(w.begin(), w.end());
+            pre[slot] += pr / G; wmed[slot] += w[G / 2]; wmax[slot] += w[G - 1]; wall[slot] += e1 - s0; skew[slot] += s1 - s0;
+            if (p + 1 < NP) sync[slot] += n0 - e1;
             cnt[slot]++;
         }
         const char *names[8] = {"embed", "qkv", "attn", "oproj", "gateup", "head", "len", "down"};
-        fprintf(stderr, "[timeline wg0] total %.1f us:", (double)(t[3 * P.n_phases - 1] - t[0]) * 0.01);
+        fprintf(stderr, "[timeline] total %.1f us\n", at(NP - 1, 2, 0) - at(0, 0, 0));
         for (int k = 0; k < 8; ++k)
-            if (cnt[k]) fprintf(stderr, " %s{n=%d pre=%.1f work=%.1f barrier_after=%.1f}", names[k], cnt[k], pre[k] / cnt[k], work[k] / cnt[k], wait[k] / cnt[k]);
-        fprintf(stderr, "\n");
-        if (getenv("SS_TRACE")) {
-            std::vector<unsigned long long> tr(2 * 4096);
-            HIP_TRY(hipMemcpy(tr.data(), tl_dev + 3 * 4096, tr.size() * 8, hipMemcpyDeviceToHost));
-            fprintf(stderr, "[trace]");
-            for (int i = 0; i < 4000 && tr[2 * i]; ++i) {
-                if (i > 0) fprintf(stderr, " %llu:+%.2f", tr[2 * i], (double)(tr[2 * i + 1] - tr[2 * i - 1]) * 0.01);
-                else fprintf(stderr, " %llu", tr[0]);
-                if ((int)tr[2 * i] >= 200 && i > 140) break;
-            }
-            fprintf(stderr, "\n");
-            HIP_TRY(hipMemset(tl_dev + 3 * 4096, 0, sizeof(unsigned long long) * 2 * 4096));
-        }
+            if (cnt[k])
+                fprintf(stderr, "  %-7s n=%d start_skew=%.1f prologue=%.1f busy_median=%.1f busy_max=%.1f first_start_to_last_end=%.1f sync_after=%.1f\n",
+                        names[k], cnt[k], skew[k] / cnt[k], pre[k] / cnt[k], wmed[k] / cnt[k], wmax[k] / cnt[k], wall[k] / cnt[k], sync[k] / cnt[k]);
     }
     return SS_OK;
 }

@@ -17,7 +17,8 @@ template <int HD, int NW> struct AttnSmem {
 // One (sequence b, head h, KV split) unit by a workgroup of NW wavefronts: writes the split's
 // unnormalised partial (part_o, part_m, part_l).  Every thread of the workgroup must call it.
 // COH: queries are read and partials written with agent-coherent accesses (persistent kernel).
-template <typename T, int HD, int NW, bool COH = false>
+// DIRECT: there is a single split, so the normalised result goes straight to the activation planes.
+template <typename T, int HD, int NW, bool COH = false, bool DIRECT = false>
 __device__ __forceinline__ void attn_unit(const AttnArgs &a, int split, int h, int b, AttnSmem<HD, NW> &sm) {
     constexpr int E = Traits<T>::E, KB = 4 * E, TPB = E / 4, NKC = HD / KB, NDT = HD / 16;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -114,6 +115,24 @@ __device__ __forceinline__ void attn_unit(const AttnArgs &a, int split, int h, i
     for (int w = 0; w < NW; ++w) wt[w] = exp2f(sm_m[w][c] - mstar);
     if (!row_ok) return;
     const int row = b * a.M + c;
+    if (DIRECT) {
+        float l = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) l += sm_l[w][c] * wt[w];
+        ActPlanes<T> out{reinterpret_cast<T *>(a.act_out), a.act_out_plane, a.ld_out};
+        for (int dt = wave; dt < NDT; dt += NW) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float acc = 0.f;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) acc += sm_o[w][dt][v][lane] * wt[w];
+                const size_t o = (size_t)row * a.ld_out + h * HD + dt * 16 + 4 * g + v;
+                if (COH) store_act_coh(out, o, acc / l);
+                else store_act(out, o, acc / l);
+            }
+        }
+        return;
+    }
     const size_t pidx = ((size_t)split * a.R + row) * a.H + h;
     if (wave == 0 && g == 0) {
         float l = 0.f;

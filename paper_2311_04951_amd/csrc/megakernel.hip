@@ -31,12 +31,13 @@
 #include "attention_core.h"
 #include "ss_mega.h"
 #include <algorithm>
+#include <type_traits>
 
 namespace ss {
 
 constexpr int MNW = MEGA_THREADS / 64; // wavefronts per workgroup
 constexpr int CH = 4;                  // 128-byte steps per chunk per wave (8 loads = 8 KB per wave)
-constexpr int SLAB_CK = 2;             // chunks per LDS activation slab
+constexpr int SLAB_CK = 8192 / (CH * MNW * 128); // chunks per LDS activation slab (8 KB of K per row)
 constexpr int RING = 3;                // chunks in flight per wave
 constexpr int CHUNK_ROW_BYTES = CH * MNW * 128; // bytes of a weight row one chunk covers (all waves)
 
@@ -83,10 +84,10 @@ template <typename T> __device__ __forceinline__ int chunks_per_tile(int K) {
 // Position in a workgroup's static chunk sequence.  Everything a step needs rides along (phase
 // fields, the tile's per-lane row pointer), so stepping costs no division and no descriptor reload.
 struct Cursor {
-    int p, tile, ck, nck;
-    int idx;    // chunk index inside the phase, padding included
-    bool dummy; // a padding position: no loads, no math (phases are padded to a multiple of RING chunks
-                // so that every phase starts at ring slot 0)
+    bool active; // positions of this workgroup remain in the current phase
+    int tile, ck, nck;
+    int idx;    // position index inside the phase, padding included
+    bool dummy; // a padding position: no data, no math
     Range r;
     int kind, N, kbytes; // phase kind, rows/pairs, bytes per weight row
     const char *W;
@@ -100,103 +101,122 @@ template <typename T> __device__ __forceinline__ void cursor_tile(Cursor &c, int
     c.wp = c.W + (size_t)row * c.kbytes + wave * 128 + g * 16;
 }
 
-template <typename T> __device__ __forceinline__ void cursor_seek(Cursor &c, const MegaCall &P, int wg, int G) {
-    while (c.p < P.n_phases) {
-        const MegaPhase ph = P.phases[c.p];
-        if (is_gemm(ph.kind)) {
-            c.r = phase_range(ph, wg, G);
-            if (c.r.ntiles > 0) {
-                c.kind = ph.kind;
-                c.N = ph.N;
-                c.kbytes = ph.K * (int)sizeof(T);
-                c.W = reinterpret_cast<const char *>(ph.W);
-                c.nck = chunks_per_tile<T>(ph.K);
-                c.tile = 0;
-                c.ck = 0;
-                c.idx = 0;
-                c.dummy = false;
-                cursor_tile<T>(c, P.hd);
-                return;
-            }
-        }
-        ++c.p;
-    }
+// Position the cursor at this workgroup's first chunk of phase ph (inactive: no share, or not a GEMM).
+template <typename T> __device__ __forceinline__ void cursor_begin(Cursor &c, const MegaPhase &ph, int hd, int wg, int G) {
+    c.active = false;
+    c.dummy = false;
+    c.live = false;
+    c.tile = 0;
+    c.ck = 0;
+    c.idx = 0;
+    c.nck = 1;
+    c.kind = ph.kind;
+    c.N = ph.N;
+    c.kbytes = 0;
+    c.W = nullptr;
+    c.wp = nullptr;
+    c.r = Range{0, 0, 0};
+    if (!is_gemm(ph.kind)) return;
+    c.r = phase_range(ph, wg, G);
+    if (c.r.ntiles <= 0) return;
+    c.active = true;
+    c.kbytes = ph.K * (int)sizeof(T);
+    c.W = reinterpret_cast<const char *>(ph.W);
+    c.nck = chunks_per_tile<T>(ph.K);
+    cursor_tile<T>(c, hd);
 }
 
-template <typename T> __device__ __forceinline__ void cursor_next(Cursor &c, const MegaCall &P, int wg, int G) {
+// Advance to the next position of the phase.  Positions are real chunks or padding: a "slab group"
+// (the chunks that share one LDS activation slab: the workgroup's whole share when K fits one slab, else
+// SLAB_CK chunks of a tile) is padded to a multiple of RING positions, so that rounds of RING steps
+// never straddle a slab reload or the end of the phase.  While `dummy` is set, (tile, ck, wp) already
+// describe the next real chunk.  Touches no memory.
+template <typename T> __device__ __forceinline__ void cursor_next(Cursor &c, int hd) {
     ++c.idx;
     if (!c.dummy) {
-        if (++c.ck < c.nck) return;
-        c.ck = 0;
-        if (++c.tile < c.r.ntiles) {
-            cursor_tile<T>(c, P.hd);
+        const bool multi = c.nck > SLAB_CK;
+        bool group_end;
+        if (++c.ck == c.nck) {
+            c.ck = 0;
+            ++c.tile;
+            group_end = multi || c.tile == c.r.ntiles;
+            if (c.tile < c.r.ntiles) cursor_tile<T>(c, hd);
+        } else {
+            group_end = multi && c.ck % SLAB_CK == 0;
+        }
+        if (!group_end) return;
+        if (c.idx % RING != 0) {
+            c.dummy = true;
             return;
         }
-        c.dummy = true; // real chunks done: pad to a multiple of RING
+    } else {
+        if (c.idx % RING != 0) return;
+        c.dummy = false;
     }
-    if (c.idx % RING != 0) return;
-    ++c.p;
-    cursor_seek<T>(c, P, wg, G);
+    if (c.tile >= c.r.ntiles) c.active = false;
 }
 
-// issue the 2*CH weight loads of chunk c for this lane: one base pointer, immediate offsets
-__device__ __forceinline__ void issue_chunk(const Cursor &c, u32x4 (&wbuf)[2 * CH]) {
+// Issue the 2*CH weight loads of chunk c for this lane.  Every call issues exactly 2*CH loads, whatever
+// the chunk is (real, padding, dead row, K tail): positions without data read a small zero-filled
+// buffer instead.  A fixed number of loads per step is what lets the compiler wait for one ring slot
+// with an exact vmcnt(N) and leave the younger slots in flight; a conditional load would force vmcnt(0).
+__device__ __forceinline__ void issue_chunk(const Cursor &c, bool valid, const char *zeros, u32x4 (&wbuf)[2 * CH]) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4;
-    if (c.dummy) return;
-#ifdef SS_EXPERIMENT_NOLOAD
-    for (int i = 0; i < 2 * CH; ++i) wbuf[i] = u32x4{(unsigned)(size_t)c.wp, 1u, 2u, 3u};
-    return;
-#endif
+    const bool real = valid && c.active && !c.dummy && c.live;
     const char *base = c.wp + (size_t)c.ck * CHUNK_ROW_BYTES;
-    const bool whole = (c.ck + 1) * CHUNK_ROW_BYTES <= c.kbytes; // uniform: the chunk lies inside the row
-    if (c.live && whole) {
+    const int kb0 = c.ck * CHUNK_ROW_BYTES + wave * 128 + g * 16;
 #pragma unroll
-        for (int i = 0; i < CH; ++i)
+    for (int i = 0; i < CH; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) wbuf[2 * i + j] = ld16(base + i * (MNW * 128) + j * 64);
-    } else {
-        const int kb0 = c.ck * CHUNK_ROW_BYTES + wave * 128 + g * 16;
-#pragma unroll
-        for (int i = 0; i < CH; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int off = i * (MNW * 128) + j * 64;
-                wbuf[2 * i + j] = (c.live && kb0 + off < c.kbytes) ? ld16(base + off) : zero16();
-            }
-    }
+        for (int j = 0; j < 2; ++j) {
+            const int off = i * (MNW * 128) + j * 64;
+            const char *a = (real && kb0 + off < c.kbytes) ? base + off : zeros;
+            wbuf[2 * i + j] = ld16_global(a);
+        }
 }
 
 constexpr int SLAB_ROW_BYTES = SLAB_CK * CH * MNW * 128; // 8192: the K range one slab covers, per hidden row
 constexpr int SLAB_PITCH = SLAB_ROW_BYTES + 48; // padded against LDS bank conflicts between rows
 
 // LDS: [ union: activation slab | attention merge area ][ red ][ small ]
+constexpr int STASH_TILES = 8; // reduced tiles kept in LDS until the epilogue flush
+
 struct MegaSmemTail {
     float red[2][MNW][4][64]; // partial tiles, double-buffered
+    float stash[STASH_TILES][4][64]; // reduced tiles: [slot][accumulator register v][lane]
+    int stash_tile[STASH_TILES];     // tile index of each slot
     float scale[16];          // row scales of the current phase
-    float sq[4][16];          // per reducer wave partial row sums of squares
+    float sq[MNW][16];        // per wave partial row sums of squares
     float blk[MNW];
     int flag;
 };
 
-// development aid: fine-grained event trace of workgroup 0, wave 0 (P.timeline + 3*4096 onwards)
-__device__ __forceinline__ void trace(const MegaCall &P, int &n, int tag) {
-    if (P.timeline && blockIdx.x == 0 && threadIdx.x == 0 && n < 4000) {
-        P.timeline[3 * 4096 + 2 * n] = (unsigned long long)tag;
-        P.timeline[3 * 4096 + 2 * n + 1] = wall_clock64();
-        ++n;
-    }
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding
+// global load (vmcnt(0)), which would drain the weight ring at each tile; this one waits for the LDS
+// queue alone, so prefetched weight loads stay in flight across it.
+// (s_waitcnt immediates, gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14].)
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_s_waitcnt(0xC07F); // lgkmcnt(0), vmcnt and expcnt untouched
+    __builtin_amdgcn_s_barrier();
 }
+
 
 struct MegaSmem {
     unsigned char *u; // slab / attention area
     MegaSmemTail *t;
 };
 
-// device-wide barrier without cache maintenance; false = aborted (bounded spin ran out or another
-// workgroup aborted).  Stores issued before it are complete (workgroup-scope release + barrier).
-__device__ __forceinline__ bool grid_sync(const MegaCall &P, unsigned epoch, int G, MegaSmem &sm) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __syncthreads();
+// Device-wide barrier without cache maintenance, in two parts so that weight loads can be put in
+// flight between them.  (1) stores_done(): every wave waits until its own stores are acknowledged
+// (vmcnt(0): on this ISA loads and stores share the counter, so this also drains the wave's loads).
+// (2) grid_arrive_wait(): workgroup barrier, wave 0 publishes the epoch and polls all slots, workgroup
+// barrier.  Waves other than wave 0 touch no memory in (2), so loads they issued after (1) stay in
+// flight across the whole device-wide barrier.  false = aborted (bounded spin ran out, or another
+// workgroup aborted).
+__device__ __forceinline__ void stores_done() { __builtin_amdgcn_s_waitcnt(0x0F70); } // vmcnt(0)
+
+__device__ __forceinline__ bool grid_arrive_wait(const MegaCall &P, unsigned epoch, int G, MegaSmem &sm) {
+    lds_barrier(); // every wave of the workgroup has passed stores_done()
     if (threadIdx.x < 64) {
         if (threadIdx.x == 0) __hip_atomic_store(&P.arrive[blockIdx.x], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         bool ok = true;
@@ -218,7 +238,7 @@ __device__ __forceinline__ bool grid_sync(const MegaCall &P, unsigned epoch, int
             if (!ok) __hip_atomic_store(P.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
-    __syncthreads();
+    lds_barrier();
     return sm.t->flag != 0;
 }
 
@@ -246,7 +266,7 @@ __device__ void do_embed(const MegaCall &P, const MegaPhase &ph, int wg, int G, 
             } else {
                 x = ld_coh(&P.h[(size_t)r * P.d + e]);
             }
-            store_act_coh(act, (size_t)r * act.ld + e, ph.gain ? x * ph.gain[e] : x);
+            store_act_coh(act, (size_t)r * act.ld + e, ph.gain ? x * ldf_global(ph.gain + e) : x);
             ss += x * x;
         }
         ss = wave_sum(ss);
@@ -281,6 +301,10 @@ __device__ void do_attn_hd(const MegaCall &P, const MegaPhase &ph, int wg, int G
     for (int u = wg; u < units; u += G) {
         const int split = u % P.nsplit, bh = u / P.nsplit;
         const int h = bh % P.H, b = bh / P.H;
+        if (P.nsplit == 1) { // one split: no partials, no merge
+            attn_unit<T, HD, MNW, true, true>(a, 0, h, b, asm_);
+            continue;
+        }
         attn_unit<T, HD, MNW, true>(a, split, h, b, asm_);
         // the split that arrives last merges all splits of (b, h); partials travel through
         // coherent accesses, so completing the stores (release at workgroup scope) is all it takes
@@ -385,10 +409,12 @@ __device__ __forceinline__ void tile_epilogue(const MegaCall &P, const MegaPhase
     if (ph.kind == PH_RESID) {
         if (live && c < P.R) {
             const size_t o = (size_t)c * P.d + n;
-            const float hn = ld_coh(&P.h[o]) + sum;
+            // plain load: these columns of h are only ever written by this workgroup (and, before the
+            // first layer, by the embedding phase, which no cache of this XCD has seen yet)
+            const float hn = P.h[o] + sum;
             st_coh(&P.h[o], hn);
             ActPlanes<T> act{reinterpret_cast<T *>(P.act[ACT_A]), P.act_plane[ACT_A], P.act_ld[ACT_A]};
-            store_act_coh(act, (size_t)c * act.ld + n, ph.gain ? hn * ph.gain[n] : hn); // no gain: nothing normalises these rows
+            store_act_coh(act, (size_t)c * act.ld + n, ph.gain ? hn * ldf_global(ph.gain + n) : hn); // no gain: nothing normalises these rows
             rowsq += hn * hn;
         }
         return;
@@ -450,31 +476,23 @@ __device__ __forceinline__ void mma2(f32x4 &acc0, f32x4 &acc1, u32x4 w, const Ac
     else acc0 = mma(acc0, w, b);
 }
 
-// multiply chunk c (weights in wbuf) into the tile accumulators
-template <typename T>
+// multiply chunk c (weights in wbuf) into the tile accumulators; SLAB: the B operand comes from the LDS
+// slab (loaded by the caller), else straight from memory with coherent loads (too many rows for LDS)
+template <typename T, bool SLAB>
 __device__ __forceinline__ void mma_chunk(const Cursor &c, const MegaCall &P, const MegaPhase &ph, const u32x4 (&wbuf)[2 * CH],
-                                          f32x4 &acc0, f32x4 &acc1, int &slab_tag, MegaSmem &sm, int &ntr) {
+                                          f32x4 &acc0, f32x4 &acc1, MegaSmem &sm) {
     constexpr int E = Traits<T>::E, KB = 4 * E, PL = Traits<T>::PLANES;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, cc = lane & 15, g = lane >> 4;
     if (c.ck == 0) {
         acc0 = f32x4{0.f, 0.f, 0.f, 0.f};
         acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    if (P.slab_rows > 0) {
-        // B operand from the LDS slab of (phase, K slab); reloaded only when that pair changes
-        const int tag = (c.p << 8) | (c.ck / SLAB_CK);
-        if (slab_tag != tag) {
-            __syncthreads(); // every wave is done with the previous slab
-            load_slab<T>(P, ph, c.ck / SLAB_CK, sm);
-            __syncthreads();
-            slab_tag = tag;
-            trace(P, ntr, 100 + ph.kind);
-        }
+    if constexpr (SLAB) {
         const bool blive = cc < P.slab_rows;
         const unsigned char *lb = sm.u + (size_t)cc * SLAB_PITCH + (c.ck % SLAB_CK) * CHUNK_ROW_BYTES + wave * 128 + g * 16;
         const size_t plane_off = (size_t)P.slab_rows * SLAB_PITCH;
 #pragma unroll
-        for (int i = 0; i < CH; ++i)
+        for (int i = 0; i < CH; ++i) {
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 Act<T> av;
@@ -483,8 +501,10 @@ __device__ __forceinline__ void mma_chunk(const Cursor &c, const MegaCall &P, co
                     av.p[pl] = blive ? *reinterpret_cast<const u32x4 *>(lb + pl * plane_off + i * (MNW * 128) + j * 64) : zero16();
                 mma2(acc0, acc1, wbuf[2 * i + j], av, j);
             }
+            // keep the scheduler from hoisting every LDS read of the chunk to the top (register pressure)
+            if (i % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+        }
     } else {
-        // too many rows for the slab: coherent loads straight from memory
         const bool head = ph.kind == PH_HEAD;
         const int brow = head ? P.head_row0 + cc * P.head_stride : cc;
         const bool blive = cc < (head ? P.head_rows : P.R);
@@ -501,27 +521,43 @@ __device__ __forceinline__ void mma_chunk(const Cursor &c, const MegaCall &P, co
             }
         }
     }
-    trace(P, ntr, 4);
 }
 
-// tile complete: fixed-order sum of the waves' partial tiles by waves 0-3 (register v = wave), epilogue
-template <typename T>
-__device__ __forceinline__ void finish_tile(const Cursor &c, const MegaCall &P, const MegaPhase &ph, const f32x4 &acc0,
-                                            const f32x4 &acc1, int &tile_seq, float &rowsq, MegaSmem &sm, int &ntr) {
+// Tile complete: fixed-order sum of the waves' partial tiles by waves 0-3 (register v = wave) into the
+// LDS stash.  No global memory is touched here: the epilogues (and their stores) run at flush time,
+// outside the chunk loop, because on this ISA a pending store would force every later wait on a
+// weight load to vmcnt(0) (loads and stores share the counter and may complete out of order).
+__device__ __forceinline__ void finish_tile(int tile, const f32x4 &acc0, const f32x4 &acc1, int &tile_seq, int &nstash,
+                                            MegaSmem &sm) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int par = tile_seq & 1;
     ++tile_seq;
 #pragma unroll
     for (int v = 0; v < 4; ++v) sm.t->red[par][wave][v][lane] = acc0[v] + acc1[v];
-    __syncthreads();
-    trace(P, ntr, 5);
+    lds_barrier();
     if (wave < 4) {
         float sum = sm.t->red[par][0][wave][lane];
 #pragma unroll
         for (int w2 = 1; w2 < MNW; ++w2) sum += sm.t->red[par][w2][wave][lane];
-        tile_epilogue<T>(P, ph, c.r, c.tile, sum, wave, rowsq, sm);
+        sm.t->stash[nstash][wave][lane] = sum;
+        if (threadIdx.x == 0) sm.t->stash_tile[nstash] = tile;
     }
-    trace(P, ntr, 6);
+    ++nstash;
+}
+
+// epilogues of the stashed tiles, spread over all waves: entry (slot, v) -> wave (slot*4 + v) % MNW
+template <typename T>
+__device__ __forceinline__ void flush_stash(const MegaCall &P, const MegaPhase &ph, const Range &r, int &nstash, float &rowsq,
+                                            MegaSmem &sm) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    lds_barrier(); // the stash writes of the last tile are visible
+    for (int e = wave; e < nstash * 4; e += MNW) {
+        const int slot = e >> 2, v = e & 3;
+        tile_epilogue<T>(P, ph, r, sm.t->stash_tile[slot], sm.t->stash[slot][v][lane], v, rowsq, sm);
+    }
+    nstash = 0;
+    stores_done(); // also makes the next chunk loop start with no store pending
+    lds_barrier(); // nobody overwrites the stash before everyone has read it
 }
 
 // ---------------------------------------------------------------- the kernel
@@ -535,65 +571,67 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
     const int wg = blockIdx.x, G = gridDim.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
-    // Weight pipeline: `la` runs RING chunks ahead of `cc` (the next chunk to multiply); the loads of
+    // Weight pipeline: `la` runs RING positions ahead of `cc` (the next chunk to multiply); the loads of
     // those chunks are in flight into the ring slots r0, r1, r2.  A step multiplies straight out of its
     // slot (which waits for that slot's loads only - later slots stay in flight), then refills the slot
-    // with the chunk RING ahead, which may belong to the next phase: barriers, phase prologues and
-    // epilogues run under weight loads that are already in flight.  Every workgroup's chunk count per
-    // phase is padded to a multiple of RING, so each phase starts at slot r0 and the code below exists
-    // once.  The attention phase needs most of the register file: the look-ahead does not cross it,
-    // and the ring is refilled right after it (before the barrier that follows).
+    // with the chunk RING ahead.  A workgroup's positions per phase are padded to a multiple of RING, so
+    // each phase starts at slot r0 and the code below exists once.  The last round of a phase does not
+    // refill: the ring is empty at a phase boundary and is refilled there with the first round of the
+    // next phase, before the device-wide barrier, so those loads fly during the barrier.
     struct State {
         Cursor cc, la;
         f32x4 acc0, acc1;
         int tile_seq, slab_tag;
         float rowsq;
     } st;
-    st.cc.p = 0;
-    cursor_seek<T>(st.cc, P, wg, G);
-    st.la = st.cc;
     st.acc0 = f32x4{0.f, 0.f, 0.f, 0.f};
     st.acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
     st.tile_seq = 0;
     st.slab_tag = -1;
     st.rowsq = 0.f;
-    int ntr = 0;
-
-    auto next_attn = [&](int from) {
-        int q = from;
-        while (q < P.n_phases && P.phases[q].kind != PH_ATTN) ++q;
-        return q;
-    };
-    int la_limit = next_attn(0);
 
     u32x4 r0[2 * CH], r1[2 * CH], r2[2 * CH];
     static_assert(RING == 3, "the loops below are written for three ring slots");
     static_assert(MNW >= 4, "waves 0-3 reduce one accumulator register each");
 
-    auto fill = [&](u32x4(&slot)[2 * CH]) {
-        if (st.la.p < la_limit) {
-            issue_chunk(st.la, slot);
-            cursor_next<T>(st.la, P, wg, G);
-        }
+    const char *zeros = reinterpret_cast<const char *>(P.zeros);
+    // The empty asm statements are compiler barriers: they pin the slot's loads to this point of the
+    // program.  Without them the scheduler sinks each load next to its use (to shorten live ranges),
+    // which would leave one 16-byte load in flight per wave instead of a ring of chunks.
+    auto fill = [&](u32x4(&slot)[2 * CH]) { // always 2*CH loads
+        asm volatile("" ::: "memory");
+        issue_chunk(st.la, true, zeros, slot);
+        asm volatile("" ::: "memory");
+        if (st.la.active) cursor_next<T>(st.la, P.hd);
     };
-    fill(r0);
-    fill(r1);
-    fill(r2);
 
     for (int p = 0; p < P.n_phases; ++p) {
         const MegaPhase ph = P.phases[p];
-        if (p > 0 && !grid_sync(P, P.epoch_base + (unsigned)p, G, sm)) return;
-        if (P.timeline && wg == 0 && threadIdx.x == 0) P.timeline[3 * p] = wall_clock64();
+        // Phase boundary: all three slots are filled unconditionally (loads of zeros when this
+        // workgroup has no share of the phase), which also tells the compiler that the slots hold
+        // nothing across a phase that does not use them.  The fills come after the wave's stores are
+        // acknowledged, so the wait for the stores does not drain them.
+        cursor_begin<T>(st.cc, ph, P.hd, wg, G);
+        st.la = st.cc;
+        if (p > 0) stores_done();
+        if (wave != 0) { // wave 0 polls memory in the barrier, which would wait for these loads
+            fill(r0);
+            fill(r1);
+            fill(r2);
+        }
+        if (p > 0 && !grid_arrive_wait(P, P.epoch_base + (unsigned)p, G, sm)) return;
+        if (wave == 0) {
+            fill(r0);
+            fill(r1);
+            fill(r2);
+        }
+        if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(3 * p) * G + wg] = wall_clock64();
         st.rowsq = 0.f;
         switch (ph.kind) {
         case PH_EMBED: do_embed<T>(P, ph, wg, G, sm); break;
         case PH_ATTN:
             do_attn<T>(P, ph, wg, G, sm);
             st.slab_tag = -1; // the attention area aliases the slab
-            la_limit = next_attn(p + 1);
-            fill(r0); // the ring was empty: start the weights of the phases after attention
-            fill(r1);
-            fill(r2);
             break;
         case PH_LEN:
             if (wg == 0 && (int)threadIdx.x < P.B) P.len[threadIdx.x] += P.M;
@@ -603,35 +641,76 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
         case PH_HEAD: compute_scales(P, G, sm); break; // read after a later __syncthreads
         default: break;
         }
-        if (P.timeline && wg == 0 && threadIdx.x == 0) P.timeline[3 * p + 1] = wall_clock64();
-        trace(P, ntr, 200 + ph.kind);
+        if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(3 * p + 1) * G + wg] = wall_clock64();
 
-        auto step = [&](u32x4(&slot)[2 * CH]) {
-            const Cursor c = st.cc;
-            cursor_next<T>(st.cc, P, wg, G);
-            if (!c.dummy) mma_chunk<T>(c, P, ph, slot, st.acc0, st.acc1, st.slab_tag, sm, ntr);
-            fill(slot);
-            trace(P, ntr, 3);
-            if (!c.dummy && c.ck + 1 == c.nck) finish_tile<T>(c, P, ph, st.acc0, st.acc1, st.tile_seq, st.rowsq, sm, ntr);
+        int nstash = 0;
+        const Range my = st.cc.r; // this workgroup's share of the phase
+        // One segment: n_fill rounds of RING steps in which each step refills its slot, then (last: the
+        // phase ends here) one round that does not.  The loops hold no global memory operation except
+        // the pinned ring loads, and nothing else is pending when they start (the wait below costs
+        // little: the ring loads it waits for are the ones the first steps need anyway); both are what
+        // lets the compiler wait for one slot with an exact count and leave the younger slots in flight.
+        auto run_segment = [&](auto slab_c, int n_fill, bool last) {
+            constexpr bool SLAB = decltype(slab_c)::value;
+            auto step = [&](auto fill_c, u32x4(&slot)[2 * CH]) {
+                const Cursor c = st.cc;
+                cursor_next<T>(st.cc, P.hd);
+                if (!c.dummy) mma_chunk<T, SLAB>(c, P, ph, slot, st.acc0, st.acc1, sm);
+                if (decltype(fill_c)::value) fill(slot);
+                if (!c.dummy && c.ck + 1 == c.nck) finish_tile(c.tile, st.acc0, st.acc1, st.tile_seq, nstash, sm);
+            };
+            stores_done();
+            for (int i = 0; i < n_fill; ++i) {
+                step(std::true_type{}, r0);
+                step(std::true_type{}, r1);
+                step(std::true_type{}, r2);
+            }
+            if (last) {
+                step(std::false_type{}, r0);
+                step(std::false_type{}, r1);
+                step(std::false_type{}, r2);
+            }
         };
-        while (st.cc.p == p) { // RING chunks (padding included) per round
-            step(r0);
-            step(r1);
-            step(r2);
+        while (st.cc.active) {
+            // one segment = rounds that share an LDS slab and fit the stash
+            const Cursor &cc = st.cc;
+            const bool multi = cc.nck > SLAB_CK;
+            const int grp_end = min((cc.ck / SLAB_CK + 1) * SLAB_CK, cc.nck); // multi: end of the slab group
+            const int grp_chunks = multi ? grp_end - cc.ck : (cc.r.ntiles - cc.tile) * cc.nck - cc.ck;
+            const int grp_rounds = (grp_chunks + RING - 1) / RING;
+            const bool last_group = multi ? (cc.tile + 1 == cc.r.ntiles && grp_end == cc.nck) : true;
+            const int tiles_per_round = multi ? 1 : RING / cc.nck + 1;
+            const int n = min(grp_rounds, max(1, (STASH_TILES - nstash) / tiles_per_round));
+            const bool final_round = last_group && n == grp_rounds; // the phase ends with this segment
+            if (P.slab_rows > 0) {
+                const int tag = (p << 8) | (cc.ck / SLAB_CK);
+                if (st.slab_tag != tag) {
+                    lds_barrier(); // every wave is done with the previous slab
+                    load_slab<T>(P, ph, cc.ck / SLAB_CK, sm);
+                    lds_barrier();
+                    st.slab_tag = tag;
+                }
+                run_segment(std::true_type{}, final_round ? n - 1 : n, final_round);
+            } else {
+                run_segment(std::false_type{}, final_round ? n - 1 : n, final_round);
+            }
+            if (final_round || nstash + tiles_per_round > STASH_TILES) flush_stash<T>(P, ph, my, nstash, st.rowsq, sm);
         }
-
         if (ph.kind == PH_RESID) {
             // publish this workgroup's partial sums of squares of the new hidden rows
             float rs = st.rowsq;
             rs += __shfl_xor(rs, 16);
             rs += __shfl_xor(rs, 32);
-            if (wave < 4 && lane < 16) sm.t->sq[wave][lane] = rs;
-            __syncthreads();
-            if (threadIdx.x < 16)
-                st_coh(&P.nsq[(size_t)threadIdx.x * G + wg],
-                       (sm.t->sq[0][threadIdx.x] + sm.t->sq[1][threadIdx.x]) + (sm.t->sq[2][threadIdx.x] + sm.t->sq[3][threadIdx.x]));
+            if (lane < 16) sm.t->sq[wave][lane] = rs;
+            lds_barrier();
+            if (threadIdx.x < 16) {
+                float tot = 0.f;
+#pragma unroll
+                for (int w2 = 0; w2 < MNW; ++w2) tot += sm.t->sq[w2][threadIdx.x];
+                st_coh(&P.nsq[(size_t)threadIdx.x * G + wg], tot);
+            }
         }
-        if (P.timeline && wg == 0 && threadIdx.x == 0) P.timeline[3 * p + 2] = wall_clock64();
+        if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(3 * p + 2) * G + wg] = wall_clock64();
     }
 }
 

@@ -58,6 +58,17 @@ __device__ __forceinline__ u32x4 ld16(const void *p) { return *reinterpret_cast<
 __device__ __forceinline__ u32x4 ld16_stream(const void *p) {
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
 }
+// 16-byte load through a pointer that is known to be global memory although the compiler cannot see
+// it (pointers read from a descriptor in memory are generic): keeps it a global_load, not a flat_load,
+// which matters for wait counting (flat loads can return out of order and force vmcnt(0))
+__device__ __forceinline__ u32x4 ld16_global(const void *p) {
+    typedef const u32x4 __attribute__((address_space(1))) * gptr;
+    return *(gptr)(p);
+}
+__device__ __forceinline__ float ldf_global(const float *p) {
+    typedef const float __attribute__((address_space(1))) * gptr;
+    return *(gptr)(p);
+}
 __device__ __forceinline__ u32x4 zero16() { return u32x4{0u, 0u, 0u, 0u}; }
 
 // The activation (B) operand of one k-block.

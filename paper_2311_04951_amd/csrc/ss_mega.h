@@ -63,11 +63,12 @@ struct MegaCall {
     unsigned epoch_base;
     unsigned spin_limit;
     int32_t *status;
+    const void *zeros; // >= 64 zero bytes: the target of weight loads that have no data to fetch
     int slab_rows, u_bytes;       // set by launch_mega: rows held in the LDS slab (0: none), size of the slab area
-    unsigned long long *timeline; // optional [3*n_phases] device clock samples of workgroup 0 (NULL: off)
+    unsigned long long *timeline; // optional [3*n_phases][G] device clock samples of every workgroup (NULL: off)
 };
 
-constexpr int MEGA_THREADS = 512;
+constexpr int MEGA_THREADS = 256;
 
 // number of workgroups a launch may use (all resident at once), and the launch itself
 int mega_grid(int dtype, int device);
