@@ -106,7 +106,7 @@ def main():
     ap.add_argument("--K", type=int, default=4)
     ap.add_argument("--layers", type=int, default=32, help="decoder layers (32 = the named workload)")
     ap.add_argument("--gen-tokens", type=int, default=256)
-    ap.add_argument("--persistent", type=int, default=0,
+    ap.add_argument("--persistent", type=int, default=1,
                     help="1: run the forward as the persistent single-launch kernel, 0: one launch per phase")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-e2e", action="store_true")
@@ -235,7 +235,11 @@ def main():
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(si, torch, shape, packed, io, prompt_len, M)
-    print(json.dumps(out))
+    print(json.dumps(out), flush=True)
+    # release the device objects while the HIP runtime is still up (not at interpreter teardown)
+    torch.cuda.synchronize()
+    for obj in (tkv, dkv, target, draft):
+        obj.close()
 
 
 if __name__ == "__main__":

@@ -86,7 +86,7 @@ int ss_device_status(ss_model *model, ss_stream stream, int32_t *status_host);
  * the elapsed times up per kernel class and clears the record.  Classes (n_classes >= 9):
  * 0 RMSNorm, 1 QKV GEMM (+rotary, +cache append), 2 attention (+merge), 3 O-projection GEMM,
  * 4 gate/up GEMM (+SwiGLU), 5 down-projection GEMM, 6 LM-head GEMM, 7 other, 8 the persistent
- * verify kernel (the whole forward of a call with at most 16 rows is one launch of it).
+ * verify kernel (the whole forward of a small call is one launch of it, see ss_model_set_persistent).
  * total_ms_host / launches_host: host arrays [n_classes].  Event recording perturbs the pass a
  * little, so timed throughput runs keep it off. */
 int ss_profile_enable(ss_model *model, int32_t on);
@@ -100,12 +100,14 @@ int ss_profile_read(ss_model *model, int32_t n_classes, double *total_ms_host, i
 int ss_model_create(const ss_model_cfg *cfg, const ss_weights *weights, ss_model **out);
 int ss_model_destroy(ss_model *model);
 
-/* Selects how the forward path of `model` is launched.  0 (default): one kernel per phase (RMSNorm,
- * QKV GEMM, attention, O projection, gate/up GEMM, down projection ...).  1: calls with at most 16
- * rows run as ONE persistent cooperative kernel (one workgroup per compute unit, device-wide
- * barriers between phases, weight loads of the next phase in flight across the barrier); larger
- * calls keep the per-phase launches.  Both paths produce results within the same tolerance of the
- * method; SS_EINVAL if the persistent kernel cannot be co-resident on this device. */
+/* Selects how the forward path of `model` is launched.  1 (default wherever the kernel can be
+ * co-resident on the device): calls whose rows (batch * M) fit the kernel's LDS activation slab (8
+ * rows for bf16 models, 16 for fp32) run as ONE persistent cooperative kernel
+ * (one workgroup per compute unit, device-wide barriers between phases, RMSNorm folded into the
+ * GEMMs, weight loads of the next phase in flight across each barrier); larger calls always use one
+ * kernel per phase.  0: one kernel per phase (RMSNorm, QKV GEMM, attention, O projection, gate/up
+ * GEMM, down projection ...) for every call.  Both paths produce results within the same tolerance
+ * of the method; SS_EINVAL if `on` is set and the persistent kernel is not available on this device. */
 int ss_model_set_persistent(ss_model *model, int32_t on);
 
 /* ---- KV cache (Sections 2, 4.2, 4.4) --------------------------------------------------------

@@ -63,6 +63,7 @@ struct ss_model {
     std::vector<void *> owned;
     // persistent verify kernel: phase programs (device), barrier state, norm partials
     int mega_G = 0;                 // workgroups per launch (0: persistent path unavailable)
+    int mega_rows = 0;              // most rows (batch * M) a persistent launch takes
     MegaPhase *prog_full = nullptr; // [embed, layers, head, len]
     MegaPhase *prog_nohead = nullptr; // [embed, layers, len]
     int n_full = 0, n_nohead = 0;
@@ -70,7 +71,7 @@ struct ss_model {
     unsigned *arrive = nullptr, *abort_flag = nullptr, *attn_cnt = nullptr;
     void *zeros = nullptr;
     unsigned epoch = 1;
-    bool persistent = false; // forward path: false = one launch per phase, true = the persistent kernel
+    bool persistent = false; // forward path: false = one launch per phase, true = the persistent kernel (default where available)
     // optional per-kernel-class timing (ss_profile_*): event pairs recorded around launches
     bool prof = false;
     std::vector<hipEvent_t> ev;
@@ -185,6 +186,7 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
         int dev = 0;
         (void)hipGetDevice(&dev);
         m->mega_G = mega_grid(c.dtype, dev);
+        m->mega_rows = mega_max_rows(c.dtype);
         if (m->mega_G > 0 && c.n_layers >= 0) {
             std::vector<MegaPhase> prog;
             auto gain_after = [&](int l) { return l + 1 < c.n_layers ? m->layers[l + 1].g1 : m->gf; };
@@ -203,14 +205,11 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
             MegaPhase ln{}; ln.kind = PH_LEN;
             std::vector<MegaPhase> nohead = prog;
             nohead.push_back(ln);
-            const bool gains_ok = true; // a missing final gain only leaves the last packed rows unscaled (unused)
             if (m->lm_head && m->gf) {
                 MegaPhase hd{}; hd.kind = PH_HEAD; hd.W = m->lm_head; hd.N = c.vocab; hd.K = c.d_model; hd.act_src = ACT_A; prog.push_back(hd);
             }
             prog.push_back(ln);
-            if (!gains_ok) {
-                m->mega_G = 0; // a model without a final gain cannot fold the norm into the next GEMM
-            } else {
+            {
                 m->n_full = (int)prog.size();
                 m->n_nohead = (int)nohead.size();
                 A((void **)&m->prog_full, sizeof(MegaPhase) * prog.size(), false);
@@ -249,6 +248,7 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
             return fail(SS_EHIP, "rope table upload: %s", hipGetErrorString(e));
         }
     }
+    m->persistent = m->mega_G > 0; // calls of at most 16 rows use the persistent kernel unless told otherwise
     *out = m;
     return SS_OK;
 }
@@ -508,7 +508,7 @@ static void run_head(ss_model *m, int nrows, int row0, int stride, float *logits
     launch_gemm(c.dtype, EPI_STORE, g, st);
 }
 
-static bool use_persistent(const ss_model *m, int R) { return m->persistent && m->mega_G > 0 && R <= 16; }
+static bool use_persistent(const ss_model *m, int R) { return m->persistent && m->mega_G > 0 && R <= m->mega_rows; }
 
 extern "C" int ss_model_set_persistent(ss_model *m, int32_t on) {
     if (!m) return fail(SS_EINVAL, "ss_model_set_persistent: NULL model");
@@ -560,11 +560,12 @@ static int run_persistent(ss_model *m, ss_kv_cache *kv, const int32_t *tokens, f
     static const bool want_timeline = getenv("SS_TIMELINE") != nullptr;
     static unsigned long long *tl_dev = nullptr;
     static size_t tl_cap = 0;
-    const size_t tl_need = (size_t)3 * P.n_phases * m->mega_G;
+    const size_t tl_need = (size_t)5 * P.n_phases * m->mega_G;
     if (want_timeline) {
         if (tl_cap < tl_need) {
             if (tl_dev) HIP_TRY(hipFree(tl_dev));
             HIP_TRY(hipMalloc((void **)&tl_dev, sizeof(unsigned long long) * tl_need));
+            HIP_TRY(hipMemset(tl_dev, 0, sizeof(unsigned long long) * tl_need));
             tl_cap = tl_need;
         }
         P.timeline = tl_dev;
@@ -582,30 +583,51 @@ static int run_persistent(ss_model *m, ss_kv_cache *kv, const int32_t *tokens, f
         HIP_TRY(hipStreamSynchronize(st));
         HIP_TRY(hipMemcpy(t.data(), tl_dev, t.size() * 8, hipMemcpyDeviceToHost));
         HIP_TRY(hipMemcpy(ph.data(), P.phases, ph.size() * sizeof(MegaPhase), hipMemcpyDeviceToHost));
-        auto at = [&](int p, int k, int wg) { return (double)t[((size_t)3 * p + k) * G + wg] * 0.01; }; // 100 MHz clock
-        double pre[8] = {0}, wmed[8] = {0}, wmax[8] = {0}, wall[8] = {0}, sync[8] = {0}, skew[8] = {0};
+        auto at = [&](int p, int k, int wg) { return (double)t[((size_t)5 * p + k) * G + wg] * 0.01; }; // 100 MHz clock
+        // per phase kind, averaged over its occurrences: medians over workgroups of the time from the
+        // phase's start to (prologue done, first slab in LDS, last round done, end), the slowest
+        // workgroup's end, and the time from the last end to the first start of the next phase
+        double acc[8][7] = {{0}};
         int cnt[8] = {0};
         std::vector<double> w(G);
+        auto median_of = [&](int p, int k) {
+            int n = 0;
+            for (int g = 0; g < G; ++g)
+                if (t[((size_t)5 * p + k) * G + g]) w[n++] = at(p, k, g) - at(p, 0, g);
+            if (!n) return 0.0;
+            std::sort(w.begin(), w.begin() + n);
+            return w[n / 2];
+        };
         for (int p = 0; p < NP; ++p) {
             const int slot = (ph[p].kind == PH_RESID && ph[p].K == c.d_ff) ? 7 : ph[p].kind;
-            double s0 = 1e300, s1 = 0, e1 = 0, n0 = 1e300, pr = 0;
+            double s0 = 1e300, s1 = 0, e1 = 0, n0 = 1e300;
             for (int g = 0; g < G; ++g) {
-                s0 = std::min(s0, at(p, 0, g)); s1 = std::max(s1, at(p, 0, g)); e1 = std::max(e1, at(p, 2, g));
+                s0 = std::min(s0, at(p, 0, g)); s1 = std::max(s1, at(p, 0, g)); e1 = std::max(e1, at(p, 4, g));
                 if (p + 1 < NP) n0 = std::min(n0, at(p + 1, 0, g));
-                w[g] = at(p, 2, g) - at(p, 0, g);
-                pr += at(p, 1, g) - at(p, 0, g);
             }
-            std::sort(w.begin(), w.end());
-            pre[slot] += pr / G; wmed[slot] += w[G / 2]; wmax[slot] += w[G - 1]; wall[slot] += e1 - s0; skew[slot] += s1 - s0;
-            if (p + 1 < NP) sync[slot] += n0 - e1;
+            acc[slot][0] += s1 - s0;
+            for (int k = 1; k <= 4; ++k) acc[slot][k] += median_of(p, k);
+            acc[slot][5] += e1 - s0;
+            if (p + 1 < NP) acc[slot][6] += n0 - e1;
             cnt[slot]++;
         }
+        if (getenv("SS_TIMELINE_WG")) { // rounds_done time of every workgroup in the first SwiGLU phase, 8 per line (XCD = column)
+            for (int p = 0; p < NP; ++p)
+                if (ph[p].kind == PH_SWIGLU) {
+                    for (int g = 0; g < G; ++g) fprintf(stderr, "%6.1f%s", at(p, 3, g) - at(p, 0, g), g % 8 == 7 ? "\n" : " ");
+                    fprintf(stderr, "epilogue (end - rounds_done):\n");
+                    for (int g = 0; g < G; ++g) fprintf(stderr, "%6.1f%s", at(p, 4, g) - at(p, 3, g), g % 8 == 7 ? "\n" : " ");
+                    break;
+                }
+        }
+        HIP_TRY(hipMemset(tl_dev, 0, sizeof(unsigned long long) * tl_need));
         const char *names[8] = {"embed", "qkv", "attn", "oproj", "gateup", "head", "len", "down"};
-        fprintf(stderr, "[timeline] total %.1f us\n", at(NP - 1, 2, 0) - at(0, 0, 0));
+        fprintf(stderr, "[timeline] total %.1f us\n", at(NP - 1, 4, 0) - at(0, 0, 0));
         for (int k = 0; k < 8; ++k)
             if (cnt[k])
-                fprintf(stderr, "  %-7s n=%d start_skew=%.1f prologue=%.1f busy_median=%.1f busy_max=%.1f first_start_to_last_end=%.1f sync_after=%.1f\n",
-                        names[k], cnt[k], skew[k] / cnt[k], pre[k] / cnt[k], wmed[k] / cnt[k], wmax[k] / cnt[k], wall[k] / cnt[k], sync[k] / cnt[k]);
+                fprintf(stderr, "  %-7s n=%d start_skew=%.1f | median: prologue=%.1f slab=%.1f rounds_done=%.1f end=%.1f | last_end=%.1f sync_after=%.1f\n",
+                        names[k], cnt[k], acc[k][0] / cnt[k], acc[k][1] / cnt[k], acc[k][2] / cnt[k], acc[k][3] / cnt[k], acc[k][4] / cnt[k],
+                        acc[k][5] / cnt[k], acc[k][6] / cnt[k]);
     }
     return SS_OK;
 }

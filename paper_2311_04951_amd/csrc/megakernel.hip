@@ -38,7 +38,7 @@ namespace ss {
 constexpr int MNW = MEGA_THREADS / 64; // wavefronts per workgroup
 constexpr int CH = 4;                  // 128-byte steps per chunk per wave (8 loads = 8 KB per wave)
 constexpr int SLAB_CK = 8192 / (CH * MNW * 128); // chunks per LDS activation slab (8 KB of K per row)
-constexpr int RING = 3;                // chunks in flight per wave
+constexpr int RING = 2;                // chunks in flight per wave
 constexpr int CHUNK_ROW_BYTES = CH * MNW * 128; // bytes of a weight row one chunk covers (all waves)
 
 struct Range {
@@ -209,16 +209,19 @@ struct MegaSmem {
 // Device-wide barrier without cache maintenance, in two parts so that weight loads can be put in
 // flight between them.  (1) stores_done(): every wave waits until its own stores are acknowledged
 // (vmcnt(0): on this ISA loads and stores share the counter, so this also drains the wave's loads).
-// (2) grid_arrive_wait(): workgroup barrier, wave 0 publishes the epoch and polls all slots, workgroup
-// barrier.  Waves other than wave 0 touch no memory in (2), so loads they issued after (1) stay in
-// flight across the whole device-wide barrier.  false = aborted (bounded spin ran out, or another
+// (2) grid_arrive(): workgroup barrier, then the epoch is published.  (3) grid_wait(): wave 0 polls all
+// slots, workgroup barrier.  Waves other than wave 0 touch no memory in (3), so loads they issue
+// between (2) and (3) stay in flight across the whole device-wide barrier.  false = aborted (bounded spin ran out, or another
 // workgroup aborted).
 __device__ __forceinline__ void stores_done() { __builtin_amdgcn_s_waitcnt(0x0F70); } // vmcnt(0)
 
-__device__ __forceinline__ bool grid_arrive_wait(const MegaCall &P, unsigned epoch, int G, MegaSmem &sm) {
+__device__ __forceinline__ void grid_arrive(const MegaCall &P, unsigned epoch, MegaSmem &sm) {
     lds_barrier(); // every wave of the workgroup has passed stores_done()
+    if (threadIdx.x == 0) __hip_atomic_store(&P.arrive[blockIdx.x], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ bool grid_wait(const MegaCall &P, unsigned epoch, int G, MegaSmem &sm) {
     if (threadIdx.x < 64) {
-        if (threadIdx.x == 0) __hip_atomic_store(&P.arrive[blockIdx.x], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         bool ok = true;
         unsigned spins = 0;
         for (;;) {
@@ -245,7 +248,7 @@ __device__ __forceinline__ bool grid_arrive_wait(const MegaCall &P, unsigned epo
 // ---------------------------------------------------------------- non-GEMM phases
 
 template <typename T>
-__device__ void do_embed(const MegaCall &P, const MegaPhase &ph, int wg, int G, MegaSmem &sm) {
+__device__ __forceinline__ void do_embed(const MegaCall &P, const MegaPhase &ph, int wg, int G, MegaSmem &sm) {
     ActPlanes<T> act{reinterpret_cast<T *>(P.act[ACT_A]), P.act_plane[ACT_A], P.act_ld[ACT_A]};
     for (int r = wg; r < P.R; r += G) {
         const T *src = nullptr;
@@ -281,7 +284,7 @@ __device__ void do_embed(const MegaCall &P, const MegaPhase &ph, int wg, int G, 
 }
 
 template <typename T, int HD>
-__device__ void do_attn_hd(const MegaCall &P, const MegaPhase &ph, int wg, int G, MegaSmem &sm) {
+__device__ __forceinline__ void do_attn_hd(const MegaCall &P, const MegaPhase &ph, int wg, int G, MegaSmem &sm) {
     AttnArgs a;
     a.q = P.act[ACT_Q];
     a.q_plane = P.act_plane[ACT_Q];
@@ -331,70 +334,101 @@ __device__ void do_attn_hd(const MegaCall &P, const MegaPhase &ph, int wg, int G
 }
 
 template <typename T>
-__device__ void do_attn(const MegaCall &P, const MegaPhase &ph, int wg, int G, MegaSmem &sm) {
+__device__ __forceinline__ void do_attn(const MegaCall &P, const MegaPhase &ph, int wg, int G, MegaSmem &sm) {
     if (P.hd == 128) do_attn_hd<T, 128>(P, ph, wg, G, sm);
     else if (P.hd == 64) do_attn_hd<T, 64>(P, ph, wg, G, sm);
     else do_attn_hd<T, 32>(P, ph, wg, G, sm);
 }
 
-// row scales 1/sqrt(mean(h^2) + eps) from the producers' partial sums: 32 threads per row, one round trip
-__device__ __forceinline__ void compute_scales(const MegaCall &P, int G, MegaSmem &sm) {
-    const int j = threadIdx.x & 31;
-    for (int row = threadIdx.x >> 5; row < 16; row += MEGA_THREADS / 32) {
-    float s = 0.f;
-    for (int i0 = 0; i0 < G; i0 += 256) { // 8 independent loads per round
-        float t[8];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const int i = i0 + j + 32 * q;
-            t[q] = i < G ? ld_coh(&P.nsq[(size_t)row * G + i]) : 0.f;
-        }
-#pragma unroll
-        for (int q = 0; q < 8; ++q) s += t[q];
-    }
-#pragma unroll
-    for (int o = 16; o > 0; o >>= 1) s += __shfl_xor(s, o);
-    if (j == 0) sm.t->scale[row] = 1.0f / sqrtf(s / (float)P.d + P.eps);
-    }
+// The activation planes a phase reads.  Written with constant indices on purpose: a run-time index
+// into an array of the by-value kernel argument makes the compiler keep a copy of it in scratch memory.
+template <typename T> __device__ __forceinline__ ActPlanes<T> act_planes(const MegaCall &P, int i) {
+    void *b = i == ACT_A ? P.act[ACT_A] : i == ACT_Q ? P.act[ACT_Q] : i == ACT_O ? P.act[ACT_O] : P.act[ACT_Z];
+    const size_t pl = i == ACT_A ? P.act_plane[ACT_A] : i == ACT_Q ? P.act_plane[ACT_Q] : i == ACT_O ? P.act_plane[ACT_O] : P.act_plane[ACT_Z];
+    const int ld = i == ACT_A ? P.act_ld[ACT_A] : i == ACT_Q ? P.act_ld[ACT_Q] : i == ACT_O ? P.act_ld[ACT_O] : P.act_ld[ACT_Z];
+    return ActPlanes<T>{reinterpret_cast<T *>(b), pl, ld};
 }
 
-// copy the hidden rows of K slab `ck` of the phase's B operand into LDS (zero beyond K)
-template <typename T>
-__device__ __forceinline__ void load_slab(const MegaCall &P, const MegaPhase &ph, int slab, MegaSmem &sm) {
+// Row scales 1/sqrt(mean(h^2) + eps) from the producers' partial sums, in two halves so that the loads
+// can share a memory round trip with other loads: 32 threads per row, rows beyond P.R are not needed.
+struct ScaleLoads {
+    float t[2][8];
+};
+__device__ __forceinline__ void scales_issue(const MegaCall &P, int G, ScaleLoads &sl) {
+    const int j = threadIdx.x & 31;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const int row = (threadIdx.x >> 5) + half * (MEGA_THREADS / 32);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int i = j + 32 * q;
+            sl.t[half][q] = (row < P.R && i < G) ? ld_coh(&P.nsq[(size_t)row * G + i]) : 0.f;
+        }
+    }
+}
+__device__ __forceinline__ void scales_finish(const MegaCall &P, int G, const ScaleLoads &sl, MegaSmem &sm) {
+    const int j = threadIdx.x & 31;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const int row = (threadIdx.x >> 5) + half * (MEGA_THREADS / 32);
+        float s = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) s += sl.t[half][q];
+        for (int i = 256 + j; i < G; i += 32) s += ld_coh(&P.nsq[(size_t)row * G + i]); // grids beyond 256 workgroups
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) s += __shfl_xor(s, o);
+        if (j == 0 && row < 16) sm.t->scale[row] = row < P.R ? 1.0f / sqrtf(s / (float)P.d + P.eps) : 0.f;
+    }
+}
+static_assert(MEGA_THREADS / 32 * 2 >= 16, "two halves of the scale loads cover 16 rows");
+
+// Copy the hidden rows of K slab `slab` of the phase's B operand into LDS (zero beyond K), in two steps:
+// slab_issue() puts every load in flight (with_scales: also the loads of the phase's row scales), so the
+// whole copy costs one memory round trip, and slab_finish() writes the data to LDS.  Other loads may
+// be issued between the two: loads return in order, so the slab does not wait for them.
+constexpr int SLAB_UNITS = SLAB_ROW_BYTES / 8 / MEGA_THREADS; // 8-byte units per thread and slab row
+template <int NPR> struct SlabLoads { // NPR: upper bound of the (plane, row) pairs in the slab
+    unsigned long long v[NPR][SLAB_UNITS]; // [(plane, row) pair][unit]
+    ScaleLoads sl;
+};
+template <typename T, int NPR>
+__device__ __forceinline__ void slab_issue(const MegaCall &P, const MegaPhase &ph, int slab, int G, bool with_scales, SlabLoads<NPR> &L) {
     constexpr int PL = Traits<T>::PLANES;
     constexpr int PER8 = 8 / (int)sizeof(T); // elements per 8-byte unit
     const bool head = ph.kind == PH_HEAD;
     const int rows = P.slab_rows;
     const int nlive = head ? P.head_rows : P.R;
-    const T *base = reinterpret_cast<const T *>(P.act[ph.act_src]);
-    const size_t plane = P.act_plane[ph.act_src];
-    const int ld = P.act_ld[ph.act_src];
-    // a row of the slab is 1024 8-byte units = ROUNDS rounds of the workgroup's threads; all loads of a batch
-    // of rows are issued before the first LDS store so that they overlap (one memory round trip)
-    constexpr int BATCH = 2, ROUNDS = SLAB_ROW_BYTES / 8 / MEGA_THREADS;
-    const int nrow = PL * rows; // (plane, row) pairs
-    for (int pr0 = 0; pr0 < nrow; pr0 += BATCH) {
-        unsigned long long v[BATCH][ROUNDS];
+    const ActPlanes<T> src_planes = act_planes<T>(P, ph.act_src);
+    const int nrow = PL * rows; // (plane, row) pairs, at most NPR
+    if (with_scales) scales_issue(P, G, L.sl);
 #pragma unroll
-        for (int b = 0; b < BATCH; ++b) {
-            const int pr = pr0 + b, r = pr % rows, pl = pr / rows;
+    for (int pr = 0; pr < NPR; ++pr) {
+        if (pr < nrow) {
+            const int r = pr % rows, pl = pr / rows;
             const int brow = head ? P.head_row0 + r * P.head_stride : r;
-            const T *src = base + pl * plane + (size_t)brow * ld;
+            const T *src = src_planes.base + pl * src_planes.plane + (size_t)brow * src_planes.ld;
 #pragma unroll
-            for (int h2 = 0; h2 < ROUNDS; ++h2) {
+            for (int h2 = 0; h2 < SLAB_UNITS; ++h2) {
                 const int x = threadIdx.x + h2 * MEGA_THREADS;
                 const int k = slab * (SLAB_ROW_BYTES / (int)sizeof(T)) + x * PER8;
-                v[b][h2] = (pr < nrow && r < nlive && k < ph.K) ? ld_coh64(src + k) : 0ull;
+                L.v[pr][h2] = (r < nlive && k < ph.K) ? ld_coh64(src + k) : 0ull;
             }
         }
-#pragma unroll
-        for (int b = 0; b < BATCH; ++b)
-#pragma unroll
-            for (int h2 = 0; h2 < ROUNDS; ++h2) {
-                const int pr = pr0 + b, x = threadIdx.x + h2 * MEGA_THREADS;
-                if (pr < nrow) *reinterpret_cast<unsigned long long *>(sm.u + (size_t)pr * SLAB_PITCH + x * 8) = v[b][h2];
-            }
     }
+}
+template <typename T, int NPR>
+__device__ __forceinline__ void slab_finish(const MegaCall &P, int G, bool with_scales, const SlabLoads<NPR> &L, MegaSmem &sm) {
+    const int nrow = Traits<T>::PLANES * P.slab_rows;
+    if (with_scales) scales_finish(P, G, L.sl, sm);
+#pragma unroll
+    for (int pr = 0; pr < NPR; ++pr)
+        if (pr < nrow) {
+#pragma unroll
+            for (int h2 = 0; h2 < SLAB_UNITS; ++h2) {
+                const int x = threadIdx.x + h2 * MEGA_THREADS;
+                *reinterpret_cast<unsigned long long *>(sm.u + (size_t)pr * SLAB_PITCH + x * 8) = L.v[pr][h2];
+            }
+        }
 }
 
 // ---------------------------------------------------------------- GEMM chunk + tile epilogue
@@ -476,51 +510,29 @@ __device__ __forceinline__ void mma2(f32x4 &acc0, f32x4 &acc1, u32x4 w, const Ac
     else acc0 = mma(acc0, w, b);
 }
 
-// multiply chunk c (weights in wbuf) into the tile accumulators; SLAB: the B operand comes from the LDS
-// slab (loaded by the caller), else straight from memory with coherent loads (too many rows for LDS)
-template <typename T, bool SLAB>
-__device__ __forceinline__ void mma_chunk(const Cursor &c, const MegaCall &P, const MegaPhase &ph, const u32x4 (&wbuf)[2 * CH],
-                                          f32x4 &acc0, f32x4 &acc1, MegaSmem &sm) {
-    constexpr int E = Traits<T>::E, KB = 4 * E, PL = Traits<T>::PLANES;
+// multiply chunk c (weights in wbuf) into the tile accumulators; the B operand comes from the LDS slab
+template <typename T>
+__device__ __forceinline__ void mma_chunk(const Cursor &c, const MegaCall &P, const u32x4 (&wbuf)[2 * CH], f32x4 &acc0, f32x4 &acc1,
+                                          MegaSmem &sm) {
+    constexpr int PL = Traits<T>::PLANES;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, cc = lane & 15, g = lane >> 4;
     if (c.ck == 0) {
         acc0 = f32x4{0.f, 0.f, 0.f, 0.f};
         acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    if constexpr (SLAB) {
-        const bool blive = cc < P.slab_rows;
-        const unsigned char *lb = sm.u + (size_t)cc * SLAB_PITCH + (c.ck % SLAB_CK) * CHUNK_ROW_BYTES + wave * 128 + g * 16;
-        const size_t plane_off = (size_t)P.slab_rows * SLAB_PITCH;
+    const bool blive = cc < P.slab_rows;
+    const unsigned char *lb = sm.u + (size_t)cc * SLAB_PITCH + (c.ck % SLAB_CK) * CHUNK_ROW_BYTES + wave * 128 + g * 16;
+    const size_t plane_off = (size_t)P.slab_rows * SLAB_PITCH;
 #pragma unroll
-        for (int i = 0; i < CH; ++i) {
+    for (int i = 0; i < CH; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                Act<T> av;
+        for (int j = 0; j < 2; ++j) {
+            Act<T> av;
 #pragma unroll
-                for (int pl = 0; pl < PL; ++pl)
-                    av.p[pl] = blive ? *reinterpret_cast<const u32x4 *>(lb + pl * plane_off + i * (MNW * 128) + j * 64) : zero16();
-                mma2(acc0, acc1, wbuf[2 * i + j], av, j);
-            }
-            // keep the scheduler from hoisting every LDS read of the chunk to the top (register pressure)
-            if (i % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+            for (int pl = 0; pl < PL; ++pl)
+                av.p[pl] = blive ? *reinterpret_cast<const u32x4 *>(lb + pl * plane_off + i * (MNW * 128) + j * 64) : zero16();
+            mma2(acc0, acc1, wbuf[2 * i + j], av, j);
         }
-    } else {
-        const bool head = ph.kind == PH_HEAD;
-        const int brow = head ? P.head_row0 + cc * P.head_stride : cc;
-        const bool blive = cc < (head ? P.head_rows : P.R);
-        ActPlanes<T> act{reinterpret_cast<T *>(P.act[ph.act_src]), P.act_plane[ph.act_src], P.act_ld[ph.act_src]};
-        const size_t aoff = (size_t)brow * act.ld + g * E;
-#pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            const int s = wave + MNW * (c.ck * CH + i);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int k = (2 * s + j) * KB;
-                const Act<T> av = (blive && k + g * E < ph.K) ? load_act_coh(act, aoff + k) : zero_act<T>();
-                mma2(acc0, acc1, wbuf[2 * i + j], av, j);
-            }
-        }
-    }
 }
 
 // Tile complete: fixed-order sum of the waves' partial tiles by waves 0-3 (register v = wave) into the
@@ -548,7 +560,7 @@ __device__ __forceinline__ void finish_tile(int tile, const f32x4 &acc0, const f
 // epilogues of the stashed tiles, spread over all waves: entry (slot, v) -> wave (slot*4 + v) % MNW
 template <typename T>
 __device__ __forceinline__ void flush_stash(const MegaCall &P, const MegaPhase &ph, const Range &r, int &nstash, float &rowsq,
-                                            MegaSmem &sm) {
+                                            bool last, MegaSmem &sm) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     lds_barrier(); // the stash writes of the last tile are visible
     for (int e = wave; e < nstash * 4; e += MNW) {
@@ -556,7 +568,8 @@ __device__ __forceinline__ void flush_stash(const MegaCall &P, const MegaPhase &
         tile_epilogue<T>(P, ph, r, sm.t->stash_tile[slot], sm.t->stash[slot][v][lane], v, rowsq, sm);
     }
     nstash = 0;
-    stores_done(); // also makes the next chunk loop start with no store pending
+    if (last) return; // end of the phase: the phase boundary waits for the stores and synchronises
+    stores_done(); // the next segment starts with no store pending
     lds_barrier(); // nobody overwrites the stash before everyone has read it
 }
 
@@ -572,10 +585,10 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
     // Weight pipeline: `la` runs RING positions ahead of `cc` (the next chunk to multiply); the loads of
-    // those chunks are in flight into the ring slots r0, r1, r2.  A step multiplies straight out of its
+    // those chunks are in flight into the ring slots.  A step multiplies straight out of its
     // slot (which waits for that slot's loads only - later slots stay in flight), then refills the slot
     // with the chunk RING ahead.  A workgroup's positions per phase are padded to a multiple of RING, so
-    // each phase starts at slot r0 and the code below exists once.  The last round of a phase does not
+    // each phase starts at slot 0 and the code below exists once.  The last round of a phase does not
     // refill: the ring is empty at a phase boundary and is refilled there with the first round of the
     // next phase, before the device-wide barrier, so those loads fly during the barrier.
     struct State {
@@ -590,8 +603,7 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
     st.slab_tag = -1;
     st.rowsq = 0.f;
 
-    u32x4 r0[2 * CH], r1[2 * CH], r2[2 * CH];
-    static_assert(RING == 3, "the loops below are written for three ring slots");
+    u32x4 ring[RING][2 * CH]; // only ever indexed by unrolled constants: lives in registers
     static_assert(MNW >= 4, "waves 0-3 reduce one accumulator register each");
 
     const char *zeros = reinterpret_cast<const char *>(P.zeros);
@@ -613,19 +625,21 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
         // acknowledged, so the wait for the stores does not drain them.
         cursor_begin<T>(st.cc, ph, P.hd, wg, G);
         st.la = st.cc;
-        if (p > 0) stores_done();
+        if (p > 0) {
+            stores_done();
+            grid_arrive(P, P.epoch_base + (unsigned)p, sm);
+        }
         if (wave != 0) { // wave 0 polls memory in the barrier, which would wait for these loads
-            fill(r0);
-            fill(r1);
-            fill(r2);
+#pragma unroll
+            for (int sl = 0; sl < RING; ++sl) fill(ring[sl]);
         }
-        if (p > 0 && !grid_arrive_wait(P, P.epoch_base + (unsigned)p, G, sm)) return;
+        if (p > 0 && !grid_wait(P, P.epoch_base + (unsigned)p, G, sm)) return;
+        if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(5 * p) * G + wg] = wall_clock64();
+        const bool want_scales = ph.kind == PH_QKV || ph.kind == PH_SWIGLU || ph.kind == PH_HEAD;
         if (wave == 0) {
-            fill(r0);
-            fill(r1);
-            fill(r2);
+#pragma unroll
+            for (int sl = 0; sl < RING; ++sl) fill(ring[sl]);
         }
-        if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(3 * p) * G + wg] = wall_clock64();
         st.rowsq = 0.f;
         switch (ph.kind) {
         case PH_EMBED: do_embed<T>(P, ph, wg, G, sm); break;
@@ -636,12 +650,9 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
         case PH_LEN:
             if (wg == 0 && (int)threadIdx.x < P.B) P.len[threadIdx.x] += P.M;
             break;
-        case PH_QKV:
-        case PH_SWIGLU:
-        case PH_HEAD: compute_scales(P, G, sm); break; // read after a later __syncthreads
         default: break;
         }
-        if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(3 * p + 1) * G + wg] = wall_clock64();
+        if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(5 * p + 1) * G + wg] = wall_clock64();
 
         int nstash = 0;
         const Range my = st.cc.r; // this workgroup's share of the phase
@@ -650,25 +661,22 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
         // the pinned ring loads, and nothing else is pending when they start (the wait below costs
         // little: the ring loads it waits for are the ones the first steps need anyway); both are what
         // lets the compiler wait for one slot with an exact count and leave the younger slots in flight.
-        auto run_segment = [&](auto slab_c, int n_fill, bool last) {
-            constexpr bool SLAB = decltype(slab_c)::value;
+        auto run_segment = [&](int n_fill, bool last) {
             auto step = [&](auto fill_c, u32x4(&slot)[2 * CH]) {
                 const Cursor c = st.cc;
                 cursor_next<T>(st.cc, P.hd);
-                if (!c.dummy) mma_chunk<T, SLAB>(c, P, ph, slot, st.acc0, st.acc1, sm);
+                if (!c.dummy) mma_chunk<T>(c, P, slot, st.acc0, st.acc1, sm);
                 if (decltype(fill_c)::value) fill(slot);
                 if (!c.dummy && c.ck + 1 == c.nck) finish_tile(c.tile, st.acc0, st.acc1, st.tile_seq, nstash, sm);
             };
             stores_done();
             for (int i = 0; i < n_fill; ++i) {
-                step(std::true_type{}, r0);
-                step(std::true_type{}, r1);
-                step(std::true_type{}, r2);
+#pragma unroll
+                for (int sl = 0; sl < RING; ++sl) step(std::true_type{}, ring[sl]);
             }
             if (last) {
-                step(std::false_type{}, r0);
-                step(std::false_type{}, r1);
-                step(std::false_type{}, r2);
+#pragma unroll
+                for (int sl = 0; sl < RING; ++sl) step(std::false_type{}, ring[sl]);
             }
         };
         while (st.cc.active) {
@@ -682,19 +690,25 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
             const int tiles_per_round = multi ? 1 : RING / cc.nck + 1;
             const int n = min(grp_rounds, max(1, (STASH_TILES - nstash) / tiles_per_round));
             const bool final_round = last_group && n == grp_rounds; // the phase ends with this segment
-            if (P.slab_rows > 0) {
-                const int tag = (p << 8) | (cc.ck / SLAB_CK);
-                if (st.slab_tag != tag) {
-                    lds_barrier(); // every wave is done with the previous slab
-                    load_slab<T>(P, ph, cc.ck / SLAB_CK, sm);
-                    lds_barrier();
-                    st.slab_tag = tag;
-                }
-                run_segment(std::true_type{}, final_round ? n - 1 : n, final_round);
-            } else {
-                run_segment(std::false_type{}, final_round ? n - 1 : n, final_round);
+            const int tag = (p << 8) | (cc.ck / SLAB_CK);
+            if (st.slab_tag != tag) {
+                lds_barrier(); // every wave is done with the previous slab
+                const bool ws = want_scales && cc.idx == 0; // first slab of the phase: with the row scales
+                auto reload = [&](auto npr_c) {
+                    SlabLoads<decltype(npr_c)::value> L;
+                    slab_issue<T>(P, ph, cc.ck / SLAB_CK, G, ws, L);
+                    asm volatile("" ::: "memory"); // keeps the compiler from fusing the two loops (load, wait, store per row)
+                    slab_finish<T>(P, G, ws, L, sm);
+                };
+                if (Traits<T>::PLANES * P.slab_rows <= 10) reload(std::integral_constant<int, 10>{});
+                else reload(std::integral_constant<int, 16>{});
+                if (P.timeline && threadIdx.x == 0 && cc.idx == 0) P.timeline[(size_t)(5 * p + 2) * G + wg] = wall_clock64();
+                lds_barrier();
+                st.slab_tag = tag;
             }
-            if (final_round || nstash + tiles_per_round > STASH_TILES) flush_stash<T>(P, ph, my, nstash, st.rowsq, sm);
+            run_segment(final_round ? n - 1 : n, final_round);
+            if (P.timeline && threadIdx.x == 0 && final_round) P.timeline[(size_t)(5 * p + 3) * G + wg] = wall_clock64();
+            if (final_round || nstash + tiles_per_round > STASH_TILES) flush_stash<T>(P, ph, my, nstash, st.rowsq, final_round, sm);
         }
         if (ph.kind == PH_RESID) {
             // publish this workgroup's partial sums of squares of the new hidden rows
@@ -710,7 +724,7 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
                 st_coh(&P.nsq[(size_t)threadIdx.x * G + wg], tot);
             }
         }
-        if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(3 * p + 2) * G + wg] = wall_clock64();
+        if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(5 * p + 4) * G + wg] = wall_clock64();
     }
 }
 
@@ -737,6 +751,16 @@ static hipError_t ensure_smem_attr(int dtype) {
     return e;
 }
 
+int mega_max_rows(int dtype) {
+    int slab_rows = 0;
+    size_t u_bytes = 0;
+    for (int rows = 16; rows >= 1; --rows) {
+        smem_plan(dtype, rows, slab_rows, u_bytes);
+        if (slab_rows == rows) return rows;
+    }
+    return 0;
+}
+
 int mega_grid(int dtype, int device) {
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) != hipSuccess) return 0;
@@ -753,6 +777,7 @@ hipError_t launch_mega(const MegaCall &call, int grid, hipStream_t st) {
     MegaCall c = call;
     size_t u_bytes;
     smem_plan(c.dtype, std::max(c.R, c.head_rows), c.slab_rows, u_bytes);
+    if (c.slab_rows <= 0) return hipErrorInvalidValue; // the hidden rows must fit the LDS slab (mega_max_rows)
     c.u_bytes = (int)u_bytes;
     void *args[] = {&c};
     const void *fn = call.dtype ? (const void *)verify_persistent_kernel<bf16_t> : (const void *)verify_persistent_kernel<float>;

@@ -64,14 +64,16 @@ struct MegaCall {
     unsigned spin_limit;
     int32_t *status;
     const void *zeros; // >= 64 zero bytes: the target of weight loads that have no data to fetch
-    int slab_rows, u_bytes;       // set by launch_mega: rows held in the LDS slab (0: none), size of the slab area
+    int slab_rows, u_bytes;       // set by launch_mega: rows held in the LDS slab, size of the slab area
     unsigned long long *timeline; // optional [3*n_phases][G] device clock samples of every workgroup (NULL: off)
 };
 
 constexpr int MEGA_THREADS = 256;
 
-// number of workgroups a launch may use (all resident at once), and the launch itself
+// number of workgroups a launch may use (all resident at once), the largest number of hidden rows a
+// launch can take (they must fit the LDS activation slab), and the launch itself
 int mega_grid(int dtype, int device);
+int mega_max_rows(int dtype);
 hipError_t launch_mega(const MegaCall &call, int grid, hipStream_t st);
 
 } // namespace ss
