@@ -25,7 +25,7 @@ namespace ss {
 template <typename T, int HD>
 __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
     __shared__ AttnSmem<HD, 4> sm;
-    attn_unit<T, HD, 4>(a, blockIdx.x, blockIdx.y, blockIdx.z, sm);
+    attn_unit<T, HD, 4>(a, blockIdx.x, blockIdx.y, blockIdx.z, a.len[blockIdx.z], sm);
 }
 
 template <typename T>

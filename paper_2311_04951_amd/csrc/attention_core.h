@@ -14,16 +14,15 @@ template <int HD, int NW> struct AttnSmem {
     float o[NW][HD / 16][4][64];
 };
 
-// One (sequence b, head h, KV split) unit by a workgroup of NW wavefronts: writes the split's
-// unnormalised partial (part_o, part_m, part_l).  Every thread of the workgroup must call it.
+// One (sequence b, head h, KV split) unit by a workgroup of NW wavefronts; L = cached length of
+// sequence b before this pass.  Writes the split's unnormalised partial (part_o, part_m, part_l).  Every thread of the workgroup must call it.
 // COH: queries are read and partials written with agent-coherent accesses (persistent kernel).
 // DIRECT: there is a single split, so the normalised result goes straight to the activation planes.
 template <typename T, int HD, int NW, bool COH = false, bool DIRECT = false>
-__device__ __forceinline__ void attn_unit(const AttnArgs &a, int split, int h, int b, AttnSmem<HD, NW> &sm) {
+__device__ __forceinline__ void attn_unit(const AttnArgs &a, int split, int h, int b, int L, AttnSmem<HD, NW> &sm) {
     constexpr int E = Traits<T>::E, KB = 4 * E, TPB = E / 4, NKC = HD / KB, NDT = HD / 16;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 15, g = lane >> 4;
-    const int L = a.len[b];
     const int ntot = L + a.M;
     const int p_begin = split * a.chunk;
     const int p_end = min(p_begin + a.chunk, ntot);
@@ -48,15 +47,37 @@ __device__ __forceinline__ void attn_unit(const AttnArgs &a, int split, int h, i
 #pragma unroll
     for (int dt = 0; dt < NDT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    for (int p0 = p_begin + wave * KB; p0 < p_end; p0 += NW * KB) {
+    // One step covers KB positions.  The key and value chunks of a step do not depend on anything
+    // computed here, so the next step's chunks are requested before the current step's arithmetic:
+    // a wave pays one memory round trip for its whole KV range instead of two per step.
+    struct Tile {
+        u32x4 k[TPB][NKC];
+        u32x4 v[NDT];
+    };
+    auto load_tile = [&](int p0, Tile &t) {
+#pragma unroll
+        for (int tt = 0; tt < TPB; ++tt) {
+            const int pos_i = p0 + (c >> 2) * E + 4 * tt + (c & 3);
+            const T *krow = Kb + (size_t)pos_i * HD + g * E;
+#pragma unroll
+            for (int kc = 0; kc < NKC; ++kc) t.k[tt][kc] = ld16_stream(krow + kc * KB);
+        }
+        const T *vrow = Vb + ((size_t)(p0 >> 6) * HD + c) * 64 + (p0 & 63) + g * E;
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt) t.v[dt] = ld16_stream(vrow + (size_t)dt * 16 * 64);
+    };
+    Tile cur, nxt;
+    const int p_first = p_begin + wave * KB;
+    if (p_first < p_end) load_tile(p_first, cur);
+    for (int p0 = p_first; p0 < p_end; p0 += NW * KB) {
+        const bool more = p0 + NW * KB < p_end;
+        if (more) load_tile(p0 + NW * KB, nxt);
         f32x4 s[TPB];
 #pragma unroll
         for (int t = 0; t < TPB; ++t) {
             s[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-            const int pos_i = p0 + (c >> 2) * E + 4 * t + (c & 3);
-            const T *krow = Kb + (size_t)pos_i * HD + g * E;
 #pragma unroll
-            for (int kc = 0; kc < NKC; ++kc) s[t] = mma(s[t], ld16_stream(krow + kc * KB), q[kc]);
+            for (int kc = 0; kc < NKC; ++kc) s[t] = mma(s[t], cur.k[t][kc], q[kc]);
         }
         // lane (c = row, g) holds the scores of positions p0 + g*E + e, e = 4t + v
         float pv[E];
@@ -86,9 +107,9 @@ __device__ __forceinline__ void attn_unit(const AttnArgs &a, int split, int h, i
 #pragma unroll
         for (int dt = 0; dt < NDT; ++dt) o[dt] *= alpha;
         const Act<T> P = pack_act(pv, T{});
-        const T *vrow = Vb + ((size_t)(p0 >> 6) * HD + c) * 64 + (p0 & 63) + g * E;
 #pragma unroll
-        for (int dt = 0; dt < NDT; ++dt) o[dt] = mma(o[dt], ld16_stream(vrow + (size_t)dt * 16 * 64), P);
+        for (int dt = 0; dt < NDT; ++dt) o[dt] = mma(o[dt], cur.v[dt], P);
+        if (more) cur = nxt;
     }
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);

@@ -188,6 +188,7 @@ struct MegaSmemTail {
     float scale[16];          // row scales of the current phase
     float sq[MNW][16];        // per wave partial row sums of squares
     float blk[MNW];
+    int len[16];              // cached lengths of the sequences before this pass (read once at kernel start)
     int flag;
 };
 
@@ -305,10 +306,10 @@ __device__ __forceinline__ void do_attn_hd(const MegaCall &P, const MegaPhase &p
         const int split = u % P.nsplit, bh = u / P.nsplit;
         const int h = bh % P.H, b = bh / P.H;
         if (P.nsplit == 1) { // one split: no partials, no merge
-            attn_unit<T, HD, MNW, true, true>(a, 0, h, b, asm_);
+            attn_unit<T, HD, MNW, true, true>(a, 0, h, b, sm.t->len[b], asm_);
             continue;
         }
-        attn_unit<T, HD, MNW, true>(a, split, h, b, asm_);
+        attn_unit<T, HD, MNW, true>(a, split, h, b, sm.t->len[b], asm_);
         // the split that arrives last merges all splits of (b, h); partials travel through
         // coherent accesses, so completing the stores (release at workgroup scope) is all it takes
         bool merge = true;
@@ -472,7 +473,7 @@ __device__ __forceinline__ void tile_epilogue(const MegaCall &P, const MegaPhase
     const int hh = n / P.hd, j = n - hh * P.hd;
     const int region = hh / P.H, h = hh - region * P.H;
     const int b = c / P.M, ii = c - b * P.M;
-    int pos = P.len[b] + ii;
+    int pos = sm.t->len[b] + ii;
     if (pos > P.max_pos - 1) pos = P.max_pos - 1; // host validation keeps these from happening
     if (pos > P.S - 1) pos = P.S - 1;
     float x0 = x0s, x1 = x1s;
@@ -583,6 +584,8 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
     sm.t = reinterpret_cast<MegaSmemTail *>(smem_raw + P.u_bytes);
     const int wg = blockIdx.x, G = gridDim.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (threadIdx.x < 16) sm.t->len[threadIdx.x] = (int)threadIdx.x < P.B ? P.len[threadIdx.x] : 0; // lengths change in the last phase only
+    lds_barrier();
 
     // Weight pipeline: `la` runs RING positions ahead of `cc` (the next chunk to multiply); the loads of
     // those chunks are in flight into the ring slots.  A step multiplies straight out of its
