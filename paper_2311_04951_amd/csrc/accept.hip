@@ -15,6 +15,7 @@
 // logits path and the materialised softmax produce identical bits.
 #include "ss_device.h"
 #include "ss_kernels.h"
+#include <algorithm>
 
 namespace ss {
 
@@ -39,25 +40,47 @@ __device__ __forceinline__ void online_merge(float &m, float &s, float m2, float
     m = mm;
 }
 
-// one workgroup per row: stats[row] = (max_v x_v, sum_v exp(x_v - max)), x = logit * inv_t
-__global__ __launch_bounds__(256) void row_stats_kernel(const float *logits, int V, float inv_t, float2 *stats) {
-    const int row = blockIdx.x;
-    const float *x = logits + (size_t)row * V;
+// one workgroup per row: stats[row] = (max_v x_v, sum_v exp(x_v - max)), x = logit * inv_t.
+// Each thread keeps STATS_UNROLL independent 16-byte loads in flight per step (the row is streamed once
+// and the kernel is bound by memory latency otherwise) and folds the step into its running (max, sum)
+// with one rescale.
+constexpr int STATS_UNROLL = 8;
+// Two row sets in one launch (the target's and the draft's logits): workgroups [0, rows_a) take set a.
+__global__ __launch_bounds__(256) void row_stats_kernel(const float *logits_a, int rows_a, float2 *stats_a, const float *logits_b,
+                                                        float2 *stats_b, int V, float inv_t) {
+    const bool first = (int)blockIdx.x < rows_a;
+    const int row = first ? blockIdx.x : blockIdx.x - rows_a;
+    const float *x = (first ? logits_a : logits_b) + (size_t)row * V;
+    float2 *stats = first ? stats_a : stats_b;
     float m = -INFINITY, s = 0.f;
     const bool vec = (V % 4 == 0) && ((reinterpret_cast<uintptr_t>(x) & 15) == 0);
     if (vec) {
         const f32x4 *x4 = reinterpret_cast<const f32x4 *>(x);
-        for (int i = threadIdx.x; i < V / 4; i += 256) {
-            const f32x4 t = __builtin_nontemporal_load(x4 + i);
-            const float a0 = scaled_logit(t[0], inv_t), a1 = scaled_logit(t[1], inv_t);
-            const float a2 = scaled_logit(t[2], inv_t), a3 = scaled_logit(t[3], inv_t);
-            const float mx = fmaxf(fmaxf(a0, a1), fmaxf(a2, a3));
+        const int n4 = V / 4;
+        for (int i0 = threadIdx.x; i0 < n4; i0 += 256 * STATS_UNROLL) {
+            f32x4 t[STATS_UNROLL];
+#pragma unroll
+            for (int j = 0; j < STATS_UNROLL; ++j) {
+                const int i = i0 + 256 * j;
+                t[j] = i < n4 ? __builtin_nontemporal_load(x4 + i) : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+            }
+            float mx = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < STATS_UNROLL; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    t[j][e] = scaled_logit(t[j][e], inv_t);
+                    mx = fmaxf(mx, t[j][e]);
+                }
             if (mx == -INFINITY) continue;
             if (mx > m) {
                 s *= expf(m - mx);
                 m = mx;
             }
-            s += (expf(a0 - m) + expf(a1 - m)) + (expf(a2 - m) + expf(a3 - m));
+            float add = 0.f;
+#pragma unroll
+            for (int j = 0; j < STATS_UNROLL; ++j) add += (expf(t[j][0] - m) + expf(t[j][1] - m)) + (expf(t[j][2] - m) + expf(t[j][3] - m));
+            s += add;
         }
     } else {
         for (int i = threadIdx.x; i < V; i += 256) online_add(m, s, scaled_logit(x[i], inv_t));
@@ -98,7 +121,12 @@ __global__ __launch_bounds__(256) void row_stats_kernel(const float *logits, int
 
 void launch_row_stats(const float *logits, int rows, int V, float inv_t, float2 *stats, hipStream_t st) {
     if (rows <= 0) return;
-    hipLaunchKernelGGL(row_stats_kernel, dim3(rows), dim3(256), 0, st, logits, V, inv_t, stats);
+    hipLaunchKernelGGL(row_stats_kernel, dim3(rows), dim3(256), 0, st, logits, rows, stats, nullptr, nullptr, V, inv_t);
+}
+void launch_row_stats2(const float *logits_a, int rows_a, float2 *stats_a, const float *logits_b, int rows_b, float2 *stats_b,
+                       int V, float inv_t, hipStream_t st) {
+    if (rows_a + rows_b <= 0) return;
+    hipLaunchKernelGGL(row_stats_kernel, dim3(rows_a + rows_b), dim3(256), 0, st, logits_a, rows_a, stats_a, logits_b, stats_b, V, inv_t);
 }
 
 __global__ __launch_bounds__(256) void softmax_write_kernel(const float *logits, int V, float inv_t, const float2 *stats,
@@ -173,20 +201,28 @@ __device__ __forceinline__ unsigned long long shfl_u64(unsigned long long x, int
     return ((unsigned long long)hi << 32) | lo;
 }
 
+// threshold of the inverse CDF: floor(u * 2^24) * S >> 24 with a 128-bit product (u is a multiple of 2^-24)
+__device__ __forceinline__ unsigned long long inv_cdf_threshold(float u, unsigned long long S) {
+    const unsigned long long mant = (unsigned long long)(u * 16777216.0f);
+    return (__umul64hi(mant, S) << 40) | ((mant * S) >> 24);
+}
+
 constexpr int SAMPLE_THREADS = 1024, SAMPLE_WAVES = SAMPLE_THREADS / 64;
 
-// Integer inverse CDF of one row by a 1024-thread workgroup.  Wave w owns the contiguous segment
-// [w*seg, (w+1)*seg); pass A sums every segment, pass B rescans the one segment that holds the
-// threshold.  Returns the token to every thread, or -1 when all weights are 0.
+// Integer inverse CDF over the range [r0, r1) of one row (r0 a multiple of 4) by a 1024-thread
+// workgroup.  Wave w owns a contiguous segment of the range; pass A sums every segment, pass B rescans
+// the one segment that holds the threshold.  have_T: the threshold T (relative to the weight in front
+// of r0, known to fall inside the range) is given; otherwise it is derived from u and the range's
+// total, and -1 is returned when that total is 0.  Returns the token to every thread.
 template <bool RESID>
-__device__ int block_inv_cdf(const RowSrc &P, const RowSrc &Q, int V, float u, unsigned long long *sm_wave,
-                             int *sm_tok) {
+__device__ int block_inv_cdf(const RowSrc &P, const RowSrc &Q, int V, int r0, int r1, bool have_T, unsigned long long T,
+                             float u, unsigned long long *sm_wave, int *sm_tok) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool vec = (V % 4 == 0) && ((reinterpret_cast<uintptr_t>(P.row) & 15) == 0) &&
                      (!RESID || (reinterpret_cast<uintptr_t>(Q.row) & 15) == 0);
-    int seg = (V + SAMPLE_WAVES - 1) / SAMPLE_WAVES;
+    int seg = (r1 - r0 + SAMPLE_WAVES - 1) / SAMPLE_WAVES;
     seg = (seg + 255) & ~255;
-    const int v_begin = wave * seg, v_end = min(v_begin + seg, V);
+    const int v_begin = min(r0 + wave * seg, r1), v_end = min(v_begin + seg, r1);
 
     unsigned long long sum = 0;
     for (int v = v_begin + 4 * lane; v < v_end; v += 256) {
@@ -200,12 +236,13 @@ __device__ int block_inv_cdf(const RowSrc &P, const RowSrc &Q, int V, float u, u
     if (lane == 0) sm_wave[wave] = sum;
     if (threadIdx.x == 0) *sm_tok = -1;
     __syncthreads();
-    unsigned long long S = 0;
-    for (int w = 0; w < SAMPLE_WAVES; ++w) S += sm_wave[w];
-    if (S == 0) return -1;
-    const unsigned long long mant = (unsigned long long)(u * 16777216.0f);
-    const unsigned long long T = (__umul64hi(mant, S) << 40) | ((mant * S) >> 24);
-    unsigned long long C = 0; // weight of all segments before mine
+    if (!have_T) {
+        unsigned long long S = 0;
+        for (int w = 0; w < SAMPLE_WAVES; ++w) S += sm_wave[w];
+        if (S == 0) return -1;
+        T = inv_cdf_threshold(u, S);
+    }
+    unsigned long long C = 0; // weight of the segments before mine
     for (int w = 0; w < wave; ++w) C += sm_wave[w];
     if (C <= T && T < C + sm_wave[wave]) { // wave-uniform: exactly one wave rescans its segment
         for (int v0 = v_begin; v0 < v_end; v0 += 256) {
@@ -298,29 +335,77 @@ __device__ __forceinline__ RowSrc make_row(const float *base, const float2 *stat
     return r;
 }
 
-// one thread per sequence: leading accepted draft tokens
-__global__ void accept_scan_kernel(AcceptArgs a) {
-    const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= a.B) return;
-    int n = 0;
-    for (int i = 0; i < a.K; ++i) {
+// Leading accepted draft tokens of sequence b, by the first K threads of a workgroup (one gather of
+// p_i(d_i), q_i(d_i) per thread, all in flight together); every thread gets the count.
+__device__ int block_accept_count(const AcceptArgs &a, int b, int *sm_rej) {
+    if (threadIdx.x == 0) *sm_rej = a.K;
+    __syncthreads();
+    if ((int)threadIdx.x < a.K) {
+        const int i = threadIdx.x;
         const int d = a.draft[b * a.K + i];
+        bool acc = false;
         if (d < 0 || d >= a.V) { // cannot be validated on the host: flagged, treated as rejected
             atomicOr(a.status, 1);
-            break;
+        } else {
+            const RowSrc P = make_row(a.p, a.p_stats, (size_t)b * (a.K + 1) + i, a.V, a.from_logits, a.inv_t);
+            const RowSrc Q = make_row(a.q, a.q_stats, (size_t)b * a.K + i, a.V, a.from_logits, a.inv_t);
+            const float pi = P.at(d), qi = Q.at(d);
+            acc = (pi >= qi) || (__fmul_rn(a.u[b * (a.K + 1) + i], qi) < pi);
         }
-        const RowSrc P = make_row(a.p, a.p_stats, (size_t)b * (a.K + 1) + i, a.V, a.from_logits, a.inv_t);
-        const RowSrc Q = make_row(a.q, a.q_stats, (size_t)b * a.K + i, a.V, a.from_logits, a.inv_t);
-        const float pi = P.at(d), qi = Q.at(d);
-        const bool acc = (pi >= qi) || (__fmul_rn(a.u[b * (a.K + 1) + i], qi) < pi);
-        if (!acc) break;
-        ++n;
+        if (!acc) atomicMin(sm_rej, i);
     }
-    a.n_accepted[b] = n;
+    __syncthreads();
+    return *sm_rej;
 }
 
-// one workgroup per sequence: residual resample at the first rejection, or the bonus token
-__global__ __launch_bounds__(SAMPLE_THREADS) void accept_sample_kernel(AcceptArgs a) {
+constexpr int PART_THREADS = 256, PART_UNROLL = 4;
+
+// grid (nseg, B): the accepted count of sequence b, and the total weight of segment blockIdx.x of the
+// row the next token is drawn from (residual at the first rejection, else the bonus row).  The
+// vocabulary is cut into nseg segments so that a few sequences still fill the chip; integer partial
+// sums make the split invisible in the result.
+__global__ __launch_bounds__(PART_THREADS) void accept_partial_kernel(AcceptArgs a, int seg_len, unsigned long long *partial) {
+    __shared__ int sm_rej;
+    __shared__ unsigned long long sm_part[PART_THREADS / 64];
+    const int b = blockIdx.y, seg = blockIdx.x, nseg = gridDim.x;
+    const int n = block_accept_count(a, b, &sm_rej);
+    if (seg == 0 && threadIdx.x == 0) a.n_accepted[b] = n;
+    const RowSrc P = make_row(a.p, a.p_stats, (size_t)b * (a.K + 1) + n, a.V, a.from_logits, a.inv_t);
+    const bool resid = n < a.K;
+    const RowSrc Q = resid ? make_row(a.q, a.q_stats, (size_t)b * a.K + n, a.V, a.from_logits, a.inv_t) : P;
+    const bool vec = (a.V % 4 == 0) && ((reinterpret_cast<uintptr_t>(P.row) & 15) == 0) && ((reinterpret_cast<uintptr_t>(Q.row) & 15) == 0);
+    const int r0 = min(seg * seg_len, a.V), r1 = min(r0 + seg_len, a.V);
+    unsigned long long sum = 0;
+    for (int v0 = r0 + 4 * threadIdx.x; v0 < r1; v0 += 4 * PART_THREADS * PART_UNROLL) {
+        unsigned long long w[PART_UNROLL][4];
+#pragma unroll
+        for (int j = 0; j < PART_UNROLL; ++j) {
+            const int v = v0 + 4 * PART_THREADS * j;
+            if (v < r1) {
+                if (resid) weights4<true>(P, Q, v, a.V, vec, w[j]);
+                else weights4<false>(P, P, v, a.V, vec, w[j]);
+            } else {
+                w[j][0] = w[j][1] = w[j][2] = w[j][3] = 0;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < PART_UNROLL; ++j) sum += (w[j][0] + w[j][1]) + (w[j][2] + w[j][3]);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sum += shfl_xor_u64(sum, o);
+    if ((threadIdx.x & 63) == 0) sm_part[threadIdx.x >> 6] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long t = 0;
+        for (int w = 0; w < PART_THREADS / 64; ++w) t += sm_part[w];
+        partial[(size_t)b * nseg + seg] = t;
+    }
+}
+
+// one workgroup per sequence: locate the segment that holds the threshold and rescan it.  All residual
+// weights zero (possible only through rounding): sample from p with the same uniform; all of those
+// zero too: argmax.
+__global__ __launch_bounds__(SAMPLE_THREADS) void accept_finish_kernel(AcceptArgs a, int seg_len, int nseg, const unsigned long long *partial) {
     __shared__ unsigned long long sm_wave[SAMPLE_WAVES];
     __shared__ int sm_tok;
     __shared__ float sm_val[SAMPLE_WAVES];
@@ -329,20 +414,50 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void accept_sample_kernel(AcceptArg
     const int n = a.n_accepted[b];
     const float u = a.u[b * (a.K + 1) + a.K];
     const RowSrc P = make_row(a.p, a.p_stats, (size_t)b * (a.K + 1) + n, a.V, a.from_logits, a.inv_t);
+    const bool resid = n < a.K;
+    const RowSrc Q = resid ? make_row(a.q, a.q_stats, (size_t)b * a.K + n, a.V, a.from_logits, a.inv_t) : P;
+    unsigned long long S = 0;
+    for (int sgi = 0; sgi < nseg; ++sgi) S += partial[(size_t)b * nseg + sgi];
     int tok = -1;
-    if (n < a.K) {
-        const RowSrc Q = make_row(a.q, a.q_stats, (size_t)b * a.K + n, a.V, a.from_logits, a.inv_t);
-        tok = block_inv_cdf<true>(P, Q, a.V, u, sm_wave, &sm_tok);
+    if (S != 0) {
+        const unsigned long long T = inv_cdf_threshold(u, S);
+        unsigned long long C = 0;
+        int sgi = 0;
+        for (; sgi < nseg - 1; ++sgi) { // the segment with C <= T < C + partial
+            const unsigned long long ps = partial[(size_t)b * nseg + sgi];
+            if (T < C + ps) break;
+            C += ps;
+        }
+        const int r0 = min(sgi * seg_len, a.V), r1 = min(r0 + seg_len, a.V);
+        tok = resid ? block_inv_cdf<true>(P, Q, a.V, r0, r1, true, T - C, u, sm_wave, &sm_tok)
+                    : block_inv_cdf<false>(P, P, a.V, r0, r1, true, T - C, u, sm_wave, &sm_tok);
+    } else if (resid) {
+        tok = block_inv_cdf<false>(P, P, a.V, 0, a.V, false, 0, u, sm_wave, &sm_tok);
     }
-    if (tok < 0) tok = block_inv_cdf<false>(P, P, a.V, u, sm_wave, &sm_tok);
     if (tok < 0) tok = block_argmax(P, a.V, sm_val, sm_idx);
     if (threadIdx.x == 0) a.next_token[b] = tok;
 }
 
-void launch_accept(const AcceptArgs &a, hipStream_t st) {
+// segments per sequence: enough workgroups to fill the chip, at least 8192 vocabulary entries each
+static int accept_segments(int B, int V, int &seg_len) {
+    int nseg = std::max(1, std::min(std::min(16, V / 8192), (1024 + B - 1) / std::max(B, 1)));
+    seg_len = (V + nseg - 1) / nseg;
+    seg_len = (seg_len + 1023) & ~1023; // multiple of the 4-wide loads of a whole workgroup
+    nseg = (V + seg_len - 1) / seg_len;
+    return std::max(nseg, 1);
+}
+
+size_t accept_workspace_bytes(int B, int V) {
+    int seg_len;
+    return sizeof(unsigned long long) * (size_t)B * accept_segments(B, V, seg_len);
+}
+
+void launch_accept(const AcceptArgs &a, unsigned long long *partial, hipStream_t st) {
     if (a.B <= 0) return;
-    hipLaunchKernelGGL(accept_scan_kernel, dim3((a.B + 63) / 64), dim3(64), 0, st, a);
-    hipLaunchKernelGGL(accept_sample_kernel, dim3(a.B), dim3(SAMPLE_THREADS), 0, st, a);
+    int seg_len;
+    const int nseg = accept_segments(a.B, a.V, seg_len);
+    hipLaunchKernelGGL(accept_partial_kernel, dim3(nseg, a.B), dim3(PART_THREADS), 0, st, a, seg_len, partial);
+    hipLaunchKernelGGL(accept_finish_kernel, dim3(a.B), dim3(SAMPLE_THREADS), 0, st, a, seg_len, nseg, partial);
 }
 
 // ------------------------------------------------------------------ sampling / argmax of plain rows
@@ -360,7 +475,7 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_rows_kernel(const float
     P.inv_t = 1.f;
     P.mx = 0.f;
     P.Z = 1.f;
-    int tok = block_inv_cdf<false>(P, P, V, u[b], sm_wave, &sm_tok);
+    int tok = block_inv_cdf<false>(P, P, V, 0, V, false, 0, u[b], sm_wave, &sm_tok);
     if (tok < 0) tok = block_argmax(P, V, sm_val, sm_idx);
     if (threadIdx.x == 0) token_out[b] = tok;
 }

@@ -750,13 +750,13 @@ extern "C" int ss_speculative_accept(const float *p_dev, const float *q_dev, con
     int rc = check_accept(p_dev, q_dev, draft_tokens_dev, uniforms_dev, batch, K, vocab, n_accepted_dev, next_token_dev, "ss_speculative_accept");
     if (rc) return rc;
     void *ws;
-    rc = scratch(0, &ws);
+    rc = scratch(accept_workspace_bytes(batch, vocab), &ws);
     if (rc) return rc;
     AcceptArgs a{};
     a.p = p_dev; a.q = q_dev; a.from_logits = 0; a.inv_t = 1.f;
     a.draft = draft_tokens_dev; a.u = uniforms_dev; a.B = batch; a.K = K; a.V = vocab;
     a.n_accepted = n_accepted_dev; a.next_token = next_token_dev; a.status = (int32_t *)ws;
-    launch_accept(a, (hipStream_t)stream);
+    launch_accept(a, (unsigned long long *)((char *)ws + 256), (hipStream_t)stream);
     return check_launch();
 }
 
@@ -769,18 +769,17 @@ extern "C" int ss_speculative_accept_logits(const float *p_logits_dev, const flo
     if (!(temperature > 0.f)) return fail(SS_EINVAL, "ss_speculative_accept_logits: temperature must be > 0");
     const size_t np = (size_t)batch * (K + 1), nq = (size_t)batch * K;
     void *ws;
-    rc = scratch(sizeof(float2) * (np + nq), &ws);
+    rc = scratch(sizeof(float2) * (np + nq) + accept_workspace_bytes(batch, vocab), &ws);
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
     float2 *ps = (float2 *)((char *)ws + 256), *qs = ps + np;
     const float inv_t = 1.0f / temperature;
-    launch_row_stats(p_logits_dev, (int)np, vocab, inv_t, ps, st);
-    launch_row_stats(q_logits_dev, (int)nq, vocab, inv_t, qs, st);
+    launch_row_stats2(p_logits_dev, (int)np, ps, q_logits_dev, (int)nq, qs, vocab, inv_t, st);
     AcceptArgs a{};
     a.p = p_logits_dev; a.q = q_logits_dev; a.p_stats = ps; a.q_stats = qs; a.from_logits = 1; a.inv_t = inv_t;
     a.draft = draft_tokens_dev; a.u = uniforms_dev; a.B = batch; a.K = K; a.V = vocab;
     a.n_accepted = n_accepted_dev; a.next_token = next_token_dev; a.status = (int32_t *)ws;
-    launch_accept(a, st);
+    launch_accept(a, (unsigned long long *)(qs + nq), st);
     if (p_out_dev) launch_softmax_write(p_logits_dev, (int)np, vocab, inv_t, ps, p_out_dev, vocab, st);
     if (q_out_dev) launch_softmax_write(q_logits_dev, (int)nq, vocab, inv_t, qs, q_out_dev, vocab, st);
     return check_launch();

@@ -70,6 +70,8 @@ void launch_kv_append(int dtype, void *kc, void *vc, const void *k, const void *
 
 // softmax / accept
 void launch_row_stats(const float *logits, int rows, int V, float inv_t, float2 *stats, hipStream_t st);
+void launch_row_stats2(const float *logits_a, int rows_a, float2 *stats_a, const float *logits_b, int rows_b, float2 *stats_b,
+                       int V, float inv_t, hipStream_t st);
 void launch_softmax_write(const float *logits, int rows, int V, float inv_t, const float2 *stats, float *probs,
                           int64_t probs_ld, hipStream_t st);
 struct AcceptArgs {
@@ -83,7 +85,9 @@ struct AcceptArgs {
     int32_t *n_accepted, *next_token;
     int32_t *status;
 };
-void launch_accept(const AcceptArgs &a, hipStream_t st);
+// partial: device workspace of accept_workspace_bytes(B, V) bytes (per-segment weight sums)
+size_t accept_workspace_bytes(int B, int V);
+void launch_accept(const AcceptArgs &a, unsigned long long *partial, hipStream_t st);
 void launch_greedy_accept(const float *p_logits, const int32_t *draft, int B, int K, int V, int32_t *row_argmax,
                           int32_t *n_accepted, int32_t *next_token, hipStream_t st);
 // token ~ row by the integer inverse CDF (rows are probabilities), or argmax when greedy

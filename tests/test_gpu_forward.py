@@ -133,6 +133,39 @@ def test_single_7b_layer_verify_matches_oracle(persistent):
     assert maxabs(got, ref) < 1e-3
 
 
+@pytest.mark.timeout(1200)
+def test_full_7b_verify_pass_matches_oracle():
+    """The benchmark workload at its full size and in the launch configuration bench.py times (32
+    7B-shaped bf16 layers + LM head, default forward path, 5 query rows, 128 cached positions):
+    every logit of the verify pass against the oracle, max-abs 2e-2; the greedy token of a row must
+    agree wherever the oracle's top-2 margin exceeds twice that tolerance."""
+    from bench import build_7b
+    shape, packed, io = build_7b(si, sv, torch, 0, si.FULL_7B.n_layers, dev())
+    gm = sv.Model(shape, io, max_rows=16, max_pos=512, packed_layers=packed)
+    W = shape.n_heads * shape.head_dim
+    layers = [{"wq": p["wqkv"][:W].cpu(), "wk": p["wqkv"][W:2 * W].cpu(), "wv": p["wqkv"][2 * W:].cpu(), "wo": p["wo"].cpu(),
+               "wg": p["wgu"][:shape.d_ff].cpu(), "wu": p["wgu"][shape.d_ff:].cpu(), "wd": p["wd"].cpu(),
+               "g1": p["g1"].cpu(), "g2": p["g2"].cpu()} for p in packed]
+    om = oracle.Model(shape, {"embed": io["embed"].cpu(), "gf": io["gf"].cpu(), "lm_head": io["lm_head"].cpu(), "layers": layers})
+    L, M = 128, 5
+    ctx = si.kv_context(shape, 3, "ctx7b", L)
+    gkv = sv.KVCache(gm, 1, L + 64)
+    for l, (k, v) in enumerate(ctx):
+        sv.ss_kv_cache_append(gkv, l, 0, 0, k.to(dev()), v.to(dev()))
+    sv.ss_kv_cache_set_len(gkv, [L])
+    okv = om.new_kv(L + 64)
+    okv.append_raw(ctx)
+    toks = si.token_ids(3, "verify7b", (M,), shape.vocab).numpy().astype(np.int32)
+    got = sv.ss_verify_forward(gm, gkv, torch.tensor(toks[None], device=dev()), M)[0].cpu().numpy()
+    ref = om.forward(okv, toks)
+    assert got.shape == ref.shape == (M, shape.vocab)
+    assert maxabs(got, ref) < 2e-2
+    top2 = np.sort(ref, axis=1)[:, -2:]
+    clear = (top2[:, 1] - top2[:, 0]) > 4e-2
+    assert (got.argmax(1)[clear] == ref.argmax(1)[clear]).all()
+    assert sv.ss_kv_cache_get_len(gkv).tolist() == [L + M]
+
+
 def test_capacity_and_shape_errors_come_from_the_host():
     shape = si.TINY_DRAFT
     _, gm, _ = model_pair(shape, seed=7, max_rows=8)
