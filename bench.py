@@ -98,6 +98,42 @@ def cpu_baseline(si, torch, shape, packed, io, prompt_len, M, seconds_target=15.
                       f"cached positions, {t_tot:.1f} s in total"}
 
 
+def standalone_accept(si, sv, torch, dev, iters=40):
+    """The stand-alone accept workload (batch 64, K 8, vocab 128256, fp32 logits, temperature 0.8):
+    time of ss_speculative_accept_logits against the algorithmic bytes of reading every logit once."""
+    B, K, V, T = 64, 8, 128256, 0.8
+    sets = []
+    for s in range(2):  # two input sets, alternated (1.1 GB together: beyond the 256 MB last-level cache)
+        pl, ql, u, ud = si.accept_workload(41 + s, B, K, V, device=dev)
+        q = sv.ss_softmax(ql, T)
+        d = torch.empty((B, K), dtype=torch.int32, device=dev)
+        zf, zi = torch.zeros(1, device=dev), torch.zeros(1, dtype=torch.int32, device=dev)
+        for i in range(K):  # draft tokens ~ q (the K = 0 case of the accept entry is a plain sample)
+            _, tok = sv.ss_speculative_accept(q[:, i].contiguous()[:, None], zf, zi, ud[:, i:i + 1].contiguous())
+            d[:, i] = tok
+        del q
+        sets.append((pl, ql, d, u))
+    na = torch.empty(B, dtype=torch.int32, device=dev)
+    nx = torch.empty(B, dtype=torch.int32, device=dev)
+
+    def run(i):
+        pl, ql, d, u = sets[i % len(sets)]
+        sv.ss_speculative_accept_logits(pl, ql, T, d, u, n_accepted=na, next_token=nx)
+
+    for i in range(4):
+        run(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(iters):
+        run(i)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / iters
+    nbytes = (2 * K + 1) * B * V * 4
+    return {"workload": f"batch {B}, K {K}, vocab {V}, fp32 logits, temperature {T}", "us_per_call": dt * 1e6,
+            "algorithmic_bytes": nbytes, "GBps": nbytes / dt / 1e9, "frac_of_hbm_peak": nbytes / dt / HBM_PEAK,
+            "mean_accepted": float(na.float().mean())}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -110,6 +146,7 @@ def main():
                     help="1: run the forward as the persistent single-launch kernel, 0: one launch per phase")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-e2e", action="store_true")
+    ap.add_argument("--no-accept-workload", action="store_true", help="skip the stand-alone accept workload leg")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of 1 GiB five times (a kernel of known traffic, for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -236,6 +273,8 @@ def main():
         "roofline": roofline,
         "end_to_end": e2e,
     }
+    if not args.no_accept_workload:
+        out["standalone_accept"] = standalone_accept(si, sv, torch, dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(si, torch, shape, packed, io, prompt_len, M)
     if args.copy_calibration:

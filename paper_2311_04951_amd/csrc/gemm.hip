@@ -1,7 +1,9 @@
 // Weight-streaming skinny GEMM for the "linear layers" of the verify pass (Section 3: K+1 rows are
 // evaluated together, and the pass is bound by reading the weights once).
 //
-//   out[m][n] = sum_k act[m][k] * W[n][k],   m < R <= 16 per row tile, W row-major [N][K].
+//   out[m][n] = sum_k act[m][k] * W[n][k],   W row-major [N][K]; the R rows form row tiles of 16, and a
+//   workgroup multiplies every weight chunk it streams with up to RT row tiles (weights are read once for
+//   up to 16*RT rows).
 //
 // One workgroup (16 wavefronts) owns 16 output columns (or a pair of 16-column tiles for the fused
 // epilogues).  Each lane streams 16-byte chunks of 16 weight rows straight from HBM into registers -
@@ -16,82 +18,15 @@
 //           planes, k and v -> KV cache at positions len[b] + i
 #include "ss_device.h"
 #include "ss_kernels.h"
-#include <cstdlib>
 
 namespace ss {
 
-// NW = wavefronts per workgroup (interleaved over K), U = 128-byte steps in flight per wave
-template <typename T, int EPI, int NW, int U>
-__global__ __launch_bounds__(NW * 64) void gemm_kernel(GemmArgs a) {
-    constexpr int E = Traits<T>::E, KB = 4 * E;
+// Sum of the waves' partial tiles of row tile rt (fixed order) and the epilogue, by one wave.
+template <typename T, int EPI, int NW>
+__device__ __forceinline__ void tile_epilogue(const GemmArgs &a, const float (&red)[NW][(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1][4][64],
+                                              const int (&n0)[(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1], int rt) {
     constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int c = lane & 15, g = lane >> 4;
-    const int rt = blockIdx.y;
-    const int K = a.K;
-
-    int n0[NT];
-    if constexpr (EPI == EPI_QKV) {
-        const int per_head = a.hd / 32;
-        const int hh = blockIdx.x / per_head; // head index over [q heads | k heads | v heads]
-        n0[0] = hh * a.hd + (blockIdx.x % per_head) * 16;
-        n0[1] = n0[0] + a.hd / 2;
-    } else if constexpr (EPI == EPI_SWIGLU) {
-        n0[0] = blockIdx.x * 16;
-        n0[1] = a.N + n0[0];
-    } else {
-        n0[0] = blockIdx.x * 16;
-    }
-    const int nrows_w = (EPI == EPI_SWIGLU) ? 2 * a.N : a.N;
-
-    const T *W = reinterpret_cast<const T *>(a.W);
-    const T *wrow[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        int n = n0[t] + c;
-        if (n > nrows_w - 1) n = nrows_w - 1; // ragged last tile: load a valid row, masked at the store
-        wrow[t] = W + (size_t)n * K + g * E;
-    }
-    ActPlanes<T> act{const_cast<T *>(reinterpret_cast<const T *>(a.act)), a.act_plane, a.ld_act};
-    const size_t aoff = (size_t)(rt * 16 + c) * a.ld_act + g * E;
-    const bool row_live = rt * 16 + c < a.R; // rows past R contribute nothing: skip their loads
-
-    f32x4 acc[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    // Each wave takes 128-byte steps (two k-blocks) of every row, interleaved with the other waves,
-    // two steps per iteration so that 4*NT weight loads are in flight per lane before the first MFMA.
-    const int nkb = (K + KB - 1) / KB;
-    for (int kp = wave; 2 * kp < nkb; kp += U * NW) {
-        u32x4 w[U][NT][2];
-        Act<T> av[U][2];
-#pragma unroll
-        for (int s = 0; s < U; ++s)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int k = (2 * (kp + s * NW) + j) * KB;
-                const bool ok = k + g * E < K; // K is a multiple of E
-#pragma unroll
-                for (int t = 0; t < NT; ++t) w[s][t][j] = ok ? ld16_stream(wrow[t] + k) : zero16();
-                av[s][j] = (ok && row_live) ? load_act(act, aoff + k) : zero_act<T>();
-            }
-#pragma unroll
-        for (int s = 0; s < U; ++s)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int t = 0; t < NT; ++t) acc[t] = mma(acc[t], w[s][t][j], av[s][j]);
-    }
-
-    // fixed-order sum of the waves' partial tiles
-    __shared__ float red[NW][NT][4][64];
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) red[wave][t][v][lane] = acc[t][v];
-    __syncthreads();
-    if (wave != 0) return;
+    const int lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
     float r[NT][4];
 #pragma unroll
     for (int t = 0; t < NT; ++t)
@@ -181,20 +116,106 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(GemmArgs a) {
     }
 }
 
+// NW = wavefronts per workgroup (interleaved over K), U = 128-byte steps in flight per wave,
+// RT = row tiles (of 16 rows) per workgroup: blockIdx.y covers row tiles [blockIdx.y*RT, +RT)
+template <typename T, int EPI, int NW, int U, int RT>
+__global__ __launch_bounds__(NW * 64) void gemm_kernel(GemmArgs a) {
+    constexpr int E = Traits<T>::E, KB = 4 * E;
+    constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const int rt0 = blockIdx.y * RT;
+    const int K = a.K;
+
+    int n0[NT];
+    if constexpr (EPI == EPI_QKV) {
+        const int per_head = a.hd / 32;
+        const int hh = blockIdx.x / per_head; // head index over [q heads | k heads | v heads]
+        n0[0] = hh * a.hd + (blockIdx.x % per_head) * 16;
+        n0[1] = n0[0] + a.hd / 2;
+    } else if constexpr (EPI == EPI_SWIGLU) {
+        n0[0] = blockIdx.x * 16;
+        n0[1] = a.N + n0[0];
+    } else {
+        n0[0] = blockIdx.x * 16;
+    }
+    const int nrows_w = (EPI == EPI_SWIGLU) ? 2 * a.N : a.N;
+
+    const T *W = reinterpret_cast<const T *>(a.W);
+    const T *wrow[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        int n = n0[t] + c;
+        if (n > nrows_w - 1) n = nrows_w - 1; // ragged last tile: load a valid row, masked at the store
+        wrow[t] = W + (size_t)n * K + g * E;
+    }
+    ActPlanes<T> act{const_cast<T *>(reinterpret_cast<const T *>(a.act)), a.act_plane, a.ld_act};
+    size_t aoff[RT];
+    bool row_live[RT]; // rows past R contribute nothing: skip their loads
+#pragma unroll
+    for (int r = 0; r < RT; ++r) {
+        aoff[r] = (size_t)((rt0 + r) * 16 + c) * a.ld_act + g * E;
+        row_live[r] = (rt0 + r) * 16 + c < a.R;
+    }
+
+    f32x4 acc[RT][NT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // Each wave takes 128-byte steps (two k-blocks) of every row, interleaved with the other waves,
+    // U steps per iteration so that 2*U*NT weight loads are in flight per lane before the first MFMA.
+    const int nkb = (K + KB - 1) / KB;
+    for (int kp = wave; 2 * kp < nkb; kp += U * NW) {
+        u32x4 w[U][NT][2];
+        Act<T> av[U][2][RT];
+#pragma unroll
+        for (int s = 0; s < U; ++s)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int k = (2 * (kp + s * NW) + j) * KB;
+                const bool ok = k + g * E < K; // K is a multiple of E
+#pragma unroll
+                for (int t = 0; t < NT; ++t) w[s][t][j] = ok ? ld16_stream(wrow[t] + k) : zero16();
+#pragma unroll
+                for (int r = 0; r < RT; ++r) av[s][j][r] = (ok && row_live[r]) ? load_act(act, aoff[r] + k) : zero_act<T>();
+            }
+#pragma unroll
+        for (int s = 0; s < U; ++s)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < RT; ++r)
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) acc[r][t] = mma(acc[r][t], w[s][t][j], av[s][j][r]);
+    }
+
+    // fixed-order sum of the waves' partial tiles, one row tile at a time; wave 0 applies the epilogue
+    __shared__ float red[NW][NT][4][64];
+#pragma unroll
+    for (int r = 0; r < RT; ++r) {
+        if (r > 0) __syncthreads(); // wave 0 has read the previous row tile's partials
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) red[wave][t][v][lane] = acc[r][t][v];
+        __syncthreads();
+        if (wave == 0) tile_epilogue<T, EPI, NW>(a, red, n0, rt0 + r);
+    }
+}
+
 template <typename T, int EPI> static void launch_gemm_t(const GemmArgs &a, hipStream_t st) {
     int tiles;
     if (EPI == EPI_QKV) tiles = 3 * a.H * (a.hd / 32);
     else tiles = (a.N + 15) / 16;
-    dim3 grid(tiles, (a.R + 15) / 16);
-    static const int cfg = getenv("SS_GEMM_CFG") ? atoi(getenv("SS_GEMM_CFG")) : 0;
-    switch (cfg) {
-    case 1: hipLaunchKernelGGL((gemm_kernel<T, EPI, 8, 2>), grid, dim3(8 * 64), 0, st, a); break;
-    case 2: hipLaunchKernelGGL((gemm_kernel<T, EPI, 8, 4>), grid, dim3(8 * 64), 0, st, a); break;
-    case 3: hipLaunchKernelGGL((gemm_kernel<T, EPI, 4, 4>), grid, dim3(4 * 64), 0, st, a); break;
-    case 4: hipLaunchKernelGGL((gemm_kernel<T, EPI, 16, 1>), grid, dim3(16 * 64), 0, st, a); break;
-    case 5: hipLaunchKernelGGL((gemm_kernel<T, EPI, 4, 2>), grid, dim3(4 * 64), 0, st, a); break;
-    case 6: hipLaunchKernelGGL((gemm_kernel<T, EPI, 8, 1>), grid, dim3(8 * 64), 0, st, a); break;
-    default: hipLaunchKernelGGL((gemm_kernel<T, EPI, 16, 2>), grid, dim3(16 * 64), 0, st, a); break;
+    const int row_tiles = (a.R + 15) / 16;
+    if (row_tiles <= 1) { // the verify pass proper: 16 waves, two steps in flight
+        hipLaunchKernelGGL((gemm_kernel<T, EPI, 16, 2, 1>), dim3(tiles, 1), dim3(16 * 64), 0, st, a);
+    } else if (row_tiles <= 3) { // larger batches and prefill chunks: the weights are streamed once for all row tiles
+        hipLaunchKernelGGL((gemm_kernel<T, EPI, 8, 1, 3>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
+    } else {
+        hipLaunchKernelGGL((gemm_kernel<T, EPI, 8, 1, 5>), dim3(tiles, (row_tiles + 4) / 5), dim3(8 * 64), 0, st, a);
     }
 }
 
