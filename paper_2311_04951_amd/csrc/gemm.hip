@@ -21,24 +21,12 @@
 
 namespace ss {
 
-// Sum of the waves' partial tiles of row tile rt (fixed order) and the epilogue, by one wave.
-template <typename T, int EPI, int NW>
-__device__ __forceinline__ void tile_epilogue(const GemmArgs &a, const float (&red)[NW][(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1][4][64],
-                                              const int (&n0)[(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1], int rt) {
-    constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
+// Epilogue of one output tile by one wave: lane (c, g) holds r[t][v] = the value of row m = rt*16 + c,
+// column n0[t] + 4g + v.
+template <typename T, int EPI>
+__device__ __forceinline__ void apply_epilogue(const GemmArgs &a, const float (&r)[(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1][4],
+                                               const int (&n0)[(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1], int rt) {
     const int lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
-    float r[NT][4];
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            float sum = red[0][t][v][lane];
-#pragma unroll 4
-            for (int w2 = 1; w2 < NW; ++w2) sum += red[w2][t][v][lane];
-            r[t][v] = sum;
-        }
-
-    // lane (c, g) holds row m = rt*16 + c, columns n0 + 4g + v
     const int m = rt * 16 + c;
     if (m >= a.R) return;
 
@@ -114,6 +102,25 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, const float (&r
             }
         }
     }
+}
+
+// Sum of the waves' partial tiles of row tile rt (fixed order) and the epilogue, by one wave.
+template <typename T, int EPI, int NW>
+__device__ __forceinline__ void tile_epilogue(const GemmArgs &a, const float (&red)[NW][(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1][4][64],
+                                              const int (&n0)[(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1], int rt) {
+    constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
+    const int lane = threadIdx.x & 63;
+    float r[NT][4];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            float sum = red[0][t][v][lane];
+#pragma unroll 4
+            for (int w2 = 1; w2 < NW; ++w2) sum += red[w2][t][v][lane];
+            r[t][v] = sum;
+        }
+    apply_epilogue<T, EPI>(a, r, n0, rt);
 }
 
 // NW = wavefronts per workgroup (interleaved over K), U = 128-byte steps in flight per wave,
@@ -205,17 +212,200 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(GemmArgs a) {
     }
 }
 
+// More than 16 rows (larger batches, prefill): the waves of a workgroup split the output columns instead
+// of K, so that all of them walk K together and share the activation rows through LDS - with R rows
+// the activations a wave needs are R*4/32 times its weight bytes, too much to fetch per wave from L2.
+//   * wave w owns the 16 (or, fused epilogues, 2 x 16) weight rows of tile blockIdx.x*NW + w and the
+//     complete K sum of its outputs: no reduction across waves;
+//   * K is walked in slabs of 256 bytes per row: the workgroup copies the slab of all RT*16 rows into
+//     LDS (double-buffered), every wave multiplies its weight chunks with every row tile;
+//   * the weight chunks of the next slab are requested before the current slab's arithmetic.
+constexpr int WIDE_SLAB_BYTES = 256;              // bytes of K per row, plane and slab
+template <typename T> struct WideSmem {
+    static constexpr int KS = WIDE_SLAB_BYTES / (int)sizeof(T); // elements of K per slab
+    static constexpr int PITCH = WIDE_SLAB_BYTES + 48;          // bytes per row, padded against bank conflicts
+};
+
+template <typename T, int EPI, int NW, int RT>
+__global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
+    constexpr int E = Traits<T>::E, KB = 4 * E, PL = Traits<T>::PLANES;
+    constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
+    constexpr int WIDE_KS = WideSmem<T>::KS;
+    constexpr int KBS = WIDE_KS / KB;             // k-blocks per slab
+    constexpr int PITCH = WideSmem<T>::PITCH;
+    constexpr int ROWS = RT * 16;
+    constexpr int BUF = PL * ROWS * PITCH;        // bytes of one slab buffer
+    extern __shared__ __align__(16) unsigned char wide_smem[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const int rt0 = blockIdx.y * RT;
+    const int K = a.K;
+    const int tile = blockIdx.x * NW + wave;
+
+    int ntiles;
+    int n0[NT];
+    if constexpr (EPI == EPI_QKV) {
+        const int per_head = a.hd / 32;
+        ntiles = 3 * a.H * per_head;
+        const int tl = min(tile, ntiles - 1);
+        const int hh = tl / per_head; // head index over [q heads | k heads | v heads]
+        n0[0] = hh * a.hd + (tl % per_head) * 16;
+        n0[1] = n0[0] + a.hd / 2;
+    } else if constexpr (EPI == EPI_SWIGLU) {
+        ntiles = (a.N + 15) / 16;
+        n0[0] = min(tile, ntiles - 1) * 16;
+        n0[1] = a.N + n0[0];
+    } else {
+        ntiles = (a.N + 15) / 16;
+        n0[0] = min(tile, ntiles - 1) * 16;
+    }
+    const bool tile_live = tile < ntiles; // a dead wave still helps with the slab copies and barriers
+    const int nrows_w = (EPI == EPI_SWIGLU) ? 2 * a.N : a.N;
+
+    const T *W = reinterpret_cast<const T *>(a.W);
+    const T *wrow[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        int n = n0[t] + c;
+        if (n > nrows_w - 1) n = nrows_w - 1; // ragged last tile: load a valid row, masked at the store
+        wrow[t] = W + (size_t)n * K + g * E;
+    }
+    const T *act = reinterpret_cast<const T *>(a.act);
+
+    // Every load below is unconditional (addresses are clamped into the operand, and what must be zero
+    // is selected afterwards) and pinned in program order by empty asm statements: a fixed number of
+    // loads per step is what lets the compiler wait for the oldest group with an exact count while the
+    // younger ones stay in flight; without the pins it sinks each load next to its use.
+    // slab copy: the (plane, row) pairs are spread over the threads in 16-byte units
+    constexpr int UNITS_PER_ROW = WIDE_KS * (int)sizeof(T) / 16;
+    constexpr int UNITS = PL * ROWS * UNITS_PER_ROW;
+    constexpr int UPT = (UNITS + NW * 64 - 1) / (NW * 64); // units per thread
+    constexpr int EPU = 16 / (int)sizeof(T);              // elements per unit
+    auto slab_load = [&](int k0, u32x4 (&v)[UPT]) {
+#pragma unroll
+        for (int i = 0; i < UPT; ++i) {
+            const int u = min((int)threadIdx.x + i * NW * 64, UNITS - 1);
+            const int pr = u / UNITS_PER_ROW, x = u % UNITS_PER_ROW;
+            const int pl = pr / ROWS, row = rt0 * 16 + pr % ROWS;
+            const int k = k0 + x * EPU;
+            const bool ok = row < a.R && k < K; // K is a multiple of the unit
+            const u32x4 t = ld16(act + pl * a.act_plane + (size_t)min(row, a.R - 1) * a.ld_act + min(k, K - EPU));
+            v[i] = ok ? t : zero16();
+        }
+        asm volatile("" ::: "memory");
+    };
+    auto slab_store = [&](int buf, const u32x4 (&v)[UPT]) {
+#pragma unroll
+        for (int i = 0; i < UPT; ++i) {
+            const int u = threadIdx.x + i * NW * 64;
+            const int pr = u / UNITS_PER_ROW, x = u % UNITS_PER_ROW;
+            if (u < UNITS) *reinterpret_cast<u32x4 *>(wide_smem + (size_t)buf * BUF + (size_t)pr * PITCH + x * 16) = v[i];
+        }
+    };
+    // weights beyond K (ragged tail, padding slabs) are read from a clamped address: the activations
+    // there are zero, so whatever finite weight comes back contributes nothing
+    auto w_load = [&](int k0, u32x4 (&w)[NT][KBS]) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int kb = 0; kb < KBS; ++kb) w[t][kb] = ld16_stream(wrow[t] + min(k0 + kb * KB, K - (g + 1) * E));
+        asm volatile("" ::: "memory");
+    };
+
+    f32x4 acc[RT][NT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    constexpr int WD = 3; // weight slabs in registers: the one being multiplied and two in flight
+    const int nslab = (K + WIDE_KS - 1) / WIDE_KS;
+    const int nstep = (nslab + WD - 1) / WD * WD; // padded: the ring position of a step is a compile-time constant
+    u32x4 wring[WD][NT][KBS];
+    u32x4 sv[UPT];
+    slab_load(0, sv);
+    w_load(0, wring[0]);
+    w_load(WIDE_KS, wring[1]);
+    slab_store(0, sv);
+    __syncthreads();
+    auto step = [&](int s, u32x4 (&wcur)[NT][KBS], u32x4 (&wfill)[NT][KBS]) {
+        slab_load((s + 1) * WIDE_KS, sv);   // next activation slab (zeros past K)
+        w_load((s + 2) * WIDE_KS, wfill);   // weights two slabs ahead
+        const unsigned char *base = wide_smem + (size_t)(s & 1) * BUF + (size_t)c * PITCH + g * 16;
+        // the LDS reads of k-block kb+1 are issued before the MFMAs of k-block kb (the scheduling
+        // barriers keep the compiler from sinking them next to their uses, which serialises every
+        // MFMA behind an LDS round trip)
+        auto read_av = [&](int kb, Act<T> (&av)[RT]) {
+#pragma unroll
+            for (int r = 0; r < RT; ++r)
+#pragma unroll
+                for (int pl = 0; pl < PL; ++pl)
+                    av[r].p[pl] = *reinterpret_cast<const u32x4 *>(base + (size_t)(pl * ROWS + r * 16) * PITCH + kb * (KB * (int)sizeof(T)));
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        Act<T> av[2][RT];
+        read_av(0, av[0]);
+#pragma unroll
+        for (int kb = 0; kb < KBS; ++kb) {
+            if (kb + 1 < KBS) read_av(kb + 1, av[(kb + 1) & 1]);
+#pragma unroll
+            for (int r = 0; r < RT; ++r)
+#pragma unroll
+                for (int t = 0; t < NT; ++t) acc[r][t] = mma(acc[r][t], wcur[t][kb], av[kb & 1][r]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        slab_store((s + 1) & 1, sv); // the other buffer: its readers finished before the last barrier
+        __syncthreads();
+    };
+    for (int s0 = 0; s0 < nstep; s0 += WD) {
+        step(s0, wring[0], wring[2]);
+        step(s0 + 1, wring[1], wring[0]);
+        step(s0 + 2, wring[2], wring[1]);
+    }
+    if (!tile_live) return;
+#pragma unroll
+    for (int r = 0; r < RT; ++r) {
+        float out[NT][4];
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) out[t][v] = acc[r][t][v];
+        apply_epilogue<T, EPI>(a, out, n0, rt0 + r);
+    }
+}
+
+template <typename T, int EPI, int NW, int RT> static void launch_wide(const GemmArgs &a, int tiles, int row_tiles, hipStream_t st) {
+    constexpr size_t smem = 2 * (size_t)Traits<T>::PLANES * RT * 16 * WideSmem<T>::PITCH;
+    static bool attr_done = false; // more than 64 KB of dynamic LDS has to be allowed once per kernel
+    if (!attr_done) {
+        (void)hipFuncSetAttribute((const void *)gemm_wide_kernel<T, EPI, NW, RT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((gemm_wide_kernel<T, EPI, NW, RT>), dim3((tiles + NW - 1) / NW, (row_tiles + RT - 1) / RT), dim3(NW * 64), smem, st, a);
+}
+
 template <typename T, int EPI> static void launch_gemm_t(const GemmArgs &a, hipStream_t st) {
     int tiles;
     if (EPI == EPI_QKV) tiles = 3 * a.H * (a.hd / 32);
     else tiles = (a.N + 15) / 16;
     const int row_tiles = (a.R + 15) / 16;
-    if (row_tiles <= 1) { // the verify pass proper: 16 waves, two steps in flight
+    if (row_tiles <= 1) { // the verify pass proper: 16 waves split K, two steps in flight
         hipLaunchKernelGGL((gemm_kernel<T, EPI, 16, 2, 1>), dim3(tiles, 1), dim3(16 * 64), 0, st, a);
-    } else if (row_tiles <= 3) { // larger batches and prefill chunks: the weights are streamed once for all row tiles
-        hipLaunchKernelGGL((gemm_kernel<T, EPI, 8, 1, 3>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
+        return;
+    }
+    // larger batches and prefill chunks: waves split the columns; fewer waves per workgroup when the
+    // matrix has few tiles, so that the launch still covers the chip
+    constexpr bool FUSED = EPI == EPI_SWIGLU || EPI == EPI_QKV; // two weight tiles per wave: more registers
+    const bool small = tiles < 8 * 128;
+    if (row_tiles <= 2) {
+        if (small) launch_wide<T, EPI, 4, 2>(a, tiles, row_tiles, st);
+        else launch_wide<T, EPI, 8, 2>(a, tiles, row_tiles, st);
+    } else if (row_tiles <= 3) {
+        if (small) launch_wide<T, EPI, 4, 3>(a, tiles, row_tiles, st);
+        else launch_wide<T, EPI, 8, 3>(a, tiles, row_tiles, st);
     } else {
-        hipLaunchKernelGGL((gemm_kernel<T, EPI, 8, 1, 5>), dim3(tiles, (row_tiles + 4) / 5), dim3(8 * 64), 0, st, a);
+        if (small || FUSED) launch_wide<T, EPI, 4, 5>(a, tiles, row_tiles, st);
+        else launch_wide<T, EPI, 8, 5>(a, tiles, row_tiles, st);
     }
 }
 

@@ -77,17 +77,18 @@ def test_rollback_then_reverify_matches_oracle(persistent):
     assert maxabs(got, ref) < tol(shape)
 
 
-@pytest.mark.parametrize("B,M,persistent", [(3, 9, False), (3, 5, True), (3, 5, False)])
+@pytest.mark.parametrize("B,M,persistent", [(3, 9, False), (3, 5, True), (3, 5, False), (5, 9, False), (8, 9, False)])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_batched_ragged_lengths_match_per_sequence_oracle(dtype, B, M, persistent):
-    """Three sequences with different context lengths verified in one call; each must equal the
-    oracle run on that sequence alone.  Contexts are built with the raw append."""
+    """Several sequences with different context lengths verified in one call (up to 72 rows: every
+    row-tile variant of the GEMMs); each must equal the oracle run on that sequence alone.  Contexts
+    are built with the raw append."""
     shape = si.DecoderShape(2, 128, 2, 64, 344, 512, dtype=dtype)
     w = si.decoder_weights(shape, seed=6)
     om = oracle.Model(shape, w)
-    gm = sv.Model(shape, weights_to_device(w), max_rows=48, max_pos=512)
+    gm = sv.Model(shape, weights_to_device(w), max_rows=80, max_pos=512)
     sv.ss_model_set_persistent(gm, persistent)
-    lens = [70, 3, 129]
+    lens = [70, 3, 129, 40, 1, 100, 64, 17][:B]
     gkv = sv.KVCache(gm, B, 200)
     toks = si.token_ids(6, "toks", (B, M), shape.vocab)
     refs = []
@@ -104,9 +105,10 @@ def test_batched_ragged_lengths_match_per_sequence_oracle(dtype, B, M, persisten
         assert maxabs(got[b], refs[b]) < tol(shape), b
     assert sv.ss_kv_cache_get_len(gkv).tolist() == [l + M for l in lens]
     # ragged roll-back: different accept counts per sequence
-    na = torch.tensor([0, M - 1, 3], dtype=torch.int32, device=dev())
+    acc = [0, M - 1, 3, M - 1, 0, 1, 2, 4][:B]
+    na = torch.tensor(acc, dtype=torch.int32, device=dev())
     sv.ss_kv_cache_rollback(gkv, na, M)
-    assert sv.ss_kv_cache_get_len(gkv).tolist() == [lens[0] + 1, lens[1] + M, lens[2] + 4]
+    assert sv.ss_kv_cache_get_len(gkv).tolist() == [l + a + 1 for l, a in zip(lens, acc)]
 
 
 @pytest.mark.parametrize("persistent", PATHS)
