@@ -23,6 +23,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK = 8.0e12  # B/s, MI355X published peak
+PERSISTENT_7B_TRAFFIC_BYTES = 13.642e9  # 13.470 GB fetched + 0.172 GB written per launch (rocprofv3 --pmc, see profiles/)
 
 
 def build_7b(si, sv, torch, seed, n_layers, dev):
@@ -256,8 +257,12 @@ def main():
         k_name = "gemm_kernel<bf16, SWIGLU> (gate/up projection, 42.8% of the pass's bytes)"
         k_us = gu["avg_us"]
     achieved = k_bytes / (k_us * 1e-6) / 1e9
+    # HBM bytes per launch from the FETCH_SIZE and WRITE_SIZE counters of two rocprofv3 --pmc runs, each scaled by
+    # what the same counter reads for a plain 1 GiB device copy (profiles/verify_pass_7b_persistent_hbm_traffic.txt);
+    # it is a measurement of the default workload only
+    traffic = PERSISTENT_7B_TRAFFIC_BYTES if ("verify_persistent" in classes and args.layers == 32 and K == 4) else None
     roofline = {"bound": "hbm", "kernel": k_name, "achieved": achieved, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                "frac": achieved / (HBM_PEAK / 1e9), "traffic": None, "algorithmic_bytes_per_launch": k_bytes,
+                "frac": achieved / (HBM_PEAK / 1e9), "traffic": traffic, "algorithmic_bytes_per_launch": k_bytes,
                 "avg_launch_us": k_us}
 
     out = {
