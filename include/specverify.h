@@ -101,7 +101,7 @@ int ss_model_create(const ss_model_cfg *cfg, const ss_weights *weights, ss_model
 int ss_model_destroy(ss_model *model);
 
 /* Selects how the forward path of `model` is launched.  1 (default wherever the kernel can be
- * co-resident on the device): calls whose rows (batch * M) fit the kernel's LDS activation slab (8
+ * co-resident on the device): calls whose rows (batch * M) fit the kernel's LDS activation slab (9
  * rows for bf16 models, 16 for fp32) run as ONE persistent cooperative kernel
  * (one workgroup per compute unit, device-wide barriers between phases, RMSNorm folded into the
  * GEMMs, weight loads of the next phase in flight across each barrier); larger calls always use one

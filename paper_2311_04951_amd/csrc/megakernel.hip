@@ -179,7 +179,7 @@ constexpr int SLAB_ROW_BYTES = SLAB_CK * CH * MNW * 128; // 8192: the K range on
 constexpr int SLAB_PITCH = SLAB_ROW_BYTES + 48; // padded against LDS bank conflicts between rows
 
 // LDS: [ union: activation slab | attention merge area ][ red ][ small ]
-constexpr int STASH_TILES = 8; // reduced tiles kept in LDS until the epilogue flush
+constexpr int STASH_TILES = 6; // reduced tiles kept in LDS until the epilogue flush
 
 struct MegaSmemTail {
     float red[2][MNW][4][64]; // partial tiles, double-buffered
@@ -388,22 +388,24 @@ static_assert(MEGA_THREADS / 32 * 2 >= 16, "two halves of the scale loads cover 
 // whole copy costs one memory round trip, and slab_finish() writes the data to LDS.  Other loads may
 // be issued between the two: loads return in order, so the slab does not wait for them.
 constexpr int SLAB_UNITS = SLAB_ROW_BYTES / 8 / MEGA_THREADS; // 8-byte units per thread and slab row
-template <int NPR> struct SlabLoads { // NPR: upper bound of the (plane, row) pairs in the slab
+template <int NPR> struct SlabLoads { // NPR: (plane, row) pairs per batch
     unsigned long long v[NPR][SLAB_UNITS]; // [(plane, row) pair][unit]
     ScaleLoads sl;
 };
 template <typename T, int NPR>
-__device__ __forceinline__ void slab_issue(const MegaCall &P, const MegaPhase &ph, int slab, int G, bool with_scales, SlabLoads<NPR> &L) {
+__device__ __forceinline__ void slab_issue(const MegaCall &P, const MegaPhase &ph, int slab, int pr0, int G, bool with_scales,
+                                           SlabLoads<NPR> &L) {
     constexpr int PL = Traits<T>::PLANES;
     constexpr int PER8 = 8 / (int)sizeof(T); // elements per 8-byte unit
     const bool head = ph.kind == PH_HEAD;
     const int rows = P.slab_rows;
     const int nlive = head ? P.head_rows : P.R;
     const ActPlanes<T> src_planes = act_planes<T>(P, ph.act_src);
-    const int nrow = PL * rows; // (plane, row) pairs, at most NPR
+    const int nrow = PL * rows; // (plane, row) pairs; this call takes pairs pr0 .. pr0 + NPR - 1
     if (with_scales) scales_issue(P, G, L.sl);
 #pragma unroll
-    for (int pr = 0; pr < NPR; ++pr) {
+    for (int i = 0; i < NPR; ++i) {
+        const int pr = pr0 + i;
         if (pr < nrow) {
             const int r = pr % rows, pl = pr / rows;
             const int brow = head ? P.head_row0 + r * P.head_stride : r;
@@ -412,24 +414,26 @@ __device__ __forceinline__ void slab_issue(const MegaCall &P, const MegaPhase &p
             for (int h2 = 0; h2 < SLAB_UNITS; ++h2) {
                 const int x = threadIdx.x + h2 * MEGA_THREADS;
                 const int k = slab * (SLAB_ROW_BYTES / (int)sizeof(T)) + x * PER8;
-                L.v[pr][h2] = (r < nlive && k < ph.K) ? ld_coh64(src + k) : 0ull;
+                L.v[i][h2] = (r < nlive && k < ph.K) ? ld_coh64(src + k) : 0ull;
             }
         }
     }
 }
 template <typename T, int NPR>
-__device__ __forceinline__ void slab_finish(const MegaCall &P, int G, bool with_scales, const SlabLoads<NPR> &L, MegaSmem &sm) {
+__device__ __forceinline__ void slab_finish(const MegaCall &P, int pr0, int G, bool with_scales, const SlabLoads<NPR> &L, MegaSmem &sm) {
     const int nrow = Traits<T>::PLANES * P.slab_rows;
     if (with_scales) scales_finish(P, G, L.sl, sm);
 #pragma unroll
-    for (int pr = 0; pr < NPR; ++pr)
+    for (int i = 0; i < NPR; ++i) {
+        const int pr = pr0 + i;
         if (pr < nrow) {
 #pragma unroll
             for (int h2 = 0; h2 < SLAB_UNITS; ++h2) {
                 const int x = threadIdx.x + h2 * MEGA_THREADS;
-                *reinterpret_cast<unsigned long long *>(sm.u + (size_t)pr * SLAB_PITCH + x * 8) = L.v[pr][h2];
+                *reinterpret_cast<unsigned long long *>(sm.u + (size_t)pr * SLAB_PITCH + x * 8) = L.v[i][h2];
             }
         }
+    }
 }
 
 // ---------------------------------------------------------------- GEMM chunk + tile epilogue
@@ -690,28 +694,30 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
             const int grp_chunks = multi ? grp_end - cc.ck : (cc.r.ntiles - cc.tile) * cc.nck - cc.ck;
             const int grp_rounds = (grp_chunks + RING - 1) / RING;
             const bool last_group = multi ? (cc.tile + 1 == cc.r.ntiles && grp_end == cc.nck) : true;
-            const int tiles_per_round = multi ? 1 : RING / cc.nck + 1;
-            const int n = min(grp_rounds, max(1, (STASH_TILES - nstash) / tiles_per_round));
+            // rounds the stash has room for: n rounds from chunk ck of a tile complete at most (ck + n*RING) / nck tiles
+            auto stash_room = [&]() { return multi ? STASH_TILES - nstash : ((STASH_TILES - nstash) * cc.nck - cc.ck) / RING; };
+            const int n = min(grp_rounds, stash_room()); // >= 1: the stash is flushed below whenever no round fits
             const bool final_round = last_group && n == grp_rounds; // the phase ends with this segment
             const int tag = (p << 8) | (cc.ck / SLAB_CK);
             if (st.slab_tag != tag) {
                 lds_barrier(); // every wave is done with the previous slab
                 const bool ws = want_scales && cc.idx == 0; // first slab of the phase: with the row scales
-                auto reload = [&](auto npr_c) {
-                    SlabLoads<decltype(npr_c)::value> L;
-                    slab_issue<T>(P, ph, cc.ck / SLAB_CK, G, ws, L);
+                // batches of 10 (plane, row) pairs, one memory round trip each (5 rows of a bf16 model: one batch)
+                auto batch = [&](int pr0, bool scales) {
+                    SlabLoads<10> L;
+                    slab_issue<T>(P, ph, cc.ck / SLAB_CK, pr0, G, scales, L);
                     asm volatile("" ::: "memory"); // keeps the compiler from fusing the two loops (load, wait, store per row)
-                    slab_finish<T>(P, G, ws, L, sm);
+                    slab_finish<T>(P, pr0, G, scales, L, sm);
                 };
-                if (Traits<T>::PLANES * P.slab_rows <= 10) reload(std::integral_constant<int, 10>{});
-                else reload(std::integral_constant<int, 16>{});
+                batch(0, ws);
+                if (Traits<T>::PLANES * P.slab_rows > 10) batch(10, false);
                 if (P.timeline && threadIdx.x == 0 && cc.idx == 0) P.timeline[(size_t)(5 * p + 2) * G + wg] = wall_clock64();
                 lds_barrier();
                 st.slab_tag = tag;
             }
             run_segment(final_round ? n - 1 : n, final_round);
             if (P.timeline && threadIdx.x == 0 && final_round) P.timeline[(size_t)(5 * p + 3) * G + wg] = wall_clock64();
-            if (final_round || nstash + tiles_per_round > STASH_TILES) flush_stash<T>(P, ph, my, nstash, st.rowsq, final_round, sm);
+            if (final_round || stash_room() < 1) flush_stash<T>(P, ph, my, nstash, st.rowsq, final_round, sm);
         }
         if (ph.kind == PH_RESID) {
             // publish this workgroup's partial sums of squares of the new hidden rows

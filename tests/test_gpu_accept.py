@@ -29,7 +29,8 @@ def _dists(seed, B, K, V, zero_frac=0.0):
     return p, q
 
 
-@pytest.mark.parametrize("B,K,V", [(3, 4, 1024), (5, 8, 1000), (2, 1, 50), (4, 0, 333), (64, 8, 4099), (2, 15, 32000)])
+@pytest.mark.parametrize("B,K,V", [(3, 4, 1024), (5, 8, 1000), (2, 1, 50), (4, 0, 333), (64, 8, 4099), (2, 15, 32000),
+                                   (3, 4, 40001), (1, 2, 131071)])   # the last two: several vocabulary segments, rows not 16-byte aligned
 def test_speculative_accept_bit_exact(B, K, V):
     p, q = _dists(B * 1000 + K, B, K, V, zero_frac=0.3 if V < 2000 else 0.0)
     # draft tokens drawn from q by the oracle's sampler so that acceptance is non-trivial
