@@ -387,16 +387,16 @@ static_assert(MEGA_THREADS / 32 * 2 >= 16, "two halves of the scale loads cover 
 // slab_issue() puts every load in flight (with_scales: also the loads of the phase's row scales), so the
 // whole copy costs one memory round trip, and slab_finish() writes the data to LDS.  Other loads may
 // be issued between the two: loads return in order, so the slab does not wait for them.
-constexpr int SLAB_UNITS = SLAB_ROW_BYTES / 8 / MEGA_THREADS; // 8-byte units per thread and slab row
+constexpr int SLAB_UNITS = SLAB_ROW_BYTES / 16 / MEGA_THREADS; // 16-byte units per thread and slab row
 template <int NPR> struct SlabLoads { // NPR: (plane, row) pairs per batch
-    unsigned long long v[NPR][SLAB_UNITS]; // [(plane, row) pair][unit]
+    u32x4 v[NPR][SLAB_UNITS]; // [(plane, row) pair][unit]
     ScaleLoads sl;
 };
 template <typename T, int NPR>
 __device__ __forceinline__ void slab_issue(const MegaCall &P, const MegaPhase &ph, int slab, int pr0, int G, bool with_scales,
                                            SlabLoads<NPR> &L) {
     constexpr int PL = Traits<T>::PLANES;
-    constexpr int PER8 = 8 / (int)sizeof(T); // elements per 8-byte unit
+    constexpr int PER16 = 16 / (int)sizeof(T); // elements per 16-byte unit
     const bool head = ph.kind == PH_HEAD;
     const int rows = P.slab_rows;
     const int nlive = head ? P.head_rows : P.R;
@@ -409,12 +409,12 @@ __device__ __forceinline__ void slab_issue(const MegaCall &P, const MegaPhase &p
         if (pr < nrow) {
             const int r = pr % rows, pl = pr / rows;
             const int brow = head ? P.head_row0 + r * P.head_stride : r;
-            const T *src = src_planes.base + pl * src_planes.plane + (size_t)brow * src_planes.ld;
+            const size_t row_off = pl * src_planes.plane + (size_t)brow * src_planes.ld; // elements
 #pragma unroll
             for (int h2 = 0; h2 < SLAB_UNITS; ++h2) {
                 const int x = threadIdx.x + h2 * MEGA_THREADS;
-                const int k = slab * (SLAB_ROW_BYTES / (int)sizeof(T)) + x * PER8;
-                L.v[i][h2] = (r < nlive && k < ph.K) ? ld_coh64(src + k) : 0ull;
+                const int k = slab * (SLAB_ROW_BYTES / (int)sizeof(T)) + x * PER16; // K is a multiple of the unit
+                L.v[i][h2] = (r < nlive && k < ph.K) ? ld16_coh_buf(src_planes.base, (uint32_t)((row_off + k) * sizeof(T))) : zero16();
             }
         }
     }
@@ -430,7 +430,7 @@ __device__ __forceinline__ void slab_finish(const MegaCall &P, int pr0, int G, b
 #pragma unroll
             for (int h2 = 0; h2 < SLAB_UNITS; ++h2) {
                 const int x = threadIdx.x + h2 * MEGA_THREADS;
-                *reinterpret_cast<unsigned long long *>(sm.u + (size_t)pr * SLAB_PITCH + x * 8) = L.v[i][h2];
+                *reinterpret_cast<u32x4 *>(sm.u + (size_t)pr * SLAB_PITCH + x * 16) = L.v[i][h2];
             }
         }
     }

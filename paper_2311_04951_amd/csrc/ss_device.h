@@ -155,10 +155,16 @@ __device__ __forceinline__ u32x4 ld16_coh(const void *p) {
     const unsigned long long a = ld_coh64(p), b = ld_coh64(reinterpret_cast<const char *>(p) + 8);
     return u32x4{(uint32_t)a, (uint32_t)(a >> 32), (uint32_t)b, (uint32_t)(b >> 32)};
 }
+// 16-byte agent-coherent load (sc0 sc1: performed at the memory side, like the relaxed agent-scope
+// atomics above, but four dwords per lane) through a raw buffer resource over `base`; `byte_off` < 4 GiB
+__device__ __forceinline__ u32x4 ld16_coh_buf(const void *base, uint32_t byte_off) {
+    const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, 0x7fffffff, 0x00020000);
+    return __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 1 | 16);
+}
 template <typename T> __device__ __forceinline__ Act<T> load_act_coh(const ActPlanes<T> &a, size_t off) {
     Act<T> r;
 #pragma unroll
-    for (int pl = 0; pl < Traits<T>::PLANES; ++pl) r.p[pl] = ld16_coh(a.base + pl * a.plane + off);
+    for (int pl = 0; pl < Traits<T>::PLANES; ++pl) r.p[pl] = ld16_coh_buf(a.base, (uint32_t)((pl * a.plane + off) * sizeof(T)));
     return r;
 }
 __device__ __forceinline__ void store_act_coh(const ActPlanes<bf16_t> &a, size_t off, float x) {
