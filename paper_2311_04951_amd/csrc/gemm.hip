@@ -217,25 +217,48 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(GemmArgs a) {
 // the activations a wave needs are R*4/32 times its weight bytes, too much to fetch per wave from L2.
 //   * wave w owns the 16 (or, fused epilogues, 2 x 16) weight rows of tile blockIdx.x*NW + w and the
 //     complete K sum of its outputs: no reduction across waves;
-//   * K is walked in slabs of 256 bytes per row: the workgroup copies the slab of all RT*16 rows into
-//     LDS (double-buffered), every wave multiplies its weight chunks with every row tile;
-//   * the weight chunks of the next slab are requested before the current slab's arithmetic.
-constexpr int WIDE_SLAB_BYTES = 256;              // bytes of K per row, plane and slab
-template <typename T> struct WideSmem {
-    static constexpr int KS = WIDE_SLAB_BYTES / (int)sizeof(T); // elements of K per slab
-    static constexpr int PITCH = WIDE_SLAB_BYTES + 48;          // bytes per row, padded against bank conflicts
-};
+//   * K is walked in slabs of 256 bytes per row.  The slab of all RT*16 rows goes from memory straight
+//     into LDS (global_load_lds, no registers), two steps ahead of its use, into one of three buffers;
+//     a 1 KB load instruction carries four rows, and the 16-byte units of a row are stored at position
+//     (unit ^ row) so that the 16 rows a wave reads together hit different banks without padding;
+//   * three weight slabs per wave in registers (one being multiplied, two in flight).
+// Every step issues the same number of memory instructions (addresses are clamped into the operands; weights
+// past K are zeroed after the load, so whatever finite activation sits there contributes nothing): the
+// waits on "the loads issued two steps ago" are exact counts.
+constexpr int WIDE_SLAB_BYTES = 256; // bytes of K per row, plane and slab
+
+// acc0 / acc1 += one weight chunk x one activation k-block, into two independent accumulators
+__device__ __forceinline__ void mma_split(f32x4 &acc0, f32x4 &acc1, u32x4 w, const Act<bf16_t> &b, int) {
+    const bf16x8 av = __builtin_bit_cast(bf16x8, w);
+    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, b.p[0]), acc0, 0, 0, 0);
+    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, b.p[1]), acc1, 0, 0, 0);
+}
+__device__ __forceinline__ void mma_split(f32x4 &acc0, f32x4 &acc1, u32x4 w, const Act<float> &b, int kb) {
+    if (kb & 1) acc1 = mma(acc1, w, b);
+    else acc0 = mma(acc0, w, b);
+}
+
+__device__ __forceinline__ void wide_barrier() { // workgroup barrier that orders LDS traffic only (no vmcnt(0))
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+    __builtin_amdgcn_s_barrier();
+}
+template <int N> __device__ __forceinline__ void wait_vmcnt_at_most() { // s_waitcnt vmcnt(N), N < 64
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
 
 template <typename T, int EPI, int NW, int RT>
 __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
     constexpr int E = Traits<T>::E, KB = 4 * E, PL = Traits<T>::PLANES;
     constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
-    constexpr int WIDE_KS = WideSmem<T>::KS;
-    constexpr int KBS = WIDE_KS / KB;             // k-blocks per slab
-    constexpr int PITCH = WideSmem<T>::PITCH;
+    constexpr int WIDE_KS = WIDE_SLAB_BYTES / (int)sizeof(T); // elements of K per slab
+    constexpr int KBS = WIDE_KS / KB;                         // k-blocks per slab (4)
+    constexpr int EPU = 16 / (int)sizeof(T);                  // elements per 16-byte unit
     constexpr int ROWS = RT * 16;
-    constexpr int BUF = PL * ROWS * PITCH;        // bytes of one slab buffer
-    extern __shared__ __align__(16) unsigned char wide_smem[];
+    constexpr int BUF = PL * ROWS * WIDE_SLAB_BYTES;          // bytes of one slab buffer
+    constexpr int GROUPS = PL * ROWS / 4;                     // 1 KB load instructions per slab (4 rows each)
+    constexpr int DPW = (GROUPS + NW - 1) / NW;               // ... per wave
+    constexpr int WN = NT * KBS;                              // weight loads per wave and step
+    __shared__ __align__(16) unsigned char slab0[BUF], slab1[BUF], slab2[BUF];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 15, g = lane >> 4;
     const int rt0 = blockIdx.y * RT;
@@ -271,67 +294,67 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
         wrow[t] = W + (size_t)n * K + g * E;
     }
     const T *act = reinterpret_cast<const T *>(a.act);
+    const int nslab = (K + WIDE_KS - 1) / WIDE_KS;
 
-    // Every load below is unconditional (addresses are clamped into the operand, and what must be zero
-    // is selected afterwards) and pinned in program order by empty asm statements: a fixed number of
-    // loads per step is what lets the compiler wait for the oldest group with an exact count while the
-    // younger ones stay in flight; without the pins it sinks each load next to its use.
-    // slab copy: the (plane, row) pairs are spread over the threads in 16-byte units
-    constexpr int UNITS_PER_ROW = WIDE_KS * (int)sizeof(T) / 16;
-    constexpr int UNITS = PL * ROWS * UNITS_PER_ROW;
-    constexpr int UPT = (UNITS + NW * 64 - 1) / (NW * 64); // units per thread
-    constexpr int EPU = 16 / (int)sizeof(T);              // elements per unit
-    auto slab_load = [&](int k0, u32x4 (&v)[UPT]) {
+    // slab s -> LDS: this wave's DPW instructions; lane l brings row (l / 16) of its 4-row group, LDS unit l % 16
+    typedef const void __attribute__((address_space(1))) *gptr;
+    typedef void __attribute__((address_space(3))) *lptr;
+    const int r4 = lane >> 4, q = lane & 15;
+    auto slab_dma = [&](int sl, unsigned char *buf) {
+        const int k0 = min(sl, nslab - 1) * WIDE_KS; // past the end: any valid slab (its weights are zero)
 #pragma unroll
-        for (int i = 0; i < UPT; ++i) {
-            const int u = min((int)threadIdx.x + i * NW * 64, UNITS - 1);
-            const int pr = u / UNITS_PER_ROW, x = u % UNITS_PER_ROW;
-            const int pl = pr / ROWS, row = rt0 * 16 + pr % ROWS;
-            const int k = k0 + x * EPU;
-            const bool ok = row < a.R && k < K; // K is a multiple of the unit
-            const u32x4 t = ld16(act + pl * a.act_plane + (size_t)min(row, a.R - 1) * a.ld_act + min(k, K - EPU));
-            v[i] = ok ? t : zero16();
+        for (int i = 0; i < DPW; ++i) {
+            const int grp = min(wave * DPW + i, GROUPS - 1); // a surplus instruction repeats the last group
+            const int pr = 4 * grp + r4, pl = pr / ROWS, row = pr % ROWS;
+            const int k = min(k0 + (q ^ (row & 15)) * EPU, a.ld_act - EPU);
+            const T *src = act + pl * a.act_plane + (size_t)min(rt0 * 16 + row, a.R - 1) * a.ld_act + k;
+            __builtin_amdgcn_global_load_lds((gptr)src, (lptr)(buf + grp * 1024), 16, 0, 0);
         }
         asm volatile("" ::: "memory");
     };
-    auto slab_store = [&](int buf, const u32x4 (&v)[UPT]) {
-#pragma unroll
-        for (int i = 0; i < UPT; ++i) {
-            const int u = threadIdx.x + i * NW * 64;
-            const int pr = u / UNITS_PER_ROW, x = u % UNITS_PER_ROW;
-            if (u < UNITS) *reinterpret_cast<u32x4 *>(wide_smem + (size_t)buf * BUF + (size_t)pr * PITCH + x * 16) = v[i];
-        }
-    };
-    // weights beyond K (ragged tail, padding slabs) are read from a clamped address: the activations
-    // there are zero, so whatever finite weight comes back contributes nothing
-    auto w_load = [&](int k0, u32x4 (&w)[NT][KBS]) {
+    auto w_load = [&](int sl, u32x4 (&w)[NT][KBS]) {
+        const int k0 = sl * WIDE_KS;
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int kb = 0; kb < KBS; ++kb) w[t][kb] = ld16_stream(wrow[t] + min(k0 + kb * KB, K - (g + 1) * E));
+            for (int kb = 0; kb < KBS; ++kb) {
+                const int k = k0 + kb * KB;
+                w[t][kb] = ld16_stream(wrow[t] + min(k, K - (g + 1) * E)); // zeroed past K when it is used
+            }
         asm volatile("" ::: "memory");
     };
 
-    f32x4 acc[RT][NT];
+    // two accumulator sets per output tile (bf16: hi and lo plane; f32: alternate k-blocks) so that
+    // consecutive MFMAs never wait on each other
+    f32x4 acc[2][RT][NT];
 #pragma unroll
-    for (int r = 0; r < RT; ++r)
+    for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int t = 0; t < NT; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int r = 0; r < RT; ++r)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) acc[h][r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    constexpr int WD = 3; // weight slabs in registers: the one being multiplied and two in flight
-    const int nslab = (K + WIDE_KS - 1) / WIDE_KS;
-    const int nstep = (nslab + WD - 1) / WD * WD; // padded: the ring position of a step is a compile-time constant
-    u32x4 wring[WD][NT][KBS];
-    u32x4 sv[UPT];
-    slab_load(0, sv);
-    w_load(0, wring[0]);
-    w_load(WIDE_KS, wring[1]);
-    slab_store(0, sv);
-    __syncthreads();
-    auto step = [&](int s, u32x4 (&wcur)[NT][KBS], u32x4 (&wfill)[NT][KBS]) {
-        slab_load((s + 1) * WIDE_KS, sv);   // next activation slab (zeros past K)
-        w_load((s + 2) * WIDE_KS, wfill);   // weights two slabs ahead
-        const unsigned char *base = wide_smem + (size_t)(s & 1) * BUF + (size_t)c * PITCH + g * 16;
+    // Activation slabs are requested two steps ahead (three LDS buffers), weight slabs WDW - 1 steps
+    // ahead (registers).  A step issues [slab sl+2 -> LDS, weights sl+WDW-1 -> registers]; buffers and
+    // register sets are compile-time choices, so the step sequence is unrolled over WDW (a multiple of 3) steps.
+    constexpr int WDW = 3; // deeper weight rings (6) were measured and are slower
+    const int nstep = (nslab + WDW - 1) / WDW * WDW;
+    u32x4 wring[WDW][NT][KBS];
+#pragma unroll
+    for (int j = 0; j < WDW - 3; ++j) w_load(j, wring[j]);
+    slab_dma(0, slab0);
+    w_load(WDW - 3, wring[WDW - 3]);
+    slab_dma(1, slab1);
+    w_load(WDW - 2, wring[WDW - 2]);
+    auto step = [&](int sl, const unsigned char *cur, unsigned char *fill, u32x4 (&wcur)[NT][KBS], u32x4 (&wfill)[NT][KBS]) {
+        // this wave's part of slab sl and its weight slab sl have landed: the only younger loads are
+        // those of the previous step (slab sl+1, weights sl+1)
+        static_assert(WDW == 3, "the wait below counts one step of younger loads");
+        wait_vmcnt_at_most<DPW + WN>();
+        wide_barrier(); // everybody's part has landed, and everybody is done reading `fill` (slab sl - 1)
+        slab_dma(sl + 2, fill);
+        w_load(sl + WDW - 1, wfill);
+        const unsigned char *base = cur + (size_t)c * WIDE_SLAB_BYTES;
         // the LDS reads of k-block kb+1 are issued before the MFMAs of k-block kb (the scheduling
         // barriers keep the compiler from sinking them next to their uses, which serialises every
         // MFMA behind an LDS round trip)
@@ -340,7 +363,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
             for (int r = 0; r < RT; ++r)
 #pragma unroll
                 for (int pl = 0; pl < PL; ++pl)
-                    av[r].p[pl] = *reinterpret_cast<const u32x4 *>(base + (size_t)(pl * ROWS + r * 16) * PITCH + kb * (KB * (int)sizeof(T)));
+                    av[r].p[pl] = *reinterpret_cast<const u32x4 *>(base + (size_t)(pl * ROWS + r * 16) * WIDE_SLAB_BYTES + (((kb * 4 + g) ^ c) * 16));
             __builtin_amdgcn_sched_barrier(0);
         };
         Act<T> av[2][RT];
@@ -348,20 +371,25 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
 #pragma unroll
         for (int kb = 0; kb < KBS; ++kb) {
             if (kb + 1 < KBS) read_av(kb + 1, av[(kb + 1) & 1]);
+            const bool in_k = sl * WIDE_KS + kb * KB + g * E < K;
 #pragma unroll
-            for (int r = 0; r < RT; ++r)
+            for (int t = 0; t < NT; ++t) {
+                const u32x4 wm = in_k ? wcur[t][kb] : zero16();
 #pragma unroll
-                for (int t = 0; t < NT; ++t) acc[r][t] = mma(acc[r][t], wcur[t][kb], av[kb & 1][r]);
+                for (int r = 0; r < RT; ++r) mma_split(acc[0][r][t], acc[1][r][t], wm, av[kb & 1][r], kb);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
-        slab_store((s + 1) & 1, sv); // the other buffer: its readers finished before the last barrier
-        __syncthreads();
     };
-    for (int s0 = 0; s0 < nstep; s0 += WD) {
-        step(s0, wring[0], wring[2]);
-        step(s0 + 1, wring[1], wring[0]);
-        step(s0 + 2, wring[2], wring[1]);
+    for (int s0 = 0; s0 < nstep; s0 += WDW) {
+#pragma unroll
+        for (int j = 0; j < WDW; j += 3) {
+            step(s0 + j, slab0, slab2, wring[j], wring[(j + WDW - 1) % WDW]);
+            step(s0 + j + 1, slab1, slab0, wring[j + 1], wring[j % WDW]);
+            step(s0 + j + 2, slab2, slab1, wring[j + 2], wring[(j + 1) % WDW]);
+        }
     }
+    wait_vmcnt_at_most<0>(); // nothing may still be landing in LDS when the workgroup ends
     if (!tile_live) return;
 #pragma unroll
     for (int r = 0; r < RT; ++r) {
@@ -369,19 +397,13 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) out[t][v] = acc[r][t][v];
+            for (int v = 0; v < 4; ++v) out[t][v] = acc[0][r][t][v] + acc[1][r][t][v];
         apply_epilogue<T, EPI>(a, out, n0, rt0 + r);
     }
 }
 
 template <typename T, int EPI, int NW, int RT> static void launch_wide(const GemmArgs &a, int tiles, int row_tiles, hipStream_t st) {
-    constexpr size_t smem = 2 * (size_t)Traits<T>::PLANES * RT * 16 * WideSmem<T>::PITCH;
-    static bool attr_done = false; // more than 64 KB of dynamic LDS has to be allowed once per kernel
-    if (!attr_done) {
-        (void)hipFuncSetAttribute((const void *)gemm_wide_kernel<T, EPI, NW, RT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        attr_done = true;
-    }
-    hipLaunchKernelGGL((gemm_wide_kernel<T, EPI, NW, RT>), dim3((tiles + NW - 1) / NW, (row_tiles + RT - 1) / RT), dim3(NW * 64), smem, st, a);
+    hipLaunchKernelGGL((gemm_wide_kernel<T, EPI, NW, RT>), dim3((tiles + NW - 1) / NW, (row_tiles + RT - 1) / RT), dim3(NW * 64), 0, st, a);
 }
 
 template <typename T, int EPI> static void launch_gemm_t(const GemmArgs &a, hipStream_t st) {
