@@ -99,8 +99,8 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
             ss_speculative_accept(p, q, d, ua_all[step:step + 1].contiguous(), na, nx)
         if observer is not None:
             observer({"step": step, "draft": d, "q": q, "logits": logits, "p": p, "n_accepted": na, "next": nx})
-        a, y = int(na.item()), int(nx.item())
-        dl = d[0].tolist()
+        host = torch.cat([na, nx, d[0]]).tolist()   # one device-to-host copy per step
+        a, y, dl = host[0], host[1], host[2:]
         ss_kv_cache_rollback(tkv, na, M, n_accepted_host=[a])
         ss_kv_cache_rollback(dkv, na, K, n_accepted_host=[a])   # a = K leaves the draft cache one row short
         x += dl[:a] + [y]
