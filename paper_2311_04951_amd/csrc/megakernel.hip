@@ -1,33 +1,34 @@
 // The verify pass as ONE persistent kernel (Section 3: the pass is bound by streaming the weights, so
-// the design goal is that the HBM stream never stops).
+// the design goal is that the HBM stream stops as rarely and as briefly as possible).
 //
-// One workgroup of 8 wavefronts per compute unit stays resident for the whole pass and walks a list
-// of phases: [embedding] then per layer [QKV, attention, O projection, gate/up, down projection],
-// then [LM head] and [cache-length update].  Consecutive phases are separated by a device-wide
-// barrier (each workgroup publishes an epoch in its own slot and polls all slots: no atomics on a
-// shared counter; the spin is bounded and sets an abort flag that makes every workgroup leave).
-// The barrier carries no cache write-back / invalidate: everything one workgroup writes for another
-// to read inside the kernel (hidden rows, packed activations, norm partials, new cache rows,
-// attention partials) moves through agent-coherent relaxed atomics, which are performed at the
-// memory side of the per-XCD L2 caches; a barrier is then two memory round trips (~4 us) instead of
-// a full L2 flush and invalidate (~8 us).
+// One workgroup of 4 wavefronts per compute unit (512 registers per lane) stays resident for the whole
+// pass and walks a list of phases: [embedding] then per layer [QKV, attention, O projection, gate/up,
+// down projection], then [LM head] and [cache-length update].  Consecutive phases are separated by a
+// device-wide barrier (each workgroup publishes an epoch in its own slot and polls all slots: no
+// atomics on a shared counter; the spin is bounded and sets an abort flag that makes every workgroup
+// leave).  The barrier carries no cache write-back / invalidate: everything one workgroup writes for
+// another to read inside the kernel (hidden rows, packed activations, norm partials, new cache rows,
+// attention partials) moves through agent-coherent accesses, which are performed at the memory side of
+// the per-XCD L2 caches.
 //
 // Every workgroup owns a fixed, byte-balanced share of each weight matrix (a contiguous range of
 // output rows / of gate-up or rotary pairs), so the sequence of 16-byte weight chunks a wavefront
-// will consume over the whole pass is static.  It is consumed through a two-deep register pipeline of
-// "chunks" (up to 16 loads = 16 KB per wavefront): the loads of the next chunk - which may belong to
-// the next tile or to the NEXT PHASE - are issued before the current chunk is multiplied, reduced and
-// written back, so barriers, reductions, epilogues and the attention phase all run under weight
-// loads that are already in flight.
+// consumes in a phase is static.  It is consumed through a ring of register slots of one "chunk" each
+// (8 loads = 8 KB per wavefront): a step multiplies out of its slot and refills it with the chunk RING
+// ahead.  The loops that do this contain no other global memory operation and every refill issues the
+// same number of loads, pinned in program order, which is what lets the compiler wait for exactly one
+// slot (s_waitcnt vmcnt(N)) while the others stay in flight.  The ring is refilled with the first
+// chunks of the next phase at each phase boundary, after the arrival flag is written, so those loads
+// fly during the barrier.
 //
-// GEMM tiles are 16 weight rows (MFMA A operand) x all K; the 8 waves interleave over K in 128-byte
-// steps and their partial 16x16 tiles are summed in a fixed order through a double-buffered LDS
-// area by waves 0-3 while waves 4-7 already multiply the next tile.  Paired epilogues put the two
-// rows of a pair (gate/up, or rotary j and j + hd/2) 8 rows apart in the same tile, so the partner is
-// one wave-shuffle away.  RMSNorm is folded into the GEMMs: the producer packs h * gain and publishes
-// per-workgroup partial sums of squares, the consumer multiplies its outputs by the row scale.
-// The hidden rows a phase multiplies with (B operand) are copied once per phase (per 4096-wide K
-// slab) into LDS, so the chain load-weights -> MFMA never waits on a second global round trip.
+// GEMM tiles are 16 weight rows (MFMA A operand) x all K; the waves interleave over K in 128-byte
+// steps and their partial 16x16 tiles are summed in a fixed order through LDS; the reduced tiles wait
+// in an LDS stash and their epilogues (and global stores) run outside the chunk loops.  Paired
+// epilogues put the two rows of a pair (gate/up, or rotary j and j + hd/2) 8 rows apart in the same
+// tile, so the partner is one wave-shuffle away.  RMSNorm is folded into the GEMMs: the producer packs
+// h * gain and publishes per-workgroup partial sums of squares, the consumer multiplies its outputs by
+// the row scale.  The hidden rows a phase multiplies with (B operand) are copied once per phase (per
+// 8 KB of K per row) into LDS, all loads of the copy in flight together.
 #include "attention_core.h"
 #include "ss_mega.h"
 #include <algorithm>
@@ -626,7 +627,7 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
 
     for (int p = 0; p < P.n_phases; ++p) {
         const MegaPhase ph = P.phases[p];
-        // Phase boundary: all three slots are filled unconditionally (loads of zeros when this
+        // Phase boundary: all ring slots are filled unconditionally (loads of zeros when this
         // workgroup has no share of the phase), which also tells the compiler that the slots hold
         // nothing across a phase that does not use them.  The fills come after the wave's stores are
         // acknowledged, so the wait for the stores does not drain them.
