@@ -247,6 +247,41 @@ __device__ __forceinline__ bool grid_wait(const MegaCall &P, unsigned epoch, int
     return sm.t->flag != 0;
 }
 
+// The attention unit (sequence b, head h) only reads what the QKV phase wrote for head h: its query
+// rows, and the new key and value rows of that head.  Its workgroup therefore waits for the owners of
+// those QKV tiles only (they publish the same epoch slots), not for the slowest workgroup of the chip;
+// workgroups without a unit do not wait at this boundary at all.
+__device__ __forceinline__ bool grid_wait_qkv_of_head(const MegaCall &P, unsigned epoch, int h, int G, MegaSmem &sm) {
+    if (threadIdx.x < 64) {
+        const int tph = P.hd / 16, units = 3 * P.H * tph; // QKV tiles per head and region, and in total
+        bool ok = true;
+        unsigned spins = 0;
+        for (;;) {
+            bool all = true;
+            for (int region = 0; region < 3; ++region) {
+                const int t_lo = (region * P.H + h) * tph, t_hi = t_lo + tph - 1;
+                // owner of tile t under the static split u0(wg) = floor(wg * units / G)
+                const int w_lo = (int)(((long long)(t_lo + 1) * G - 1) / units), w_hi = (int)(((long long)(t_hi + 1) * G - 1) / units);
+                for (int i = w_lo + (int)threadIdx.x; i <= w_hi; i += 64) {
+                    const unsigned v = __hip_atomic_load(&P.arrive[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if ((int)(v - epoch) < 0) all = false;
+                }
+            }
+            if (__all(all)) break;
+            if (++spins > P.spin_limit || __hip_atomic_load(P.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
+                ok = false;
+                break;
+            }
+        }
+        if (threadIdx.x == 0) {
+            sm.t->flag = ok ? 1 : 0;
+            if (!ok) __hip_atomic_store(P.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    lds_barrier();
+    return sm.t->flag != 0;
+}
+
 // ---------------------------------------------------------------- non-GEMM phases
 
 template <typename T>
@@ -641,7 +676,14 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
 #pragma unroll
             for (int sl = 0; sl < RING; ++sl) fill(ring[sl]);
         }
-        if (p > 0 && !grid_wait(P, P.epoch_base + (unsigned)p, G, sm)) return;
+        if (p > 0) {
+            const int attn_units = P.B * P.H * P.nsplit;
+            if (ph.kind == PH_ATTN && attn_units <= G) { // one unit per workgroup at most: wait for its producers only
+                if (wg < attn_units && !grid_wait_qkv_of_head(P, P.epoch_base + (unsigned)p, (wg / P.nsplit) % P.H, G, sm)) return;
+            } else if (!grid_wait(P, P.epoch_base + (unsigned)p, G, sm)) {
+                return;
+            }
+        }
         if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(5 * p) * G + wg] = wall_clock64();
         const bool want_scales = ph.kind == PH_QKV || ph.kind == PH_SWIGLU || ph.kind == PH_HEAD;
         if (wave == 0) {
