@@ -110,6 +110,16 @@ int ss_model_destroy(ss_model *model);
  * of the method; SS_EINVAL if `on` is set and the persistent kernel is not available on this device. */
 int ss_model_set_persistent(ss_model *model, int32_t on);
 
+/* Tuning and test knobs of the persistent kernel (no effect on the per-phase path).
+ * workgroups: size of the cooperative grid; 0 = default (one per compute unit), at most that.
+ * data_sync: 1 (default): between GEMM phases the consumers validate the activation data itself
+ * (elements not yet written carry a reserved bit pattern) instead of waiting at a device-wide
+ * barrier; used for a launch only when every workgroup owns part of every GEMM phase (grid <=
+ * d_model, d_ff, vocab and 3*n_heads*head_dim/16), otherwise, and with 0, every phase boundary is a
+ * barrier.  Results are identical bit for bit in both modes.  SS_EINVAL on a NULL model, a negative or
+ * too large grid, or when the persistent kernel is not available. */
+int ss_model_set_persistent_options(ss_model *model, int32_t workgroups, int32_t data_sync);
+
 /* ---- KV cache (Sections 2, 4.2, 4.4) --------------------------------------------------------
  * kv_cache_alloc: a contiguous, page-free cache for `batch` sequences of up to `max_seq`
  * positions in the model's storage type, allocated (and zero-filled) by the library together

@@ -24,7 +24,7 @@ EXPORTS = [
     "ss_kv_cache_free", "ss_kv_cache_bytes", "ss_kv_cache_append", "ss_kv_cache_set_len",
     "ss_kv_cache_get_len", "ss_kv_cache_rollback", "ss_verify_forward", "ss_decoder_layers_forward",
     "ss_draft_step", "ss_softmax", "ss_speculative_accept", "ss_speculative_accept_logits",
-    "ss_greedy_accept", "ss_profile_enable", "ss_profile_read", "ss_model_set_persistent",
+    "ss_greedy_accept", "ss_profile_enable", "ss_profile_read", "ss_model_set_persistent", "ss_model_set_persistent_options",
 ]
 
 PROFILE_CLASSES = ["rmsnorm", "qkv_gemm", "attention", "oproj_gemm", "gateup_gemm", "down_gemm", "head_gemm", "other",
@@ -85,6 +85,7 @@ def lib():
             "ss_greedy_accept": [vp, vp, i32, i32, i32, vp, vp, vp],
             "ss_profile_enable": [vp, i32],
             "ss_model_set_persistent": [vp, i32],
+            "ss_model_set_persistent_options": [vp, i32, i32],
             "ss_profile_read": [vp, i32, vp, vp],
         }
         for name, args in sig.items():
@@ -302,6 +303,10 @@ def ss_device_status(model: Model, stream=None) -> int:
 
 def ss_model_set_persistent(model: Model, on: bool):
     _check(lib().ss_model_set_persistent(model.handle, int(bool(on))))
+
+
+def ss_model_set_persistent_options(model: Model, workgroups: int = 0, data_sync: bool = True):
+    _check(lib().ss_model_set_persistent_options(model.handle, int(workgroups), int(bool(data_sync))))
 
 
 def ss_profile_enable(model: Model, on: bool):

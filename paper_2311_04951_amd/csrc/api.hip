@@ -52,6 +52,7 @@ struct ss_model {
     int R16;            // max_rows rounded up to 16
     float *h;           // [max_rows][d] residual stream
     void *act_a;        // planes [R16][d]   normalised hidden rows
+    void *act_a1 = nullptr; // second buffer of the same shape (persistent kernel: rows packed by the O projection)
     void *act_q;        // planes [R16][W]   rotated queries
     void *act_o;        // planes [R16][W]   attention output
     void *act_z;        // planes [R16][F]   SwiGLU output
@@ -63,7 +64,10 @@ struct ss_model {
     std::vector<void *> owned;
     // persistent verify kernel: phase programs (device), barrier state, norm partials
     int mega_G = 0;                 // workgroups per launch (0: persistent path unavailable)
+    int mega_G_max = 0;             // one per compute unit: what the barrier arrays are sized for
     int mega_rows = 0;              // most rows (batch * M) a persistent launch takes
+    int mega_min_units = 0;         // fewest ownership units of any GEMM phase: data synchronisation needs a grid no larger
+    bool data_sync = true;          // persistent kernel: self-validating activations instead of barriers where possible
     MegaPhase *prog_full = nullptr; // [embed, layers, head, len]
     MegaPhase *prog_nohead = nullptr; // [embed, layers, len]
     int n_full = 0, n_nohead = 0;
@@ -185,7 +189,7 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
     {
         int dev = 0;
         (void)hipGetDevice(&dev);
-        m->mega_G = mega_grid(c.dtype, dev);
+        m->mega_G = m->mega_G_max = mega_grid(c.dtype, dev);
         m->mega_rows = mega_max_rows(c.dtype);
         if (m->mega_G > 0 && c.n_layers >= 0) {
             std::vector<MegaPhase> prog;
@@ -193,28 +197,46 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
             MegaPhase e{};
             e.kind = PH_EMBED;
             e.gain = c.n_layers ? m->layers[0].g1 : m->gf;
+            e.act_dst = ACT_A;
+            e.clear_phase = -1;
             prog.push_back(e);
+            // Program layout: phase 0 = embedding, layer l = phases 1 + 5*l .. 5 + 5*l (QKV, attention, O, gate/up, down).
+            // sync: how a phase's input is synchronised when the launch runs with data synchronisation;
+            // clear_phase: whose outputs a phase resets (see clear_outputs() in the kernel source).
             for (int l = 0; l < c.n_layers; ++l) {
                 const ss_layer_weights &L = m->layers[l];
-                MegaPhase q{}; q.kind = PH_QKV; q.layer = l; q.W = L.wqkv; q.N = 3 * m->W; q.K = c.d_model; q.act_src = ACT_A; prog.push_back(q);
-                MegaPhase a{}; a.kind = PH_ATTN; a.layer = l; prog.push_back(a);
-                MegaPhase o{}; o.kind = PH_RESID; o.layer = l; o.W = L.wo; o.N = c.d_model; o.K = m->W; o.act_src = ACT_O; o.gain = L.g2; prog.push_back(o);
-                MegaPhase u{}; u.kind = PH_SWIGLU; u.layer = l; u.W = L.wgu; u.N = c.d_ff; u.K = c.d_model; u.act_src = ACT_A; prog.push_back(u);
-                MegaPhase dn{}; dn.kind = PH_RESID; dn.layer = l; dn.W = L.wd; dn.N = c.d_model; dn.K = c.d_ff; dn.act_src = ACT_Z; dn.gain = gain_after(l); prog.push_back(dn);
+                const int p0 = 1 + 5 * l;
+                MegaPhase q{}; q.kind = PH_QKV; q.layer = l; q.W = L.wqkv; q.N = 3 * m->W; q.K = c.d_model; q.act_src = ACT_A;
+                q.sync = l ? SYNC_DATA : SYNC_FLAGS; q.clear_phase = p0 + 2; prog.push_back(q);
+                MegaPhase a{}; a.kind = PH_ATTN; a.layer = l; a.sync = SYNC_FLAGS; a.clear_phase = -1; prog.push_back(a);
+                MegaPhase o{}; o.kind = PH_RESID; o.layer = l; o.W = L.wo; o.N = c.d_model; o.K = m->W; o.act_src = ACT_O; o.gain = L.g2;
+                o.act_dst = ACT_A1; o.sync = SYNC_DATA_ATTN; o.clear_phase = p0 + 3; prog.push_back(o);
+                MegaPhase u{}; u.kind = PH_SWIGLU; u.layer = l; u.W = L.wgu; u.N = c.d_ff; u.K = c.d_model; u.act_src = ACT_A1;
+                u.sync = SYNC_DATA; u.clear_phase = p0 + 4; prog.push_back(u);
+                MegaPhase dn{}; dn.kind = PH_RESID; dn.layer = l; dn.W = L.wd; dn.N = c.d_model; dn.K = c.d_ff; dn.act_src = ACT_Z; dn.gain = gain_after(l);
+                dn.act_dst = ACT_A; dn.sync = SYNC_DATA; dn.clear_phase = l + 1 < c.n_layers ? p0 + 5 + 1 : -1; prog.push_back(dn);
             }
-            MegaPhase ln{}; ln.kind = PH_LEN;
+            if (c.n_layers) prog[0].clear_phase = 2; // the embedding clears what the first attention phase writes
+            MegaPhase ln{}; ln.kind = PH_LEN; ln.sync = SYNC_FLAGS; ln.clear_phase = -1;
             std::vector<MegaPhase> nohead = prog;
             nohead.push_back(ln);
             if (m->lm_head && m->gf) {
-                MegaPhase hd{}; hd.kind = PH_HEAD; hd.W = m->lm_head; hd.N = c.vocab; hd.K = c.d_model; hd.act_src = ACT_A; prog.push_back(hd);
+                MegaPhase hd{}; hd.kind = PH_HEAD; hd.W = m->lm_head; hd.N = c.vocab; hd.K = c.d_model; hd.act_src = ACT_A;
+                hd.sync = c.n_layers ? SYNC_DATA : SYNC_FLAGS; hd.clear_phase = -1; prog.push_back(hd);
             }
             prog.push_back(ln);
+            m->mega_min_units = c.vocab;
+            for (const MegaPhase &ph : prog) {
+                if (ph.kind == PH_QKV) m->mega_min_units = std::min(m->mega_min_units, ph.N / 16);
+                if (ph.kind == PH_RESID || ph.kind == PH_SWIGLU || ph.kind == PH_HEAD) m->mega_min_units = std::min(m->mega_min_units, ph.N);
+            }
             {
                 m->n_full = (int)prog.size();
                 m->n_nohead = (int)nohead.size();
                 A((void **)&m->prog_full, sizeof(MegaPhase) * prog.size(), false);
                 A((void **)&m->prog_nohead, sizeof(MegaPhase) * nohead.size(), false);
-                A((void **)&m->nsq, sizeof(float) * 16 * (size_t)m->mega_G, true);
+                A((void **)&m->nsq, sizeof(float) * 2 * 16 * (size_t)m->mega_G, true);
+                A(&m->act_a1, pe * c.d_model, true);
                 A((void **)&m->arrive, sizeof(unsigned) * (size_t)m->mega_G, true);
                 A((void **)&m->abort_flag, sizeof(unsigned), true);
                 A(&m->zeros, 256, true);
@@ -267,7 +289,7 @@ extern "C" int ss_device_status(ss_model *m, ss_stream stream, int32_t *status_h
             // a device-wide barrier gave up: reset the barrier state so that later launches start clean
             *status_host |= 2;
             HIP_TRY(hipMemsetAsync(m->abort_flag, 0, sizeof(unsigned), st));
-            HIP_TRY(hipMemsetAsync(m->arrive, 0, sizeof(unsigned) * (size_t)m->mega_G, st));
+            HIP_TRY(hipMemsetAsync(m->arrive, 0, sizeof(unsigned) * (size_t)m->mega_G_max, st));
             HIP_TRY(hipMemsetAsync(m->attn_cnt, 0, sizeof(unsigned) * (size_t)m->cfg.max_rows * m->cfg.n_heads, st));
             HIP_TRY(hipStreamSynchronize(st));
             m->epoch = 1;
@@ -517,6 +539,16 @@ extern "C" int ss_model_set_persistent(ss_model *m, int32_t on) {
     return SS_OK;
 }
 
+extern "C" int ss_model_set_persistent_options(ss_model *m, int32_t workgroups, int32_t data_sync) {
+    if (!m) return fail(SS_EINVAL, "ss_model_set_persistent_options: NULL model");
+    if (m->mega_G_max <= 0) return fail(SS_EINVAL, "the persistent verify kernel is not available for this model on this device");
+    if (workgroups < 0 || workgroups > m->mega_G_max)
+        return fail(SS_EINVAL, "ss_model_set_persistent_options: workgroups %d outside 0..%d", workgroups, m->mega_G_max);
+    m->mega_G = workgroups ? workgroups : m->mega_G_max;
+    m->data_sync = data_sync != 0;
+    return SS_OK;
+}
+
 // One launch of the persistent kernel: [embedding | given rows] -> layers -> [LM head] -> lengths += M.
 static int run_persistent(ss_model *m, ss_kv_cache *kv, const int32_t *tokens, float *h, int batch, int M, float *logits,
                           int head_rows, int head_row0, int head_stride, hipStream_t st) {
@@ -531,11 +563,14 @@ static int run_persistent(ss_model *m, ss_kv_cache *kv, const int32_t *tokens, f
     P.R = batch * M; P.B = batch; P.M = M;
     P.eps = c.rms_eps;
     P.tokens = tokens; P.embed = m->embed; P.h = h;
-    P.act[ACT_A] = m->act_a; P.act_plane[ACT_A] = pl * c.d_model; P.act_ld[ACT_A] = c.d_model;
-    P.act[ACT_Q] = m->act_q; P.act_plane[ACT_Q] = pl * m->W; P.act_ld[ACT_Q] = m->W;
-    P.act[ACT_O] = m->act_o; P.act_plane[ACT_O] = pl * m->W; P.act_ld[ACT_O] = m->W;
-    P.act[ACT_Z] = m->act_z; P.act_plane[ACT_Z] = pl * c.d_ff; P.act_ld[ACT_Z] = c.d_ff;
+    P.act_a = ActDesc{m->act_a, pl * c.d_model, c.d_model};
+    P.act_q = ActDesc{m->act_q, pl * m->W, m->W};
+    P.act_o = ActDesc{m->act_o, pl * m->W, m->W};
+    P.act_z = ActDesc{m->act_z, pl * c.d_ff, c.d_ff};
+    P.act_a1 = ActDesc{m->act_a1, pl * c.d_model, c.d_model};
     P.nsq = m->nsq;
+    // self-validating activations need every workgroup to own part of every GEMM phase (and the norm partials of at most 256)
+    P.data_sync = m->data_sync && m->mega_G <= m->mega_min_units && m->mega_G <= 256;
     P.logits = logits; P.ldo = c.vocab; P.head_rows = head_rows; P.head_row0 = head_row0; P.head_stride = head_stride;
     P.kc = kv->k; P.vc = kv->v; P.layer_elems = kv->layer_elems; P.len = kv->len_dev; P.S = kv->S; P.max_pos = c.max_pos;
     P.rope = m->rope;

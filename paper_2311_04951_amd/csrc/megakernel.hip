@@ -191,6 +191,7 @@ struct MegaSmemTail {
     float blk[MNW];
     int len[16];              // cached lengths of the sequences before this pass (read once at kernel start)
     int flag;
+    int ok;                   // cleared by a wave whose bounded wait for input data ran out
 };
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding
@@ -222,13 +223,13 @@ __device__ __forceinline__ void grid_arrive(const MegaCall &P, unsigned epoch, M
     if (threadIdx.x == 0) __hip_atomic_store(&P.arrive[blockIdx.x], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-__device__ __forceinline__ bool grid_wait(const MegaCall &P, unsigned epoch, int G, MegaSmem &sm) {
+__device__ __forceinline__ bool grid_wait(const MegaCall &P, unsigned epoch, int lo, int hi, MegaSmem &sm) { // slots lo .. hi-1
     if (threadIdx.x < 64) {
         bool ok = true;
         unsigned spins = 0;
         for (;;) {
             bool all = true;
-            for (int i = threadIdx.x; i < G; i += 64) {
+            for (int i = lo + (int)threadIdx.x; i < hi; i += 64) {
                 const unsigned v = __hip_atomic_load(&P.arrive[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if ((int)(v - epoch) < 0) all = false;
             }
@@ -286,7 +287,7 @@ __device__ __forceinline__ bool grid_wait_qkv_of_head(const MegaCall &P, unsigne
 
 template <typename T>
 __device__ __forceinline__ void do_embed(const MegaCall &P, const MegaPhase &ph, int wg, int G, MegaSmem &sm) {
-    ActPlanes<T> act{reinterpret_cast<T *>(P.act[ACT_A]), P.act_plane[ACT_A], P.act_ld[ACT_A]};
+    const ActPlanes<T> act = act_planes<T>(P, ACT_A);
     for (int r = wg; r < P.R; r += G) {
         const T *src = nullptr;
         if (P.tokens) {
@@ -323,9 +324,10 @@ __device__ __forceinline__ void do_embed(const MegaCall &P, const MegaPhase &ph,
 template <typename T, int HD>
 __device__ __forceinline__ void do_attn_hd(const MegaCall &P, const MegaPhase &ph, int wg, int G, MegaSmem &sm) {
     AttnArgs a;
-    a.q = P.act[ACT_Q];
-    a.q_plane = P.act_plane[ACT_Q];
-    a.ldq = P.act_ld[ACT_Q];
+    const ActDesc dq = P.act_q, dout = P.act_o;
+    a.q = dq.base;
+    a.q_plane = dq.plane;
+    a.ldq = dq.ld;
     const size_t esz = sizeof(T);
     a.kcache = (char *)P.kc + P.layer_elems * ph.layer * esz;
     a.vcache = (char *)P.vc + P.layer_elems * ph.layer * esz;
@@ -333,7 +335,7 @@ __device__ __forceinline__ void do_attn_hd(const MegaCall &P, const MegaPhase &p
     a.B = P.B; a.M = P.M; a.H = P.H; a.hd = HD; a.S = P.S; a.R = P.R;
     a.nsplit = P.nsplit; a.chunk = P.chunk;
     a.part_o = P.part_o; a.part_m = P.part_m; a.part_l = P.part_l;
-    a.act_out = P.act[ACT_O]; a.act_out_plane = P.act_plane[ACT_O]; a.ld_out = P.act_ld[ACT_O];
+    a.act_out = dout.base; a.act_out_plane = dout.plane; a.ld_out = dout.ld;
     a.scale_log2e = P.scale_log2e;
     AttnSmem<HD, MNW> &asm_ = *reinterpret_cast<AttnSmem<HD, MNW> *>(sm.u);
     ActPlanes<T> out{reinterpret_cast<T *>(a.act_out), a.act_out_plane, a.ld_out};
@@ -377,41 +379,62 @@ __device__ __forceinline__ void do_attn(const MegaCall &P, const MegaPhase &ph, 
     else do_attn_hd<T, 32>(P, ph, wg, G, sm);
 }
 
-// The activation planes a phase reads.  Written with constant indices on purpose: a run-time index
-// into an array of the by-value kernel argument makes the compiler keep a copy of it in scratch memory.
-template <typename T> __device__ __forceinline__ ActPlanes<T> act_planes(const MegaCall &P, int i) {
-    void *b = i == ACT_A ? P.act[ACT_A] : i == ACT_Q ? P.act[ACT_Q] : i == ACT_O ? P.act[ACT_O] : P.act[ACT_Z];
-    const size_t pl = i == ACT_A ? P.act_plane[ACT_A] : i == ACT_Q ? P.act_plane[ACT_Q] : i == ACT_O ? P.act_plane[ACT_O] : P.act_plane[ACT_Z];
-    const int ld = i == ACT_A ? P.act_ld[ACT_A] : i == ACT_Q ? P.act_ld[ACT_Q] : i == ACT_O ? P.act_ld[ACT_O] : P.act_ld[ACT_Z];
-    return ActPlanes<T>{reinterpret_cast<T *>(b), pl, ld};
+// The activation planes a phase reads or writes (selects between named fields, see MegaCall).
+__device__ __forceinline__ ActDesc act_desc(const MegaCall &P, int i) {
+    // values first, selects second: a conditional expression between two members is an lvalue, i.e. a
+    // run-time address into the argument, which is exactly what has to be avoided
+    const ActDesc a = P.act_a, q = P.act_q, o = P.act_o, z = P.act_z, a1 = P.act_a1;
+    ActDesc r = a1;
+    if (i == ACT_A) r = a;
+    if (i == ACT_Q) r = q;
+    if (i == ACT_O) r = o;
+    if (i == ACT_Z) r = z;
+    return r;
 }
+template <typename T> __device__ __forceinline__ ActPlanes<T> act_planes(const MegaCall &P, int i) {
+    const ActDesc a = act_desc(P, i);
+    return ActPlanes<T>{reinterpret_cast<T *>(a.base), a.plane, a.ld};
+}
+// the norm partials that go with hidden rows packed into ACT_A (set 0) or ACT_A1 (set 1)
+__device__ __forceinline__ float *nsq_set(const MegaCall &P, int act, int G) { return P.nsq + (act == ACT_A1 ? (size_t)16 * G : 0); }
 
 // Row scales 1/sqrt(mean(h^2) + eps) from the producers' partial sums, in two halves so that the loads
 // can share a memory round trip with other loads: 32 threads per row, rows beyond P.R are not needed.
 struct ScaleLoads {
     float t[2][8];
 };
-__device__ __forceinline__ void scales_issue(const MegaCall &P, int G, ScaleLoads &sl) {
-    const int j = threadIdx.x & 31;
+__device__ __forceinline__ bool scale_slot(const MegaCall &P, int G, int half, int q, int &row, int &i) { // false: no such partial
+    row = (threadIdx.x >> 5) + half * (MEGA_THREADS / 32);
+    i = (threadIdx.x & 31) + 32 * q;
+    return row < P.R && i < G;
+}
+// every thread issues all 16 loads (a fixed number of loads keeps the waits on them exact); slots
+// without a partial read a valid address and are ignored when used
+__device__ __forceinline__ void scales_issue(const MegaCall &P, const float *nsq, int G, bool only_unset, ScaleLoads &sl) {
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-        const int row = (threadIdx.x >> 5) + half * (MEGA_THREADS / 32);
+    for (int half = 0; half < 2; ++half)
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
-            const int i = j + 32 * q;
-            sl.t[half][q] = (row < P.R && i < G) ? ld_coh(&P.nsq[(size_t)row * G + i]) : 0.f;
+            int row, i;
+            const bool valid = scale_slot(P, G, half, q, row, i);
+            const float *src = &nsq[(size_t)min(row, P.R - 1) * G + min(i, G - 1)];
+            if (!only_unset) sl.t[half][q] = ld_coh(src);
+            else if (valid && f2u(sl.t[half][q]) == 0xffffffffu) sl.t[half][q] = ld_coh(src);
         }
-    }
 }
-__device__ __forceinline__ void scales_finish(const MegaCall &P, int G, const ScaleLoads &sl, MegaSmem &sm) {
+__device__ __forceinline__ void scales_finish(const MegaCall &P, const float *nsq, int G, const ScaleLoads &sl, MegaSmem &sm) {
     const int j = threadIdx.x & 31;
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
         const int row = (threadIdx.x >> 5) + half * (MEGA_THREADS / 32);
         float s = 0.f;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) s += sl.t[half][q];
-        for (int i = 256 + j; i < G; i += 32) s += ld_coh(&P.nsq[(size_t)row * G + i]); // grids beyond 256 workgroups
+        for (int q = 0; q < 8; ++q) {
+            int r2, i;
+            s += scale_slot(P, G, half, q, r2, i) ? sl.t[half][q] : 0.f;
+        }
+        if (row < P.R)
+            for (int i = 256 + j; i < G; i += 32) s += ld_coh(&nsq[(size_t)row * G + i]); // grids beyond 256 workgroups (flag barriers only)
 #pragma unroll
         for (int o = 16; o > 0; o >>= 1) s += __shfl_xor(s, o);
         if (j == 0 && row < 16) sm.t->scale[row] = row < P.R ? 1.0f / sqrtf(s / (float)P.d + P.eps) : 0.f;
@@ -423,50 +446,173 @@ static_assert(MEGA_THREADS / 32 * 2 >= 16, "two halves of the scale loads cover 
 // slab_issue() puts every load in flight (with_scales: also the loads of the phase's row scales), so the
 // whole copy costs one memory round trip, and slab_finish() writes the data to LDS.  Other loads may
 // be issued between the two: loads return in order, so the slab does not wait for them.
+//
+// Self-validating data.  Between a producer's stores and a consumer's loads the usual protocol costs
+// three dependent trips through the memory fabric (store acknowledgement, flag, poll) before the slab
+// can even be requested.  In data-sync mode a producer just stores, and the consumer loads the slab
+// and looks at it: every element of an activation buffer (and every norm partial) is reset, well
+// before it is written, to a bit pattern no computed value has (all ones: a NaN with a full payload;
+// bf16_rne and the fp32 arithmetic produce other NaNs at most), so a unit that still shows the pattern
+// has not arrived and is simply loaded again (bounded).  Each element is validated on its own, so no
+// ordering between different stores is assumed.  The resets ride on causality, see clear_outputs().
 constexpr int SLAB_UNITS = SLAB_ROW_BYTES / 16 / MEGA_THREADS; // 16-byte units per thread and slab row
 template <int NPR> struct SlabLoads { // NPR: (plane, row) pairs per batch
     u32x4 v[NPR][SLAB_UNITS]; // [(plane, row) pair][unit]
     ScaleLoads sl;
 };
+static_assert(10 * SLAB_UNITS < 31, "one mask bit per unit of a batch, bit 31 for the row scales");
+
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+// running maximum that ends at all ones iff some element seen was the "not written yet" pattern
+template <typename T> __device__ __forceinline__ uint32_t unset_acc(uint32_t m, uint32_t w);
+template <> __device__ __forceinline__ uint32_t unset_acc<bf16_t>(uint32_t m, uint32_t w) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2, m), __builtin_bit_cast(u16x2, w)));
+}
+template <> __device__ __forceinline__ uint32_t unset_acc<float>(uint32_t m, uint32_t w) { return m > w ? m : w; }
+template <typename T> __device__ __forceinline__ bool unset_seen(uint32_t m);
+template <> __device__ __forceinline__ bool unset_seen<bf16_t>(uint32_t m) { return (m & 0xffffu) == 0xffffu || (m >> 16) == 0xffffu; }
+template <> __device__ __forceinline__ bool unset_seen<float>(uint32_t m) { return m == 0xffffffffu; }
+template <typename T> __device__ __forceinline__ bool unit_unset(const u32x4 &v) {
+    return unset_seen<T>(unset_acc<T>(unset_acc<T>(v[0], v[1]), unset_acc<T>(v[2], v[3])));
+}
+__device__ __forceinline__ void store_unset(bf16_t *p) { st_coh(p, bf16_t{(uint16_t)0xffffu}); }
+__device__ __forceinline__ void store_unset(float *p) { st_coh(p, u2f(0xffffffffu)); }
+
+// Unit (i, h2) of a batch that starts at (plane, row) pair pr0: byte offset of its 16 bytes in the source
+// planes, clamped to a valid address when the unit does not exist (pair beyond the slab rows, row
+// without data, K tail); false: it does not exist and counts as zeros.
+template <typename T>
+__device__ __forceinline__ bool slab_unit(const MegaCall &P, const MegaPhase &ph, const ActPlanes<T> &src, int slab, int pr, int h2,
+                                          uint32_t &byte_off) {
+    constexpr int PER16 = 16 / (int)sizeof(T); // elements per 16-byte unit
+    const bool head = ph.kind == PH_HEAD;
+    const int rows = P.slab_rows, nrow = Traits<T>::PLANES * rows;
+    const int nlive = head ? P.head_rows : P.R;
+    const int prc = min(pr, nrow - 1);
+    const int r = prc % rows, pl = prc / rows, rc = min(r, nlive - 1);
+    const int brow = head ? P.head_row0 + rc * P.head_stride : rc;
+    const int x = threadIdx.x + h2 * MEGA_THREADS;
+    const int k = slab * (SLAB_ROW_BYTES / (int)sizeof(T)) + x * PER16; // K is a multiple of the unit
+    const bool valid = pr < nrow && r < nlive && k < ph.K;
+    byte_off = (uint32_t)((pl * src.plane + (size_t)brow * src.ld + (k < ph.K ? k : 0)) * sizeof(T));
+    return valid;
+}
+// All loads of a batch (with_scales: and of the row scales), unconditionally: the number of loads in
+// flight is a compile-time constant, so a later wait for them can leave younger loads in flight.
 template <typename T, int NPR>
 __device__ __forceinline__ void slab_issue(const MegaCall &P, const MegaPhase &ph, int slab, int pr0, int G, bool with_scales,
                                            SlabLoads<NPR> &L) {
-    constexpr int PL = Traits<T>::PLANES;
-    constexpr int PER16 = 16 / (int)sizeof(T); // elements per 16-byte unit
-    const bool head = ph.kind == PH_HEAD;
-    const int rows = P.slab_rows;
-    const int nlive = head ? P.head_rows : P.R;
-    const ActPlanes<T> src_planes = act_planes<T>(P, ph.act_src);
-    const int nrow = PL * rows; // (plane, row) pairs; this call takes pairs pr0 .. pr0 + NPR - 1
-    if (with_scales) scales_issue(P, G, L.sl);
+    const ActPlanes<T> src = act_planes<T>(P, ph.act_src);
+    if (with_scales) scales_issue(P, nsq_set(P, ph.act_src, G), G, false, L.sl);
+#pragma unroll
+    for (int i = 0; i < NPR; ++i)
+#pragma unroll
+        for (int h2 = 0; h2 < SLAB_UNITS; ++h2) {
+            uint32_t off;
+            slab_unit<T>(P, ph, src, slab, pr0 + i, h2, off);
+            L.v[i][h2] = ld16_coh_buf(src.base, off);
+        }
+}
+// true: something this lane loaded still shows the "not written yet" pattern
+template <typename T, int NPR>
+__device__ __forceinline__ bool slab_unset(const MegaCall &P, const MegaPhase &ph, int slab, int pr0, int G, bool with_scales,
+                                           const SlabLoads<NPR> &L) {
+    const ActPlanes<T> src = act_planes<T>(P, ph.act_src);
+    uint32_t m = 0, ms = 0;
+#pragma unroll
+    for (int i = 0; i < NPR; ++i)
+#pragma unroll
+        for (int h2 = 0; h2 < SLAB_UNITS; ++h2) {
+            uint32_t off;
+            const bool valid = slab_unit<T>(P, ph, src, slab, pr0 + i, h2, off);
+            const uint32_t um = unset_acc<T>(unset_acc<T>(L.v[i][h2][0], L.v[i][h2][1]), unset_acc<T>(L.v[i][h2][2], L.v[i][h2][3]));
+            m = unset_acc<T>(m, valid ? um : 0u);
+        }
+    if (with_scales) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                int row, i;
+                ms = unset_acc<float>(ms, scale_slot(P, G, half, q, row, i) ? f2u(L.sl.t[half][q]) : 0u);
+            }
+    }
+    return unset_seen<T>(m) || unset_seen<float>(ms);
+}
+// After a first slab_unset() found the pattern: wait (bounded) until nothing this wave loaded shows
+// it, loading again what does.  false: gave up (the caller raises the abort flag).
+template <typename T, int NPR>
+__device__ __forceinline__ bool slab_retry(const MegaCall &P, const MegaPhase &ph, int slab, int pr0, int G, bool with_scales,
+                                           SlabLoads<NPR> &L) {
+    const ActPlanes<T> src = act_planes<T>(P, ph.act_src);
+    for (unsigned spins = 0; spins < P.spin_limit; ++spins) {
+        if (__hip_atomic_load(P.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) return false;
+        if (with_scales) scales_issue(P, nsq_set(P, ph.act_src, G), G, true, L.sl);
+#pragma unroll
+        for (int i = 0; i < NPR; ++i)
+#pragma unroll
+            for (int h2 = 0; h2 < SLAB_UNITS; ++h2) {
+                uint32_t off;
+                if (slab_unit<T>(P, ph, src, slab, pr0 + i, h2, off) && unit_unset<T>(L.v[i][h2])) L.v[i][h2] = ld16_coh_buf(src.base, off);
+            }
+        if (!__any(slab_unset<T>(P, ph, slab, pr0, G, with_scales, L))) return true;
+    }
+    return false;
+}
+template <typename T, int NPR>
+__device__ __forceinline__ void slab_finish(const MegaCall &P, const MegaPhase &ph, int slab, int pr0, int G, bool with_scales,
+                                            const SlabLoads<NPR> &L, MegaSmem &sm) {
+    const ActPlanes<T> src = act_planes<T>(P, ph.act_src);
+    const int nrow = Traits<T>::PLANES * P.slab_rows;
+    if (with_scales) scales_finish(P, nsq_set(P, ph.act_src, G), G, L.sl, sm);
 #pragma unroll
     for (int i = 0; i < NPR; ++i) {
         const int pr = pr0 + i;
         if (pr < nrow) {
-            const int r = pr % rows, pl = pr / rows;
-            const int brow = head ? P.head_row0 + r * P.head_stride : r;
-            const size_t row_off = pl * src_planes.plane + (size_t)brow * src_planes.ld; // elements
 #pragma unroll
             for (int h2 = 0; h2 < SLAB_UNITS; ++h2) {
+                uint32_t off;
+                const bool valid = slab_unit<T>(P, ph, src, slab, pr, h2, off);
                 const int x = threadIdx.x + h2 * MEGA_THREADS;
-                const int k = slab * (SLAB_ROW_BYTES / (int)sizeof(T)) + x * PER16; // K is a multiple of the unit
-                L.v[i][h2] = (r < nlive && k < ph.K) ? ld16_coh_buf(src_planes.base, (uint32_t)((row_off + k) * sizeof(T))) : zero16();
+                *reinterpret_cast<u32x4 *>(sm.u + (size_t)pr * SLAB_PITCH + x * 16) = valid ? L.v[i][h2] : zero16();
             }
         }
     }
 }
-template <typename T, int NPR>
-__device__ __forceinline__ void slab_finish(const MegaCall &P, int pr0, int G, bool with_scales, const SlabLoads<NPR> &L, MegaSmem &sm) {
-    const int nrow = Traits<T>::PLANES * P.slab_rows;
-    if (with_scales) scales_finish(P, G, L.sl, sm);
-#pragma unroll
-    for (int i = 0; i < NPR; ++i) {
-        const int pr = pr0 + i;
-        if (pr < nrow) {
-#pragma unroll
-            for (int h2 = 0; h2 < SLAB_UNITS; ++h2) {
-                const int x = threadIdx.x + h2 * MEGA_THREADS;
-                *reinterpret_cast<u32x4 *>(sm.u + (size_t)pr * SLAB_PITCH + x * 16) = L.v[i][h2];
+
+// Reset, to the "not written yet" pattern, what this workgroup will write in phase `tp` (a later phase).
+// Called in an earlier phase c, once that phase's input is complete, and followed by a wait for the
+// store acknowledgements before phase c's own outputs are stored.  Two things must hold:
+//  (1) nobody still reads the old contents: they were consumed at the start of a phase before c, and
+//      the input of c being complete means that every workgroup has finished the phase before c;
+//  (2) every consumer sees the reset before it first looks for the new data: it looks after finishing
+//      phase `tp`, whose input it found complete; that input descends, store by store, from the outputs
+//      of phase c of EVERY workgroup, which were stored after the resets were acknowledged.
+// The schedule that satisfies both (set by the host in MegaPhase::clear_phase): QKV clears what the O
+// projection writes, the O projection what gate/up writes, gate/up what the down projection writes, and
+// the down projection (the embedding, before the first layer) what the next attention phase writes.
+// It needs every workgroup to own part of every GEMM phase, which the host checks (MegaCall::data_sync).
+template <typename T>
+__device__ __forceinline__ void clear_outputs(const MegaCall &P, const MegaPhase &tp, int wg, int G) {
+    constexpr int PL = Traits<T>::PLANES;
+    if (tp.kind == PH_RESID || tp.kind == PH_SWIGLU) {
+        const Range r = phase_range(tp, wg, G); // columns of the output = rows (pairs) of the weight matrix
+        const ActPlanes<T> a = act_planes<T>(P, tp.kind == PH_RESID ? tp.act_dst : ACT_Z);
+        const int ncol = r.u1 - r.u0, n = ncol * P.R * PL;
+        for (int idx = threadIdx.x; idx < n; idx += MEGA_THREADS) {
+            const int col = r.u0 + idx % ncol, rest = idx / ncol, row = rest % P.R, pl = rest / P.R;
+            store_unset(a.base + pl * a.plane + (size_t)row * a.ld + col);
+        }
+        if (tp.kind == PH_RESID && threadIdx.x < 16) store_unset(&nsq_set(P, tp.act_dst, G)[(size_t)threadIdx.x * G + wg]);
+    } else if (tp.kind == PH_ATTN) {
+        const ActPlanes<T> o = act_planes<T>(P, ACT_O);
+        const int units = P.B * P.H * P.nsplit, n = P.M * P.hd * PL;
+        for (int u = wg; u < units; u += G) {
+            if (u % P.nsplit != 0) continue; // one of the splits of (sequence, head) does it
+            const int bh = u / P.nsplit, h = bh % P.H, b = bh / P.H;
+            for (int idx = threadIdx.x; idx < n; idx += MEGA_THREADS) {
+                const int e = idx % P.hd, rest = idx / P.hd, c = rest % P.M, pl = rest / P.M;
+                store_unset(o.base + pl * o.plane + (size_t)(b * P.M + c) * o.ld + h * P.hd + e);
             }
         }
     }
@@ -474,11 +620,11 @@ __device__ __forceinline__ void slab_finish(const MegaCall &P, int pr0, int G, b
 
 // ---------------------------------------------------------------- GEMM chunk + tile epilogue
 
+// Epilogue of one output element: A-row i (0..15) of tile `tile` for hidden row c.  Paired epilogues
+// (gate/up, rotary) are called for i < 8 with `partner` = the value of A-row i + 8.
 template <typename T>
-__device__ __forceinline__ void tile_epilogue(const MegaCall &P, const MegaPhase &ph, const Range &r, int tile, float sum,
-                                              int v, float &rowsq, MegaSmem &sm) {
-    const int lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
-    const int i = 4 * g + v; // A-row of this element; the B row (hidden row) is c
+__device__ __forceinline__ void elem_epilogue(const MegaCall &P, const MegaPhase &ph, const Range &r, int tile, int i, int c, float sum,
+                                              float partner, float &rowsq, MegaSmem &sm) {
     bool live;
     const int n = a_row(ph.kind, ph.N, r, P.hd, tile, i, live);
     if (ph.kind == PH_RESID) {
@@ -488,7 +634,7 @@ __device__ __forceinline__ void tile_epilogue(const MegaCall &P, const MegaPhase
             // first layer, by the embedding phase, which no cache of this XCD has seen yet)
             const float hn = P.h[o] + sum;
             st_coh(&P.h[o], hn);
-            ActPlanes<T> act{reinterpret_cast<T *>(P.act[ACT_A]), P.act_plane[ACT_A], P.act_ld[ACT_A]};
+            const ActPlanes<T> act = act_planes<T>(P, ph.act_dst);
             store_act_coh(act, (size_t)c * act.ld + n, ph.gain ? hn * ldf_global(ph.gain + n) : hn); // no gain: nothing normalises these rows
             rowsq += hn * hn;
         }
@@ -498,13 +644,11 @@ __device__ __forceinline__ void tile_epilogue(const MegaCall &P, const MegaPhase
         if (live && c < P.head_rows) P.logits[(size_t)c * P.ldo + n] = sum * sm.t->scale[P.head_row0 + c * P.head_stride];
         return;
     }
-    // paired epilogues: lanes g < 2 hold the first row of a pair, lane + 32 holds its partner
-    const float partner = __shfl_down(sum, 32);
-    if (g >= 2 || !live || c >= P.R) return;
+    if (!live || c >= P.R) return;
     const float sc = sm.t->scale[c];
     const float x0s = sum * sc, x1s = partner * sc;
     if (ph.kind == PH_SWIGLU) {
-        ActPlanes<T> z{reinterpret_cast<T *>(P.act[ACT_Z]), P.act_plane[ACT_Z], P.act_ld[ACT_Z]};
+        const ActPlanes<T> z = act_planes<T>(P, ACT_Z);
         const float s = x0s / (1.0f + expf(-x0s));
         store_act_coh(z, (size_t)c * z.ld + n, s * x1s); // n = pair index = column of z
         return;
@@ -523,7 +667,7 @@ __device__ __forceinline__ void tile_epilogue(const MegaCall &P, const MegaPhase
         x1 = x0s * cs.y + x1s * cs.x;
     }
     if (region == 0) {
-        ActPlanes<T> q{reinterpret_cast<T *>(P.act[ACT_Q]), P.act_plane[ACT_Q], P.act_ld[ACT_Q]};
+        const ActPlanes<T> q = act_planes<T>(P, ACT_Q);
         const size_t o = (size_t)c * q.ld + h * P.hd + j;
         store_act_coh(q, o, x0);
         store_act_coh(q, o + P.hd / 2, x1);
@@ -598,18 +742,30 @@ __device__ __forceinline__ void finish_tile(int tile, const f32x4 &acc0, const f
     ++nstash;
 }
 
-// epilogues of the stashed tiles, spread over all waves: entry (slot, v) -> wave (slot*4 + v) % MNW
+// Epilogues of the stashed tiles, one output element per thread and pass: thread t takes hidden row
+// c = t & 15 (which keeps a thread's contribution to the row sums of squares on one row) and A-row
+// t >> 4 of a tile (paired epilogues: pair (t >> 4) & 7 of one of two tiles).  Element (i, c) of a
+// reduced tile sits in the stash at [register i & 3][lane c + 16 * (i >> 2)] (MFMA output layout).
+// A wave-per-accumulator-register split would run the same ~150 instructions six times per wave
+// with 10 of 64 lanes doing useful work, which took 2.5 us at every phase end.
 template <typename T>
 __device__ __forceinline__ void flush_stash(const MegaCall &P, const MegaPhase &ph, const Range &r, int &nstash, float &rowsq,
                                             bool last, MegaSmem &sm) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     lds_barrier(); // the stash writes of the last tile are visible
-    for (int e = wave; e < nstash * 4; e += MNW) {
-        const int slot = e >> 2, v = e & 3;
-        tile_epilogue<T>(P, ph, r, sm.t->stash_tile[slot], sm.t->stash[slot][v][lane], v, rowsq, sm);
+    const int c = threadIdx.x & 15, ii = threadIdx.x >> 4;
+    if (ph.kind == PH_QKV || ph.kind == PH_SWIGLU) {
+        const int i = ii & 7;
+        for (int slot = ii >> 3; slot < nstash; slot += MEGA_THREADS / 128) {
+            const float sum = sm.t->stash[slot][i & 3][c + 16 * (i >> 2)];
+            const float partner = sm.t->stash[slot][i & 3][c + 16 * (i >> 2) + 32];
+            elem_epilogue<T>(P, ph, r, sm.t->stash_tile[slot], i, c, sum, partner, rowsq, sm);
+        }
+    } else {
+        for (int slot = 0; slot < nstash; ++slot)
+            elem_epilogue<T>(P, ph, r, sm.t->stash_tile[slot], ii, c, sm.t->stash[slot][ii & 3][c + 16 * (ii >> 2)], 0.f, rowsq, sm);
     }
     nstash = 0;
-    if (last) return; // end of the phase: the phase boundary waits for the stores and synchronises
+    if (last) return; // end of the phase: the phase boundary synchronises
     stores_done(); // the next segment starts with no store pending
     lds_barrier(); // nobody overwrites the stash before everyone has read it
 }
@@ -625,6 +781,7 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
     const int wg = blockIdx.x, G = gridDim.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (threadIdx.x < 16) sm.t->len[threadIdx.x] = (int)threadIdx.x < P.B ? P.len[threadIdx.x] : 0; // lengths change in the last phase only
+    if (threadIdx.x == 0) sm.t->ok = 1;
     lds_barrier();
 
     // Weight pipeline: `la` runs RING positions ahead of `cc` (the next chunk to multiply); the loads of
@@ -664,46 +821,25 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
         const MegaPhase ph = P.phases[p];
         // Phase boundary: all ring slots are filled unconditionally (loads of zeros when this
         // workgroup has no share of the phase), which also tells the compiler that the slots hold
-        // nothing across a phase that does not use them.  The fills come after the wave's stores are
-        // acknowledged, so the wait for the stores does not drain them.
+        // nothing across a phase that does not use them.
         cursor_begin<T>(st.cc, ph, P.hd, wg, G);
         st.la = st.cc;
-        if (p > 0) {
-            stores_done();
-            grid_arrive(P, P.epoch_base + (unsigned)p, sm);
-        }
-        if (wave != 0) { // wave 0 polls memory in the barrier, which would wait for these loads
-#pragma unroll
-            for (int sl = 0; sl < RING; ++sl) fill(ring[sl]);
-        }
-        if (p > 0) {
-            const int attn_units = P.B * P.H * P.nsplit;
-            if (ph.kind == PH_ATTN && attn_units <= G) { // one unit per workgroup at most: wait for its producers only
-                if (wg < attn_units && !grid_wait_qkv_of_head(P, P.epoch_base + (unsigned)p, (wg / P.nsplit) % P.H, G, sm)) return;
-            } else if (!grid_wait(P, P.epoch_base + (unsigned)p, G, sm)) {
-                return;
-            }
-        }
-        if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(5 * p) * G + wg] = wall_clock64();
+        const unsigned epoch = P.epoch_base + (unsigned)p;
+        const int attn_units = P.B * P.H * P.nsplit;
         const bool want_scales = ph.kind == PH_QKV || ph.kind == PH_SWIGLU || ph.kind == PH_HEAD;
-        if (wave == 0) {
-#pragma unroll
-            for (int sl = 0; sl < RING; ++sl) fill(ring[sl]);
+        // How this phase's input becomes visible.  Flags: the producers wait for their stores, publish
+        // their epoch, and the consumer polls the epochs before it loads anything.  Data: nobody waits
+        // for acknowledgements; the consumer loads the first slab at once (together with the weight
+        // prefetch) and validates it (slab_unset, slab_retry).  After the attention phase the workgroups without
+        // a unit would find nothing for a long time, so they first wait for the units' epochs (a hint:
+        // the data is validated all the same).
+        const bool polled = P.data_sync && ph.sync != SYNC_FLAGS && st.cc.active;
+        const bool hint_first = polled && ph.sync == SYNC_DATA_ATTN && wg >= attn_units;
+        const bool spec = polled && !hint_first;
+        if (p > 0) {
+            if (!polled) stores_done(); // (a workgroup without a share of a data-synchronised phase cannot occur: the host checks)
+            grid_arrive(P, epoch, sm);
         }
-        st.rowsq = 0.f;
-        switch (ph.kind) {
-        case PH_EMBED: do_embed<T>(P, ph, wg, G, sm); break;
-        case PH_ATTN:
-            do_attn<T>(P, ph, wg, G, sm);
-            st.slab_tag = -1; // the attention area aliases the slab
-            break;
-        case PH_LEN:
-            if (wg == 0 && (int)threadIdx.x < P.B) P.len[threadIdx.x] += P.M;
-            break;
-        default: break;
-        }
-        if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(5 * p + 1) * G + wg] = wall_clock64();
-
         int nstash = 0;
         const Range my = st.cc.r; // this workgroup's share of the phase
         // One segment: n_fill rounds of RING steps in which each step refills its slot, then (last: the
@@ -729,6 +865,98 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
                 for (int sl = 0; sl < RING; ++sl) step(std::false_type{}, ring[sl]);
             }
         };
+        // One K slab of the B operand into LDS, in batches of 10 (plane, row) pairs, one memory round trip
+        // each (5 rows of a bf16 model: one batch).
+        // false: a bounded wait for the data ran out (every wave of the workgroup returns the same).
+        auto load_slab = [&](int slab, bool scales, bool fills, SlabLoads<10> &L) __attribute__((always_inline)) {
+            bool ok = true;
+            slab_issue<T>(P, ph, slab, 0, G, scales, L);
+            asm volatile("" ::: "memory"); // keeps the compiler from fusing the two loops (load, wait, store per row)
+            // The first look at the data is straight-line code behind the loads (once per branch), so it
+            // waits for them with an exact count and leaves the younger weight prefetch in flight.
+            bool dirty;
+            if (fills) { // the weight prefetch goes out behind the slab: loads return in order, and the slab is needed first
+#pragma unroll
+                for (int sl = 0; sl < RING; ++sl) fill(ring[sl]);
+                dirty = polled && __any(slab_unset<T>(P, ph, slab, 0, G, scales, L));
+            } else {
+                dirty = polled && __any(slab_unset<T>(P, ph, slab, 0, G, scales, L));
+            }
+            if (dirty) ok = slab_retry<T>(P, ph, slab, 0, G, scales, L);
+            lds_barrier(); // every wave is done with the previous slab
+            slab_finish<T>(P, ph, slab, 0, G, scales, L, sm);
+            if (Traits<T>::PLANES * P.slab_rows > 10) {
+                slab_issue<T>(P, ph, slab, 10, G, false, L);
+                asm volatile("" ::: "memory");
+                if (polled && ok && __any(slab_unset<T>(P, ph, slab, 10, G, false, L))) ok = slab_retry<T>(P, ph, slab, 10, G, false, L);
+                slab_finish<T>(P, ph, slab, 10, G, false, L, sm);
+            }
+            if (!ok && lane == 0) {
+                sm.t->ok = 0;
+                __hip_atomic_store(P.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (P.timeline && threadIdx.x == 0 && st.cc.idx == 0) P.timeline[(size_t)(5 * p + 2) * G + wg] = wall_clock64();
+            lds_barrier();
+            return sm.t->ok != 0;
+        };
+        const bool multi_slab = st.cc.nck > SLAB_CK;
+        const bool clears = P.data_sync && ph.clear_phase >= 0;
+        st.rowsq = 0.f;
+        if (st.cc.active) {
+            // GEMM phase with work: the first slab is loaded (and, with data synchronisation, validated) in the loop below
+            // (spec: the ring is filled right behind the first slab's loads, see load_slab)
+            if (wave != 0 && !spec) { // wave 0 polls memory in a barrier, which would wait for these loads
+#pragma unroll
+                for (int sl = 0; sl < RING; ++sl) fill(ring[sl]);
+            }
+            if (p > 0 && !spec) {
+                if (hint_first ? !grid_wait(P, epoch, 0, min(attn_units, G), sm) : !grid_wait(P, epoch, 0, G, sm)) return;
+            }
+            if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(5 * p) * G + wg] = wall_clock64();
+            if (wave == 0 && !spec) {
+#pragma unroll
+                for (int sl = 0; sl < RING; ++sl) fill(ring[sl]);
+            }
+            if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(5 * p + 1) * G + wg] = wall_clock64();
+        } else {
+            // No GEMM work in this phase (embedding, attention, length update, or no share of a small
+            // GEMM): the weight ring is not used; giving it a constant value here tells the compiler
+            // that nothing of it lives across the attention code.
+#pragma unroll
+            for (int sl = 0; sl < RING; ++sl)
+#pragma unroll
+                for (int k = 0; k < 2 * CH; ++k) ring[sl][k] = zero16();
+            if (p > 0) {
+                if (ph.kind == PH_ATTN && attn_units <= G) { // one unit per workgroup at most: wait for its producers only
+                    if (wg < attn_units && !grid_wait_qkv_of_head(P, epoch, (wg / P.nsplit) % P.H, G, sm)) return;
+                } else if (!grid_wait(P, epoch, 0, G, sm)) {
+                    return;
+                }
+            }
+            if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(5 * p) * G + wg] = wall_clock64();
+            switch (ph.kind) {
+            case PH_EMBED:
+                if (clears) clear_outputs<T>(P, P.phases[ph.clear_phase], wg, G);
+                do_embed<T>(P, ph, wg, G, sm);
+                break;
+            case PH_ATTN:
+                do_attn<T>(P, ph, wg, G, sm);
+                st.slab_tag = -1; // the attention area aliases the slab
+                break;
+            case PH_LEN:
+                if (wg == 0 && (int)threadIdx.x < P.B) P.len[threadIdx.x] += P.M;
+                break;
+            case PH_RESID: // no share of the new hidden rows: this workgroup's partial sums of squares are zero
+                if (threadIdx.x < 16) st_coh(&nsq_set(P, ph.act_dst, G)[(size_t)threadIdx.x * G + wg], 0.f);
+                break;
+            default: break;
+            }
+            if (P.timeline && threadIdx.x == 0) {
+                P.timeline[(size_t)(5 * p + 1) * G + wg] = wall_clock64();
+                P.timeline[(size_t)(5 * p + 4) * G + wg] = wall_clock64();
+            }
+            continue;
+        }
         while (st.cc.active) {
             // one segment = rounds that share an LDS slab and fit the stash
             const Cursor &cc = st.cc;
@@ -743,20 +971,11 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
             const bool final_round = last_group && n == grp_rounds; // the phase ends with this segment
             const int tag = (p << 8) | (cc.ck / SLAB_CK);
             if (st.slab_tag != tag) {
-                lds_barrier(); // every wave is done with the previous slab
-                const bool ws = want_scales && cc.idx == 0; // first slab of the phase: with the row scales
-                // batches of 10 (plane, row) pairs, one memory round trip each (5 rows of a bf16 model: one batch)
-                auto batch = [&](int pr0, bool scales) {
-                    SlabLoads<10> L;
-                    slab_issue<T>(P, ph, cc.ck / SLAB_CK, pr0, G, scales, L);
-                    asm volatile("" ::: "memory"); // keeps the compiler from fusing the two loops (load, wait, store per row)
-                    slab_finish<T>(P, pr0, G, scales, L, sm);
-                };
-                batch(0, ws);
-                if (Traits<T>::PLANES * P.slab_rows > 10) batch(10, false);
-                if (P.timeline && threadIdx.x == 0 && cc.idx == 0) P.timeline[(size_t)(5 * p + 2) * G + wg] = wall_clock64();
-                lds_barrier();
+                SlabLoads<10> L;
+                if (!load_slab(cc.ck / SLAB_CK, want_scales && cc.idx == 0, spec && cc.idx == 0, L)) return; // first slab of the phase: with the row scales
                 st.slab_tag = tag;
+                // the whole input has been seen once the first tile's last slab is in; the resets are acknowledged before the rounds start
+                if (clears && cc.tile == 0 && (!multi || grp_end == cc.nck)) clear_outputs<T>(P, P.phases[ph.clear_phase], wg, G);
             }
             run_segment(final_round ? n - 1 : n, final_round);
             if (P.timeline && threadIdx.x == 0 && final_round) P.timeline[(size_t)(5 * p + 3) * G + wg] = wall_clock64();
@@ -773,7 +992,7 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
                 float tot = 0.f;
 #pragma unroll
                 for (int w2 = 0; w2 < MNW; ++w2) tot += sm.t->sq[w2][threadIdx.x];
-                st_coh(&P.nsq[(size_t)threadIdx.x * G + wg], tot);
+                st_coh(&nsq_set(P, ph.act_dst, G)[(size_t)threadIdx.x * G + wg], tot);
             }
         }
         if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(5 * p + 4) * G + wg] = wall_clock64();

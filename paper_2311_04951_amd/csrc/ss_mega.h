@@ -17,7 +17,23 @@ enum PhaseKind : int {
     PH_LEN        // cache lengths += M
 };
 
-enum ActBuf : int { ACT_A = 0, ACT_Q = 1, ACT_O = 2, ACT_Z = 3, ACT_COUNT = 4 };
+// ACT_A / ACT_A1: the packed hidden rows alternate between two buffers (the down projection and the
+// embedding write ACT_A, the O projection writes ACT_A1), so that one can be cleared while the other is read
+enum ActBuf : int { ACT_A = 0, ACT_Q = 1, ACT_O = 2, ACT_Z = 3, ACT_A1 = 4, ACT_COUNT = 5 };
+
+// How the inputs of a phase become visible to a workgroup (MegaPhase::sync)
+enum PhaseSync : int {
+    SYNC_FLAGS = 0,     // device-wide barrier on the arrival flags, producers wait for their stores first
+    SYNC_DATA = 1,      // self-validating data: the consumer polls the activation slab itself
+    SYNC_DATA_ATTN = 2  // same; the producers are the attention units (workgroups without a unit wait for their flags first)
+};
+
+// activation planes: element (row, col) of plane pl lives at base[pl*plane + row*ld + col]
+struct ActDesc {
+    void *base;
+    size_t plane; // elements between planes
+    int ld;       // elements between rows
+};
 
 struct MegaPhase {
     int kind, layer;
@@ -26,6 +42,9 @@ struct MegaPhase {
     int K;
     int act_src;       // activation planes read (B operand)
     const float *gain; // EMBED / RESID: gain of the NEXT RMSNorm, folded in when the new rows are packed
+    int act_dst;       // EMBED / RESID: activation planes written (ACT_A or ACT_A1); the norm partials use the same parity
+    int sync;          // PhaseSync, honoured when MegaCall::data_sync is set
+    int clear_phase;   // index of the later phase whose outputs this phase resets to the "not written yet" pattern (-1: none)
 };
 
 struct MegaCall {
@@ -39,10 +58,9 @@ struct MegaCall {
     const int32_t *tokens; // NULL: rows are taken from h as given
     const void *embed;
     float *h;              // [R][d] residual stream (in/out)
-    void *act[ACT_COUNT];  // activation planes
-    size_t act_plane[ACT_COUNT];
-    int act_ld[ACT_COUNT];
-    float *nsq;            // [16][G] per-workgroup partial sums of squares of the rows of h
+    ActDesc act_a, act_q, act_o, act_z, act_a1; // activation planes, one named field per ActBuf (an array here would be indexed at run time,
+                                                // which makes the compiler keep a copy of the whole argument in scratch memory)
+    float *nsq;            // [2][16][G] per-workgroup partial sums of squares of the rows of h (index 0 goes with ACT_A, 1 with ACT_A1)
     // LM head: output row r reads activation row head_row0 + r*head_stride
     float *logits;
     int ldo, head_rows, head_row0, head_stride;
@@ -63,9 +81,10 @@ struct MegaCall {
     unsigned epoch_base;
     unsigned spin_limit;
     int32_t *status;
+    int data_sync;     // 1: phases marked SYNC_DATA* poll their input data instead of waiting at a barrier
     const void *zeros; // >= 64 zero bytes: the target of weight loads that have no data to fetch
     int slab_rows, u_bytes;       // set by launch_mega: rows held in the LDS slab, size of the slab area
-    unsigned long long *timeline; // optional [3*n_phases][G] device clock samples of every workgroup (NULL: off)
+    unsigned long long *timeline; // optional [5*n_phases][G] device clock samples of every workgroup (NULL: off)
 };
 
 constexpr int MEGA_THREADS = 256;

@@ -22,11 +22,21 @@ def model_pair(shape, seed, max_rows=16, max_pos=256, persistent=False):
     """(oracle model, GPU model, host weights) over identical seeded weights."""
     w = si.decoder_weights(shape, seed)
     gm = sv.Model(shape, weights_to_device(w), max_rows=max_rows, max_pos=max_pos)
-    sv.ss_model_set_persistent(gm, persistent)
+    set_path(gm, persistent)
     return oracle.Model(shape, w), gm, w
 
 
-PATHS = [False, True]   # per-phase launches, persistent kernel
+# Forward paths under test: per-phase launches; the persistent kernel as it runs by default (on these
+# small shapes a grid of one workgroup per compute unit leaves workgroups without a share of some
+# phase, so every phase boundary is a barrier); the persistent kernel on a grid of 8 workgroups, where
+# every workgroup owns part of every GEMM phase and the activations synchronise themselves.
+PATHS = [False, True, "grid8"]
+
+
+def set_path(gm, path):
+    sv.ss_model_set_persistent(gm, bool(path))
+    if isinstance(path, str):
+        sv.ss_model_set_persistent_options(gm, int(path[4:]), True)
 
 
 def tol(shape):

@@ -10,7 +10,7 @@ import torch
 import oracle
 import paper_2311_04951_amd as sv
 import seeded_inputs as si
-from gpu_util import PATHS, dev, maxabs, model_pair, tol, weights_to_device
+from gpu_util import PATHS, dev, maxabs, model_pair, set_path, tol, weights_to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -41,6 +41,7 @@ def test_fp32_verify_logits_match_oracle(shape, persistent):
 
 
 @pytest.mark.parametrize("shape", [si.DecoderShape(2, 128, 2, 64, 344, 512, dtype="bf16"),
+                                   si.DecoderShape(2, 128, 2, 64, 4608, 512, dtype="bf16"),   # down projection: K spans two LDS slabs
                                    si.DecoderShape(1, 512, 4, 128, 1376, 1000, dtype="bf16"),
                                    si.DecoderShape(3, 256, 8, 32, 688, 333, dtype="bf16")])
 @pytest.mark.parametrize("persistent", PATHS)
@@ -78,7 +79,7 @@ def test_rollback_then_reverify_matches_oracle(persistent):
 
 
 @pytest.mark.parametrize("B,M,persistent", [(3, 9, False), (3, 5, True), (3, 5, False), (5, 9, False), (8, 9, False),
-                                            (3, 3, True), (1, 9, True), (4, 4, True)])   # 9 and 16 rows: the persistent kernel's largest calls (bf16 / fp32)
+                                            (3, 3, True), (1, 9, True), (4, 4, True), (3, 3, "grid8"), (1, 9, "grid8"), (4, 4, "grid8")])   # 9 and 16 rows: the persistent kernel's largest calls (bf16 / fp32)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_batched_ragged_lengths_match_per_sequence_oracle(dtype, B, M, persistent):
     """Several sequences with different context lengths verified in one call (up to 72 rows: every
@@ -88,7 +89,7 @@ def test_batched_ragged_lengths_match_per_sequence_oracle(dtype, B, M, persisten
     w = si.decoder_weights(shape, seed=6)
     om = oracle.Model(shape, w)
     gm = sv.Model(shape, weights_to_device(w), max_rows=80, max_pos=512)
-    sv.ss_model_set_persistent(gm, persistent)
+    set_path(gm, persistent)
     lens = [70, 3, 129, 40, 1, 100, 64, 17][:B]
     gkv = sv.KVCache(gm, B, 200)
     toks = si.token_ids(6, "toks", (B, M), shape.vocab)
@@ -121,7 +122,7 @@ def test_single_7b_layer_verify_matches_oracle(persistent):
     w = {"embed": None, "gf": None, "lm_head": None, "layers": [lw]}
     om = oracle.Model(shape, w)
     gm = sv.Model(shape, weights_to_device(w), max_rows=16, max_pos=2048)
-    sv.ss_model_set_persistent(gm, persistent)
+    set_path(gm, persistent)
     L, M = 1024, 5
     ctx = si.kv_context(shape, 0, "ctx", L)
     gkv = sv.KVCache(gm, 1, L + 64)

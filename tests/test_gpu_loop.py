@@ -9,7 +9,7 @@ import oracle
 import paper_2311_04951_amd as sv
 import seeded_inputs as si
 from paper_2311_04951_amd import generate as gen
-from gpu_util import PATHS, dev, maxabs, weights_to_device
+from gpu_util import PATHS, dev, maxabs, set_path, weights_to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -22,8 +22,8 @@ def _pair(seed, early=False, persistent=False):
         dshape, dw = si.TINY_DRAFT, si.decoder_weights(si.TINY_DRAFT, seed + 100)
     gt = sv.Model(si.TINY_TARGET, weights_to_device(tw), max_rows=16, max_pos=256)
     gd = sv.Model(dshape, weights_to_device(dw), max_rows=16, max_pos=256)
-    sv.ss_model_set_persistent(gt, persistent)
-    sv.ss_model_set_persistent(gd, persistent)
+    set_path(gt, persistent)
+    set_path(gd, persistent)
     return (oracle.Model(si.TINY_TARGET, tw), oracle.Model(dshape, dw)), (gt, gd)
 
 
