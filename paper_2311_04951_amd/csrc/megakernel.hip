@@ -620,11 +620,34 @@ __device__ __forceinline__ void clear_outputs(const MegaCall &P, const MegaPhase
 
 // ---------------------------------------------------------------- GEMM chunk + tile epilogue
 
+// What a thread carries from the start of a phase to its epilogue.  A workgroup with a single tile of
+// a residual phase (the usual case) fetches its element of h and of the gain while the weights
+// stream, instead of paying a memory round trip between the last MFMA and the stores.
+struct EpiState {
+    float rowsq;       // this thread's share of the row sums of squares of the new hidden rows
+    float h_pre, g_pre;
+    bool pre;          // h_pre / g_pre hold h[c][n] and gain[n] of this thread's element of tile 0
+};
+// this thread's element of a residual phase's tile: A-row t >> 4, hidden row t & 15 (see flush_stash)
+__device__ __forceinline__ void epi_prefetch(const MegaCall &P, const MegaPhase &ph, const Range &r, EpiState &es) {
+    es.pre = ph.kind == PH_RESID && r.ntiles == 1;
+    es.h_pre = 0.f;
+    es.g_pre = 1.f;
+    if (!es.pre) return;
+    const int c = threadIdx.x & 15, i = threadIdx.x >> 4;
+    bool live;
+    const int n = a_row(ph.kind, ph.N, r, P.hd, 0, i, live);
+    if (live && c < P.R) {
+        es.h_pre = P.h[(size_t)c * P.d + n]; // plain load: see elem_epilogue
+        if (ph.gain) es.g_pre = ldf_global(ph.gain + n);
+    }
+}
+
 // Epilogue of one output element: A-row i (0..15) of tile `tile` for hidden row c.  Paired epilogues
 // (gate/up, rotary) are called for i < 8 with `partner` = the value of A-row i + 8.
 template <typename T>
 __device__ __forceinline__ void elem_epilogue(const MegaCall &P, const MegaPhase &ph, const Range &r, int tile, int i, int c, float sum,
-                                              float partner, float &rowsq, MegaSmem &sm) {
+                                              float partner, EpiState &es, MegaSmem &sm) {
     bool live;
     const int n = a_row(ph.kind, ph.N, r, P.hd, tile, i, live);
     if (ph.kind == PH_RESID) {
@@ -632,11 +655,12 @@ __device__ __forceinline__ void elem_epilogue(const MegaCall &P, const MegaPhase
             const size_t o = (size_t)c * P.d + n;
             // plain load: these columns of h are only ever written by this workgroup (and, before the
             // first layer, by the embedding phase, which no cache of this XCD has seen yet)
-            const float hn = P.h[o] + sum;
+            const float hn = (es.pre ? es.h_pre : P.h[o]) + sum;
             st_coh(&P.h[o], hn);
             const ActPlanes<T> act = act_planes<T>(P, ph.act_dst);
-            store_act_coh(act, (size_t)c * act.ld + n, ph.gain ? hn * ldf_global(ph.gain + n) : hn); // no gain: nothing normalises these rows
-            rowsq += hn * hn;
+            const float gn = es.pre ? es.g_pre : (ph.gain ? ldf_global(ph.gain + n) : 1.f); // no gain: nothing normalises these rows
+            store_act_coh(act, (size_t)c * act.ld + n, ph.gain ? hn * gn : hn);
+            es.rowsq += hn * hn;
         }
         return;
     }
@@ -749,7 +773,7 @@ __device__ __forceinline__ void finish_tile(int tile, const f32x4 &acc0, const f
 // A wave-per-accumulator-register split would run the same ~150 instructions six times per wave
 // with 10 of 64 lanes doing useful work, which took 2.5 us at every phase end.
 template <typename T>
-__device__ __forceinline__ void flush_stash(const MegaCall &P, const MegaPhase &ph, const Range &r, int &nstash, float &rowsq,
+__device__ __forceinline__ void flush_stash(const MegaCall &P, const MegaPhase &ph, const Range &r, int &nstash, EpiState &es,
                                             bool last, MegaSmem &sm) {
     lds_barrier(); // the stash writes of the last tile are visible
     const int c = threadIdx.x & 15, ii = threadIdx.x >> 4;
@@ -758,11 +782,11 @@ __device__ __forceinline__ void flush_stash(const MegaCall &P, const MegaPhase &
         for (int slot = ii >> 3; slot < nstash; slot += MEGA_THREADS / 128) {
             const float sum = sm.t->stash[slot][i & 3][c + 16 * (i >> 2)];
             const float partner = sm.t->stash[slot][i & 3][c + 16 * (i >> 2) + 32];
-            elem_epilogue<T>(P, ph, r, sm.t->stash_tile[slot], i, c, sum, partner, rowsq, sm);
+            elem_epilogue<T>(P, ph, r, sm.t->stash_tile[slot], i, c, sum, partner, es, sm);
         }
     } else {
         for (int slot = 0; slot < nstash; ++slot)
-            elem_epilogue<T>(P, ph, r, sm.t->stash_tile[slot], ii, c, sm.t->stash[slot][ii & 3][c + 16 * (ii >> 2)], 0.f, rowsq, sm);
+            elem_epilogue<T>(P, ph, r, sm.t->stash_tile[slot], ii, c, sm.t->stash[slot][ii & 3][c + 16 * (ii >> 2)], 0.f, es, sm);
     }
     nstash = 0;
     if (last) return; // end of the phase: the phase boundary synchronises
@@ -795,13 +819,16 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
         Cursor cc, la;
         f32x4 acc0, acc1;
         int tile_seq, slab_tag;
-        float rowsq;
+        EpiState es;
     } st;
     st.acc0 = f32x4{0.f, 0.f, 0.f, 0.f};
     st.acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
     st.tile_seq = 0;
     st.slab_tag = -1;
-    st.rowsq = 0.f;
+    st.es.rowsq = 0.f;
+    st.es.pre = false;
+    st.es.h_pre = 0.f;
+    st.es.g_pre = 1.f;
 
     u32x4 ring[RING][2 * CH]; // only ever indexed by unrolled constants: lives in registers
     static_assert(MNW >= 4, "waves 0-3 reduce one accumulator register each");
@@ -901,9 +928,10 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
         };
         const bool multi_slab = st.cc.nck > SLAB_CK;
         const bool clears = P.data_sync && ph.clear_phase >= 0;
-        st.rowsq = 0.f;
+        st.es.rowsq = 0.f;
         if (st.cc.active) {
             // GEMM phase with work: the first slab is loaded (and, with data synchronisation, validated) in the loop below
+            epi_prefetch(P, ph, my, st.es);
             // (spec: the ring is filled right behind the first slab's loads, see load_slab)
             if (wave != 0 && !spec) { // wave 0 polls memory in a barrier, which would wait for these loads
 #pragma unroll
@@ -979,11 +1007,11 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
             }
             run_segment(final_round ? n - 1 : n, final_round);
             if (P.timeline && threadIdx.x == 0 && final_round) P.timeline[(size_t)(5 * p + 3) * G + wg] = wall_clock64();
-            if (final_round || stash_room() < 1) flush_stash<T>(P, ph, my, nstash, st.rowsq, final_round, sm);
+            if (final_round || stash_room() < 1) flush_stash<T>(P, ph, my, nstash, st.es, final_round, sm);
         }
         if (ph.kind == PH_RESID) {
             // publish this workgroup's partial sums of squares of the new hidden rows
-            float rs = st.rowsq;
+            float rs = st.es.rowsq;
             rs += __shfl_xor(rs, 16);
             rs += __shfl_xor(rs, 32);
             if (lane < 16) sm.t->sq[wave][lane] = rs;
