@@ -3,13 +3,21 @@
 //
 // One workgroup of 4 wavefronts per compute unit (512 registers per lane) stays resident for the whole
 // pass and walks a list of phases: [embedding] then per layer [QKV, attention, O projection, gate/up,
-// down projection], then [LM head] and [cache-length update].  Consecutive phases are separated by a
-// device-wide barrier (each workgroup publishes an epoch in its own slot and polls all slots: no
-// atomics on a shared counter; the spin is bounded and sets an abort flag that makes every workgroup
-// leave).  The barrier carries no cache write-back / invalidate: everything one workgroup writes for
+// down projection], then [LM head] and [cache-length update].  Everything one workgroup writes for
 // another to read inside the kernel (hidden rows, packed activations, norm partials, new cache rows,
 // attention partials) moves through agent-coherent accesses, which are performed at the memory side of
-// the per-XCD L2 caches.
+// the per-XCD L2 caches, so no phase boundary carries a cache write-back / invalidate.  Two ways of
+// ordering consumers behind producers are used:
+//  * flags: a device-wide barrier (each workgroup waits for its store acknowledgements, publishes an
+//    epoch in its own slot and polls the slots it depends on: no atomics on a shared counter).  Used
+//    in front of the first layer, in front of attention (an attention unit polls only the owners of
+//    its head's Q, K, V tiles) and at the end;
+//  * data: between GEMM phases the activations validate themselves.  Every element a phase will write
+//    is reset beforehand to a reserved bit pattern, the consumer loads its LDS slab without waiting
+//    for anybody and loads again whatever still shows the pattern (see slab_unset, slab_retry and
+//    clear_outputs).  This removes three dependent trips through the memory fabric (acknowledgement,
+//    flag, poll) from every such boundary.
+// All waits are bounded and raise an abort flag that makes every workgroup leave.
 //
 // Every workgroup owns a fixed, byte-balanced share of each weight matrix (a contiguous range of
 // output rows / of gate-up or rotary pairs), so the sequence of 16-byte weight chunks a wavefront
@@ -18,14 +26,14 @@
 // ahead.  The loops that do this contain no other global memory operation and every refill issues the
 // same number of loads, pinned in program order, which is what lets the compiler wait for exactly one
 // slot (s_waitcnt vmcnt(N)) while the others stay in flight.  The ring is refilled with the first
-// chunks of the next phase at each phase boundary, after the arrival flag is written, so those loads
-// fly during the barrier.
+// chunks of the next phase at each phase boundary (behind the loads of the activation slab, which is
+// needed first), so those loads fly while the boundary's dependencies resolve.
 //
 // GEMM tiles are 16 weight rows (MFMA A operand) x all K; the waves interleave over K in 128-byte
 // steps and their partial 16x16 tiles are summed in a fixed order through LDS; the reduced tiles wait
 // in an LDS stash and their epilogues (and global stores) run outside the chunk loops.  Paired
 // epilogues put the two rows of a pair (gate/up, or rotary j and j + hd/2) 8 rows apart in the same
-// tile, so the partner is one wave-shuffle away.  RMSNorm is folded into the GEMMs: the producer packs
+// tile, so one thread finds both values of a pair in the same stashed tile.  RMSNorm is folded into the GEMMs: the producer packs
 // h * gain and publishes per-workgroup partial sums of squares, the consumer multiplies its outputs by
 // the row scale.  The hidden rows a phase multiplies with (B operand) are copied once per phase (per
 // 8 KB of K per row) into LDS, all loads of the copy in flight together.
@@ -1020,7 +1028,7 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
                 float tot = 0.f;
 #pragma unroll
                 for (int w2 = 0; w2 < MNW; ++w2) tot += sm.t->sq[w2][threadIdx.x];
-                st_coh(&nsq_set(P, ph.act_dst, G)[(size_t)threadIdx.x * G + wg], tot);
+                st_coh(&nsq_set(P, ph.act_dst, G)[(size_t)threadIdx.x * G + wg], f2u(tot) == 0xffffffffu ? u2f(0xffc00000u) : tot); // the all-ones pattern is reserved
             }
         }
         if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(5 * p + 4) * G + wg] = wall_clock64();

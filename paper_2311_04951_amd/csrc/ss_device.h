@@ -167,13 +167,19 @@ template <typename T> __device__ __forceinline__ Act<T> load_act_coh(const ActPl
     for (int pl = 0; pl < Traits<T>::PLANES; ++pl) r.p[pl] = ld16_coh_buf(a.base, (uint32_t)((pl * a.plane + off) * sizeof(T)));
     return r;
 }
+// The all-ones bit pattern is reserved (the persistent kernel uses it for "not written yet"): a NaN
+// that happens to carry it is stored as another NaN.
 __device__ __forceinline__ void store_act_coh(const ActPlanes<bf16_t> &a, size_t off, float x) {
     uint32_t hi = bf16_rne(x);
     uint32_t lo = bf16_rne(x - bf16_bits_to_f32(hi));
+    hi = hi == 0xffffu ? 0xffc0u : hi;
+    lo = lo == 0xffffu ? 0xffc0u : lo;
     st_coh(a.base + off, bf16_t{(uint16_t)hi});
     st_coh(a.base + a.plane + off, bf16_t{(uint16_t)lo});
 }
-__device__ __forceinline__ void store_act_coh(const ActPlanes<float> &a, size_t off, float x) { st_coh(a.base + off, x); }
+__device__ __forceinline__ void store_act_coh(const ActPlanes<float> &a, size_t off, float x) {
+    st_coh(a.base + off, f2u(x) == 0xffffffffu ? u2f(0xffc00000u) : x);
+}
 
 __device__ __forceinline__ float wave_max(float x) {
 #pragma unroll
