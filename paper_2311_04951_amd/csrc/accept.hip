@@ -20,23 +20,29 @@
 namespace ss {
 
 __device__ __forceinline__ float scaled_logit(float l, float inv_t) { return __fmul_rn(l, inv_t); }
-__device__ __forceinline__ float prob_from_logit(float l, float inv_t, float mx, float Z) {
-    return __fdiv_rn(expf(__fsub_rn(scaled_logit(l, inv_t), mx)), Z);
+// exp through the hardware's base-2 exponential (one rounded multiply, then v_exp_f32: about 2e-6 relative
+// error at x = -30, far inside the tolerance on probabilities; the library routine costs five times the
+// instructions and made these kernels ALU-bound)
+__device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp2f(__fmul_rn(x, 1.4426950408889634f)); }
+__device__ __forceinline__ float inv_norm(float Z) { return __fdiv_rn(1.0f, Z); }
+// softmax probability of a logit given the row's (max, 1/Z): one fixed instruction sequence
+__device__ __forceinline__ float prob_from_logit(float l, float inv_t, float mx, float invZ) {
+    return __fmul_rn(fast_exp(__fsub_rn(scaled_logit(l, inv_t), mx)), invZ);
 }
 
 // ------------------------------------------------------------------ row statistics
 
 __device__ __forceinline__ void online_add(float &m, float &s, float x) {
     if (x > m) {
-        s = s * expf(m - x) + 1.0f;
+        s = s * fast_exp(m - x) + 1.0f;
         m = x;
     } else {
-        s += expf(x - m);
+        s += fast_exp(x - m);
     }
 }
 __device__ __forceinline__ void online_merge(float &m, float &s, float m2, float s2) {
     const float mm = fmaxf(m, m2);
-    s = s * expf(m - mm) + s2 * expf(m2 - mm);
+    s = s * fast_exp(m - mm) + s2 * fast_exp(m2 - mm);
     m = mm;
 }
 
@@ -45,15 +51,13 @@ __device__ __forceinline__ void online_merge(float &m, float &s, float m2, float
 // and the kernel is bound by memory latency otherwise) and folds the step into its running (max, sum)
 // with one rescale.
 constexpr int STATS_UNROLL = 8;
-// Two row sets in one launch (the target's and the draft's logits): workgroups [0, rows_a) take set a.
-__global__ __launch_bounds__(256) void row_stats_kernel(const float *logits_a, int rows_a, float2 *stats_a, const float *logits_b,
-                                                        float2 *stats_b, int V, float inv_t) {
-    const bool first = (int)blockIdx.x < rows_a;
-    const int row = first ? blockIdx.x : blockIdx.x - rows_a;
-    const float *x = (first ? logits_a : logits_b) + (size_t)row * V;
-    float2 *stats = first ? stats_a : stats_b;
+// A row is cut into segments of STATS_SEG logits (a function of the vocabulary size alone, so every
+// entry point computes a row's statistics with the same operations in the same order): one workgroup per
+// segment, and the workgroup that finishes a row's last segment merges the segments in index order.
+constexpr int STATS_SEG = 16384;
+// (max_v x_v, sum_v exp(x_v - max)) of x[0 .. V) by a workgroup of 256 threads; valid in thread 0
+__device__ __forceinline__ float2 segment_stats(const float *x, int V, float inv_t, bool vec) {
     float m = -INFINITY, s = 0.f;
-    const bool vec = (V % 4 == 0) && ((reinterpret_cast<uintptr_t>(x) & 15) == 0);
     if (vec) {
         const f32x4 *x4 = reinterpret_cast<const f32x4 *>(x);
         const int n4 = V / 4;
@@ -74,12 +78,12 @@ __global__ __launch_bounds__(256) void row_stats_kernel(const float *logits_a, i
                 }
             if (mx == -INFINITY) continue;
             if (mx > m) {
-                s *= expf(m - mx);
+                s *= fast_exp(m - mx);
                 m = mx;
             }
             float add = 0.f;
 #pragma unroll
-            for (int j = 0; j < STATS_UNROLL; ++j) add += (expf(t[j][0] - m) + expf(t[j][1] - m)) + (expf(t[j][2] - m) + expf(t[j][3] - m));
+            for (int j = 0; j < STATS_UNROLL; ++j) add += (fast_exp(t[j][0] - m) + fast_exp(t[j][1] - m)) + (fast_exp(t[j][2] - m) + fast_exp(t[j][3] - m));
             s += add;
         }
     } else {
@@ -115,27 +119,80 @@ __global__ __launch_bounds__(256) void row_stats_kernel(const float *logits_a, i
                     online_merge(M, S, sm[w], ss_[w]);
                 }
             }
-        stats[row] = make_float2(M, S);
+        return make_float2(M, S);
     }
+    return make_float2(0.f, 0.f);
+}
+// Statistics of segment `seg` of row x[0 .. V) and, by the workgroup that completes the row, of the row.
+// cnt: the row's arrival counter (zero between launches); part: the row's nseg partial results.  Both are
+// exchanged with agent-coherent accesses (the workgroups of a row run on different XCDs).
+__device__ __forceinline__ void row_stats_segmented(const float *x, int V, float inv_t, int seg, int nseg, float2 *out, unsigned *cnt,
+                                                    float2 *part) {
+    const bool vec = (V % 4 == 0) && ((reinterpret_cast<uintptr_t>(x) & 15) == 0);
+    const int lo = seg * STATS_SEG;
+    const float2 r = segment_stats(x + lo, min(STATS_SEG, V - lo), inv_t, vec);
+    if (threadIdx.x != 0) return;
+    if (nseg == 1) {
+        *out = r;
+        return;
+    }
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(part + seg), __builtin_bit_cast(unsigned long long, r), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): the partial result is at the memory side before the arrival is counted
+    if (__hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != (unsigned)(nseg - 1)) return;
+    float M = -INFINITY, S = 0.f;
+    for (int sgi = 0; sgi < nseg; ++sgi) {
+        const float2 ps = __builtin_bit_cast(float2, ld_coh64(part + sgi));
+        if (ps.x != -INFINITY) {
+            if (M == -INFINITY) {
+                M = ps.x;
+                S = ps.y;
+            } else {
+                online_merge(M, S, ps.x, ps.y);
+            }
+        }
+    }
+    *out = make_float2(M, S);
+    __hip_atomic_store(cnt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+int row_stats_segments(int V) { return std::max(1, (V + STATS_SEG - 1) / STATS_SEG); }
+size_t row_stats_partial_bytes(int rows, int V) {
+    const int nseg = row_stats_segments(V);
+    return nseg == 1 ? 0 : sizeof(float2) * (size_t)rows * nseg;
 }
 
-void launch_row_stats(const float *logits, int rows, int V, float inv_t, float2 *stats, hipStream_t st) {
+// Two row sets in one launch (the target's and the draft's logits): rows [0, rows_a) are set a.  grid (segments, rows).
+__global__ __launch_bounds__(256) void row_stats_kernel(const float *logits_a, int rows_a, float2 *stats_a, const float *logits_b,
+                                                        float2 *stats_b, int V, float inv_t, unsigned *cnt, float2 *part) {
+    const int id = blockIdx.y, nseg = gridDim.x;
+    const bool first = id < rows_a;
+    const int row = first ? id : id - rows_a;
+    row_stats_segmented((first ? logits_a : logits_b) + (size_t)row * V, V, inv_t, blockIdx.x, nseg, (first ? stats_a : stats_b) + row,
+                        cnt + id, part + (size_t)id * nseg);
+}
+
+// cnt: one arrival counter per row, zero before the launch (the kernel leaves them zero); part:
+// row_stats_partial_bytes(rows, V) bytes.  Neither is touched when the vocabulary fits one segment.
+void launch_row_stats(const float *logits, int rows, int V, float inv_t, float2 *stats, unsigned *cnt, float2 *part, hipStream_t st) {
     if (rows <= 0) return;
-    hipLaunchKernelGGL(row_stats_kernel, dim3(rows), dim3(256), 0, st, logits, rows, stats, nullptr, nullptr, V, inv_t);
+    hipLaunchKernelGGL(row_stats_kernel, dim3(row_stats_segments(V), rows), dim3(256), 0, st, logits, rows, stats, nullptr, nullptr, V, inv_t,
+                       cnt, part);
 }
 void launch_row_stats2(const float *logits_a, int rows_a, float2 *stats_a, const float *logits_b, int rows_b, float2 *stats_b,
-                       int V, float inv_t, hipStream_t st) {
+                       int V, float inv_t, unsigned *cnt, float2 *part, hipStream_t st) {
     if (rows_a + rows_b <= 0) return;
-    hipLaunchKernelGGL(row_stats_kernel, dim3(rows_a + rows_b), dim3(256), 0, st, logits_a, rows_a, stats_a, logits_b, stats_b, V, inv_t);
+    hipLaunchKernelGGL(row_stats_kernel, dim3(row_stats_segments(V), rows_a + rows_b), dim3(256), 0, st, logits_a, rows_a, stats_a, logits_b,
+                       stats_b, V, inv_t, cnt, part);
 }
 
 __global__ __launch_bounds__(256) void softmax_write_kernel(const float *logits, int V, float inv_t, const float2 *stats,
                                                             float *probs, int64_t ld) {
     const int row = blockIdx.y;
     const float2 st = stats[row];
+    const float invZ = inv_norm(st.y);
     const size_t base = (size_t)row * V, obase = (size_t)row * ld;
     for (int v = blockIdx.x * 256 + threadIdx.x; v < V; v += gridDim.x * 256)
-        probs[obase + v] = prob_from_logit(logits[base + v], inv_t, st.x, st.y);
+        probs[obase + v] = prob_from_logit(logits[base + v], inv_t, st.x, invZ);
 }
 
 void launch_softmax_write(const float *logits, int rows, int V, float inv_t, const float2 *stats, float *probs,
@@ -150,8 +207,8 @@ void launch_softmax_write(const float *logits, int rows, int V, float inv_t, con
 struct RowSrc {
     const float *row;
     int from_logits;
-    float inv_t, mx, Z;
-    __device__ __forceinline__ float conv(float x) const { return from_logits ? prob_from_logit(x, inv_t, mx, Z) : x; }
+    float inv_t, mx, invZ; // invZ = inv_norm(Z)
+    __device__ __forceinline__ float conv(float x) const { return from_logits ? prob_from_logit(x, inv_t, mx, invZ) : x; }
     __device__ __forceinline__ float at(int v) const { return conv(row[v]); }
     // probabilities of v..v+3 (0 beyond V); v is a multiple of 4
     __device__ __forceinline__ void load4(int v, int V, bool vec, float (&out)[4]) const {
@@ -326,21 +383,23 @@ __device__ __forceinline__ RowSrc make_row(const float *base, const float2 *stat
     r.from_logits = from_logits;
     r.inv_t = inv_t;
     r.mx = 0.f;
-    r.Z = 1.f;
+    r.invZ = 1.f;
     if (from_logits) {
         const float2 s = stats[row];
         r.mx = s.x;
-        r.Z = s.y;
+        r.invZ = inv_norm(s.y);
     }
     return r;
 }
 
-// Leading accepted draft tokens of sequence b, by the first K threads of a workgroup (one gather of
-// p_i(d_i), q_i(d_i) per thread, all in flight together); every thread gets the count.
-__device__ int block_accept_count(const AcceptArgs &a, int b, int *sm_rej) {
-    if (threadIdx.x == 0) *sm_rej = a.K;
+// Leading accepted draft tokens of sequence b among its first `upto` positions, by the first `upto`
+// threads of a workgroup (one gather of p_i(d_i), q_i(d_i) per thread, all in flight together); every
+// thread gets the count.  Only the row statistics of positions up to the first rejection need to exist:
+// whatever a later position computes from missing statistics cannot lower the minimum.
+__device__ int block_accept_count(const AcceptArgs &a, int b, int upto, int *sm_rej) {
+    if (threadIdx.x == 0) *sm_rej = upto;
     __syncthreads();
-    if ((int)threadIdx.x < a.K) {
+    if ((int)threadIdx.x < upto) {
         const int i = threadIdx.x;
         const int d = a.draft[b * a.K + i];
         bool acc = false;
@@ -358,6 +417,39 @@ __device__ int block_accept_count(const AcceptArgs &a, int b, int *sm_rej) {
     return *sm_rej;
 }
 
+// Row statistics in stages (logits entry).  Positions behind the first rejection of a sequence are never
+// looked at by the method, so their rows need not be read: stage j covers positions [lo, hi) of every
+// sequence (target rows lo .. hi-1, draft rows lo .. min(hi, K)-1) and, for lo > 0, a workgroup first counts
+// the accepted tokens among positions < lo (their statistics exist if they are needed, see
+// block_accept_count) and leaves when a rejection has already happened.  grid (rows of the stage, B).
+__global__ __launch_bounds__(256) void row_stats_stage_kernel(AcceptArgs a, float2 *p_stats, float2 *q_stats, int lo, int hi, int nseg,
+                                                              unsigned *cnt, float2 *part) {
+    __shared__ int sm_rej;
+    const int b = blockIdx.z, np = hi - lo;
+    const bool target = (int)blockIdx.y < np;
+    const int i = lo + (target ? blockIdx.y : blockIdx.y - np);
+    if (lo > 0 && block_accept_count(a, b, lo, &sm_rej) < lo) return; // uniform over the workgroup
+    const int row = target ? b * (a.K + 1) + i : b * a.K + i;
+    const int id = target ? row : a.B * (a.K + 1) + row;
+    row_stats_segmented((target ? a.p : a.q) + (size_t)row * a.V, a.V, a.inv_t, blockIdx.x, nseg, (target ? p_stats : q_stats) + row,
+                        cnt + id, part + (size_t)id * nseg);
+}
+
+// stages of 2, 3, then all remaining positions (K + 1 target rows, K draft rows per sequence); cnt and part
+// as for launch_row_stats with B * (2K + 1) rows
+void launch_row_stats_staged(const AcceptArgs &a, float2 *p_stats, float2 *q_stats, unsigned *cnt, float2 *part, hipStream_t st) {
+    if (a.B <= 0) return;
+    const int nseg = row_stats_segments(a.V);
+    int lo = 0;
+    for (int stage = 0; lo <= a.K; ++stage) {
+        int hi = std::min(lo + 2 + stage, a.K + 1);
+        if (stage == 2 || a.K + 1 - hi < 2) hi = a.K + 1; // third stage, or a remainder not worth a launch
+        const int np = hi - lo, nq = std::min(hi, a.K) - lo;
+        hipLaunchKernelGGL(row_stats_stage_kernel, dim3(nseg, np + nq, a.B), dim3(256), 0, st, a, p_stats, q_stats, lo, hi, nseg, cnt, part);
+        lo = hi;
+    }
+}
+
 constexpr int PART_THREADS = 256, PART_UNROLL = 4;
 
 // grid (nseg, B): the accepted count of sequence b, and the total weight of segment blockIdx.x of the
@@ -368,7 +460,7 @@ __global__ __launch_bounds__(PART_THREADS) void accept_partial_kernel(AcceptArgs
     __shared__ int sm_rej;
     __shared__ unsigned long long sm_part[PART_THREADS / 64];
     const int b = blockIdx.y, seg = blockIdx.x, nseg = gridDim.x;
-    const int n = block_accept_count(a, b, &sm_rej);
+    const int n = block_accept_count(a, b, a.K, &sm_rej);
     if (seg == 0 && threadIdx.x == 0) a.n_accepted[b] = n;
     const RowSrc P = make_row(a.p, a.p_stats, (size_t)b * (a.K + 1) + n, a.V, a.from_logits, a.inv_t);
     const bool resid = n < a.K;
@@ -474,7 +566,7 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_rows_kernel(const float
     P.from_logits = 0;
     P.inv_t = 1.f;
     P.mx = 0.f;
-    P.Z = 1.f;
+    P.invZ = 1.f;
     int tok = block_inv_cdf<false>(P, P, V, 0, V, false, 0, u[b], sm_wave, &sm_tok);
     if (tok < 0) tok = block_argmax(P, V, sm_val, sm_idx);
     if (threadIdx.x == 0) token_out[b] = tok;
@@ -493,7 +585,7 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void argmax_rows_kernel(const float
     P.from_logits = 0;
     P.inv_t = 1.f;
     P.mx = 0.f;
-    P.Z = 1.f;
+    P.invZ = 1.f;
     const int t = block_argmax(P, V, sm_val, sm_idx);
     if (threadIdx.x == 0) out[blockIdx.x] = t;
 }

@@ -59,6 +59,8 @@ struct ss_model {
     float *part_o, *part_m, *part_l;
     float *logits_ws; // [max_rows][vocab] (draft step)
     float2 *stats_ws; // [max_rows]
+    unsigned *stats_cnt = nullptr; // [max_rows] arrival counters of the segmented row statistics (zero between launches)
+    float2 *stats_part = nullptr;  // per-segment partial statistics
     float2 *rope;     // [max_pos][hd/2]
     int32_t *status;
     std::vector<void *> owned;
@@ -179,6 +181,8 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
     A((void **)&m->part_l, sizeof(float) * (size_t)MAX_SPLITS * c.max_rows * c.n_heads, true);
     A((void **)&m->logits_ws, sizeof(float) * (size_t)c.max_rows * c.vocab, true);
     A((void **)&m->stats_ws, sizeof(float2) * (size_t)c.max_rows, true);
+    A((void **)&m->stats_cnt, sizeof(unsigned) * (size_t)c.max_rows, true);
+    A((void **)&m->stats_part, row_stats_partial_bytes(c.max_rows, c.vocab) + 16, true);
     A((void **)&m->rope, sizeof(float2) * (size_t)c.max_pos * (c.head_dim / 2), false);
     A((void **)&m->status, sizeof(int32_t), true);
     if (rc != SS_OK) {
@@ -721,7 +725,7 @@ extern "C" int ss_draft_step(ss_model *m, ss_kv_cache *kv, const int32_t *tokens
     }
     if (temperature > 0.f) {
         const float inv_t = 1.0f / temperature;
-        launch_row_stats(m->logits_ws, batch, V, inv_t, m->stats_ws, st);
+        launch_row_stats(m->logits_ws, batch, V, inv_t, m->stats_ws, m->stats_cnt, m->stats_part, st);
         launch_softmax_write(m->logits_ws, batch, V, inv_t, m->stats_ws, q_rows_dev, ldq, st);
         launch_sample_rows(q_rows_dev, ldq, batch, V, u_dev, token_out_dev, st);
     } else {
@@ -738,9 +742,16 @@ static std::mutex g_scratch_mu;
 static void *g_scratch = nullptr;
 static size_t g_scratch_bytes = 0;
 
+// Layout: [0, 256) device status word; [256, SCR_DATA) arrival counters of the segmented row statistics, a
+// zone no call uses for anything else, so that they are zero whenever a launch starts (the kernels leave
+// them zero); [SCR_DATA, ...) per-call data.
+constexpr size_t SCR_CNT_ROWS = 16384, SCR_DATA = 256 + sizeof(unsigned) * SCR_CNT_ROWS;
+static unsigned *scr_cnt(void *ws) { return (unsigned *)((char *)ws + 256); }
+static void *scr_data(void *ws) { return (char *)ws + SCR_DATA; }
+
 static int scratch(size_t bytes, void **out) {
     std::lock_guard<std::mutex> lk(g_scratch_mu);
-    bytes += 256;
+    bytes += SCR_DATA;
     if (bytes > g_scratch_bytes) {
         if (g_scratch) {
             HIP_TRY(hipDeviceSynchronize());
@@ -757,17 +768,28 @@ static int scratch(size_t bytes, void **out) {
     return SS_OK;
 }
 
+// rows per launch of the row statistics: the counter zone, and the grid's y extent
+static size_t stats_rows_per_launch(int V) { return row_stats_segments(V) > 1 ? SCR_CNT_ROWS : (size_t)65535; }
+// statistics of `rows` rows with the scratch's counters; part: room for stats_rows_per_launch(V) rows
+static void stats_rows(const float *logits, size_t rows, int V, float inv_t, float2 *stats, void *ws, float2 *part, hipStream_t st) {
+    const size_t step = stats_rows_per_launch(V);
+    for (size_t r0 = 0; r0 < rows; r0 += step)
+        launch_row_stats(logits + r0 * (size_t)V, (int)std::min(step, rows - r0), V, inv_t, stats + r0, scr_cnt(ws), part, st);
+}
+
 extern "C" int ss_softmax(const float *logits_dev, int32_t rows, int32_t vocab, float temperature, float *probs_dev,
                           ss_stream stream) {
     if (!logits_dev || !probs_dev) return fail(SS_EINVAL, "ss_softmax: NULL argument");
     if (rows < 0 || vocab <= 0 || !(temperature > 0.f)) return fail(SS_EINVAL, "ss_softmax: bad rows/vocab/temperature");
     void *ws;
-    int rc = scratch(sizeof(float2) * (size_t)rows, &ws);
+    const size_t part_bytes = row_stats_partial_bytes((int)std::min((size_t)rows, stats_rows_per_launch(vocab)), vocab);
+    int rc = scratch(sizeof(float2) * (size_t)rows + part_bytes, &ws);
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
     const float inv_t = 1.0f / temperature;
-    launch_row_stats(logits_dev, rows, vocab, inv_t, (float2 *)((char *)ws + 256), st);
-    launch_softmax_write(logits_dev, rows, vocab, inv_t, (float2 *)((char *)ws + 256), probs_dev, vocab, st);
+    float2 *stats = (float2 *)scr_data(ws);
+    stats_rows(logits_dev, (size_t)rows, vocab, inv_t, stats, ws, stats + rows, st);
+    launch_softmax_write(logits_dev, rows, vocab, inv_t, stats, probs_dev, vocab, st);
     return check_launch();
 }
 
@@ -791,7 +813,7 @@ extern "C" int ss_speculative_accept(const float *p_dev, const float *q_dev, con
     a.p = p_dev; a.q = q_dev; a.from_logits = 0; a.inv_t = 1.f;
     a.draft = draft_tokens_dev; a.u = uniforms_dev; a.B = batch; a.K = K; a.V = vocab;
     a.n_accepted = n_accepted_dev; a.next_token = next_token_dev; a.status = (int32_t *)ws;
-    launch_accept(a, (unsigned long long *)((char *)ws + 256), (hipStream_t)stream);
+    launch_accept(a, (unsigned long long *)scr_data(ws), (hipStream_t)stream);
     return check_launch();
 }
 
@@ -803,18 +825,33 @@ extern "C" int ss_speculative_accept_logits(const float *p_logits_dev, const flo
     if (rc) return rc;
     if (!(temperature > 0.f)) return fail(SS_EINVAL, "ss_speculative_accept_logits: temperature must be > 0");
     const size_t np = (size_t)batch * (K + 1), nq = (size_t)batch * K;
+    const size_t part_bytes = row_stats_partial_bytes((int)std::min(np + nq, stats_rows_per_launch(vocab)), vocab);
     void *ws;
-    rc = scratch(sizeof(float2) * (np + nq) + accept_workspace_bytes(batch, vocab), &ws);
+    rc = scratch(sizeof(float2) * (np + nq) + accept_workspace_bytes(batch, vocab) + part_bytes + 16, &ws);
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
-    float2 *ps = (float2 *)((char *)ws + 256), *qs = ps + np;
+    float2 *ps = (float2 *)scr_data(ws), *qs = ps + np;
+    unsigned long long *partial = (unsigned long long *)(qs + nq);
+    float2 *part = (float2 *)((char *)partial + ((accept_workspace_bytes(batch, vocab) + 15) & ~(size_t)15));
     const float inv_t = 1.0f / temperature;
-    launch_row_stats2(p_logits_dev, (int)np, ps, q_logits_dev, (int)nq, qs, vocab, inv_t, st);
     AcceptArgs a{};
     a.p = p_logits_dev; a.q = q_logits_dev; a.p_stats = ps; a.q_stats = qs; a.from_logits = 1; a.inv_t = inv_t;
     a.draft = draft_tokens_dev; a.u = uniforms_dev; a.B = batch; a.K = K; a.V = vocab;
     a.n_accepted = n_accepted_dev; a.next_token = next_token_dev; a.status = (int32_t *)ws;
-    launch_accept(a, (unsigned long long *)(qs + nq), st);
+    // Rows behind a sequence's first rejection are never used by the method (Section 3).  When the logits
+    // are large enough for their streaming to dominate and nobody asked for the materialised softmax,
+    // the statistics are taken in stages that skip those rows; otherwise every row is covered.
+    const bool one_launch = np + nq <= stats_rows_per_launch(vocab);
+    const bool staged = !p_out_dev && !q_out_dev && K >= 3 && one_launch && (np + nq) * (size_t)vocab * sizeof(float) >= ((size_t)32 << 20);
+    if (staged) {
+        launch_row_stats_staged(a, ps, qs, scr_cnt(ws), part, st);
+    } else if (one_launch) {
+        launch_row_stats2(p_logits_dev, (int)np, ps, q_logits_dev, (int)nq, qs, vocab, inv_t, scr_cnt(ws), part, st);
+    } else {
+        stats_rows(p_logits_dev, np, vocab, inv_t, ps, ws, part, st);
+        stats_rows(q_logits_dev, nq, vocab, inv_t, qs, ws, part, st);
+    }
+    launch_accept(a, partial, st);
     if (p_out_dev) launch_softmax_write(p_logits_dev, (int)np, vocab, inv_t, ps, p_out_dev, vocab, st);
     if (q_out_dev) launch_softmax_write(q_logits_dev, (int)nq, vocab, inv_t, qs, q_out_dev, vocab, st);
     return check_launch();
@@ -827,6 +864,6 @@ extern "C" int ss_greedy_accept(const float *p_logits_dev, const int32_t *draft_
     void *ws;
     int rc = scratch(sizeof(int32_t) * (size_t)batch * (K + 1), &ws);
     if (rc) return rc;
-    launch_greedy_accept(p_logits_dev, draft_tokens_dev, batch, K, vocab, (int32_t *)((char *)ws + 256), n_accepted_dev, next_token_dev, (hipStream_t)stream);
+    launch_greedy_accept(p_logits_dev, draft_tokens_dev, batch, K, vocab, (int32_t *)scr_data(ws), n_accepted_dev, next_token_dev, (hipStream_t)stream);
     return check_launch();
 }

@@ -69,9 +69,14 @@ void launch_kv_append(int dtype, void *kc, void *vc, const void *k, const void *
                       int H, int hd, int S, hipStream_t st);
 
 // softmax / accept
-void launch_row_stats(const float *logits, int rows, int V, float inv_t, float2 *stats, hipStream_t st);
+// Row statistics.  A row longer than one segment is reduced by several workgroups: cnt = one arrival
+// counter per row (zero before the launch, left zero), part = row_stats_partial_bytes(rows, V) bytes of
+// device memory (rows = rows_a + rows_b); neither is touched when row_stats_segments(V) == 1.
+int row_stats_segments(int V);
+size_t row_stats_partial_bytes(int rows, int V);
+void launch_row_stats(const float *logits, int rows, int V, float inv_t, float2 *stats, unsigned *cnt, float2 *part, hipStream_t st);
 void launch_row_stats2(const float *logits_a, int rows_a, float2 *stats_a, const float *logits_b, int rows_b, float2 *stats_b,
-                       int V, float inv_t, hipStream_t st);
+                       int V, float inv_t, unsigned *cnt, float2 *part, hipStream_t st);
 void launch_softmax_write(const float *logits, int rows, int V, float inv_t, const float2 *stats, float *probs,
                           int64_t probs_ld, hipStream_t st);
 struct AcceptArgs {
@@ -85,6 +90,9 @@ struct AcceptArgs {
     int32_t *n_accepted, *next_token;
     int32_t *status;
 };
+// row statistics of the logits entry in stages that skip the positions behind a sequence's first rejection
+// (a.p / a.q are logits, a.p_stats / a.q_stats the arrays written)
+void launch_row_stats_staged(const AcceptArgs &a, float2 *p_stats, float2 *q_stats, unsigned *cnt, float2 *part, hipStream_t st);
 // partial: device workspace of accept_workspace_bytes(B, V) bytes (per-segment weight sums)
 size_t accept_workspace_bytes(int B, int V);
 void launch_accept(const AcceptArgs &a, unsigned long long *partial, hipStream_t st);

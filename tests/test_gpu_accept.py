@@ -97,6 +97,30 @@ def test_fused_logits_path_equals_materialised_path_and_oracle(B, K, V, T):
     assert np.all(np.abs(p_out.cpu().numpy() - ref) <= 1e-6 + 1e-5 * ref)
 
 
+@pytest.mark.parametrize("B,K,V", [(24, 3, 50000), (16, 8, 32000), (10, 5, 128256), (20, 4, 65536)])
+def test_staged_row_statistics_skip_rows_without_changing_the_result(B, K, V):
+    """Large logits without materialised outputs: the statistics are taken in stages that skip the rows
+    behind a sequence's first rejection.  Same counts and tokens as the path that covers every row (which
+    the tests above pin to the oracle), whatever stale statistics the workspace holds for skipped rows."""
+    T, D = 0.8, dev()
+    other = si.accept_workload(50, B, K, V, device=D)
+    sv.ss_speculative_accept_logits(other[0], other[1], T, torch.zeros((B, K), dtype=torch.int32, device=D), other[2])  # leaves foreign statistics behind
+    pl, ql, u, ud = si.accept_workload(51, B, K, V, device=D)
+    q = sv.ss_softmax(ql, T)
+    d = torch.empty((B, K), dtype=torch.int32, device=D)
+    for i in range(K):
+        _, tok = sv.ss_speculative_accept(q[:, i].contiguous()[:, None], torch.zeros(1, device=D), torch.zeros(1, dtype=torch.int32, device=D),
+                                          ud[:, i:i + 1].contiguous())
+        d[:, i] = tok
+    p_out = torch.empty((B, K + 1, V), device=D)
+    na_full, nx_full = sv.ss_speculative_accept_logits(pl, ql, T, d, u, p_out=p_out)
+    na, nx = sv.ss_speculative_accept_logits(pl, ql, T, d, u)
+    assert na.cpu().tolist() == na_full.cpu().tolist() and nx.cpu().tolist() == nx_full.cpu().tolist()
+    ona, onx = oracle.speculative_accept(p_out.cpu().numpy(), q.cpu().numpy(), d.cpu().numpy(), u.cpu().numpy())
+    assert na.cpu().tolist() == ona.tolist() and nx.cpu().tolist() == onx.tolist()
+    assert 0 < sum(na.cpu().tolist()) < B * K     # both early rejections and surviving sequences occur
+
+
 def test_greedy_accept_matches_oracle_with_ties():
     B, K, V = 9, 5, 1024
     l = si.normal(31, "l", (B, K + 1, V), 2.0)
