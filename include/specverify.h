@@ -179,7 +179,9 @@ int ss_draft_step(ss_model *draft, ss_kv_cache *draft_kv, const int32_t *tokens_
                   int32_t *token_out_dev, ss_stream stream);
 
 /* ---- softmax (per-row statistics by wavefront reductions over the vocabulary) ---------------
- * probs_dev[r][v] = exp(logits[r][v]/T - max_r) / sum_v exp(...), fp32 [rows][vocab]. */
+ * probs_dev[r][v] = exp(logits[r][v]/T - max_r) / sum_v exp(...), fp32 [rows][vocab], evaluated with the
+ * hardware base-2 exponential and one reciprocal per row (relative error a few 1e-6).  Every entry
+ * point of the library that turns logits into probabilities produces these same bits. */
 int ss_softmax(const float *logits_dev, int32_t rows, int32_t vocab, float temperature, float *probs_dev,
                ss_stream stream);
 
@@ -199,8 +201,10 @@ int ss_speculative_accept(const float *p_dev, const float *q_dev, const int32_t 
                           int32_t *n_accepted_dev, int32_t *next_token_dev, ss_stream stream);
 
 /* Same step straight from logits: p = softmax(p_logits/T), q = softmax(q_logits/T) are never
- * materialised (one read of all logits for the row statistics, then a re-read of the one or two
- * rows the sampling needs).  Returns exactly what ss_speculative_accept returns on the
+ * materialised (one read of the logits for the row statistics, then a re-read of the one or two
+ * rows the sampling needs; when the logits are large and no output below is asked for, rows behind
+ * a sequence's first rejection, which the method never uses, are not read at all).  Returns exactly
+ * what ss_speculative_accept returns on the
  * probabilities ss_softmax would produce.  p_out_dev / q_out_dev, if not NULL, receive those
  * probabilities ([batch][K+1][vocab] / [batch][K][vocab]).  temperature > 0. */
 int ss_speculative_accept_logits(const float *p_logits_dev, const float *q_logits_dev, float temperature,
