@@ -219,6 +219,27 @@ int ss_speculative_accept_logits(const float *p_logits_dev, const float *q_logit
 int ss_greedy_accept(const float *p_logits_dev, const int32_t *draft_tokens_dev, int32_t batch, int32_t K,
                      int32_t vocab, int32_t *n_accepted_dev, int32_t *next_token_dev, ss_stream stream);
 
+/* ---- one whole speculative step for a single sequence (Sections 3, 4.3, 4.4) -----------------
+ * The calls above, issued back to back without returning to the caller, so that a decode loop
+ * pays one library call and one host synchronisation per step:
+ *   K x ss_draft_step on (draft, draft_kv): call 0 feeds feed_dev[0 .. *n_feed) (one token, or two
+ *     after a step that accepted all K), call i > 0 feeds the token call i-1 produced; the draft's
+ *     probability rows go to q_rows_dev [K][vocab] (temperature > 0);
+ *   ss_verify_forward on (target, target_kv) over verify_tokens_dev [K+1] = [last committed token,
+ *     d_1 .. d_K] -> logits_dev [K+1][vocab];
+ *   temperature > 0: ss_softmax -> p_dev [K+1][vocab], then ss_speculative_accept with
+ *     u_accept_dev [K+1]; temperature == 0: ss_greedy_accept (p_dev, q_rows_dev, u_*_dev unused);
+ *   both caches rolled back to their committed length.
+ * Outputs: result_dev int32 [2] = (n_accepted a, next token y); out_host int32 [K+2] = (a, y, d_1 ..
+ * d_K) after a stream synchronisation; feed_dev / *n_feed are rewritten for the next step ([y], or
+ * [d_K, y] when a == K: the draft cache is then one row short).  All *_dev buffers are the caller's
+ * device memory; 1 <= K <= 15; both caches hold one sequence.  Errors as in the calls it is made of. */
+int ss_speculative_step(ss_model *target, ss_kv_cache *target_kv, ss_model *draft, ss_kv_cache *draft_kv,
+                        int32_t K, float temperature, int32_t *feed_dev, int32_t *n_feed,
+                        const float *u_draft_dev, const float *u_accept_dev, int32_t *verify_tokens_dev,
+                        float *q_rows_dev, float *logits_dev, float *p_dev, int32_t *result_dev,
+                        int32_t *out_host, ss_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

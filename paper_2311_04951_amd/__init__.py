@@ -25,6 +25,7 @@ EXPORTS = [
     "ss_kv_cache_get_len", "ss_kv_cache_rollback", "ss_verify_forward", "ss_decoder_layers_forward",
     "ss_draft_step", "ss_softmax", "ss_speculative_accept", "ss_speculative_accept_logits",
     "ss_greedy_accept", "ss_profile_enable", "ss_profile_read", "ss_model_set_persistent", "ss_model_set_persistent_options",
+    "ss_speculative_step",
 ]
 
 PROFILE_CLASSES = ["rmsnorm", "qkv_gemm", "attention", "oproj_gemm", "gateup_gemm", "down_gemm", "head_gemm", "other",
@@ -86,6 +87,7 @@ def lib():
             "ss_profile_enable": [vp, i32],
             "ss_model_set_persistent": [vp, i32],
             "ss_model_set_persistent_options": [vp, i32, i32],
+            "ss_speculative_step": [vp, vp, vp, vp, i32, C.c_float, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp],
             "ss_profile_read": [vp, i32, vp, vp],
         }
         for name, args in sig.items():
@@ -293,6 +295,32 @@ def ss_greedy_accept(p_logits, draft_tokens, n_accepted=None, next_token=None, s
                                   _dev(draft_tokens, torch.int32) if K1 > 1 else C.c_void_p(0), B, K1 - 1, V,
                                   _dev(n_accepted), _dev(next_token), _stream(stream)))
     return n_accepted, next_token
+
+
+class StepBuffers:
+    """Device and host buffers of ss_speculative_step for one sequence (allocated once per decode loop)."""
+
+    def __init__(self, K: int, vocab: int, first_token: int, device):
+        self.K, self.V = K, vocab
+        i32, f32 = torch.int32, torch.float32
+        self.feed = torch.tensor([first_token, 0], dtype=i32, device=device)
+        self.n_feed = C.c_int32(1)
+        self.verify_tokens = torch.zeros(K + 1, dtype=i32, device=device)
+        self.q = torch.zeros((K, vocab), dtype=f32, device=device)
+        self.logits = torch.empty((K + 1, vocab), dtype=f32, device=device)
+        self.p = torch.empty((K + 1, vocab), dtype=f32, device=device)
+        self.result = torch.zeros(2, dtype=i32, device=device)
+        self.out = (C.c_int32 * (K + 2))()
+
+
+def ss_speculative_step(target: Model, target_kv: KVCache, draft: Model, draft_kv: KVCache, buf: StepBuffers,
+                        temperature: float, u_draft=None, u_accept=None, stream=None):
+    """One speculative step; returns (n_accepted, next_token, [d_1..d_K]) as host integers."""
+    _check(lib().ss_speculative_step(
+        target.handle, target_kv.handle, draft.handle, draft_kv.handle, buf.K, float(temperature), _dev(buf.feed, torch.int32),
+        C.byref(buf.n_feed), _dev(u_draft, torch.float32), _dev(u_accept, torch.float32), _dev(buf.verify_tokens, torch.int32),
+        _dev(buf.q), _dev(buf.logits), _dev(buf.p), _dev(buf.result, torch.int32), buf.out, _stream(stream)))
+    return buf.out[0], buf.out[1], list(buf.out[2:2 + buf.K])
 
 
 def ss_device_status(model: Model, stream=None) -> int:

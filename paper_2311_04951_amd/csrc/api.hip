@@ -867,3 +867,57 @@ extern "C" int ss_greedy_accept(const float *p_logits_dev, const int32_t *draft_
     launch_greedy_accept(p_logits_dev, draft_tokens_dev, batch, K, vocab, (int32_t *)scr_data(ws), n_accepted_dev, next_token_dev, (hipStream_t)stream);
     return check_launch();
 }
+
+// ------------------------------------------------------------------------------------------ one speculative step
+
+extern "C" int ss_speculative_step(ss_model *target, ss_kv_cache *tkv, ss_model *draft, ss_kv_cache *dkv, int32_t K,
+                                   float temperature, int32_t *feed_dev, int32_t *n_feed, const float *u_draft_dev,
+                                   const float *u_accept_dev, int32_t *vt, float *q_rows_dev, float *logits_dev, float *p_dev,
+                                   int32_t *result_dev, int32_t *out_host, ss_stream stream) {
+    if (!target || !tkv || !draft || !dkv || !feed_dev || !n_feed || !vt || !logits_dev || !result_dev || !out_host)
+        return fail(SS_EINVAL, "ss_speculative_step: NULL argument");
+    if (K < 1 || K > SS_MAX_ROWS_PER_SEQ - 1) return fail(SS_EINVAL, "ss_speculative_step: K must be in [1, %d]", SS_MAX_ROWS_PER_SEQ - 1);
+    if (*n_feed != 1 && *n_feed != 2) return fail(SS_EINVAL, "ss_speculative_step: *n_feed must be 1 or 2");
+    if (tkv->B != 1 || dkv->B != 1) return fail(SS_EINVAL, "ss_speculative_step: one sequence per cache");
+    if (target->cfg.vocab != draft->cfg.vocab) return fail(SS_EINVAL, "ss_speculative_step: the two models have different vocabularies");
+    if (!(temperature >= 0.f)) return fail(SS_EINVAL, "ss_speculative_step: temperature must be >= 0");
+    const bool sample = temperature > 0.f;
+    if (sample && (!u_draft_dev || !u_accept_dev || !q_rows_dev || !p_dev)) return fail(SS_EINVAL, "ss_speculative_step: sampling needs uniforms, q_rows_dev and p_dev");
+    hipStream_t st = (hipStream_t)stream;
+    const int V = target->cfg.vocab, M = K + 1;
+    int rc;
+    for (int i = 0; i < K; ++i) {
+        rc = ss_draft_step(draft, dkv, i ? vt + i : feed_dev, 1, i ? 1 : *n_feed, temperature, sample ? u_draft_dev + i : nullptr,
+                           sample ? q_rows_dev + (size_t)i * V : nullptr, V, vt + i + 1, stream);
+        if (rc) return rc;
+    }
+    HIP_TRY(hipMemcpyAsync(vt, feed_dev + (*n_feed - 1), sizeof(int32_t), hipMemcpyDeviceToDevice, st)); // the last committed token
+    rc = ss_verify_forward(target, tkv, vt, 1, M, logits_dev, stream);
+    if (rc) return rc;
+    if (sample) {
+        rc = ss_softmax(logits_dev, M, V, temperature, p_dev, stream);
+        if (rc) return rc;
+        rc = ss_speculative_accept(p_dev, q_rows_dev, vt + 1, u_accept_dev, 1, K, V, result_dev, result_dev + 1, stream);
+    } else {
+        rc = ss_greedy_accept(logits_dev, vt + 1, 1, K, V, result_dev, result_dev + 1, stream);
+    }
+    if (rc) return rc;
+    launch_len_rollback(tkv->len_dev, result_dev, 1, M, st);
+    launch_len_rollback(dkv->len_dev, result_dev, 1, K, st); // a == K leaves the draft cache one row short of the target's
+    HIP_TRY(hipMemcpyAsync(out_host, result_dev, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(out_host + 2, vt + 1, K * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    const int a = std::min(std::max(out_host[0], 0), K);
+    tkv->len_ub[0] -= M - 1 - a;
+    dkv->len_ub[0] -= K - 1 - std::min(a, K - 1);
+    // the next step's draft feed: [y], or [d_K, y] after a fully accepted step
+    if (a < K) {
+        HIP_TRY(hipMemcpyAsync(feed_dev, result_dev + 1, sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+        *n_feed = 1;
+    } else {
+        HIP_TRY(hipMemcpyAsync(feed_dev, vt + K, sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+        HIP_TRY(hipMemcpyAsync(feed_dev + 1, result_dev + 1, sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+        *n_feed = 2;
+    }
+    return check_launch();
+}

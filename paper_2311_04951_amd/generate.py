@@ -14,8 +14,8 @@ import time
 
 import torch
 
-from . import (KVCache, Model, ss_draft_step, ss_greedy_accept, ss_kv_cache_rollback, ss_softmax,
-               ss_speculative_accept, ss_verify_forward)
+from . import (KVCache, Model, StepBuffers, ss_draft_step, ss_greedy_accept, ss_kv_cache_rollback, ss_softmax,
+               ss_speculative_accept, ss_speculative_step, ss_verify_forward)
 
 
 def prefill(model: Model, kv: KVCache, tokens, chunk: int = 16):
@@ -57,7 +57,10 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
                          u_draft=None, u_accept=None, max_seq=None, observer=None):
     """Returns (tokens[n_new], stats).  u_draft [steps, K], u_accept [steps, K+1] (temperature > 0).
     `observer(dict)` (optional) sees each step's device tensors: draft tokens, q rows, target logits,
-    n_accepted, next token."""
+    n_accepted, next token; with an observer the step is issued call by call from here, without one
+    it is a single ss_speculative_step per step (same calls, same results)."""
+    if observer is None:
+        return _speculative_generate_native(target, draft, prompt, n_new, K, temperature, u_draft, u_accept, max_seq)
     dev = torch.device("cuda")
     V = target.shape.vocab
     M = K + 1
@@ -113,3 +116,32 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
     dkv.close()
     return x[n0:n0 + n_new], {"steps": step, "accepted": accepted, "loop_seconds": loop_s,
                               "generated": len(x) - n0}
+
+
+def _speculative_generate_native(target, draft, prompt, n_new, K, temperature, u_draft, u_accept, max_seq):
+    dev = torch.device("cuda")
+    greedy = temperature == 0
+    cap = max_seq or (len(prompt) + n_new + K + 2)
+    tkv, dkv = KVCache(target, 1, cap), KVCache(draft, 1, cap)
+    prefill(target, tkv, list(prompt[:-1]))
+    prefill(draft, dkv, list(prompt[:-1]))
+    buf = StepBuffers(K, target.shape.vocab, int(prompt[-1]), dev)
+    ud_all = ua_all = None
+    if not greedy:
+        ud_all = torch.as_tensor(u_draft, dtype=torch.float32).to(dev).contiguous()
+        ua_all = torch.as_tensor(u_accept, dtype=torch.float32).to(dev).contiguous()
+    out, accepted = [], []
+    step = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while len(out) < n_new:
+        a, y, d = ss_speculative_step(target, tkv, draft, dkv, buf, temperature,
+                                      None if greedy else ud_all[step], None if greedy else ua_all[step])
+        out += d[:a] + [y]
+        accepted.append(a)
+        step += 1
+    torch.cuda.synchronize()
+    loop_s = time.perf_counter() - t0
+    tkv.close()
+    dkv.close()
+    return out[:n_new], {"steps": step, "accepted": accepted, "loop_seconds": loop_s, "generated": len(out)}

@@ -96,6 +96,25 @@ def test_sampled_run_in_lock_step_with_the_oracle(persistent):
             pending = [d[K - 1], y]
     assert x[len(prompt):len(prompt) + n_new] == sp
     assert 0 < sum(stats["accepted"]) < K * stats["steps"]      # both accepts and rejections occurred
+    # the same run as one ss_speculative_step per step (no observer): identical tokens and accept counts
+    sp2, stats2 = gen.speculative_generate(gt, gd, prompt, n_new, K, T, ud, ua)
+    assert sp2 == sp and stats2["accepted"] == stats["accepted"]
+
+
+@pytest.mark.parametrize("K", [1, 3, 8])
+def test_native_step_handles_the_fully_accepted_catch_up(K):
+    """Draft == target at temperature 1: every draft token is accepted (p == q bit for bit), so every step
+    ends with a == K and the next one feeds two tokens to the draft.  One-call steps and call-by-call
+    steps (observer attached) must produce the same stream."""
+    (ot, _), (gt, _) = _pair(3, persistent=True)
+    prompt = si.token_ids(3, "prompt", (20,), 1024).numpy().tolist()
+    n_new = 33
+    ud = si.uniforms(3, "ud", (n_new, K)).numpy()
+    ua = si.uniforms(3, "ua", (n_new, K + 1)).numpy()
+    a_native, st_native = gen.speculative_generate(gt, gt, prompt, n_new, K, 1.0, ud, ua)
+    a_calls, st_calls = gen.speculative_generate(gt, gt, prompt, n_new, K, 1.0, ud, ua, observer=lambda s: None)
+    assert a_native == a_calls and st_native["accepted"] == st_calls["accepted"]
+    assert all(a == K for a in st_native["accepted"])
 
 
 def test_sampled_autoregressive_matches_oracle_stream():
