@@ -59,6 +59,8 @@ struct ss_model {
     float *part_o, *part_m, *part_l;
     float *logits_ws; // [max_rows][vocab] (draft step)
     float2 *stats_ws; // [max_rows]
+    float *splitk_ws = nullptr;    // partial tiles of split-K GEMM launches (models that take more than 16 rows per call)
+    size_t splitk_ws_bytes = 0;
     unsigned *stats_cnt = nullptr; // [max_rows] arrival counters of the segmented row statistics (zero between launches)
     float2 *stats_part = nullptr;  // per-segment partial statistics
     float2 *rope;     // [max_pos][hd/2]
@@ -181,6 +183,11 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
     A((void **)&m->part_l, sizeof(float) * (size_t)MAX_SPLITS * c.max_rows * c.n_heads, true);
     A((void **)&m->logits_ws, sizeof(float) * (size_t)c.max_rows * c.vocab, true);
     A((void **)&m->stats_ws, sizeof(float2) * (size_t)c.max_rows, true);
+    if (c.max_rows > 16) {
+        const size_t cols = (size_t)std::max(std::max(3 * m->W, 2 * c.d_ff), c.d_model);
+        m->splitk_ws_bytes = 4 * cols * (size_t)((c.max_rows + 15) / 16) * 64;
+        A((void **)&m->splitk_ws, m->splitk_ws_bytes, false);
+    }
     A((void **)&m->stats_cnt, sizeof(unsigned) * (size_t)c.max_rows, true);
     A((void **)&m->stats_part, row_stats_partial_bytes(c.max_rows, c.vocab) + 16, true);
     A((void **)&m->rope, sizeof(float2) * (size_t)c.max_pos * (c.head_dim / 2), false);
@@ -461,6 +468,7 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
             launch_rmsnorm_pack(c.dtype, m->h, L.g1, R, d, c.rms_eps, m->act_a, pl * d, d, st);
         }
         GemmArgs g{};
+        g.splitk_ws = m->splitk_ws; g.splitk_ws_bytes = m->splitk_ws_bytes;
         g.W = L.wqkv; g.N = 3 * W; g.K = d;
         g.act = m->act_a; g.act_plane = pl * d; g.ld_act = d; g.R = R;
         g.act_out = m->act_q; g.act_out_plane = pl * W; g.ld_act_out = W;
@@ -485,6 +493,7 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
         }
 
         GemmArgs o{};
+        o.splitk_ws = m->splitk_ws; o.splitk_ws_bytes = m->splitk_ws_bytes;
         o.W = L.wo; o.N = d; o.K = W;
         o.act = m->act_o; o.act_plane = pl * W; o.ld_act = W; o.R = R;
         o.out = m->h; o.resid = m->h; o.ldo = d;
@@ -497,6 +506,7 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
             launch_rmsnorm_pack(c.dtype, m->h, L.g2, R, d, c.rms_eps, m->act_a, pl * d, d, st);
         }
         GemmArgs u{};
+        u.splitk_ws = m->splitk_ws; u.splitk_ws_bytes = m->splitk_ws_bytes;
         u.W = L.wgu; u.N = F; u.K = d;
         u.act = m->act_a; u.act_plane = pl * d; u.ld_act = d; u.R = R;
         u.act_out = m->act_z; u.act_out_plane = pl * F; u.ld_act_out = F;
@@ -506,6 +516,7 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
         }
 
         GemmArgs dn{};
+        dn.splitk_ws = m->splitk_ws; dn.splitk_ws_bytes = m->splitk_ws_bytes;
         dn.W = L.wd; dn.N = d; dn.K = F;
         dn.act = m->act_z; dn.act_plane = pl * F; dn.ld_act = F; dn.R = R;
         dn.out = m->h; dn.resid = m->h; dn.ldo = d;

@@ -246,6 +246,32 @@ template <int N> __device__ __forceinline__ void wait_vmcnt_at_most() { // s_wai
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+// columns of wave tile `tile`: n0[t] = first column of its t-th 16-column output tile; returns the number of wave tiles
+template <int EPI>
+__device__ __forceinline__ int wide_tile_cols(const GemmArgs &a, int tile, int (&n0)[(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1]) {
+    int ntiles;
+    if constexpr (EPI == EPI_QKV) {
+        const int per_head = a.hd / 32;
+        ntiles = 3 * a.H * per_head;
+        const int tl = min(tile, ntiles - 1);
+        const int hh = tl / per_head; // head index over [q heads | k heads | v heads]
+        n0[0] = hh * a.hd + (tl % per_head) * 16;
+        n0[1] = n0[0] + a.hd / 2;
+    } else if constexpr (EPI == EPI_SWIGLU) {
+        ntiles = (a.N + 15) / 16;
+        n0[0] = min(tile, ntiles - 1) * 16;
+        n0[1] = a.N + n0[0];
+    } else {
+        ntiles = (a.N + 15) / 16;
+        n0[0] = min(tile, ntiles - 1) * 16;
+    }
+    return ntiles;
+}
+// split-K partial tiles: [split][wave tile][row tile][t][v][lane] fp32, i.e. the accumulator layout of a wave
+__device__ __forceinline__ size_t splitk_index(int z, int ntiles, int tile, int row_tiles, int rt, int NT, int t, int v, int lane) {
+    return (((((size_t)z * ntiles + tile) * row_tiles + rt) * NT + t) * 4 + v) * 64 + lane;
+}
+
 template <typename T, int EPI, int NW, int RT>
 __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
     constexpr int E = Traits<T>::E, KB = 4 * E, PL = Traits<T>::PLANES;
@@ -265,23 +291,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
     const int K = a.K;
     const int tile = blockIdx.x * NW + wave;
 
-    int ntiles;
     int n0[NT];
-    if constexpr (EPI == EPI_QKV) {
-        const int per_head = a.hd / 32;
-        ntiles = 3 * a.H * per_head;
-        const int tl = min(tile, ntiles - 1);
-        const int hh = tl / per_head; // head index over [q heads | k heads | v heads]
-        n0[0] = hh * a.hd + (tl % per_head) * 16;
-        n0[1] = n0[0] + a.hd / 2;
-    } else if constexpr (EPI == EPI_SWIGLU) {
-        ntiles = (a.N + 15) / 16;
-        n0[0] = min(tile, ntiles - 1) * 16;
-        n0[1] = a.N + n0[0];
-    } else {
-        ntiles = (a.N + 15) / 16;
-        n0[0] = min(tile, ntiles - 1) * 16;
-    }
+    const int ntiles = wide_tile_cols<EPI>(a, tile, n0);
     const bool tile_live = tile < ntiles; // a dead wave still helps with the slab copies and barriers
     const int nrows_w = (EPI == EPI_SWIGLU) ? 2 * a.N : a.N;
 
@@ -294,14 +305,19 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
         wrow[t] = W + (size_t)n * K + g * E;
     }
     const T *act = reinterpret_cast<const T *>(a.act);
-    const int nslab = (K + WIDE_KS - 1) / WIDE_KS;
+    // split-K (a.ksplit > 1): workgroup z multiplies K slabs [s_lo, s_hi) only and leaves raw partial tiles
+    const int nslab_all = (K + WIDE_KS - 1) / WIDE_KS;
+    const int s_lo = a.ksplit > 1 ? blockIdx.z * a.kslabs : 0;
+    const int s_hi = a.ksplit > 1 ? min(s_lo + a.kslabs, nslab_all) : nslab_all;
+    const int nslab = s_hi - s_lo;
+    const int k_end = min(K, s_hi * WIDE_KS);
 
     // slab s -> LDS: this wave's DPW instructions; lane l brings row (l / 16) of its 4-row group, LDS unit l % 16
     typedef const void __attribute__((address_space(1))) *gptr;
     typedef void __attribute__((address_space(3))) *lptr;
     const int r4 = lane >> 4, q = lane & 15;
     auto slab_dma = [&](int sl, unsigned char *buf) {
-        const int k0 = min(sl, nslab - 1) * WIDE_KS; // past the end: any valid slab (its weights are zero)
+        const int k0 = (s_lo + min(sl, nslab - 1)) * WIDE_KS; // past the end: any valid slab (its weights are zero)
 #pragma unroll
         for (int i = 0; i < DPW; ++i) {
             const int grp = min(wave * DPW + i, GROUPS - 1); // a surplus instruction repeats the last group
@@ -313,7 +329,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
         asm volatile("" ::: "memory");
     };
     auto w_load = [&](int sl, u32x4 (&w)[NT][KBS]) {
-        const int k0 = sl * WIDE_KS;
+        const int k0 = (s_lo + sl) * WIDE_KS;
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
@@ -371,7 +387,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
 #pragma unroll
         for (int kb = 0; kb < KBS; ++kb) {
             if (kb + 1 < KBS) read_av(kb + 1, av[(kb + 1) & 1]);
-            const bool in_k = sl * WIDE_KS + kb * KB + g * E < K;
+            const bool in_k = (s_lo + sl) * WIDE_KS + kb * KB + g * E < k_end;
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 const u32x4 wm = in_k ? wcur[t][kb] : zero16();
@@ -391,6 +407,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
     }
     wait_vmcnt_at_most<0>(); // nothing may still be landing in LDS when the workgroup ends
     if (!tile_live) return;
+    const int row_tiles = (a.R + 15) / 16;
 #pragma unroll
     for (int r = 0; r < RT; ++r) {
         float out[NT][4];
@@ -398,12 +415,63 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
         for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int v = 0; v < 4; ++v) out[t][v] = acc[0][r][t][v] + acc[1][r][t][v];
-        apply_epilogue<T, EPI>(a, out, n0, rt0 + r);
+        if (a.ksplit > 1) {
+            if (rt0 + r < row_tiles) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) a.splitk_ws[splitk_index(blockIdx.z, ntiles, tile, row_tiles, rt0 + r, NT, t, v, lane)] = out[t][v];
+            }
+        } else {
+            apply_epilogue<T, EPI>(a, out, n0, rt0 + r);
+        }
     }
 }
 
-template <typename T, int EPI, int NW, int RT> static void launch_wide(const GemmArgs &a, int tiles, int row_tiles, hipStream_t st) {
-    hipLaunchKernelGGL((gemm_wide_kernel<T, EPI, NW, RT>), dim3((tiles + NW - 1) / NW, (row_tiles + RT - 1) / RT), dim3(NW * 64), 0, st, a);
+// Second pass of a split-K launch: one wave per (wave tile, row tile) sums the splits' partial tiles in
+// split order and runs the epilogue.  grid (wave tiles, row tiles).
+template <typename T, int EPI>
+__global__ __launch_bounds__(64) void gemm_splitk_finish_kernel(GemmArgs a) {
+    constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
+    const int lane = threadIdx.x, tile = blockIdx.x, rt = blockIdx.y, row_tiles = gridDim.y;
+    int n0[NT];
+    const int ntiles = wide_tile_cols<EPI>(a, tile, n0);
+    float out[NT][4];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            float s = 0.f;
+            for (int z = 0; z < a.ksplit; ++z) s += a.splitk_ws[splitk_index(z, ntiles, tile, row_tiles, rt, NT, t, v, lane)];
+            out[t][v] = s;
+        }
+    apply_epilogue<T, EPI>(a, out, n0, rt);
+}
+
+// Matrices with few column tiles would leave most of the chip idle (one workgroup per compute unit fits:
+// 64 workgroups for a 4096-column projection).  K is then split over up to 4 workgroups whose partial
+// tiles a second small launch sums in a fixed order; the split count is the largest that still fits the
+// chip in one round, so the extra traffic (partials written and read once) stays a fraction of the weights.
+template <typename T, int EPI, int NW, int RT> static void launch_wide(const GemmArgs &a0, int tiles, int row_tiles, hipStream_t st) {
+    constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
+    constexpr int WIDE_KS = WIDE_SLAB_BYTES / (int)sizeof(T);
+    GemmArgs a = a0;
+    const int gx = (tiles + NW - 1) / NW, gy = (row_tiles + RT - 1) / RT;
+    const int nslab = (a.K + WIDE_KS - 1) / WIDE_KS;
+    int ks = std::min(std::min(256 / std::max(gx * gy, 1), 4), nslab);
+    a.ksplit = 1;
+    a.kslabs = nslab;
+    if (ks > 1 && a.splitk_ws) {
+        const int per = (nslab + ks - 1) / ks;
+        ks = (nslab + per - 1) / per; // no empty split
+        const size_t need = sizeof(float) * (size_t)ks * tiles * row_tiles * NT * 256;
+        if (ks > 1 && need <= a.splitk_ws_bytes) {
+            a.ksplit = ks;
+            a.kslabs = per;
+        }
+    }
+    hipLaunchKernelGGL((gemm_wide_kernel<T, EPI, NW, RT>), dim3(gx, gy, a.ksplit), dim3(NW * 64), 0, st, a);
+    if (a.ksplit > 1) hipLaunchKernelGGL((gemm_splitk_finish_kernel<T, EPI>), dim3(tiles, row_tiles), dim3(64), 0, st, a);
 }
 
 template <typename T, int EPI> static void launch_gemm_t(const GemmArgs &a, hipStream_t st) {

@@ -35,6 +35,10 @@ struct GemmArgs {
     const int32_t *len;  // [batch] lengths before this call's append
     const float2 *rope;  // [max_pos][hd/2] (cos, sin)
     void *kcache, *vcache; // this layer's K and V
+    // launches of more than 16 rows only: device workspace for split-K partial tiles (NULL: never split)
+    float *splitk_ws;
+    size_t splitk_ws_bytes;
+    int ksplit, kslabs; // set by the launcher: K splits, K slabs per split
 };
 void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st);
 
