@@ -137,6 +137,35 @@ def test_single_7b_layer_verify_matches_oracle(persistent):
     assert maxabs(got, ref) < 1e-3
 
 
+@pytest.mark.timeout(900)
+def test_batched_7b_layer_72_rows_matches_per_sequence_oracle():
+    """The batched workload's launch shapes at full width: one 7B-shaped bf16 layer, 8 sequences with
+    ragged contexts, K = 8 -> 72 rows in one call (wide GEMMs with split-K, split-KV attention).  Each
+    sequence's hidden rows against the oracle run on that sequence alone (reduced depth and context:
+    the full 32-layer, 4096-position pass is out of the oracle's reach)."""
+    shape = si.LAYER_7B
+    lw = si.layer_weights(shape, seed=0, layer=0)
+    w = {"embed": None, "gf": None, "lm_head": None, "layers": [lw]}
+    om = oracle.Model(shape, w)
+    B, M = 8, 9
+    lens = [300, 17, 129, 64, 1, 255, 190, 77]
+    gm = sv.Model(shape, weights_to_device(w), max_rows=B * M, max_pos=512)
+    gkv = sv.KVCache(gm, B, 384)
+    h = si.normal(9, "h72", (B, M, shape.d_model), 1.0)
+    refs = []
+    for b in range(B):
+        ctx = si.kv_context(shape, 9, f"ctx72_{b}", lens[b])
+        sv.ss_kv_cache_append(gkv, 0, b, 0, ctx[0][0].to(dev()), ctx[0][1].to(dev()))
+        okv = om.new_kv(384)
+        okv.append_raw(ctx)
+        refs.append(om.layers_forward(okv, h[b].numpy()))
+    sv.ss_kv_cache_set_len(gkv, lens)
+    got = sv.ss_decoder_layers_forward(gm, gkv, h.reshape(B * M, -1).to(dev()).clone(), B, M).cpu().numpy().reshape(B, M, -1)
+    for b in range(B):
+        assert maxabs(got[b], refs[b]) < 2e-2, b
+    assert sv.ss_kv_cache_get_len(gkv).tolist() == [l + M for l in lens]
+
+
 @pytest.mark.timeout(1200)
 def test_full_7b_verify_pass_matches_oracle():
     """The benchmark workload at its full size and in the launch configuration bench.py times (32
