@@ -494,7 +494,15 @@ template <typename T, int EPI> static void launch_gemm_t(const GemmArgs &a, hipS
         if (small) launch_wide<T, EPI, 4, 3>(a, tiles, row_tiles, st);
         else launch_wide<T, EPI, 8, 3>(a, tiles, row_tiles, st);
     } else {
-        if (small || FUSED) launch_wide<T, EPI, 4, 5>(a, tiles, row_tiles, st);
+        // one workgroup per compute unit fits: 3 waves per workgroup when that fills more of a 256-unit chip
+        // in whole rounds than 4 (688 gate/up tiles: 230 workgroups instead of 172; 384 QKV tiles: 128, split in two)
+        auto fill = [&](int nw) {
+            const int wgs = (tiles + nw - 1) / nw * ((row_tiles + 4) / 5);
+            const int ks = std::max(1, std::min(256 / std::max(wgs, 1), 4));
+            return (double)(wgs * ks) / (double)((wgs * ks + 255) / 256 * 256);
+        };
+        if ((small || FUSED) && fill(3) > fill(4) + 0.1) launch_wide<T, EPI, 3, 5>(a, tiles, row_tiles, st);
+        else if (small || FUSED) launch_wide<T, EPI, 4, 5>(a, tiles, row_tiles, st);
         else launch_wide<T, EPI, 8, 5>(a, tiles, row_tiles, st);
     }
 }
