@@ -293,40 +293,38 @@ __device__ __forceinline__ bool grid_wait_qkv_of_head(const MegaCall &P, unsigne
 
 // ---------------------------------------------------------------- non-GEMM phases
 
+// Embedding phase: every workgroup takes a slice of the columns of all hidden rows (the way the residual
+// phases own columns), so the gather is one short step for the whole chip and each workgroup has its own
+// partial sums of squares to publish.  Thread t works on hidden row t & 15 and columns (t >> 4) + 16 j of
+// the slice; returns this thread's share of its row's sum of squares.
 template <typename T>
-__device__ __forceinline__ void do_embed(const MegaCall &P, const MegaPhase &ph, int wg, int G, MegaSmem &sm) {
+__device__ __forceinline__ float do_embed(const MegaCall &P, const MegaPhase &ph, int wg, int G) {
     const ActPlanes<T> act = act_planes<T>(P, ACT_A);
-    for (int r = wg; r < P.R; r += G) {
-        const T *src = nullptr;
-        if (P.tokens) {
-            int tok = P.tokens[r];
-            if (tok < 0 || tok >= P.V) {
-                if (threadIdx.x == 0) atomicOr(P.status, 1);
-                tok = tok < 0 ? 0 : P.V - 1;
-            }
-            src = reinterpret_cast<const T *>(P.embed) + (size_t)tok * P.d;
+    const int c0 = (int)((long long)wg * P.d / G), c1 = (int)((long long)(wg + 1) * P.d / G);
+    const int r = threadIdx.x & 15;
+    float ss = 0.f;
+    if (r >= P.R) return ss;
+    const T *src = nullptr;
+    if (P.tokens) {
+        int tok = P.tokens[r];
+        if (tok < 0 || tok >= P.V) {
+            atomicOr(P.status, 1);
+            tok = tok < 0 ? 0 : P.V - 1;
         }
-        float ss = 0.f;
-        for (int e = threadIdx.x; e < P.d; e += MEGA_THREADS) {
-            float x;
-            if (src) {
-                x = to_f32(src[e]);
-                st_coh(&P.h[(size_t)r * P.d + e], x);
-            } else {
-                x = ld_coh(&P.h[(size_t)r * P.d + e]);
-            }
-            store_act_coh(act, (size_t)r * act.ld + e, ph.gain ? x * ldf_global(ph.gain + e) : x);
-            ss += x * x;
-        }
-        ss = wave_sum(ss);
-        __syncthreads();
-        if ((threadIdx.x & 63) == 0) sm.t->blk[threadIdx.x >> 6] = ss;
-        __syncthreads();
-        float tot = 0.f;
-#pragma unroll
-        for (int w = 0; w < MNW; ++w) tot += sm.t->blk[w];
-        for (int s = threadIdx.x; s < G; s += MEGA_THREADS) st_coh(&P.nsq[(size_t)r * G + s], s == 0 ? tot : 0.f);
+        src = reinterpret_cast<const T *>(P.embed) + (size_t)tok * P.d;
     }
+    for (int e = c0 + (int)(threadIdx.x >> 4); e < c1; e += MEGA_THREADS / 16) {
+        float x;
+        if (src) {
+            x = to_f32(src[e]);
+            st_coh(&P.h[(size_t)r * P.d + e], x);
+        } else {
+            x = ld_coh(&P.h[(size_t)r * P.d + e]);
+        }
+        store_act_coh(act, (size_t)r * act.ld + e, ph.gain ? x * ldf_global(ph.gain + e) : x);
+        ss += x * x;
+    }
+    return ss;
 }
 
 template <typename T, int HD>
@@ -875,6 +873,20 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
             if (!polled) stores_done(); // (a workgroup without a share of a data-synchronised phase cannot occur: the host checks)
             grid_arrive(P, epoch, sm);
         }
+        // publish this workgroup's partial sums of squares of the new hidden rows: thread t holds a share of row t & 15
+        auto publish_rowsq = [&](float rs, int act_dst) {
+            rs += __shfl_xor(rs, 16);
+            rs += __shfl_xor(rs, 32);
+            lds_barrier(); // readers of the previous use are done
+            if (lane < 16) sm.t->sq[wave][lane] = rs;
+            lds_barrier();
+            if (threadIdx.x < 16) {
+                float tot = 0.f;
+#pragma unroll
+                for (int w2 = 0; w2 < MNW; ++w2) tot += sm.t->sq[w2][threadIdx.x];
+                st_coh(&nsq_set(P, act_dst, G)[(size_t)threadIdx.x * G + wg], f2u(tot) == 0xffffffffu ? u2f(0xffc00000u) : tot); // the all-ones pattern is reserved
+            }
+        };
         int nstash = 0;
         const Range my = st.cc.r; // this workgroup's share of the phase
         // One segment: n_fill rounds of RING steps in which each step refills its slot, then (last: the
@@ -965,6 +977,9 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
             if (p > 0) {
                 if (ph.kind == PH_ATTN && attn_units <= G) { // one unit per workgroup at most: wait for its producers only
                     if (wg < attn_units && !grid_wait_qkv_of_head(P, epoch, (wg / P.nsplit) % P.H, G, sm)) return;
+                } else if (ph.kind == PH_LEN) {
+                    // nothing to wait for: the lengths were read by every workgroup before the first phase
+                    // boundary of the launch, which this workgroup has long passed
                 } else if (!grid_wait(P, epoch, 0, G, sm)) {
                     return;
                 }
@@ -973,7 +988,7 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
             switch (ph.kind) {
             case PH_EMBED:
                 if (clears) clear_outputs<T>(P, P.phases[ph.clear_phase], wg, G);
-                do_embed<T>(P, ph, wg, G, sm);
+                publish_rowsq(do_embed<T>(P, ph, wg, G), ACT_A);
                 break;
             case PH_ATTN:
                 do_attn<T>(P, ph, wg, G, sm);
@@ -1017,20 +1032,7 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
             if (P.timeline && threadIdx.x == 0 && final_round) P.timeline[(size_t)(5 * p + 3) * G + wg] = wall_clock64();
             if (final_round || stash_room() < 1) flush_stash<T>(P, ph, my, nstash, st.es, final_round, sm);
         }
-        if (ph.kind == PH_RESID) {
-            // publish this workgroup's partial sums of squares of the new hidden rows
-            float rs = st.es.rowsq;
-            rs += __shfl_xor(rs, 16);
-            rs += __shfl_xor(rs, 32);
-            if (lane < 16) sm.t->sq[wave][lane] = rs;
-            lds_barrier();
-            if (threadIdx.x < 16) {
-                float tot = 0.f;
-#pragma unroll
-                for (int w2 = 0; w2 < MNW; ++w2) tot += sm.t->sq[w2][threadIdx.x];
-                st_coh(&nsq_set(P, ph.act_dst, G)[(size_t)threadIdx.x * G + wg], f2u(tot) == 0xffffffffu ? u2f(0xffc00000u) : tot); // the all-ones pattern is reserved
-            }
-        }
+        if (ph.kind == PH_RESID) publish_rowsq(st.es.rowsq, ph.act_dst);
         if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(5 * p + 4) * G + wg] = wall_clock64();
     }
 }
