@@ -23,7 +23,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK = 8.0e12  # B/s, MI355X published peak
-PERSISTENT_7B_TRAFFIC_BYTES = 13.613e9  # 13.476 GB fetched + 0.137 GB written per launch (rocprofv3 --pmc, see profiles/)
+PERSISTENT_7B_TRAFFIC_BYTES = 13.608e9  # 13.472 GB fetched + 0.136 GB written per launch (rocprofv3 --pmc, see profiles/)
 
 
 def build_7b(si, sv, torch, seed, n_layers, dev):
