@@ -157,6 +157,33 @@ def test_persistent_kernel_is_deterministic_and_independent_of_its_synchronisati
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[1], outs[2])
 
 
+def test_7b_width_data_synchronisation_equals_barriers_over_many_launches():
+    """Three 7B-shaped layers + LM head on the default grid (one workgroup per compute unit, where the
+    self-validating protocol is what runs): 60 launches with the row count changing from call to call
+    (1, 5, 9, 2, ... rows: the buffers keep rows of earlier, larger calls), context growing and rolled
+    back.  Every launch must give the logits of the barrier-only mode bit for bit."""
+    from bench import build_7b
+    shape, packed, io = build_7b(si, sv, torch, 5, 3, dev())
+    ms = []
+    for data_sync in (False, True):
+        gm = sv.Model(shape, io, max_rows=16, max_pos=1024, packed_layers=packed)
+        sv.ss_model_set_persistent_options(gm, 0, data_sync)
+        ms.append((gm, sv.KVCache(gm, 1, 1024)))
+    toks = si.token_ids(5, "many", (60, 9), shape.vocab).to(dev()).int()
+    rows = [1, 5, 9, 2, 9, 1, 4, 8, 3, 5]
+    for it in range(60):
+        M = rows[it % len(rows)]
+        t = toks[it:it + 1, :M].contiguous()
+        a = sv.ss_verify_forward(ms[0][0], ms[0][1], t, M)
+        b = sv.ss_verify_forward(ms[1][0], ms[1][1], t, M)
+        assert torch.equal(a, b), it
+        if it % 7 == 6:   # reject most of the rows of this call, as the rejection step would
+            for gm, kv in ms:
+                sv.ss_kv_cache_rollback(kv, torch.zeros(1, dtype=torch.int32, device=dev()), M, n_accepted_host=[0])
+    assert sv.ss_device_status(ms[0][0]) == 0 and sv.ss_device_status(ms[1][0]) == 0
+    assert sv.ss_kv_cache_get_len(ms[0][1]).tolist() == sv.ss_kv_cache_get_len(ms[1][1]).tolist()
+
+
 @pytest.mark.timeout(900)
 def test_batched_7b_layer_72_rows_matches_per_sequence_oracle():
     """The batched workload's launch shapes at full width: one 7B-shaped bf16 layer, 8 sequences with
