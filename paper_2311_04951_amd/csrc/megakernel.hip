@@ -820,7 +820,7 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
     // with the chunk RING ahead.  A workgroup's positions per phase are padded to a multiple of RING, so
     // each phase starts at slot 0 and the code below exists once.  The last round of a phase does not
     // refill: the ring is empty at a phase boundary and is refilled there with the first round of the
-    // next phase, before the device-wide barrier, so those loads fly during the barrier.
+    // next phase, so those loads fly while the boundary's dependencies resolve.
     struct State {
         Cursor cc, la;
         f32x4 acc0, acc1;
@@ -852,9 +852,8 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
 
     for (int p = 0; p < P.n_phases; ++p) {
         const MegaPhase ph = P.phases[p];
-        // Phase boundary: all ring slots are filled unconditionally (loads of zeros when this
-        // workgroup has no share of the phase), which also tells the compiler that the slots hold
-        // nothing across a phase that does not use them.
+        // Phase boundary.  A workgroup with GEMM work in the phase fills all ring slots here (see below);
+        // one without leaves the ring alone.
         cursor_begin<T>(st.cc, ph, P.hd, wg, G);
         st.la = st.cc;
         const unsigned epoch = P.epoch_base + (unsigned)p;
