@@ -191,6 +191,18 @@ def main():
                "autoregressive_tokens_per_s": n_ar / ar_stats["loop_seconds"],
                "speedup_vs_autoregressive": (st["generated"] / st["loop_seconds"]) / (n_ar / ar_stats["loop_seconds"]),
                "temperature": T, "K": K, "draft": f"first {dshape.n_layers} target layers + shared norm and LM head"}
+        # the other draft lengths of the workload (K = 2, 4, 8), sampled and greedy, on a shorter run
+        sweep = {}
+        n_sw = min(96, n_new)
+        for k2 in (2, 4, 8):
+            for t2 in (1.0, 0.0):
+                _, s2 = gen.speculative_generate(target, draft, prompt, n_sw, k2, t2, si.uniforms(1, f"ud{k2}", (n_sw, k2)),
+                                                 si.uniforms(1, f"ua{k2}", (n_sw, k2 + 1)))
+                sweep[f"K{k2}_{'greedy' if t2 == 0.0 else 'T1'}"] = {
+                    "accepted_tokens_per_s": round(s2["generated"] / s2["loop_seconds"], 1),
+                    "mean_accepted_per_step": round(sum(s2["accepted"]) / max(1, s2["steps"]), 3),
+                    "ms_per_step": round(1e3 * s2["loop_seconds"] / max(1, s2["steps"]), 3)}
+        e2e["by_draft_length"] = sweep
 
     # ---- state for the verify-pass legs: prompt in the cache, real draft rows from the draft model
     total_steps = args.warmup + 2 * args.steps + 4
