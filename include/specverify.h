@@ -6,6 +6,9 @@
  * never frees caller memory.  `stream` is a hipStream_t passed as void* (NULL = the null
  * stream); all work of a call is enqueued on it and, unless a call says otherwise, nothing
  * synchronises with the host.  Handles are not thread-safe: one stream per handle at a time.
+ * The entry points without a handle (ss_softmax, ss_speculative_accept*, ss_greedy_accept) share
+ * one library-owned device workspace, grown on demand (the only allocation a hot-path call can
+ * make, and it synchronises the device when it happens): issue them on one stream at a time.
  *
  * Return value of every call: SS_OK (0) or a negative code.  Arguments are validated on the
  * host before anything is launched, so SS_EINVAL / SS_ECAPACITY never leave partial device
