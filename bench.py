@@ -135,6 +135,76 @@ def standalone_accept(si, sv, torch, dev, iters=40):
             "mean_accepted": float(na.float().mean())}
 
 
+def layer_pass(si, sv, torch, dev, target, shape, iters=20, L=1024, M=5):
+    """The one-layer workload at full width (5 query rows against 1024 cached positions), measured over the
+    target's distinct layers in turn (every layer has its own weights and cache, 13 GB in all, so
+    nothing is served from the last-level cache): median time of ss_decoder_layers_forward per layer."""
+    kv = sv.KVCache(target, 1, L + 64)
+    W = shape.n_heads * shape.head_dim
+    for l in range(shape.n_layers):
+        k = si.normal(7, f"lp_k{l}", (L, W), 1.0, device=dev, dtype=torch.bfloat16)
+        v = si.normal(7, f"lp_v{l}", (L, W), 1.0, device=dev, dtype=torch.bfloat16)
+        sv.ss_kv_cache_append(kv, l, 0, 0, k, v)
+    h0 = si.normal(7, "lp_h", (M, shape.d_model), 1.0, device=dev)
+    times = []
+    for it in range(iters + 3):
+        sv.ss_kv_cache_set_len(kv, [L])
+        h = h0.clone()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        sv.ss_decoder_layers_forward(target, kv, h, 1, M)
+        torch.cuda.synchronize()
+        if it >= 3:
+            times.append((time.perf_counter() - t0) / shape.n_layers)
+    kv.close()
+    times.sort()
+    t = times[len(times) // 2]
+    nbytes = layer_bytes(shape) + 2 * (L + M) * W * 2 + 2 * M * W * 2
+    return {"workload": f"one 7B-shaped bf16 layer, {M} query rows, {L} cached positions; median over {iters} passes through "
+                        f"{shape.n_layers} distinct layers", "us_per_layer": t * 1e6, "algorithmic_bytes_per_layer": nbytes,
+            "GBps": nbytes / t / 1e9, "frac_of_hbm_peak": nbytes / t / HBM_PEAK}
+
+
+def batched_workload(si, sv, torch, dev, shape, packed, io, iters=5, B=8, L=4096, M=9):
+    """The batched long-context workload: 8 sequences with 4096 cached positions each, K = 8 (72 rows per
+    verify pass, one launch per phase: wide GEMMs and split-KV attention)."""
+    m = sv.Model(shape, io, max_rows=B * M, max_pos=L + 512, packed_layers=packed)
+    kv = sv.KVCache(m, B, L + 512)
+    W = shape.n_heads * shape.head_dim
+    for l in range(shape.n_layers):
+        k = si.normal(5, f"bw_k{l}", (L, W), 1.0, device=dev, dtype=torch.bfloat16)
+        v = si.normal(5, f"bw_v{l}", (L, W), 1.0, device=dev, dtype=torch.bfloat16)
+        for b in range(B):
+            sv.ss_kv_cache_append(kv, l, b, 0, k, v)
+    toks = si.token_ids(0, "bw_t", (B, M), shape.vocab).to(dev).int()
+    logits = torch.empty((B, M, shape.vocab), device=dev)
+
+    def run():
+        sv.ss_kv_cache_set_len(kv, [L] * B)
+        sv.ss_verify_forward(m, kv, toks, M, logits)
+
+    for _ in range(2):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(iters):
+        run()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / iters
+    sv.ss_profile_enable(m, True)
+    for _ in range(3):
+        run()
+    torch.cuda.synchronize()
+    prof = sv.ss_profile_read(m)
+    nbytes = shape.n_layers * layer_bytes(shape) + shape.vocab * shape.d_model * 2 + shape.n_layers * B * 2 * (L + M) * W * 2
+    out = {"workload": f"batch {B}, context {L}, K {M - 1} ({B * M} rows per pass), {shape.n_layers} layers", "ms_per_pass": dt * 1e3,
+           "rows_per_s": B * M / dt, "algorithmic_bytes": nbytes, "GBps": nbytes / dt / 1e9, "frac_of_hbm_peak": nbytes / dt / HBM_PEAK,
+           "class_ms_per_pass": {k: round(ms / 3, 3) for k, (ms, n) in prof.items() if n}}
+    kv.close()
+    m.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -148,6 +218,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-e2e", action="store_true")
     ap.add_argument("--no-accept-workload", action="store_true", help="skip the stand-alone accept workload leg")
+    ap.add_argument("--no-layer-pass", action="store_true", help="skip the one-layer leg (5 rows, 1024 cached positions)")
+    ap.add_argument("--batched-workload", action="store_true",
+                    help="also time the batched long-context workload (8 x 4096 positions, 72 rows; needs 20 GB more)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of 1 GiB five times (a kernel of known traffic, for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -290,8 +363,12 @@ def main():
         "roofline": roofline,
         "end_to_end": e2e,
     }
+    if not args.no_layer_pass:
+        out["layer_pass"] = layer_pass(si, sv, torch, dev, target, shape)
     if not args.no_accept_workload:
         out["standalone_accept"] = standalone_accept(si, sv, torch, dev)
+    if args.batched_workload:
+        out["batched_workload"] = batched_workload(si, sv, torch, dev, shape, packed, io)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(si, torch, shape, packed, io, prompt_len, M)
     if args.copy_calibration:

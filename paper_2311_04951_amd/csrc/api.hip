@@ -591,10 +591,12 @@ static int run_persistent(ss_model *m, ss_kv_cache *kv, const int32_t *tokens, f
     P.rope = m->rope;
     int Lmax = 0;
     for (int b = 0; b < batch; ++b) Lmax = std::max(Lmax, kv->len_ub[b] + M);
-    // one (sequence, head, split) unit per workgroup when possible; a split is worth its merge only once
-    // a unit would otherwise walk more than ~1024 positions (4 blocks per wave)
+    // One (sequence, head, split) unit per workgroup when possible.  Splitting the KV range costs a merge
+    // through memory (about 3 us), which pays once a unit would otherwise walk more than ~400 positions;
+    // from there on as many splits as there are idle workgroups is best (measured at 512, 1024 and 4000
+    // positions: 8 splits beat 1, 2 and 4; below 300 positions one unit per head wins).
     const int fit = std::max(1, m->mega_G / (batch * c.n_heads));
-    int nsplit = std::max(1, std::min(std::min((Lmax + 1023) / 1024, fit), MAX_SPLITS));
+    int nsplit = Lmax <= 384 ? 1 : std::max(1, std::min(std::min((Lmax + 127) / 128, fit), MAX_SPLITS));
     const int chunk = round_up((Lmax + nsplit - 1) / nsplit, 64);
     nsplit = (Lmax + chunk - 1) / chunk;
     P.nsplit = nsplit; P.chunk = chunk;

@@ -137,22 +137,22 @@ def test_single_7b_layer_verify_matches_oracle(persistent):
     assert maxabs(got, ref) < 1e-3
 
 
-@pytest.mark.parametrize("dtype,M", [("bf16", 5), ("bf16", 9), ("f32", 16)])
-def test_persistent_kernel_is_deterministic_and_independent_of_its_synchronisation(dtype, M):
+@pytest.mark.parametrize("dtype,M,ctx", [("bf16", 5, 40), ("bf16", 9, 40), ("f32", 16, 40), ("bf16", 5, 456)])   # 456: split-KV attention with its merge
+def test_persistent_kernel_is_deterministic_and_independent_of_its_synchronisation(dtype, M, ctx):
     """The same call three ways: barriers at every phase boundary, self-validating activations, and the
     latter once more.  The arithmetic does not depend on how the phases are ordered in time, so the
     logits agree bit for bit (a stale or half-written activation would show up here)."""
     shape = si.DecoderShape(3, 256, 4, 64, 688, 1000, dtype=dtype)
     w = weights_to_device(si.decoder_weights(shape, seed=12))
-    toks = si.token_ids(12, "toks", (40 + M,), shape.vocab).numpy().astype(np.int32)
+    toks = si.token_ids(12, "toks", (ctx + M,), shape.vocab).numpy().astype(np.int32)
     outs = []
     for data_sync in (False, True, True):
-        gm = sv.Model(shape, w, max_rows=16, max_pos=256)
+        gm = sv.Model(shape, w, max_rows=16, max_pos=512)
         sv.ss_model_set_persistent(gm, True)
         sv.ss_model_set_persistent_options(gm, 8, data_sync)
-        gkv = sv.KVCache(gm, 1, 128)
-        _gpu_forward_chunks(gm, gkv, toks[:40], [16, 16, 8])
-        outs.append(sv.ss_verify_forward(gm, gkv, torch.tensor(toks[None, 40:], device=dev()), M).clone())
+        gkv = sv.KVCache(gm, 1, 512)
+        _gpu_forward_chunks(gm, gkv, toks[:ctx], [16] * (ctx // 16) + [ctx % 16] * (ctx % 16 > 0))
+        outs.append(sv.ss_verify_forward(gm, gkv, torch.tensor(toks[None, ctx:], device=dev()), M).clone())
         assert sv.ss_device_status(gm) == 0
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[1], outs[2])
 
