@@ -25,21 +25,63 @@ void launch_embed(int dtype, const void *embed, const int32_t *tokens, int R, in
     else hipLaunchKernelGGL((embed_kernel<float>), dim3(R), dim3(256), 0, st, (const float *)embed, tokens, d, vocab, h, status);
 }
 
-// act[r][:] = h[src][:] * gain / sqrt(mean(h[src]^2) + eps) with src = row0 + r*row_stride
+// act[r][:] = h[src][:] * gain / sqrt(mean(h[src]^2) + eps) with src = row0 + r*row_stride.
+// One workgroup per row; a row of up to 8192 elements stays in registers between the two passes (16-byte
+// loads, 8-byte stores of four packed values per plane); longer or unaligned rows take the plain loops.
+__device__ __forceinline__ void store_act4(const ActPlanes<bf16_t> &a, size_t off, const float (&x)[4]) {
+    uint32_t hi[4], lo[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        hi[j] = bf16_rne(x[j]);
+        lo[j] = bf16_rne(x[j] - bf16_bits_to_f32(hi[j]));
+    }
+    *reinterpret_cast<uint2 *>(a.base + off) = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
+    *reinterpret_cast<uint2 *>(a.base + a.plane + off) = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
+}
+__device__ __forceinline__ void store_act4(const ActPlanes<float> &a, size_t off, const float (&x)[4]) {
+    *reinterpret_cast<float4 *>(a.base + off) = make_float4(x[0], x[1], x[2], x[3]);
+}
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(const float *h, const float *gain, int row0, int row_stride,
                                                            int d, float eps, ActPlanes<T> act) {
+    constexpr int MAXV = 8; // float4 per thread kept in registers
     const int r = blockIdx.x;
     const float *x = h + (size_t)(row0 + r * row_stride) * d;
+    const bool vec = d % 4 == 0 && d <= 256 * 4 * MAXV && act.ld % 4 == 0 && act.plane % 4 == 0 &&
+                     (reinterpret_cast<uintptr_t>(h) & 15) == 0 && (reinterpret_cast<uintptr_t>(gain) & 15) == 0 &&
+                     (reinterpret_cast<uintptr_t>(act.base) & 15) == 0;
+    float4 v[MAXV];
     float ss = 0.f;
-    for (int e = threadIdx.x; e < d; e += 256) ss += x[e] * x[e];
+    if (vec) {
+#pragma unroll
+        for (int j = 0; j < MAXV; ++j) {
+            const int e4 = threadIdx.x + 256 * j;
+            v[j] = e4 * 4 < d ? reinterpret_cast<const float4 *>(x)[e4] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int j = 0; j < MAXV; ++j) ss += (v[j].x * v[j].x + v[j].y * v[j].y) + (v[j].z * v[j].z + v[j].w * v[j].w);
+    } else {
+        for (int e = threadIdx.x; e < d; e += 256) ss += x[e] * x[e];
+    }
     ss = wave_sum(ss);
     __shared__ float part[4];
     if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
     __syncthreads();
     const float tot = (part[0] + part[1]) + (part[2] + part[3]);
     const float scale = 1.0f / sqrtf(tot / (float)d + eps);
-    for (int e = threadIdx.x; e < d; e += 256) store_act(act, (size_t)r * act.ld + e, x[e] * scale * gain[e]);
+    if (vec) {
+#pragma unroll
+        for (int j = 0; j < MAXV; ++j) {
+            const int e4 = threadIdx.x + 256 * j;
+            if (e4 * 4 < d) {
+                const float4 g = reinterpret_cast<const float4 *>(gain)[e4];
+                const float o[4] = {v[j].x * scale * g.x, v[j].y * scale * g.y, v[j].z * scale * g.z, v[j].w * scale * g.w};
+                store_act4(act, (size_t)r * act.ld + 4 * e4, o);
+            }
+        }
+    } else {
+        for (int e = threadIdx.x; e < d; e += 256) store_act(act, (size_t)r * act.ld + e, x[e] * scale * gain[e]);
+    }
 }
 
 void launch_rmsnorm_pack_rows(int dtype, const float *h, const float *gain, int nrows, int row0, int row_stride,
