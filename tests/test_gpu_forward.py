@@ -159,7 +159,7 @@ def test_persistent_kernel_is_deterministic_and_independent_of_its_synchronisati
 
 def test_7b_width_data_synchronisation_equals_barriers_over_many_launches():
     """Three 7B-shaped layers + LM head on the default grid (one workgroup per compute unit, where the
-    self-validating protocol is what runs): 60 launches with the row count changing from call to call
+    self-validating protocol is what runs): 200 launches with the row count changing from call to call
     (1, 5, 9, 2, ... rows: the buffers keep rows of earlier, larger calls), context growing and rolled
     back.  Every launch must give the logits of the barrier-only mode bit for bit."""
     from bench import build_7b
@@ -169,9 +169,9 @@ def test_7b_width_data_synchronisation_equals_barriers_over_many_launches():
         gm = sv.Model(shape, io, max_rows=16, max_pos=1024, packed_layers=packed)
         sv.ss_model_set_persistent_options(gm, 0, data_sync)
         ms.append((gm, sv.KVCache(gm, 1, 1024)))
-    toks = si.token_ids(5, "many", (60, 9), shape.vocab).to(dev()).int()
+    toks = si.token_ids(5, "many", (200, 9), shape.vocab).to(dev()).int()
     rows = [1, 5, 9, 2, 9, 1, 4, 8, 3, 5]
-    for it in range(60):
+    for it in range(200):
         M = rows[it % len(rows)]
         t = toks[it:it + 1, :M].contiguous()
         a = sv.ss_verify_forward(ms[0][0], ms[0][1], t, M)
@@ -180,6 +180,9 @@ def test_7b_width_data_synchronisation_equals_barriers_over_many_launches():
         if it % 7 == 6:   # reject most of the rows of this call, as the rejection step would
             for gm, kv in ms:
                 sv.ss_kv_cache_rollback(kv, torch.zeros(1, dtype=torch.int32, device=dev()), M, n_accepted_host=[0])
+        if it % 50 == 49:  # and start over on a short context now and then
+            for gm, kv in ms:
+                sv.ss_kv_cache_set_len(kv, [33])
     assert sv.ss_device_status(ms[0][0]) == 0 and sv.ss_device_status(ms[1][0]) == 0
     assert sv.ss_kv_cache_get_len(ms[0][1]).tolist() == sv.ss_kv_cache_get_len(ms[1][1]).tolist()
 
