@@ -286,8 +286,14 @@ def autoregressive_generate(target: Model, prompt, n_new: int, temperature: floa
 
 
 def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int,
-                         temperature: float, u_draft=None, u_accept=None, max_seq=None):
+                         temperature: float, u_draft=None, u_accept=None, max_seq=None, shared_kv=False):
     """Speculative sampling with two KV caches (Sections 3, 4.3, 4.4).
+
+    shared_kv (the other answer to Section 4.4's "do we have two separate caches?", for a draft made of
+    the target's first layers): the draft reads and writes the leading layers of the target's cache.
+    Its K calls leave the cache at n-1+K positions; the length is set back to n-1 and the verify call
+    rewrites those positions for every layer, so afterwards the cache is complete up to n+K for both
+    models and no catch-up call is ever needed.
 
     State at the start of a step: n committed tokens, both caches hold positions of the first n-1.
     Draft phase: K one-token draft calls (after a fully accepted step the first call feeds the two
@@ -297,10 +303,12 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
     x = [int(t) for t in prompt]
     n0 = len(x)
     cap = max_seq or (n0 + n_new + K + 2)
-    tkv, dkv = target.new_kv(cap), draft.new_kv(cap)
+    tkv = target.new_kv(cap)
+    dkv = tkv if shared_kv else draft.new_kv(cap)
     if n0 > 1:
         target.forward(tkv, x[:-1], want_logits=False)
-        draft.forward(dkv, x[:-1], want_logits=False)
+        if not shared_kv:
+            draft.forward(dkv, x[:-1], want_logits=False)
     pending = [x[-1]]
     step = 0
     accepted_hist = []
@@ -319,6 +327,8 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
                 tok = sample(q_rows[i], u_draft[step][i])
             d.append(tok)
             feed = [tok]
+        if shared_kv:
+            tkv.set_len(n - 1)   # the draft's rows of the leading layers are rewritten by the verify call
         pl = target.forward(tkv, [x[-1]] + d)
         if greedy:
             na, nx = greedy_accept(pl[None], np.asarray([d], dtype=np.int32))
@@ -329,8 +339,9 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
         a, y = int(na[0]), int(nx[0])
         x += d[:a] + [y]
         tkv.set_len(n + a)
-        if a < K:
-            dkv.set_len(n + a)
+        if shared_kv or a < K:
+            if not shared_kv:
+                dkv.set_len(n + a)
             pending = [y]
         else:
             pending = [d[K - 1], y]

@@ -284,3 +284,33 @@ def test_sampled_speculative_with_identical_models_equals_sampling_from_the_targ
     assert all(a == K for a in stats["accepted"])
     u_ar = np.concatenate([np.concatenate([ud[s], ua[s, K:]]) for s in range(steps)])
     assert sp == oracle.autoregressive_generate(target, prompt, n_new, 1.0, u_ar)
+
+
+@pytest.mark.parametrize("K,temperature", [(1, 0.0), (4, 0.0), (3, 1.0), (8, 1.0)])
+def test_shared_cache_for_an_early_exit_draft_changes_nothing(K, temperature):
+    """Section 4.4 asks whether two separate caches are needed.  For a draft made of the target's first
+    layers they are not: the draft can work in the leading layers of the target's cache (its rows are
+    rewritten by the verify call).  The keys and values it would have kept in a cache of its own are
+    the same numbers, so the token stream and the accept counts are identical to the two-cache loop -
+    and the greedy stream still equals autoregressive greedy decoding."""
+    tw = si.decoder_weights(si.TINY_TARGET, 11)
+    dshape, dw = si.early_exit_draft(si.TINY_TARGET, tw, 1)
+    target, draft = oracle.Model(si.TINY_TARGET, tw), oracle.Model(dshape, dw)
+    prompt = si.token_ids(11, "prompt", (20,), 1024).numpy()
+    n_new = 30
+    ud = si.uniforms(11, "ud", (n_new, K)).numpy()
+    ua = si.uniforms(11, "ua", (n_new, K + 1)).numpy()
+    two, st2 = oracle.speculative_generate(target, draft, prompt, n_new, K, temperature, ud, ua)
+    one, st1 = oracle.speculative_generate(target, draft, prompt, n_new, K, temperature, ud, ua, shared_kv=True)
+    assert one == two and st1["accepted"] == st2["accepted"]
+    if temperature == 0.0:
+        assert one == oracle.autoregressive_generate(target, prompt, n_new, 0.0)
+
+
+def test_shared_cache_with_the_target_as_its_own_draft_accepts_everything():
+    """Draft == target on one cache: every step accepts all K tokens, and no two-token catch-up exists."""
+    tw = si.decoder_weights(si.TINY_TARGET, 12)
+    target = oracle.Model(si.TINY_TARGET, tw)
+    prompt = si.token_ids(12, "prompt", (8,), 1024).numpy()
+    sp, stats = oracle.speculative_generate(target, target, prompt, 20, 3, 0.0, shared_kv=True)
+    assert sp == oracle.autoregressive_generate(target, prompt, 20, 0.0) and all(a == 3 for a in stats["accepted"])
