@@ -276,6 +276,11 @@ def main():
                     "mean_accepted_per_step": round(sum(s2["accepted"]) / max(1, s2["steps"]), 3),
                     "ms_per_step": round(1e3 * s2["loop_seconds"] / max(1, s2["steps"]), 3)}
         e2e["by_draft_length"] = sweep
+        # the same loop with one cache shared by both models (the draft works in the target's first layers' cache)
+        _, s3 = gen.speculative_generate(target, draft, prompt, n_new, K, T, ud, ua, shared_kv=True)
+        e2e["shared_kv_cache"] = {"accepted_tokens_per_s": s3["generated"] / s3["loop_seconds"], "steps": s3["steps"],
+                                  "mean_accepted_per_step": sum(s3["accepted"]) / max(1, s3["steps"]),
+                                  "ms_per_step": 1e3 * s3["loop_seconds"] / max(1, s3["steps"])}
 
     # ---- state for the verify-pass legs: prompt in the cache, real draft rows from the draft model
     total_steps = args.warmup + 2 * args.steps + 4

@@ -235,7 +235,11 @@ int ss_greedy_accept(const float *p_logits_dev, const int32_t *draft_tokens_dev,
  *   both caches rolled back to their committed length.
  * Outputs: result_dev int32 [2] = (n_accepted a, next token y); out_host int32 [K+2] = (a, y, d_1 ..
  * d_K) after a stream synchronisation; feed_dev / *n_feed are rewritten for the next step ([y], or
- * [d_K, y] when a == K: the draft cache is then one row short).  All *_dev buffers are the caller's
+ * [d_K, y] when a == K: the draft cache is then one row short).
+ * draft_kv == target_kv selects the shared-cache scheme for a draft made of the target's leading
+ * layers (any model may run on the leading layers of a deeper cache with the same heads and storage
+ * type): the draft's K calls append to the target's cache, the length is set back by K before the
+ * verify pass rewrites those positions for every layer, and the feed is always one token.  All *_dev buffers are the caller's
  * device memory; 1 <= K <= 15; both caches hold one sequence.  Errors as in the calls it is made of. */
 int ss_speculative_step(ss_model *target, ss_kv_cache *target_kv, ss_model *draft, ss_kv_cache *draft_kv,
                         int32_t K, float temperature, int32_t *feed_dev, int32_t *n_feed,

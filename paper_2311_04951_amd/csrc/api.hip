@@ -436,7 +436,9 @@ extern "C" int ss_kv_cache_rollback(ss_kv_cache *kv, const int32_t *n_accepted_d
 
 static int check_pair(const ss_model *m, const ss_kv_cache *kv, int batch, int M, const char *who) {
     if (!m || !kv) return fail(SS_EINVAL, "%s: NULL handle", who);
-    if (kv->n_layers != m->cfg.n_layers || kv->H != m->cfg.n_heads || kv->hd != m->cfg.head_dim || kv->dtype != m->cfg.dtype)
+    // a model may run on the leading layers of a deeper cache of the same head geometry (an early-exit draft
+    // working in the target's cache)
+    if (kv->n_layers < m->cfg.n_layers || kv->H != m->cfg.n_heads || kv->hd != m->cfg.head_dim || kv->dtype != m->cfg.dtype)
         return fail(SS_EINVAL, "%s: cache was allocated for a different model shape", who);
     if (batch != kv->B) return fail(SS_EINVAL, "%s: batch %d != cache batch %d", who, batch, kv->B);
     if (M < 1 || M > SS_MAX_ROWS_PER_SEQ) return fail(SS_EINVAL, "%s: rows per sequence must be in [1, %d]", who, SS_MAX_ROWS_PER_SEQ);
@@ -890,7 +892,9 @@ extern "C" int ss_speculative_step(ss_model *target, ss_kv_cache *tkv, ss_model 
     if (!target || !tkv || !draft || !dkv || !feed_dev || !n_feed || !vt || !logits_dev || !result_dev || !out_host)
         return fail(SS_EINVAL, "ss_speculative_step: NULL argument");
     if (K < 1 || K > SS_MAX_ROWS_PER_SEQ - 1) return fail(SS_EINVAL, "ss_speculative_step: K must be in [1, %d]", SS_MAX_ROWS_PER_SEQ - 1);
+    const bool shared = dkv == tkv; // the draft works in the leading layers of the target's cache
     if (*n_feed != 1 && *n_feed != 2) return fail(SS_EINVAL, "ss_speculative_step: *n_feed must be 1 or 2");
+    if (shared && *n_feed != 1) return fail(SS_EINVAL, "ss_speculative_step: a shared cache never needs a two-token feed");
     if (tkv->B != 1 || dkv->B != 1) return fail(SS_EINVAL, "ss_speculative_step: one sequence per cache");
     if (target->cfg.vocab != draft->cfg.vocab) return fail(SS_EINVAL, "ss_speculative_step: the two models have different vocabularies");
     if (!(temperature >= 0.f)) return fail(SS_EINVAL, "ss_speculative_step: temperature must be >= 0");
@@ -905,6 +909,10 @@ extern "C" int ss_speculative_step(ss_model *target, ss_kv_cache *tkv, ss_model 
         if (rc) return rc;
     }
     HIP_TRY(hipMemcpyAsync(vt, feed_dev + (*n_feed - 1), sizeof(int32_t), hipMemcpyDeviceToDevice, st)); // the last committed token
+    if (shared) { // the K positions the draft appended are rewritten, for every layer, by the verify pass
+        launch_len_add(tkv->len_dev, 1, -K, st);
+        tkv->len_ub[0] -= K;
+    }
     rc = ss_verify_forward(target, tkv, vt, 1, M, logits_dev, stream);
     if (rc) return rc;
     if (sample) {
@@ -916,15 +924,15 @@ extern "C" int ss_speculative_step(ss_model *target, ss_kv_cache *tkv, ss_model 
     }
     if (rc) return rc;
     launch_len_rollback(tkv->len_dev, result_dev, 1, M, st);
-    launch_len_rollback(dkv->len_dev, result_dev, 1, K, st); // a == K leaves the draft cache one row short of the target's
+    if (!shared) launch_len_rollback(dkv->len_dev, result_dev, 1, K, st); // a == K leaves the draft cache one row short of the target's
     HIP_TRY(hipMemcpyAsync(out_host, result_dev, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipMemcpyAsync(out_host + 2, vt + 1, K * sizeof(int32_t), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     const int a = std::min(std::max(out_host[0], 0), K);
     tkv->len_ub[0] -= M - 1 - a;
-    dkv->len_ub[0] -= K - 1 - std::min(a, K - 1);
-    // the next step's draft feed: [y], or [d_K, y] after a fully accepted step
-    if (a < K) {
+    if (!shared) dkv->len_ub[0] -= K - 1 - std::min(a, K - 1);
+    // the next step's draft feed: [y], or [d_K, y] after a fully accepted step of the two-cache scheme
+    if (a < K || shared) {
         HIP_TRY(hipMemcpyAsync(feed_dev, result_dev + 1, sizeof(int32_t), hipMemcpyDeviceToDevice, st));
         *n_feed = 1;
     } else {

@@ -14,7 +14,7 @@ import time
 
 import torch
 
-from . import (KVCache, Model, StepBuffers, ss_draft_step, ss_greedy_accept, ss_kv_cache_rollback, ss_softmax,
+from . import (KVCache, Model, StepBuffers, ss_draft_step, ss_greedy_accept, ss_kv_cache_rollback, ss_kv_cache_set_len, ss_softmax,
                ss_speculative_accept, ss_speculative_step, ss_verify_forward)
 
 
@@ -54,21 +54,25 @@ def autoregressive_generate(target: Model, prompt, n_new: int, temperature: floa
 
 
 def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int, temperature: float,
-                         u_draft=None, u_accept=None, max_seq=None, observer=None):
+                         u_draft=None, u_accept=None, max_seq=None, observer=None, shared_kv=False):
     """Returns (tokens[n_new], stats).  u_draft [steps, K], u_accept [steps, K+1] (temperature > 0).
     `observer(dict)` (optional) sees each step's device tensors: draft tokens, q rows, target logits,
     n_accepted, next token; with an observer the step is issued call by call from here, without one
-    it is a single ss_speculative_step per step (same calls, same results)."""
+    it is a single ss_speculative_step per step (same calls, same results).
+    shared_kv (Section 4.4, for a draft made of the target's first layers): one cache; the draft works in
+    its leading layers, the verify pass rewrites the draft's positions, no catch-up call exists."""
     if observer is None:
-        return _speculative_generate_native(target, draft, prompt, n_new, K, temperature, u_draft, u_accept, max_seq)
+        return _speculative_generate_native(target, draft, prompt, n_new, K, temperature, u_draft, u_accept, max_seq, shared_kv)
     dev = torch.device("cuda")
     V = target.shape.vocab
     M = K + 1
     greedy = temperature == 0
     cap = max_seq or (len(prompt) + n_new + K + 2)
-    tkv, dkv = KVCache(target, 1, cap), KVCache(draft, 1, cap)
+    tkv = KVCache(target, 1, cap)
+    dkv = tkv if shared_kv else KVCache(draft, 1, cap)
     prefill(target, tkv, list(prompt[:-1]))
-    prefill(draft, dkv, list(prompt[:-1]))
+    if not shared_kv:
+        prefill(draft, dkv, list(prompt[:-1]))
     x = [int(t) for t in prompt]
     n0 = len(x)
     pending = [x[-1]]
@@ -93,6 +97,8 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
                           vt[0, i + 1:i + 2])
             feed = vt[:, i + 1:i + 2]
         vt[0, 0] = x[-1]
+        if shared_kv:
+            ss_kv_cache_set_len(tkv, [len(x) - 1])   # the verify pass rewrites the draft's K positions
         ss_verify_forward(target, tkv, vt, M, logits)
         d = vt[:, 1:].contiguous()
         if greedy:
@@ -105,26 +111,30 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
         host = torch.cat([na, nx, d[0]]).tolist()   # one device-to-host copy per step
         a, y, dl = host[0], host[1], host[2:]
         ss_kv_cache_rollback(tkv, na, M, n_accepted_host=[a])
-        ss_kv_cache_rollback(dkv, na, K, n_accepted_host=[a])   # a = K leaves the draft cache one row short
+        if not shared_kv:
+            ss_kv_cache_rollback(dkv, na, K, n_accepted_host=[a])   # a = K leaves the draft cache one row short
         x += dl[:a] + [y]
-        pending = [y] if a < K else [dl[K - 1], y]
+        pending = [y] if (a < K or shared_kv) else [dl[K - 1], y]
         accepted.append(a)
         step += 1
     torch.cuda.synchronize()
     loop_s = time.perf_counter() - t0
     tkv.close()
-    dkv.close()
+    if not shared_kv:
+        dkv.close()
     return x[n0:n0 + n_new], {"steps": step, "accepted": accepted, "loop_seconds": loop_s,
                               "generated": len(x) - n0}
 
 
-def _speculative_generate_native(target, draft, prompt, n_new, K, temperature, u_draft, u_accept, max_seq):
+def _speculative_generate_native(target, draft, prompt, n_new, K, temperature, u_draft, u_accept, max_seq, shared_kv=False):
     dev = torch.device("cuda")
     greedy = temperature == 0
     cap = max_seq or (len(prompt) + n_new + K + 2)
-    tkv, dkv = KVCache(target, 1, cap), KVCache(draft, 1, cap)
+    tkv = KVCache(target, 1, cap)
+    dkv = tkv if shared_kv else KVCache(draft, 1, cap)
     prefill(target, tkv, list(prompt[:-1]))
-    prefill(draft, dkv, list(prompt[:-1]))
+    if not shared_kv:
+        prefill(draft, dkv, list(prompt[:-1]))
     buf = StepBuffers(K, target.shape.vocab, int(prompt[-1]), dev)
     ud_all = ua_all = None
     if not greedy:
@@ -143,5 +153,6 @@ def _speculative_generate_native(target, draft, prompt, n_new, K, temperature, u
     torch.cuda.synchronize()
     loop_s = time.perf_counter() - t0
     tkv.close()
-    dkv.close()
+    if not shared_kv:
+        dkv.close()
     return out[:n_new], {"steps": step, "accepted": accepted, "loop_seconds": loop_s, "generated": len(out)}

@@ -125,3 +125,25 @@ def test_sampled_autoregressive_matches_oracle_stream():
     ref = oracle.autoregressive_generate(ot, prompt, 24, 1.0, u)
     # identical unless a uniform falls within float noise of a CDF edge (probability ~1e-5 per token)
     assert got == ref
+
+
+@pytest.mark.parametrize("K,T", [(4, 0.0), (2, 1.0), (8, 1.0)])
+def test_shared_cache_for_an_early_exit_draft_on_gpu(K, T):
+    """One cache for both models (Section 4.4): the early-exit draft works in the leading layers of the
+    target's cache.  Same token stream and accept counts as with two caches (the draft's keys and values
+    are the numbers the target writes for those layers), through one-call steps and call-by-call steps;
+    greedy equals autoregressive greedy."""
+    (ot, od), (gt, gd) = _pair(4, early=True, persistent=True)
+    prompt = si.token_ids(4, "prompt", (24,), 1024).numpy().tolist()
+    n_new = 40
+    ud = si.uniforms(4, "ud", (n_new, K)).numpy()
+    ua = si.uniforms(4, "ua", (n_new, K + 1)).numpy()
+    two, st2 = gen.speculative_generate(gt, gd, prompt, n_new, K, T, ud, ua)
+    one, st1 = gen.speculative_generate(gt, gd, prompt, n_new, K, T, ud, ua, shared_kv=True)
+    calls, st0 = gen.speculative_generate(gt, gd, prompt, n_new, K, T, ud, ua, shared_kv=True, observer=lambda s: None)
+    assert one == two == calls and st1["accepted"] == st2["accepted"] == st0["accepted"]
+    if T == 0.0:
+        assert one == gen.autoregressive_generate(gt, prompt, n_new, 0.0)
+    ref, _ = oracle.speculative_generate(ot, od, prompt, n_new, K, T, ud, ua, shared_kv=True)
+    if T == 0.0:
+        assert one == ref
