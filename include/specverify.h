@@ -106,8 +106,9 @@ int ss_model_destroy(ss_model *model);
 /* Selects how the forward path of `model` is launched.  1 (default wherever the kernel can be
  * co-resident on the device): calls whose rows (batch * M) fit the kernel's LDS activation slab (9
  * rows for bf16 models, 16 for fp32) run as ONE persistent cooperative kernel
- * (one workgroup per compute unit, device-wide barriers between phases, RMSNorm folded into the
- * GEMMs, weight loads of the next phase in flight across each barrier); larger calls always use one
+ * (one workgroup per compute unit, phases ordered by device-wide barriers or by self-validating
+ * activations, RMSNorm folded into the GEMMs, weight loads of the next phase in flight across each
+ * phase boundary); larger calls always use one
  * kernel per phase.  0: one kernel per phase (RMSNorm, QKV GEMM, attention, O projection, gate/up
  * GEMM, down projection ...) for every call.  Both paths produce results within the same tolerance
  * of the method; SS_EINVAL if `on` is set and the persistent kernel is not available on this device. */
@@ -129,7 +130,9 @@ int ss_model_set_persistent_options(ss_model *model, int32_t workgroups, int32_t
  * with a device array len[batch] of current lengths (all 0).
  * Device layout per layer l, sequence b, head h (S = max_seq rounded up to 64):
  *   K[l][b][h][S][hd]           keys, already rotated, one row per position
- *   V[l][b][h][S/64][hd][64]    values, transposed inside blocks of 64 positions */
+ *   V[l][b][h][S/64][hd][64]    values, transposed inside blocks of 64 positions
+ * A model with fewer layers but the same heads and storage type may be run on such a cache: it uses
+ * the leading layers (an early-exit draft sharing the target's cache, Section 4.4). */
 int ss_kv_cache_alloc(const ss_model *model, int32_t batch, int32_t max_seq, ss_kv_cache **out);
 int ss_kv_cache_free(ss_kv_cache *kv);
 size_t ss_kv_cache_bytes(const ss_model *model, int32_t batch, int32_t max_seq);
