@@ -121,6 +121,35 @@ def test_staged_row_statistics_skip_rows_without_changing_the_result(B, K, V):
     assert 0 < sum(na.cpu().tolist()) < B * K     # both early rejections and surviving sequences occur
 
 
+def test_gpu_rejection_step_emits_the_target_distribution():
+    """The guarantee of Section 3, measured on the kernels themselves (no oracle involved): 2^18 sequences
+    share one pair of rows p, q over 8 tokens; each draws d ~ q with the library's sampler, runs the
+    rejection step, and emits d if accepted, else the resampled token.  The histogram of the emitted
+    token must be p (chi-square, 7 degrees of freedom, p-value > 1e-4; the same test rejects q), and the
+    acceptance rate must be 1 - ||p - q||_1 / 2 within four standard deviations."""
+    from scipy import stats
+    B, V, D = 1 << 18, 8, dev()
+    g = torch.Generator().manual_seed(77)
+    p1 = torch.softmax(torch.randn(V, generator=g), 0)
+    q1 = torch.softmax(torch.randn(V, generator=g) * 1.5, 0)
+    p = p1.to(D).repeat(B, 1, 1).repeat(1, 2, 1).contiguous()       # [B, K + 1 = 2, V]: the bonus row is p again
+    q = q1.to(D).repeat(B, 1, 1).contiguous()                        # [B, 1, V]
+    ud = si.uniforms(77, "chi_ud", (B, 1), device=D)
+    ua = si.uniforms(77, "chi_ua", (B, 2), device=D)
+    zf, zi = torch.zeros(1, device=D), torch.zeros(1, dtype=torch.int32, device=D)
+    _, d = sv.ss_speculative_accept(q, zf, zi, ud)                   # K = 0: a plain sample from q per sequence
+    na, nx = sv.ss_speculative_accept(p, q, d[:, None].contiguous(), ua)
+    emitted = torch.where(na == 1, d, nx).cpu().numpy()
+    counts = np.bincount(emitted, minlength=V).astype(np.float64)
+    pe, qe = p1.double().numpy(), q1.double().numpy()
+    chi_p = ((counts - B * pe) ** 2 / (B * pe)).sum()
+    chi_q = ((counts - B * qe) ** 2 / (B * qe)).sum()
+    assert stats.chi2.sf(chi_p, V - 1) > 1e-4
+    assert stats.chi2.sf(chi_q, V - 1) < 1e-12
+    rate, expect = float((na == 1).float().mean()), 1.0 - 0.5 * np.abs(pe - qe).sum()
+    assert abs(rate - expect) < 4.0 * np.sqrt(expect * (1 - expect) / B)
+
+
 def test_greedy_accept_matches_oracle_with_ties():
     B, K, V = 9, 5, 1024
     l = si.normal(31, "l", (B, K + 1, V), 2.0)
