@@ -354,6 +354,13 @@ def main():
     roofline = {"bound": "hbm", "kernel": k_name, "achieved": achieved, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                 "frac": achieved / (HBM_PEAK / 1e9), "traffic": traffic, "algorithmic_bytes_per_launch": k_bytes,
                 "avg_launch_us": k_us}
+    # what a dependency-free read kernel reaches on this machine over a 2 GiB buffer (beyond the last-level cache):
+    # the practical ceiling beside the nominal peak
+    probe_buf = torch.empty(1 << 29, dtype=torch.float32, device=dev).fill_(1.0)
+    stream_GBps = sv.ss_probe_read_bandwidth(probe_buf, iters=20)
+    del probe_buf
+    roofline["read_stream_GBps"] = stream_GBps
+    roofline["frac_of_read_stream"] = achieved / stream_GBps
 
     out = {
         "metric": "verify-pass tokens/s", "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -374,6 +381,9 @@ def main():
         out["standalone_accept"] = standalone_accept(si, sv, torch, dev)
     if args.batched_workload:
         out["batched_workload"] = batched_workload(si, sv, torch, dev, shape, packed, io)
+    for leg in ("layer_pass", "standalone_accept", "batched_workload"):
+        if leg in out and "GBps" in out[leg]:
+            out[leg]["frac_of_read_stream"] = out[leg]["GBps"] / stream_GBps
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(si, torch, shape, packed, io, prompt_len, M)
     if args.copy_calibration:

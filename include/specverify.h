@@ -95,6 +95,18 @@ int ss_device_status(ss_model *model, ss_stream stream, int32_t *status_host);
 int ss_profile_enable(ss_model *model, int32_t on);
 int ss_profile_read(ss_model *model, int32_t n_classes, double *total_ms_host, int64_t *launches_host);
 
+/* Read-stream probe of the device the caller has made current: a plain kernel that reads
+ * buf_dev[0, bytes) once per launch with wide independent loads and keeps nothing.  One untimed
+ * launch, then `iters` launches timed with a HIP event pair on `stream`; *gbps_host receives
+ * bytes * iters / elapsed in GB/s (synchronises `stream`).  It gives the HBM read rate a kernel
+ * with no dependencies reaches on this device, the practical ceiling the verify pass (a weight
+ * stream, Section 2 "memory bandwidth bound") is judged against next to the nominal figure.
+ * buf_dev: dev, 16-byte aligned, bytes a multiple of 16 and >= 1 MiB, contents arbitrary, never
+ * written; take it larger than the last-level cache or the figure is a cache rate.
+ * sink_dev: dev, one uint32 the kernel may write.  iters in [1, 10000]. */
+int ss_probe_read_bandwidth(const void *buf_dev, size_t bytes, int32_t iters, uint32_t *sink_dev, double *gbps_host,
+                            ss_stream stream);
+
 /* ---- model -------------------------------------------------------------------------------
  * Creates a handle over caller-owned weights (which must outlive it) and allocates the
  * model's activation workspace and rotary table on the current device (the only allocations

@@ -25,7 +25,7 @@ EXPORTS = [
     "ss_kv_cache_get_len", "ss_kv_cache_rollback", "ss_verify_forward", "ss_decoder_layers_forward",
     "ss_draft_step", "ss_softmax", "ss_speculative_accept", "ss_speculative_accept_logits",
     "ss_greedy_accept", "ss_profile_enable", "ss_profile_read", "ss_model_set_persistent", "ss_model_set_persistent_options",
-    "ss_speculative_step",
+    "ss_speculative_step", "ss_probe_read_bandwidth",
 ]
 
 PROFILE_CLASSES = ["rmsnorm", "qkv_gemm", "attention", "oproj_gemm", "gateup_gemm", "down_gemm", "head_gemm", "other",
@@ -89,6 +89,7 @@ def lib():
             "ss_model_set_persistent_options": [vp, i32, i32],
             "ss_speculative_step": [vp, vp, vp, vp, i32, C.c_float, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp],
             "ss_profile_read": [vp, i32, vp, vp],
+            "ss_probe_read_bandwidth": [vp, C.c_size_t, i32, vp, vp, vp],
         }
         for name, args in sig.items():
             getattr(L, name).argtypes = args
@@ -331,6 +332,15 @@ def ss_device_status(model: Model, stream=None) -> int:
 
 def ss_model_set_persistent(model: Model, on: bool):
     _check(lib().ss_model_set_persistent(model.handle, int(bool(on))))
+
+
+def ss_probe_read_bandwidth(buf, iters=20, stream=None):
+    """GB/s a dependency-free read kernel reaches over the device tensor `buf` (read once per launch)."""
+    sink = torch.zeros(1, dtype=torch.int32, device=buf.device)
+    out = C.c_double(0.0)
+    _check(lib().ss_probe_read_bandwidth(_dev(buf), buf.numel() * buf.element_size(), int(iters), _dev(sink), C.byref(out),
+                                         _stream(stream)))
+    return out.value
 
 
 def ss_model_set_persistent_options(model: Model, workgroups: int = 0, data_sync: bool = True):

@@ -333,6 +333,34 @@ extern "C" int ss_profile_read(ss_model *m, int32_t n_classes, double *total_ms_
     return SS_OK;
 }
 
+extern "C" int ss_probe_read_bandwidth(const void *buf_dev, size_t bytes, int32_t iters, uint32_t *sink_dev, double *gbps_host,
+                                       ss_stream stream) {
+    if (!buf_dev || !sink_dev || !gbps_host) return fail(SS_EINVAL, "ss_probe_read_bandwidth: NULL argument");
+    if (bytes < ((size_t)1 << 20) || (bytes & 15) || ((uintptr_t)buf_dev & 15) || iters < 1 || iters > 10000)
+        return fail(SS_EINVAL, "ss_probe_read_bandwidth: need a 16-byte aligned buffer of >= 1 MiB in 16-byte units and 1..10000 launches");
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    HIP_TRY(hipEventCreate(&e0));
+    hipError_t err = hipEventCreate(&e1);
+    float ms = 0.f;
+    if (err == hipSuccess) {
+        ss::launch_read_probe(buf_dev, bytes, sink_dev, st);   // untimed first launch
+        err = hipEventRecord(e0, st);
+        for (int i = 0; i < iters && err == hipSuccess; ++i) {
+            ss::launch_read_probe(buf_dev, bytes, sink_dev, st);
+            err = hipGetLastError();
+        }
+        if (err == hipSuccess) err = hipEventRecord(e1, st);
+        if (err == hipSuccess) err = hipEventSynchronize(e1);
+        if (err == hipSuccess) err = hipEventElapsedTime(&ms, e0, e1);
+    }
+    (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (err != hipSuccess) return fail(SS_EHIP, "ss_probe_read_bandwidth: %s", hipGetErrorString(err));
+    *gbps_host = ms > 0.f ? (double)bytes * iters / (ms * 1e-3) / 1e9 : 0.0;
+    return SS_OK;
+}
+
 // ------------------------------------------------------------------------------------------ cache
 
 extern "C" size_t ss_kv_cache_bytes(const ss_model *m, int32_t batch, int32_t max_seq) {

@@ -140,4 +140,27 @@ void launch_kv_append(int dtype, void *kc, void *vc, const void *k, const void *
     else hipLaunchKernelGGL((kv_append_kernel<float>), dim3(n_rows), dim3(256), 0, st, (float *)kc, (float *)vc, (const float *)k, (const float *)v, seq, pos0, H, hd, S);
 }
 
+// Read-stream probe: every lane keeps eight independent 16-byte loads in flight, a wavefront instruction
+// covers 1 KB contiguous, the grid walks the buffer once.  The loads are folded into a word that is stored
+// only if it equals a value the data cannot be arranged to avoid checking, which keeps them alive.
+typedef uint32_t probe_u32x4 __attribute__((ext_vector_type(4)));
+__global__ void __launch_bounds__(256) read_probe_kernel(const probe_u32x4 *__restrict__ src, size_t n16, uint32_t *sink) {
+    constexpr int U = 8;
+    const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (size_t)gridDim.x * blockDim.x;
+    probe_u32x4 acc = {0u, 0u, 0u, 0u};
+    size_t i = tid;
+    for (; i + (U - 1) * stride < n16; i += U * stride) {
+        probe_u32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc ^= v[u];
+    }
+    for (; i < n16; i += stride) acc ^= __builtin_nontemporal_load(src + i);
+    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u) sink[0] = 1u;
+}
+void launch_read_probe(const void *buf, size_t bytes, uint32_t *sink, hipStream_t st) {
+    hipLaunchKernelGGL(read_probe_kernel, dim3(4096), dim3(256), 0, st, (const probe_u32x4 *)buf, bytes / 16, sink);
+}
+
 } // namespace ss

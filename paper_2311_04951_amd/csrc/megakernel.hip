@@ -293,6 +293,8 @@ __device__ __forceinline__ bool grid_wait_qkv_of_head(const MegaCall &P, unsigne
 
 // ---------------------------------------------------------------- non-GEMM phases
 
+template <typename T> __device__ __forceinline__ ActPlanes<T> act_planes(const MegaCall &P, int i);
+
 // Embedding phase: every workgroup takes a slice of the columns of all hidden rows (the way the residual
 // phases own columns), so the gather is one short step for the whole chip and each workgroup has its own
 // partial sums of squares to publish.  Thread t works on hidden row t & 15 and columns (t >> 4) + 16 j of

@@ -67,6 +67,7 @@ void launch_rmsnorm_pack(int dtype, const float *h, const float *gain, int R, in
 // gathers the last row of every sequence: rows b*M + M-1 -> compact rows b (norm + pack)
 void launch_rmsnorm_pack_rows(int dtype, const float *h, const float *gain, int nrows, int row0, int row_stride,
                               int d, float eps, void *act, size_t act_plane, int ld_act, hipStream_t st);
+void launch_read_probe(const void *buf, size_t bytes, uint32_t *sink, hipStream_t st);
 void launch_len_add(int32_t *len, int batch, int delta, hipStream_t st);
 void launch_len_rollback(int32_t *len, const int32_t *n_accepted, int batch, int M, hipStream_t st);
 void launch_kv_append(int dtype, void *kc, void *vc, const void *k, const void *v, int seq, int pos0, int n_rows,

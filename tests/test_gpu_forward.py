@@ -264,3 +264,16 @@ def test_capacity_and_shape_errors_come_from_the_host():
     bad = torch.full((1, 1), shape.vocab + 5, dtype=torch.int32, device=dev())
     sv.ss_verify_forward(gm, gkv, bad, 1, logits=False)
     assert sv.ss_device_status(gm) == 1 and sv.ss_device_status(gm) == 0   # clamped, flagged, cleared
+
+
+def test_read_stream_probe_reports_a_plausible_rate():
+    """The probe reads a 1 GiB buffer (never written: the contents are checked afterwards) at a rate between
+    a tenth of and the whole nominal HBM peak; bad arguments are refused on the host."""
+    buf = torch.full((1 << 28,), 3.0, dtype=torch.float32, device=dev())
+    rate = sv.ss_probe_read_bandwidth(buf, iters=5)
+    assert 800.0 < rate < 8000.0
+    assert float(buf[::4097].min()) == 3.0 and float(buf[-1]) == 3.0
+    with pytest.raises(sv.SpecVerifyError):
+        sv.ss_probe_read_bandwidth(buf[:1024])
+    with pytest.raises(sv.SpecVerifyError):
+        sv.ss_probe_read_bandwidth(buf, iters=0)
