@@ -254,8 +254,11 @@ int ss_greedy_accept(const float *p_logits_dev, const int32_t *draft_tokens_dev,
  * draft_kv == target_kv selects the shared-cache scheme for a draft made of the target's leading
  * layers (any model may run on the leading layers of a deeper cache with the same heads and storage
  * type): the draft's K calls append to the target's cache, the length is set back by K before the
- * verify pass rewrites those positions for every layer, and the feed is always one token.  All *_dev buffers are the caller's
- * device memory; 1 <= K <= 15; both caches hold one sequence.  Errors as in the calls it is made of. */
+ * verify pass rewrites those positions for every layer, and the feed is always one token.
+ * All *_dev buffers are the caller's device memory; 1 <= K <= 15; both caches hold one sequence.
+ * Errors as in the calls it is made of; shapes and the room both caches need for the whole step
+ * (draft: *n_feed + K - 1 rows, target: K + 1) are checked before the first of them runs, so a
+ * refused step leaves both caches as they were. */
 int ss_speculative_step(ss_model *target, ss_kv_cache *target_kv, ss_model *draft, ss_kv_cache *draft_kv,
                         int32_t K, float temperature, int32_t *feed_dev, int32_t *n_feed,
                         const float *u_draft_dev, const float *u_accept_dev, int32_t *verify_tokens_dev,

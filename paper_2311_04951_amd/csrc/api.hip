@@ -930,7 +930,15 @@ extern "C" int ss_speculative_step(ss_model *target, ss_kv_cache *tkv, ss_model 
     if (sample && (!u_draft_dev || !u_accept_dev || !q_rows_dev || !p_dev)) return fail(SS_EINVAL, "ss_speculative_step: sampling needs uniforms, q_rows_dev and p_dev");
     hipStream_t st = (hipStream_t)stream;
     const int V = target->cfg.vocab, M = K + 1;
-    int rc;
+    // everything the calls below would refuse is refused here, before the first of them changes a cache
+    int rc = check_pair(target, tkv, 1, M, "ss_speculative_step (target)");
+    if (rc) return rc;
+    rc = check_pair(draft, dkv, 1, *n_feed, "ss_speculative_step (draft)");
+    if (rc) return rc;
+    const int draft_rows = *n_feed + K - 1;
+    if (dkv->len_ub[0] + draft_rows > dkv->max_seq || dkv->len_ub[0] + draft_rows > draft->cfg.max_pos)
+        return fail(SS_ECAPACITY, "ss_speculative_step: the draft cache at length <= %d has no room for %d rows (max_seq %d, max_pos %d)",
+                    dkv->len_ub[0], draft_rows, dkv->max_seq, draft->cfg.max_pos);
     for (int i = 0; i < K; ++i) {
         rc = ss_draft_step(draft, dkv, i ? vt + i : feed_dev, 1, i ? 1 : *n_feed, temperature, sample ? u_draft_dev + i : nullptr,
                            sample ? q_rows_dev + (size_t)i * V : nullptr, V, vt + i + 1, stream);

@@ -147,3 +147,47 @@ def test_shared_cache_for_an_early_exit_draft_on_gpu(K, T):
     ref, _ = oracle.speculative_generate(ot, od, prompt, n_new, K, T, ud, ua, shared_kv=True)
     if T == 0.0:
         assert one == ref
+
+
+def test_native_step_refuses_bad_requests_before_touching_a_cache():
+    """A step that cannot finish (no room for the draft's rows, no room for the verify rows, K out of range,
+    models with different vocabularies) is refused up front: error code set, cache lengths unchanged."""
+    (_, _), (gt, gd) = _pair(5, early=True, persistent=True)
+    K, V = 4, si.TINY_TARGET.vocab
+    prompt = si.token_ids(5, "prompt", (12,), 1024)
+    ud, ua = si.uniforms(5, "ud", (K,)).to(dev()), si.uniforms(5, "ua", (K + 1,)).to(dev())
+
+    def caches(t_seq, d_seq):
+        tkv, dkv = sv.KVCache(gt, 1, t_seq), sv.KVCache(gd, 1, d_seq)
+        tok = prompt[None, :11].to(torch.int32).to(dev()).contiguous()
+        sv.ss_verify_forward(gt, tkv, tok, 11, logits=False)
+        sv.ss_verify_forward(gd, dkv, tok, 11, logits=False)
+        return tkv, dkv
+
+    buf = sv.StepBuffers(K, V, int(prompt[11]), dev())
+    # the draft needs 11 + 4 positions, its cache has 13: fails at what would have been the third draft step
+    tkv, dkv = caches(64, 13)
+    with pytest.raises(sv.SpecVerifyError) as e:
+        sv.ss_speculative_step(gt, tkv, gd, dkv, buf, 1.0, ud, ua)
+    assert e.value.code == sv.SS_ECAPACITY
+    assert sv.ss_kv_cache_get_len(tkv).tolist() == [11] and sv.ss_kv_cache_get_len(dkv).tolist() == [11]
+    # the target needs 11 + 5 positions, its cache has 15
+    tkv, dkv = caches(15, 64)
+    with pytest.raises(sv.SpecVerifyError) as e:
+        sv.ss_speculative_step(gt, tkv, gd, dkv, buf, 1.0, ud, ua)
+    assert e.value.code == sv.SS_ECAPACITY
+    assert sv.ss_kv_cache_get_len(tkv).tolist() == [11] and sv.ss_kv_cache_get_len(dkv).tolist() == [11]
+    # K beyond the 16-row limit of a verify pass
+    tkv, dkv = caches(64, 64)
+    big = sv.StepBuffers(16, V, int(prompt[11]), dev())
+    with pytest.raises(sv.SpecVerifyError) as e:
+        sv.ss_speculative_step(gt, tkv, gd, dkv, big, 0.0)
+    assert e.value.code == sv.SS_EINVAL
+    # sampling without uniforms
+    with pytest.raises(sv.SpecVerifyError) as e:
+        sv.ss_speculative_step(gt, tkv, gd, dkv, buf, 1.0)
+    assert e.value.code == sv.SS_EINVAL
+    assert sv.ss_kv_cache_get_len(tkv).tolist() == [11] and sv.ss_kv_cache_get_len(dkv).tolist() == [11]
+    # and the same caches then take a good step
+    a, y, d = sv.ss_speculative_step(gt, tkv, gd, dkv, buf, 1.0, ud, ua)
+    assert 0 <= a <= K and 0 <= y < V and sv.ss_kv_cache_get_len(tkv).tolist() == [11 + a + 1]
