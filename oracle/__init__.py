@@ -59,6 +59,9 @@ def lib():
         L.orc_sample_residual.argtypes = [vp, vp, i32, f32]
         L.orc_speculative_accept.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp]
         L.orc_greedy_accept.argtypes = [vp, vp, i32, i32, i32, vp, vp]
+        L.orc_quantize_rows_int8.argtypes = [vp, i32, i32, i32, vp, vp]
+        L.orc_linear_w8.argtypes = [vp, vp, vp, i32, i32, vp]
+        L.orc_model_set_scales.argtypes = [vp, i32, C.POINTER(vp)]
         L.orc_f32_to_bf16.restype = C.c_uint16
         L.orc_f32_to_bf16.argtypes = [f32]
         L.orc_bf16_to_f32.restype = f32
@@ -108,6 +111,24 @@ def linear(W, x, is_bf16=False):
     x = _f32(x)
     y = np.empty(W.shape[0], dtype=np.float32)
     lib().orc_linear(_p(W), int(is_bf16), _p(x), W.shape[0], W.shape[1], _p(y))
+    return y
+
+
+def quantize_rows_int8(W, is_bf16=False):
+    """Weight-only int8 of a matrix [N, K] in the storage type -> (q int8 [N, K], scale fp32 [N])."""
+    Ws = _storage(W, is_bf16)
+    N, K = Ws.shape
+    q = np.empty((N, K), dtype=np.int8)
+    s = np.empty(N, dtype=np.float32)
+    lib().orc_quantize_rows_int8(_p(Ws), int(is_bf16), N, K, _p(q), _p(s))
+    return q, s
+
+
+def linear_w8(q, scale, x):
+    q = np.ascontiguousarray(q, dtype=np.int8)
+    scale, x = _f32(scale), _f32(x)
+    y = np.empty(q.shape[0], dtype=np.float32)
+    lib().orc_linear_w8(_p(q), _p(scale), _p(x), q.shape[0], q.shape[1], _p(y))
     return y
 
 
@@ -177,8 +198,11 @@ class Model:
     vocab, rope_base, rms_eps, dtype ("bf16" | "f32"); `weights` is the dict layout of
     seeded_inputs.decoder_weights (torch tensors or ndarrays; bf16 as uint16 bits)."""
 
-    def __init__(self, shape, weights):
+    def __init__(self, shape, weights, int8_weights=False):
+        """int8_weights: the seven matrices of every layer and the LM head are quantised row-wise
+        (quantize_rows_int8) from the given weights; embedding, gains and cache keep the storage type."""
         self.shape = shape
+        self.int8_weights = bool(int8_weights)
         self.is_bf16 = shape.dtype == "bf16"
         L = lib()
         self._keep = []
@@ -189,12 +213,23 @@ class Model:
             ws = [self._hold(_storage(lw[n], self.is_bf16)) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd")]
             gs = [self._hold(_f32(lw[n].detach().cpu().numpy() if hasattr(lw[n], "detach") else lw[n]))
                   for n in ("g1", "g2")]
+            if self.int8_weights:
+                qs = [quantize_rows_int8(w, self.is_bf16) for w in ws]
+                ws = [self._hold(q) for q, _ in qs]
+                sc = [self._hold(s_) for _, s_ in qs]
             L.orc_model_set_layer(self.h, l, *[_p(a) for a in ws + gs])
+            if self.int8_weights:
+                L.orc_model_set_scales(self.h, l, (C.c_void_p * 7)(*[a.ctypes.data for a in sc]))
         if weights.get("embed") is not None:
             gf = weights["gf"]
             gf = self._hold(_f32(gf.detach().cpu().numpy() if hasattr(gf, "detach") else gf))
             emb = self._hold(_storage(weights["embed"], self.is_bf16))
             head = self._hold(_storage(weights["lm_head"], self.is_bf16))
+            if self.int8_weights:
+                hq, hs = quantize_rows_int8(head, self.is_bf16)
+                head = self._hold(hq)
+                self._hold(hs)
+                L.orc_model_set_scales(self.h, -1, (C.c_void_p * 1)(hs.ctypes.data))
             L.orc_model_set_io(self.h, _p(emb), _p(gf), _p(head))
 
     def _hold(self, a):

@@ -14,6 +14,9 @@
  *     min(1, p/q); on the first rejection resample from norm(max(0, p - q)); bonus token from
  *     the last row when nothing was rejected).
  *   - Section 4.4: two caches of different size; truncation of the stale tail is a length write.
+ *   - Sections 2 and 3 assume a quantised model without fixing the precision.  The reading taken here:
+ *     weight-only int8 with one scale per output row (orc_quantize_rows_int8), activations untouched;
+ *     a quantised matrix stands for the real numbers scale_n * q[n][k].
  *
  * The paper names no architecture beyond a Llama-2 model id (Section 4.1), so the decoder is the
  * Llama-style one of the synthetic workloads: RMSNorm -> QKV -> rotary embedding (split-half
@@ -97,6 +100,43 @@ void orc_linear(const void *W, int is_bf16, const float *x, int N, int K, float 
     }
 }
 
+/* Weight-only int8 (the reading of the paper's "quantized model", Sections 2 and 3): row n of a matrix
+ * becomes q[n][k] in [-127, 127] and one fp32 scale, s_n = fl32(max_k |w[n][k]| / 127) (1 for an all-zero
+ * row) and q[n][k] = nearest integer (ties to even) of fl32(w[n][k] / s_n); every step is a single fp32
+ * operation, so any IEEE implementation produces the same bytes.  W is in the storage type. */
+void orc_quantize_rows_int8(const void *W, int is_bf16, int N, int K, int8_t *q, float *scale) {
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        size_t base = (size_t)n * (size_t)K;
+        float amax = 0.0f;
+        for (int k = 0; k < K; ++k) {
+            float a = fabsf((float)st_get(W, is_bf16, base + k));
+            if (a > amax) amax = a;
+        }
+        volatile float sv = amax > 0.0f ? amax / 127.0f : 1.0f; /* volatile: one rounding to fp32, no wider temporaries */
+        float sc = sv;
+        scale[n] = sc;
+        for (int k = 0; k < K; ++k) {
+            volatile float r = (float)st_get(W, is_bf16, base + k) / sc;
+            float t = rintf(r); /* default rounding mode: nearest, ties to even */
+            if (t > 127.0f) t = 127.0f;
+            if (t < -127.0f) t = -127.0f;
+            q[base + k] = (int8_t)t;
+        }
+    }
+}
+
+/* y_n = scale_n * sum_k q[n][k] x_k: the linear layer of a weight-only int8 matrix */
+void orc_linear_w8(const int8_t *q, const float *scale, const float *x, int N, int K, float *y) {
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        double acc = 0.0;
+        size_t base = (size_t)n * (size_t)K;
+        for (int k = 0; k < K; ++k) acc += (double)q[base + k] * (double)x[k];
+        y[n] = (float)((double)scale[n] * acc);
+    }
+}
+
 /* Rotary embedding of one head vector at absolute position pos, split-half pairing:
  * (v_j, v_{j+hd/2}) rotated by angle pos * base^(-2j/hd), j = 0..hd/2-1. */
 void orc_rope(float *v, int hd, int64_t pos, double base) {
@@ -137,6 +177,7 @@ int orc_argmax(const float *x, int V) {
 typedef struct {
     const void *wq, *wk, *wv, *wo, *wg, *wu, *wd;
     const float *g1, *g2;
+    const float *sq, *sk, *sv, *so, *sg, *su, *sd; /* row scales: non-NULL = the matrix is int8 */
 } orc_layer;
 
 typedef struct {
@@ -145,6 +186,7 @@ typedef struct {
     orc_layer *layers;
     const void *embed, *lm_head;
     const float *gf;
+    const float *s_head; /* row scales of an int8 LM head, or NULL */
 } orc_model;
 
 /* KV cache of ONE sequence (Sections 2, 4.2): per layer, keys (already rotated) and values of
@@ -175,6 +217,20 @@ void orc_model_set_layer(orc_model *m, int l, const void *wq, const void *wk, co
 
 void orc_model_set_io(orc_model *m, const void *embed, const float *gf, const void *lm_head) {
     m->embed = embed; m->gf = gf; m->lm_head = lm_head;
+}
+
+/* Declares the seven matrices of layer l (and, with l == -1, the LM head through s[0]) to be int8 with
+ * these row scales; the matrix pointers given to orc_model_set_layer / orc_model_set_io then point to int8. */
+void orc_model_set_scales(orc_model *m, int l, const float *const *s) {
+    if (l < 0) { m->s_head = s[0]; return; }
+    orc_layer *L = &m->layers[l];
+    L->sq = s[0]; L->sk = s[1]; L->sv = s[2]; L->so = s[3]; L->sg = s[4]; L->su = s[5]; L->sd = s[6];
+}
+
+/* one linear layer of the model: int8 with row scales when the scales are there, else the storage type */
+static void lin(const void *W, const float *scale, int is_bf16, const float *x, int N, int K, float *y) {
+    if (scale) orc_linear_w8((const int8_t *)W, scale, x, N, K, y);
+    else orc_linear(W, is_bf16, x, N, K, y);
 }
 
 void orc_model_free(orc_model *m) {
@@ -280,9 +336,9 @@ int orc_layers_forward(const orc_model *m, orc_kv *c, float *h, int M) {
         for (int i = 0; i < M; ++i) {
             int pos = c->len + i;
             orc_rmsnorm(h + (size_t)i * d, L->g1, d, m->rms_eps, a);
-            orc_linear(L->wq, bf, a, W, d, q + (size_t)i * W);
-            orc_linear(L->wk, bf, a, W, d, kk);
-            orc_linear(L->wv, bf, a, W, d, vv);
+            lin(L->wq, L->sq, bf, a, W, d, q + (size_t)i * W);
+            lin(L->wk, L->sk, bf, a, W, d, kk);
+            lin(L->wv, L->sv, bf, a, W, d, vv);
             for (int hh = 0; hh < H; ++hh) {
                 orc_rope(q + (size_t)i * W + hh * hd, hd, pos, m->rope_base);
                 orc_rope(kk + hh * hd, hd, pos, m->rope_base);
@@ -296,13 +352,13 @@ int orc_layers_forward(const orc_model *m, orc_kv *c, float *h, int M) {
         for (int i = 0; i < M; ++i) {
             float *hi = h + (size_t)i * d;
             attention_row(m, c, l, q + (size_t)i * W, c->len + i, o);
-            orc_linear(L->wo, bf, o, d, W, t);
+            lin(L->wo, L->so, bf, o, d, W, t);
             for (int e = 0; e < d; ++e) hi[e] = hi[e] + t[e];
             orc_rmsnorm(hi, L->g2, d, m->rms_eps, a);
-            orc_linear(L->wg, bf, a, F, d, gg);
-            orc_linear(L->wu, bf, a, F, d, uu);
+            lin(L->wg, L->sg, bf, a, F, d, gg);
+            lin(L->wu, L->su, bf, a, F, d, uu);
             for (int e = 0; e < F; ++e) gg[e] = (float)(silu((double)gg[e]) * (double)uu[e]);
-            orc_linear(L->wd, bf, gg, d, F, t);
+            lin(L->wd, L->sd, bf, gg, d, F, t);
             for (int e = 0; e < d; ++e) hi[e] = hi[e] + t[e];
         }
     }
@@ -326,7 +382,7 @@ void orc_head(const orc_model *m, const float *h, int M, float *logits) {
     float *a = (float *)malloc(sizeof(float) * (size_t)m->d_model);
     for (int i = 0; i < M; ++i) {
         orc_rmsnorm(h + (size_t)i * m->d_model, m->gf, m->d_model, m->rms_eps, a);
-        orc_linear(m->lm_head, m->is_bf16, a, m->vocab, m->d_model, logits + (size_t)i * m->vocab);
+        lin(m->lm_head, m->s_head, m->is_bf16, a, m->vocab, m->d_model, logits + (size_t)i * m->vocab);
     }
     free(a);
 }
