@@ -52,6 +52,12 @@ typedef struct {
     int32_t dtype;    /* SS_DTYPE_F32 | SS_DTYPE_BF16 */
     int32_t max_rows; /* largest batch * M any call on this model will pass */
     int32_t max_pos;  /* rotary table length: positions 0..max_pos-1 */
+    int32_t weight_int8; /* 0: matrices in the storage type.  1: the four matrices of every layer and the
+                          * LM head are int8 with one fp32 scale per output row (the quantised model that
+                          * Sections 2 and 3 assume; see ss_quantize_rows_int8).  Needs dtype bf16, max_rows
+                          * <= 16, and d_model, n_heads*head_dim and d_ff multiples of 16.  The embedding,
+                          * the gains and the KV cache keep the storage type; such a model runs with one
+                          * launch per phase (the persistent kernel does not take int8 matrices). */
 } ss_model_cfg;
 
 /* One layer's weights, dev pointers, row-major [out_features][in_features] in the storage type:
@@ -63,13 +69,16 @@ typedef struct {
 typedef struct {
     const void *wqkv, *wo, *wgu, *wd;
     const float *g1, *g2;
+    const float *sqkv, *so, *sgu, *sd; /* weight_int8 only: dev fp32 row scales [3*H*hd], [d], [2*F], [d]; the
+                                        * matrices above are then int8 with the same shapes.  Else ignored. */
 } ss_layer_weights;
 
 typedef struct {
     const void *embed;              /* dev [vocab][d], storage type */
     const ss_layer_weights *layers; /* host array [n_layers] of dev pointers */
     const float *gf;                /* dev [d] fp32 final RMSNorm gain */
-    const void *lm_head;            /* dev [vocab][d], storage type */
+    const void *lm_head;            /* dev [vocab][d], storage type (int8 with weight_int8) */
+    const float *s_head;            /* weight_int8 only: dev fp32 [vocab] row scales of lm_head */
 } ss_weights;
 
 typedef struct ss_model ss_model;
@@ -94,6 +103,15 @@ int ss_device_status(ss_model *model, ss_stream stream, int32_t *status_host);
  * little, so timed throughput runs keep it off. */
 int ss_profile_enable(ss_model *model, int32_t on);
 int ss_profile_read(ss_model *model, int32_t n_classes, double *total_ms_host, int64_t *launches_host);
+
+/* Weight-only int8 of a matrix w_dev [rows][K] held in storage type `dtype` (the reading taken of the
+ * quantised model Sections 2 and 3 assume; the precision is not fixed there): per row n,
+ * scale_dev[n] = fl32(max_k |w[n][k]| / 127) (1 for an all-zero row) and q_dev[n][k] = the nearest
+ * integer, ties to even, of fl32(w[n][k] / scale_dev[n]), in [-127, 127].  The row then stands for the
+ * real numbers scale[n] * q[n][k].  q_dev: dev int8 [rows][K]; scale_dev: dev fp32 [rows]; both the
+ * caller's.  Enqueued on `stream`, no host synchronisation.  rows, K >= 1. */
+int ss_quantize_rows_int8(const void *w_dev, int32_t dtype, int64_t rows, int64_t K, int8_t *q_dev, float *scale_dev,
+                          ss_stream stream);
 
 /* Read-stream probe of the device the caller has made current: a plain kernel that reads
  * buf_dev[0, bytes) once per launch with wide independent loads and keeps nothing.  One untimed

@@ -25,7 +25,7 @@ EXPORTS = [
     "ss_kv_cache_get_len", "ss_kv_cache_rollback", "ss_verify_forward", "ss_decoder_layers_forward",
     "ss_draft_step", "ss_softmax", "ss_speculative_accept", "ss_speculative_accept_logits",
     "ss_greedy_accept", "ss_profile_enable", "ss_profile_read", "ss_model_set_persistent", "ss_model_set_persistent_options",
-    "ss_speculative_step", "ss_probe_read_bandwidth",
+    "ss_speculative_step", "ss_probe_read_bandwidth", "ss_quantize_rows_int8",
 ]
 
 PROFILE_CLASSES = ["rmsnorm", "qkv_gemm", "attention", "oproj_gemm", "gateup_gemm", "down_gemm", "head_gemm", "other",
@@ -41,15 +41,16 @@ class SpecVerifyError(RuntimeError):
 class _Cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "head_dim", "d_ff", "vocab")] + \
                [("rope_base", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int32),
-                ("max_rows", C.c_int32), ("max_pos", C.c_int32)]
+                ("max_rows", C.c_int32), ("max_pos", C.c_int32), ("weight_int8", C.c_int32)]
 
 
 class _LayerW(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("wqkv", "wo", "wgu", "wd", "g1", "g2")]
+    _fields_ = [(n, C.c_void_p) for n in ("wqkv", "wo", "wgu", "wd", "g1", "g2", "sqkv", "so", "sgu", "sd")]
 
 
 class _Weights(C.Structure):
-    _fields_ = [("embed", C.c_void_p), ("layers", C.POINTER(_LayerW)), ("gf", C.c_void_p), ("lm_head", C.c_void_p)]
+    _fields_ = [("embed", C.c_void_p), ("layers", C.POINTER(_LayerW)), ("gf", C.c_void_p), ("lm_head", C.c_void_p),
+                ("s_head", C.c_void_p)]
 
 
 _lib = None
@@ -90,6 +91,7 @@ def lib():
             "ss_speculative_step": [vp, vp, vp, vp, i32, C.c_float, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp],
             "ss_profile_read": [vp, i32, vp, vp],
             "ss_probe_read_bandwidth": [vp, C.c_size_t, i32, vp, vp, vp],
+            "ss_quantize_rows_int8": [vp, i32, i64, i64, vp, vp, vp],
         }
         for name, args in sig.items():
             getattr(L, name).argtypes = args
@@ -132,10 +134,14 @@ class Model:
     rope_base, rms_eps, dtype ("bf16" | "f32"); `weights` is a dict
     {embed, layers: [{wq, wk, wv, wo, wg, wu, wd, g1, g2}], gf, lm_head} of device tensors.  Packing
     q|k|v and gate|up into the fused matrices the library streams is a one-off copy done here
-    (memory plumbing; pass `packed_layers` = [{wqkv, wo, wgu, wd, g1, g2}] to skip it)."""
+    (memory plumbing; pass `packed_layers` = [{wqkv, wo, wgu, wd, g1, g2}] to skip it).
+    int8_weights: the library quantises the packed matrices and the LM head row by row
+    (ss_quantize_rows_int8) and the model streams the int8 copies; packed layers that already carry
+    int8 matrices with their scales ({..., sqkv, so, sgu, sd}) and weights["s_head"] are taken as they are."""
 
-    def __init__(self, shape, weights=None, max_rows=16, max_pos=4096, packed_layers=None):
+    def __init__(self, shape, weights=None, max_rows=16, max_pos=4096, packed_layers=None, int8_weights=False):
         self.shape = shape
+        self.int8_weights = bool(int8_weights)
         st = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
         if packed_layers is None:
             packed_layers = []
@@ -145,22 +151,39 @@ class Model:
                     "wo": lw["wo"].contiguous(),
                     "wgu": torch.cat([lw["wg"], lw["wu"]], 0).contiguous(),
                     "wd": lw["wd"].contiguous(), "g1": lw["g1"].contiguous(), "g2": lw["g2"].contiguous()})
-        self.layers = packed_layers
         self.embed = weights.get("embed") if weights else None
         self.gf = weights.get("gf") if weights else None
         self.lm_head = weights.get("lm_head") if weights else None
+        self.s_head = weights.get("s_head") if weights else None
+        wt = st
+        if self.int8_weights:
+            wt = torch.int8
+            quantised = []
+            for pl in packed_layers:
+                if pl["wqkv"].dtype == torch.int8:
+                    quantised.append(pl)
+                    continue
+                ql = {"g1": pl["g1"], "g2": pl["g2"]}
+                for n, sn in (("wqkv", "sqkv"), ("wo", "so"), ("wgu", "sgu"), ("wd", "sd")):
+                    ql[n], ql[sn] = ss_quantize_rows_int8(pl[n])
+                quantised.append(ql)
+            packed_layers = quantised
+            if self.lm_head is not None and self.lm_head.dtype != torch.int8:
+                self.lm_head, self.s_head = ss_quantize_rows_int8(self.lm_head)
+        self.layers = packed_layers
         arr = (_LayerW * max(1, len(packed_layers)))()
         for i, pl in enumerate(packed_layers):
             for n in ("wqkv", "wo", "wgu", "wd"):
-                setattr(arr[i], n, _dev(pl[n], st).value)
-            for n in ("g1", "g2"):
+                setattr(arr[i], n, _dev(pl[n], wt).value)
+            for n in ("g1", "g2") + (("sqkv", "so", "sgu", "sd") if self.int8_weights else ()):
                 setattr(arr[i], n, _dev(pl[n], torch.float32).value)
         w = _Weights(_dev(self.embed, st if self.embed is not None else None), arr,
                      _dev(self.gf, torch.float32 if self.gf is not None else None),
-                     _dev(self.lm_head, st if self.lm_head is not None else None))
+                     _dev(self.lm_head, wt if self.lm_head is not None else None),
+                     _dev(self.s_head, torch.float32 if self.s_head is not None else None))
         cfg = _Cfg(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ff, shape.vocab,
                    shape.rope_base, shape.rms_eps, SS_DTYPE_BF16 if shape.dtype == "bf16" else SS_DTYPE_F32,
-                   max_rows, max_pos)
+                   max_rows, max_pos, int(self.int8_weights))
         h = C.c_void_p()
         _check(lib().ss_model_create(C.byref(cfg), C.byref(w), C.byref(h)))
         self.handle = h
@@ -332,6 +355,17 @@ def ss_device_status(model: Model, stream=None) -> int:
 
 def ss_model_set_persistent(model: Model, on: bool):
     _check(lib().ss_model_set_persistent(model.handle, int(bool(on))))
+
+
+def ss_quantize_rows_int8(w, stream=None):
+    """Row-wise int8 of a device matrix [rows, K] (fp32 or bf16) -> (q int8 [rows, K], scale fp32 [rows])."""
+    if w.dim() != 2 or w.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("expected a 2-d fp32 or bf16 matrix")
+    q = torch.empty(w.shape, dtype=torch.int8, device=w.device)
+    s = torch.empty(w.shape[0], dtype=torch.float32, device=w.device)
+    _check(lib().ss_quantize_rows_int8(_dev(w), SS_DTYPE_BF16 if w.dtype == torch.bfloat16 else SS_DTYPE_F32, w.shape[0], w.shape[1],
+                                       _dev(q), _dev(s), _stream(stream)))
+    return q, s
 
 
 def ss_probe_read_bandwidth(buf, iters=20, stream=None):

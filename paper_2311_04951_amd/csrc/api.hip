@@ -48,6 +48,7 @@ struct ss_model {
     std::vector<ss_layer_weights> layers;
     const void *embed, *lm_head;
     const float *gf;
+    const float *s_head = nullptr; // row scales of an int8 LM head
     int planes, esz, W; // activation planes, storage element size, H*hd
     int R16;            // max_rows rounded up to 16
     float *h;           // [max_rows][d] residual stream
@@ -157,6 +158,15 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
     for (int l = 0; l < c.n_layers; ++l) {
         const ss_layer_weights &L = w->layers[l];
         if (!L.wqkv || !L.wo || !L.wgu || !L.wd || !L.g1 || !L.g2) return fail(SS_EINVAL, "layer %d has a NULL weight", l);
+        if (c.weight_int8 && (!L.sqkv || !L.so || !L.sgu || !L.sd)) return fail(SS_EINVAL, "layer %d of an int8 model has a NULL scale vector", l);
+    }
+    if (c.weight_int8) {
+        if (c.weight_int8 != 1) return fail(SS_EINVAL, "weight_int8 must be 0 or 1");
+        if (c.dtype != SS_DTYPE_BF16) return fail(SS_EINVAL, "int8 weights need bf16 storage for activations and cache");
+        if (c.max_rows > 16) return fail(SS_EINVAL, "int8 weights: calls of at most 16 rows (max_rows %d)", c.max_rows);
+        if (c.d_model % 16 || (c.n_heads * c.head_dim) % 16 || c.d_ff % 16)
+            return fail(SS_EINVAL, "int8 weights: d_model, n_heads*head_dim and d_ff must be multiples of 16");
+        if (w->lm_head && !w->s_head) return fail(SS_EINVAL, "int8 LM head without a scale vector");
     }
     ss_model *m = new ss_model();
     m->cfg = c;
@@ -164,6 +174,7 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
     m->embed = w->embed;
     m->lm_head = w->lm_head;
     m->gf = w->gf;
+    m->s_head = c.weight_int8 ? w->s_head : nullptr;
     m->planes = c.dtype == SS_DTYPE_BF16 ? 2 : 1;
     m->esz = c.dtype == SS_DTYPE_BF16 ? 2 : 4;
     m->W = c.n_heads * c.head_dim;
@@ -200,7 +211,7 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
     {
         int dev = 0;
         (void)hipGetDevice(&dev);
-        m->mega_G = m->mega_G_max = mega_grid(c.dtype, dev);
+        m->mega_G = m->mega_G_max = c.weight_int8 ? 0 : mega_grid(c.dtype, dev); // the persistent kernel streams storage-type matrices only
         m->mega_rows = mega_max_rows(c.dtype);
         if (m->mega_G > 0 && c.n_layers >= 0) {
             std::vector<MegaPhase> prog;
@@ -331,6 +342,15 @@ extern "C" int ss_profile_read(ss_model *m, int32_t n_classes, double *total_ms_
     }
     m->ev_used = 0;
     return SS_OK;
+}
+
+extern "C" int ss_quantize_rows_int8(const void *w_dev, int32_t dtype, int64_t rows, int64_t K, int8_t *q_dev, float *scale_dev,
+                                     ss_stream stream) {
+    if (!w_dev || !q_dev || !scale_dev) return fail(SS_EINVAL, "ss_quantize_rows_int8: NULL argument");
+    if (dtype != SS_DTYPE_F32 && dtype != SS_DTYPE_BF16) return fail(SS_EINVAL, "ss_quantize_rows_int8: dtype must be f32 or bf16");
+    if (rows < 1 || K < 1 || rows > 0x7fffffffLL) return fail(SS_EINVAL, "ss_quantize_rows_int8: rows %lld, K %lld out of range", (long long)rows, (long long)K);
+    launch_quantize_rows_int8(dtype, w_dev, rows, K, q_dev, scale_dev, (hipStream_t)stream);
+    return check_launch();
 }
 
 extern "C" int ss_probe_read_bandwidth(const void *buf_dev, size_t bytes, int32_t iters, uint32_t *sink_dev, double *gbps_host,
@@ -499,7 +519,7 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
         }
         GemmArgs g{};
         g.splitk_ws = m->splitk_ws; g.splitk_ws_bytes = m->splitk_ws_bytes;
-        g.W = L.wqkv; g.N = 3 * W; g.K = d;
+        g.W = L.wqkv; g.N = 3 * W; g.K = d; g.wscale = c.weight_int8 ? L.sqkv : nullptr;
         g.act = m->act_a; g.act_plane = pl * d; g.ld_act = d; g.R = R;
         g.act_out = m->act_q; g.act_out_plane = pl * W; g.ld_act_out = W;
         g.H = c.n_heads; g.hd = c.head_dim; g.M = M; g.S = kv->S; g.max_pos = c.max_pos;
@@ -524,7 +544,7 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
 
         GemmArgs o{};
         o.splitk_ws = m->splitk_ws; o.splitk_ws_bytes = m->splitk_ws_bytes;
-        o.W = L.wo; o.N = d; o.K = W;
+        o.W = L.wo; o.N = d; o.K = W; o.wscale = c.weight_int8 ? L.so : nullptr;
         o.act = m->act_o; o.act_plane = pl * W; o.ld_act = W; o.R = R;
         o.out = m->h; o.resid = m->h; o.ldo = d;
         {
@@ -537,7 +557,7 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
         }
         GemmArgs u{};
         u.splitk_ws = m->splitk_ws; u.splitk_ws_bytes = m->splitk_ws_bytes;
-        u.W = L.wgu; u.N = F; u.K = d;
+        u.W = L.wgu; u.N = F; u.K = d; u.wscale = c.weight_int8 ? L.sgu : nullptr;
         u.act = m->act_a; u.act_plane = pl * d; u.ld_act = d; u.R = R;
         u.act_out = m->act_z; u.act_out_plane = pl * F; u.ld_act_out = F;
         {
@@ -547,7 +567,7 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
 
         GemmArgs dn{};
         dn.splitk_ws = m->splitk_ws; dn.splitk_ws_bytes = m->splitk_ws_bytes;
-        dn.W = L.wd; dn.N = d; dn.K = F;
+        dn.W = L.wd; dn.N = d; dn.K = F; dn.wscale = c.weight_int8 ? L.sd : nullptr;
         dn.act = m->act_z; dn.act_plane = pl * F; dn.ld_act = F; dn.R = R;
         dn.out = m->h; dn.resid = m->h; dn.ldo = d;
         {
@@ -569,7 +589,7 @@ static void run_head(ss_model *m, int nrows, int row0, int stride, float *logits
     }
     ProfScope ps(m, PT_HEAD, st);
     GemmArgs g{};
-    g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model;
+    g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model; g.wscale = m->s_head;
     g.act = m->act_a; g.act_plane = pl * c.d_model; g.ld_act = c.d_model; g.R = nrows;
     g.out = logits; g.ldo = c.vocab;
     launch_gemm(c.dtype, EPI_STORE, g, st);

@@ -140,6 +140,36 @@ void launch_kv_append(int dtype, void *kc, void *vc, const void *k, const void *
     else hipLaunchKernelGGL((kv_append_kernel<float>), dim3(n_rows), dim3(256), 0, st, (float *)kc, (float *)vc, (const float *)k, (const float *)v, seq, pos0, H, hd, S);
 }
 
+// Row-wise int8 quantisation (one workgroup per row).  Every step is one IEEE fp32 operation (maximum of
+// absolute values, a correctly rounded division by 127, a correctly rounded division by the scale, round to
+// nearest even), so the bytes do not depend on how the row is split over threads.
+template <typename T>
+__global__ void __launch_bounds__(256) quantize_rows_int8_kernel(const T *__restrict__ W, long long K, int8_t *__restrict__ q, float *__restrict__ scale) {
+    __shared__ float red[256];
+    const size_t base = (size_t)blockIdx.x * (size_t)K;
+    float amax = 0.f;
+    for (long long k = threadIdx.x; k < K; k += 256) amax = fmaxf(amax, fabsf(to_f32(W[base + k])));
+    red[threadIdx.x] = amax;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + s]);
+        __syncthreads();
+    }
+    amax = red[0];
+    const float sc = amax > 0.f ? __fdiv_rn(amax, 127.0f) : 1.0f;
+    if (threadIdx.x == 0) scale[blockIdx.x] = sc;
+    for (long long k = threadIdx.x; k < K; k += 256) {
+        float t = rintf(__fdiv_rn(to_f32(W[base + k]), sc));
+        t = fminf(fmaxf(t, -127.0f), 127.0f);
+        q[base + k] = (int8_t)(int)t;
+    }
+}
+void launch_quantize_rows_int8(int dtype, const void *W, long long rows, long long K, int8_t *q, float *scale, hipStream_t st) {
+    if (rows <= 0) return;
+    if (dtype) hipLaunchKernelGGL((quantize_rows_int8_kernel<bf16_t>), dim3((unsigned)rows), dim3(256), 0, st, (const bf16_t *)W, K, q, scale);
+    else hipLaunchKernelGGL((quantize_rows_int8_kernel<float>), dim3((unsigned)rows), dim3(256), 0, st, (const float *)W, K, q, scale);
+}
+
 // Read-stream probe: every lane keeps eight independent 16-byte loads in flight, a wavefront instruction
 // covers 1 KB contiguous, the grid walks the buffer once.  The loads are folded into a word that is stored
 // only if it equals a value the data cannot be arranged to avoid checking, which keeps them alive.

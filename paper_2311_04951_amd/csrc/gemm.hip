@@ -212,6 +212,101 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(GemmArgs a) {
     }
 }
 
+// ---- weight-only int8 matrices (the quantised model Sections 2 and 3 assume; one fp32 scale per output row)
+//
+// Same decomposition as gemm_kernel for at most 16 rows.  A lane's 16-byte load holds 16 consecutive K
+// entries of its weight row, i.e. two MFMA k-blocks: lane (c, g) supplies k = 64*step + 16*g + 8*j .. +7 to
+// block j, and reads the activations of exactly those k.  An int8 value is exact in bf16, the sum runs
+// in fp32, and the row scale multiplies the finished sum, so the only roundings are those of the sum.
+__device__ __forceinline__ uint32_t w8_pair_to_bf16x2(uint32_t x, int first_byte) {
+    const float f0 = (float)((int)(x << (24 - 8 * first_byte)) >> 24); // sign-extended bytes
+    const float f1 = (float)((int)(x << (16 - 8 * first_byte)) >> 24);
+    return (f2u(f0) >> 16) | (f2u(f1) & 0xffff0000u); // |q| <= 127: the low 16 bits of the fp32 are zero
+}
+__device__ __forceinline__ u32x4 w8_to_bf16x8(uint32_t a, uint32_t b) {
+    return u32x4{w8_pair_to_bf16x2(a, 0), w8_pair_to_bf16x2(a, 2), w8_pair_to_bf16x2(b, 0), w8_pair_to_bf16x2(b, 2)};
+}
+
+template <int EPI, int NW, int U>
+__global__ __launch_bounds__(NW * 64) void gemm_w8_kernel(GemmArgs a) {
+    typedef bf16_t T;
+    constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const int K = a.K;
+
+    int n0[NT];
+    if constexpr (EPI == EPI_QKV) {
+        const int per_head = a.hd / 32;
+        const int hh = blockIdx.x / per_head;
+        n0[0] = hh * a.hd + (blockIdx.x % per_head) * 16;
+        n0[1] = n0[0] + a.hd / 2;
+    } else if constexpr (EPI == EPI_SWIGLU) {
+        n0[0] = blockIdx.x * 16;
+        n0[1] = a.N + n0[0];
+    } else {
+        n0[0] = blockIdx.x * 16;
+    }
+    const int nrows_w = (EPI == EPI_SWIGLU) ? 2 * a.N : a.N;
+
+    const int8_t *W = reinterpret_cast<const int8_t *>(a.W);
+    const int8_t *wrow[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        int n = n0[t] + c;
+        if (n > nrows_w - 1) n = nrows_w - 1; // ragged last tile: a valid row, masked at the store
+        wrow[t] = W + (size_t)n * K + g * 16;
+    }
+    ActPlanes<T> act{const_cast<T *>(reinterpret_cast<const T *>(a.act)), a.act_plane, a.ld_act};
+    const size_t aoff = (size_t)c * a.ld_act + g * 16;
+    const bool row_live = c < a.R;
+
+    f32x4 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int nsteps = (K + 63) / 64; // 64 entries of K (64 bytes of a weight row) per step
+    for (int ks = wave; ks < nsteps; ks += U * NW) {
+        u32x4 w[U][NT];
+        Act<T> av[U][2];
+#pragma unroll
+        for (int s = 0; s < U; ++s) {
+            const int k = (ks + s * NW) * 64;
+            const bool ok = k + g * 16 < K; // K is a multiple of 16
+#pragma unroll
+            for (int t = 0; t < NT; ++t) w[s][t] = ok ? ld16_stream(wrow[t] + k) : zero16();
+#pragma unroll
+            for (int j = 0; j < 2; ++j) av[s][j] = (ok && row_live) ? load_act(act, aoff + k + 8 * j) : zero_act<T>();
+        }
+#pragma unroll
+        for (int s = 0; s < U; ++s)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int t = 0; t < NT; ++t) acc[t] = mma(acc[t], w8_to_bf16x8(w[s][t][2 * j], w[s][t][2 * j + 1]), av[s][j]);
+    }
+
+    // fixed-order sum of the waves' partial tiles; wave 0 scales the columns and applies the epilogue
+    __shared__ float red[NW][NT][4][64];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red[wave][t][v][lane] = acc[t][v];
+    __syncthreads();
+    if (wave != 0) return;
+    float r[NT][4];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            float sum = red[0][t][v][lane];
+#pragma unroll 4
+            for (int w2 = 1; w2 < NW; ++w2) sum += red[w2][t][v][lane];
+            r[t][v] = sum * a.wscale[min(n0[t] + 4 * g + v, nrows_w - 1)];
+        }
+    apply_epilogue<T, EPI>(a, r, n0, 0);
+}
+
 // More than 16 rows (larger batches, prefill): the waves of a workgroup split the output columns instead
 // of K, so that all of them walk K together and share the activation rows through LDS - with R rows
 // the activations a wave needs are R*4/32 times its weight bytes, too much to fetch per wave from L2.
@@ -507,7 +602,21 @@ template <typename T, int EPI> static void launch_gemm_t(const GemmArgs &a, hipS
     }
 }
 
+template <int EPI> static void launch_gemm_w8(const GemmArgs &a, hipStream_t st) {
+    const int tiles = EPI == EPI_QKV ? 3 * a.H * (a.hd / 32) : (a.N + 15) / 16;
+    hipLaunchKernelGGL((gemm_w8_kernel<EPI, 16, 2>), dim3(tiles, 1), dim3(16 * 64), 0, st, a);
+}
+
 void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st) {
+    if (a.wscale) { // int8 weights: the caller has checked bf16 planes, at most 16 rows, K % 16 == 0
+        switch (epi) {
+        case EPI_STORE: launch_gemm_w8<EPI_STORE>(a, st); break;
+        case EPI_RESID: launch_gemm_w8<EPI_RESID>(a, st); break;
+        case EPI_SWIGLU: launch_gemm_w8<EPI_SWIGLU>(a, st); break;
+        case EPI_QKV: launch_gemm_w8<EPI_QKV>(a, st); break;
+        }
+        return;
+    }
 #define SS_CASE(EP)                                                  \
     case EP:                                                         \
         if (dtype) launch_gemm_t<bf16_t, EP>(a, st);                 \

@@ -39,6 +39,9 @@ struct GemmArgs {
     float *splitk_ws;
     size_t splitk_ws_bytes;
     int ksplit, kslabs; // set by the launcher: K splits, K slabs per split
+    // weight-only int8: W is int8 [N][K] and output column n is scaled by wscale[n] (NULL: W is in the storage type).
+    // Launches of at most 16 rows with bf16 activation planes only; K a multiple of 16.
+    const float *wscale;
 };
 void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st);
 
@@ -67,6 +70,8 @@ void launch_rmsnorm_pack(int dtype, const float *h, const float *gain, int R, in
 // gathers the last row of every sequence: rows b*M + M-1 -> compact rows b (norm + pack)
 void launch_rmsnorm_pack_rows(int dtype, const float *h, const float *gain, int nrows, int row0, int row_stride,
                               int d, float eps, void *act, size_t act_plane, int ld_act, hipStream_t st);
+// row-wise int8 quantisation of W [rows][K] (storage type): scale = max|w| / 127 (1 for a zero row), q = rint(w / scale)
+void launch_quantize_rows_int8(int dtype, const void *W, long long rows, long long K, int8_t *q, float *scale, hipStream_t st);
 void launch_read_probe(const void *buf, size_t bytes, uint32_t *sink, hipStream_t st);
 void launch_len_add(int32_t *len, int batch, int delta, hipStream_t st);
 void launch_len_rollback(int32_t *len, const int32_t *n_accepted, int batch, int M, hipStream_t st);
