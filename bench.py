@@ -165,6 +165,62 @@ def layer_pass(si, sv, torch, dev, target, shape, iters=20, L=1024, M=5):
             "GBps": nbytes / t / 1e9, "frac_of_hbm_peak": nbytes / t / HBM_PEAK}
 
 
+def int8_weights_leg(si, sv, torch, gen, dev, target, persistent, shape, packed, io, prompt, K, steps):
+    """The verify pass with weight-only int8 matrices (the quantised model the paper assumes; one scale per
+    output row): the same 7B-shaped weights quantised by the library, K + 1 rows per pass, one launch per
+    phase (the persistent kernel streams bf16 matrices only), beside the bf16 model on the same
+    per-phase path; then the speculative loop and the autoregressive baseline on the int8 pair."""
+    M = K + 1
+    t8 = sv.Model(shape, io, max_rows=16, max_pos=4096, packed_layers=packed, int8_weights=True)
+    d8 = sv.Model(si.DecoderShape(**{**shape.as_dict(), "n_layers": min(2, shape.n_layers)}),
+                  {"embed": io["embed"], "gf": io["gf"], "lm_head": t8.lm_head, "s_head": t8.s_head},
+                  max_rows=16, max_pos=4096, packed_layers=t8.layers[:min(2, shape.n_layers)], int8_weights=True)
+    vt = si.token_ids(3, "int8_rows", (1, M), shape.vocab).to(torch.int32).to(dev)
+    zero = torch.zeros(1, dtype=torch.int32, device=dev)
+    logits = torch.empty((1, M, shape.vocab), dtype=torch.float32, device=dev)
+
+    def timed(model):
+        kv = sv.KVCache(model, 1, len(prompt) + M * (steps + 3) + 16)   # the host's bound on the length grows by M per pass
+        gen.prefill(model, kv, prompt[:-1])
+        for it in range(steps + 3):
+            if it == 3:
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+            sv.ss_verify_forward(model, kv, vt, M, logits)
+            sv.ss_kv_cache_rollback(kv, zero, M)          # commits one row: the context grows by one per pass
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        kv.close()
+        return dt
+
+    t_int8 = timed(t8)
+    sv.ss_model_set_persistent(target, False)
+    t_bf16 = timed(target)
+    sv.ss_model_set_persistent(target, persistent)
+    W = shape.n_heads * shape.head_dim
+    L = len(prompt) + steps // 2
+    rows = shape.n_layers * (3 * W + 2 * shape.d_model + 2 * shape.d_ff) + shape.vocab          # one fp32 scale per matrix row
+    nbytes = (shape.n_layers * layer_bytes(shape) + shape.vocab * shape.d_model * 2) // 2 + 4 * rows \
+        + shape.n_layers * 2 * (L + 2 * M) * W * 2 + M * shape.vocab * 4
+    out = {"workload": f"7B-shaped target with int8 matrices ({shape.n_layers} layers), batch 1, K={K}, KV context ~{L}, "
+                       "one launch per phase",
+           "ms_per_pass": 1e3 * t_int8, "verify_pass_tokens_per_s": M / t_int8, "algorithmic_bytes": nbytes,
+           "GBps": nbytes / t_int8 / 1e9, "frac_of_hbm_peak": nbytes / t_int8 / HBM_PEAK,
+           "bf16_same_path_ms_per_pass": 1e3 * t_bf16, "speedup_vs_bf16_same_path": t_bf16 / t_int8}
+    n_new = 96
+    ud, ua = si.uniforms(2, "ud8", (n_new, K)), si.uniforms(2, "ua8", (n_new, K + 1))
+    _, st = gen.speculative_generate(t8, d8, prompt, n_new, K, 1.0, ud, ua)
+    ar = {}
+    gen.autoregressive_generate(t8, prompt, 48, 1.0, si.uniforms(2, "uar8", (48,)), stats=ar)
+    out["end_to_end"] = {"accepted_tokens_per_s": st["generated"] / st["loop_seconds"],
+                         "mean_accepted_per_step": sum(st["accepted"]) / max(1, st["steps"]),
+                         "ms_per_step": 1e3 * st["loop_seconds"] / max(1, st["steps"]),
+                         "autoregressive_tokens_per_s": 48 / ar["loop_seconds"]}
+    d8.close()
+    t8.close()
+    return out
+
+
 def batched_workload(si, sv, torch, dev, shape, packed, io, iters=5, B=8, L=4096, M=9):
     """The batched long-context workload: 8 sequences with 4096 cached positions each, K = 8 (72 rows per
     verify pass, one launch per phase: wide GEMMs and split-KV attention)."""
@@ -218,6 +274,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-e2e", action="store_true")
     ap.add_argument("--no-accept-workload", action="store_true", help="skip the stand-alone accept workload leg")
+    ap.add_argument("--no-int8-leg", action="store_true", help="skip the weight-only int8 leg")
     ap.add_argument("--no-layer-pass", action="store_true", help="skip the one-layer leg (5 rows, 1024 cached positions)")
     ap.add_argument("--batched-workload", action="store_true",
                     help="also time the batched long-context workload (8 x 4096 positions, 72 rows; needs 20 GB more)")
@@ -379,9 +436,11 @@ def main():
         out["layer_pass"] = layer_pass(si, sv, torch, dev, target, shape)
     if not args.no_accept_workload:
         out["standalone_accept"] = standalone_accept(si, sv, torch, dev)
+    if not args.no_int8_leg:
+        out["int8_weights"] = int8_weights_leg(si, sv, torch, gen, dev, target, bool(args.persistent), shape, packed, io, prompt, K, args.steps)
     if args.batched_workload:
         out["batched_workload"] = batched_workload(si, sv, torch, dev, shape, packed, io)
-    for leg in ("layer_pass", "standalone_accept", "batched_workload"):
+    for leg in ("layer_pass", "standalone_accept", "batched_workload", "int8_weights"):
         if leg in out and "GBps" in out[leg]:
             out[leg]["frac_of_read_stream"] = out[leg]["GBps"] / stream_GBps
     if not args.no_cpu_baseline:

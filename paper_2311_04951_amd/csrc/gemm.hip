@@ -602,9 +602,12 @@ template <typename T, int EPI> static void launch_gemm_t(const GemmArgs &a, hipS
     }
 }
 
+// 8 waves per workgroup and two steps in flight per wave: measured best on the 7B-shaped layer among
+// (4 | 8 | 16 waves) x (1..4 steps) - the registers go to the activation operands (four 16-byte loads per
+// weight load), so more steps in flight cost occupancy, and smaller workgroups give more of them per compute unit.
 template <int EPI> static void launch_gemm_w8(const GemmArgs &a, hipStream_t st) {
     const int tiles = EPI == EPI_QKV ? 3 * a.H * (a.hd / 32) : (a.N + 15) / 16;
-    hipLaunchKernelGGL((gemm_w8_kernel<EPI, 16, 2>), dim3(tiles, 1), dim3(16 * 64), 0, st, a);
+    hipLaunchKernelGGL((gemm_w8_kernel<EPI, 8, 2>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
 }
 
 void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st) {
