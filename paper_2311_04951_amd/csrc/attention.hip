@@ -28,6 +28,13 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
     attn_unit<T, HD, 4>(a, blockIdx.x, blockIdx.y, blockIdx.z, a.len[blockIdx.z], sm);
 }
 
+// a single split: the workgroup normalises and writes the activation planes itself (no partials, no merge launch)
+template <typename T, int HD>
+__global__ __launch_bounds__(256) void attn_direct_kernel(AttnArgs a) {
+    __shared__ AttnSmem<HD, 4> sm;
+    attn_unit<T, HD, 4, false, true>(a, 0, blockIdx.y, blockIdx.z, a.len[blockIdx.z], sm);
+}
+
 template <typename T>
 __global__ void attn_merge_kernel(AttnArgs a) {
     const int row = blockIdx.x, h = blockIdx.y, e = threadIdx.x;
@@ -37,6 +44,12 @@ __global__ void attn_merge_kernel(AttnArgs a) {
 
 template <typename T> static void launch_attention_t(const AttnArgs &a, hipStream_t st) {
     dim3 grid(a.nsplit, a.H, a.B);
+    if (a.nsplit == 1) {
+        if (a.hd == 128) hipLaunchKernelGGL((attn_direct_kernel<T, 128>), grid, dim3(256), 0, st, a);
+        else if (a.hd == 64) hipLaunchKernelGGL((attn_direct_kernel<T, 64>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((attn_direct_kernel<T, 32>), grid, dim3(256), 0, st, a);
+        return;
+    }
     if (a.hd == 128) hipLaunchKernelGGL((attn_partial_kernel<T, 128>), grid, dim3(256), 0, st, a);
     else if (a.hd == 64) hipLaunchKernelGGL((attn_partial_kernel<T, 64>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((attn_partial_kernel<T, 32>), grid, dim3(256), 0, st, a);
