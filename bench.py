@@ -28,7 +28,11 @@ PERSISTENT_7B_TRAFFIC_BYTES = 13.608e9  # 13.472 GB fetched + 0.136 GB written p
 
 def build_7b(si, sv, torch, seed, n_layers, dev):
     """Random-init weights generated on the GPU, packed once into the library's fused matrices."""
-    shape = si.DecoderShape(**{**si.FULL_7B.as_dict(), "n_layers": n_layers})
+    return build_packed(si, torch, si.DecoderShape(**{**si.FULL_7B.as_dict(), "n_layers": n_layers}), seed, dev)
+
+
+def build_packed(si, torch, shape, seed, dev):
+    n_layers = shape.n_layers
     packed = []
     for l in range(n_layers):
         lw = si.layer_weights(shape, seed, l, device=dev)
@@ -221,6 +225,44 @@ def int8_weights_leg(si, sv, torch, gen, dev, target, persistent, shape, packed,
     return out
 
 
+def paper_pair_leg(si, sv, torch, gen, dev, prompt_len=128, n_new=96, K=5):
+    """The size ratio of the paper's own experiment (Section 6: a 12B target with a 3B draft, K = 5) on
+    Llama-shaped stand-ins with random weights: a 13B-shaped target (40 layers, d 5120, 40 heads, FFN 13824)
+    and a separate 3B-shaped draft (28 layers, d 3072, 24 heads, FFN 8192) with its own cache.  Random
+    weights make the draft useless as a predictor, so the figures are costs per step, not the paper's speed-up."""
+    ts = si.DecoderShape(40, 5120, 40, 128, 13824, 32000, dtype="bf16")
+    ds = si.DecoderShape(28, 3072, 24, 128, 8192, 32000, dtype="bf16")
+    _, tp, tio = build_packed(si, torch, ts, 11, dev)
+    _, dp, dio = build_packed(si, torch, ds, 12, dev)
+    target = sv.Model(ts, tio, max_rows=16, max_pos=1024, packed_layers=tp)
+    draft = sv.Model(ds, dio, max_rows=16, max_pos=1024, packed_layers=dp)
+    prompt = si.token_ids(11, "prompt", (prompt_len,), ts.vocab).tolist()
+    ud, ua = si.uniforms(11, "ud", (n_new, K)), si.uniforms(11, "ua", (n_new, K + 1))
+    gen.speculative_generate(target, draft, prompt, 8, K, 1.0, ud[:8], ua[:8])          # warm-up
+    _, st = gen.speculative_generate(target, draft, prompt, n_new, K, 1.0, ud, ua)
+    ar = {}
+    n_ar = 32
+    gen.autoregressive_generate(target, prompt, n_ar, 1.0, si.uniforms(11, "uar", (n_ar,)), stats=ar)
+    dr = {}
+    gen.autoregressive_generate(draft, prompt, n_ar, 1.0, si.uniforms(12, "uar", (n_ar,)), stats=dr)
+    t_step = st["loop_seconds"] / max(1, st["steps"])
+    t_target1, t_draft1 = ar["loop_seconds"] / n_ar, dr["loop_seconds"] / n_ar
+    tb = ts.n_layers * layer_bytes(ts) + ts.vocab * ts.d_model * 2
+    db = ds.n_layers * layer_bytes(ds) + ds.vocab * ds.d_model * 2
+    out = {"workload": f"13B-shaped target ({tb / 1e9:.1f} GB) + separate 3B-shaped draft ({db / 1e9:.1f} GB), bf16, batch 1, K={K}, "
+                       f"T=1, prompt {prompt_len}, {n_new} tokens, random weights",
+           "accepted_tokens_per_s": st["generated"] / st["loop_seconds"], "ms_per_step": 1e3 * t_step,
+           "mean_accepted_per_step": sum(st["accepted"]) / max(1, st["steps"]),
+           "autoregressive_tokens_per_s": 1.0 / t_target1, "target_ms_per_token": 1e3 * t_target1,
+           "draft_ms_per_token": 1e3 * t_draft1,
+           "target_GBps": tb / t_target1 / 1e9, "draft_GBps": db / t_draft1 / 1e9,
+           # accepted draft tokens per step at which a step (K draft tokens + one verify pass) yields as many tokens per second as one target token per pass
+           "break_even_accepted_per_step": t_step / t_target1 - 1.0}
+    for obj in (target, draft):
+        obj.close()
+    return out
+
+
 def batched_workload(si, sv, torch, dev, shape, packed, io, iters=5, B=8, L=4096, M=9):
     """The batched long-context workload: 8 sequences with 4096 cached positions each, K = 8 (72 rows per
     verify pass, one launch per phase: wide GEMMs and split-KV attention)."""
@@ -275,6 +317,7 @@ def main():
     ap.add_argument("--no-e2e", action="store_true")
     ap.add_argument("--no-accept-workload", action="store_true", help="skip the stand-alone accept workload leg")
     ap.add_argument("--no-int8-leg", action="store_true", help="skip the weight-only int8 leg")
+    ap.add_argument("--no-paper-pair", action="store_true", help="skip the 13B/3B-shaped target/draft pair (the paper's size ratio)")
     ap.add_argument("--no-layer-pass", action="store_true", help="skip the one-layer leg (5 rows, 1024 cached positions)")
     ap.add_argument("--batched-workload", action="store_true",
                     help="also time the batched long-context workload (8 x 4096 positions, 72 rows; needs 20 GB more)")
@@ -438,6 +481,8 @@ def main():
         out["standalone_accept"] = standalone_accept(si, sv, torch, dev)
     if not args.no_int8_leg:
         out["int8_weights"] = int8_weights_leg(si, sv, torch, gen, dev, target, bool(args.persistent), shape, packed, io, prompt, K, args.steps)
+    if not args.no_paper_pair:
+        out["paper_size_pair"] = paper_pair_leg(si, sv, torch, gen, dev)
     if args.batched_workload:
         out["batched_workload"] = batched_workload(si, sv, torch, dev, shape, packed, io)
     for leg in ("layer_pass", "standalone_accept", "batched_workload", "int8_weights"):

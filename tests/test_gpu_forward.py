@@ -277,3 +277,30 @@ def test_read_stream_probe_reports_a_plausible_rate():
         sv.ss_probe_read_bandwidth(buf[:1024])
     with pytest.raises(sv.SpecVerifyError):
         sv.ss_probe_read_bandwidth(buf, iters=0)
+
+
+@pytest.mark.parametrize("persistent", [False, True])
+@pytest.mark.parametrize("d,H,F", [(5120, 40, 13824), (3072, 24, 8192)])
+def test_single_layer_of_13b_and_3b_width_matches_oracle(d, H, F, persistent):
+    """One bf16 layer at the widths of a 13B-shaped target and a 3B-shaped draft (the size ratio of the
+    paper's Section 6 experiment), K = 5 (6 query rows) against 200 cached positions: weight rows of 10 KB
+    and 27 KB (two and four activation slabs in the persistent kernel), 20 and 12 output rows per workgroup."""
+    shape = si.DecoderShape(1, d, H, 128, F, 32000, dtype="bf16")
+    lw = si.layer_weights(shape, seed=3, layer=0)
+    w = {"embed": None, "gf": None, "lm_head": None, "layers": [lw]}
+    om = oracle.Model(shape, w)
+    gm = sv.Model(shape, weights_to_device(w), max_rows=16, max_pos=512)
+    set_path(gm, persistent)
+    L, M = 200, 6
+    ctx = si.kv_context(shape, 3, "ctx", L)
+    gkv = sv.KVCache(gm, 1, L + 64)
+    sv.ss_kv_cache_append(gkv, 0, 0, 0, ctx[0][0].to(dev()), ctx[0][1].to(dev()))
+    sv.ss_kv_cache_set_len(gkv, [L])
+    okv = om.new_kv(L + 64)
+    okv.append_raw(ctx)
+    h = si.normal(3, "h", (M, shape.d_model), 1.0)
+    got = sv.ss_decoder_layers_forward(gm, gkv, h.to(dev()).clone(), 1, M).cpu().numpy()
+    ref = om.layers_forward(okv, h.numpy())
+    assert maxabs(got, ref) < 2e-2
+    assert maxabs(got, ref) < 2e-3
+    assert sv.ss_device_status(gm) == 0
