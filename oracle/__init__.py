@@ -62,6 +62,7 @@ def lib():
         L.orc_quantize_rows_int8.argtypes = [vp, i32, i32, i32, vp, vp]
         L.orc_linear_w8.argtypes = [vp, vp, vp, i32, i32, vp]
         L.orc_model_set_scales.argtypes = [vp, i32, C.POINTER(vp)]
+        L.orc_top_p_filter.argtypes = [vp, i32, f32, vp]
         L.orc_f32_to_bf16.restype = C.c_uint16
         L.orc_f32_to_bf16.argtypes = [f32]
         L.orc_bf16_to_f32.restype = f32
@@ -164,6 +165,19 @@ def sample(p, u) -> int:
 def sample_residual(p, q, u) -> int:
     p, q = _f32(p), _f32(q)
     return lib().orc_sample_residual(_p(p), _p(q), p.size, float(u))
+
+
+def top_p_filter(p, top_p):
+    """Rows of probabilities [..., V] -> the rows restricted to their top-p nucleus and renormalised
+    (top_p >= 1: returned unchanged)."""
+    p = _f32(p)
+    if top_p >= 1.0:
+        return p.copy()
+    flat = p.reshape(-1, p.shape[-1])
+    out = np.empty_like(flat)
+    for r in range(flat.shape[0]):
+        lib().orc_top_p_filter(_p(flat[r]), flat.shape[1], float(top_p), _p(out[r]))
+    return out.reshape(p.shape)
 
 
 def speculative_accept(p, q, draft, u):
@@ -302,9 +316,10 @@ class KVCache:
 # ------------------------------------------------------------------ host loops
 
 def autoregressive_generate(target: Model, prompt, n_new: int, temperature: float, u=None,
-                            max_seq=None):
+                            max_seq=None, top_p=1.0):
     """Section 3, Eq. (1) with a KV cache (Section 4.2).  temperature == 0 selects argmax;
-    otherwise token ~ softmax(logits / T) by the integer inverse CDF with uniforms u[n_new]."""
+    otherwise token ~ softmax(logits / T), restricted to its top-p nucleus when top_p < 1, by the
+    integer inverse CDF with uniforms u[n_new]."""
     x = [int(t) for t in prompt]
     kv = target.new_kv(max_seq or (len(x) + n_new + 1))
     logits = target.forward(kv, x)[-1]
@@ -313,7 +328,7 @@ def autoregressive_generate(target: Model, prompt, n_new: int, temperature: floa
         if temperature == 0:
             t = argmax(logits)
         else:
-            t = sample(softmax(logits, temperature), u[i])
+            t = sample(top_p_filter(softmax(logits, temperature), top_p), u[i])
         out.append(t)
         if i + 1 < n_new:
             logits = target.forward(kv, [t])[-1]
@@ -321,7 +336,7 @@ def autoregressive_generate(target: Model, prompt, n_new: int, temperature: floa
 
 
 def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int,
-                         temperature: float, u_draft=None, u_accept=None, max_seq=None, shared_kv=False):
+                         temperature: float, u_draft=None, u_accept=None, max_seq=None, shared_kv=False, top_p=1.0):
     """Speculative sampling with two KV caches (Sections 3, 4.3, 4.4).
 
     shared_kv (the other answer to Section 4.4's "do we have two separate caches?", for a draft made of
@@ -334,6 +349,8 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
     Draft phase: K one-token draft calls (after a fully accepted step the first call feeds the two
     tokens the draft cache is missing).  Verify: one target call over [x_n, d_1..d_K].  Accept:
     the modified rejection rule.  Fix-up: both caches are truncated to n + a positions.
+    top_p < 1: the draft's and the target's rows are both restricted to their top-p nucleus before
+    anything is sampled or compared, so the run emits the filtered target distribution.
     u_draft [steps, K], u_accept [steps, K+1].  Returns (tokens[n_new], stats dict)."""
     x = [int(t) for t in prompt]
     n0 = len(x)
@@ -358,7 +375,7 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
             if greedy:
                 tok = argmax(ql)
             else:
-                q_rows[i] = softmax(ql, temperature)
+                q_rows[i] = top_p_filter(softmax(ql, temperature), top_p)
                 tok = sample(q_rows[i], u_draft[step][i])
             d.append(tok)
             feed = [tok]
@@ -368,7 +385,7 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
         if greedy:
             na, nx = greedy_accept(pl[None], np.asarray([d], dtype=np.int32))
         else:
-            p_rows = softmax(pl, temperature)
+            p_rows = top_p_filter(softmax(pl, temperature), top_p)
             na, nx = speculative_accept(p_rows[None], q_rows[None], np.asarray([d], dtype=np.int32),
                                         np.asarray([u_accept[step]], dtype=np.float32))
         a, y = int(na[0]), int(nx[0])

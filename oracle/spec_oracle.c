@@ -449,6 +449,54 @@ int orc_sample_residual(const float *p, const float *q, int V, float u) {
     return t >= 0 ? t : orc_sample(p, V, u);
 }
 
+/* Top-p ("nucleus") selection, the other token selection rule Section 3 names besides argmax: keep the most
+ * probable tokens whose probabilities add up to at least top_p, renormalise, sample from what is left.
+ * The paper gives no arithmetic; the reading taken here makes the kept set exact and order-independent:
+ *   w_v = min(trunc(p_v * 2^32), 2^32 - 1), S = sum w_v (integers; S = 0: the row is returned unchanged);
+ *   P24 = nearest integer to top_p * 2^24, clamped to [1, 2^24]; target T = ceil(P24 * S / 2^24), at least 1;
+ *   tokens ordered by (w descending, index ascending); kept = the shortest prefix whose weights add up to >= T;
+ *   S' = sum of the kept weights, Z' = fl32(S') * 2^-32, out_v = fl32(p_v / Z') for kept v, else 0.
+ * Applied to the target's and the draft's rows alike before the rejection step, the step then emits the
+ * filtered target distribution (the guarantee of Section 3 holds for any pair of distributions). */
+typedef struct { uint32_t w; int32_t v; } orc_wv;
+static int cmp_wv(const void *a, const void *b) {
+    const orc_wv *x = (const orc_wv *)a, *y = (const orc_wv *)b;
+    if (x->w != y->w) return x->w > y->w ? -1 : 1;
+    return x->v < y->v ? -1 : (x->v > y->v ? 1 : 0);
+}
+static inline uint32_t fx_weight32(float r) {
+    uint64_t w = fx_weight(r);
+    return w > 0xffffffffu ? 0xffffffffu : (uint32_t)w;
+}
+int orc_top_p_filter(const float *p, int V, float top_p, float *out) {
+    orc_wv *o = (orc_wv *)malloc(sizeof(orc_wv) * (size_t)V);
+    uint64_t S = 0;
+    for (int v = 0; v < V; ++v) { o[v].w = fx_weight32(p[v]); o[v].v = v; S += o[v].w; }
+    int kept = 0;
+    if (S == 0) {
+        for (int v = 0; v < V; ++v) out[v] = p[v];
+        free(o);
+        return V;
+    }
+    double pr = rint((double)top_p * 16777216.0);
+    uint64_t P24 = pr < 1.0 ? 1 : (pr > 16777216.0 ? 16777216u : (uint64_t)pr);
+    unsigned __int128 prod = (unsigned __int128)P24 * (unsigned __int128)S + 16777215u;
+    uint64_t T = (uint64_t)(prod >> 24);
+    if (T < 1) T = 1;
+    qsort(o, (size_t)V, sizeof(orc_wv), cmp_wv);
+    uint64_t C = 0;
+    while (kept < V && C < T) C += o[kept++].w;
+    volatile float zs = (float)C;          /* uint64 -> fp32, round to nearest even */
+    float Z = zs * 2.3283064365386963e-10f; /* * 2^-32, exact */
+    for (int v = 0; v < V; ++v) out[v] = 0.0f;
+    for (int i = 0; i < kept; ++i) {
+        volatile float r = p[o[i].v] / Z;
+        out[o[i].v] = r;
+    }
+    free(o);
+    return kept;
+}
+
 /* The modified rejection step (Sections 3, 4.3) for a batch of sequences.
  * p [B][K+1][V], q [B][K][V] probabilities; draft [B][K]; u [B][K+1]: u[b][i<K] decides draft
  * token i, u[b][K] drives the one sampling that happens (residual resample or bonus).
