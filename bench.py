@@ -376,6 +376,12 @@ def main():
                     "mean_accepted_per_step": round(sum(s2["accepted"]) / max(1, s2["steps"]), 3),
                     "ms_per_step": round(1e3 * s2["loop_seconds"] / max(1, s2["steps"]), 3)}
         e2e["by_draft_length"] = sweep
+        # top-p selection (nucleus 0.9) on both models' rows
+        n_tp = min(96, n_new)
+        _, s4 = gen.speculative_generate(target, draft, prompt, n_tp, K, T, ud[:n_tp], ua[:n_tp], top_p=0.9)
+        e2e["top_p_0.9"] = {"accepted_tokens_per_s": s4["generated"] / s4["loop_seconds"],
+                            "mean_accepted_per_step": sum(s4["accepted"]) / max(1, s4["steps"]),
+                            "ms_per_step": 1e3 * s4["loop_seconds"] / max(1, s4["steps"])}
         # the same loop with one cache shared by both models (the draft works in the target's first layers' cache)
         _, s3 = gen.speculative_generate(target, draft, prompt, n_new, K, T, ud, ua, shared_kv=True)
         e2e["shared_kv_cache"] = {"accepted_tokens_per_s": s3["generated"] / s3["loop_seconds"], "steps": s3["steps"],

@@ -209,10 +209,29 @@ int ss_decoder_layers_forward(ss_model *model, ss_kv_cache *kv, float *h_dev, in
  *   temperature > 0 : q = softmax(logits / temperature) written to q_rows_dev + b*ldq (fp32
  *                     [vocab]); token ~ q by the integer inverse CDF with uniform u_dev[b]
  *   temperature == 0: token = argmax (lowest index on ties); q_rows_dev and u_dev may be NULL.
+ * top_p < 1 (temperature > 0 only): q is restricted to its top-p nucleus and renormalised before
+ * the token is drawn (see ss_top_p_filter), and that filtered row is what q_rows_dev receives;
+ * top_p >= 1: no filtering; top_p <= 0: SS_EINVAL.
  * token_out_dev int32 [batch].  Calling it on the target model is an autoregressive decode step. */
 int ss_draft_step(ss_model *draft, ss_kv_cache *draft_kv, const int32_t *tokens_dev, int32_t batch,
-                  int32_t m, float temperature, const float *u_dev, float *q_rows_dev, int64_t ldq,
-                  int32_t *token_out_dev, ss_stream stream);
+                  int32_t m, float temperature, float top_p, const float *u_dev, float *q_rows_dev,
+                  int64_t ldq, int32_t *token_out_dev, ss_stream stream);
+
+/* ---- top-p ("nucleus") selection (Section 3 names "randomly selected from top-p" beside argmax) --
+ * Every row of probs_dev fp32 [rows][vocab] is restricted to its most probable tokens whose
+ * probabilities add up to at least top_p, and renormalised.  The paper gives no arithmetic; this is
+ * the rule, chosen so that any implementation keeps the same set:
+ *   w_v = min(trunc(p_v * 2^32), 2^32 - 1); S = sum_v w_v (S = 0: the row is returned unchanged);
+ *   P24 = nearest integer to top_p * 2^24 (ties to even), clamped to [1, 2^24];
+ *   target = ceil(P24 * S / 2^24), at least 1;
+ *   kept = the shortest prefix, in the order (w descending, index ascending), whose weights add
+ *          up to >= target; S' = their sum; Z' = fl32(S') * 2^-32;
+ *   out_v = fl32(p_v / Z') for kept v, 0 otherwise.
+ * Filtering the target's and the draft's rows alike and then applying the rejection step emits the
+ * filtered target distribution.  out_dev may be probs_dev (in place).  top_p >= 1 copies the rows
+ * unchanged; top_p <= 0 is SS_EINVAL. */
+int ss_top_p_filter(const float *probs_dev, int32_t rows, int32_t vocab, float top_p, float *out_dev,
+                    ss_stream stream);
 
 /* ---- softmax (per-row statistics by wavefront reductions over the vocabulary) ---------------
  * probs_dev[r][v] = exp(logits[r][v]/T - max_r) / sum_v exp(...), fp32 [rows][vocab], evaluated with the
@@ -263,7 +282,8 @@ int ss_greedy_accept(const float *p_logits_dev, const int32_t *draft_tokens_dev,
  *     probability rows go to q_rows_dev [K][vocab] (temperature > 0);
  *   ss_verify_forward on (target, target_kv) over verify_tokens_dev [K+1] = [last committed token,
  *     d_1 .. d_K] -> logits_dev [K+1][vocab];
- *   temperature > 0: ss_softmax -> p_dev [K+1][vocab], then ss_speculative_accept with
+ *   temperature > 0: ss_softmax -> p_dev [K+1][vocab] (top_p < 1: then ss_top_p_filter in place, as
+ *     the draft's calls did to their rows), then ss_speculative_accept with
  *     u_accept_dev [K+1]; temperature == 0: ss_greedy_accept (p_dev, q_rows_dev, u_*_dev unused);
  *   both caches rolled back to their committed length.
  * Outputs: result_dev int32 [2] = (n_accepted a, next token y); out_host int32 [K+2] = (a, y, d_1 ..
@@ -278,7 +298,7 @@ int ss_greedy_accept(const float *p_logits_dev, const int32_t *draft_tokens_dev,
  * (draft: *n_feed + K - 1 rows, target: K + 1) are checked before the first of them runs, so a
  * refused step leaves both caches as they were. */
 int ss_speculative_step(ss_model *target, ss_kv_cache *target_kv, ss_model *draft, ss_kv_cache *draft_kv,
-                        int32_t K, float temperature, int32_t *feed_dev, int32_t *n_feed,
+                        int32_t K, float temperature, float top_p, int32_t *feed_dev, int32_t *n_feed,
                         const float *u_draft_dev, const float *u_accept_dev, int32_t *verify_tokens_dev,
                         float *q_rows_dev, float *logits_dev, float *p_dev, int32_t *result_dev,
                         int32_t *out_host, ss_stream stream);

@@ -552,6 +552,170 @@ void launch_accept(const AcceptArgs &a, unsigned long long *partial, hipStream_t
     hipLaunchKernelGGL(accept_finish_kernel, dim3(a.B), dim3(SAMPLE_THREADS), 0, st, a, seg_len, nseg, partial);
 }
 
+// ------------------------------------------------------------------ top-p filter
+//
+// Top-p ("nucleus") selection of probability rows (Section 3 names it beside argmax; the arithmetic is fixed
+// in the header of the C ABI): 32-bit integer weights, kept set = shortest prefix in (weight descending, index
+// ascending) order whose weights reach the target, renormalised by one fp32 division per element.  One
+// workgroup per row finds the threshold weight by a three-digit radix selection (11 + 11 + 10 bits) over
+// histograms of weight sums in LDS: all sums are integers, so the result does not depend on the order in
+// which threads add.  Four reads of the row (three digits, one write pass; L2-resident), a fifth only when
+// equal weights straddle the boundary.
+constexpr int TP_THREADS = 1024, TP_WAVES = TP_THREADS / 64, TP_BINS = 2048, TP_UNROLL = 8;
+
+__device__ __forceinline__ uint32_t fx_weight32(float r) {
+    const unsigned long long w = fx_weight(r);
+    return w > 0xffffffffull ? 0xffffffffu : (uint32_t)w;
+}
+
+// Workgroup-wide exclusive prefix sum of one value per thread in thread order; also returns the total.
+__device__ __forceinline__ unsigned long long block_excl_scan(unsigned long long mine, unsigned long long *sm_wave, unsigned long long &total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned long long incl = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const unsigned long long t = shfl_up_u64(incl, o);
+        if (lane >= o) incl += t;
+    }
+    __syncthreads(); // sm_wave may still be read from a previous call
+    if (lane == 63) sm_wave[wave] = incl;
+    __syncthreads();
+    unsigned long long before = 0;
+    total = 0;
+#pragma unroll
+    for (int w = 0; w < TP_WAVES; ++w) {
+        const unsigned long long x = sm_wave[w];
+        if (w < wave) before += x;
+        total += x;
+    }
+    return before + incl - mine;
+}
+
+__global__ __launch_bounds__(TP_THREADS) void top_p_filter_kernel(const float *probs, long long ld_in, int V, unsigned P24, float *out, long long ld_out) {
+    __shared__ unsigned long long hist[TP_BINS];
+    __shared__ unsigned long long sm_wave[TP_WAVES];
+    __shared__ unsigned long long sm_above, sm_binw;
+    __shared__ int sm_bin, sm_cut;
+    const float *p = probs + (size_t)blockIdx.x * (size_t)ld_in;
+    float *o = out + (size_t)blockIdx.x * (size_t)ld_out;
+    const int t = threadIdx.x;
+
+    uint32_t prefix = 0;          // the digits of the threshold weight chosen so far
+    unsigned long long need = 0;  // what the keys inside the chosen range still have to contribute
+    unsigned long long S = 0, tie_weight = 0, target = 0;
+    const int shifts[3] = {21, 10, 0}, nbits[3] = {11, 11, 10};
+#pragma unroll
+    for (int pass = 0; pass < 3; ++pass) {
+        const int sh = shifts[pass], nb = nbits[pass];
+        for (int b = t; b < TP_BINS; b += TP_THREADS) hist[b] = 0;
+        __syncthreads();
+        // A thread adds up runs of elements that fall into one bin before it touches the histogram: in the first
+        // digit the weights of a whole vocabulary usually share their leading zeros (one bin), and per-element
+        // atomics on one address would serialise.
+        uint32_t run_bin = 0xffffffffu;
+        unsigned long long run_sum = 0;
+        for (int v0 = 0; v0 < V; v0 += TP_UNROLL * TP_THREADS) {
+            float x[TP_UNROLL]; // the loads of a batch go out together
+#pragma unroll
+            for (int e = 0; e < TP_UNROLL; ++e) {
+                const int v = v0 + e * TP_THREADS + t;
+                x[e] = v < V ? p[v] : 0.f;
+            }
+#pragma unroll
+            for (int e = 0; e < TP_UNROLL; ++e) {
+                const uint32_t w = fx_weight32(x[e]);
+                // keys inside the range chosen so far (pass 0: every key with a weight)
+                if (w != 0 && (pass == 0 || (w >> (sh + nb)) == prefix)) {
+                    const uint32_t bin = (w >> sh) & ((1u << nb) - 1);
+                    if (bin != run_bin) {
+                        if (run_bin != 0xffffffffu) atomicAdd(&hist[run_bin], run_sum);
+                        run_bin = bin;
+                        run_sum = 0;
+                    }
+                    run_sum += w;
+                }
+            }
+        }
+        if (run_bin != 0xffffffffu) atomicAdd(&hist[run_bin], run_sum);
+        __syncthreads();
+        // thread t owns bins 2047 - 2t and 2046 - 2t, so thread order is descending weight order
+        const unsigned long long a = hist[TP_BINS - 1 - 2 * t], b = hist[TP_BINS - 2 - 2 * t];
+        unsigned long long total;
+        const unsigned long long above = block_excl_scan(a + b, sm_wave, total);
+        if (pass == 0) {
+            S = total;
+            if (S == 0) { // nothing has a weight: the row is returned as it is
+                for (int v = t; v < V; v += TP_THREADS) o[v] = p[v];
+                return;
+            }
+            // target = ceil(P24 * S / 2^24) from the 128-bit product, at least 1
+            const unsigned long long lo = (unsigned long long)P24 * S, hi = __umul64hi((unsigned long long)P24, S);
+            const unsigned long long lo2 = lo + 16777215ull, hi2 = hi + (lo2 < lo ? 1ull : 0ull);
+            need = (hi2 << 40) | (lo2 >> 24);
+            if (need < 1) need = 1;
+            target = need;
+        }
+        if (above < need && need <= above + a) {
+            sm_bin = TP_BINS - 1 - 2 * t;
+            sm_above = above;
+            sm_binw = a;
+        } else if (above + a < need && need <= above + a + b) {
+            sm_bin = TP_BINS - 2 - 2 * t;
+            sm_above = above + a;
+            sm_binw = b;
+        }
+        __syncthreads();
+        prefix = (prefix << nb) | (uint32_t)sm_bin;
+        need -= sm_above;
+        tie_weight = sm_binw;
+        __syncthreads(); // everyone has read the choice before the next pass overwrites it
+    }
+    // prefix = threshold weight tau (>= 1); need = what tokens of weight tau must contribute; tie_weight = their total
+    const unsigned long long tau = prefix;
+    const unsigned long long n_ties = tie_weight / tau, n_keep = (need + tau - 1) / tau;
+    int cut = V; // ties are kept up to and including this index
+    if (n_keep < n_ties) {
+        // the n_keep-th token of weight tau in index order: contiguous chunks per thread, counts scanned over threads
+        const int chunk = (V + TP_THREADS - 1) / TP_THREADS;
+        const int v0 = min(t * chunk, V), v1 = min(v0 + chunk, V);
+        unsigned long long cnt = 0;
+        for (int v = v0; v < v1; ++v) cnt += fx_weight32(p[v]) == prefix;
+        unsigned long long total;
+        const unsigned long long before = block_excl_scan(cnt, sm_wave, total);
+        if (before < n_keep && n_keep <= before + cnt) {
+            unsigned long long seen = before;
+            for (int v = v0; v < v1; ++v)
+                if (fx_weight32(p[v]) == prefix && ++seen == n_keep) {
+                    sm_cut = v;
+                    break;
+                }
+        }
+        __syncthreads();
+        cut = sm_cut;
+    }
+    // weight of the kept set: everything above tau (target - need) plus the kept tokens of weight tau
+    const unsigned long long kept = target - need + n_keep * tau;
+    const float Z = __fmul_rn(__ull2float_rn(kept), 2.3283064365386963e-10f);
+    for (int v0 = 0; v0 < V; v0 += TP_UNROLL * TP_THREADS) {
+        float x[TP_UNROLL];
+#pragma unroll
+        for (int e = 0; e < TP_UNROLL; ++e) {
+            const int v = v0 + e * TP_THREADS + t;
+            x[e] = v < V ? p[v] : 0.f;
+        }
+#pragma unroll
+        for (int e = 0; e < TP_UNROLL; ++e) {
+            const int v = v0 + e * TP_THREADS + t;
+            const uint32_t w = fx_weight32(x[e]);
+            if (v < V) o[v] = (w > prefix || (w == prefix && v <= cut)) ? __fdiv_rn(x[e], Z) : 0.f;
+        }
+    }
+}
+void launch_top_p_filter(const float *probs, long long ld_in, int rows, int V, unsigned P24, float *out, long long ld_out, hipStream_t st) {
+    if (rows <= 0) return;
+    hipLaunchKernelGGL(top_p_filter_kernel, dim3(rows), dim3(TP_THREADS), 0, st, probs, ld_in, V, P24, out, ld_out);
+}
+
 // ------------------------------------------------------------------ sampling / argmax of plain rows
 
 __global__ __launch_bounds__(SAMPLE_THREADS) void sample_rows_kernel(const float *probs, int64_t ld, int V, const float *u,

@@ -767,10 +767,41 @@ extern "C" int ss_verify_forward(ss_model *m, ss_kv_cache *kv, const int32_t *to
     return check_launch();
 }
 
+// top_p on the 2^-24 grid the filter works on; 0 = no filtering (top_p >= 1)
+static int top_p_grid(float top_p, unsigned *P24, const char *who) {
+    if (!(top_p > 0.f)) return fail(SS_EINVAL, "%s: top_p must be > 0 (>= 1 switches the filter off)", who);
+    if (top_p >= 1.f) {
+        *P24 = 0;
+        return SS_OK;
+    }
+    const double g = std::nearbyint((double)top_p * 16777216.0); // to nearest, ties to even
+    *P24 = g < 1.0 ? 1u : (g > 16777216.0 ? 16777216u : (unsigned)g);
+    return SS_OK;
+}
+
+extern "C" int ss_top_p_filter(const float *probs_dev, int32_t rows, int32_t vocab, float top_p, float *out_dev, ss_stream stream) {
+    if (!probs_dev || !out_dev) return fail(SS_EINVAL, "ss_top_p_filter: NULL argument");
+    if (rows < 0 || vocab <= 0) return fail(SS_EINVAL, "ss_top_p_filter: bad shape");
+    unsigned P24 = 0;
+    int rc = top_p_grid(top_p, &P24, "ss_top_p_filter");
+    if (rc) return rc;
+    if (rows == 0) return SS_OK;
+    hipStream_t st = (hipStream_t)stream;
+    if (P24 == 0) {
+        if (out_dev != probs_dev) HIP_TRY(hipMemcpyAsync(out_dev, probs_dev, sizeof(float) * (size_t)rows * vocab, hipMemcpyDeviceToDevice, st));
+        return SS_OK;
+    }
+    launch_top_p_filter(probs_dev, vocab, rows, vocab, P24, out_dev, vocab, st);
+    return check_launch();
+}
+
 extern "C" int ss_draft_step(ss_model *m, ss_kv_cache *kv, const int32_t *tokens_dev, int32_t batch, int32_t mrows,
-                             float temperature, const float *u_dev, float *q_rows_dev, int64_t ldq,
+                             float temperature, float top_p, const float *u_dev, float *q_rows_dev, int64_t ldq,
                              int32_t *token_out_dev, ss_stream stream) {
     int rc = check_pair(m, kv, batch, mrows, "ss_draft_step");
+    if (rc) return rc;
+    unsigned P24 = 0;
+    rc = top_p_grid(top_p, &P24, "ss_draft_step");
     if (rc) return rc;
     if (!tokens_dev || !token_out_dev) return fail(SS_EINVAL, "ss_draft_step: NULL argument");
     if (!m->embed || !m->lm_head || !m->gf) return fail(SS_EINVAL, "ss_draft_step: model has no embedding / LM head");
@@ -790,6 +821,7 @@ extern "C" int ss_draft_step(ss_model *m, ss_kv_cache *kv, const int32_t *tokens
         const float inv_t = 1.0f / temperature;
         launch_row_stats(m->logits_ws, batch, V, inv_t, m->stats_ws, m->stats_cnt, m->stats_part, st);
         launch_softmax_write(m->logits_ws, batch, V, inv_t, m->stats_ws, q_rows_dev, ldq, st);
+        if (P24) launch_top_p_filter(q_rows_dev, ldq, batch, V, P24, q_rows_dev, ldq, st);
         launch_sample_rows(q_rows_dev, ldq, batch, V, u_dev, token_out_dev, st);
     } else {
         launch_argmax_rows(m->logits_ws, V, batch, V, token_out_dev, st);
@@ -934,7 +966,7 @@ extern "C" int ss_greedy_accept(const float *p_logits_dev, const int32_t *draft_
 // ------------------------------------------------------------------------------------------ one speculative step
 
 extern "C" int ss_speculative_step(ss_model *target, ss_kv_cache *tkv, ss_model *draft, ss_kv_cache *dkv, int32_t K,
-                                   float temperature, int32_t *feed_dev, int32_t *n_feed, const float *u_draft_dev,
+                                   float temperature, float top_p, int32_t *feed_dev, int32_t *n_feed, const float *u_draft_dev,
                                    const float *u_accept_dev, int32_t *vt, float *q_rows_dev, float *logits_dev, float *p_dev,
                                    int32_t *result_dev, int32_t *out_host, ss_stream stream) {
     if (!target || !tkv || !draft || !dkv || !feed_dev || !n_feed || !vt || !logits_dev || !result_dev || !out_host)
@@ -946,6 +978,8 @@ extern "C" int ss_speculative_step(ss_model *target, ss_kv_cache *tkv, ss_model 
     if (tkv->B != 1 || dkv->B != 1) return fail(SS_EINVAL, "ss_speculative_step: one sequence per cache");
     if (target->cfg.vocab != draft->cfg.vocab) return fail(SS_EINVAL, "ss_speculative_step: the two models have different vocabularies");
     if (!(temperature >= 0.f)) return fail(SS_EINVAL, "ss_speculative_step: temperature must be >= 0");
+    unsigned P24 = 0;
+    if (int rc0 = top_p_grid(top_p, &P24, "ss_speculative_step")) return rc0;
     const bool sample = temperature > 0.f;
     if (sample && (!u_draft_dev || !u_accept_dev || !q_rows_dev || !p_dev)) return fail(SS_EINVAL, "ss_speculative_step: sampling needs uniforms, q_rows_dev and p_dev");
     hipStream_t st = (hipStream_t)stream;
@@ -960,7 +994,7 @@ extern "C" int ss_speculative_step(ss_model *target, ss_kv_cache *tkv, ss_model 
         return fail(SS_ECAPACITY, "ss_speculative_step: the draft cache at length <= %d has no room for %d rows (max_seq %d, max_pos %d)",
                     dkv->len_ub[0], draft_rows, dkv->max_seq, draft->cfg.max_pos);
     for (int i = 0; i < K; ++i) {
-        rc = ss_draft_step(draft, dkv, i ? vt + i : feed_dev, 1, i ? 1 : *n_feed, temperature, sample ? u_draft_dev + i : nullptr,
+        rc = ss_draft_step(draft, dkv, i ? vt + i : feed_dev, 1, i ? 1 : *n_feed, temperature, top_p, sample ? u_draft_dev + i : nullptr,
                            sample ? q_rows_dev + (size_t)i * V : nullptr, V, vt + i + 1, stream);
         if (rc) return rc;
     }
@@ -974,6 +1008,7 @@ extern "C" int ss_speculative_step(ss_model *target, ss_kv_cache *tkv, ss_model 
     if (sample) {
         rc = ss_softmax(logits_dev, M, V, temperature, p_dev, stream);
         if (rc) return rc;
+        if (P24) launch_top_p_filter(p_dev, V, M, V, P24, p_dev, V, st); // the draft's rows were filtered by its own calls
         rc = ss_speculative_accept(p_dev, q_rows_dev, vt + 1, u_accept_dev, 1, K, V, result_dev, result_dev + 1, stream);
     } else {
         rc = ss_greedy_accept(logits_dev, vt + 1, 1, K, V, result_dev, result_dev + 1, stream);
