@@ -39,3 +39,11 @@ def test_product_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 src = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in src.replace("oracle-free", ""), f
+
+
+def test_bench_refuses_more_than_one_gpu_before_touching_a_device():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=60)
+    assert r.returncode != 0 and r.stdout.strip() == ""
+    assert "one GPU" in r.stderr
