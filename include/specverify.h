@@ -154,6 +154,13 @@ int ss_model_set_persistent(ss_model *model, int32_t on);
  * too large grid, or when the persistent kernel is not available. */
 int ss_model_set_persistent_options(ss_model *model, int32_t workgroups, int32_t data_sync);
 
+/* Every wait inside the persistent kernel is bounded: after `polls` unsuccessful looks at what it waits
+ * for (default 2^20, about a second), a workgroup raises the kernel's abort flag and leaves; every other
+ * workgroup leaves at its next wait, the call's results are invalid, and ss_device_status reports bit 1
+ * and resets the synchronisation state, after which the model works again.  A small limit makes a call
+ * fail fast (and is how the failure path is tested: the kernel still ends normally).  polls >= 1. */
+int ss_model_set_wait_limit(ss_model *model, uint32_t polls);
+
 /* ---- KV cache (Sections 2, 4.2, 4.4) --------------------------------------------------------
  * kv_cache_alloc: a contiguous, page-free cache for `batch` sequences of up to `max_seq`
  * positions in the model's storage type, allocated (and zero-filled) by the library together

@@ -26,6 +26,7 @@ EXPORTS = [
     "ss_draft_step", "ss_softmax", "ss_speculative_accept", "ss_speculative_accept_logits",
     "ss_greedy_accept", "ss_profile_enable", "ss_profile_read", "ss_model_set_persistent", "ss_model_set_persistent_options",
     "ss_speculative_step", "ss_probe_read_bandwidth", "ss_quantize_rows_int8", "ss_top_p_filter",
+    "ss_model_set_wait_limit",
 ]
 
 PROFILE_CLASSES = ["rmsnorm", "qkv_gemm", "attention", "oproj_gemm", "gateup_gemm", "down_gemm", "head_gemm", "other",
@@ -89,6 +90,7 @@ def lib():
             "ss_profile_enable": [vp, i32],
             "ss_model_set_persistent": [vp, i32],
             "ss_model_set_persistent_options": [vp, i32, i32],
+            "ss_model_set_wait_limit": [vp, C.c_uint32],
             "ss_speculative_step": [vp, vp, vp, vp, i32, C.c_float, C.c_float, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp],
             "ss_profile_read": [vp, i32, vp, vp],
             "ss_probe_read_bandwidth": [vp, C.c_size_t, i32, vp, vp, vp],
@@ -391,6 +393,10 @@ def ss_probe_read_bandwidth(buf, iters=20, stream=None):
 
 def ss_model_set_persistent_options(model: Model, workgroups: int = 0, data_sync: bool = True):
     _check(lib().ss_model_set_persistent_options(model.handle, int(workgroups), int(bool(data_sync))))
+
+
+def ss_model_set_wait_limit(model: Model, polls: int):
+    _check(lib().ss_model_set_wait_limit(model.handle, int(polls)))
 
 
 def ss_profile_enable(model: Model, on: bool):

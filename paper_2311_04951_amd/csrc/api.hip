@@ -73,6 +73,7 @@ struct ss_model {
     int mega_rows = 0;              // most rows (batch * M) a persistent launch takes
     int mega_min_units = 0;         // fewest ownership units of any GEMM phase: data synchronisation needs a grid no larger
     bool data_sync = true;          // persistent kernel: self-validating activations instead of barriers where possible
+    unsigned spin_limit = 1u << 20; // persistent kernel: polls of a bounded wait before the workgroup gives up
     MegaPhase *prog_full = nullptr; // [embed, layers, head, len]
     MegaPhase *prog_nohead = nullptr; // [embed, layers, len]
     int n_full = 0, n_nohead = 0;
@@ -614,6 +615,13 @@ extern "C" int ss_model_set_persistent_options(ss_model *m, int32_t workgroups, 
     return SS_OK;
 }
 
+extern "C" int ss_model_set_wait_limit(ss_model *m, uint32_t polls) {
+    if (!m) return fail(SS_EINVAL, "ss_model_set_wait_limit: NULL model");
+    if (polls < 1) return fail(SS_EINVAL, "ss_model_set_wait_limit: at least one poll");
+    m->spin_limit = polls;
+    return SS_OK;
+}
+
 // One launch of the persistent kernel: [embedding | given rows] -> layers -> [LM head] -> lengths += M.
 static int run_persistent(ss_model *m, ss_kv_cache *kv, const int32_t *tokens, float *h, int batch, int M, float *logits,
                           int head_rows, int head_row0, int head_stride, hipStream_t st) {
@@ -653,7 +661,7 @@ static int run_persistent(ss_model *m, ss_kv_cache *kv, const int32_t *tokens, f
     P.part_o = m->part_o; P.part_m = m->part_m; P.part_l = m->part_l; P.attn_cnt = m->attn_cnt;
     P.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)c.head_dim));
     P.arrive = m->arrive; P.abort_flag = m->abort_flag; P.epoch_base = m->epoch;
-    P.spin_limit = 1u << 20;
+    P.spin_limit = m->spin_limit;
     P.status = m->status;
     P.zeros = m->zeros;
     m->epoch += (unsigned)P.n_phases + 1;

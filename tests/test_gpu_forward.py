@@ -304,3 +304,30 @@ def test_single_layer_of_13b_and_3b_width_matches_oracle(d, H, F, persistent):
     assert maxabs(got, ref) < 2e-2
     assert maxabs(got, ref) < 2e-3
     assert sv.ss_device_status(gm) == 0
+
+
+@pytest.mark.parametrize("path", [True, "grid8"])
+def test_a_wait_that_gives_up_is_reported_and_the_model_recovers(path):
+    """Every wait of the persistent kernel is bounded.  With the bound set to a single poll the kernel gives
+    up at its first unsatisfied wait (and still ends normally); the status word says so, the synchronisation
+    state is reset, and the same model then reproduces its earlier result bit for bit."""
+    shape = si.DecoderShape(3, 256, 4, 64, 688, 1000, dtype="bf16")
+    gm = sv.Model(shape, weights_to_device(si.decoder_weights(shape, seed=12)), max_rows=16, max_pos=256)
+    set_path(gm, path)
+    toks = si.token_ids(12, "toks", (25,), shape.vocab).numpy().astype(np.int32)
+    kv = sv.KVCache(gm, 1, 128)
+    _gpu_forward_chunks(gm, kv, toks[:20], [16, 4])
+    rows = torch.tensor(toks[None, 20:], device=dev())
+    ref = sv.ss_verify_forward(gm, kv, rows, 5).clone()
+    assert sv.ss_device_status(gm) == 0
+    sv.ss_model_set_wait_limit(gm, 1)
+    sv.ss_kv_cache_set_len(kv, [20])
+    sv.ss_verify_forward(gm, kv, rows, 5)             # enqueues; the kernel leaves early
+    assert sv.ss_device_status(gm) & 2                # ... and says so; the call's results are not used
+    sv.ss_model_set_wait_limit(gm, 1 << 20)
+    sv.ss_kv_cache_set_len(kv, [20])
+    again = sv.ss_verify_forward(gm, kv, rows, 5)
+    assert sv.ss_device_status(gm) == 0
+    assert torch.equal(again, ref)
+    with pytest.raises(sv.SpecVerifyError):
+        sv.ss_model_set_wait_limit(gm, 0)
