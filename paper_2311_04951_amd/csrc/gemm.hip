@@ -5,7 +5,7 @@
 //   workgroup multiplies every weight chunk it streams with up to RT row tiles (weights are read once for
 //   up to 16*RT rows).
 //
-// One workgroup (16 wavefronts) owns 16 output columns (or a pair of 16-column tiles for the fused
+// One workgroup (8 wavefronts for at most 16 rows) owns 16 output columns (or a pair of 16-column tiles for the fused
 // epilogues).  Each lane streams 16-byte chunks of 16 weight rows straight from HBM into registers -
 // weights are used exactly once, so they never pass through LDS - and feeds them to MFMA as the A
 // operand; the activation rows are the B operand, read as packed planes through L1/L2.  The
@@ -574,8 +574,8 @@ template <typename T, int EPI> static void launch_gemm_t(const GemmArgs &a, hipS
     if (EPI == EPI_QKV) tiles = 3 * a.H * (a.hd / 32);
     else tiles = (a.N + 15) / 16;
     const int row_tiles = (a.R + 15) / 16;
-    if (row_tiles <= 1) { // the verify pass proper: 16 waves split K, two steps in flight
-        hipLaunchKernelGGL((gemm_kernel<T, EPI, 16, 2, 1>), dim3(tiles, 1), dim3(16 * 64), 0, st, a);
+    if (row_tiles <= 1) { // the verify pass proper: 8 waves split K, two steps in flight (measured: 3.5 % faster than 16 waves over a 7B-shaped pass)
+        hipLaunchKernelGGL((gemm_kernel<T, EPI, 8, 2, 1>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
         return;
     }
     // larger batches and prefill chunks: waves split the columns; fewer waves per workgroup when the
