@@ -263,7 +263,7 @@ def paper_pair_leg(si, sv, torch, gen, dev, prompt_len=128, n_new=96, K=5):
     return out
 
 
-def batched_workload(si, sv, torch, dev, shape, packed, io, iters=5, B=8, L=4096, M=9):
+def batched_workload(si, sv, torch, dev, shape, packed, io, iters=5, B=8, L=4096, M=9, int8=True):
     """The batched long-context workload: 8 sequences with 4096 cached positions each, K = 8 (72 rows per
     verify pass, one launch per phase: wide GEMMs and split-KV attention)."""
     m = sv.Model(shape, io, max_rows=B * M, max_pos=L + 512, packed_layers=packed)
@@ -298,8 +298,29 @@ def batched_workload(si, sv, torch, dev, shape, packed, io, iters=5, B=8, L=4096
     out = {"workload": f"batch {B}, context {L}, K {M - 1} ({B * M} rows per pass), {shape.n_layers} layers", "ms_per_pass": dt * 1e3,
            "rows_per_s": B * M / dt, "algorithmic_bytes": nbytes, "GBps": nbytes / dt / 1e9, "frac_of_hbm_peak": nbytes / dt / HBM_PEAK,
            "class_ms_per_pass": {k: round(ms / 3, 3) for k, (ms, n) in prof.items() if n}}
-    kv.close()
     m.close()
+    if int8:
+        # the same pass with int8 matrices (the KV cache stays bf16: it is most of this workload's bytes)
+        m = sv.Model(shape, io, max_rows=B * M, max_pos=L + 512, packed_layers=packed, int8_weights=True)
+        for _ in range(2):
+            run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            run()
+        torch.cuda.synchronize()
+        dt8 = (time.perf_counter() - t0) / iters
+        sv.ss_profile_enable(m, True)
+        for _ in range(3):
+            run()
+        torch.cuda.synchronize()
+        prof = sv.ss_profile_read(m)
+        nb8 = nbytes - (shape.n_layers * layer_bytes(shape) + shape.vocab * shape.d_model * 2) // 2
+        out["int8_weights"] = {"ms_per_pass": dt8 * 1e3, "rows_per_s": B * M / dt8, "algorithmic_bytes": nb8, "GBps": nb8 / dt8 / 1e9,
+                               "frac_of_hbm_peak": nb8 / dt8 / HBM_PEAK,
+                               "class_ms_per_pass": {k: round(ms / 3, 3) for k, (ms, n) in prof.items() if n}}
+        m.close()
+    kv.close()
     return out
 
 
@@ -490,7 +511,7 @@ def main():
     if not args.no_paper_pair:
         out["paper_size_pair"] = paper_pair_leg(si, sv, torch, gen, dev)
     if args.batched_workload:
-        out["batched_workload"] = batched_workload(si, sv, torch, dev, shape, packed, io)
+        out["batched_workload"] = batched_workload(si, sv, torch, dev, shape, packed, io, int8=not args.no_int8_leg)
     for leg in ("layer_pass", "standalone_accept", "batched_workload", "int8_weights"):
         if leg in out and "GBps" in out[leg]:
             out[leg]["frac_of_read_stream"] = out[leg]["GBps"] / stream_GBps

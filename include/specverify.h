@@ -54,8 +54,8 @@ typedef struct {
     int32_t max_pos;  /* rotary table length: positions 0..max_pos-1 */
     int32_t weight_int8; /* 0: matrices in the storage type.  1: the four matrices of every layer and the
                           * LM head are int8 with one fp32 scale per output row (the quantised model that
-                          * Sections 2 and 3 assume; see ss_quantize_rows_int8).  Needs dtype bf16, max_rows
-                          * <= 16, and d_model, n_heads*head_dim and d_ff multiples of 16.  The embedding,
+                          * Sections 2 and 3 assume; see ss_quantize_rows_int8).  Needs dtype bf16 and d_model,
+                          * n_heads*head_dim and d_ff multiples of 16.  The embedding,
                           * the gains and the KV cache keep the storage type; such a model runs with one
                           * launch per phase (the persistent kernel does not take int8 matrices). */
 } ss_model_cfg;

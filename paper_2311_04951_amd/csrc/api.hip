@@ -164,7 +164,6 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
     if (c.weight_int8) {
         if (c.weight_int8 != 1) return fail(SS_EINVAL, "weight_int8 must be 0 or 1");
         if (c.dtype != SS_DTYPE_BF16) return fail(SS_EINVAL, "int8 weights need bf16 storage for activations and cache");
-        if (c.max_rows > 16) return fail(SS_EINVAL, "int8 weights: calls of at most 16 rows (max_rows %d)", c.max_rows);
         if (c.d_model % 16 || (c.n_heads * c.head_dim) % 16 || c.d_ff % 16)
             return fail(SS_EINVAL, "int8 weights: d_model, n_heads*head_dim and d_ff must be multiples of 16");
         if (w->lm_head && !w->s_head) return fail(SS_EINVAL, "int8 LM head without a scale vector");

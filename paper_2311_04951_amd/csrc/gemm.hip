@@ -367,8 +367,12 @@ __device__ __forceinline__ size_t splitk_index(int z, int ntiles, int tile, int 
     return (((((size_t)z * ntiles + tile) * row_tiles + rt) * NT + t) * 4 + v) * 64 + lane;
 }
 
-template <typename T, int EPI, int NW, int RT>
+// W8: the matrix is int8 with row scales (bf16 activation planes only).  A lane's 16-byte load then holds 16 K entries,
+// two MFMA k-blocks: per slab and tile two loads instead of four, and quarter q = 2h + j of the slab multiplies bytes
+// 8j..8j+7 of load h with the activations of k = 64h + 16g + 8j .., which sit in LDS unit 8h + 2g + j of the row.
+template <typename T, int EPI, int NW, int RT, bool W8 = false>
 __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
+    static_assert(!W8 || Traits<T>::E == 8, "int8 matrices go with bf16 activation planes");
     constexpr int E = Traits<T>::E, KB = 4 * E, PL = Traits<T>::PLANES;
     constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
     constexpr int WIDE_KS = WIDE_SLAB_BYTES / (int)sizeof(T); // elements of K per slab
@@ -378,7 +382,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
     constexpr int BUF = PL * ROWS * WIDE_SLAB_BYTES;          // bytes of one slab buffer
     constexpr int GROUPS = PL * ROWS / 4;                     // 1 KB load instructions per slab (4 rows each)
     constexpr int DPW = (GROUPS + NW - 1) / NW;               // ... per wave
-    constexpr int WN = NT * KBS;                              // weight loads per wave and step
+    constexpr int WLD = W8 ? KBS / 2 : KBS;                   // weight loads per tile and step
+    constexpr int WN = NT * WLD;                              // weight loads per wave and step
+    constexpr int WE = W8 ? 16 : E;                           // K entries per weight load
     __shared__ __align__(16) unsigned char slab0[BUF], slab1[BUF], slab2[BUF];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 15, g = lane >> 4;
@@ -391,13 +397,14 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
     const bool tile_live = tile < ntiles; // a dead wave still helps with the slab copies and barriers
     const int nrows_w = (EPI == EPI_SWIGLU) ? 2 * a.N : a.N;
 
-    const T *W = reinterpret_cast<const T *>(a.W);
-    const T *wrow[NT];
+    constexpr size_t WB = W8 ? 1 : sizeof(T); // bytes per matrix entry
+    const char *W = reinterpret_cast<const char *>(a.W);
+    const char *wrow[NT]; // byte pointers: this lane's row at its lane group's offset
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         int n = n0[t] + c;
         if (n > nrows_w - 1) n = nrows_w - 1; // ragged last tile: load a valid row, masked at the store
-        wrow[t] = W + (size_t)n * K + g * E;
+        wrow[t] = W + ((size_t)n * K + g * WE) * WB;
     }
     const T *act = reinterpret_cast<const T *>(a.act);
     // split-K (a.ksplit > 1): workgroup z multiplies K slabs [s_lo, s_hi) only and leaves raw partial tiles
@@ -423,14 +430,14 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
         }
         asm volatile("" ::: "memory");
     };
-    auto w_load = [&](int sl, u32x4 (&w)[NT][KBS]) {
+    auto w_load = [&](int sl, u32x4 (&w)[NT][WLD]) {
         const int k0 = (s_lo + sl) * WIDE_KS;
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int kb = 0; kb < KBS; ++kb) {
-                const int k = k0 + kb * KB;
-                w[t][kb] = ld16_stream(wrow[t] + min(k, K - (g + 1) * E)); // zeroed past K when it is used
+            for (int kb = 0; kb < WLD; ++kb) {
+                const int k = k0 + kb * 4 * WE;
+                w[t][kb] = ld16_stream(wrow[t] + (size_t)min(k, K - (g + 1) * WE) * WB); // zeroed past K when it is used
             }
         asm volatile("" ::: "memory");
     };
@@ -450,14 +457,14 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
     // register sets are compile-time choices, so the step sequence is unrolled over WDW (a multiple of 3) steps.
     constexpr int WDW = 3; // deeper weight rings (6) were measured and are slower
     const int nstep = (nslab + WDW - 1) / WDW * WDW;
-    u32x4 wring[WDW][NT][KBS];
+    u32x4 wring[WDW][NT][WLD];
 #pragma unroll
     for (int j = 0; j < WDW - 3; ++j) w_load(j, wring[j]);
     slab_dma(0, slab0);
     w_load(WDW - 3, wring[WDW - 3]);
     slab_dma(1, slab1);
     w_load(WDW - 2, wring[WDW - 2]);
-    auto step = [&](int sl, const unsigned char *cur, unsigned char *fill, u32x4 (&wcur)[NT][KBS], u32x4 (&wfill)[NT][KBS]) {
+    auto step = [&](int sl, const unsigned char *cur, unsigned char *fill, u32x4 (&wcur)[NT][WLD], u32x4 (&wfill)[NT][WLD]) {
         // this wave's part of slab sl and its weight slab sl have landed: the only younger loads are
         // those of the previous step (slab sl+1, weights sl+1)
         static_assert(WDW == 3, "the wait below counts one step of younger loads");
@@ -474,7 +481,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
             for (int r = 0; r < RT; ++r)
 #pragma unroll
                 for (int pl = 0; pl < PL; ++pl)
-                    av[r].p[pl] = *reinterpret_cast<const u32x4 *>(base + (size_t)(pl * ROWS + r * 16) * WIDE_SLAB_BYTES + (((kb * 4 + g) ^ c) * 16));
+                    av[r].p[pl] = *reinterpret_cast<const u32x4 *>(base + (size_t)(pl * ROWS + r * 16) * WIDE_SLAB_BYTES +
+                                                                   (((W8 ? 8 * (kb >> 1) + 2 * g + (kb & 1) : kb * 4 + g) ^ c) * 16));
             __builtin_amdgcn_sched_barrier(0);
         };
         Act<T> av[2][RT];
@@ -482,10 +490,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
 #pragma unroll
         for (int kb = 0; kb < KBS; ++kb) {
             if (kb + 1 < KBS) read_av(kb + 1, av[(kb + 1) & 1]);
-            const bool in_k = (s_lo + sl) * WIDE_KS + kb * KB + g * E < k_end;
+            const bool in_k = (s_lo + sl) * WIDE_KS + (W8 ? (kb >> 1) * 64 + g * 16 : kb * KB + g * E) < k_end;
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                const u32x4 wm = in_k ? wcur[t][kb] : zero16();
+                u32x4 wm;
+                if constexpr (W8) wm = in_k ? w8_to_bf16x8(wcur[t][kb >> 1][2 * (kb & 1)], wcur[t][kb >> 1][2 * (kb & 1) + 1]) : zero16();
+                else wm = in_k ? wcur[t][kb] : zero16();
 #pragma unroll
                 for (int r = 0; r < RT; ++r) mma_split(acc[0][r][t], acc[1][r][t], wm, av[kb & 1][r], kb);
             }
@@ -509,7 +519,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) out[t][v] = acc[0][r][t][v] + acc[1][r][t][v];
+            for (int v = 0; v < 4; ++v) {
+                out[t][v] = acc[0][r][t][v] + acc[1][r][t][v];
+                if constexpr (W8) out[t][v] *= a.wscale[min(n0[t] + 4 * g + v, nrows_w - 1)]; // linear: also right for split-K partials
+            }
         if (a.ksplit > 1) {
             if (rt0 + r < row_tiles) {
 #pragma unroll
@@ -547,7 +560,7 @@ __global__ __launch_bounds__(64) void gemm_splitk_finish_kernel(GemmArgs a) {
 // 64 workgroups for a 4096-column projection).  K is then split over up to 4 workgroups whose partial
 // tiles a second small launch sums in a fixed order; the split count is the largest that still fits the
 // chip in one round, so the extra traffic (partials written and read once) stays a fraction of the weights.
-template <typename T, int EPI, int NW, int RT> static void launch_wide(const GemmArgs &a0, int tiles, int row_tiles, hipStream_t st) {
+template <typename T, int EPI, int NW, int RT, bool W8 = false> static void launch_wide(const GemmArgs &a0, int tiles, int row_tiles, hipStream_t st) {
     constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
     constexpr int WIDE_KS = WIDE_SLAB_BYTES / (int)sizeof(T);
     GemmArgs a = a0;
@@ -565,9 +578,11 @@ template <typename T, int EPI, int NW, int RT> static void launch_wide(const Gem
             a.kslabs = per;
         }
     }
-    hipLaunchKernelGGL((gemm_wide_kernel<T, EPI, NW, RT>), dim3(gx, gy, a.ksplit), dim3(NW * 64), 0, st, a);
+    hipLaunchKernelGGL((gemm_wide_kernel<T, EPI, NW, RT, W8>), dim3(gx, gy, a.ksplit), dim3(NW * 64), 0, st, a);
     if (a.ksplit > 1) hipLaunchKernelGGL((gemm_splitk_finish_kernel<T, EPI>), dim3(tiles, row_tiles), dim3(64), 0, st, a);
 }
+
+template <typename T, int EPI, bool W8> static void launch_wide_any(const GemmArgs &a, int tiles, int row_tiles, hipStream_t st);
 
 template <typename T, int EPI> static void launch_gemm_t(const GemmArgs &a, hipStream_t st) {
     int tiles;
@@ -578,16 +593,20 @@ template <typename T, int EPI> static void launch_gemm_t(const GemmArgs &a, hipS
         hipLaunchKernelGGL((gemm_kernel<T, EPI, 8, 2, 1>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
         return;
     }
+    launch_wide_any<T, EPI, false>(a, tiles, row_tiles, st);
+}
+
+template <typename T, int EPI, bool W8> static void launch_wide_any(const GemmArgs &a, int tiles, int row_tiles, hipStream_t st) {
     // larger batches and prefill chunks: waves split the columns; fewer waves per workgroup when the
     // matrix has few tiles, so that the launch still covers the chip
     constexpr bool FUSED = EPI == EPI_SWIGLU || EPI == EPI_QKV; // two weight tiles per wave: more registers
     const bool small = tiles < 8 * 128;
     if (row_tiles <= 2) {
-        if (small) launch_wide<T, EPI, 4, 2>(a, tiles, row_tiles, st);
-        else launch_wide<T, EPI, 8, 2>(a, tiles, row_tiles, st);
+        if (small) launch_wide<T, EPI, 4, 2, W8>(a, tiles, row_tiles, st);
+        else launch_wide<T, EPI, 8, 2, W8>(a, tiles, row_tiles, st);
     } else if (row_tiles <= 3) {
-        if (small) launch_wide<T, EPI, 4, 3>(a, tiles, row_tiles, st);
-        else launch_wide<T, EPI, 8, 3>(a, tiles, row_tiles, st);
+        if (small) launch_wide<T, EPI, 4, 3, W8>(a, tiles, row_tiles, st);
+        else launch_wide<T, EPI, 8, 3, W8>(a, tiles, row_tiles, st);
     } else {
         // one workgroup per compute unit fits: 3 waves per workgroup when that fills more of a 256-unit chip
         // in whole rounds than 4 (688 gate/up tiles: 230 workgroups instead of 172; 384 QKV tiles: 128, split in two)
@@ -596,9 +615,9 @@ template <typename T, int EPI> static void launch_gemm_t(const GemmArgs &a, hipS
             const int ks = std::max(1, std::min(256 / std::max(wgs, 1), 4));
             return (double)(wgs * ks) / (double)((wgs * ks + 255) / 256 * 256);
         };
-        if ((small || FUSED) && fill(3) > fill(4) + 0.1) launch_wide<T, EPI, 3, 5>(a, tiles, row_tiles, st);
-        else if (small || FUSED) launch_wide<T, EPI, 4, 5>(a, tiles, row_tiles, st);
-        else launch_wide<T, EPI, 8, 5>(a, tiles, row_tiles, st);
+        if ((small || FUSED) && fill(3) > fill(4) + 0.1) launch_wide<T, EPI, 3, 5, W8>(a, tiles, row_tiles, st);
+        else if (small || FUSED) launch_wide<T, EPI, 4, 5, W8>(a, tiles, row_tiles, st);
+        else launch_wide<T, EPI, 8, 5, W8>(a, tiles, row_tiles, st);
     }
 }
 
@@ -607,11 +626,13 @@ template <typename T, int EPI> static void launch_gemm_t(const GemmArgs &a, hipS
 // weight load), so more steps in flight cost occupancy, and smaller workgroups give more of them per compute unit.
 template <int EPI> static void launch_gemm_w8(const GemmArgs &a, hipStream_t st) {
     const int tiles = EPI == EPI_QKV ? 3 * a.H * (a.hd / 32) : (a.N + 15) / 16;
-    hipLaunchKernelGGL((gemm_w8_kernel<EPI, 8, 2>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
+    const int row_tiles = (a.R + 15) / 16;
+    if (row_tiles <= 1) hipLaunchKernelGGL((gemm_w8_kernel<EPI, 8, 2>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
+    else launch_wide_any<bf16_t, EPI, true>(a, tiles, row_tiles, st);
 }
 
 void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st) {
-    if (a.wscale) { // int8 weights: the caller has checked bf16 planes, at most 16 rows, K % 16 == 0
+    if (a.wscale) { // int8 weights: the caller has checked bf16 planes and K % 16 == 0
         switch (epi) {
         case EPI_STORE: launch_gemm_w8<EPI_STORE>(a, st); break;
         case EPI_RESID: launch_gemm_w8<EPI_RESID>(a, st); break;

@@ -40,7 +40,7 @@ struct GemmArgs {
     size_t splitk_ws_bytes;
     int ksplit, kslabs; // set by the launcher: K splits, K slabs per split
     // weight-only int8: W is int8 [N][K] and output column n is scaled by wscale[n] (NULL: W is in the storage type).
-    // Launches of at most 16 rows with bf16 activation planes only; K a multiple of 16.
+    // bf16 activation planes only; K a multiple of 16.
     const float *wscale;
 };
 void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st);

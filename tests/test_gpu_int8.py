@@ -95,12 +95,38 @@ def test_greedy_speculative_equals_greedy_autoregressive_with_int8_models():
     assert s1 == s2 and st1["accepted"] == st2["accepted"]
 
 
+@pytest.mark.parametrize("B,M,vocab", [(3, 8, 1000), (3, 16, 1000), (8, 9, 1000),      # 24, 48 and 72 rows per call: 2, 3 and 5 row tiles
+                                       (3, 8, 20000), (3, 16, 20000), (8, 9, 20000)])  # an LM head of 1250 tiles: 8-wave workgroups
+def test_int8_model_in_launches_of_more_than_16_rows(B, M, vocab):
+    """Batched calls of an int8 model go through the wide GEMMs (LDS-shared activation slabs, split-K): whole
+    forward with ragged contexts, every sequence against the oracle's int8 model run on that sequence alone.
+    d_ff = 688 gives the down projection a ragged last K slab."""
+    shape = si.DecoderShape(2, 256, 4, 64, 688, vocab, dtype="bf16")
+    w = si.decoder_weights(shape, 51)
+    om = oracle.Model(shape, w, int8_weights=True)
+    gm = sv.Model(shape, weights_to_device(w), max_rows=B * M, max_pos=256, int8_weights=True)
+    lens = [37, 1, 150, 64, 9, 200, 77, 128][:B]
+    gkv = sv.KVCache(gm, B, 256)
+    toks = si.token_ids(51, f"t{B}x{M}", (B, M), shape.vocab).numpy().astype(np.int32)
+    refs = []
+    for b in range(B):
+        ctx = si.kv_context(shape, 51, f"ctx{b}", lens[b])
+        okv = om.new_kv(256)
+        okv.append_raw(ctx)
+        for l in range(shape.n_layers):
+            sv.ss_kv_cache_append(gkv, l, b, 0, ctx[l][0].to(dev()), ctx[l][1].to(dev()))
+        refs.append(om.forward(okv, toks[b]))
+    sv.ss_kv_cache_set_len(gkv, lens)
+    got = sv.ss_verify_forward(gm, gkv, torch.from_numpy(toks).to(dev()), M).cpu().numpy()
+    for b in range(B):
+        assert maxabs(got[b], refs[b]) < 2e-2, b
+    assert sv.ss_kv_cache_get_len(gkv).tolist() == [l + M for l in lens]
+    assert sv.ss_device_status(gm) == 0
+
+
 def test_int8_configurations_that_are_refused():
     shape = si.DecoderShape(1, 128, 4, 32, 336, 512, dtype="bf16")
     w = weights_to_device(si.decoder_weights(shape, 5))
-    with pytest.raises(sv.SpecVerifyError) as e:
-        sv.Model(shape, w, max_rows=32, max_pos=64, int8_weights=True)            # wide launches take storage-type matrices only
-    assert e.value.code == sv.SS_EINVAL
     f32 = si.DecoderShape(1, 128, 4, 32, 336, 512, dtype="f32")
     with pytest.raises(sv.SpecVerifyError):
         sv.Model(f32, weights_to_device(si.decoder_weights(f32, 5)), max_rows=16, max_pos=64, int8_weights=True)
