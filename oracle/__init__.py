@@ -62,6 +62,9 @@ def lib():
         L.orc_quantize_rows_int8.argtypes = [vp, i32, i32, i32, vp, vp]
         L.orc_linear_w8.argtypes = [vp, vp, vp, i32, i32, vp]
         L.orc_model_set_scales.argtypes = [vp, i32, C.POINTER(vp)]
+        L.orc_quantize_rows_int4.argtypes = [vp, i32, i32, i32, i32, vp, vp]
+        L.orc_linear_w4.argtypes = [vp, vp, vp, i32, i32, i32, vp]
+        L.orc_model_set_wbits.argtypes = [vp, i32]
         L.orc_top_p_filter.argtypes = [vp, i32, f32, vp]
         L.orc_f32_to_bf16.restype = C.c_uint16
         L.orc_f32_to_bf16.argtypes = [f32]
@@ -123,6 +126,29 @@ def quantize_rows_int8(W, is_bf16=False):
     s = np.empty(N, dtype=np.float32)
     lib().orc_quantize_rows_int8(_p(Ws), int(is_bf16), N, K, _p(q), _p(s))
     return q, s
+
+
+W4_GROUP = 128
+
+
+def quantize_rows_int4(W, is_bf16=False, group=W4_GROUP):
+    """Weight-only int4 with group scales of a matrix [N, K] in the storage type -> (packed uint8 [N, K/2],
+    scale fp32 [K/group, N])."""
+    Ws = _storage(W, is_bf16)
+    N, K = Ws.shape
+    assert K % group == 0 and group % 2 == 0
+    q = np.zeros((N, K // 2), dtype=np.uint8)
+    s = np.empty((K // group, N), dtype=np.float32)
+    lib().orc_quantize_rows_int4(_p(Ws), int(is_bf16), N, K, group, _p(q), _p(s))
+    return q, s
+
+
+def linear_w4(q, scale, x, group=W4_GROUP):
+    q = np.ascontiguousarray(q, dtype=np.uint8)
+    scale, x = _f32(scale), _f32(x)
+    y = np.empty(q.shape[0], dtype=np.float32)
+    lib().orc_linear_w4(_p(q), _p(scale), _p(x), q.shape[0], q.shape[1] * 2, group, _p(y))
+    return y
 
 
 def linear_w8(q, scale, x):
@@ -212,23 +238,29 @@ class Model:
     vocab, rope_base, rms_eps, dtype ("bf16" | "f32"); `weights` is the dict layout of
     seeded_inputs.decoder_weights (torch tensors or ndarrays; bf16 as uint16 bits)."""
 
-    def __init__(self, shape, weights, int8_weights=False):
-        """int8_weights: the seven matrices of every layer and the LM head are quantised row-wise
-        (quantize_rows_int8) from the given weights; embedding, gains and cache keep the storage type."""
+    def __init__(self, shape, weights, int8_weights=False, int4_weights=False):
+        """int8_weights / int4_weights: the seven matrices of every layer and the LM head are quantised
+        (quantize_rows_int8: one scale per row; quantize_rows_int4: groups of 128 along K) from the given
+        weights; embedding, gains and cache keep the storage type."""
         self.shape = shape
-        self.int8_weights = bool(int8_weights)
+        assert not (int8_weights and int4_weights)
+        self.int4_weights = bool(int4_weights)
+        self.int8_weights = bool(int8_weights) or self.int4_weights   # "quantised": the code below is shared
+        quant = quantize_rows_int4 if self.int4_weights else quantize_rows_int8
         self.is_bf16 = shape.dtype == "bf16"
         L = lib()
         self._keep = []
         self.h = L.orc_model_new(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim,
                                  shape.d_ff, shape.vocab, shape.rope_base, shape.rms_eps,
                                  int(self.is_bf16))
+        if self.int4_weights:
+            L.orc_model_set_wbits(self.h, 4)
         for l, lw in enumerate(weights["layers"]):
             ws = [self._hold(_storage(lw[n], self.is_bf16)) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd")]
             gs = [self._hold(_f32(lw[n].detach().cpu().numpy() if hasattr(lw[n], "detach") else lw[n]))
                   for n in ("g1", "g2")]
             if self.int8_weights:
-                qs = [quantize_rows_int8(w, self.is_bf16) for w in ws]
+                qs = [quant(w, self.is_bf16) for w in ws]
                 ws = [self._hold(q) for q, _ in qs]
                 sc = [self._hold(s_) for _, s_ in qs]
             L.orc_model_set_layer(self.h, l, *[_p(a) for a in ws + gs])
@@ -240,7 +272,7 @@ class Model:
             emb = self._hold(_storage(weights["embed"], self.is_bf16))
             head = self._hold(_storage(weights["lm_head"], self.is_bf16))
             if self.int8_weights:
-                hq, hs = quantize_rows_int8(head, self.is_bf16)
+                hq, hs = quant(head, self.is_bf16)
                 head = self._hold(hq)
                 self._hold(hs)
                 L.orc_model_set_scales(self.h, -1, (C.c_void_p * 1)(hs.ctypes.data))

@@ -126,6 +126,58 @@ void orc_quantize_rows_int8(const void *W, int is_bf16, int N, int K, int8_t *q,
     }
 }
 
+/* Weight-only int4 with group scales (the second, coarser reading of the same "quantized model"): along K, groups of
+ * `group` consecutive entries of a row share one fp32 scale, s = fl32(max |w| / 7) over the group (1 for an all-zero
+ * group), and q = nearest integer (ties to even) of fl32(w / s), clamped to [-7, 7].  Packing: byte b of a row holds
+ * entry 2b in its low and entry 2b+1 in its high four bits (two's complement); scales are stored group-major,
+ * scale[j][n] for group j of row n.  K must be a multiple of `group`, `group` even. */
+void orc_quantize_rows_int4(const void *W, int is_bf16, int N, int K, int group, uint8_t *q, float *scale) {
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        size_t base = (size_t)n * (size_t)K;
+        for (int j = 0; j < K / group; ++j) {
+            float amax = 0.0f;
+            for (int k = j * group; k < (j + 1) * group; ++k) {
+                float a = fabsf((float)st_get(W, is_bf16, base + k));
+                if (a > amax) amax = a;
+            }
+            volatile float sv = amax > 0.0f ? amax / 7.0f : 1.0f;
+            float sc = sv;
+            scale[(size_t)j * (size_t)N + n] = sc;
+            for (int k = j * group; k < (j + 1) * group; ++k) {
+                volatile float r = (float)st_get(W, is_bf16, base + k) / sc;
+                float t = rintf(r);
+                if (t > 7.0f) t = 7.0f;
+                if (t < -7.0f) t = -7.0f;
+                uint8_t nib = (uint8_t)((int)t & 0xf);
+                uint8_t *byte = &q[(base + k) / 2];
+                if (k & 1) *byte = (uint8_t)((*byte & 0x0f) | (nib << 4));
+                else *byte = (uint8_t)((*byte & 0xf0) | nib);
+            }
+        }
+    }
+}
+
+static inline int nibble_at(const uint8_t *q, size_t idx) {
+    int v = (q[idx / 2] >> ((idx & 1) ? 4 : 0)) & 0xf;
+    return v >= 8 ? v - 16 : v;
+}
+
+/* y_n = sum_j scale[j][n] * sum_{k in group j} q[n][k] x_k */
+void orc_linear_w4(const uint8_t *q, const float *scale, const float *x, int N, int K, int group, float *y) {
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        double acc = 0.0;
+        size_t base = (size_t)n * (size_t)K;
+        for (int j = 0; j < K / group; ++j) {
+            double part = 0.0;
+            for (int k = j * group; k < (j + 1) * group; ++k) part += (double)nibble_at(q, base + k) * (double)x[k];
+            acc += (double)scale[(size_t)j * (size_t)N + n] * part;
+        }
+        y[n] = (float)acc;
+    }
+}
+
 /* y_n = scale_n * sum_k q[n][k] x_k: the linear layer of a weight-only int8 matrix */
 void orc_linear_w8(const int8_t *q, const float *scale, const float *x, int N, int K, float *y) {
 #pragma omp parallel for schedule(static)
@@ -187,7 +239,9 @@ typedef struct {
     const void *embed, *lm_head;
     const float *gf;
     const float *s_head; /* row scales of an int8 LM head, or NULL */
+    int wbits;           /* 8: scales are per row; 4: int4 matrices with group scales of ORC_W4_GROUP entries */
 } orc_model;
+#define ORC_W4_GROUP 128
 
 /* KV cache of ONE sequence (Sections 2, 4.2): per layer, keys (already rotated) and values of
  * every past position, row-major [max_seq][n_heads*head_dim], in the storage type. */
@@ -203,6 +257,7 @@ orc_model *orc_model_new(int n_layers, int d_model, int n_heads, int head_dim, i
     m->n_layers = n_layers; m->d_model = d_model; m->n_heads = n_heads; m->head_dim = head_dim;
     m->d_ff = d_ff; m->vocab = vocab; m->rope_base = rope_base; m->rms_eps = rms_eps;
     m->is_bf16 = is_bf16;
+    m->wbits = 8;
     m->layers = (orc_layer *)calloc((size_t)n_layers, sizeof(orc_layer));
     return m;
 }
@@ -227,10 +282,13 @@ void orc_model_set_scales(orc_model *m, int l, const float *const *s) {
     L->sq = s[0]; L->sk = s[1]; L->sv = s[2]; L->so = s[3]; L->sg = s[4]; L->su = s[5]; L->sd = s[6];
 }
 
-/* one linear layer of the model: int8 with row scales when the scales are there, else the storage type */
-static void lin(const void *W, const float *scale, int is_bf16, const float *x, int N, int K, float *y) {
-    if (scale) orc_linear_w8((const int8_t *)W, scale, x, N, K, y);
-    else orc_linear(W, is_bf16, x, N, K, y);
+void orc_model_set_wbits(orc_model *m, int bits) { m->wbits = bits; }
+
+/* one linear layer of the model: quantised when the scales are there (int8 per row, or int4 in groups), else the storage type */
+static void lin_q(const orc_model *m, const void *W, const float *scale, const float *x, int N, int K, float *y) {
+    if (scale && m->wbits == 4) orc_linear_w4((const uint8_t *)W, scale, x, N, K, ORC_W4_GROUP, y);
+    else if (scale) orc_linear_w8((const int8_t *)W, scale, x, N, K, y);
+    else orc_linear(W, m->is_bf16, x, N, K, y);
 }
 
 void orc_model_free(orc_model *m) {
@@ -336,9 +394,9 @@ int orc_layers_forward(const orc_model *m, orc_kv *c, float *h, int M) {
         for (int i = 0; i < M; ++i) {
             int pos = c->len + i;
             orc_rmsnorm(h + (size_t)i * d, L->g1, d, m->rms_eps, a);
-            lin(L->wq, L->sq, bf, a, W, d, q + (size_t)i * W);
-            lin(L->wk, L->sk, bf, a, W, d, kk);
-            lin(L->wv, L->sv, bf, a, W, d, vv);
+            lin_q(m, L->wq, L->sq, a, W, d, q + (size_t)i * W);
+            lin_q(m, L->wk, L->sk, a, W, d, kk);
+            lin_q(m, L->wv, L->sv, a, W, d, vv);
             for (int hh = 0; hh < H; ++hh) {
                 orc_rope(q + (size_t)i * W + hh * hd, hd, pos, m->rope_base);
                 orc_rope(kk + hh * hd, hd, pos, m->rope_base);
@@ -352,13 +410,13 @@ int orc_layers_forward(const orc_model *m, orc_kv *c, float *h, int M) {
         for (int i = 0; i < M; ++i) {
             float *hi = h + (size_t)i * d;
             attention_row(m, c, l, q + (size_t)i * W, c->len + i, o);
-            lin(L->wo, L->so, bf, o, d, W, t);
+            lin_q(m, L->wo, L->so, o, d, W, t);
             for (int e = 0; e < d; ++e) hi[e] = hi[e] + t[e];
             orc_rmsnorm(hi, L->g2, d, m->rms_eps, a);
-            lin(L->wg, L->sg, bf, a, F, d, gg);
-            lin(L->wu, L->su, bf, a, F, d, uu);
+            lin_q(m, L->wg, L->sg, a, F, d, gg);
+            lin_q(m, L->wu, L->su, a, F, d, uu);
             for (int e = 0; e < F; ++e) gg[e] = (float)(silu((double)gg[e]) * (double)uu[e]);
-            lin(L->wd, L->sd, bf, gg, d, F, t);
+            lin_q(m, L->wd, L->sd, gg, d, F, t);
             for (int e = 0; e < d; ++e) hi[e] = hi[e] + t[e];
         }
     }
@@ -382,7 +440,7 @@ void orc_head(const orc_model *m, const float *h, int M, float *logits) {
     float *a = (float *)malloc(sizeof(float) * (size_t)m->d_model);
     for (int i = 0; i < M; ++i) {
         orc_rmsnorm(h + (size_t)i * m->d_model, m->gf, m->d_model, m->rms_eps, a);
-        lin(m->lm_head, m->s_head, m->is_bf16, a, m->vocab, m->d_model, logits + (size_t)i * m->vocab);
+        lin_q(m, m->lm_head, m->s_head, a, m->vocab, m->d_model, logits + (size_t)i * m->vocab);
     }
     free(a);
 }
