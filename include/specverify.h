@@ -39,6 +39,10 @@ extern "C" {
 #define SS_DTYPE_F32 0
 #define SS_DTYPE_BF16 1
 
+#define SS_QUANT_NONE 0
+#define SS_QUANT_INT8 1
+#define SS_QUANT_INT4_G128 2
+
 #define SS_MAX_ROWS_PER_SEQ 16 /* M = K + 1 query rows per sequence in one call */
 
 typedef void *ss_stream; /* hipStream_t */
@@ -52,12 +56,16 @@ typedef struct {
     int32_t dtype;    /* SS_DTYPE_F32 | SS_DTYPE_BF16 */
     int32_t max_rows; /* largest batch * M any call on this model will pass */
     int32_t max_pos;  /* rotary table length: positions 0..max_pos-1 */
-    int32_t weight_int8; /* 0: matrices in the storage type.  1: the four matrices of every layer and the
-                          * LM head are int8 with one fp32 scale per output row (the quantised model that
-                          * Sections 2 and 3 assume; see ss_quantize_rows_int8).  Needs dtype bf16 and d_model,
-                          * n_heads*head_dim and d_ff multiples of 16.  The embedding,
-                          * the gains and the KV cache keep the storage type; such a model runs with one
-                          * launch per phase (the persistent kernel does not take int8 matrices). */
+    int32_t weight_quant; /* SS_QUANT_NONE: matrices in the storage type.  Otherwise the four matrices of every
+                           * layer and the LM head are quantised weight-only (the quantised model that Sections 2
+                           * and 3 assume; the paper fixes no precision, these are this library's two readings):
+                           * SS_QUANT_INT8: int8, one fp32 scale per output row (ss_quantize_rows_int8); d_model,
+                           *   n_heads*head_dim and d_ff multiples of 16;
+                           * SS_QUANT_INT4_G128: int4, two entries per byte, one fp32 scale per group of 128 entries
+                           *   along K (ss_quantize_rows_int4); those three sizes multiples of 128 and max_rows <= 16.
+                           * Both need dtype bf16.  The embedding, the gains and the KV cache keep the storage type;
+                           * such a model runs with one launch per phase (the persistent kernel streams
+                           * storage-type matrices only). */
 } ss_model_cfg;
 
 /* One layer's weights, dev pointers, row-major [out_features][in_features] in the storage type:
@@ -69,16 +77,18 @@ typedef struct {
 typedef struct {
     const void *wqkv, *wo, *wgu, *wd;
     const float *g1, *g2;
-    const float *sqkv, *so, *sgu, *sd; /* weight_int8 only: dev fp32 row scales [3*H*hd], [d], [2*F], [d]; the
-                                        * matrices above are then int8 with the same shapes.  Else ignored. */
+    const float *sqkv, *so, *sgu, *sd; /* quantised models only: dev fp32 scales of the four matrices above, which are
+                                        * then int8 [rows][K] or packed int4 [rows][K/2] of the same shapes.
+                                        * INT8: one per row ([3*H*hd], [d], [2*F], [d]); INT4_G128: group-major
+                                        * [K/128][rows].  Else ignored. */
 } ss_layer_weights;
 
 typedef struct {
     const void *embed;              /* dev [vocab][d], storage type */
     const ss_layer_weights *layers; /* host array [n_layers] of dev pointers */
     const float *gf;                /* dev [d] fp32 final RMSNorm gain */
-    const void *lm_head;            /* dev [vocab][d], storage type (int8 with weight_int8) */
-    const float *s_head;            /* weight_int8 only: dev fp32 [vocab] row scales of lm_head */
+    const void *lm_head;            /* dev [vocab][d], storage type (quantised models: int8 [vocab][d] / int4 [vocab][d/2]) */
+    const float *s_head;            /* quantised models only: dev fp32 scales of lm_head, [vocab] / [d/128][vocab] */
 } ss_weights;
 
 typedef struct ss_model ss_model;
@@ -111,6 +121,13 @@ int ss_profile_read(ss_model *model, int32_t n_classes, double *total_ms_host, i
  * real numbers scale[n] * q[n][k].  q_dev: dev int8 [rows][K]; scale_dev: dev fp32 [rows]; both the
  * caller's.  Enqueued on `stream`, no host synchronisation.  rows, K >= 1. */
 int ss_quantize_rows_int8(const void *w_dev, int32_t dtype, int64_t rows, int64_t K, int8_t *q_dev, float *scale_dev,
+                          ss_stream stream);
+
+/* Weight-only int4 with group scales of the same matrix: along K, groups of 128 consecutive entries of a row share
+ * scale = fl32(max |w| / 7) over the group (1 for an all-zero group); q = the nearest integer, ties to even, of
+ * fl32(w / scale), in [-7, 7].  q_dev: dev uint8 [rows][K/2], byte b of a row = entry 2b in the low and entry 2b+1
+ * in the high four bits (two's complement); scale_dev: dev fp32 [K/128][rows] (group-major).  K a multiple of 128. */
+int ss_quantize_rows_int4(const void *w_dev, int32_t dtype, int64_t rows, int64_t K, uint8_t *q_dev, float *scale_dev,
                           ss_stream stream);
 
 /* Read-stream probe of the device the caller has made current: a plain kernel that reads

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libspecverify.so")
 SS_OK, SS_EINVAL, SS_ECAPACITY, SS_EHIP = 0, -1, -2, -3
 SS_DTYPE_F32, SS_DTYPE_BF16 = 0, 1
 SS_MAX_ROWS_PER_SEQ = 16
+SS_QUANT_NONE, SS_QUANT_INT8, SS_QUANT_INT4_G128 = 0, 1, 2
 
 EXPORTS = [
     "ss_last_error", "ss_device_status", "ss_model_create", "ss_model_destroy", "ss_kv_cache_alloc",
@@ -26,7 +27,7 @@ EXPORTS = [
     "ss_draft_step", "ss_softmax", "ss_speculative_accept", "ss_speculative_accept_logits",
     "ss_greedy_accept", "ss_profile_enable", "ss_profile_read", "ss_model_set_persistent", "ss_model_set_persistent_options",
     "ss_speculative_step", "ss_probe_read_bandwidth", "ss_quantize_rows_int8", "ss_top_p_filter",
-    "ss_model_set_wait_limit",
+    "ss_model_set_wait_limit", "ss_quantize_rows_int4",
 ]
 
 PROFILE_CLASSES = ["rmsnorm", "qkv_gemm", "attention", "oproj_gemm", "gateup_gemm", "down_gemm", "head_gemm", "other",
@@ -42,7 +43,7 @@ class SpecVerifyError(RuntimeError):
 class _Cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "head_dim", "d_ff", "vocab")] + \
                [("rope_base", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int32),
-                ("max_rows", C.c_int32), ("max_pos", C.c_int32), ("weight_int8", C.c_int32)]
+                ("max_rows", C.c_int32), ("max_pos", C.c_int32), ("weight_quant", C.c_int32)]
 
 
 class _LayerW(C.Structure):
@@ -95,6 +96,7 @@ def lib():
             "ss_profile_read": [vp, i32, vp, vp],
             "ss_probe_read_bandwidth": [vp, C.c_size_t, i32, vp, vp, vp],
             "ss_quantize_rows_int8": [vp, i32, i64, i64, vp, vp, vp],
+            "ss_quantize_rows_int4": [vp, i32, i64, i64, vp, vp, vp],
         }
         for name, args in sig.items():
             getattr(L, name).argtypes = args
@@ -138,13 +140,19 @@ class Model:
     {embed, layers: [{wq, wk, wv, wo, wg, wu, wd, g1, g2}], gf, lm_head} of device tensors.  Packing
     q|k|v and gate|up into the fused matrices the library streams is a one-off copy done here
     (memory plumbing; pass `packed_layers` = [{wqkv, wo, wgu, wd, g1, g2}] to skip it).
-    int8_weights: the library quantises the packed matrices and the LM head row by row
-    (ss_quantize_rows_int8) and the model streams the int8 copies; packed layers that already carry
-    int8 matrices with their scales ({..., sqkv, so, sgu, sd}) and weights["s_head"] are taken as they are."""
+    int8_weights / int4_weights: the library quantises the packed matrices and the LM head
+    (ss_quantize_rows_int8: one scale per row; ss_quantize_rows_int4: groups of 128 along K) and the model
+    streams the quantised copies; packed layers that already carry quantised matrices with their scales
+    ({..., sqkv, so, sgu, sd}) and weights["s_head"] are taken as they are."""
 
-    def __init__(self, shape, weights=None, max_rows=16, max_pos=4096, packed_layers=None, int8_weights=False):
+    def __init__(self, shape, weights=None, max_rows=16, max_pos=4096, packed_layers=None, int8_weights=False,
+                 int4_weights=False):
         self.shape = shape
-        self.int8_weights = bool(int8_weights)
+        if int8_weights and int4_weights:
+            raise ValueError("one quantisation at a time")
+        self.int4_weights = bool(int4_weights)
+        self.int8_weights = bool(int8_weights) or self.int4_weights     # "quantised": the code below is shared
+        quantise = ss_quantize_rows_int4 if self.int4_weights else ss_quantize_rows_int8
         st = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
         if packed_layers is None:
             packed_layers = []
@@ -160,19 +168,19 @@ class Model:
         self.s_head = weights.get("s_head") if weights else None
         wt = st
         if self.int8_weights:
-            wt = torch.int8
+            wt = torch.uint8 if self.int4_weights else torch.int8
             quantised = []
             for pl in packed_layers:
-                if pl["wqkv"].dtype == torch.int8:
+                if pl["wqkv"].dtype == wt:
                     quantised.append(pl)
                     continue
                 ql = {"g1": pl["g1"], "g2": pl["g2"]}
                 for n, sn in (("wqkv", "sqkv"), ("wo", "so"), ("wgu", "sgu"), ("wd", "sd")):
-                    ql[n], ql[sn] = ss_quantize_rows_int8(pl[n])
+                    ql[n], ql[sn] = quantise(pl[n])
                 quantised.append(ql)
             packed_layers = quantised
-            if self.lm_head is not None and self.lm_head.dtype != torch.int8:
-                self.lm_head, self.s_head = ss_quantize_rows_int8(self.lm_head)
+            if self.lm_head is not None and self.lm_head.dtype != wt:
+                self.lm_head, self.s_head = quantise(self.lm_head)
         self.layers = packed_layers
         arr = (_LayerW * max(1, len(packed_layers)))()
         for i, pl in enumerate(packed_layers):
@@ -186,7 +194,7 @@ class Model:
                      _dev(self.s_head, torch.float32 if self.s_head is not None else None))
         cfg = _Cfg(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ff, shape.vocab,
                    shape.rope_base, shape.rms_eps, SS_DTYPE_BF16 if shape.dtype == "bf16" else SS_DTYPE_F32,
-                   max_rows, max_pos, int(self.int8_weights))
+                   max_rows, max_pos, SS_QUANT_INT4_G128 if self.int4_weights else (SS_QUANT_INT8 if self.int8_weights else SS_QUANT_NONE))
         h = C.c_void_p()
         _check(lib().ss_model_create(C.byref(cfg), C.byref(w), C.byref(h)))
         self.handle = h
@@ -378,6 +386,18 @@ def ss_quantize_rows_int8(w, stream=None):
     q = torch.empty(w.shape, dtype=torch.int8, device=w.device)
     s = torch.empty(w.shape[0], dtype=torch.float32, device=w.device)
     _check(lib().ss_quantize_rows_int8(_dev(w), SS_DTYPE_BF16 if w.dtype == torch.bfloat16 else SS_DTYPE_F32, w.shape[0], w.shape[1],
+                                       _dev(q), _dev(s), _stream(stream)))
+    return q, s
+
+
+def ss_quantize_rows_int4(w, stream=None):
+    """int4 with group scales of a device matrix [rows, K] (fp32 or bf16, K % 128 == 0) ->
+    (packed uint8 [rows, K/2], scale fp32 [K/128, rows])."""
+    if w.dim() != 2 or w.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("expected a 2-d fp32 or bf16 matrix")
+    q = torch.empty((w.shape[0], w.shape[1] // 2), dtype=torch.uint8, device=w.device)
+    s = torch.empty((max(1, w.shape[1] // 128), w.shape[0]), dtype=torch.float32, device=w.device)
+    _check(lib().ss_quantize_rows_int4(_dev(w), SS_DTYPE_BF16 if w.dtype == torch.bfloat16 else SS_DTYPE_F32, w.shape[0], w.shape[1],
                                        _dev(q), _dev(s), _stream(stream)))
     return q, s
 

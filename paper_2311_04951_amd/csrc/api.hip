@@ -159,14 +159,16 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
     for (int l = 0; l < c.n_layers; ++l) {
         const ss_layer_weights &L = w->layers[l];
         if (!L.wqkv || !L.wo || !L.wgu || !L.wd || !L.g1 || !L.g2) return fail(SS_EINVAL, "layer %d has a NULL weight", l);
-        if (c.weight_int8 && (!L.sqkv || !L.so || !L.sgu || !L.sd)) return fail(SS_EINVAL, "layer %d of an int8 model has a NULL scale vector", l);
+        if (c.weight_quant && (!L.sqkv || !L.so || !L.sgu || !L.sd)) return fail(SS_EINVAL, "layer %d of a quantised model has a NULL scale array", l);
     }
-    if (c.weight_int8) {
-        if (c.weight_int8 != 1) return fail(SS_EINVAL, "weight_int8 must be 0 or 1");
-        if (c.dtype != SS_DTYPE_BF16) return fail(SS_EINVAL, "int8 weights need bf16 storage for activations and cache");
-        if (c.d_model % 16 || (c.n_heads * c.head_dim) % 16 || c.d_ff % 16)
-            return fail(SS_EINVAL, "int8 weights: d_model, n_heads*head_dim and d_ff must be multiples of 16");
-        if (w->lm_head && !w->s_head) return fail(SS_EINVAL, "int8 LM head without a scale vector");
+    if (c.weight_quant) {
+        if (c.weight_quant != SS_QUANT_INT8 && c.weight_quant != SS_QUANT_INT4_G128) return fail(SS_EINVAL, "weight_quant must be SS_QUANT_NONE, SS_QUANT_INT8 or SS_QUANT_INT4_G128");
+        if (c.dtype != SS_DTYPE_BF16) return fail(SS_EINVAL, "quantised weights need bf16 storage for activations and cache");
+        const int mult = c.weight_quant == SS_QUANT_INT4_G128 ? 128 : 16;
+        if (c.d_model % mult || (c.n_heads * c.head_dim) % mult || c.d_ff % mult)
+            return fail(SS_EINVAL, "quantised weights: d_model, n_heads*head_dim and d_ff must be multiples of %d", mult);
+        if (c.weight_quant == SS_QUANT_INT4_G128 && c.max_rows > 16) return fail(SS_EINVAL, "int4 weights: calls of at most 16 rows (max_rows %d)", c.max_rows);
+        if (w->lm_head && !w->s_head) return fail(SS_EINVAL, "quantised LM head without scales");
     }
     ss_model *m = new ss_model();
     m->cfg = c;
@@ -174,7 +176,7 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
     m->embed = w->embed;
     m->lm_head = w->lm_head;
     m->gf = w->gf;
-    m->s_head = c.weight_int8 ? w->s_head : nullptr;
+    m->s_head = c.weight_quant ? w->s_head : nullptr;
     m->planes = c.dtype == SS_DTYPE_BF16 ? 2 : 1;
     m->esz = c.dtype == SS_DTYPE_BF16 ? 2 : 4;
     m->W = c.n_heads * c.head_dim;
@@ -211,7 +213,7 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
     {
         int dev = 0;
         (void)hipGetDevice(&dev);
-        m->mega_G = m->mega_G_max = c.weight_int8 ? 0 : mega_grid(c.dtype, dev); // the persistent kernel streams storage-type matrices only
+        m->mega_G = m->mega_G_max = c.weight_quant ? 0 : mega_grid(c.dtype, dev); // the persistent kernel streams storage-type matrices only
         m->mega_rows = mega_max_rows(c.dtype);
         if (m->mega_G > 0 && c.n_layers >= 0) {
             std::vector<MegaPhase> prog;
@@ -350,6 +352,15 @@ extern "C" int ss_quantize_rows_int8(const void *w_dev, int32_t dtype, int64_t r
     if (dtype != SS_DTYPE_F32 && dtype != SS_DTYPE_BF16) return fail(SS_EINVAL, "ss_quantize_rows_int8: dtype must be f32 or bf16");
     if (rows < 1 || K < 1 || rows > 0x7fffffffLL) return fail(SS_EINVAL, "ss_quantize_rows_int8: rows %lld, K %lld out of range", (long long)rows, (long long)K);
     launch_quantize_rows_int8(dtype, w_dev, rows, K, q_dev, scale_dev, (hipStream_t)stream);
+    return check_launch();
+}
+
+extern "C" int ss_quantize_rows_int4(const void *w_dev, int32_t dtype, int64_t rows, int64_t K, uint8_t *q_dev, float *scale_dev,
+                                     ss_stream stream) {
+    if (!w_dev || !q_dev || !scale_dev) return fail(SS_EINVAL, "ss_quantize_rows_int4: NULL argument");
+    if (dtype != SS_DTYPE_F32 && dtype != SS_DTYPE_BF16) return fail(SS_EINVAL, "ss_quantize_rows_int4: dtype must be f32 or bf16");
+    if (rows < 1 || K < 128 || K % 128 || rows > 0x7fffffffLL) return fail(SS_EINVAL, "ss_quantize_rows_int4: rows %lld, K %lld (K must be a multiple of 128)", (long long)rows, (long long)K);
+    launch_quantize_rows_int4(dtype, w_dev, rows, K, q_dev, scale_dev, (hipStream_t)stream);
     return check_launch();
 }
 
@@ -509,6 +520,7 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
     const int chunk = round_up((Lmax + nsplit - 1) / nsplit, 64);
     nsplit = (Lmax + chunk - 1) / chunk;
 
+    const int wbits = c.weight_quant == SS_QUANT_INT4_G128 ? 4 : 8;
     for (int l = 0; l < c.n_layers; ++l) {
         const ss_layer_weights &L = m->layers[l];
         char *kc = (char *)kv->k + kv->layer_elems * l * kv->esz;
@@ -519,7 +531,7 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
         }
         GemmArgs g{};
         g.splitk_ws = m->splitk_ws; g.splitk_ws_bytes = m->splitk_ws_bytes;
-        g.W = L.wqkv; g.N = 3 * W; g.K = d; g.wscale = c.weight_int8 ? L.sqkv : nullptr;
+        g.W = L.wqkv; g.N = 3 * W; g.K = d; g.wscale = c.weight_quant ? L.sqkv : nullptr; g.wbits = wbits;
         g.act = m->act_a; g.act_plane = pl * d; g.ld_act = d; g.R = R;
         g.act_out = m->act_q; g.act_out_plane = pl * W; g.ld_act_out = W;
         g.H = c.n_heads; g.hd = c.head_dim; g.M = M; g.S = kv->S; g.max_pos = c.max_pos;
@@ -544,7 +556,7 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
 
         GemmArgs o{};
         o.splitk_ws = m->splitk_ws; o.splitk_ws_bytes = m->splitk_ws_bytes;
-        o.W = L.wo; o.N = d; o.K = W; o.wscale = c.weight_int8 ? L.so : nullptr;
+        o.W = L.wo; o.N = d; o.K = W; o.wscale = c.weight_quant ? L.so : nullptr; o.wbits = wbits;
         o.act = m->act_o; o.act_plane = pl * W; o.ld_act = W; o.R = R;
         o.out = m->h; o.resid = m->h; o.ldo = d;
         {
@@ -557,7 +569,7 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
         }
         GemmArgs u{};
         u.splitk_ws = m->splitk_ws; u.splitk_ws_bytes = m->splitk_ws_bytes;
-        u.W = L.wgu; u.N = F; u.K = d; u.wscale = c.weight_int8 ? L.sgu : nullptr;
+        u.W = L.wgu; u.N = F; u.K = d; u.wscale = c.weight_quant ? L.sgu : nullptr; u.wbits = wbits;
         u.act = m->act_a; u.act_plane = pl * d; u.ld_act = d; u.R = R;
         u.act_out = m->act_z; u.act_out_plane = pl * F; u.ld_act_out = F;
         {
@@ -567,7 +579,7 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
 
         GemmArgs dn{};
         dn.splitk_ws = m->splitk_ws; dn.splitk_ws_bytes = m->splitk_ws_bytes;
-        dn.W = L.wd; dn.N = d; dn.K = F; dn.wscale = c.weight_int8 ? L.sd : nullptr;
+        dn.W = L.wd; dn.N = d; dn.K = F; dn.wscale = c.weight_quant ? L.sd : nullptr; dn.wbits = wbits;
         dn.act = m->act_z; dn.act_plane = pl * F; dn.ld_act = F; dn.R = R;
         dn.out = m->h; dn.resid = m->h; dn.ldo = d;
         {
@@ -589,7 +601,7 @@ static void run_head(ss_model *m, int nrows, int row0, int stride, float *logits
     }
     ProfScope ps(m, PT_HEAD, st);
     GemmArgs g{};
-    g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model; g.wscale = m->s_head;
+    g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model; g.wscale = m->s_head; g.wbits = c.weight_quant == SS_QUANT_INT4_G128 ? 4 : 8;
     g.act = m->act_a; g.act_plane = pl * c.d_model; g.ld_act = c.d_model; g.R = nrows;
     g.out = logits; g.ldo = c.vocab;
     launch_gemm(c.dtype, EPI_STORE, g, st);

@@ -170,6 +170,30 @@ void launch_quantize_rows_int8(int dtype, const void *W, long long rows, long lo
     else hipLaunchKernelGGL((quantize_rows_int8_kernel<float>), dim3((unsigned)rows), dim3(256), 0, st, (const float *)W, K, q, scale);
 }
 
+// int4 with one scale per group of 128 entries: a wavefront per group, a lane per byte (two entries).  The
+// same single IEEE operations as the int8 quantiser, with 7 in place of 127.
+template <typename T>
+__global__ void __launch_bounds__(256) quantize_rows_int4_kernel(const T *__restrict__ W, long long rows, long long K, uint8_t *__restrict__ q, float *__restrict__ scale) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const size_t base = (size_t)blockIdx.x * (size_t)K;
+    for (long long j = wave; j < K / 128; j += 4) {
+        const size_t k = base + (size_t)j * 128 + 2 * lane;
+        const float w0 = to_f32(W[k]), w1 = to_f32(W[k + 1]);
+        float amax = fmaxf(fabsf(w0), fabsf(w1));
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+        const float sc = amax > 0.f ? __fdiv_rn(amax, 7.0f) : 1.0f;
+        if (lane == 0) scale[(size_t)j * (size_t)rows + blockIdx.x] = sc;
+        const float t0 = fminf(fmaxf(rintf(__fdiv_rn(w0, sc)), -7.0f), 7.0f), t1 = fminf(fmaxf(rintf(__fdiv_rn(w1, sc)), -7.0f), 7.0f);
+        q[k / 2] = (uint8_t)(((int)t0 & 0xf) | (((int)t1 & 0xf) << 4));
+    }
+}
+void launch_quantize_rows_int4(int dtype, const void *W, long long rows, long long K, uint8_t *q, float *scale, hipStream_t st) {
+    if (rows <= 0) return;
+    if (dtype) hipLaunchKernelGGL((quantize_rows_int4_kernel<bf16_t>), dim3((unsigned)rows), dim3(256), 0, st, (const bf16_t *)W, rows, K, q, scale);
+    else hipLaunchKernelGGL((quantize_rows_int4_kernel<float>), dim3((unsigned)rows), dim3(256), 0, st, (const float *)W, rows, K, q, scale);
+}
+
 // Read-stream probe: every lane keeps eight independent 16-byte loads in flight, a wavefront instruction
 // covers 1 KB contiguous, the grid walks the buffer once.  The loads are folded into a word that is stored
 // only if it equals a value the data cannot be arranged to avoid checking, which keeps them alive.

@@ -307,6 +307,106 @@ __global__ __launch_bounds__(NW * 64) void gemm_w8_kernel(GemmArgs a) {
     apply_epilogue<T, EPI>(a, r, n0, 0);
 }
 
+// ---- weight-only int4 matrices with one scale per group of 128 K entries (the coarser reading of the same
+// quantised model).  A lane's 16-byte load holds 32 consecutive K entries of its weight row, i.e. four MFMA
+// k-blocks (dword j = entries 8j..8j+7, entry e in bits 4e..4e+3, two's complement): a step covers 128 entries
+// of K for the 16 rows, which is exactly one scale group, so a step accumulates into a fresh tile and the
+// tile is added to the running sum times the group's scales of the lane's four output columns
+// (scales are stored group-major, scale[group][column]).  K is a multiple of 128.
+__device__ __forceinline__ u32x4 w4_to_bf16x8(uint32_t x) {
+    uint32_t r[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float f0 = (float)((int)(x << (28 - 8 * i)) >> 28); // sign-extended nibbles 2i and 2i + 1
+        const float f1 = (float)((int)(x << (24 - 8 * i)) >> 28);
+        r[i] = (f2u(f0) >> 16) | (f2u(f1) & 0xffff0000u); // |q| <= 7: exact in bf16
+    }
+    return u32x4{r[0], r[1], r[2], r[3]};
+}
+
+template <int EPI, int NW, int U>
+__global__ __launch_bounds__(NW * 64) void gemm_w4_kernel(GemmArgs a) {
+    typedef bf16_t T;
+    constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const int K = a.K;
+
+    int n0[NT];
+    if constexpr (EPI == EPI_QKV) {
+        const int per_head = a.hd / 32;
+        const int hh = blockIdx.x / per_head;
+        n0[0] = hh * a.hd + (blockIdx.x % per_head) * 16;
+        n0[1] = n0[0] + a.hd / 2;
+    } else if constexpr (EPI == EPI_SWIGLU) {
+        n0[0] = blockIdx.x * 16;
+        n0[1] = a.N + n0[0];
+    } else {
+        n0[0] = blockIdx.x * 16;
+    }
+    const int nrows_w = (EPI == EPI_SWIGLU) ? 2 * a.N : a.N;
+
+    const unsigned char *W = reinterpret_cast<const unsigned char *>(a.W);
+    const unsigned char *wrow[NT];
+    int ncol[NT][4]; // the lane's four output columns (weight rows 4g + v of the tile), clamped into the matrix
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        int n = n0[t] + c;
+        if (n > nrows_w - 1) n = nrows_w - 1; // ragged last tile: a valid row, masked at the store
+        wrow[t] = W + (size_t)n * (K / 2) + g * 16;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) ncol[t][v] = min(n0[t] + 4 * g + v, nrows_w - 1);
+    }
+    ActPlanes<T> act{const_cast<T *>(reinterpret_cast<const T *>(a.act)), a.act_plane, a.ld_act};
+    const size_t aoff = (size_t)c * a.ld_act + g * 32;
+    const bool row_live = c < a.R;
+
+    f32x4 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int nsteps = K / 128; // one scale group per step
+    for (int ks = wave; ks < nsteps; ks += U * NW) {
+        u32x4 w[U][NT];
+        Act<T> av[U][4];
+        float sc[U][NT][4];
+#pragma unroll
+        for (int s = 0; s < U; ++s) {
+            const int step = ks + s * NW;
+            const bool ok = step < nsteps;
+            const int st2 = ok ? step : nsteps - 1; // (clamped addresses: every lane issues every load)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                w[s][t] = ok ? ld16_stream(wrow[t] + (size_t)st2 * 64) : zero16();
+#pragma unroll
+                for (int v = 0; v < 4; ++v) sc[s][t][v] = a.wscale[(size_t)st2 * nrows_w + ncol[t][v]];
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) av[s][j] = (ok && row_live) ? load_act(act, aoff + (size_t)st2 * 128 + 8 * j) : zero_act<T>();
+        }
+#pragma unroll
+        for (int s = 0; s < U; ++s)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                f32x4 part = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) part = mma(part, w4_to_bf16x8(w[s][t][j]), av[s][j]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[t][v] += sc[s][t][v] * part[v];
+            }
+    }
+
+    // fixed-order sum of the waves' partial tiles; wave 0 applies the epilogue
+    __shared__ float red[NW][NT][4][64];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red[wave][t][v][lane] = acc[t][v];
+    __syncthreads();
+    if (wave != 0) return;
+    tile_epilogue<T, EPI, NW>(a, red, n0, 0);
+}
+
 // More than 16 rows (larger batches, prefill): the waves of a workgroup split the output columns instead
 // of K, so that all of them walk K together and share the activation rows through LDS - with R rows
 // the activations a wave needs are R*4/32 times its weight bytes, too much to fetch per wave from L2.
@@ -631,7 +731,24 @@ template <int EPI> static void launch_gemm_w8(const GemmArgs &a, hipStream_t st)
     else launch_wide_any<bf16_t, EPI, true>(a, tiles, row_tiles, st);
 }
 
+#ifndef SS_W4_U
+#define SS_W4_U 2
+#endif
+template <int EPI> static void launch_gemm_w4(const GemmArgs &a, hipStream_t st) {
+    const int tiles = EPI == EPI_QKV ? 3 * a.H * (a.hd / 32) : (a.N + 15) / 16;
+    hipLaunchKernelGGL((gemm_w4_kernel<EPI, 8, SS_W4_U>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
+}
+
 void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st) {
+    if (a.wscale && a.wbits == 4) { // int4 weights: the caller has checked bf16 planes, at most 16 rows, K % 128 == 0
+        switch (epi) {
+        case EPI_STORE: launch_gemm_w4<EPI_STORE>(a, st); break;
+        case EPI_RESID: launch_gemm_w4<EPI_RESID>(a, st); break;
+        case EPI_SWIGLU: launch_gemm_w4<EPI_SWIGLU>(a, st); break;
+        case EPI_QKV: launch_gemm_w4<EPI_QKV>(a, st); break;
+        }
+        return;
+    }
     if (a.wscale) { // int8 weights: the caller has checked bf16 planes and K % 16 == 0
         switch (epi) {
         case EPI_STORE: launch_gemm_w8<EPI_STORE>(a, st); break;

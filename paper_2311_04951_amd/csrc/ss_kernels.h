@@ -42,6 +42,7 @@ struct GemmArgs {
     // weight-only int8: W is int8 [N][K] and output column n is scaled by wscale[n] (NULL: W is in the storage type).
     // bf16 activation planes only; K a multiple of 16.
     const float *wscale;
+    int wbits; // with wscale: 8 = int8, one scale per output column; 4 = int4, two entries per byte, scales [K/128][columns] (at most 16 rows, K % 128 == 0)
 };
 void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st);
 
@@ -72,6 +73,8 @@ void launch_rmsnorm_pack_rows(int dtype, const float *h, const float *gain, int 
                               int d, float eps, void *act, size_t act_plane, int ld_act, hipStream_t st);
 // row-wise int8 quantisation of W [rows][K] (storage type): scale = max|w| / 127 (1 for a zero row), q = rint(w / scale)
 void launch_quantize_rows_int8(int dtype, const void *W, long long rows, long long K, int8_t *q, float *scale, hipStream_t st);
+// int4 with group scales: q [rows][K/2] (entry 2b low, 2b+1 high nibble of byte b), scale [K/128][rows]; K % 128 == 0
+void launch_quantize_rows_int4(int dtype, const void *W, long long rows, long long K, uint8_t *q, float *scale, hipStream_t st);
 void launch_read_probe(const void *buf, size_t bytes, uint32_t *sink, hipStream_t st);
 void launch_len_add(int32_t *len, int batch, int delta, hipStream_t st);
 void launch_len_rollback(int32_t *len, const int32_t *n_accepted, int batch, int M, hipStream_t st);
