@@ -169,16 +169,18 @@ def layer_pass(si, sv, torch, dev, target, shape, iters=20, L=1024, M=5):
             "GBps": nbytes / t / 1e9, "frac_of_hbm_peak": nbytes / t / HBM_PEAK}
 
 
-def int8_weights_leg(si, sv, torch, gen, dev, target, persistent, shape, packed, io, prompt, K, steps):
-    """The verify pass with weight-only int8 matrices (the quantised model the paper assumes; one scale per
-    output row): the same 7B-shaped weights quantised by the library, K + 1 rows per pass, one launch per
-    phase (the persistent kernel streams bf16 matrices only), beside the bf16 model on the same
-    per-phase path; then the speculative loop and the autoregressive baseline on the int8 pair."""
+def int8_weights_leg(si, sv, torch, gen, dev, target, persistent, shape, packed, io, prompt, K, steps, bits=8):
+    """The verify pass with weight-only quantised matrices (the quantised model the paper assumes; bits = 8: one
+    scale per output row, bits = 4: one scale per group of 128 entries along K): the same 7B-shaped weights
+    quantised by the library, K + 1 rows per pass, one launch per phase (the persistent kernel streams bf16
+    matrices only), beside the bf16 model on the same per-phase path; then the speculative loop and the
+    autoregressive baseline on the quantised pair."""
     M = K + 1
-    t8 = sv.Model(shape, io, max_rows=16, max_pos=4096, packed_layers=packed, int8_weights=True)
+    qkw = {"int4_weights": True} if bits == 4 else {"int8_weights": True}
+    t8 = sv.Model(shape, io, max_rows=16, max_pos=4096, packed_layers=packed, **qkw)
     d8 = sv.Model(si.DecoderShape(**{**shape.as_dict(), "n_layers": min(2, shape.n_layers)}),
                   {"embed": io["embed"], "gf": io["gf"], "lm_head": t8.lm_head, "s_head": t8.s_head},
-                  max_rows=16, max_pos=4096, packed_layers=t8.layers[:min(2, shape.n_layers)], int8_weights=True)
+                  max_rows=16, max_pos=4096, packed_layers=t8.layers[:min(2, shape.n_layers)], **qkw)
     vt = si.token_ids(3, "int8_rows", (1, M), shape.vocab).to(torch.int32).to(dev)
     zero = torch.zeros(1, dtype=torch.int32, device=dev)
     logits = torch.empty((1, M, shape.vocab), dtype=torch.float32, device=dev)
@@ -203,10 +205,13 @@ def int8_weights_leg(si, sv, torch, gen, dev, target, persistent, shape, packed,
     sv.ss_model_set_persistent(target, persistent)
     W = shape.n_heads * shape.head_dim
     L = len(prompt) + steps // 2
-    rows = shape.n_layers * (3 * W + 2 * shape.d_model + 2 * shape.d_ff) + shape.vocab          # one fp32 scale per matrix row
-    nbytes = (shape.n_layers * layer_bytes(shape) + shape.vocab * shape.d_model * 2) // 2 + 4 * rows \
-        + shape.n_layers * 2 * (L + 2 * M) * W * 2 + M * shape.vocab * 4
-    out = {"workload": f"7B-shaped target with int8 matrices ({shape.n_layers} layers), batch 1, K={K}, KV context ~{L}, "
+    wbytes16 = shape.n_layers * layer_bytes(shape) + shape.vocab * shape.d_model * 2                # the matrices in bf16
+    if bits == 4:
+        nscale = wbytes16 // 2 // 128                                                                 # one fp32 scale per 128 entries
+    else:
+        nscale = shape.n_layers * (3 * W + 2 * shape.d_model + 2 * shape.d_ff) + shape.vocab         # one fp32 scale per matrix row
+    nbytes = wbytes16 * bits // 16 + 4 * nscale + shape.n_layers * 2 * (L + 2 * M) * W * 2 + M * shape.vocab * 4
+    out = {"workload": f"7B-shaped target with int{bits} matrices ({shape.n_layers} layers), batch 1, K={K}, KV context ~{L}, "
                        "one launch per phase",
            "ms_per_pass": 1e3 * t_int8, "verify_pass_tokens_per_s": M / t_int8, "algorithmic_bytes": nbytes,
            "GBps": nbytes / t_int8 / 1e9, "frac_of_hbm_peak": nbytes / t_int8 / HBM_PEAK,
@@ -337,7 +342,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-e2e", action="store_true")
     ap.add_argument("--no-accept-workload", action="store_true", help="skip the stand-alone accept workload leg")
-    ap.add_argument("--no-int8-leg", action="store_true", help="skip the weight-only int8 leg")
+    ap.add_argument("--no-int8-leg", action="store_true", help="skip the weight-only int8 and int4 legs")
     ap.add_argument("--no-paper-pair", action="store_true", help="skip the 13B/3B-shaped target/draft pair (the paper's size ratio)")
     ap.add_argument("--no-layer-pass", action="store_true", help="skip the one-layer leg (5 rows, 1024 cached positions)")
     ap.add_argument("--batched-workload", action="store_true",
@@ -508,11 +513,12 @@ def main():
         out["standalone_accept"] = standalone_accept(si, sv, torch, dev)
     if not args.no_int8_leg:
         out["int8_weights"] = int8_weights_leg(si, sv, torch, gen, dev, target, bool(args.persistent), shape, packed, io, prompt, K, args.steps)
+        out["int4_weights"] = int8_weights_leg(si, sv, torch, gen, dev, target, bool(args.persistent), shape, packed, io, prompt, K, args.steps, bits=4)
     if not args.no_paper_pair:
         out["paper_size_pair"] = paper_pair_leg(si, sv, torch, gen, dev)
     if args.batched_workload:
         out["batched_workload"] = batched_workload(si, sv, torch, dev, shape, packed, io, int8=not args.no_int8_leg)
-    for leg in ("layer_pass", "standalone_accept", "batched_workload", "int8_weights"):
+    for leg in ("layer_pass", "standalone_accept", "batched_workload", "int8_weights", "int4_weights"):
         if leg in out and "GBps" in out[leg]:
             out[leg]["frac_of_read_stream"] = out[leg]["GBps"] / stream_GBps
     if not args.no_cpu_baseline:

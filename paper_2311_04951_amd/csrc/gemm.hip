@@ -731,12 +731,11 @@ template <int EPI> static void launch_gemm_w8(const GemmArgs &a, hipStream_t st)
     else launch_wide_any<bf16_t, EPI, true>(a, tiles, row_tiles, st);
 }
 
-#ifndef SS_W4_U
-#define SS_W4_U 2
-#endif
+// 8 waves, one step in flight: measured best of (4 | 8 | 16 waves) x (1 | 2 steps) on the 7B-shaped layer (a step
+// already holds 13 to 17 loads per lane: one of weights, eight of activations, the scales)
 template <int EPI> static void launch_gemm_w4(const GemmArgs &a, hipStream_t st) {
     const int tiles = EPI == EPI_QKV ? 3 * a.H * (a.hd / 32) : (a.N + 15) / 16;
-    hipLaunchKernelGGL((gemm_w4_kernel<EPI, 8, SS_W4_U>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
+    hipLaunchKernelGGL((gemm_w4_kernel<EPI, 8, 1>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
 }
 
 void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st) {
