@@ -285,7 +285,8 @@ int ss_speculative_accept(const float *p_dev, const float *q_dev, const int32_t 
  * a sequence's first rejection, which the method never uses, are not read at all).  Returns exactly
  * what ss_speculative_accept returns on the
  * probabilities ss_softmax would produce.  p_out_dev / q_out_dev, if not NULL, receive those
- * probabilities ([batch][K+1][vocab] / [batch][K][vocab]).  temperature > 0. */
+ * probabilities ([batch][K+1][vocab] / [batch][K][vocab]).  temperature > 0.  No top-p here: a caller
+ * that filters (ss_top_p_filter) materialises the probabilities and uses ss_speculative_accept. */
 int ss_speculative_accept_logits(const float *p_logits_dev, const float *q_logits_dev, float temperature,
                                  const int32_t *draft_tokens_dev, const float *uniforms_dev,
                                  int32_t batch, int32_t K, int32_t vocab, int32_t *n_accepted_dev,
