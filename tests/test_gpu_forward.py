@@ -217,19 +217,23 @@ def test_batched_7b_layer_72_rows_matches_per_sequence_oracle():
 
 
 @pytest.mark.timeout(1200)
-def test_full_7b_verify_pass_matches_oracle():
+@pytest.mark.parametrize("quant", [None, "int8", "int4"])
+def test_full_7b_verify_pass_matches_oracle(quant):
     """The benchmark workload at its full size and in the launch configuration bench.py times (32
     7B-shaped bf16 layers + LM head, default forward path, 5 query rows, 128 cached positions):
     every logit of the verify pass against the oracle, max-abs 2e-2; the greedy token of a row must
-    agree wherever the oracle's top-2 margin exceeds twice that tolerance."""
+    agree wherever the oracle's top-2 margin exceeds twice that tolerance.  Also with the matrices
+    quantised to int8 and to int4 (the bench's int8_weights / int4_weights legs), against the oracle's
+    model quantised the same way."""
     from bench import build_7b
+    qkw = {} if quant is None else {f"{quant}_weights": True}
     shape, packed, io = build_7b(si, sv, torch, 0, si.FULL_7B.n_layers, dev())
-    gm = sv.Model(shape, io, max_rows=16, max_pos=512, packed_layers=packed)
+    gm = sv.Model(shape, io, max_rows=16, max_pos=512, packed_layers=packed, **qkw)
     W = shape.n_heads * shape.head_dim
     layers = [{"wq": p["wqkv"][:W].cpu(), "wk": p["wqkv"][W:2 * W].cpu(), "wv": p["wqkv"][2 * W:].cpu(), "wo": p["wo"].cpu(),
                "wg": p["wgu"][:shape.d_ff].cpu(), "wu": p["wgu"][shape.d_ff:].cpu(), "wd": p["wd"].cpu(),
                "g1": p["g1"].cpu(), "g2": p["g2"].cpu()} for p in packed]
-    om = oracle.Model(shape, {"embed": io["embed"].cpu(), "gf": io["gf"].cpu(), "lm_head": io["lm_head"].cpu(), "layers": layers})
+    om = oracle.Model(shape, {"embed": io["embed"].cpu(), "gf": io["gf"].cpu(), "lm_head": io["lm_head"].cpu(), "layers": layers}, **qkw)
     L, M = 128, 5
     ctx = si.kv_context(shape, 3, "ctx7b", L)
     gkv = sv.KVCache(gm, 1, L + 64)
