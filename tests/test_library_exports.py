@@ -47,3 +47,18 @@ def test_bench_refuses_more_than_one_gpu_before_touching_a_device():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=60)
     assert r.returncode != 0 and r.stdout.strip() == ""
     assert "one GPU" in r.stderr
+
+
+def test_bench_algorithmic_bytes_are_the_documented_sums():
+    """The roofline figure divides these bytes by a measured time: every weight once (bf16), the KV context
+    once, the new K/V rows, the logits."""
+    import bench
+    import seeded_inputs as si
+    s = si.FULL_7B
+    layer = 2 * (4 * 4096 * 4096 + 3 * 4096 * 11008)                 # q, k, v, o + gate, up, down in bf16
+    assert bench.layer_bytes(s) == layer == 404_750_336
+    L, M = 145, 5
+    want = 32 * layer + 32000 * 4096 * 2 + 32 * 2 * (L + M) * 4096 * 2 + 32 * 2 * M * 4096 * 2 + M * 32000 * 4
+    assert bench.verify_pass_bytes(s, L, M) == want
+    assert abs(want - 13.296e9) < 0.01e9                              # the figure the profiles and DESIGN.md quote
+    assert bench.HBM_PEAK == 8e12
