@@ -60,5 +60,5 @@ def test_bench_algorithmic_bytes_are_the_documented_sums():
     L, M = 145, 5
     want = 32 * layer + 32000 * 4096 * 2 + 32 * 2 * (L + M) * 4096 * 2 + 32 * 2 * M * 4096 * 2 + M * 32000 * 4
     assert bench.verify_pass_bytes(s, L, M) == want
-    assert abs(want - 13.296e9) < 0.01e9                              # the figure the profiles and the design doc quote
+    assert abs(want - 13.296e9) < 0.01e9                              # the figure the committed profile summaries quote
     assert bench.HBM_PEAK == 8e12
