@@ -26,26 +26,6 @@ HBM_PEAK = 8.0e12  # B/s, MI355X published peak
 PERSISTENT_7B_TRAFFIC_BYTES = 13.608e9  # 13.472 GB fetched + 0.136 GB written per launch (rocprofv3 --pmc, see profiles/)
 
 
-def build_7b(si, sv, torch, seed, n_layers, dev):
-    """Random-init weights generated on the GPU, packed once into the library's fused matrices."""
-    return build_packed(si, torch, si.DecoderShape(**{**si.FULL_7B.as_dict(), "n_layers": n_layers}), seed, dev)
-
-
-def build_packed(si, torch, shape, seed, dev):
-    n_layers = shape.n_layers
-    packed = []
-    for l in range(n_layers):
-        lw = si.layer_weights(shape, seed, l, device=dev)
-        packed.append({"wqkv": torch.cat([lw["wq"], lw["wk"], lw["wv"]], 0), "wo": lw["wo"],
-                       "wgu": torch.cat([lw["wg"], lw["wu"]], 0), "wd": lw["wd"], "g1": lw["g1"], "g2": lw["g2"]})
-        del lw
-    dt = si.storage_dtype(shape)
-    io = {"embed": si.normal(seed, "embed", (shape.vocab, shape.d_model), 0.02, device=dev, dtype=dt),
-          "gf": si.normal(seed, "gf", (shape.d_model,), 0.02, mean=1.0, device=dev),
-          "lm_head": si.normal(seed, "lm_head", (shape.vocab, shape.d_model), 0.02, device=dev, dtype=dt)}
-    return shape, packed, io
-
-
 def layer_bytes(shape):
     d, F, W = shape.d_model, shape.d_ff, shape.n_heads * shape.head_dim
     return 2 * (3 * W * d + d * W + 3 * d * F)
@@ -237,8 +217,8 @@ def paper_pair_leg(si, sv, torch, gen, dev, prompt_len=128, n_new=96, K=5):
     weights make the draft useless as a predictor, so the figures are costs per step, not the paper's speed-up."""
     ts = si.DecoderShape(40, 5120, 40, 128, 13824, 32000, dtype="bf16")
     ds = si.DecoderShape(28, 3072, 24, 128, 8192, 32000, dtype="bf16")
-    _, tp, tio = build_packed(si, torch, ts, 11, dev)
-    _, dp, dio = build_packed(si, torch, ds, 12, dev)
+    _, tp, tio = si.packed_decoder(ts, 11, dev)
+    _, dp, dio = si.packed_decoder(ds, 12, dev)
     target = sv.Model(ts, tio, max_rows=16, max_pos=1024, packed_layers=tp)
     draft = sv.Model(ds, dio, max_rows=16, max_pos=1024, packed_layers=dp)
     prompt = si.token_ids(11, "prompt", (prompt_len,), ts.vocab).tolist()
@@ -364,7 +344,7 @@ def main():
     torch.cuda.set_device(dev)
     K, M, T = args.K, args.K + 1, 1.0
     prompt_len = 128
-    shape, packed, io = build_7b(si, sv, torch, 0, args.layers, dev)
+    shape, packed, io = si.packed_7b(0, args.layers, dev)
     max_pos = 4096
     target = sv.Model(shape, io, max_rows=16, max_pos=max_pos, packed_layers=packed)
     dshape = si.DecoderShape(**{**shape.as_dict(), "n_layers": min(2, args.layers)})

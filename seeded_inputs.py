@@ -108,6 +108,37 @@ def decoder_weights(shape: DecoderShape, seed: int, device="cpu") -> dict:
     }
 
 
+def packed_decoder(shape: DecoderShape, seed: int, device="cpu"):
+    """The same decoder as decoder_weights(), layer by layer, with q|k|v and gate|up concatenated into the
+    fused matrices a weight-streaming forward reads ([3*H*hd, d] and [2*F, d]); only one layer's separate
+    matrices exist at a time, so a 7B-shaped model can be drawn directly in device memory.
+    Returns (shape, packed layers [{wqkv, wo, wgu, wd, g1, g2}], {embed, gf, lm_head})."""
+    packed = []
+    for l in range(shape.n_layers):
+        lw = layer_weights(shape, seed, l, device=device)
+        packed.append({"wqkv": torch.cat([lw["wq"], lw["wk"], lw["wv"]], 0), "wo": lw["wo"],
+                       "wgu": torch.cat([lw["wg"], lw["wu"]], 0), "wd": lw["wd"], "g1": lw["g1"], "g2": lw["g2"]})
+        del lw
+    dt = storage_dtype(shape)
+    io = {"embed": normal(seed, "embed", (shape.vocab, shape.d_model), 0.02, device=device, dtype=dt),
+          "gf": normal(seed, "gf", (shape.d_model,), 0.02, mean=1.0, device=device),
+          "lm_head": normal(seed, "lm_head", (shape.vocab, shape.d_model), 0.02, device=device, dtype=dt)}
+    return shape, packed, io
+
+
+def packed_7b(seed: int, n_layers: int, device="cpu"):
+    """packed_decoder() of the 7B shape with the given depth."""
+    return packed_decoder(DecoderShape(**{**FULL_7B.as_dict(), "n_layers": n_layers}), seed, device)
+
+
+def unpack_layers(shape: DecoderShape, packed):
+    """Packed layers -> the separate host matrices {wq, wk, wv, wo, wg, wu, wd, g1, g2} (views, same bits)."""
+    W = shape.n_heads * shape.head_dim
+    return [{"wq": p["wqkv"][:W].cpu(), "wk": p["wqkv"][W:2 * W].cpu(), "wv": p["wqkv"][2 * W:].cpu(), "wo": p["wo"].cpu(),
+             "wg": p["wgu"][:shape.d_ff].cpu(), "wu": p["wgu"][shape.d_ff:].cpu(), "wd": p["wd"].cpu(),
+             "g1": p["g1"].cpu(), "g2": p["g2"].cpu()} for p in packed]
+
+
 def early_exit_draft(target_shape: DecoderShape, target_weights: dict, n_layers: int):
     """Draft = the target's first `n_layers` layers + its final gain and LM head (same tensors)."""
     ds = DecoderShape(**{**target_shape.as_dict(), "n_layers": n_layers})

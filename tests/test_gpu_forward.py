@@ -162,8 +162,7 @@ def test_7b_width_data_synchronisation_equals_barriers_over_many_launches():
     self-validating protocol is what runs): 200 launches with the row count changing from call to call
     (1, 5, 9, 2, ... rows: the buffers keep rows of earlier, larger calls), context growing and rolled
     back.  Every launch must give the logits of the barrier-only mode bit for bit."""
-    from bench import build_7b
-    shape, packed, io = build_7b(si, sv, torch, 5, 3, dev())
+    shape, packed, io = si.packed_7b(5, 3, dev())
     ms = []
     for data_sync in (False, True):
         gm = sv.Model(shape, io, max_rows=16, max_pos=1024, packed_layers=packed)
@@ -225,15 +224,11 @@ def test_full_7b_verify_pass_matches_oracle(quant):
     agree wherever the oracle's top-2 margin exceeds twice that tolerance.  Also with the matrices
     quantised to int8 and to int4 (the bench's int8_weights / int4_weights legs), against the oracle's
     model quantised the same way."""
-    from bench import build_7b
     qkw = {} if quant is None else {f"{quant}_weights": True}
-    shape, packed, io = build_7b(si, sv, torch, 0, si.FULL_7B.n_layers, dev())
+    shape, packed, io = si.packed_7b(0, si.FULL_7B.n_layers, dev())
     gm = sv.Model(shape, io, max_rows=16, max_pos=512, packed_layers=packed, **qkw)
-    W = shape.n_heads * shape.head_dim
-    layers = [{"wq": p["wqkv"][:W].cpu(), "wk": p["wqkv"][W:2 * W].cpu(), "wv": p["wqkv"][2 * W:].cpu(), "wo": p["wo"].cpu(),
-               "wg": p["wgu"][:shape.d_ff].cpu(), "wu": p["wgu"][shape.d_ff:].cpu(), "wd": p["wd"].cpu(),
-               "g1": p["g1"].cpu(), "g2": p["g2"].cpu()} for p in packed]
-    om = oracle.Model(shape, {"embed": io["embed"].cpu(), "gf": io["gf"].cpu(), "lm_head": io["lm_head"].cpu(), "layers": layers}, **qkw)
+    om = oracle.Model(shape, {"embed": io["embed"].cpu(), "gf": io["gf"].cpu(), "lm_head": io["lm_head"].cpu(),
+                              "layers": si.unpack_layers(shape, packed)}, **qkw)
     L, M = 128, 5
     ctx = si.kv_context(shape, 3, "ctx7b", L)
     gkv = sv.KVCache(gm, 1, L + 64)

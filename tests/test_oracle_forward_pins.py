@@ -97,14 +97,14 @@ def test_rope_closed_forms_and_relative_position_property():
 
 # ---------------------------------------------------------------- whole decoder vs a library Llama
 
-def _hf_llama(shape, w):
+def _hf_llama(shape, w, attn="eager"):
     from transformers import LlamaConfig, LlamaForCausalLM
     cfg = LlamaConfig(hidden_size=shape.d_model, intermediate_size=shape.d_ff,
                       num_hidden_layers=shape.n_layers, num_attention_heads=shape.n_heads,
                       num_key_value_heads=shape.n_heads, head_dim=shape.head_dim, vocab_size=shape.vocab,
                       rms_norm_eps=shape.rms_eps, rope_theta=shape.rope_base, tie_word_embeddings=False,
                       attention_bias=False, mlp_bias=False, max_position_embeddings=4096,
-                      attn_implementation="eager")
+                      attn_implementation=attn)
     m = LlamaForCausalLM(cfg).double().eval()
     sd = {"model.embed_tokens.weight": w["embed"], "model.norm.weight": w["gf"], "lm_head.weight": w["lm_head"]}
     for l, lw in enumerate(w["layers"]):
@@ -136,18 +136,33 @@ def test_forward_matches_library_llama_fp64(shape):
 
 
 def test_bf16_storage_rounds_only_weights_and_cache():
+    """bf16 storage rounds (to nearest even) the weights and the cache entries, nothing else.  Reference: the
+    library Llama in fp64 over the same bf16 weights, with an attention function that rounds the keys (after the
+    rotary embedding) and the values to bf16, as a cache in that storage type holds them, before they are used.
+    A further rounding anywhere in the oracle (of the queries, of the hidden rows, of an attention output)
+    would show as an error of 1e-3, two orders above the bound."""
+    from transformers import AttentionInterface
+    from transformers.masking_utils import AttentionMaskInterface, eager_mask
+    from transformers.models.llama.modeling_llama import eager_attention_forward
+
+    def attention_over_bf16_cache(module, query, key, value, attention_mask, **kw):
+        rnd = lambda t: t.float().to(torch.bfloat16).double()   # one rounding to fp32, then the storage rounding
+        return eager_attention_forward(module, query, rnd(key), rnd(value), attention_mask, **kw)
+
+    AttentionInterface.register("eager_bf16_cache", attention_over_bf16_cache)
+    AttentionMaskInterface.register("eager_bf16_cache", eager_mask)     # the same additive causal mask as "eager"
     shape = si.DecoderShape(2, 128, 2, 64, 344, 512, dtype="bf16")
     w = si.decoder_weights(shape, seed=12)
     toks = si.token_ids(12, "toks", (24,), shape.vocab).numpy()
     m = oracle.Model(shape, w)
-    kv = m.new_kv(32)
-    got = m.forward(kv, toks)
-    # reference: the same bf16 weights widened to fp64 in the library Llama (which keeps K/V
-    # unrounded); the only difference left is the bf16 rounding of cache entries
+    got = np.concatenate([m.forward(kv := m.new_kv(32), toks[:19]), m.forward(kv, toks[19:])])   # prefill + a 5-row verify pass
+    ids = torch.tensor(toks[None].astype(np.int64))
     with torch.no_grad():
-        ref = _hf_llama(shape, w)(torch.tensor(toks[None].astype(np.int64))).logits[0].numpy()
-    err = np.max(np.abs(got - ref))
-    assert 1e-7 < err < 5e-3
+        ref = _hf_llama(shape, w, attn="eager_bf16_cache")(ids).logits[0].numpy()
+        unrounded = _hf_llama(shape, w)(ids).logits[0].numpy()
+    assert np.max(np.abs(got - ref)) < 1e-6     # measured 1.1e-7
+    # and the cache rounding is really there: against a cache that keeps fp64 keys and values the gap is far larger
+    assert 1e-4 < np.max(np.abs(got - unrounded)) < 5e-3
 
 
 # ---------------------------------------------------------------- what KV caching must preserve
