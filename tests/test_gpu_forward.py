@@ -216,6 +216,90 @@ def test_batched_7b_layer_72_rows_matches_per_sequence_oracle():
 
 
 @pytest.mark.timeout(1200)
+def test_batched_long_context_layer_at_its_real_shape_matches_per_sequence_oracle():
+    """The batched long-context workload at its real shape, reduced in depth only (the oracle cannot run 32 layers
+    of it): one 7B-shaped bf16 layer, 8 sequences whose caches hold 4096 - jitter(0..63) positions (the KV cache
+    "can be quite large", Section 2), K = 8 -> 72 rows in one call against a cache of 4608 positions per
+    sequence: block indices far past the first cache blocks, the transposed value blocks of a long sequence,
+    16-way split-KV attention with partly empty tail splits, split-K wide GEMMs.  Every sequence's hidden rows
+    against the oracle run on that sequence alone; then a ragged roll-back (Section 4.4: sequences accept
+    different numbers of tokens) and a second 72-row pass over the shortened caches, checked the same way."""
+    shape = si.LAYER_7B
+    lw = si.layer_weights(shape, seed=0, layer=0)
+    w = {"embed": None, "gf": None, "lm_head": None, "layers": [lw]}
+    om = oracle.Model(shape, w)
+    B, M, S = 8, 9, 4608
+    lens = [4096 - j for j in [0, 63, 1, 37, 50, 12, 31, 64 - 41]]
+    assert len(set(lens)) == B and min(lens) > 4096 - 64
+    gm = sv.Model(shape, weights_to_device(w), max_rows=B * M, max_pos=S)
+    gkv = sv.KVCache(gm, B, S)
+    h = si.normal(21, "h72", (2, B, M, shape.d_model), 1.0)
+    okvs = []
+    for b in range(B):
+        ctx = si.kv_context(shape, 21, f"ctx4096_{b}", lens[b])
+        sv.ss_kv_cache_append(gkv, 0, b, 0, ctx[0][0].to(dev()), ctx[0][1].to(dev()))
+        okv = om.new_kv(S)
+        okv.append_raw(ctx)
+        okvs.append(okv)
+        del ctx
+    sv.ss_kv_cache_set_len(gkv, lens)
+    got = sv.ss_decoder_layers_forward(gm, gkv, h[0].reshape(B * M, -1).to(dev()).clone(), B, M).cpu().numpy().reshape(B, M, -1)
+    worst = 0.0
+    for b in range(B):
+        err = maxabs(got[b], om.layers_forward(okvs[b], h[0, b].numpy()))
+        worst = max(worst, err)
+        assert err < 2e-2, (b, err)
+    assert sv.ss_kv_cache_get_len(gkv).tolist() == [l + M for l in lens]
+    # ragged roll-back, then the next pass
+    acc = [0, 8, 3, 8, 1, 5, 2, 7]
+    sv.ss_kv_cache_rollback(gkv, torch.tensor(acc, dtype=torch.int32, device=dev()), M, n_accepted_host=acc)
+    lens2 = [l + a + 1 for l, a in zip(lens, acc)]
+    assert sv.ss_kv_cache_get_len(gkv).tolist() == lens2
+    got = sv.ss_decoder_layers_forward(gm, gkv, h[1].reshape(B * M, -1).to(dev()).clone(), B, M).cpu().numpy().reshape(B, M, -1)
+    for b in range(B):
+        okvs[b].set_len(lens2[b])
+        err = maxabs(got[b], om.layers_forward(okvs[b], h[1, b].numpy()))
+        worst = max(worst, err)
+        assert err < 2e-2, (b, err)
+    assert worst < 2e-3          # the bf16 path keeps fp32 activations: far inside the bar
+    assert sv.ss_kv_cache_get_len(gkv).tolist() == [l + M for l in lens2]
+    assert sv.ss_device_status(gm) == 0
+
+
+@pytest.mark.timeout(1200)
+def test_persistent_kernel_at_7b_width_for_every_row_count_and_a_long_context_matches_oracle():
+    """The persistent kernel on its default grid (one workgroup per compute unit, self-validating activations)
+    at 7B width, three layers + LM head, against the ORACLE (not against its own barrier mode): 1 row (the
+    autoregressive baseline and every draft step, Section 3 Eq. 1), 3 rows (K = 2), 5 and 9 rows (K = 4, 8), each
+    against 140 cached positions (one attention unit per head) and against about 4000 (eight KV splits merged
+    inside the kernel)."""
+    shape, packed, io = si.packed_7b(5, 3, dev())
+    gm = sv.Model(shape, io, max_rows=16, max_pos=4096, packed_layers=packed)
+    om = oracle.Model(shape, {"embed": io["embed"].cpu(), "gf": io["gf"].cpu(), "lm_head": io["lm_head"].cpu(),
+                              "layers": si.unpack_layers(shape, packed)})
+    Lbig = 4003
+    ctx = si.kv_context(shape, 22, "ctx_long", Lbig)
+    gkv = sv.KVCache(gm, 1, 4096)
+    dctx = [(k.to(dev()), v.to(dev())) for k, v in ctx]
+    worst = 0.0
+    for L, M in [(Lbig, 9), (Lbig, 1), (3990, 5), (140, 1), (140, 3), (140, 9), (385, 5)]:   # 385: the shortest context that is split
+        for l, (k, v) in enumerate(dctx):                     # the previous case overwrote rows of the context
+            sv.ss_kv_cache_append(gkv, l, 0, 0, k[:L].contiguous(), v[:L].contiguous())
+        sv.ss_kv_cache_set_len(gkv, [L])
+        okv = om.new_kv(L + 16)
+        okv.append_raw([(k[:L], v[:L]) for k, v in ctx])
+        toks = si.token_ids(22, f"rows{L}_{M}", (M,), shape.vocab).numpy().astype(np.int32)
+        got = sv.ss_verify_forward(gm, gkv, torch.tensor(toks[None], device=dev()), M)[0].cpu().numpy()
+        ref = om.forward(okv, toks)
+        err = maxabs(got, ref)
+        worst = max(worst, err)
+        assert err < 2e-2, (L, M, err)
+        assert sv.ss_kv_cache_get_len(gkv).tolist() == [L + M]
+    assert worst < 2e-3
+    assert sv.ss_device_status(gm) == 0
+
+
+@pytest.mark.timeout(1200)
 @pytest.mark.parametrize("quant", [None, "int8", "int4"])
 def test_full_7b_verify_pass_matches_oracle(quant):
     """The benchmark workload at its full size and in the launch configuration bench.py times (32

@@ -149,6 +149,52 @@ def test_shared_cache_for_an_early_exit_draft_on_gpu(K, T):
         assert one == ref
 
 
+@pytest.mark.parametrize("persistent", PATHS)
+def test_shared_cache_sampled_run_in_lock_step_with_the_oracle(persistent):
+    """Temperature 1, K = 4, one cache for both models (Section 4.4).  Each step the oracle is run on the GPU's
+    history with ITS shared cache (draft calls on the leading layers, length set back, verify call rewrites the
+    positions): the draft's rows and the target's logits by tolerance, draft sampling and the accept / resample
+    decisions bit-exact on the GPU's own q and p."""
+    K, n_new, T = 4, 48, 1.0
+    (ot, od), (gt, gd) = _pair(6, early=True, persistent=persistent)
+    prompt = si.token_ids(6, "prompt", (32,), 1024).numpy().tolist()
+    ud = si.uniforms(6, "ud", (n_new, K)).numpy()
+    ua = si.uniforms(6, "ua", (n_new, K + 1)).numpy()
+    seen = []
+
+    def obs(s):
+        seen.append({k: (v.detach().cpu().numpy().copy() if hasattr(v, "detach") else v) for k, v in s.items()})
+
+    sp, stats = gen.speculative_generate(gt, gd, prompt, n_new, K, T, ud, ua, observer=obs, shared_kv=True)
+    assert len(sp) == n_new and stats["steps"] == len(seen)
+    x = list(prompt)
+    okv = ot.new_kv(256)
+    ot.forward(okv, x[:-1], want_logits=False)
+    for s in seen:
+        n, st = len(x), s["step"]
+        d = s["draft"][0].tolist()
+        feed = [x[-1]]
+        for i in range(K):
+            ql = od.forward(okv, feed)[-1]                      # the draft appends to the leading layers of the one cache
+            assert maxabs(s["q"][0, i], oracle.softmax(ql, T)) < 1e-5
+            assert d[i] == oracle.sample(s["q"][0, i], ud[st][i])
+            feed = [d[i]]
+        assert len(okv) == n - 1 + K
+        okv.set_len(n - 1)                                      # the verify pass rewrites those positions for every layer
+        pl = ot.forward(okv, [x[-1]] + d)
+        assert maxabs(s["logits"][0], pl) < 1e-4
+        ona, onx = oracle.speculative_accept(s["p"], s["q"], s["draft"], ua[st][None])
+        assert ona.tolist() == s["n_accepted"].tolist() and onx.tolist() == s["next"].tolist()
+        a, y = int(ona[0]), int(onx[0])
+        x += d[:a] + [y]
+        okv.set_len(n + a)
+    assert x[len(prompt):len(prompt) + n_new] == sp
+    assert 0 < sum(stats["accepted"]) < K * stats["steps"]
+    # one ss_speculative_step per step on the shared cache: the same stream
+    sp2, stats2 = gen.speculative_generate(gt, gd, prompt, n_new, K, T, ud, ua, shared_kv=True)
+    assert sp2 == sp and stats2["accepted"] == stats["accepted"]
+
+
 def test_native_step_refuses_bad_requests_before_touching_a_cache():
     """A step that cannot finish (no room for the draft's rows, no room for the verify rows, K out of range,
     models with different vocabularies) is refused up front: error code set, cache lengths unchanged."""
