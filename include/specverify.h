@@ -6,15 +6,18 @@
  * never frees caller memory.  `stream` is a hipStream_t passed as void* (NULL = the null
  * stream); all work of a call is enqueued on it and, unless a call says otherwise, nothing
  * synchronises with the host.  Handles are not thread-safe: one stream per handle at a time.
- * The entry points without a handle (ss_softmax, ss_speculative_accept*, ss_greedy_accept) share
- * one library-owned device workspace, grown on demand (the only allocation a hot-path call can
- * make, and it synchronises the device when it happens): issue them on one stream at a time.
+ * Hot-path calls (ss_verify_forward, ss_draft_step, ss_softmax, ss_top_p_filter, ss_top_k_filter,
+ * ss_speculative_accept*, ss_greedy_accept, ss_kv_cache_rollback, ss_kv_cache_truncate) allocate
+ * nothing and never wait for the device: the entry points without a handle take a caller-owned
+ * device workspace (ss_workspace_bytes, ss_workspace_init), the others use what their model
+ * allocated when it was created.
  *
  * Return value of every call: SS_OK (0) or a negative code.  Arguments are validated on the
  * host before anything is launched, so SS_EINVAL / SS_ECAPACITY never leave partial device
  * state behind.  ss_last_error() returns a message for the calling thread's last failure.
  * Values that only the device sees (token ids) are clamped into range by the kernels and the
- * event is recorded in a device status word readable through ss_device_status().
+ * event is recorded in a device status word: of the model (ss_device_status) for calls that take
+ * one, of the workspace (ss_workspace_status) for the others.
  *
  * Method references are to the paper's sections: Section 3 (autoregressive vs speculative
  * sampling, the K-rows-for-the-price-of-one premise, recovery of the target distribution),
@@ -35,6 +38,7 @@ extern "C" {
 #define SS_EINVAL (-1)    /* NULL pointer, bad shape, unsupported size */
 #define SS_ECAPACITY (-2) /* KV cache or workspace too small for the request */
 #define SS_EHIP (-3)      /* a HIP runtime call failed; see ss_last_error() */
+#define SS_EABORTED (-4)  /* a bounded wait inside the persistent verify kernel gave up; the call's results are invalid */
 
 #define SS_DTYPE_F32 0
 #define SS_DTYPE_BF16 1
@@ -96,6 +100,17 @@ typedef struct ss_kv_cache ss_kv_cache;
 
 const char *ss_last_error(void);
 
+/* Releases everything the library still holds on every device: all live models and caches are destroyed
+ * (their handles become invalid; a later ss_model_destroy / ss_kv_cache_free on them is a no-op).  Meant to be
+ * called once before the process ends, while the HIP runtime is still up (a Python binding registers it with
+ * atexit), so that no device memory is released from static destructors or interpreter teardown. */
+int ss_shutdown(void);
+
+/* For callers that must prove their decode loop allocates nothing: while `on` is non-zero every path of the
+ * library that would allocate device memory (ss_model_create, ss_kv_cache_alloc / ss_kv_cache_create) fails with
+ * SS_EHIP instead.  The hot-path calls are unaffected: they never allocate. */
+int ss_freeze_allocations(int32_t on);
+
 /* Reads and clears the device status word of `model` (synchronises `stream`).
  * bit 0: a token id outside [0, vocab) reached a kernel and was clamped.
  * bit 1: a device-wide barrier of the persistent verify kernel gave up waiting (its spin is bounded);
@@ -135,7 +150,8 @@ int ss_quantize_rows_int4(const void *w_dev, int32_t dtype, int64_t rows, int64_
  * launch, then `iters` launches timed with a HIP event pair on `stream`; *gbps_host receives
  * bytes * iters / elapsed in GB/s (synchronises `stream`).  It gives the HBM read rate a kernel
  * with no dependencies reaches on this device, the practical ceiling the verify pass (a weight
- * stream, Section 2 "memory bandwidth bound") is judged against next to the nominal figure.
+ * stream: Section 2 describes decoding as bound by memory bandwidth) is judged against next to the
+ * nominal figure.
  * buf_dev: dev, 16-byte aligned, bytes a multiple of 16 and >= 1 MiB, contents arbitrary, never
  * written; take it larger than the last-level cache or the figure is a cache rate.
  * sink_dev: dev, one uint32 the kernel may write.  iters in [1, 10000]. */
@@ -178,18 +194,34 @@ int ss_model_set_persistent_options(ss_model *model, int32_t workgroups, int32_t
  * fail fast (and is how the failure path is tested: the kernel still ends normally).  polls >= 1. */
 int ss_model_set_wait_limit(ss_model *model, uint32_t polls);
 
-/* ---- KV cache (Sections 2, 4.2, 4.4) --------------------------------------------------------
- * kv_cache_alloc: a contiguous, page-free cache for `batch` sequences of up to `max_seq`
- * positions in the model's storage type, allocated (and zero-filled) by the library together
- * with a device array len[batch] of current lengths (all 0).
- * Device layout per layer l, sequence b, head h (S = max_seq rounded up to 64):
+/* Development aid, not part of the method: while buf_dev (dev, `entries` 64-bit words, zero-filled by the caller)
+ * is set and entries >= 5 * phases * workgroups of a launch, every workgroup of the persistent kernel records
+ * the device clock at five points of each phase (start, prologue done, first activation slab in LDS, last
+ * round done, end) at buf[(5 * phase + point) * workgroups + workgroup].  NULL switches it off. */
+int ss_model_set_timeline(ss_model *model, unsigned long long *buf_dev, size_t entries);
+
+/* ---- KV cache (Sections 2, 4.2: keys and values of past tokens are kept instead of recomputed;
+ *      Section 4.4: the caches of the two models have different sizes and the target's goes stale) ----
+ * A contiguous, page-free cache for `batch` sequences of up to `max_seq` positions in the model's
+ * storage type.  The keys and values live in ONE caller-owned device buffer of
+ * ss_kv_cache_bytes(model, batch, max_seq) bytes (16-byte aligned); the library owns only the handle
+ * and a device array len[batch] of current lengths (all 0 after creation).
+ * Layout of the buffer: all keys, then all values; per layer l, sequence b, head h (S = max_seq rounded
+ * up to 64):
  *   K[l][b][h][S][hd]           keys, already rotated, one row per position
  *   V[l][b][h][S/64][hd][64]    values, transposed inside blocks of 64 positions
+ * ss_kv_cache_create clears the buffer (enqueued on `stream`; this call is off the hot path): the
+ * attention kernel multiplies the value entries of masked positions inside a sequence's last block of
+ * 64 by weights that are exactly zero, so those entries must hold finite numbers.  From then on only
+ * this library writes the buffer.  The buffer must outlive the handle; the library never frees it.
  * A model with fewer layers but the same heads and storage type may be run on such a cache: it uses
- * the leading layers (an early-exit draft sharing the target's cache, Section 4.4). */
+ * the leading layers (an early-exit draft sharing the target's cache, Section 4.4).
+ * ss_kv_cache_alloc is the same with a buffer the library allocates (and frees in ss_kv_cache_free). */
+size_t ss_kv_cache_bytes(const ss_model *model, int32_t batch, int32_t max_seq);
+int ss_kv_cache_create(const ss_model *model, int32_t batch, int32_t max_seq, void *buf_dev, size_t buf_bytes,
+                       ss_stream stream, ss_kv_cache **out);
 int ss_kv_cache_alloc(const ss_model *model, int32_t batch, int32_t max_seq, ss_kv_cache **out);
 int ss_kv_cache_free(ss_kv_cache *kv);
-size_t ss_kv_cache_bytes(const ss_model *model, int32_t batch, int32_t max_seq);
 
 /* kv_cache_append: raw append for one sequence and one layer of n_rows rows of already-rotated
  * keys and of values, dev [n_rows][H*hd] in the storage type, at positions pos0..pos0+n_rows-1.
@@ -198,9 +230,18 @@ size_t ss_kv_cache_bytes(const ss_model *model, int32_t batch, int32_t max_seq);
 int ss_kv_cache_append(ss_kv_cache *kv, int32_t layer, int32_t seq, int32_t pos0, const void *k_dev,
                        const void *v_dev, int32_t n_rows, ss_stream stream);
 
-/* Sets every sequence's length from a host array [batch] (0 <= len <= max_seq).  Rows past a
- * length are dead and get overwritten by later appends: truncation moves no data. */
+/* Sets every sequence's length from a host array [batch] (0 <= len <= max_seq); may raise a length (after
+ * raw appends) as well as lower it.  Synchronises `stream` (the host array is read asynchronously): for
+ * building contexts, not for the decode loop.  Rows past a length are dead and get overwritten by later
+ * appends: truncation moves no data (Section 4.4). */
 int ss_kv_cache_set_len(ss_kv_cache *kv, const int32_t *len_host, ss_stream stream);
+/* Truncation from a DEVICE array (Section 4.4: the stale tail of a cache is dropped by moving its length):
+ * len[b] = min(len[b], max(new_len_dev[b], 0)) for every sequence, enqueued on `stream`, no host
+ * synchronisation.  A value above the current length leaves it unchanged and sets bit 2 of the status word
+ * status_dev points to (dev int32, may be NULL).  new_len_host (host int32 [batch], may be NULL) lets the
+ * library tighten the host-side upper bound it keeps for its capacity checks. */
+int ss_kv_cache_truncate(ss_kv_cache *kv, const int32_t *new_len_dev, const int32_t *new_len_host, int32_t *status_dev,
+                         ss_stream stream);
 /* Copies the device lengths to a host array [batch]; synchronises `stream`. */
 int ss_kv_cache_get_len(ss_kv_cache *kv, int32_t *len_host, ss_stream stream);
 
@@ -222,8 +263,10 @@ int ss_kv_cache_rollback(ss_kv_cache *kv, const int32_t *n_accepted_dev, const i
 int ss_verify_forward(ss_model *model, ss_kv_cache *kv, const int32_t *tokens_dev, int32_t batch,
                       int32_t M, float *logits_dev, ss_stream stream);
 
-/* The decoder layers alone over given hidden rows h_dev fp32 [batch*M][d] (updated in place):
- * everything ss_verify_forward does between the embedding and the final norm. */
+/* The decoder layers of the same pass alone (Section 3: the target scores all rows of a call together;
+ * Sections 2, 4.2: against the cache) over given hidden rows h_dev fp32 [batch*M][d], updated in place:
+ * everything ss_verify_forward does between the embedding and the final norm, cache append included.
+ * The entry point of the one-layer workload. */
 int ss_decoder_layers_forward(ss_model *model, ss_kv_cache *kv, float *h_dev, int32_t batch, int32_t M,
                               ss_stream stream);
 
@@ -241,7 +284,7 @@ int ss_draft_step(ss_model *draft, ss_kv_cache *draft_kv, const int32_t *tokens_
                   int32_t m, float temperature, float top_p, const float *u_dev, float *q_rows_dev,
                   int64_t ldq, int32_t *token_out_dev, ss_stream stream);
 
-/* ---- top-p ("nucleus") selection (Section 3 names "randomly selected from top-p" beside argmax) --
+/* ---- top-p ("nucleus") selection (Section 3 names sampling from the top-p set beside argmax) --------
  * Every row of probs_dev fp32 [rows][vocab] is restricted to its most probable tokens whose
  * probabilities add up to at least top_p, and renormalised.  The paper gives no arithmetic; this is
  * the rule, chosen so that any implementation keeps the same set:
@@ -257,12 +300,30 @@ int ss_draft_step(ss_model *draft, ss_kv_cache *draft_kv, const int32_t *tokens_
 int ss_top_p_filter(const float *probs_dev, int32_t rows, int32_t vocab, float top_p, float *out_dev,
                     ss_stream stream);
 
-/* ---- softmax (per-row statistics by wavefront reductions over the vocabulary) ---------------
+/* ---- device workspace of the entry points that take no handle ---------------------------------
+ * ss_softmax, ss_speculative_accept, ss_speculative_accept_logits and ss_greedy_accept keep their
+ * intermediate results (row statistics, per-segment partial sums, arrival counters, a status word) in a
+ * caller-owned device buffer, so that none of them allocates or waits for the device.
+ * ss_workspace_bytes(rows, vocab): size that serves any of these calls touching at most `rows` rows of
+ * `vocab` logits or probabilities in total (softmax: rows; accept: batch * (2K + 1); greedy: batch * (K + 1)).
+ * ss_workspace_init: clears the buffer (enqueued on `stream`); call it once after allocating.  After that
+ * the buffer must only be passed to this library, to one call at a time (calls on different streams
+ * need different workspaces); every call leaves it ready for the next.  A call whose need exceeds
+ * ws_bytes returns SS_ECAPACITY before anything is launched.
+ * ss_workspace_status reads and clears the workspace's status word (synchronises `stream`):
+ * bit 0: a draft token id outside [0, vocab) reached the rejection step and was treated as rejected. */
+size_t ss_workspace_bytes(int64_t rows, int32_t vocab);
+int ss_workspace_init(void *ws_dev, size_t ws_bytes, ss_stream stream);
+int ss_workspace_status(void *ws_dev, size_t ws_bytes, ss_stream stream, int32_t *status_host);
+
+/* ---- softmax (the per-position distributions p and q of Section 3 that the rejection step compares;
+ *      per-row statistics by wavefront reductions over the vocabulary) ----------------------------
  * probs_dev[r][v] = exp(logits[r][v]/T - max_r) / sum_v exp(...), fp32 [rows][vocab], evaluated with the
  * hardware base-2 exponential and one reciprocal per row (relative error a few 1e-6).  Every entry
- * point of the library that turns logits into probabilities produces these same bits. */
+ * point of the library that turns logits into probabilities produces these same bits.
+ * ws_dev / ws_bytes: workspace, at least ss_workspace_bytes(rows, vocab). */
 int ss_softmax(const float *logits_dev, int32_t rows, int32_t vocab, float temperature, float *probs_dev,
-               ss_stream stream);
+               void *ws_dev, size_t ws_bytes, ss_stream stream);
 
 /* ---- modified rejection step (Sections 3, 4.3) -----------------------------------------------
  * p_dev fp32 [batch][K+1][vocab] target probabilities, q_dev fp32 [batch][K][vocab] draft
@@ -274,10 +335,12 @@ int ss_softmax(const float *logits_dev, int32_t rows, int32_t vocab, float tempe
  * by an integer inverse CDF: w_v = trunc(r_v * 2^32), S = sum w_v, threshold = (u*2^24 * S) >> 24,
  * token = smallest v whose inclusive prefix sum exceeds the threshold.  If the residual weights
  * are all 0 the target row itself is sampled; if those are all 0 too, its argmax.  The result is
- * a pure function of the input bits.  K may be 0.  n_accepted_dev, next_token_dev: int32 [batch]. */
+ * a pure function of the input bits.  K may be 0.  n_accepted_dev, next_token_dev: int32 [batch].
+ * ws_dev / ws_bytes: workspace, at least ss_workspace_bytes(batch * (2K + 1), vocab). */
 int ss_speculative_accept(const float *p_dev, const float *q_dev, const int32_t *draft_tokens_dev,
                           const float *uniforms_dev, int32_t batch, int32_t K, int32_t vocab,
-                          int32_t *n_accepted_dev, int32_t *next_token_dev, ss_stream stream);
+                          int32_t *n_accepted_dev, int32_t *next_token_dev, void *ws_dev, size_t ws_bytes,
+                          ss_stream stream);
 
 /* Same step straight from logits: p = softmax(p_logits/T), q = softmax(q_logits/T) are never
  * materialised (one read of the logits for the row statistics, then a re-read of the one or two
@@ -286,18 +349,24 @@ int ss_speculative_accept(const float *p_dev, const float *q_dev, const int32_t 
  * what ss_speculative_accept returns on the
  * probabilities ss_softmax would produce.  p_out_dev / q_out_dev, if not NULL, receive those
  * probabilities ([batch][K+1][vocab] / [batch][K][vocab]).  temperature > 0.  No top-p here: a caller
- * that filters (ss_top_p_filter) materialises the probabilities and uses ss_speculative_accept. */
+ * that filters (ss_top_p_filter) materialises the probabilities and uses ss_speculative_accept.
+ * ws_dev / ws_bytes: workspace, at least ss_workspace_bytes(batch * (2K + 1), vocab). */
 int ss_speculative_accept_logits(const float *p_logits_dev, const float *q_logits_dev, float temperature,
                                  const int32_t *draft_tokens_dev, const float *uniforms_dev,
                                  int32_t batch, int32_t K, int32_t vocab, int32_t *n_accepted_dev,
                                  int32_t *next_token_dev, float *p_out_dev, float *q_out_dev,
-                                 ss_stream stream);
+                                 void *ws_dev, size_t ws_bytes, ss_stream stream);
 
-/* Greedy mode (argmax selection, Section 3): a draft token is accepted iff it equals the argmax
- * of its target row (lowest index on ties); next = argmax of the first mismatching row, or of the
- * bonus row.  p_logits_dev fp32 [batch][K+1][vocab]. */
+/* Greedy mode (Section 3 names argmax as the deterministic selection rule; with one-hot p and q the
+ * rejection rule of Sections 3 / 4.3 reduces to this): a draft token is accepted iff it equals the argmax
+ * of its target row; next = argmax of the first mismatching row, or of the bonus row.  Ties go to the
+ * lowest index (the paper does not say; any fixed rule keeps greedy speculative decoding equal to greedy
+ * autoregressive decoding, i.e. speculation does not change what is generated, as Section 3 requires).
+ * p_logits_dev fp32 [batch][K+1][vocab].  ws_dev / ws_bytes: workspace, at least
+ * ss_workspace_bytes(batch * (K + 1), vocab). */
 int ss_greedy_accept(const float *p_logits_dev, const int32_t *draft_tokens_dev, int32_t batch, int32_t K,
-                     int32_t vocab, int32_t *n_accepted_dev, int32_t *next_token_dev, ss_stream stream);
+                     int32_t vocab, int32_t *n_accepted_dev, int32_t *next_token_dev, void *ws_dev, size_t ws_bytes,
+                     ss_stream stream);
 
 /* ---- one whole speculative step for a single sequence (Sections 3, 4.3, 4.4) -----------------
  * The calls above, issued back to back without returning to the caller, so that a decode loop
@@ -319,9 +388,13 @@ int ss_greedy_accept(const float *p_logits_dev, const int32_t *draft_tokens_dev,
  * type): the draft's K calls append to the target's cache, the length is set back by K before the
  * verify pass rewrites those positions for every layer, and the feed is always one token.
  * All *_dev buffers are the caller's device memory; 1 <= K <= 15; both caches hold one sequence.
+ * The step's softmax and rejection kernels use the target model's own workspace (allocated with the model).
  * Errors as in the calls it is made of; shapes and the room both caches need for the whole step
  * (draft: *n_feed + K - 1 rows, target: K + 1) are checked before the first of them runs, so a
- * refused step leaves both caches as they were. */
+ * refused step leaves both caches as they were.  SS_EABORTED: a bounded wait of the persistent kernel
+ * gave up in one of the step's forward passes (the flag travels to the host with the step's result); the
+ * synchronisation state of both models has been reset, both cache lengths have been put back to the
+ * host-tracked values from before the step, *n_feed and feed_dev are unchanged, the outputs are invalid. */
 int ss_speculative_step(ss_model *target, ss_kv_cache *target_kv, ss_model *draft, ss_kv_cache *draft_kv,
                         int32_t K, float temperature, float top_p, int32_t *feed_dev, int32_t *n_feed,
                         const float *u_draft_dev, const float *u_accept_dev, int32_t *verify_tokens_dev,

@@ -7,6 +7,7 @@ no CPU fallback - importing works without a GPU, calling does not.
 """
 from __future__ import annotations
 
+import atexit
 import ctypes as C
 import os
 
@@ -15,7 +16,7 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libspecverify.so")
 
-SS_OK, SS_EINVAL, SS_ECAPACITY, SS_EHIP = 0, -1, -2, -3
+SS_OK, SS_EINVAL, SS_ECAPACITY, SS_EHIP, SS_EABORTED = 0, -1, -2, -3, -4
 SS_DTYPE_F32, SS_DTYPE_BF16 = 0, 1
 SS_MAX_ROWS_PER_SEQ = 16
 SS_QUANT_NONE, SS_QUANT_INT8, SS_QUANT_INT4_G128 = 0, 1, 2
@@ -27,7 +28,8 @@ EXPORTS = [
     "ss_draft_step", "ss_softmax", "ss_speculative_accept", "ss_speculative_accept_logits",
     "ss_greedy_accept", "ss_profile_enable", "ss_profile_read", "ss_model_set_persistent", "ss_model_set_persistent_options",
     "ss_speculative_step", "ss_probe_read_bandwidth", "ss_quantize_rows_int8", "ss_top_p_filter",
-    "ss_model_set_wait_limit", "ss_quantize_rows_int4",
+    "ss_model_set_wait_limit", "ss_quantize_rows_int4", "ss_shutdown", "ss_kv_cache_create", "ss_kv_cache_truncate",
+    "ss_workspace_bytes", "ss_workspace_init", "ss_workspace_status", "ss_model_set_timeline", "ss_freeze_allocations",
 ]
 
 PROFILE_CLASSES = ["rmsnorm", "qkv_gemm", "attention", "oproj_gemm", "gateup_gemm", "down_gemm", "head_gemm", "other",
@@ -69,11 +71,21 @@ def lib():
         vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
         L.ss_last_error.restype = C.c_char_p
         L.ss_kv_cache_bytes.restype = C.c_size_t
+        L.ss_workspace_bytes.restype = C.c_size_t
+        sz = C.c_size_t
         sig = {
             "ss_device_status": [vp, vp, vp],
             "ss_model_create": [C.POINTER(_Cfg), C.POINTER(_Weights), C.POINTER(vp)],
             "ss_model_destroy": [vp],
             "ss_kv_cache_alloc": [vp, i32, i32, C.POINTER(vp)],
+            "ss_kv_cache_create": [vp, i32, i32, vp, sz, vp, C.POINTER(vp)],
+            "ss_kv_cache_truncate": [vp, vp, vp, vp, vp],
+            "ss_workspace_bytes": [i64, i32],
+            "ss_workspace_init": [vp, sz, vp],
+            "ss_workspace_status": [vp, sz, vp, vp],
+            "ss_model_set_timeline": [vp, vp, sz],
+            "ss_shutdown": [],
+            "ss_freeze_allocations": [i32],
             "ss_kv_cache_free": [vp],
             "ss_kv_cache_bytes": [vp, i32, i32],
             "ss_kv_cache_append": [vp, i32, i32, i32, vp, vp, i32, vp],
@@ -84,10 +96,10 @@ def lib():
             "ss_decoder_layers_forward": [vp, vp, vp, i32, i32, vp],
             "ss_draft_step": [vp, vp, vp, i32, i32, f32, f32, vp, vp, i64, vp, vp],
             "ss_top_p_filter": [vp, i32, i32, f32, vp, vp],
-            "ss_softmax": [vp, i32, i32, f32, vp, vp],
-            "ss_speculative_accept": [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp],
-            "ss_speculative_accept_logits": [vp, vp, f32, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp],
-            "ss_greedy_accept": [vp, vp, i32, i32, i32, vp, vp, vp],
+            "ss_softmax": [vp, i32, i32, f32, vp, vp, sz, vp],
+            "ss_speculative_accept": [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp],
+            "ss_speculative_accept_logits": [vp, vp, f32, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp],
+            "ss_greedy_accept": [vp, vp, i32, i32, i32, vp, vp, vp, sz, vp],
             "ss_profile_enable": [vp, i32],
             "ss_model_set_persistent": [vp, i32],
             "ss_model_set_persistent_options": [vp, i32, i32],
@@ -101,7 +113,19 @@ def lib():
         for name, args in sig.items():
             getattr(L, name).argtypes = args
         _lib = L
+        atexit.register(ss_shutdown)     # releases what is still alive while the HIP runtime is up
     return _lib
+
+
+def ss_freeze_allocations(on: bool):
+    _check(lib().ss_freeze_allocations(int(bool(on))))
+
+
+def ss_shutdown():
+    """Destroys every live model and cache of the library (handles held by Python objects become no-ops)."""
+    if _lib is not None:
+        _lib.ss_shutdown()
+    _workspaces.clear()
 
 
 def _check(rc):
@@ -208,24 +232,82 @@ class Model:
 
 
 class KVCache:
-    def __init__(self, model: Model, batch: int, max_seq: int):
+    """Owner of an ss_kv_cache handle over a buffer allocated here with torch (the caller-owned buffer of
+    ss_kv_cache_create); `buf` may be given to place the cache in existing device memory."""
+
+    def __init__(self, model: Model, batch: int, max_seq: int, buf=None, stream=None):
         self.model, self.batch, self.max_seq = model, batch, max_seq
+        need = lib().ss_kv_cache_bytes(model.handle, batch, max_seq)
         h = C.c_void_p()
-        _check(lib().ss_kv_cache_alloc(model.handle, batch, max_seq, C.byref(h)))
+        if isinstance(buf, str) and buf == "library":     # the convenience call: the library allocates (and frees) the buffer
+            self.buf = None
+            _check(lib().ss_kv_cache_alloc(model.handle, batch, max_seq, C.byref(h)))
+            self.handle = h
+            return
+        if buf is None:
+            buf = torch.empty(max(need, 16), dtype=torch.uint8, device=torch.device("cuda", torch.cuda.current_device()))
+        self.buf = buf
+        _check(lib().ss_kv_cache_create(model.handle, batch, max_seq, _dev(buf), buf.numel() * buf.element_size(), _stream(stream),
+                                        C.byref(h)))
         self.handle = h
 
     def close(self):
         if getattr(self, "handle", None) and _lib is not None:
             _lib.ss_kv_cache_free(self.handle)
             self.handle = None
+        self.buf = None
 
     __del__ = close
+
+
+# ---------------------------------------------------------------------------------- workspaces
+
+_workspaces = {}
+
+
+def ss_workspace_bytes(rows: int, vocab: int) -> int:
+    return lib().ss_workspace_bytes(int(rows), int(vocab))
+
+
+def ss_workspace_init(ws, stream=None):
+    _check(lib().ss_workspace_init(_dev(ws), ws.numel() * ws.element_size(), _stream(stream)))
+    return ws
+
+
+def ss_workspace_status(ws, stream=None) -> int:
+    out = C.c_int32(0)
+    _check(lib().ss_workspace_status(_dev(ws), ws.numel() * ws.element_size(), _stream(stream), C.byref(out)))
+    return out.value
+
+
+def workspace(device, rows: int, vocab: int):
+    """A device workspace for the calls without a handle: one per (device, stream), kept between calls and
+    replaced by a larger one when a call needs more (memory plumbing: the C calls never allocate)."""
+    need = ss_workspace_bytes(rows, vocab)
+    key = (str(device), torch.cuda.current_stream().cuda_stream)
+    ws = _workspaces.get(key)
+    if ws is None or ws.numel() < need:
+        ws = torch.empty(max(need, 1 << 20), dtype=torch.uint8, device=device)
+        ss_workspace_init(ws)
+        _workspaces[key] = ws
+    return ws
+
+
+def _ws_args(ws, device, rows, vocab):
+    if ws is None:
+        ws = workspace(device, rows, vocab)
+    return _dev(ws), ws.numel() * ws.element_size()
 
 
 # ---------------------------------------------------------------------------------- entry points
 
 def ss_kv_cache_alloc(model: Model, batch: int, max_seq: int) -> KVCache:
     return KVCache(model, batch, max_seq)
+
+
+def ss_kv_cache_create(model: Model, batch: int, max_seq: int, buf, stream=None) -> KVCache:
+    """A cache over the caller's device buffer `buf` (at least ss_kv_cache_bytes bytes; the call clears it)."""
+    return KVCache(model, batch, max_seq, buf=buf, stream=stream)
 
 
 def ss_kv_cache_bytes(model: Model, batch: int, max_seq: int) -> int:
@@ -241,6 +323,15 @@ def ss_kv_cache_set_len(kv: KVCache, lens, stream=None):
     if a.size != kv.batch:
         raise ValueError("one length per sequence")
     _check(lib().ss_kv_cache_set_len(kv.handle, p, _stream(stream)))
+
+
+def ss_kv_cache_truncate(kv: KVCache, new_len, new_len_host=None, status=None, stream=None):
+    """Device-side truncation: len[b] = min(len[b], new_len[b]) (new_len: device int32 [batch])."""
+    hp = C.c_void_p(0)
+    if new_len_host is not None:
+        keep, hp = _host_i32(new_len_host)
+    _check(lib().ss_kv_cache_truncate(kv.handle, _dev(new_len, torch.int32), hp, _dev(status, torch.int32 if status is not None else None),
+                                      _stream(stream)))
 
 
 def ss_kv_cache_get_len(kv: KVCache, stream=None):
@@ -284,13 +375,13 @@ def ss_draft_step(draft: Model, kv: KVCache, tokens, m: int, temperature: float,
     return token_out
 
 
-def ss_softmax(logits, temperature: float, probs=None, stream=None):
+def ss_softmax(logits, temperature: float, probs=None, stream=None, ws=None):
     V = logits.shape[-1]
     rows = logits.numel() // V
     if probs is None:
         probs = torch.empty_like(logits)
     _check(lib().ss_softmax(_dev(logits, torch.float32), rows, V, float(temperature), _dev(probs, torch.float32),
-                            _stream(stream)))
+                            *_ws_args(ws, logits.device, rows, V), _stream(stream)))
     return probs
 
 
@@ -312,33 +403,34 @@ def _accept_out(batch, device, n_accepted, next_token):
     return n_accepted, next_token
 
 
-def ss_speculative_accept(p, q, draft_tokens, uniforms, n_accepted=None, next_token=None, stream=None):
+def ss_speculative_accept(p, q, draft_tokens, uniforms, n_accepted=None, next_token=None, stream=None, ws=None):
     B, K1, V = p.shape
     n_accepted, next_token = _accept_out(B, p.device, n_accepted, next_token)
     _check(lib().ss_speculative_accept(_dev(p, torch.float32), _dev(q, torch.float32) if K1 > 1 else C.c_void_p(0),
                                        _dev(draft_tokens, torch.int32) if K1 > 1 else C.c_void_p(0),
                                        _dev(uniforms, torch.float32), B, K1 - 1, V, _dev(n_accepted), _dev(next_token),
-                                       _stream(stream)))
+                                       *_ws_args(ws, p.device, B * (2 * K1 - 1), V), _stream(stream)))
     return n_accepted, next_token
 
 
 def ss_speculative_accept_logits(p_logits, q_logits, temperature, draft_tokens, uniforms, n_accepted=None,
-                                 next_token=None, p_out=None, q_out=None, stream=None):
+                                 next_token=None, p_out=None, q_out=None, stream=None, ws=None):
     B, K1, V = p_logits.shape
     n_accepted, next_token = _accept_out(B, p_logits.device, n_accepted, next_token)
     _check(lib().ss_speculative_accept_logits(
         _dev(p_logits, torch.float32), _dev(q_logits, torch.float32) if K1 > 1 else C.c_void_p(0), float(temperature),
         _dev(draft_tokens, torch.int32) if K1 > 1 else C.c_void_p(0), _dev(uniforms, torch.float32), B, K1 - 1, V,
-        _dev(n_accepted), _dev(next_token), _dev(p_out), _dev(q_out), _stream(stream)))
+        _dev(n_accepted), _dev(next_token), _dev(p_out), _dev(q_out), *_ws_args(ws, p_logits.device, B * (2 * K1 - 1), V),
+        _stream(stream)))
     return n_accepted, next_token
 
 
-def ss_greedy_accept(p_logits, draft_tokens, n_accepted=None, next_token=None, stream=None):
+def ss_greedy_accept(p_logits, draft_tokens, n_accepted=None, next_token=None, stream=None, ws=None):
     B, K1, V = p_logits.shape
     n_accepted, next_token = _accept_out(B, p_logits.device, n_accepted, next_token)
     _check(lib().ss_greedy_accept(_dev(p_logits, torch.float32),
                                   _dev(draft_tokens, torch.int32) if K1 > 1 else C.c_void_p(0), B, K1 - 1, V,
-                                  _dev(n_accepted), _dev(next_token), _stream(stream)))
+                                  _dev(n_accepted), _dev(next_token), *_ws_args(ws, p_logits.device, B * K1, V), _stream(stream)))
     return n_accepted, next_token
 
 
@@ -413,6 +505,14 @@ def ss_probe_read_bandwidth(buf, iters=20, stream=None):
 
 def ss_model_set_persistent_options(model: Model, workgroups: int = 0, data_sync: bool = True):
     _check(lib().ss_model_set_persistent_options(model.handle, int(workgroups), int(bool(data_sync))))
+
+
+def ss_model_set_timeline(model: Model, buf):
+    """Development aid: device clock samples of the persistent kernel into `buf` (int64 device tensor, zero-filled)."""
+    if buf is None:
+        _check(lib().ss_model_set_timeline(model.handle, C.c_void_p(0), 0))
+    else:
+        _check(lib().ss_model_set_timeline(model.handle, _dev(buf, torch.int64), buf.numel()))
 
 
 def ss_model_set_wait_limit(model: Model, polls: int):

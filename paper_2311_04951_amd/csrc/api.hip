@@ -11,8 +11,10 @@
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
+#include <set>
 #include <string>
 #include <algorithm>
+#include <atomic>
 #include <vector>
 
 using namespace ss;
@@ -64,6 +66,10 @@ struct ss_model {
     size_t splitk_ws_bytes = 0;
     unsigned *stats_cnt = nullptr; // [max_rows] arrival counters of the segmented row statistics (zero between launches)
     float2 *stats_part = nullptr;  // per-segment partial statistics
+    void *ws = nullptr;            // workspace of the softmax / rejection kernels of ss_speculative_step (layout: see workspace section)
+    size_t ws_bytes = 0;
+    unsigned long long *timeline = nullptr; // development aid: caller's buffer of device clock samples (ss_model_set_timeline)
+    size_t timeline_entries = 0;
     float2 *rope;     // [max_pos][hd/2]
     int32_t *status;
     std::vector<void *> owned;
@@ -119,7 +125,8 @@ struct ProfScope {
 struct ss_kv_cache {
     int n_layers, H, hd, dtype, esz;
     int B, max_seq, S;
-    void *k, *v; // [n_layers][B][H][S][hd] each (V block-transposed)
+    void *k, *v; // [n_layers][B][H][S][hd] each (V block-transposed): the two halves of one buffer
+    bool owns_buf; // the buffer was allocated by ss_kv_cache_alloc (else it is the caller's)
     int32_t *len_dev;
     std::vector<int32_t> len_ub; // host upper bound of every length
     size_t layer_elems;
@@ -129,20 +136,51 @@ static const int MAX_SPLITS = 16;
 
 extern "C" const char *ss_last_error(void) { return g_err.c_str(); }
 
+// Live handles.  ss_shutdown() destroys whatever is still alive while the HIP runtime is up; destroy / free calls
+// on a handle that is no longer registered do nothing, so a binding may release its objects in any order.
+static std::mutex g_reg_mu;
+static std::set<ss_model *> g_models;
+static std::set<ss_kv_cache *> g_caches;
+static bool reg_take(ss_model *m) {
+    std::lock_guard<std::mutex> lk(g_reg_mu);
+    return g_models.erase(m) != 0;
+}
+static bool reg_take(ss_kv_cache *kv) {
+    std::lock_guard<std::mutex> lk(g_reg_mu);
+    return g_caches.erase(kv) != 0;
+}
+
 // ------------------------------------------------------------------------------------------ model
 
+// ss_freeze_allocations: while set, every path of the library that would allocate device memory fails instead
+static std::atomic<int> g_alloc_frozen{0};
+static hipError_t lib_malloc(void **p, size_t bytes) {
+    if (g_alloc_frozen.load()) return hipErrorOutOfMemory;
+    return hipMalloc(p, bytes);
+}
+
+extern "C" int ss_freeze_allocations(int32_t on) {
+    g_alloc_frozen.store(on != 0);
+    return SS_OK;
+}
+
 static int dev_alloc(ss_model *m, void **p, size_t bytes, bool zero) {
+    if (g_alloc_frozen.load()) return fail(SS_EHIP, "device allocations are frozen (ss_freeze_allocations)");
     HIP_TRY(hipMalloc(p, bytes ? bytes : 16));
     m->owned.push_back(*p);
     if (zero) HIP_TRY(hipMemset(*p, 0, bytes ? bytes : 16));
     return SS_OK;
 }
 
-extern "C" int ss_model_destroy(ss_model *m) {
-    if (!m) return SS_OK;
+static void model_release(ss_model *m) {
     for (void *p : m->owned) (void)hipFree(p);
     for (hipEvent_t e : m->ev) (void)hipEventDestroy(e);
     delete m;
+}
+
+extern "C" int ss_model_destroy(ss_model *m) {
+    if (!m || !reg_take(m)) return SS_OK;
+    model_release(m);
     return SS_OK;
 }
 
@@ -203,10 +241,12 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
     }
     A((void **)&m->stats_cnt, sizeof(unsigned) * (size_t)c.max_rows, true);
     A((void **)&m->stats_part, row_stats_partial_bytes(c.max_rows, c.vocab) + 16, true);
+    m->ws_bytes = ss_workspace_bytes(2 * (int64_t)c.max_rows, c.vocab); // target rows + draft rows of a step
+    A(&m->ws, m->ws_bytes, true);
     A((void **)&m->rope, sizeof(float2) * (size_t)c.max_pos * (c.head_dim / 2), false);
     A((void **)&m->status, sizeof(int32_t), true);
     if (rc != SS_OK) {
-        ss_model_destroy(m);
+        model_release(m);
         return rc;
     }
     // phase programs of the persistent verify kernel
@@ -271,7 +311,7 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
                     if (e1 != hipSuccess || e2 != hipSuccess) rc = fail(SS_EHIP, "program upload failed");
                 }
                 if (rc != SS_OK) {
-                    ss_model_destroy(m);
+                    model_release(m);
                     return rc;
                 }
             }
@@ -290,11 +330,15 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
         }
         hipError_t e = hipMemcpy(m->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice);
         if (e != hipSuccess) {
-            ss_model_destroy(m);
+            model_release(m);
             return fail(SS_EHIP, "rope table upload: %s", hipGetErrorString(e));
         }
     }
     m->persistent = m->mega_G > 0; // calls of at most 16 rows use the persistent kernel unless told otherwise
+    {
+        std::lock_guard<std::mutex> lk(g_reg_mu);
+        g_models.insert(m);
+    }
     *out = m;
     return SS_OK;
 }
@@ -400,19 +444,27 @@ extern "C" size_t ss_kv_cache_bytes(const ss_model *m, int32_t batch, int32_t ma
     return 2 * (size_t)m->cfg.n_layers * batch * m->W * S * m->esz;
 }
 
-extern "C" int ss_kv_cache_free(ss_kv_cache *kv) {
-    if (!kv) return SS_OK;
-    if (kv->k) (void)hipFree(kv->k);
-    if (kv->v) (void)hipFree(kv->v);
+static void cache_release(ss_kv_cache *kv) {
+    if (kv->owns_buf && kv->k) (void)hipFree(kv->k);
     if (kv->len_dev) (void)hipFree(kv->len_dev);
     delete kv;
+}
+
+extern "C" int ss_kv_cache_free(ss_kv_cache *kv) {
+    if (!kv || !reg_take(kv)) return SS_OK;
+    cache_release(kv);
     return SS_OK;
 }
 
-extern "C" int ss_kv_cache_alloc(const ss_model *m, int32_t batch, int32_t max_seq, ss_kv_cache **out) {
-    if (!m || !out) return fail(SS_EINVAL, "ss_kv_cache_alloc: NULL argument");
-    if (batch <= 0 || max_seq <= 0) return fail(SS_EINVAL, "batch and max_seq must be positive");
-    if (max_seq > m->cfg.max_pos) return fail(SS_EINVAL, "max_seq %d exceeds the model's rotary table (%d)", max_seq, m->cfg.max_pos);
+// handle over the caller's buffer (or one allocated here when buf is NULL): keys in the first half, values in the second
+static int cache_create(const ss_model *m, int32_t batch, int32_t max_seq, void *buf, size_t buf_bytes, hipStream_t st, ss_kv_cache **out,
+                        const char *who) {
+    if (!m || !out) return fail(SS_EINVAL, "%s: NULL argument", who);
+    if (batch <= 0 || max_seq <= 0) return fail(SS_EINVAL, "%s: batch and max_seq must be positive", who);
+    if (max_seq > m->cfg.max_pos) return fail(SS_EINVAL, "%s: max_seq %d exceeds the model's rotary table (%d)", who, max_seq, m->cfg.max_pos);
+    const size_t need = ss_kv_cache_bytes(m, batch, max_seq);
+    if (buf && buf_bytes < need) return fail(SS_ECAPACITY, "%s: the buffer has %zu bytes, the cache needs %zu", who, buf_bytes, need);
+    if (buf && ((uintptr_t)buf & 15)) return fail(SS_EINVAL, "%s: the buffer must be 16-byte aligned", who);
     ss_kv_cache *kv = new ss_kv_cache();
     kv->n_layers = m->cfg.n_layers;
     kv->H = m->cfg.n_heads;
@@ -425,21 +477,41 @@ extern "C" int ss_kv_cache_alloc(const ss_model *m, int32_t batch, int32_t max_s
     kv->layer_elems = (size_t)batch * kv->H * kv->S * kv->hd;
     kv->k = kv->v = nullptr;
     kv->len_dev = nullptr;
+    kv->owns_buf = buf == nullptr;
     kv->len_ub.assign(batch, 0);
-    const size_t bytes = kv->layer_elems * kv->n_layers * kv->esz;
-    hipError_t e = hipMalloc(&kv->k, bytes ? bytes : 16);
-    if (e == hipSuccess) e = hipMalloc(&kv->v, bytes ? bytes : 16);
-    if (e == hipSuccess) e = hipMalloc((void **)&kv->len_dev, sizeof(int32_t) * batch);
-    // zero fill: attention may touch (masked) positions past a length, which must hold finite values
-    if (e == hipSuccess) e = hipMemset(kv->k, 0, bytes ? bytes : 16);
-    if (e == hipSuccess) e = hipMemset(kv->v, 0, bytes ? bytes : 16);
-    if (e == hipSuccess) e = hipMemset(kv->len_dev, 0, sizeof(int32_t) * batch);
+    hipError_t e = hipSuccess;
+    if (!buf) e = lib_malloc(&buf, need ? need : 16);
+    if (e == hipSuccess) {
+        kv->k = buf;
+        kv->v = (char *)buf + need / 2;
+        e = lib_malloc((void **)&kv->len_dev, sizeof(int32_t) * batch);
+    }
+    // zero fill: attention multiplies the (masked) value entries past a length inside its last block by zero weights,
+    // so they must hold finite numbers
+    if (e == hipSuccess && need) e = hipMemsetAsync(buf, 0, need, st);
+    if (e == hipSuccess) e = hipMemsetAsync(kv->len_dev, 0, sizeof(int32_t) * batch, st);
     if (e != hipSuccess) {
-        ss_kv_cache_free(kv);
-        return fail(SS_EHIP, "ss_kv_cache_alloc: %s", hipGetErrorString(e));
+        cache_release(kv);
+        return fail(SS_EHIP, "%s: %s", who, hipGetErrorString(e));
+    }
+    {
+        std::lock_guard<std::mutex> lk(g_reg_mu);
+        g_caches.insert(kv);
     }
     *out = kv;
     return SS_OK;
+}
+
+extern "C" int ss_kv_cache_create(const ss_model *m, int32_t batch, int32_t max_seq, void *buf_dev, size_t buf_bytes, ss_stream stream,
+                                  ss_kv_cache **out) {
+    if (!buf_dev) return fail(SS_EINVAL, "ss_kv_cache_create: buf_dev is NULL");
+    return cache_create(m, batch, max_seq, buf_dev, buf_bytes, (hipStream_t)stream, out, "ss_kv_cache_create");
+}
+
+extern "C" int ss_kv_cache_alloc(const ss_model *m, int32_t batch, int32_t max_seq, ss_kv_cache **out) {
+    int rc = cache_create(m, batch, max_seq, nullptr, 0, nullptr, out, "ss_kv_cache_alloc");
+    if (rc == SS_OK) HIP_TRY(hipStreamSynchronize(nullptr));
+    return rc;
 }
 
 extern "C" int ss_kv_cache_append(ss_kv_cache *kv, int32_t layer, int32_t seq, int32_t pos0, const void *k_dev,
@@ -464,6 +536,15 @@ extern "C" int ss_kv_cache_set_len(ss_kv_cache *kv, const int32_t *len_host, ss_
     HIP_TRY(hipStreamSynchronize(st));
     kv->len_ub.assign(len_host, len_host + kv->B);
     return SS_OK;
+}
+
+extern "C" int ss_kv_cache_truncate(ss_kv_cache *kv, const int32_t *new_len_dev, const int32_t *new_len_host, int32_t *status_dev,
+                                    ss_stream stream) {
+    if (!kv || !new_len_dev) return fail(SS_EINVAL, "ss_kv_cache_truncate: NULL argument");
+    launch_len_truncate(kv->len_dev, new_len_dev, kv->B, status_dev, (hipStream_t)stream);
+    if (new_len_host)
+        for (int b = 0; b < kv->B; ++b) kv->len_ub[b] = std::min(kv->len_ub[b], std::max(new_len_host[b], 0));
+    return check_launch();
 }
 
 extern "C" int ss_kv_cache_get_len(ss_kv_cache *kv, int32_t *len_host, ss_stream stream) {
@@ -626,6 +707,13 @@ extern "C" int ss_model_set_persistent_options(ss_model *m, int32_t workgroups, 
     return SS_OK;
 }
 
+extern "C" int ss_model_set_timeline(ss_model *m, unsigned long long *buf_dev, size_t entries) {
+    if (!m) return fail(SS_EINVAL, "ss_model_set_timeline: NULL model");
+    m->timeline = buf_dev;
+    m->timeline_entries = buf_dev ? entries : 0;
+    return SS_OK;
+}
+
 extern "C" int ss_model_set_wait_limit(ss_model *m, uint32_t polls) {
     if (!m) return fail(SS_EINVAL, "ss_model_set_wait_limit: NULL model");
     if (polls < 1) return fail(SS_EINVAL, "ss_model_set_wait_limit: at least one poll");
@@ -676,80 +764,14 @@ static int run_persistent(ss_model *m, ss_kv_cache *kv, const int32_t *tokens, f
     P.status = m->status;
     P.zeros = m->zeros;
     m->epoch += (unsigned)P.n_phases + 1;
-    // development aid (SS_TIMELINE=1): device clock samples of every workgroup at each phase's start,
-    // after its prologue and at its end, summarised per phase kind on stderr after the launch
-    static const bool want_timeline = getenv("SS_TIMELINE") != nullptr;
-    static unsigned long long *tl_dev = nullptr;
-    static size_t tl_cap = 0;
-    const size_t tl_need = (size_t)5 * P.n_phases * m->mega_G;
-    if (want_timeline) {
-        if (tl_cap < tl_need) {
-            if (tl_dev) HIP_TRY(hipFree(tl_dev));
-            HIP_TRY(hipMalloc((void **)&tl_dev, sizeof(unsigned long long) * tl_need));
-            HIP_TRY(hipMemset(tl_dev, 0, sizeof(unsigned long long) * tl_need));
-            tl_cap = tl_need;
-        }
-        P.timeline = tl_dev;
-    }
+    // development aid: device clock samples of every workgroup, into the caller's buffer when it is large enough
+    if (m->timeline && m->timeline_entries >= (size_t)5 * P.n_phases * m->mega_G) P.timeline = m->timeline;
     {
         ProfScope ps(m, PT_PERSISTENT, st);
         hipError_t e = launch_mega(P, m->mega_G, st);
         if (e != hipSuccess) return fail(SS_EHIP, "persistent verify kernel launch: %s", hipGetErrorString(e));
     }
     for (int b = 0; b < batch; ++b) kv->len_ub[b] += M;
-    if (want_timeline) {
-        const int G = m->mega_G, NP = P.n_phases;
-        std::vector<unsigned long long> t(tl_need);
-        std::vector<MegaPhase> ph(NP);
-        HIP_TRY(hipStreamSynchronize(st));
-        HIP_TRY(hipMemcpy(t.data(), tl_dev, t.size() * 8, hipMemcpyDeviceToHost));
-        HIP_TRY(hipMemcpy(ph.data(), P.phases, ph.size() * sizeof(MegaPhase), hipMemcpyDeviceToHost));
-        auto at = [&](int p, int k, int wg) { return (double)t[((size_t)5 * p + k) * G + wg] * 0.01; }; // 100 MHz clock
-        // per phase kind, averaged over its occurrences: medians over workgroups of the time from the
-        // phase's start to (prologue done, first slab in LDS, last round done, end), the slowest
-        // workgroup's end, and the time from the last end to the first start of the next phase
-        double acc[8][7] = {{0}};
-        int cnt[8] = {0};
-        std::vector<double> w(G);
-        auto median_of = [&](int p, int k) {
-            int n = 0;
-            for (int g = 0; g < G; ++g)
-                if (t[((size_t)5 * p + k) * G + g]) w[n++] = at(p, k, g) - at(p, 0, g);
-            if (!n) return 0.0;
-            std::sort(w.begin(), w.begin() + n);
-            return w[n / 2];
-        };
-        for (int p = 0; p < NP; ++p) {
-            const int slot = (ph[p].kind == PH_RESID && ph[p].K == c.d_ff) ? 7 : ph[p].kind;
-            double s0 = 1e300, s1 = 0, e1 = 0, n0 = 1e300;
-            for (int g = 0; g < G; ++g) {
-                s0 = std::min(s0, at(p, 0, g)); s1 = std::max(s1, at(p, 0, g)); e1 = std::max(e1, at(p, 4, g));
-                if (p + 1 < NP) n0 = std::min(n0, at(p + 1, 0, g));
-            }
-            acc[slot][0] += s1 - s0;
-            for (int k = 1; k <= 4; ++k) acc[slot][k] += median_of(p, k);
-            acc[slot][5] += e1 - s0;
-            if (p + 1 < NP) acc[slot][6] += n0 - e1;
-            cnt[slot]++;
-        }
-        if (getenv("SS_TIMELINE_WG")) { // rounds_done time of every workgroup in the first SwiGLU phase, 8 per line (XCD = column)
-            for (int p = 0; p < NP; ++p)
-                if (ph[p].kind == PH_SWIGLU) {
-                    for (int g = 0; g < G; ++g) fprintf(stderr, "%6.1f%s", at(p, 3, g) - at(p, 0, g), g % 8 == 7 ? "\n" : " ");
-                    fprintf(stderr, "epilogue (end - rounds_done):\n");
-                    for (int g = 0; g < G; ++g) fprintf(stderr, "%6.1f%s", at(p, 4, g) - at(p, 3, g), g % 8 == 7 ? "\n" : " ");
-                    break;
-                }
-        }
-        HIP_TRY(hipMemset(tl_dev, 0, sizeof(unsigned long long) * tl_need));
-        const char *names[8] = {"embed", "qkv", "attn", "oproj", "gateup", "head", "len", "down"};
-        fprintf(stderr, "[timeline] total %.1f us\n", at(NP - 1, 4, 0) - at(0, 0, 0));
-        for (int k = 0; k < 8; ++k)
-            if (cnt[k])
-                fprintf(stderr, "  %-7s n=%d start_skew=%.1f | median: prologue=%.1f slab=%.1f rounds_done=%.1f end=%.1f | last_end=%.1f sync_after=%.1f\n",
-                        names[k], cnt[k], acc[k][0] / cnt[k], acc[k][1] / cnt[k], acc[k][2] / cnt[k], acc[k][3] / cnt[k], acc[k][4] / cnt[k],
-                        acc[k][5] / cnt[k], acc[k][6] / cnt[k]);
-    }
     return SS_OK;
 }
 
@@ -850,12 +872,8 @@ extern "C" int ss_draft_step(ss_model *m, ss_kv_cache *kv, const int32_t *tokens
 
 // ------------------------------------------------------------------------------------------ softmax / accept
 
-// Library scratch for the standalone softmax / accept entry points (row statistics, row argmax,
-// status word): one buffer per process, grown on demand, so steady-state calls allocate nothing.
-static std::mutex g_scratch_mu;
-static void *g_scratch = nullptr;
-static size_t g_scratch_bytes = 0;
-
+// Workspace of the softmax / accept entry points (row statistics, per-segment sums, row argmax, status word): device
+// memory of the caller (or of a model, for ss_speculative_step), cleared once by ss_workspace_init.
 // Layout: [0, 256) device status word; [256, SCR_DATA) arrival counters of the segmented row statistics, a
 // zone no call uses for anything else, so that they are zero whenever a launch starts (the kernels leave
 // them zero); [SCR_DATA, ...) per-call data.
@@ -863,28 +881,56 @@ constexpr size_t SCR_CNT_ROWS = 16384, SCR_DATA = 256 + sizeof(unsigned) * SCR_C
 static unsigned *scr_cnt(void *ws) { return (unsigned *)((char *)ws + 256); }
 static void *scr_data(void *ws) { return (char *)ws + SCR_DATA; }
 
-static int scratch(size_t bytes, void **out) {
-    std::lock_guard<std::mutex> lk(g_scratch_mu);
-    bytes += SCR_DATA;
-    if (bytes > g_scratch_bytes) {
-        if (g_scratch) {
-            HIP_TRY(hipDeviceSynchronize());
-            HIP_TRY(hipFree(g_scratch));
-            g_scratch = nullptr;
-            g_scratch_bytes = 0;
-        }
-        size_t n = std::max(bytes, (size_t)1 << 20);
-        HIP_TRY(hipMalloc(&g_scratch, n));
-        HIP_TRY(hipMemset(g_scratch, 0, n));
-        g_scratch_bytes = n;
-    }
-    *out = g_scratch;
+// rows per launch of the row statistics: the counter zone, and the grid's y extent
+static size_t stats_rows_per_launch(int V) { return row_stats_segments(V) > 1 ? SCR_CNT_ROWS : (size_t)65535; }
+
+// what each call keeps behind SCR_DATA
+static size_t softmax_need(size_t rows, int V) {
+    return SCR_DATA + sizeof(float2) * rows + row_stats_partial_bytes((int)std::min(rows, stats_rows_per_launch(V)), V) + 16;
+}
+static size_t accept_need(int B, int V) { return SCR_DATA + accept_workspace_bytes(B, V) + 16; }
+static size_t accept_logits_need(int B, int K, int V) {
+    const size_t rows = (size_t)B * (2 * K + 1);
+    return SCR_DATA + sizeof(float2) * rows + ((accept_workspace_bytes(B, V) + 15) & ~(size_t)15) +
+           row_stats_partial_bytes((int)std::min(rows, stats_rows_per_launch(V)), V) + 16;
+}
+static size_t greedy_need(int B, int K) { return SCR_DATA + sizeof(int32_t) * (size_t)B * (K + 1) + 16; }
+
+extern "C" size_t ss_workspace_bytes(int64_t rows, int32_t vocab) {
+    if (rows < 0 || vocab <= 0) return 0;
+    const size_t r = (size_t)std::max<int64_t>(rows, 1);
+    // an upper bound of the four calls' needs when they touch `rows` rows in total (a batch is at most `rows` sequences)
+    const size_t acc = sizeof(unsigned long long) * r * 16; // per-segment sums of the rejection step: at most 16 segments per sequence
+    return SCR_DATA + sizeof(float2) * r + ((acc + 15) & ~(size_t)15) + row_stats_partial_bytes((int)std::min(r, stats_rows_per_launch(vocab)), vocab) +
+           sizeof(int32_t) * r + 64;
+}
+
+static int check_ws(const void *ws, size_t have, size_t need, const char *who) {
+    if (!ws) return fail(SS_EINVAL, "%s: ws_dev is NULL", who);
+    if ((uintptr_t)ws & 15) return fail(SS_EINVAL, "%s: the workspace must be 16-byte aligned", who);
+    if (have < need) return fail(SS_ECAPACITY, "%s: the workspace has %zu bytes, this call needs %zu (ss_workspace_bytes)", who, have, need);
     return SS_OK;
 }
 
-// rows per launch of the row statistics: the counter zone, and the grid's y extent
-static size_t stats_rows_per_launch(int V) { return row_stats_segments(V) > 1 ? SCR_CNT_ROWS : (size_t)65535; }
-// statistics of `rows` rows with the scratch's counters; part: room for stats_rows_per_launch(V) rows
+extern "C" int ss_workspace_init(void *ws_dev, size_t ws_bytes, ss_stream stream) {
+    int rc = check_ws(ws_dev, ws_bytes, SCR_DATA, "ss_workspace_init");
+    if (rc) return rc;
+    launch_fill_u32((uint32_t *)ws_dev, ws_bytes / 4, 0u, (hipStream_t)stream);
+    return check_launch();
+}
+
+extern "C" int ss_workspace_status(void *ws_dev, size_t ws_bytes, ss_stream stream, int32_t *status_host) {
+    int rc = check_ws(ws_dev, ws_bytes, SCR_DATA, "ss_workspace_status");
+    if (rc) return rc;
+    if (!status_host) return fail(SS_EINVAL, "ss_workspace_status: status_host is NULL");
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(hipMemcpyAsync(status_host, ws_dev, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (*status_host) launch_fill_u32((uint32_t *)ws_dev, 1, 0u, st);
+    return check_launch();
+}
+
+// statistics of `rows` rows with the workspace's counters; part: room for stats_rows_per_launch(V) rows
 static void stats_rows(const float *logits, size_t rows, int V, float inv_t, float2 *stats, void *ws, float2 *part, hipStream_t st) {
     const size_t step = stats_rows_per_launch(V);
     for (size_t r0 = 0; r0 < rows; r0 += step)
@@ -892,12 +938,10 @@ static void stats_rows(const float *logits, size_t rows, int V, float inv_t, flo
 }
 
 extern "C" int ss_softmax(const float *logits_dev, int32_t rows, int32_t vocab, float temperature, float *probs_dev,
-                          ss_stream stream) {
+                          void *ws, size_t ws_bytes, ss_stream stream) {
     if (!logits_dev || !probs_dev) return fail(SS_EINVAL, "ss_softmax: NULL argument");
     if (rows < 0 || vocab <= 0 || !(temperature > 0.f)) return fail(SS_EINVAL, "ss_softmax: bad rows/vocab/temperature");
-    void *ws;
-    const size_t part_bytes = row_stats_partial_bytes((int)std::min((size_t)rows, stats_rows_per_launch(vocab)), vocab);
-    int rc = scratch(sizeof(float2) * (size_t)rows + part_bytes, &ws);
+    int rc = check_ws(ws, ws_bytes, softmax_need((size_t)rows, vocab), "ss_softmax");
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
     const float inv_t = 1.0f / temperature;
@@ -915,34 +959,38 @@ static int check_accept(const void *p, const void *q, const void *d, const void 
     return SS_OK;
 }
 
+// the rejection step on materialised probabilities; status: device status word, partial: accept_workspace_bytes(B, V) bytes
+static void accept_probs(const float *p, const float *q, const int32_t *d, const float *u, int B, int K, int V, int32_t *na, int32_t *nx,
+                         int32_t *status, unsigned long long *partial, hipStream_t st) {
+    AcceptArgs a{};
+    a.p = p; a.q = q; a.from_logits = 0; a.inv_t = 1.f;
+    a.draft = d; a.u = u; a.B = B; a.K = K; a.V = V;
+    a.n_accepted = na; a.next_token = nx; a.status = status;
+    launch_accept(a, partial, st);
+}
+
 extern "C" int ss_speculative_accept(const float *p_dev, const float *q_dev, const int32_t *draft_tokens_dev,
                                      const float *uniforms_dev, int32_t batch, int32_t K, int32_t vocab,
-                                     int32_t *n_accepted_dev, int32_t *next_token_dev, ss_stream stream) {
+                                     int32_t *n_accepted_dev, int32_t *next_token_dev, void *ws, size_t ws_bytes, ss_stream stream) {
     int rc = check_accept(p_dev, q_dev, draft_tokens_dev, uniforms_dev, batch, K, vocab, n_accepted_dev, next_token_dev, "ss_speculative_accept");
     if (rc) return rc;
-    void *ws;
-    rc = scratch(accept_workspace_bytes(batch, vocab), &ws);
+    rc = check_ws(ws, ws_bytes, accept_need(batch, vocab), "ss_speculative_accept");
     if (rc) return rc;
-    AcceptArgs a{};
-    a.p = p_dev; a.q = q_dev; a.from_logits = 0; a.inv_t = 1.f;
-    a.draft = draft_tokens_dev; a.u = uniforms_dev; a.B = batch; a.K = K; a.V = vocab;
-    a.n_accepted = n_accepted_dev; a.next_token = next_token_dev; a.status = (int32_t *)ws;
-    launch_accept(a, (unsigned long long *)scr_data(ws), (hipStream_t)stream);
+    accept_probs(p_dev, q_dev, draft_tokens_dev, uniforms_dev, batch, K, vocab, n_accepted_dev, next_token_dev, (int32_t *)ws,
+                 (unsigned long long *)scr_data(ws), (hipStream_t)stream);
     return check_launch();
 }
 
 extern "C" int ss_speculative_accept_logits(const float *p_logits_dev, const float *q_logits_dev, float temperature,
                                             const int32_t *draft_tokens_dev, const float *uniforms_dev, int32_t batch,
                                             int32_t K, int32_t vocab, int32_t *n_accepted_dev, int32_t *next_token_dev,
-                                            float *p_out_dev, float *q_out_dev, ss_stream stream) {
+                                            float *p_out_dev, float *q_out_dev, void *ws, size_t ws_bytes, ss_stream stream) {
     int rc = check_accept(p_logits_dev, q_logits_dev, draft_tokens_dev, uniforms_dev, batch, K, vocab, n_accepted_dev, next_token_dev, "ss_speculative_accept_logits");
     if (rc) return rc;
     if (!(temperature > 0.f)) return fail(SS_EINVAL, "ss_speculative_accept_logits: temperature must be > 0");
-    const size_t np = (size_t)batch * (K + 1), nq = (size_t)batch * K;
-    const size_t part_bytes = row_stats_partial_bytes((int)std::min(np + nq, stats_rows_per_launch(vocab)), vocab);
-    void *ws;
-    rc = scratch(sizeof(float2) * (np + nq) + accept_workspace_bytes(batch, vocab) + part_bytes + 16, &ws);
+    rc = check_ws(ws, ws_bytes, accept_logits_need(batch, K, vocab), "ss_speculative_accept_logits");
     if (rc) return rc;
+    const size_t np = (size_t)batch * (K + 1), nq = (size_t)batch * K;
     hipStream_t st = (hipStream_t)stream;
     float2 *ps = (float2 *)scr_data(ws), *qs = ps + np;
     unsigned long long *partial = (unsigned long long *)(qs + nq);
@@ -972,11 +1020,10 @@ extern "C" int ss_speculative_accept_logits(const float *p_logits_dev, const flo
 }
 
 extern "C" int ss_greedy_accept(const float *p_logits_dev, const int32_t *draft_tokens_dev, int32_t batch, int32_t K,
-                                int32_t vocab, int32_t *n_accepted_dev, int32_t *next_token_dev, ss_stream stream) {
+                                int32_t vocab, int32_t *n_accepted_dev, int32_t *next_token_dev, void *ws, size_t ws_bytes, ss_stream stream) {
     if (batch < 0 || K < 0 || K > SS_MAX_ROWS_PER_SEQ - 1 || vocab <= 0) return fail(SS_EINVAL, "ss_greedy_accept: bad batch/K/vocab");
     if (!p_logits_dev || !n_accepted_dev || !next_token_dev || (K > 0 && !draft_tokens_dev)) return fail(SS_EINVAL, "ss_greedy_accept: NULL argument");
-    void *ws;
-    int rc = scratch(sizeof(int32_t) * (size_t)batch * (K + 1), &ws);
+    int rc = check_ws(ws, ws_bytes, greedy_need(batch, K), "ss_greedy_accept");
     if (rc) return rc;
     launch_greedy_accept(p_logits_dev, draft_tokens_dev, batch, K, vocab, (int32_t *)scr_data(ws), n_accepted_dev, next_token_dev, (hipStream_t)stream);
     return check_launch();
@@ -1012,6 +1059,7 @@ extern "C" int ss_speculative_step(ss_model *target, ss_kv_cache *tkv, ss_model 
     if (dkv->len_ub[0] + draft_rows > dkv->max_seq || dkv->len_ub[0] + draft_rows > draft->cfg.max_pos)
         return fail(SS_ECAPACITY, "ss_speculative_step: the draft cache at length <= %d has no room for %d rows (max_seq %d, max_pos %d)",
                     dkv->len_ub[0], draft_rows, dkv->max_seq, draft->cfg.max_pos);
+    const int t_len0 = tkv->len_ub[0], d_len0 = dkv->len_ub[0];
     for (int i = 0; i < K; ++i) {
         rc = ss_draft_step(draft, dkv, i ? vt + i : feed_dev, 1, i ? 1 : *n_feed, temperature, top_p, sample ? u_draft_dev + i : nullptr,
                            sample ? q_rows_dev + (size_t)i * V : nullptr, V, vt + i + 1, stream);
@@ -1024,20 +1072,35 @@ extern "C" int ss_speculative_step(ss_model *target, ss_kv_cache *tkv, ss_model 
     }
     rc = ss_verify_forward(target, tkv, vt, 1, M, logits_dev, stream);
     if (rc) return rc;
+    // the softmax and the rejection step work in the target model's own workspace
     if (sample) {
-        rc = ss_softmax(logits_dev, M, V, temperature, p_dev, stream);
+        rc = ss_softmax(logits_dev, M, V, temperature, p_dev, target->ws, target->ws_bytes, stream);
         if (rc) return rc;
         if (P24) launch_top_p_filter(p_dev, V, M, V, P24, p_dev, V, st); // the draft's rows were filtered by its own calls
-        rc = ss_speculative_accept(p_dev, q_rows_dev, vt + 1, u_accept_dev, 1, K, V, result_dev, result_dev + 1, stream);
+        rc = ss_speculative_accept(p_dev, q_rows_dev, vt + 1, u_accept_dev, 1, K, V, result_dev, result_dev + 1, target->ws, target->ws_bytes, stream);
     } else {
-        rc = ss_greedy_accept(logits_dev, vt + 1, 1, K, V, result_dev, result_dev + 1, stream);
+        rc = ss_greedy_accept(logits_dev, vt + 1, 1, K, V, result_dev, result_dev + 1, target->ws, target->ws_bytes, stream);
     }
     if (rc) return rc;
     launch_len_rollback(tkv->len_dev, result_dev, 1, M, st);
     if (!shared) launch_len_rollback(dkv->len_dev, result_dev, 1, K, st); // a == K leaves the draft cache one row short of the target's
     HIP_TRY(hipMemcpyAsync(out_host, result_dev, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipMemcpyAsync(out_host + 2, vt + 1, K * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    // the abort flags of the persistent kernel travel with the result: a wait that gave up must not go unnoticed
+    unsigned ab[2] = {0u, 0u};
+    if (target->abort_flag) HIP_TRY(hipMemcpyAsync(&ab[0], target->abort_flag, sizeof(unsigned), hipMemcpyDeviceToHost, st));
+    if (draft->abort_flag && draft != target) HIP_TRY(hipMemcpyAsync(&ab[1], draft->abort_flag, sizeof(unsigned), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
+    if (ab[0] | ab[1]) {
+        int32_t dummy = 0;
+        if (ab[0]) (void)ss_device_status(target, stream, &dummy); // resets the synchronisation state
+        if (ab[1]) (void)ss_device_status(draft, stream, &dummy);
+        const int32_t tl = t_len0, dl = d_len0;
+        (void)ss_kv_cache_set_len(tkv, &tl, stream);
+        if (!shared) (void)ss_kv_cache_set_len(dkv, &dl, stream);
+        return fail(SS_EABORTED, "ss_speculative_step: a bounded wait of the persistent kernel gave up (%s model); cache lengths restored",
+                    ab[0] ? "target" : "draft");
+    }
     const int a = std::min(std::max(out_host[0], 0), K);
     tkv->len_ub[0] -= M - 1 - a;
     if (!shared) dkv->len_ub[0] -= K - 1 - std::min(a, K - 1);
@@ -1051,4 +1114,21 @@ extern "C" int ss_speculative_step(ss_model *target, ss_kv_cache *tkv, ss_model 
         *n_feed = 2;
     }
     return check_launch();
+}
+
+// ------------------------------------------------------------------------------------------ shutdown
+
+extern "C" int ss_shutdown(void) {
+    std::set<ss_model *> models;
+    std::set<ss_kv_cache *> caches;
+    {
+        std::lock_guard<std::mutex> lk(g_reg_mu);
+        models.swap(g_models);
+        caches.swap(g_caches);
+    }
+    if (models.empty() && caches.empty()) return SS_OK;
+    (void)hipDeviceSynchronize();
+    for (ss_kv_cache *kv : caches) cache_release(kv);
+    for (ss_model *m : models) model_release(m);
+    return SS_OK;
 }

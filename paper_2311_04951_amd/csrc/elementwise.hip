@@ -3,6 +3,7 @@
 // length write) and the raw cache append used to build an existing context.
 #include "ss_device.h"
 #include "ss_kernels.h"
+#include <algorithm>
 
 namespace ss {
 
@@ -119,6 +120,31 @@ __global__ void len_rollback_kernel(int32_t *len, const int32_t *n_accepted, int
 }
 void launch_len_rollback(int32_t *len, const int32_t *n_accepted, int batch, int M, hipStream_t st) {
     hipLaunchKernelGGL(len_rollback_kernel, dim3((batch + 63) / 64), dim3(64), 0, st, len, n_accepted, batch, M);
+}
+
+// truncation from a device array (Section 4.4: dropping the stale tail of a cache is a length write)
+__global__ void len_truncate_kernel(int32_t *len, const int32_t *new_len, int batch, int32_t *status) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < batch) {
+        const int want = new_len[b] < 0 ? 0 : new_len[b];
+        if (want > len[b]) {
+            if (status) atomicOr(status, 4);
+        } else {
+            len[b] = want;
+        }
+    }
+}
+void launch_len_truncate(int32_t *len, const int32_t *new_len, int batch, int32_t *status, hipStream_t st) {
+    hipLaunchKernelGGL(len_truncate_kernel, dim3((batch + 63) / 64), dim3(64), 0, st, len, new_len, batch, status);
+}
+
+__global__ void fill_u32_kernel(uint32_t *p, size_t n, uint32_t value) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = value;
+}
+void launch_fill_u32(uint32_t *p, size_t n, uint32_t value, hipStream_t st) {
+    if (!n) return;
+    const unsigned blocks = (unsigned)std::min<size_t>((n + 255) / 256, 1024);
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks), dim3(256), 0, st, p, n, value);
 }
 
 // raw append: rows [n_rows][H*hd] of rotated keys / values into sequence `seq` at pos0..

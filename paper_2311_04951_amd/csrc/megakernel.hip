@@ -1093,7 +1093,12 @@ hipError_t launch_mega(const MegaCall &call, int grid, hipStream_t st) {
     const void *fn = call.dtype ? (const void *)verify_persistent_kernel<bf16_t> : (const void *)verify_persistent_kernel<float>;
     hipError_t e = ensure_smem_attr(call.dtype);
     if (e != hipSuccess) return e;
-    return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(MEGA_THREADS), args, u_bytes + sizeof(MegaSmemTail), st);
+    // An ordinary launch: the grid never exceeds the compute units (mega_grid) and a workgroup asks for more than half
+    // of a compute unit's LDS, so at most one fits per unit and every workgroup becomes resident as soon as units are
+    // free; should another kernel hold units for long, the bounded waits end the launch with the abort flag set
+    // instead of hanging.  (A cooperative launch gives the same placement through a separate device queue.)
+    const size_t smem = std::max(u_bytes + sizeof(MegaSmemTail), LDS_BYTES / 2 + 1024);
+    return hipLaunchKernel(fn, dim3(grid), dim3(MEGA_THREADS), args, smem, st);
 }
 
 } // namespace ss

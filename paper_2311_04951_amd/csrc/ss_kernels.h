@@ -78,6 +78,10 @@ void launch_quantize_rows_int4(int dtype, const void *W, long long rows, long lo
 void launch_read_probe(const void *buf, size_t bytes, uint32_t *sink, hipStream_t st);
 void launch_len_add(int32_t *len, int batch, int delta, hipStream_t st);
 void launch_len_rollback(int32_t *len, const int32_t *n_accepted, int batch, int M, hipStream_t st);
+// len[b] = min(len[b], max(new_len[b], 0)); a value above the current length sets bit 2 of *status (may be NULL)
+void launch_len_truncate(int32_t *len, const int32_t *new_len, int batch, int32_t *status, hipStream_t st);
+// fills n 32-bit words with `value` (a kernel, so that it may be recorded into a graph)
+void launch_fill_u32(uint32_t *p, size_t n, uint32_t value, hipStream_t st);
 void launch_kv_append(int dtype, void *kc, void *vc, const void *k, const void *v, int seq, int pos0, int n_rows,
                       int H, int hd, int S, hipStream_t st);
 

@@ -14,8 +14,17 @@ import time
 
 import torch
 
-from . import (KVCache, Model, StepBuffers, ss_draft_step, ss_greedy_accept, ss_kv_cache_rollback, ss_kv_cache_set_len, ss_softmax, ss_top_p_filter,
+from . import (KVCache, Model, SpecVerifyError, StepBuffers, ss_device_status, ss_draft_step, ss_greedy_accept, ss_kv_cache_rollback, ss_kv_cache_set_len, ss_softmax, ss_top_p_filter,
                ss_speculative_accept, ss_speculative_step, ss_verify_forward)
+
+
+def _check_status(*models):
+    """A decode loop's results are only valid if no kernel flagged anything (a clamped token id, a wait of the
+    persistent kernel that gave up): read the status words once, after the loop."""
+    for m in models:
+        st = ss_device_status(m)
+        if st:
+            raise SpecVerifyError(-4 if st & 2 else -1, f"device status {st} after a decode loop (bit 0: token id clamped, bit 1: wait gave up)")
 
 
 def prefill(model: Model, kv: KVCache, tokens, chunk: int = 16):
@@ -49,6 +58,7 @@ def autoregressive_generate(target: Model, prompt, n_new: int, temperature: floa
     torch.cuda.synchronize()
     if stats is not None:
         stats["loop_seconds"] = time.perf_counter() - t0
+    _check_status(target)
     out = buf[1:].tolist()
     kv.close()
     return out
@@ -124,6 +134,7 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
         step += 1
     torch.cuda.synchronize()
     loop_s = time.perf_counter() - t0
+    _check_status(target, draft)
     tkv.close()
     if not shared_kv:
         dkv.close()
@@ -158,6 +169,7 @@ def _speculative_generate_native(target, draft, prompt, n_new, K, temperature, u
         step += 1
     torch.cuda.synchronize()
     loop_s = time.perf_counter() - t0
+    _check_status(target, draft)
     tkv.close()
     if not shared_kv:
         dkv.close()

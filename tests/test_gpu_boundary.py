@@ -1,0 +1,184 @@
+"""The boundary's conventions on the GPU: caller-owned cache buffers and workspaces, device-side truncation, no
+allocation on the hot path, status words, failures that reach the caller, shutdown."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2311_04951_amd as sv
+import seeded_inputs as si
+from paper_2311_04951_amd import generate as gen
+from gpu_util import dev, maxabs, weights_to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def _tiny(seed=31, persistent=True):
+    tw = si.decoder_weights(si.TINY_TARGET, seed)
+    dshape, dw = si.early_exit_draft(si.TINY_TARGET, tw, 1)
+    gt = sv.Model(si.TINY_TARGET, weights_to_device(tw), max_rows=16, max_pos=256)
+    gd = sv.Model(dshape, weights_to_device(dw), max_rows=16, max_pos=256)
+    for m in (gt, gd):
+        sv.ss_model_set_persistent(m, persistent)
+    return tw, gt, gd
+
+
+def test_cache_in_a_caller_owned_buffer_matches_the_library_allocated_one_and_the_oracle():
+    """The same pass on a cache whose keys and values live in the caller's buffer (a slice of a larger tensor
+    filled with NaN bit patterns beforehand: creation clears what it needs) and on one the library allocated."""
+    shape = si.TINY_TARGET
+    w = si.decoder_weights(shape, seed=32)
+    gm = sv.Model(shape, weights_to_device(w), max_rows=32, max_pos=256)
+    need = sv.ss_kv_cache_bytes(gm, 2, 100)
+    assert need == 2 * shape.n_layers * 2 * shape.n_heads * shape.head_dim * 128 * 4      # K and V, S = 128 positions, fp32
+    arena = torch.full((need + 4096,), 0xFF, dtype=torch.uint8, device=dev())
+    own = sv.ss_kv_cache_create(gm, 2, 100, arena[1024:1024 + need])
+    lib_kv = sv.KVCache(gm, 2, 100, buf="library")
+    with pytest.raises(sv.SpecVerifyError) as e:
+        sv.ss_kv_cache_create(gm, 2, 100, arena[:need - 16])
+    assert e.value.code == sv.SS_ECAPACITY
+    with pytest.raises(sv.SpecVerifyError) as e:
+        sv.ss_kv_cache_create(gm, 2, 100, arena[4:4 + need])
+    assert e.value.code == sv.SS_EINVAL
+    toks = si.token_ids(32, "toks", (2, 21), shape.vocab)
+    om = oracle.Model(shape, w)
+    outs = []
+    for kv in (own, lib_kv):
+        sv.ss_verify_forward(gm, kv, toks[:, :16].contiguous().to(dev()), 16, logits=False)
+        outs.append(sv.ss_verify_forward(gm, kv, toks[:, 16:].contiguous().to(dev()), 5).clone())
+    assert torch.equal(outs[0], outs[1])
+    for b in range(2):
+        okv = om.new_kv(100)
+        om.forward(okv, toks[b, :16].numpy(), want_logits=False)
+        assert maxabs(outs[0][b], om.forward(okv, toks[b, 16:].numpy())) < 1e-4
+    assert bool((arena[:1024] == 0xFF).all()) and bool((arena[1024 + need:] == 0xFF).all())   # nothing outside the buffer was touched
+    own.close()
+    lib_kv.close()
+    lib_kv.close()      # a second release of a handle is a no-op
+
+
+def test_device_side_truncation_only_lowers_lengths():
+    shape = si.TINY_DRAFT
+    gm = sv.Model(shape, weights_to_device(si.decoder_weights(shape, seed=33)), max_rows=16, max_pos=128)
+    kv = sv.KVCache(gm, 3, 64)
+    sv.ss_kv_cache_set_len(kv, [10, 20, 30])
+    status = torch.zeros(1, dtype=torch.int32, device=dev())
+    sv.ss_kv_cache_truncate(kv, torch.tensor([4, 20, 31], dtype=torch.int32, device=dev()), status=status)
+    assert sv.ss_kv_cache_get_len(kv).tolist() == [4, 20, 30]          # 31 > 30: left alone and flagged
+    assert int(status.item()) == 4
+    sv.ss_kv_cache_truncate(kv, torch.tensor([-5, 7, 30], dtype=torch.int32, device=dev()), new_len_host=[0, 7, 30])
+    assert sv.ss_kv_cache_get_len(kv).tolist() == [0, 7, 30]
+
+
+def test_hot_path_runs_with_allocations_frozen():
+    """One verify step the way the bench times it (forward, softmax, rejection step, roll-back), a draft step, the
+    fused logits entry, the greedy entry and whole speculative steps, with every allocating path of the library
+    switched off and the workspace passed in by the caller; free device memory does not move either."""
+    tw, gt, gd = _tiny()
+    V, K, M = si.TINY_TARGET.vocab, 4, 5
+    tkv, dkv = sv.KVCache(gt, 1, 128), sv.KVCache(gd, 1, 128)
+    prompt = si.token_ids(31, "prompt", (1, 16), V).to(dev())
+    sv.ss_verify_forward(gt, tkv, prompt, 16, logits=False)
+    sv.ss_verify_forward(gd, dkv, prompt, 16, logits=False)
+    ws = torch.empty(sv.ss_workspace_bytes(2 * K + 1, V), dtype=torch.uint8, device=dev())
+    sv.ss_workspace_init(ws)
+    vt = si.token_ids(31, "rows", (1, M), V).to(dev())
+    u = si.uniforms(31, "u", (1, M)).to(dev())
+    logits = torch.empty((1, M, V), device=dev())
+    p, q = torch.empty_like(logits), torch.empty((1, K, V), device=dev())
+    na, nx = torch.empty(1, dtype=torch.int32, device=dev()), torch.empty(1, dtype=torch.int32, device=dev())
+    tok = torch.empty(1, dtype=torch.int32, device=dev())
+    buf = sv.StepBuffers(K, V, int(prompt[0, -1]), dev())
+    ud, ua = si.uniforms(31, "ud", (K,)).to(dev()), si.uniforms(31, "ua", (K + 1,)).to(dev())
+    torch.cuda.synchronize()
+    free0 = torch.cuda.mem_get_info()[0]
+    sv.ss_freeze_allocations(True)
+    try:
+        with pytest.raises(sv.SpecVerifyError):                      # the switch is live
+            sv.Model(si.TINY_DRAFT, weights_to_device(si.decoder_weights(si.TINY_DRAFT, 1)), max_rows=4, max_pos=32)
+        with pytest.raises(sv.SpecVerifyError):
+            sv.KVCache(gt, 1, 32, buf="library")
+        for it in range(3):
+            sv.ss_verify_forward(gt, tkv, vt, M, logits)
+            sv.ss_softmax(logits, 1.0, p, ws=ws)
+            sv.ss_softmax(logits[:, :K].contiguous() * 0.9, 1.0, q, ws=ws)
+            sv.ss_speculative_accept(p, q, vt[:, 1:].contiguous(), u, na, nx, ws=ws)
+            a1, x1 = na.clone(), nx.clone()
+            sv.ss_speculative_accept_logits(logits, logits[:, :K].contiguous() * 0.9, 1.0, vt[:, 1:].contiguous(), u, na, nx, ws=ws)
+            assert torch.equal(a1, na) and torch.equal(x1, nx)
+            sv.ss_greedy_accept(logits, vt[:, 1:].contiguous(), na, nx, ws=ws)
+            sv.ss_kv_cache_rollback(tkv, na, M)
+            sv.ss_draft_step(gd, dkv, vt[:, :1].contiguous(), 1, 1.0, u[0, :1], q[0, 0], V, tok)
+        sv.ss_kv_cache_set_len(tkv, [16])
+        sv.ss_kv_cache_set_len(dkv, [16])
+        for it in range(3):
+            a, y, d = sv.ss_speculative_step(gt, tkv, gd, dkv, buf, 1.0, ud, ua)
+            assert 0 <= a <= K and 0 <= y < V
+        torch.cuda.synchronize()
+    finally:
+        sv.ss_freeze_allocations(False)
+    assert torch.cuda.mem_get_info()[0] == free0
+    assert sv.ss_workspace_status(ws) == 0 and sv.ss_device_status(gt) == 0
+
+
+def test_an_out_of_range_draft_token_is_flagged_in_the_workspace_status_word():
+    B, K, V = 2, 3, 500
+    pl, ql, u, ud = si.accept_workload(7, B, K, V, device=dev())
+    p, q = sv.ss_softmax(pl, 1.0), sv.ss_softmax(ql, 1.0)
+    ws = sv.ss_workspace_init(torch.empty(sv.ss_workspace_bytes(B * (2 * K + 1), V), dtype=torch.uint8, device=dev()))
+    d = torch.tensor([[1, 2, 3], [4, V + 9, 5]], dtype=torch.int32, device=dev())
+    na, nx = sv.ss_speculative_accept(p, q, d, u, ws=ws)
+    assert int(na[1]) <= 1                                            # the bad token counts as rejected
+    assert sv.ss_workspace_status(ws) == 1 and sv.ss_workspace_status(ws) == 0      # read and cleared
+    d[1, 1] = 7
+    sv.ss_speculative_accept(p, q, d, u, ws=ws)
+    assert sv.ss_workspace_status(ws) == 0
+
+
+def test_a_speculative_step_whose_kernel_gives_up_returns_an_error_and_restores_the_caches():
+    """The bounded wait of the persistent kernel, forced to give up by a limit of one poll (the kernel still ends
+    normally): the step reports SS_EABORTED instead of handing out garbage, both caches are back at their length,
+    the feed is untouched, and the same step then succeeds and equals the step of an untouched pair."""
+    tw, gt, gd = _tiny(seed=34)
+    for m in (gt, gd):
+        sv.ss_model_set_persistent_options(m, 8, True)
+    V, K = si.TINY_TARGET.vocab, 4
+    prompt = si.token_ids(34, "prompt", (1, 16), V).to(dev())
+    ud, ua = si.uniforms(34, "ud", (K,)).to(dev()), si.uniforms(34, "ua", (K + 1,)).to(dev())
+
+    def fresh():
+        tkv, dkv = sv.KVCache(gt, 1, 128), sv.KVCache(gd, 1, 128)
+        sv.ss_verify_forward(gt, tkv, prompt[:, :15].contiguous(), 15, logits=False)
+        sv.ss_verify_forward(gd, dkv, prompt[:, :15].contiguous(), 15, logits=False)
+        return tkv, dkv, sv.StepBuffers(K, V, int(prompt[0, 15]), dev())
+
+    tkv, dkv, buf = fresh()
+    want = sv.ss_speculative_step(gt, tkv, gd, dkv, buf, 1.0, ud, ua)
+    tkv, dkv, buf = fresh()
+    sv.ss_model_set_wait_limit(gt, 1)
+    with pytest.raises(sv.SpecVerifyError) as e:
+        sv.ss_speculative_step(gt, tkv, gd, dkv, buf, 1.0, ud, ua)
+    assert e.value.code == sv.SS_EABORTED
+    assert sv.ss_kv_cache_get_len(tkv).tolist() == [15] and sv.ss_kv_cache_get_len(dkv).tolist() == [15]
+    assert buf.n_feed.value == 1 and int(buf.feed[0]) == int(prompt[0, 15])
+    sv.ss_model_set_wait_limit(gt, 1 << 20)
+    assert sv.ss_speculative_step(gt, tkv, gd, dkv, buf, 1.0, ud, ua) == want
+    assert sv.ss_device_status(gt) == 0 and sv.ss_device_status(gd) == 0
+
+
+def test_shutdown_releases_live_handles_and_later_releases_are_no_ops():
+    shape = si.TINY_DRAFT
+    w = weights_to_device(si.decoder_weights(shape, seed=35))
+    gm = sv.Model(shape, w, max_rows=4, max_pos=64)
+    kv = sv.KVCache(gm, 1, 32, buf="library")
+    sv.ss_verify_forward(gm, kv, torch.zeros((1, 4), dtype=torch.int32, device=dev()), 4, logits=False)
+    sv.ss_shutdown()
+    kv.close()
+    gm.close()
+    # the library works again afterwards
+    gm = sv.Model(shape, w, max_rows=4, max_pos=64)
+    kv = sv.KVCache(gm, 1, 32)
+    out = sv.ss_verify_forward(gm, kv, torch.zeros((1, 4), dtype=torch.int32, device=dev()), 4)
+    assert bool(torch.isfinite(out).all())

@@ -62,3 +62,31 @@ def test_bench_algorithmic_bytes_are_the_documented_sums():
     assert bench.verify_pass_bytes(s, L, M) == want
     assert abs(want - 13.296e9) < 0.01e9                              # the figure the committed profile summaries quote
     assert bench.HBM_PEAK == 8e12
+
+
+def test_calls_without_a_handle_refuse_a_workspace_that_is_too_small_on_the_host():
+    """Argument validation happens before anything is launched, so it can be exercised without a GPU: made-up
+    (aligned, never dereferenced) device addresses, a workspace one byte short of what the call needs."""
+    L = sv.lib()
+    vp = ctypes.c_void_p
+    fake = [vp(0x10000 * (i + 1)) for i in range(8)]
+    rows, V, B, K = 9, 32000, 1, 4
+    assert sv.ss_workspace_bytes(rows, V) > 0 and sv.ss_workspace_bytes(0, V) > 0 and sv.ss_workspace_bytes(4, 0) == 0
+    assert sv.ss_workspace_bytes(64 * 17, 128256) >= sv.ss_workspace_bytes(17, 128256)
+    small = 1024
+    assert L.ss_softmax(fake[0], rows, V, 1.0, fake[1], fake[2], small, None) == sv.SS_ECAPACITY
+    assert b"workspace" in L.ss_last_error()
+    assert L.ss_speculative_accept(fake[0], fake[1], fake[2], fake[3], B, K, V, fake[4], fake[5], fake[6], small, None) == sv.SS_ECAPACITY
+    assert L.ss_speculative_accept_logits(fake[0], fake[1], 0.8, fake[2], fake[3], B, K, V, fake[4], fake[5], None, None,
+                                          fake[6], small, None) == sv.SS_ECAPACITY
+    assert L.ss_greedy_accept(fake[0], fake[1], B, K, V, fake[2], fake[3], fake[4], small, None) == sv.SS_ECAPACITY
+    assert L.ss_workspace_init(fake[0], small, None) == sv.SS_ECAPACITY
+    # a NULL or misaligned workspace is a bad argument, not a capacity problem
+    big = sv.ss_workspace_bytes(rows, V)
+    assert L.ss_softmax(fake[0], rows, V, 1.0, fake[1], None, big, None) == sv.SS_EINVAL
+    assert L.ss_softmax(fake[0], rows, V, 1.0, fake[1], vp(0x10004), big, None) == sv.SS_EINVAL
+    # the device-array truncation and the cache creation validate on the host as well
+    assert L.ss_kv_cache_truncate(None, fake[0], None, None, None) == sv.SS_EINVAL
+    out = vp()
+    assert L.ss_kv_cache_create(None, 1, 64, fake[0], 1 << 20, None, ctypes.byref(out)) == sv.SS_EINVAL
+    assert L.ss_shutdown() == 0 and L.ss_shutdown() == 0      # nothing alive: a no-op, twice
