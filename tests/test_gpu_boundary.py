@@ -92,34 +92,41 @@ def test_hot_path_runs_with_allocations_frozen():
     tok = torch.empty(1, dtype=torch.int32, device=dev())
     buf = sv.StepBuffers(K, V, int(prompt[0, -1]), dev())
     ud, ua = si.uniforms(31, "ud", (K,)).to(dev()), si.uniforms(31, "ua", (K + 1,)).to(dev())
-    torch.cuda.synchronize()
-    free0 = torch.cuda.mem_get_info()[0]
+    ql, d = torch.empty((1, K, V), device=dev()), vt[:, 1:].contiguous()
+    a1, x1 = torch.empty_like(na), torch.empty_like(nx)
+    same = torch.zeros(3, dtype=torch.bool, device=dev())
+    small = weights_to_device(si.decoder_weights(si.TINY_DRAFT, 1))
     sv.ss_freeze_allocations(True)
     try:
         with pytest.raises(sv.SpecVerifyError):                      # the switch is live
-            sv.Model(si.TINY_DRAFT, weights_to_device(si.decoder_weights(si.TINY_DRAFT, 1)), max_rows=4, max_pos=32)
+            sv.Model(si.TINY_DRAFT, small, max_rows=4, max_pos=32)
         with pytest.raises(sv.SpecVerifyError):
             sv.KVCache(gt, 1, 32, buf="library")
-        for it in range(3):
+        torch.cuda.synchronize()
+        free0 = torch.cuda.mem_get_info()[0]
+        for it in range(3):      # only library calls and in-place tensor operations from here to the second reading
             sv.ss_verify_forward(gt, tkv, vt, M, logits)
             sv.ss_softmax(logits, 1.0, p, ws=ws)
-            sv.ss_softmax(logits[:, :K].contiguous() * 0.9, 1.0, q, ws=ws)
-            sv.ss_speculative_accept(p, q, vt[:, 1:].contiguous(), u, na, nx, ws=ws)
-            a1, x1 = na.clone(), nx.clone()
-            sv.ss_speculative_accept_logits(logits, logits[:, :K].contiguous() * 0.9, 1.0, vt[:, 1:].contiguous(), u, na, nx, ws=ws)
-            assert torch.equal(a1, na) and torch.equal(x1, nx)
-            sv.ss_greedy_accept(logits, vt[:, 1:].contiguous(), na, nx, ws=ws)
+            ql.copy_(logits[:, :K]).mul_(0.9)
+            sv.ss_softmax(ql, 1.0, q, ws=ws)
+            sv.ss_speculative_accept(p, q, d, u, a1, x1, ws=ws)
+            sv.ss_speculative_accept_logits(logits, ql, 1.0, d, u, na, nx, ws=ws)
+            same[it] = torch.equal(a1, na) and torch.equal(x1, nx)
+            sv.ss_greedy_accept(logits, d, na, nx, ws=ws)
             sv.ss_kv_cache_rollback(tkv, na, M)
-            sv.ss_draft_step(gd, dkv, vt[:, :1].contiguous(), 1, 1.0, u[0, :1], q[0, 0], V, tok)
+            sv.ss_draft_step(gd, dkv, vt[:, :1], 1, 1.0, u[0, :1], q[0, 0], V, tok)
+        torch.cuda.synchronize()
+        assert torch.cuda.mem_get_info()[0] == free0
+        assert bool(same.all())
         sv.ss_kv_cache_set_len(tkv, [16])
         sv.ss_kv_cache_set_len(dkv, [16])
         for it in range(3):
-            a, y, d = sv.ss_speculative_step(gt, tkv, gd, dkv, buf, 1.0, ud, ua)
+            a, y, dd = sv.ss_speculative_step(gt, tkv, gd, dkv, buf, 1.0, ud, ua)
             assert 0 <= a <= K and 0 <= y < V
         torch.cuda.synchronize()
+        assert torch.cuda.mem_get_info()[0] == free0
     finally:
         sv.ss_freeze_allocations(False)
-    assert torch.cuda.mem_get_info()[0] == free0
     assert sv.ss_workspace_status(ws) == 0 and sv.ss_device_status(gt) == 0
 
 
