@@ -108,7 +108,9 @@ int ss_shutdown(void);
 
 /* For callers that must prove their decode loop allocates nothing: while `on` is non-zero every path of the
  * library that would allocate device memory (ss_model_create, ss_kv_cache_alloc / ss_kv_cache_create) fails with
- * SS_EHIP instead.  The hot-path calls are unaffected: they never allocate. */
+ * SS_EHIP instead.  The hot-path calls are unaffected: they never allocate.  Switching it on also completes, on the
+ * current device, the one-off set-up that ss_speculative_accept_noalloc would otherwise do in its first call there
+ * (its built-in scratch array receives its device address), so that call does no set-up work afterwards. */
 int ss_freeze_allocations(int32_t on);
 
 /* Reads and clears the device status word of `model` (synchronises `stream`).
@@ -341,6 +343,20 @@ int ss_speculative_accept(const float *p_dev, const float *q_dev, const int32_t 
                           const float *uniforms_dev, int32_t batch, int32_t K, int32_t vocab,
                           int32_t *n_accepted_dev, int32_t *next_token_dev, void *ws_dev, size_t ws_bytes,
                           ss_stream stream);
+
+/* ss_speculative_accept for callers that cannot provide or allocate a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation): the same kernels, with their scratch (per-segment weight sums,
+ * status word) in a 64 KiB device array built into the library.  Allocates nothing, frees nothing, never waits for
+ * the device.  Limit: 256 + 8 * batch * segments bytes must fit the array, where segments <= 16 is the number of
+ * vocabulary segments per sequence the kernels use (batch * segments < 1024 + batch, and segments = 1 from batch
+ * 1024 on): any batch up to 8160 at any vocabulary; beyond the limit SS_ECAPACITY, before anything is launched.  Every call on a device shares that
+ * device's array: calls that overlap in time on one device (different streams) race; consecutive calls need no
+ * clearing in between.  status_dev (dev int32, may be NULL): receives bit 0 when a draft token id outside
+ * [0, vocab) was treated as rejected (NULL: the flag goes to a word of the array that no call reads).
+ * Results are bit-identical to ss_speculative_accept. */
+int ss_speculative_accept_noalloc(const float *p_dev, const float *q_dev, const int32_t *draft_tokens_dev,
+                                  const float *uniforms_dev, int32_t batch, int32_t K, int32_t vocab,
+                                  int32_t *n_accepted_dev, int32_t *next_token_dev, int32_t *status_dev, ss_stream stream);
 
 /* Same step straight from logits: p = softmax(p_logits/T), q = softmax(q_logits/T) are never
  * materialised (one read of the logits for the row statistics, then a re-read of the one or two

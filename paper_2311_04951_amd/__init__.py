@@ -30,6 +30,7 @@ EXPORTS = [
     "ss_speculative_step", "ss_probe_read_bandwidth", "ss_quantize_rows_int8", "ss_top_p_filter",
     "ss_model_set_wait_limit", "ss_quantize_rows_int4", "ss_shutdown", "ss_kv_cache_create", "ss_kv_cache_truncate",
     "ss_workspace_bytes", "ss_workspace_init", "ss_workspace_status", "ss_model_set_timeline", "ss_freeze_allocations",
+    "ss_speculative_accept_noalloc",
 ]
 
 PROFILE_CLASSES = ["rmsnorm", "qkv_gemm", "attention", "oproj_gemm", "gateup_gemm", "down_gemm", "head_gemm", "other",
@@ -98,6 +99,7 @@ def lib():
             "ss_top_p_filter": [vp, i32, i32, f32, vp, vp],
             "ss_softmax": [vp, i32, i32, f32, vp, vp, sz, vp],
             "ss_speculative_accept": [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp],
+            "ss_speculative_accept_noalloc": [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp],
             "ss_speculative_accept_logits": [vp, vp, f32, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp],
             "ss_greedy_accept": [vp, vp, i32, i32, i32, vp, vp, vp, sz, vp],
             "ss_profile_enable": [vp, i32],
@@ -410,6 +412,17 @@ def ss_speculative_accept(p, q, draft_tokens, uniforms, n_accepted=None, next_to
                                        _dev(draft_tokens, torch.int32) if K1 > 1 else C.c_void_p(0),
                                        _dev(uniforms, torch.float32), B, K1 - 1, V, _dev(n_accepted), _dev(next_token),
                                        *_ws_args(ws, p.device, B * (2 * K1 - 1), V), _stream(stream)))
+    return n_accepted, next_token
+
+
+def ss_speculative_accept_noalloc(p, q, draft_tokens, uniforms, n_accepted, next_token, status=None, stream=None):
+    """The rejection step with the library's built-in scratch array: every tensor, outputs included, is the caller's."""
+    B, K1, V = p.shape
+    _check(lib().ss_speculative_accept_noalloc(_dev(p, torch.float32), _dev(q, torch.float32) if K1 > 1 else C.c_void_p(0),
+                                               _dev(draft_tokens, torch.int32) if K1 > 1 else C.c_void_p(0),
+                                               _dev(uniforms, torch.float32), B, K1 - 1, V, _dev(n_accepted, torch.int32),
+                                               _dev(next_token, torch.int32), _dev(status, torch.int32 if status is not None else None),
+                                               _stream(stream)))
     return n_accepted, next_token
 
 

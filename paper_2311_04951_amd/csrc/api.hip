@@ -159,11 +159,6 @@ static hipError_t lib_malloc(void **p, size_t bytes) {
     return hipMalloc(p, bytes);
 }
 
-extern "C" int ss_freeze_allocations(int32_t on) {
-    g_alloc_frozen.store(on != 0);
-    return SS_OK;
-}
-
 static int dev_alloc(ss_model *m, void **p, size_t bytes, bool zero) {
     if (g_alloc_frozen.load()) return fail(SS_EHIP, "device allocations are frozen (ss_freeze_allocations)");
     HIP_TRY(hipMalloc(p, bytes ? bytes : 16));
@@ -1026,6 +1021,65 @@ extern "C" int ss_greedy_accept(const float *p_logits_dev, const int32_t *draft_
     int rc = check_ws(ws, ws_bytes, greedy_need(batch, K), "ss_greedy_accept");
     if (rc) return rc;
     launch_greedy_accept(p_logits_dev, draft_tokens_dev, batch, K, vocab, (int32_t *)scr_data(ws), n_accepted_dev, next_token_dev, (hipStream_t)stream);
+    return check_launch();
+}
+
+// ------------------------------------------------------------------------------------------ rejection step without a workspace argument
+
+// Scratch of ss_speculative_accept_noalloc: the status word ([0, 256)) and the per-segment weight sums of the
+// rejection step, in a device array that is part of the library's code object (every device the library runs
+// on holds its own copy at its own address until the process ends).  In host code the array's name is only a
+// handle for hipGetSymbolAddress: the address the kernels get is the one that call returns, kept per device.
+constexpr size_t NOALLOC_SCRATCH_BYTES = 64 * 1024;
+static __device__ __align__(256) unsigned char noalloc_scratch[NOALLOC_SCRATCH_BYTES];
+constexpr int NOALLOC_MAX_DEVICES = 64;
+static std::mutex g_noalloc_mu;
+static void *g_noalloc_ptr[NOALLOC_MAX_DEVICES];
+
+// device address of the scratch array on the current device (resolved once per device)
+static int noalloc_scratch_ptr(void **out) {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= NOALLOC_MAX_DEVICES) return fail(SS_EINVAL, "ss_speculative_accept_noalloc: device index %d is not supported", dev);
+    std::lock_guard<std::mutex> lk(g_noalloc_mu);
+    if (!g_noalloc_ptr[dev]) {
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(noalloc_scratch)));
+        if (!p) return fail(SS_EHIP, "ss_speculative_accept_noalloc: the scratch array has no address on device %d", dev);
+        g_noalloc_ptr[dev] = p;
+    }
+    *out = g_noalloc_ptr[dev];
+    return SS_OK;
+}
+
+extern "C" int ss_freeze_allocations(int32_t on) {
+    if (on) {
+        // set-up that a later call would otherwise do on its first use: the built-in scratch array is given its
+        // address on the current device now (loading the code object that holds it is what takes device memory)
+        void *scratch = nullptr;
+        int rc = noalloc_scratch_ptr(&scratch);
+        if (rc) return rc;
+    }
+    g_alloc_frozen.store(on != 0);
+    return SS_OK;
+}
+
+extern "C" int ss_speculative_accept_noalloc(const float *p_dev, const float *q_dev, const int32_t *draft_tokens_dev,
+                                             const float *uniforms_dev, int32_t batch, int32_t K, int32_t vocab,
+                                             int32_t *n_accepted_dev, int32_t *next_token_dev, int32_t *status_dev, ss_stream stream) {
+    int rc = check_accept(p_dev, q_dev, draft_tokens_dev, uniforms_dev, batch, K, vocab, n_accepted_dev, next_token_dev, "ss_speculative_accept_noalloc");
+    if (rc) return rc;
+    const size_t need = 256 + accept_workspace_bytes(batch, vocab);
+    if (need > NOALLOC_SCRATCH_BYTES)
+        return fail(SS_ECAPACITY, "ss_speculative_accept_noalloc: batch %d at vocabulary %d needs %zu bytes of scratch, the built-in array has %zu "
+                    "(use ss_speculative_accept with a workspace)", batch, vocab, need, NOALLOC_SCRATCH_BYTES);
+    void *scratch = nullptr;
+    rc = noalloc_scratch_ptr(&scratch);
+    if (rc) return rc;
+    // nothing here has to start at zero: every per-segment sum the finish kernel reads is written by this call's first
+    // kernel, and the status word only ever accumulates flags
+    accept_probs(p_dev, q_dev, draft_tokens_dev, uniforms_dev, batch, K, vocab, n_accepted_dev, next_token_dev,
+                 status_dev ? status_dev : (int32_t *)scratch, (unsigned long long *)((char *)scratch + 256), (hipStream_t)stream);
     return check_launch();
 }
 
