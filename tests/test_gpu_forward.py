@@ -292,6 +292,7 @@ def test_persistent_kernel_at_7b_width_for_every_row_count_and_a_long_context_ma
         got = sv.ss_verify_forward(gm, gkv, torch.tensor(toks[None], device=dev()), M)[0].cpu().numpy()
         ref = om.forward(okv, toks)
         err = maxabs(got, ref)
+        print(f"context {L}, {M} rows: max |logits - oracle| = {err:.2e}", flush=True)
         worst = max(worst, err)
         assert err < 2e-2, (L, M, err)
         assert sv.ss_kv_cache_get_len(gkv).tolist() == [L + M]
