@@ -197,10 +197,9 @@ int ss_model_set_persistent_options(ss_model *model, int32_t workgroups, int32_t
 int ss_model_set_wait_limit(ss_model *model, uint32_t polls);
 
 /* Development aid, not part of the method: while buf_dev (dev, `entries` 64-bit words, zero-filled by the caller)
- * is set and entries >= 8 * phases * workgroups of a launch, every workgroup of the persistent kernel records
- * the device clock at points of each phase (0 start, 1 first activation slab arrived, 2 slab validated in LDS,
- * 3 last round done, 4 end, 5 first look at the slab done; 6 holds the number of further looks it took) at
- * buf[(8 * phase + point) * workgroups + workgroup].  NULL switches it off. */
+ * is set and entries >= 5 * phases * workgroups of a launch, every workgroup of the persistent kernel records
+ * the device clock at five points of each phase (start, prologue done, first activation slab in LDS, last
+ * round done, end) at buf[(5 * phase + point) * workgroups + workgroup].  NULL switches it off. */
 int ss_model_set_timeline(ss_model *model, unsigned long long *buf_dev, size_t entries);
 
 /* ---- KV cache (Sections 2, 4.2: keys and values of past tokens are kept instead of recomputed;

@@ -83,10 +83,6 @@ struct ss_model {
     MegaPhase *prog_full = nullptr; // [embed, layers, head, len]
     MegaPhase *prog_nohead = nullptr; // [embed, layers, len]
     int n_full = 0, n_nohead = 0;
-    std::vector<MegaPhase> prog_full_h, prog_nohead_h; // host copies (the chunk schedules inside depend on the grid)
-    uint32_t *sched = nullptr;      // chunk schedules of the GEMM phases, for a grid of sched_G workgroups
-    size_t sched_words = 0;
-    int sched_G = 0;
     float *nsq = nullptr;
     unsigned *arrive = nullptr, *abort_flag = nullptr, *attn_cnt = nullptr;
     void *zeros = nullptr;
@@ -180,30 +176,6 @@ static void model_release(ss_model *m) {
 extern "C" int ss_model_destroy(ss_model *m) {
     if (!m || !reg_take(m)) return SS_OK;
     model_release(m);
-    return SS_OK;
-}
-
-// (Re)builds the chunk schedules of the persistent kernel for the current grid and uploads them with both programs.
-// Off the hot path: model creation and ss_model_set_persistent_options.
-static int upload_programs(ss_model *m) {
-    std::vector<uint32_t> table = mega_build_schedules(m->prog_full_h, m->mega_G, m->cfg.dtype, m->cfg.head_dim);
-    // the program without the LM head has the same phases in the same places, up to the head
-    for (size_t i = 0; i < m->prog_nohead_h.size(); ++i) {
-        const MegaPhase &src = m->prog_full_h[i];
-        MegaPhase &dst = m->prog_nohead_h[i];
-        if (dst.kind != src.kind || dst.N != src.N || dst.K != src.K) continue; // (the final length update)
-        dst.ntiles_lo = src.ntiles_lo;
-        memcpy(dst.sched_off, src.sched_off, sizeof dst.sched_off);
-    }
-    if (table.size() > m->sched_words) {
-        int rc = dev_alloc(m, (void **)&m->sched, sizeof(uint32_t) * table.size(), false);
-        if (rc) return rc;
-        m->sched_words = table.size();
-    }
-    HIP_TRY(hipMemcpy(m->sched, table.data(), sizeof(uint32_t) * table.size(), hipMemcpyHostToDevice));
-    HIP_TRY(hipMemcpy(m->prog_full, m->prog_full_h.data(), sizeof(MegaPhase) * m->prog_full_h.size(), hipMemcpyHostToDevice));
-    HIP_TRY(hipMemcpy(m->prog_nohead, m->prog_nohead_h.data(), sizeof(MegaPhase) * m->prog_nohead_h.size(), hipMemcpyHostToDevice));
-    m->sched_G = m->mega_G;
     return SS_OK;
 }
 
@@ -328,9 +300,11 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
                 A((void **)&m->abort_flag, sizeof(unsigned), true);
                 A(&m->zeros, 256, true);
                 A((void **)&m->attn_cnt, sizeof(unsigned) * (size_t)c.max_rows * c.n_heads, true);
-                m->prog_full_h = prog;
-                m->prog_nohead_h = nohead;
-                if (rc == SS_OK) rc = upload_programs(m);
+                if (rc == SS_OK) {
+                    hipError_t e1 = hipMemcpy(m->prog_full, prog.data(), sizeof(MegaPhase) * prog.size(), hipMemcpyHostToDevice);
+                    hipError_t e2 = hipMemcpy(m->prog_nohead, nohead.data(), sizeof(MegaPhase) * nohead.size(), hipMemcpyHostToDevice);
+                    if (e1 != hipSuccess || e2 != hipSuccess) rc = fail(SS_EHIP, "program upload failed");
+                }
                 if (rc != SS_OK) {
                     model_release(m);
                     return rc;
@@ -725,10 +699,6 @@ extern "C" int ss_model_set_persistent_options(ss_model *m, int32_t workgroups, 
         return fail(SS_EINVAL, "ss_model_set_persistent_options: workgroups %d outside 0..%d", workgroups, m->mega_G_max);
     m->mega_G = workgroups ? workgroups : m->mega_G_max;
     m->data_sync = data_sync != 0;
-    if (m->mega_G != m->sched_G) { // the chunk schedules depend on the grid
-        HIP_TRY(hipDeviceSynchronize()); // no launch may still be reading the old ones
-        return upload_programs(m);
-    }
     return SS_OK;
 }
 
@@ -788,10 +758,9 @@ static int run_persistent(ss_model *m, ss_kv_cache *kv, const int32_t *tokens, f
     P.spin_limit = m->spin_limit;
     P.status = m->status;
     P.zeros = m->zeros;
-    P.sched = m->sched;
     m->epoch += (unsigned)P.n_phases + 1;
     // development aid: device clock samples of every workgroup, into the caller's buffer when it is large enough
-    if (m->timeline && m->timeline_entries >= (size_t)MEGA_TL_SLOTS * P.n_phases * m->mega_G) P.timeline = m->timeline;
+    if (m->timeline && m->timeline_entries >= (size_t)5 * P.n_phases * m->mega_G) P.timeline = m->timeline;
     {
         ProfScope ps(m, PT_PERSISTENT, st);
         hipError_t e = launch_mega(P, m->mega_G, st);

@@ -21,8 +21,7 @@ template <int HD, int NW> struct AttnSmem {
 template <typename T, int HD, int NW, bool COH = false, bool DIRECT = false>
 __device__ __forceinline__ void attn_unit(const AttnArgs &a, int split, int h, int b, int L, AttnSmem<HD, NW> &sm) {
     constexpr int E = Traits<T>::E, KB = 4 * E, TPB = E / 4, NKC = HD / KB, NDT = HD / 16;
-    const int t = thread_index();
-    const int lane = t & 63, wave = t >> 6;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 15, g = lane >> 4;
     const int ntot = L + a.M;
     const int p_begin = split * a.chunk;

@@ -46,55 +46,18 @@ namespace ss {
 
 constexpr int MNW = MEGA_THREADS / 64; // wavefronts per workgroup
 constexpr int CH = 4;                  // 128-byte steps per chunk per wave (8 loads = 8 KB per wave)
-constexpr int RING = MEGA_RING;        // chunks in flight per wave (48 KB; the hardware counts at most 63 loads per wave)
+constexpr int SLAB_CK = 8192 / (CH * MNW * 128); // chunks per LDS activation slab (8 KB of K per row)
+constexpr int RING = 2;                // chunks in flight per wave
 constexpr int CHUNK_ROW_BYTES = CH * MNW * 128; // bytes of a weight row one chunk covers (all waves)
-constexpr int MAX_SLAB_CK = MEGA_MAX_SLAB_CK; // most chunks an LDS activation slab covers (12 KB of K per row and plane); the launch
-                                       // picks MegaCall::slab_ck <= this so that the rows of the call fit the LDS
-static_assert(RING + 2 <= MEGA_ROW_WORDS, "a schedule row holds the codes of one round and its action word");
-// An LDS slab holds, per hidden row and plane, slab_ck chunks of K = slab_ck * CHUNK_ROW_BYTES bytes, at a pitch padded
-// against LDS bank conflicts between rows.
-__host__ __device__ constexpr int slab_row_bytes(int slab_ck) { return slab_ck * CHUNK_ROW_BYTES; }
-__host__ __device__ constexpr int slab_pitch(int slab_ck) { return slab_ck * CHUNK_ROW_BYTES + 48; }
 
 struct Range {
     int u0, u1, ntiles;
 };
 
-// the thread index, opaque to loop-invariant code motion (see thread_index())
-__device__ __forceinline__ int tid() { return thread_index(); }
-
-// Phase descriptor i of the program.  The program is written once by the host when the model is created and is read-only
-// for every kernel, so it is read through the constant address space: with a uniform index that is a scalar load, which
-// the counter of vector memory operations does not see (a vector load here would make the code wait for every weight
-// load in flight before it could look at the descriptor).
-__device__ __forceinline__ MegaPhase load_phase(const MegaPhase *prog, int i) {
-    static_assert(sizeof(MegaPhase) % 4 == 0, "copied word by word");
-    typedef const uint32_t __attribute__((address_space(4))) *cptr;
-    struct Words {
-        uint32_t w[sizeof(MegaPhase) / 4];
-    } words;
-    cptr src = (cptr)(uintptr_t)(prog + i);
-#pragma unroll
-    for (size_t j = 0; j < sizeof(MegaPhase) / 4; ++j) words.w[j] = src[j];
-    return __builtin_bit_cast(MegaPhase, words);
-}
-
-// word `idx` of phase descriptor i's table of schedule offsets (a run-time index into a copy of the descriptor would put the
-// copy into scratch memory)
-__device__ __forceinline__ int load_sched_off(const MegaPhase *prog, int i, int idx) {
-    typedef const int __attribute__((address_space(4))) *cptr;
-    return ((cptr)(uintptr_t)(&prog[i].sched_off[0][0]))[idx];
-}
-
-// A value that is the same in every lane, said so that the compiler keeps it in a scalar register and
-// branches on it with scalar branches (it cannot always prove uniformity through the phase loop).
-__device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
-__device__ __forceinline__ bool uni(bool x) { return __builtin_amdgcn_readfirstlane((int)x) != 0; }
-
-__host__ __device__ __forceinline__ bool is_gemm(int kind) { return kind == PH_QKV || kind == PH_RESID || kind == PH_SWIGLU || kind == PH_HEAD; }
+__device__ __forceinline__ bool is_gemm(int kind) { return kind == PH_QKV || kind == PH_RESID || kind == PH_SWIGLU || kind == PH_HEAD; }
 
 // the share of phase ph owned by workgroup wg: units are tiles (QKV), pairs (SWIGLU) or rows
-__host__ __device__ __forceinline__ Range phase_range(const MegaPhase &ph, int wg, int G) {
+__device__ __forceinline__ Range phase_range(const MegaPhase &ph, int wg, int G) {
     const int units = ph.kind == PH_QKV ? ph.N / 16 : ph.N;
     Range r; // wg * units < 2^31 for every shape the host accepts
     r.u0 = (int)((unsigned)wg * (unsigned)units / (unsigned)G);
@@ -122,61 +85,107 @@ __device__ __forceinline__ int a_row(int kind, int N, const Range &r, int hd, in
     return row;
 }
 
-// One round of a phase's chunk schedule (see ss_mega.h), held in scalar registers.
-struct Row {
-    uint32_t w[MEGA_ROW_WORDS];
-};
-__device__ __forceinline__ Row load_row(const uint32_t *sched, int off_words) { // the schedule is read-only: scalar loads
-    typedef const uint32_t __attribute__((address_space(4))) *cptr;
-    cptr src = (cptr)(uintptr_t)(sched + uni(off_words)); // said to be uniform: the loads are scalar, the row lives in scalar registers
-    Row r;
-#pragma unroll
-    for (int j = 0; j < MEGA_ROW_WORDS; ++j) r.w[j] = (uint32_t)uni((int)src[j]);
-    return r;
-}
-__device__ __forceinline__ Row none_row() { // nothing to fetch: every position is padding
-    Row r;
-#pragma unroll
-    for (int j = 0; j < MEGA_ROW_WORDS; ++j) r.w[j] = POS_DUMMY;
-    r.w[RING] = ACT_NO_SLAB | ACT_SEG_END | ACT_PHASE_END; // (a consumer that ever ran it would leave its loops at once)
-    return r;
+template <typename T> __device__ __forceinline__ int chunks_per_tile(int K) {
+    const int row_bytes = K * (int)sizeof(T);
+    return (row_bytes + CHUNK_ROW_BYTES - 1) / CHUNK_ROW_BYTES;
 }
 
-// Where the weight look-ahead is: the phase its next round belongs to and what it takes to form that phase's addresses.
-struct Feed {
-    int p;       // program index of the phase the row `nxt` belongs to (-1: before the first)
-    int off;     // word offset of that row in the schedule table
-    bool active; // `nxt` is a row of phase p's schedule (else: nothing to fetch)
+// Position in a workgroup's static chunk sequence.  Everything a step needs rides along (phase
+// fields, the tile's per-lane row pointer), so stepping costs no division and no descriptor reload.
+struct Cursor {
+    bool active; // positions of this workgroup remain in the current phase
+    int tile, ck, nck;
+    int idx;    // position index inside the phase, padding included
+    bool dummy; // a padding position: no data, no math
+    Range r;
+    int kind, N, kbytes; // phase kind, rows/pairs, bytes per weight row
     const char *W;
-    int kind, N, kbytes;
-    Range rg;
     const char *wp; // this lane's pointer into its weight row of the current tile (+ its wave / lane-group offset)
     bool live;      // the lane's A-row exists
 };
 
-// Issue the 2*CH weight loads of the position `code` of the look-ahead's phase.  Every call issues exactly 2*CH loads,
-// whatever the position is (real, padding, dead row, K tail): positions without data read a small zero-filled buffer
-// instead.  A fixed number of loads per step is what lets the compiler wait for one ring slot with an exact vmcnt(N)
-// and leave the younger slots in flight; a conditional load would force vmcnt(0).
-__device__ __forceinline__ void issue_chunk(Feed &f, uint32_t code, int hd, const char *zeros, u32x4 (&wbuf)[2 * CH]) {
-    const int t = tid(), lane = t & 63, wave = t >> 6, cc = lane & 15, g = lane >> 4;
-    if (uni((code & POS_FIRST) != 0)) { // a new tile: this lane's weight row
-        const int row = a_row(f.kind, f.N, f.rg, hd, (int)((code >> 8) & 0xfffu), cc, f.live);
-        f.wp = f.W + (size_t)row * f.kbytes + wave * 128 + g * 16;
+template <typename T> __device__ __forceinline__ void cursor_tile(Cursor &c, int hd) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, cc = lane & 15, g = lane >> 4;
+    const int row = a_row(c.kind, c.N, c.r, hd, c.tile, cc, c.live);
+    c.wp = c.W + (size_t)row * c.kbytes + wave * 128 + g * 16;
+}
+
+// Position the cursor at this workgroup's first chunk of phase ph (inactive: no share, or not a GEMM).
+template <typename T> __device__ __forceinline__ void cursor_begin(Cursor &c, const MegaPhase &ph, int hd, int wg, int G) {
+    c.active = false;
+    c.dummy = false;
+    c.live = false;
+    c.tile = 0;
+    c.ck = 0;
+    c.idx = 0;
+    c.nck = 1;
+    c.kind = ph.kind;
+    c.N = ph.N;
+    c.kbytes = 0;
+    c.W = nullptr;
+    c.wp = nullptr;
+    c.r = Range{0, 0, 0};
+    if (!is_gemm(ph.kind)) return;
+    c.r = phase_range(ph, wg, G);
+    if (c.r.ntiles <= 0) return;
+    c.active = true;
+    c.kbytes = ph.K * (int)sizeof(T);
+    c.W = reinterpret_cast<const char *>(ph.W);
+    c.nck = chunks_per_tile<T>(ph.K);
+    cursor_tile<T>(c, hd);
+}
+
+// Advance to the next position of the phase.  Positions are real chunks or padding: a "slab group"
+// (the chunks that share one LDS activation slab: the workgroup's whole share when K fits one slab, else
+// SLAB_CK chunks of a tile) is padded to a multiple of RING positions, so that rounds of RING steps
+// never straddle a slab reload or the end of the phase.  While `dummy` is set, (tile, ck, wp) already
+// describe the next real chunk.  Touches no memory.
+template <typename T> __device__ __forceinline__ void cursor_next(Cursor &c, int hd) {
+    ++c.idx;
+    if (!c.dummy) {
+        const bool multi = c.nck > SLAB_CK;
+        bool group_end;
+        if (++c.ck == c.nck) {
+            c.ck = 0;
+            ++c.tile;
+            group_end = multi || c.tile == c.r.ntiles;
+            if (c.tile < c.r.ntiles) cursor_tile<T>(c, hd);
+        } else {
+            group_end = multi && c.ck % SLAB_CK == 0;
+        }
+        if (!group_end) return;
+        if (c.idx % RING != 0) {
+            c.dummy = true;
+            return;
+        }
+    } else {
+        if (c.idx % RING != 0) return;
+        c.dummy = false;
     }
-    const int ck = (int)(code & 0xffu);
-    const bool real = f.active && !(code & POS_DUMMY) && f.live;
-    const char *base = f.wp + (size_t)ck * CHUNK_ROW_BYTES;
-    const int kb0 = ck * CHUNK_ROW_BYTES + wave * 128 + g * 16;
+    if (c.tile >= c.r.ntiles) c.active = false;
+}
+
+// Issue the 2*CH weight loads of chunk c for this lane.  Every call issues exactly 2*CH loads, whatever
+// the chunk is (real, padding, dead row, K tail): positions without data read a small zero-filled
+// buffer instead.  A fixed number of loads per step is what lets the compiler wait for one ring slot
+// with an exact vmcnt(N) and leave the younger slots in flight; a conditional load would force vmcnt(0).
+__device__ __forceinline__ void issue_chunk(const Cursor &c, bool valid, const char *zeros, u32x4 (&wbuf)[2 * CH]) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4;
+    const bool real = valid && c.active && !c.dummy && c.live;
+    const char *base = c.wp + (size_t)c.ck * CHUNK_ROW_BYTES;
+    const int kb0 = c.ck * CHUNK_ROW_BYTES + wave * 128 + g * 16;
 #pragma unroll
     for (int i = 0; i < CH; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int off = i * (MNW * 128) + j * 64;
-            const char *a = (real && kb0 + off < f.kbytes) ? base + off : zeros;
+            const char *a = (real && kb0 + off < c.kbytes) ? base + off : zeros;
             wbuf[2 * i + j] = ld16_global(a);
         }
 }
+
+constexpr int SLAB_ROW_BYTES = SLAB_CK * CH * MNW * 128; // 8192: the K range one slab covers, per hidden row
+constexpr int SLAB_PITCH = SLAB_ROW_BYTES + 48; // padded against LDS bank conflicts between rows
 
 // LDS: [ union: activation slab | attention merge area ][ red ][ small ]
 constexpr int STASH_TILES = 6; // reduced tiles kept in LDS until the epilogue flush
@@ -219,16 +228,16 @@ __device__ __forceinline__ void stores_done() { __builtin_amdgcn_s_waitcnt(0x0F7
 
 __device__ __forceinline__ void grid_arrive(const MegaCall &P, unsigned epoch, MegaSmem &sm) {
     lds_barrier(); // every wave of the workgroup has passed stores_done()
-    if (tid() == 0) __hip_atomic_store(&P.arrive[blockIdx.x], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (threadIdx.x == 0) __hip_atomic_store(&P.arrive[blockIdx.x], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __device__ __forceinline__ bool grid_wait(const MegaCall &P, unsigned epoch, int lo, int hi, MegaSmem &sm) { // slots lo .. hi-1
-    if (tid() < 64) {
+    if (threadIdx.x < 64) {
         bool ok = true;
         unsigned spins = 0;
         for (;;) {
             bool all = true;
-            for (int i = lo + (int)tid(); i < hi; i += 64) {
+            for (int i = lo + (int)threadIdx.x; i < hi; i += 64) {
                 const unsigned v = __hip_atomic_load(&P.arrive[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if ((int)(v - epoch) < 0) all = false;
             }
@@ -238,7 +247,7 @@ __device__ __forceinline__ bool grid_wait(const MegaCall &P, unsigned epoch, int
                 break;
             }
         }
-        if (tid() == 0) {
+        if (threadIdx.x == 0) {
             sm.t->flag = ok ? 1 : 0;
             if (!ok) __hip_atomic_store(P.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
@@ -252,7 +261,7 @@ __device__ __forceinline__ bool grid_wait(const MegaCall &P, unsigned epoch, int
 // those QKV tiles only (they publish the same epoch slots), not for the slowest workgroup of the chip;
 // workgroups without a unit do not wait at this boundary at all.
 __device__ __forceinline__ bool grid_wait_qkv_of_head(const MegaCall &P, unsigned epoch, int h, int G, MegaSmem &sm) {
-    if (tid() < 64) {
+    if (threadIdx.x < 64) {
         const int tph = P.hd / 16, units = 3 * P.H * tph; // QKV tiles per head and region, and in total
         bool ok = true;
         unsigned spins = 0;
@@ -262,7 +271,7 @@ __device__ __forceinline__ bool grid_wait_qkv_of_head(const MegaCall &P, unsigne
                 const int t_lo = (region * P.H + h) * tph, t_hi = t_lo + tph - 1;
                 // owner of tile t under the static split u0(wg) = floor(wg * units / G)
                 const int w_lo = (int)(((long long)(t_lo + 1) * G - 1) / units), w_hi = (int)(((long long)(t_hi + 1) * G - 1) / units);
-                for (int i = w_lo + (int)tid(); i <= w_hi; i += 64) {
+                for (int i = w_lo + (int)threadIdx.x; i <= w_hi; i += 64) {
                     const unsigned v = __hip_atomic_load(&P.arrive[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     if ((int)(v - epoch) < 0) all = false;
                 }
@@ -273,7 +282,7 @@ __device__ __forceinline__ bool grid_wait_qkv_of_head(const MegaCall &P, unsigne
                 break;
             }
         }
-        if (tid() == 0) {
+        if (threadIdx.x == 0) {
             sm.t->flag = ok ? 1 : 0;
             if (!ok) __hip_atomic_store(P.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
@@ -294,7 +303,7 @@ template <typename T>
 __device__ __forceinline__ float do_embed(const MegaCall &P, const MegaPhase &ph, int wg, int G) {
     const ActPlanes<T> act = act_planes<T>(P, ACT_A);
     const int c0 = (int)((long long)wg * P.d / G), c1 = (int)((long long)(wg + 1) * P.d / G);
-    const int r = tid() & 15;
+    const int r = threadIdx.x & 15;
     float ss = 0.f;
     if (r >= P.R) return ss;
     const T *src = nullptr;
@@ -306,7 +315,7 @@ __device__ __forceinline__ float do_embed(const MegaCall &P, const MegaPhase &ph
         }
         src = reinterpret_cast<const T *>(P.embed) + (size_t)tok * P.d;
     }
-    for (int e = c0 + (int)(tid() >> 4); e < c1; e += MEGA_THREADS / 16) {
+    for (int e = c0 + (int)(threadIdx.x >> 4); e < c1; e += MEGA_THREADS / 16) {
         float x;
         if (src) {
             x = to_f32(src[e]);
@@ -353,7 +362,7 @@ __device__ __forceinline__ void do_attn_hd(const MegaCall &P, const MegaPhase &p
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __syncthreads();
         if (P.nsplit > 1) {
-            if (tid() == 0) {
+            if (threadIdx.x == 0) {
                 const unsigned old = __hip_atomic_fetch_add(&P.attn_cnt[bh], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 sm.t->flag = old == (unsigned)(P.nsplit - 1);
             }
@@ -361,11 +370,11 @@ __device__ __forceinline__ void do_attn_hd(const MegaCall &P, const MegaPhase &p
             merge = sm.t->flag != 0;
         }
         if (merge) {
-            for (int idx = tid(); idx < P.M * HD; idx += MEGA_THREADS) {
+            for (int idx = threadIdx.x; idx < P.M * HD; idx += MEGA_THREADS) {
                 const int c = idx / HD, e = idx - c * HD, row = b * P.M + c;
                 store_act_coh(out, (size_t)row * a.ld_out + h * HD + e, attn_merge_elem<true>(a, row, h, e));
             }
-            if (P.nsplit > 1 && tid() == 0) __hip_atomic_store(&P.attn_cnt[bh], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (P.nsplit > 1 && threadIdx.x == 0) __hip_atomic_store(&P.attn_cnt[bh], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         __syncthreads();
     }
@@ -403,8 +412,8 @@ struct ScaleLoads {
     float t[2][8];
 };
 __device__ __forceinline__ bool scale_slot(const MegaCall &P, int G, int half, int q, int &row, int &i) { // false: no such partial
-    row = (tid() >> 5) + half * (MEGA_THREADS / 32);
-    i = (tid() & 31) + 32 * q;
+    row = (threadIdx.x >> 5) + half * (MEGA_THREADS / 32);
+    i = (threadIdx.x & 31) + 32 * q;
     return row < P.R && i < G;
 }
 // every thread issues all 16 loads (a fixed number of loads keeps the waits on them exact); slots
@@ -422,10 +431,10 @@ __device__ __forceinline__ void scales_issue(const MegaCall &P, const float *nsq
         }
 }
 __device__ __forceinline__ void scales_finish(const MegaCall &P, const float *nsq, int G, const ScaleLoads &sl, MegaSmem &sm) {
-    const int j = tid() & 31;
+    const int j = threadIdx.x & 31;
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
-        const int row = (tid() >> 5) + half * (MEGA_THREADS / 32);
+        const int row = (threadIdx.x >> 5) + half * (MEGA_THREADS / 32);
         float s = 0.f;
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
@@ -454,9 +463,12 @@ static_assert(MEGA_THREADS / 32 * 2 >= 16, "two halves of the scale loads cover 
 // bf16_rne and the fp32 arithmetic produce other NaNs at most), so a unit that still shows the pattern
 // has not arrived and is simply loaded again (bounded).  Each element is validated on its own, so no
 // ordering between different stores is assumed.  The resets ride on causality, see clear_outputs().
-constexpr int SLAB_UNITS = MAX_SLAB_CK * CHUNK_ROW_BYTES / 16 / MEGA_THREADS; // 16-byte units per thread and slab row (the largest slab)
-constexpr int SLAB_BATCH = 10; // (plane, row) pairs per validation mask
-static_assert(SLAB_BATCH * SLAB_UNITS <= 32, "one mask bit per unit of a batch");
+constexpr int SLAB_UNITS = SLAB_ROW_BYTES / 16 / MEGA_THREADS; // 16-byte units per thread and slab row
+template <int NPR> struct SlabLoads { // NPR: (plane, row) pairs per batch
+    u32x4 v[NPR][SLAB_UNITS]; // [(plane, row) pair][unit]
+    ScaleLoads sl;
+};
+static_assert(10 * SLAB_UNITS < 31, "one mask bit per unit of a batch, bit 31 for the row scales");
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 // running maximum that ends at all ones iff some element seen was the "not written yet" pattern
@@ -474,128 +486,106 @@ template <typename T> __device__ __forceinline__ bool unit_unset(const u32x4 &v)
 __device__ __forceinline__ void store_unset(bf16_t *p) { st_coh(p, bf16_t{(uint16_t)0xffffu}); }
 __device__ __forceinline__ void store_unset(float *p) { st_coh(p, u2f(0xffffffffu)); }
 
-// One 16-byte agent-coherent load per lane (sc0 sc1: performed at the memory side, like ld16_coh_buf) that the memory
-// system writes straight into LDS, lane l at lds_wave_base + 16 l: no registers hold the slab.
-__device__ __forceinline__ void dma16_coh(const void *src, unsigned char *lds_wave_base) {
-    typedef const void __attribute__((address_space(1))) *gptr;
-    typedef void __attribute__((address_space(3))) *lptr;
-    __builtin_amdgcn_global_load_lds((gptr)src, (lptr)lds_wave_base, 16, 0, 1 | 16);
-}
-// The 16-byte units of K slab `slab` that this thread handles for the hidden rows r0 .. r0 + SLAB_BATCH / PLANES - 1 (a
-// "batch": at most 32 units, one mask bit each).  A slab row is a whole number of 1 KB wave instructions; thread t takes
-// unit t + h2 * threads of every (plane, row) pair.  f(bit, valid, byte offset of the unit in the source planes - clamped
-// to a valid address when the unit holds no data (row without data, K tail) -, the unit's place in LDS, the LDS base of the
-// wave instruction that carries it); valid false: the unit holds no data and counts as zeros.
-// (Written without divisions and with the row loop unrolled: this runs at every phase boundary.)
-template <typename T, typename F>
-__device__ __forceinline__ void slab_units(const MegaCall &P, const MegaPhase &ph, int slab, int r0, MegaSmem &sm, F f) {
-    constexpr int PL = Traits<T>::PLANES, BR = SLAB_BATCH / PL, PER16 = 16 / (int)sizeof(T);
-    const ActPlanes<T> src = act_planes<T>(P, ph.act_src);
+// Unit (i, h2) of a batch that starts at (plane, row) pair pr0: byte offset of its 16 bytes in the source
+// planes, clamped to a valid address when the unit does not exist (pair beyond the slab rows, row
+// without data, K tail); false: it does not exist and counts as zeros.
+template <typename T>
+__device__ __forceinline__ bool slab_unit(const MegaCall &P, const MegaPhase &ph, const ActPlanes<T> &src, int slab, int pr, int h2,
+                                          uint32_t &byte_off) {
+    constexpr int PER16 = 16 / (int)sizeof(T); // elements per 16-byte unit
     const bool head = ph.kind == PH_HEAD;
+    const int rows = P.slab_rows, nrow = Traits<T>::PLANES * rows;
     const int nlive = head ? P.head_rows : P.R;
-    const int t = tid(), wave = t >> 6;
-    const int srb = slab_row_bytes(P.slab_ck), pitch = slab_pitch(P.slab_ck);
-    const int kslab = slab * (srb / (int)sizeof(T));
+    const int prc = min(pr, nrow - 1);
+    const int r = prc % rows, pl = prc / rows, rc = min(r, nlive - 1);
+    const int brow = head ? P.head_row0 + rc * P.head_stride : rc;
+    const int x = threadIdx.x + h2 * MEGA_THREADS;
+    const int k = slab * (SLAB_ROW_BYTES / (int)sizeof(T)) + x * PER16; // K is a multiple of the unit
+    const bool valid = pr < nrow && r < nlive && k < ph.K;
+    byte_off = (uint32_t)((pl * src.plane + (size_t)brow * src.ld + (k < ph.K ? k : 0)) * sizeof(T));
+    return valid;
+}
+// All loads of a batch (with_scales: and of the row scales), unconditionally: the number of loads in
+// flight is a compile-time constant, so a later wait for them can leave younger loads in flight.
+template <typename T, int NPR>
+__device__ __forceinline__ void slab_issue(const MegaCall &P, const MegaPhase &ph, int slab, int pr0, int G, bool with_scales,
+                                           SlabLoads<NPR> &L) {
+    const ActPlanes<T> src = act_planes<T>(P, ph.act_src);
+    if (with_scales) scales_issue(P, nsq_set(P, ph.act_src, G), G, false, L.sl);
 #pragma unroll
-    for (int rr = 0; rr < BR; ++rr) {
-        const int r = r0 + rr;
-        if (r < P.slab_rows) {
-            const int rc = min(r, nlive - 1);
-            const int brow = head ? P.head_row0 + rc * P.head_stride : rc;
+    for (int i = 0; i < NPR; ++i)
 #pragma unroll
-            for (int pl = 0; pl < PL; ++pl)
-#pragma unroll
-                for (int h2 = 0; h2 < SLAB_UNITS; ++h2)
-                    if ((wave * 64 + h2 * MEGA_THREADS) * 16 < srb) { // the wave's instruction h2 lies inside the slab row
-                        const int x = t + h2 * MEGA_THREADS, k = kslab + x * PER16; // K is a multiple of the unit
-                        const bool valid = r < nlive && k < ph.K;
-                        const uint32_t off = (uint32_t)((pl * src.plane + (size_t)brow * src.ld + (k < ph.K ? k : 0)) * sizeof(T));
-                        unsigned char *row_lds = sm.u + (size_t)(pl * P.slab_rows + r) * pitch;
-                        f((rr * PL + pl) * SLAB_UNITS + h2, valid, off, row_lds + x * 16, row_lds + (wave * 64 + h2 * MEGA_THREADS) * 16);
-                    }
+        for (int h2 = 0; h2 < SLAB_UNITS; ++h2) {
+            uint32_t off;
+            slab_unit<T>(P, ph, src, slab, pr0 + i, h2, off);
+            L.v[i][h2] = ld16_coh_buf(src.base, off);
         }
+}
+// true: something this lane loaded still shows the "not written yet" pattern
+template <typename T, int NPR>
+__device__ __forceinline__ bool slab_unset(const MegaCall &P, const MegaPhase &ph, int slab, int pr0, int G, bool with_scales,
+                                           const SlabLoads<NPR> &L) {
+    const ActPlanes<T> src = act_planes<T>(P, ph.act_src);
+    uint32_t m = 0, ms = 0;
+#pragma unroll
+    for (int i = 0; i < NPR; ++i)
+#pragma unroll
+        for (int h2 = 0; h2 < SLAB_UNITS; ++h2) {
+            uint32_t off;
+            const bool valid = slab_unit<T>(P, ph, src, slab, pr0 + i, h2, off);
+            const uint32_t um = unset_acc<T>(unset_acc<T>(L.v[i][h2][0], L.v[i][h2][1]), unset_acc<T>(L.v[i][h2][2], L.v[i][h2][3]));
+            m = unset_acc<T>(m, valid ? um : 0u);
+        }
+    if (with_scales) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                int row, i;
+                ms = unset_acc<float>(ms, scale_slot(P, G, half, q, row, i) ? f2u(L.sl.t[half][q]) : 0u);
+            }
     }
+    return unset_seen<T>(m) || unset_seen<float>(ms);
 }
-constexpr int slab_batch_rows(int planes) { return SLAB_BATCH / planes; }
-// All loads of K slab `slab` (with_scales: and of the row scales, into registers), unconditionally and straight into LDS.
-// The caller has made sure that nobody still reads the LDS area.
-template <typename T>
-__device__ __forceinline__ void slab_issue(const MegaCall &P, const MegaPhase &ph, int slab, int G, bool with_scales, ScaleLoads &sl, MegaSmem &sm) {
-    const char *base = reinterpret_cast<const char *>(act_planes<T>(P, ph.act_src).base);
-    if (with_scales) scales_issue(P, nsq_set(P, ph.act_src, G), G, false, sl);
-    for (int r0 = 0; r0 < P.slab_rows; r0 += slab_batch_rows(Traits<T>::PLANES))
-        slab_units<T>(P, ph, slab, r0, sm, [&](int, bool, uint32_t off, unsigned char *, unsigned char *wave_lds) { dma16_coh(base + off, wave_lds); });
-}
-// Looks at what has arrived in LDS: a bit of the result is set when this thread's unit of that number still shows the
-// "not written yet" pattern.  Units without data are ignored (and zeroed when `finish` is set: call it that way once,
-// after the first load has landed).  The units of a hidden row are read together, then judged, so that the LDS
-// latency is paid once per row and not once per unit.
-template <typename T>
-__device__ __forceinline__ uint32_t slab_look(const MegaCall &P, const MegaPhase &ph, int slab, int r0, bool finish, MegaSmem &sm) {
-    constexpr int PL = Traits<T>::PLANES, BR = SLAB_BATCH / PL, PER16 = 16 / (int)sizeof(T), NU = PL * SLAB_UNITS;
-    const int nlive = ph.kind == PH_HEAD ? P.head_rows : P.R;
-    const int t = tid(), wave = t >> 6;
-    const int srb = slab_row_bytes(P.slab_ck), pitch = slab_pitch(P.slab_ck);
-    const int kslab = slab * (srb / (int)sizeof(T));
-    uint32_t mask = 0;
-#pragma unroll
-    for (int rr = 0; rr < BR; ++rr) {
-        const int r = r0 + rr;
-        if (r < P.slab_rows) {
-            u32x4 v[NU];
-#pragma unroll
-            for (int pl = 0; pl < PL; ++pl)
-#pragma unroll
-                for (int h2 = 0; h2 < SLAB_UNITS; ++h2) { // (a unit outside the slab row reads the thread's first unit instead)
-                    const bool in = (wave * 64 + h2 * MEGA_THREADS) * 16 < srb;
-                    v[pl * SLAB_UNITS + h2] = *reinterpret_cast<const u32x4 *>(sm.u + (size_t)(pl * P.slab_rows + r) * pitch + (t + (in ? h2 : 0) * MEGA_THREADS) * 16);
-                }
-#pragma unroll
-            for (int pl = 0; pl < PL; ++pl)
-#pragma unroll
-                for (int h2 = 0; h2 < SLAB_UNITS; ++h2) {
-                    const bool in = (wave * 64 + h2 * MEGA_THREADS) * 16 < srb;
-                    const int x = t + h2 * MEGA_THREADS, k = kslab + x * PER16;
-                    const bool valid = r < nlive && k < ph.K;
-                    if (in && valid && unit_unset<T>(v[pl * SLAB_UNITS + h2])) mask |= 1u << ((rr * PL + pl) * SLAB_UNITS + h2);
-                    if (in && !valid && finish) *reinterpret_cast<u32x4 *>(sm.u + (size_t)(pl * P.slab_rows + r) * pitch + x * 16) = zero16();
-                }
-        }
-    }
-    return mask;
-}
-__device__ __forceinline__ bool scales_unset(const MegaCall &P, int G, const ScaleLoads &sl) {
-    uint32_t ms = 0;
-#pragma unroll
-    for (int half = 0; half < 2; ++half)
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            int row, i;
-            ms = unset_acc<float>(ms, scale_slot(P, G, half, q, row, i) ? f2u(sl.t[half][q]) : 0u);
-        }
-    return unset_seen<float>(ms);
-}
-// After a first look found the pattern: wait (bounded) until nothing this wave loaded shows it, loading again what does.
-// false: gave up (the caller raises the abort flag).
-template <typename T>
-__device__ __forceinline__ bool slab_retry(const MegaCall &P, const MegaPhase &ph, int slab, int r0, int G, bool with_scales, uint32_t mask,
-                                           ScaleLoads &sl, MegaSmem &sm, unsigned long long *tl_spins = nullptr) {
-    const char *base = reinterpret_cast<const char *>(act_planes<T>(P, ph.act_src).base);
+// After a first slab_unset() found the pattern: wait (bounded) until nothing this wave loaded shows
+// it, loading again what does.  false: gave up (the caller raises the abort flag).
+template <typename T, int NPR>
+__device__ __forceinline__ bool slab_retry(const MegaCall &P, const MegaPhase &ph, int slab, int pr0, int G, bool with_scales,
+                                           SlabLoads<NPR> &L) {
+    const ActPlanes<T> src = act_planes<T>(P, ph.act_src);
     for (unsigned spins = 0; spins < P.spin_limit; ++spins) {
-        const unsigned aborted = __hip_atomic_load(P.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); // rides with the loads below: one round trip
-        if (with_scales) scales_issue(P, nsq_set(P, ph.act_src, G), G, true, sl);
-        slab_units<T>(P, ph, slab, r0, sm, [&](int bit, bool, uint32_t off, unsigned char *, unsigned char *wave_lds) {
-            if (__any((mask >> bit & 1u) != 0u)) dma16_coh(base + off, wave_lds); // a wave instruction with a missing unit is issued again as a whole
-        });
-        stores_done(); // the loads have landed in LDS (and in the registers of the scales)
-        if (aborted != 0u) return false;
-        mask = slab_look<T>(P, ph, slab, r0, false, sm);
-        if (!__any(mask != 0u || (with_scales && scales_unset(P, G, sl)))) {
-            if (tl_spins) *tl_spins = spins + 1;
-            return true;
-        }
+        if (__hip_atomic_load(P.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) return false;
+        if (with_scales) scales_issue(P, nsq_set(P, ph.act_src, G), G, true, L.sl);
+#pragma unroll
+        for (int i = 0; i < NPR; ++i)
+#pragma unroll
+            for (int h2 = 0; h2 < SLAB_UNITS; ++h2) {
+                uint32_t off;
+                if (slab_unit<T>(P, ph, src, slab, pr0 + i, h2, off) && unit_unset<T>(L.v[i][h2])) L.v[i][h2] = ld16_coh_buf(src.base, off);
+            }
+        if (!__any(slab_unset<T>(P, ph, slab, pr0, G, with_scales, L))) return true;
     }
     return false;
+}
+template <typename T, int NPR>
+__device__ __forceinline__ void slab_finish(const MegaCall &P, const MegaPhase &ph, int slab, int pr0, int G, bool with_scales,
+                                            const SlabLoads<NPR> &L, MegaSmem &sm) {
+    const ActPlanes<T> src = act_planes<T>(P, ph.act_src);
+    const int nrow = Traits<T>::PLANES * P.slab_rows;
+    if (with_scales) scales_finish(P, nsq_set(P, ph.act_src, G), G, L.sl, sm);
+#pragma unroll
+    for (int i = 0; i < NPR; ++i) {
+        const int pr = pr0 + i;
+        if (pr < nrow) {
+#pragma unroll
+            for (int h2 = 0; h2 < SLAB_UNITS; ++h2) {
+                uint32_t off;
+                const bool valid = slab_unit<T>(P, ph, src, slab, pr, h2, off);
+                const int x = threadIdx.x + h2 * MEGA_THREADS;
+                *reinterpret_cast<u32x4 *>(sm.u + (size_t)pr * SLAB_PITCH + x * 16) = valid ? L.v[i][h2] : zero16();
+            }
+        }
+    }
 }
 
 // Reset, to the "not written yet" pattern, what this workgroup will write in phase `tp` (a later phase).
@@ -617,18 +607,18 @@ __device__ __forceinline__ void clear_outputs(const MegaCall &P, const MegaPhase
         const Range r = phase_range(tp, wg, G); // columns of the output = rows (pairs) of the weight matrix
         const ActPlanes<T> a = act_planes<T>(P, tp.kind == PH_RESID ? tp.act_dst : ACT_Z);
         const int ncol = r.u1 - r.u0, n = ncol * P.R * PL;
-        for (int idx = tid(); idx < n; idx += MEGA_THREADS) {
+        for (int idx = threadIdx.x; idx < n; idx += MEGA_THREADS) {
             const int col = r.u0 + idx % ncol, rest = idx / ncol, row = rest % P.R, pl = rest / P.R;
             store_unset(a.base + pl * a.plane + (size_t)row * a.ld + col);
         }
-        if (tp.kind == PH_RESID && tid() < 16) store_unset(&nsq_set(P, tp.act_dst, G)[(size_t)tid() * G + wg]);
+        if (tp.kind == PH_RESID && threadIdx.x < 16) store_unset(&nsq_set(P, tp.act_dst, G)[(size_t)threadIdx.x * G + wg]);
     } else if (tp.kind == PH_ATTN) {
         const ActPlanes<T> o = act_planes<T>(P, ACT_O);
         const int units = P.B * P.H * P.nsplit, n = P.M * P.hd * PL;
         for (int u = wg; u < units; u += G) {
             if (u % P.nsplit != 0) continue; // one of the splits of (sequence, head) does it
             const int bh = u / P.nsplit, h = bh % P.H, b = bh / P.H;
-            for (int idx = tid(); idx < n; idx += MEGA_THREADS) {
+            for (int idx = threadIdx.x; idx < n; idx += MEGA_THREADS) {
                 const int e = idx % P.hd, rest = idx / P.hd, c = rest % P.M, pl = rest / P.M;
                 store_unset(o.base + pl * o.plane + (size_t)(b * P.M + c) * o.ld + h * P.hd + e);
             }
@@ -652,7 +642,7 @@ __device__ __forceinline__ void epi_prefetch(const MegaCall &P, const MegaPhase 
     es.h_pre = 0.f;
     es.g_pre = 1.f;
     if (!es.pre) return;
-    const int c = tid() & 15, i = tid() >> 4;
+    const int c = threadIdx.x & 15, i = threadIdx.x >> 4;
     bool live;
     const int n = a_row(ph.kind, ph.N, r, P.hd, 0, i, live);
     if (live && c < P.R) {
@@ -737,22 +727,27 @@ __device__ __forceinline__ void mma2(f32x4 &acc0, f32x4 &acc1, u32x4 w, const Ac
     else acc0 = mma(acc0, w, b);
 }
 
-// multiply a chunk (weights in wbuf; sck = its index inside the LDS slab) into the tile accumulators; the B operand
-// comes from the LDS slab.  Lanes whose hidden row does not exist read the last row that does (their output columns
-// are never looked at), so no LDS read is conditional.
+// multiply chunk c (weights in wbuf) into the tile accumulators; the B operand comes from the LDS slab
 template <typename T>
-__device__ __forceinline__ void mma_chunk(int sck, const MegaCall &P, const u32x4 (&wbuf)[2 * CH], f32x4 &acc0, f32x4 &acc1, MegaSmem &sm) {
+__device__ __forceinline__ void mma_chunk(const Cursor &c, const MegaCall &P, const u32x4 (&wbuf)[2 * CH], f32x4 &acc0, f32x4 &acc1,
+                                          MegaSmem &sm) {
     constexpr int PL = Traits<T>::PLANES;
-    const int t = tid(), lane = t & 63, wave = t >> 6, cc = min(lane & 15, P.slab_rows - 1), g = lane >> 4;
-    const unsigned char *lb = sm.u + (size_t)cc * slab_pitch(P.slab_ck) + sck * CHUNK_ROW_BYTES + wave * 128 + g * 16;
-    const size_t plane_off = (size_t)P.slab_rows * slab_pitch(P.slab_ck);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, cc = lane & 15, g = lane >> 4;
+    if (c.ck == 0) {
+        acc0 = f32x4{0.f, 0.f, 0.f, 0.f};
+        acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const bool blive = cc < P.slab_rows;
+    const unsigned char *lb = sm.u + (size_t)cc * SLAB_PITCH + (c.ck % SLAB_CK) * CHUNK_ROW_BYTES + wave * 128 + g * 16;
+    const size_t plane_off = (size_t)P.slab_rows * SLAB_PITCH;
 #pragma unroll
     for (int i = 0; i < CH; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             Act<T> av;
 #pragma unroll
-            for (int pl = 0; pl < PL; ++pl) av.p[pl] = *reinterpret_cast<const u32x4 *>(lb + pl * plane_off + i * (MNW * 128) + j * 64);
+            for (int pl = 0; pl < PL; ++pl)
+                av.p[pl] = blive ? *reinterpret_cast<const u32x4 *>(lb + pl * plane_off + i * (MNW * 128) + j * 64) : zero16();
             mma2(acc0, acc1, wbuf[2 * i + j], av, j);
         }
 }
@@ -763,7 +758,7 @@ __device__ __forceinline__ void mma_chunk(int sck, const MegaCall &P, const u32x
 // weight load to vmcnt(0) (loads and stores share the counter and may complete out of order).
 __device__ __forceinline__ void finish_tile(int tile, const f32x4 &acc0, const f32x4 &acc1, int &tile_seq, int &nstash,
                                             MegaSmem &sm) {
-    const int lane = tid() & 63, wave = tid() >> 6;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int par = tile_seq & 1;
     ++tile_seq;
 #pragma unroll
@@ -774,7 +769,7 @@ __device__ __forceinline__ void finish_tile(int tile, const f32x4 &acc0, const f
 #pragma unroll
         for (int w2 = 1; w2 < MNW; ++w2) sum += sm.t->red[par][w2][wave][lane];
         sm.t->stash[nstash][wave][lane] = sum;
-        if (tid() == 0) sm.t->stash_tile[nstash] = tile;
+        if (threadIdx.x == 0) sm.t->stash_tile[nstash] = tile;
     }
     ++nstash;
 }
@@ -789,7 +784,7 @@ template <typename T>
 __device__ __forceinline__ void flush_stash(const MegaCall &P, const MegaPhase &ph, const Range &r, int &nstash, EpiState &es,
                                             bool last, MegaSmem &sm) {
     lds_barrier(); // the stash writes of the last tile are visible
-    const int c = tid() & 15, ii = tid() >> 4;
+    const int c = threadIdx.x & 15, ii = threadIdx.x >> 4;
     if (ph.kind == PH_QKV || ph.kind == PH_SWIGLU) {
         const int i = ii & 7;
         for (int slot = ii >> 3; slot < nstash; slot += MEGA_THREADS / 128) {
@@ -815,113 +810,66 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
     MegaSmem sm;
     sm.u = smem_raw;
     sm.t = reinterpret_cast<MegaSmemTail *>(smem_raw + P.u_bytes);
-    const int wg = uni((int)blockIdx.x), G = uni((int)gridDim.x);
-    const int lane = tid() & 63, wave = tid() >> 6;
-    if (tid() < 16) sm.t->len[tid()] = (int)tid() < P.B ? P.len[tid()] : 0; // lengths change in the last phase only
-    if (tid() == 0) sm.t->ok = 1;
+    const int wg = blockIdx.x, G = gridDim.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (threadIdx.x < 16) sm.t->len[threadIdx.x] = (int)threadIdx.x < P.B ? P.len[threadIdx.x] : 0; // lengths change in the last phase only
+    if (threadIdx.x == 0) sm.t->ok = 1;
     lds_barrier();
 
-    // Weight pipeline.  The workgroup's chunk positions over all its GEMM phases form one sequence, cut into rounds of
-    // RING positions (the phases' schedules, built by the host).  `cur` is the round being multiplied, `nxt` the one
-    // after it - possibly the first round of the next GEMM phase: weights depend on nothing.  A step multiplies
-    // straight out of its ring slot (which waits for that slot's loads only - later slots stay in flight), then
-    // refills the slot with the same position of `nxt`.  So while a phase's epilogue runs and the next phase's input
-    // is awaited, the first RING chunks of that phase (48 KB per wave, 192 KB per compute unit) keep the memory
-    // system busy, and the O projection's whole share arrives during the attention phase.
-    f32x4 acc0 = f32x4{0.f, 0.f, 0.f, 0.f}, acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
-    int tile_seq = 0;
-    EpiState es;
-    es.rowsq = 0.f;
-    es.pre = false;
-    es.h_pre = 0.f;
-    es.g_pre = 1.f;
+    // Weight pipeline: `la` runs RING positions ahead of `cc` (the next chunk to multiply); the loads of
+    // those chunks are in flight into the ring slots.  A step multiplies straight out of its
+    // slot (which waits for that slot's loads only - later slots stay in flight), then refills the slot
+    // with the chunk RING ahead.  A workgroup's positions per phase are padded to a multiple of RING, so
+    // each phase starts at slot 0 and the code below exists once.  The last round of a phase does not
+    // refill: the ring is empty at a phase boundary and is refilled there with the first round of the
+    // next phase, so those loads fly while the boundary's dependencies resolve.
+    struct State {
+        Cursor cc, la;
+        f32x4 acc0, acc1;
+        int tile_seq, slab_tag;
+        EpiState es;
+    } st;
+    st.acc0 = f32x4{0.f, 0.f, 0.f, 0.f};
+    st.acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
+    st.tile_seq = 0;
+    st.slab_tag = -1;
+    st.es.rowsq = 0.f;
+    st.es.pre = false;
+    st.es.h_pre = 0.f;
+    st.es.g_pre = 1.f;
 
     u32x4 ring[RING][2 * CH]; // only ever indexed by unrolled constants: lives in registers
     static_assert(MNW >= 4, "waves 0-3 reduce one accumulator register each");
-    static_assert(RING * 2 * CH <= 63, "the hardware counts at most 63 vector memory operations in flight per wave");
 
     const char *zeros = reinterpret_cast<const char *>(P.zeros);
-    Feed fd;
-    fd.p = -1;
-    fd.off = 0;
-    fd.active = false;
-    fd.W = nullptr;
-    fd.kind = PH_LEN;
-    fd.N = 0;
-    fd.kbytes = 0;
-    fd.rg = Range{0, 0, 0};
-    fd.wp = zeros;
-    fd.live = false;
-    Row cur = none_row(), nxt = none_row();
-    // `nxt` becomes the round behind it: the next row of its phase's schedule, or the first row of this workgroup's next
-    // GEMM phase with work (none left: a row of padding)
-    auto advance = [&]() {
-        if (uni(fd.active && !(nxt.w[RING] & ACT_PHASE_END))) {
-            fd.off = uni(fd.off + MEGA_ROW_WORDS);
-            nxt = load_row(P.sched, fd.off);
-            return;
-        }
-        fd.active = false;
-        nxt = none_row();
-        for (;;) {
-            fd.p = uni(fd.p);
-            if (fd.p + 1 >= P.n_phases) break;
-            const MegaPhase nph = load_phase(P.phases, fd.p + 1);
-            ++fd.p;
-            if (!uni(is_gemm(nph.kind))) continue;
-            const Range rg = phase_range(nph, wg, G);
-            if (uni(rg.ntiles <= 0)) continue;
-            const int variant = rg.ntiles - nph.ntiles_lo; // shares differ by at most one tile
-            if (uni(variant < 0 || variant > 1)) continue;
-            const int off = uni(load_sched_off(P.phases, fd.p, 2 * (P.slab_ck - MEGA_MIN_SLAB_CK) + variant));
-            if (off < 0) continue;
-            fd.active = true;
-            fd.W = reinterpret_cast<const char *>(nph.W);
-            fd.kind = nph.kind;
-            fd.N = nph.N;
-            fd.kbytes = nph.K * (int)sizeof(T);
-            fd.rg = Range{uni(rg.u0), uni(rg.u1), uni(rg.ntiles)};
-            fd.off = off;
-            nxt = load_row(P.sched, fd.off);
-            return;
-        }
-    };
     // The empty asm statements are compiler barriers: they pin the slot's loads to this point of the
     // program.  Without them the scheduler sinks each load next to its use (to shorten live ranges),
     // which would leave one 16-byte load in flight per wave instead of a ring of chunks.
-    auto fill = [&](u32x4(&slot)[2 * CH], uint32_t code) { // always 2*CH loads
+    auto fill = [&](u32x4(&slot)[2 * CH]) { // always 2*CH loads
         asm volatile("" ::: "memory");
-        issue_chunk(fd, code, P.hd, zeros, slot);
+        issue_chunk(st.la, true, zeros, slot);
         asm volatile("" ::: "memory");
+        if (st.la.active) cursor_next<T>(st.la, P.hd);
     };
-    // `cur` = the first round of the look-ahead's phase, its loads issued; `nxt` = the round behind it
-    auto prime_ring = [&]() {
-        advance();
-        cur = nxt;
-#pragma unroll
-        for (int sl = 0; sl < RING; ++sl) fill(ring[sl], cur.w[sl]);
-        advance();
-    };
-    prime_ring(); // the first RING chunks of the first GEMM phase: nothing to wait for
 
     for (int p = 0; p < P.n_phases; ++p) {
-        const MegaPhase ph = load_phase(P.phases, uni(p));
-        // Phase boundary.  The ring already holds the first RING chunks of this workgroup's next GEMM phase.
-        const Range my = is_gemm(ph.kind) ? phase_range(ph, wg, G) : Range{0, 0, 0}; // this workgroup's share of the phase
-        const bool work = my.ntiles > 0;
+        const MegaPhase ph = P.phases[p];
+        // Phase boundary.  A workgroup with GEMM work in the phase fills all ring slots here (see below);
+        // one without leaves the ring alone.
+        cursor_begin<T>(st.cc, ph, P.hd, wg, G);
+        st.la = st.cc;
         const unsigned epoch = P.epoch_base + (unsigned)p;
         const int attn_units = P.B * P.H * P.nsplit;
         const bool want_scales = ph.kind == PH_QKV || ph.kind == PH_SWIGLU || ph.kind == PH_HEAD;
         // How this phase's input becomes visible.  Flags: the producers wait for their stores, publish
         // their epoch, and the consumer polls the epochs before it loads anything.  Data: nobody waits
-        // for acknowledgements; the consumer loads the first slab at once and validates it (slab_look,
-        // slab_retry).  After the attention phase the workgroups without
+        // for acknowledgements; the consumer loads the first slab at once (together with the weight
+        // prefetch) and validates it (slab_unset, slab_retry).  After the attention phase the workgroups without
         // a unit would find nothing for a long time, so they first wait for the units' epochs (a hint:
         // the data is validated all the same).
-        const bool polled = P.data_sync && ph.sync != SYNC_FLAGS && work;
+        const bool polled = P.data_sync && ph.sync != SYNC_FLAGS && st.cc.active;
         const bool hint_first = polled && ph.sync == SYNC_DATA_ATTN && wg >= attn_units;
         const bool spec = polled && !hint_first;
-        const int t = tid(), lane = t & 63, wave = t >> 6;
         if (p > 0) {
             if (!polled) stores_done(); // (a workgroup without a share of a data-synchronised phase cannot occur: the host checks)
             grid_arrive(P, epoch, sm);
@@ -933,49 +881,100 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
             lds_barrier(); // readers of the previous use are done
             if (lane < 16) sm.t->sq[wave][lane] = rs;
             lds_barrier();
-            if (t < 16) {
+            if (threadIdx.x < 16) {
                 float tot = 0.f;
 #pragma unroll
-                for (int w2 = 0; w2 < MNW; ++w2) tot += sm.t->sq[w2][t];
-                st_coh(&nsq_set(P, act_dst, G)[(size_t)t * G + wg], f2u(tot) == 0xffffffffu ? u2f(0xffc00000u) : tot); // the all-ones pattern is reserved
+                for (int w2 = 0; w2 < MNW; ++w2) tot += sm.t->sq[w2][threadIdx.x];
+                st_coh(&nsq_set(P, act_dst, G)[(size_t)threadIdx.x * G + wg], f2u(tot) == 0xffffffffu ? u2f(0xffc00000u) : tot); // the all-ones pattern is reserved
             }
         };
         int nstash = 0;
-        // One K slab of the B operand into LDS: all its loads in flight together (one memory round trip), straight into
-        // LDS; then, with data synchronisation, a look at what arrived and more loads for whatever is still missing.
-        // false: a bounded wait for the data ran out (every wave of the workgroup returns the same).
-        auto load_slab = [&](int slab, bool scales) __attribute__((always_inline)) {
-            bool ok = true;
-            ScaleLoads sl;
-            // Loads return to a wave in the order it issued them, so a slab requested now would come back behind the weight
-            // chunks in flight - late, and showing memory as it was when the request went out.  The wave lets its ring land
-            // first (those bytes are this phase's first rounds: the wait is streaming time, not idle time) and asks then.
+        const Range my = st.cc.r; // this workgroup's share of the phase
+        // One segment: n_fill rounds of RING steps in which each step refills its slot, then (last: the
+        // phase ends here) one round that does not.  The loops hold no global memory operation except
+        // the pinned ring loads, and nothing else is pending when they start (the wait below costs
+        // little: the ring loads it waits for are the ones the first steps need anyway); both are what
+        // lets the compiler wait for one slot with an exact count and leave the younger slots in flight.
+        auto run_segment = [&](int n_fill, bool last) {
+            auto step = [&](auto fill_c, u32x4(&slot)[2 * CH]) {
+                const Cursor c = st.cc;
+                cursor_next<T>(st.cc, P.hd);
+                if (!c.dummy) mma_chunk<T>(c, P, slot, st.acc0, st.acc1, sm);
+                if (decltype(fill_c)::value) fill(slot);
+                if (!c.dummy && c.ck + 1 == c.nck) finish_tile(c.tile, st.acc0, st.acc1, st.tile_seq, nstash, sm);
+            };
             stores_done();
-            lds_barrier(); // every wave is done with the previous slab (or with the attention area, which it aliases)
-            slab_issue<T>(P, ph, slab, G, scales, sl, sm);
-            stores_done();
-            if (P.timeline && t == 0 && scales) P.timeline[(size_t)(MEGA_TL_SLOTS * p + 1) * G + wg] = wall_clock64();
-            for (int pr0 = 0; pr0 < P.slab_rows; pr0 += slab_batch_rows(Traits<T>::PLANES)) { // batches of hidden rows
-                const bool sc = scales && pr0 == 0;
-                const uint32_t mask = slab_look<T>(P, ph, slab, pr0, true, sm); // units without data become zeros
-                if (P.timeline && t == 0 && scales && pr0 == 0) P.timeline[(size_t)(MEGA_TL_SLOTS * p + 5) * G + wg] = wall_clock64(); // first look done
-                if (polled && ok && __any(mask != 0u || (sc && scales_unset(P, G, sl))))
-                    ok = slab_retry<T>(P, ph, slab, pr0, G, sc, mask, sl, sm, (P.timeline && t == 0 && scales) ? &P.timeline[(size_t)(MEGA_TL_SLOTS * p + 6) * G + wg] : nullptr);
+            for (int i = 0; i < n_fill; ++i) {
+#pragma unroll
+                for (int sl = 0; sl < RING; ++sl) step(std::true_type{}, ring[sl]);
             }
-            if (scales) scales_finish(P, nsq_set(P, ph.act_src, G), G, sl, sm);
+            if (last) {
+#pragma unroll
+                for (int sl = 0; sl < RING; ++sl) step(std::false_type{}, ring[sl]);
+            }
+        };
+        // One K slab of the B operand into LDS, in batches of 10 (plane, row) pairs, one memory round trip
+        // each (5 rows of a bf16 model: one batch).
+        // false: a bounded wait for the data ran out (every wave of the workgroup returns the same).
+        auto load_slab = [&](int slab, bool scales, bool fills, SlabLoads<10> &L) __attribute__((always_inline)) {
+            bool ok = true;
+            slab_issue<T>(P, ph, slab, 0, G, scales, L);
+            asm volatile("" ::: "memory"); // keeps the compiler from fusing the two loops (load, wait, store per row)
+            // The first look at the data is straight-line code behind the loads (once per branch), so it
+            // waits for them with an exact count and leaves the younger weight prefetch in flight.
+            bool dirty;
+            if (fills) { // the weight prefetch goes out behind the slab: loads return in order, and the slab is needed first
+#pragma unroll
+                for (int sl = 0; sl < RING; ++sl) fill(ring[sl]);
+                dirty = polled && __any(slab_unset<T>(P, ph, slab, 0, G, scales, L));
+            } else {
+                dirty = polled && __any(slab_unset<T>(P, ph, slab, 0, G, scales, L));
+            }
+            if (dirty) ok = slab_retry<T>(P, ph, slab, 0, G, scales, L);
+            lds_barrier(); // every wave is done with the previous slab
+            slab_finish<T>(P, ph, slab, 0, G, scales, L, sm);
+            if (Traits<T>::PLANES * P.slab_rows > 10) {
+                slab_issue<T>(P, ph, slab, 10, G, false, L);
+                asm volatile("" ::: "memory");
+                if (polled && ok && __any(slab_unset<T>(P, ph, slab, 10, G, false, L))) ok = slab_retry<T>(P, ph, slab, 10, G, false, L);
+                slab_finish<T>(P, ph, slab, 10, G, false, L, sm);
+            }
             if (!ok && lane == 0) {
                 sm.t->ok = 0;
                 __hip_atomic_store(P.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            if (P.timeline && t == 0 && scales) P.timeline[(size_t)(MEGA_TL_SLOTS * p + 2) * G + wg] = wall_clock64();
+            if (P.timeline && threadIdx.x == 0 && st.cc.idx == 0) P.timeline[(size_t)(5 * p + 2) * G + wg] = wall_clock64();
             lds_barrier();
             return sm.t->ok != 0;
         };
+        const bool multi_slab = st.cc.nck > SLAB_CK;
         const bool clears = P.data_sync && ph.clear_phase >= 0;
-        es.rowsq = 0.f;
-        if (!work) {
-            // No GEMM work in this phase (embedding, attention, length update, or no share of a small GEMM): the ring
-            // keeps the chunks of the next GEMM phase, which arrive meanwhile.
+        st.es.rowsq = 0.f;
+        if (st.cc.active) {
+            // GEMM phase with work: the first slab is loaded (and, with data synchronisation, validated) in the loop below
+            epi_prefetch(P, ph, my, st.es);
+            // (spec: the ring is filled right behind the first slab's loads, see load_slab)
+            if (wave != 0 && !spec) { // wave 0 polls memory in a barrier, which would wait for these loads
+#pragma unroll
+                for (int sl = 0; sl < RING; ++sl) fill(ring[sl]);
+            }
+            if (p > 0 && !spec) {
+                if (hint_first ? !grid_wait(P, epoch, 0, min(attn_units, G), sm) : !grid_wait(P, epoch, 0, G, sm)) return;
+            }
+            if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(5 * p) * G + wg] = wall_clock64();
+            if (wave == 0 && !spec) {
+#pragma unroll
+                for (int sl = 0; sl < RING; ++sl) fill(ring[sl]);
+            }
+            if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(5 * p + 1) * G + wg] = wall_clock64();
+        } else {
+            // No GEMM work in this phase (embedding, attention, length update, or no share of a small
+            // GEMM): the weight ring is not used; giving it a constant value here tells the compiler
+            // that nothing of it lives across the attention code.
+#pragma unroll
+            for (int sl = 0; sl < RING; ++sl)
+#pragma unroll
+                for (int k = 0; k < 2 * CH; ++k) ring[sl][k] = zero16();
             if (p > 0) {
                 if (ph.kind == PH_ATTN && attn_units <= G) { // one unit per workgroup at most: wait for its producers only
                     if (wg < attn_units && !grid_wait_qkv_of_head(P, epoch, (wg / P.nsplit) % P.H, G, sm)) return;
@@ -986,196 +985,69 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
                     return;
                 }
             }
-            if (P.timeline && t == 0) P.timeline[(size_t)(MEGA_TL_SLOTS * p) * G + wg] = wall_clock64();
+            if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(5 * p) * G + wg] = wall_clock64();
             switch (ph.kind) {
             case PH_EMBED:
-                if (clears) clear_outputs<T>(P, load_phase(P.phases, uni(ph.clear_phase)), wg, G);
+                if (clears) clear_outputs<T>(P, P.phases[ph.clear_phase], wg, G);
                 publish_rowsq(do_embed<T>(P, ph, wg, G), ACT_A);
                 break;
-            case PH_ATTN: // (the ring stays live across it: the O projection's chunks arrive meanwhile)
+            case PH_ATTN:
                 do_attn<T>(P, ph, wg, G, sm);
+                st.slab_tag = -1; // the attention area aliases the slab
                 break;
             case PH_LEN:
-                if (wg == 0 && t < P.B) P.len[t] += P.M;
+                if (wg == 0 && (int)threadIdx.x < P.B) P.len[threadIdx.x] += P.M;
                 break;
             case PH_RESID: // no share of the new hidden rows: this workgroup's partial sums of squares are zero
-                if (t < 16) st_coh(&nsq_set(P, ph.act_dst, G)[(size_t)t * G + wg], 0.f);
+                if (threadIdx.x < 16) st_coh(&nsq_set(P, ph.act_dst, G)[(size_t)threadIdx.x * G + wg], 0.f);
                 break;
             default: break;
             }
-            if (P.timeline && t == 0) {
-                P.timeline[(size_t)(MEGA_TL_SLOTS * p + 1) * G + wg] = wall_clock64();
-                P.timeline[(size_t)(MEGA_TL_SLOTS * p + 4) * G + wg] = wall_clock64();
+            if (P.timeline && threadIdx.x == 0) {
+                P.timeline[(size_t)(5 * p + 1) * G + wg] = wall_clock64();
+                P.timeline[(size_t)(5 * p + 4) * G + wg] = wall_clock64();
             }
             continue;
         }
-        // GEMM phase with work: the first slab is loaded (and, with data synchronisation, validated) by its first segment
-        epi_prefetch(P, ph, my, es);
-        if (p > 0 && !spec) {
-            if (hint_first ? !grid_wait(P, epoch, 0, min(attn_units, G), sm) : !grid_wait(P, epoch, 0, G, sm)) return;
-        }
-        if (P.timeline && t == 0) P.timeline[(size_t)(MEGA_TL_SLOTS * p) * G + wg] = wall_clock64();
-        bool first_segment = true;
-        for (;;) {
-            // One segment: rounds that share an LDS slab and fit the stash.  Its loop holds no global memory operation
-            // except the pinned ring loads (the schedule is read with scalar loads), and nothing else is pending when
-            // it starts; both are what lets the compiler wait for one slot with an exact count and leave the younger
-            // slots in flight.
-            const uint32_t act0 = cur.w[RING];
-            if (uni((act0 & 0xffu) != ACT_NO_SLAB)) {
-                if (!load_slab((int)(act0 & 0xffu), want_scales && first_segment)) return; // first slab of the phase: with the row scales
+        while (st.cc.active) {
+            // one segment = rounds that share an LDS slab and fit the stash
+            const Cursor &cc = st.cc;
+            const bool multi = cc.nck > SLAB_CK;
+            const int grp_end = min((cc.ck / SLAB_CK + 1) * SLAB_CK, cc.nck); // multi: end of the slab group
+            const int grp_chunks = multi ? grp_end - cc.ck : (cc.r.ntiles - cc.tile) * cc.nck - cc.ck;
+            const int grp_rounds = (grp_chunks + RING - 1) / RING;
+            const bool last_group = multi ? (cc.tile + 1 == cc.r.ntiles && grp_end == cc.nck) : true;
+            // rounds the stash has room for: n rounds from chunk ck of a tile complete at most (ck + n*RING) / nck tiles
+            auto stash_room = [&]() { return multi ? STASH_TILES - nstash : ((STASH_TILES - nstash) * cc.nck - cc.ck) / RING; };
+            const int n = min(grp_rounds, stash_room()); // >= 1: the stash is flushed below whenever no round fits
+            const bool final_round = last_group && n == grp_rounds; // the phase ends with this segment
+            const int tag = (p << 8) | (cc.ck / SLAB_CK);
+            if (st.slab_tag != tag) {
+                SlabLoads<10> L;
+                if (!load_slab(cc.ck / SLAB_CK, want_scales && cc.idx == 0, spec && cc.idx == 0, L)) return; // first slab of the phase: with the row scales
+                st.slab_tag = tag;
                 // the whole input has been seen once the first tile's last slab is in; the resets are acknowledged before the rounds start
-                if (clears && (act0 & ACT_CLEAR)) clear_outputs<T>(P, load_phase(P.phases, uni(ph.clear_phase)), wg, G);
+                if (clears && cc.tile == 0 && (!multi || grp_end == cc.nck)) clear_outputs<T>(P, P.phases[ph.clear_phase], wg, G);
             }
-            first_segment = false;
-            stores_done();
-            uint32_t act;
-            do {
-                act = cur.w[RING];
-#pragma unroll
-                for (int sl = 0; sl < RING; ++sl) {
-                    const uint32_t code = cur.w[sl];
-                    const bool real = uni(!(code & POS_DUMMY));
-                    if (real) {
-                        if (uni((code & POS_FIRST) != 0)) {
-                            acc0 = f32x4{0.f, 0.f, 0.f, 0.f};
-                            acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
-                        }
-                        mma_chunk<T>((int)((code >> 20) & 7u), P, ring[sl], acc0, acc1, sm);
-                    }
-                    fill(ring[sl], nxt.w[sl]);
-                    if (uni(real && (code & POS_LAST))) finish_tile((int)((code >> 8) & 0xfffu), acc0, acc1, tile_seq, nstash, sm);
-                }
-                cur = nxt;
-                advance();
-            } while (uni(!(act & ACT_SEG_END)));
-            const bool phase_end = (act & ACT_PHASE_END) != 0;
-            if (P.timeline && t == 0 && phase_end) P.timeline[(size_t)(MEGA_TL_SLOTS * p + 3) * G + wg] = wall_clock64();
-            if (act & ACT_FLUSH) flush_stash<T>(P, ph, my, nstash, es, phase_end, sm);
-            if (phase_end) break;
+            run_segment(final_round ? n - 1 : n, final_round);
+            if (P.timeline && threadIdx.x == 0 && final_round) P.timeline[(size_t)(5 * p + 3) * G + wg] = wall_clock64();
+            if (final_round || stash_room() < 1) flush_stash<T>(P, ph, my, nstash, st.es, final_round, sm);
         }
-        if (ph.kind == PH_RESID) publish_rowsq(es.rowsq, ph.act_dst);
-        if (P.timeline && t == 0) P.timeline[(size_t)(MEGA_TL_SLOTS * p + 4) * G + wg] = wall_clock64();
+        if (ph.kind == PH_RESID) publish_rowsq(st.es.rowsq, ph.act_dst);
+        if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)(5 * p + 4) * G + wg] = wall_clock64();
     }
-}
-
-// ---------------------------------------------------------------- host: chunk schedules
-
-// The schedule of one GEMM phase shape for a share of `ntiles` tiles and `slab_ck` chunks per LDS slab (format: ss_mega.h).
-static void build_schedule(int K, int esz, int ntiles, int slab_ck, std::vector<uint32_t> &out) {
-    const int nck = (K * esz + CHUNK_ROW_BYTES - 1) / CHUNK_ROW_BYTES; // chunks per tile
-    const bool multi = nck > slab_ck; // K spans several LDS slabs: a tile's chunks come in slab groups
-    struct Pos {
-        uint32_t code;
-        int slab;       // K slab the position multiplies with
-        bool first_of_group;
-    };
-    std::vector<Pos> pos;
-    auto pad = [&]() {
-        while (pos.size() % RING) pos.push_back(Pos{POS_DUMMY, -1, false});
-    };
-    for (int tile = 0; tile < ntiles; ++tile)
-        for (int ck = 0; ck < nck; ++ck) {
-            const int slab = multi ? ck / slab_ck : 0, sck = multi ? ck % slab_ck : ck;
-            const bool group_start = multi ? sck == 0 : (tile == 0 && ck == 0);
-            if (group_start) pad(); // a slab group starts a round
-            uint32_t code = (uint32_t)ck | ((uint32_t)tile << 8) | ((uint32_t)sck << 20);
-            if (ck == 0) code |= POS_FIRST;
-            if (ck == nck - 1) code |= POS_LAST;
-            pos.push_back(Pos{code, slab, group_start});
-        }
-    pad();
-    const int nrounds = (int)pos.size() / RING;
-    std::vector<uint32_t> action(nrounds, ACT_NO_SLAB);
-    int nstash = 0;
-    for (int r = 0; r < nrounds; ++r) {
-        const Pos &p0 = pos[(size_t)r * RING];
-        int completes = 0;
-        bool last_slab_of_first_tile = false;
-        for (int sl = 0; sl < RING; ++sl) {
-            const Pos &q = pos[(size_t)r * RING + sl];
-            if (!(q.code & POS_DUMMY) && (q.code & POS_LAST)) ++completes;
-        }
-        if (p0.first_of_group) { // the round starts a slab group: the segment before it ends, the slab is loaded
-            if (r > 0) action[r - 1] |= ACT_SEG_END;
-            action[r] = (action[r] & ~0xffu) | (uint32_t)p0.slab;
-            const int tile = (int)((p0.code >> 8) & 0xfffu);
-            last_slab_of_first_tile = tile == 0 && (!multi || (p0.slab + 1) * slab_ck >= nck);
-            if (last_slab_of_first_tile) action[r] |= ACT_CLEAR; // from here on the whole input of the phase has been seen
-        }
-        if (nstash + completes > STASH_TILES) { // the stash cannot take this round's tiles: flush behind the previous round
-            action[r - 1] |= ACT_SEG_END | ACT_FLUSH;
-            nstash = 0;
-        }
-        nstash += completes;
-    }
-    action[nrounds - 1] |= ACT_SEG_END | ACT_FLUSH | ACT_PHASE_END;
-    for (int r = 0; r < nrounds; ++r) {
-        for (int sl = 0; sl < RING; ++sl) out.push_back(pos[(size_t)r * RING + sl].code);
-        out.push_back(action[r]);
-        for (int j = RING + 1; j < MEGA_ROW_WORDS; ++j) out.push_back(0u);
-    }
-}
-
-std::vector<uint32_t> mega_build_schedules(std::vector<MegaPhase> &prog, int grid, int dtype, int head_dim) {
-    (void)head_dim;
-    const int esz = dtype ? 2 : 4;
-    std::vector<uint32_t> table;
-    struct Key {
-        int kind, N, K;
-        int ntiles_lo, off[MEGA_MAX_SLAB_CK - MEGA_MIN_SLAB_CK + 1][2];
-    };
-    std::vector<Key> done;
-    for (MegaPhase &ph : prog) {
-        if (!is_gemm(ph.kind)) continue;
-        const Key *hit = nullptr;
-        for (const Key &k : done)
-            if (k.kind == ph.kind && k.N == ph.N && k.K == ph.K) hit = &k;
-        if (!hit) {
-            Key k{};
-            k.kind = ph.kind; k.N = ph.N; k.K = ph.K;
-            int lo = 1 << 30, hi = 0;
-            for (int wg = 0; wg < grid; ++wg) {
-                const int nt = phase_range(ph, wg, grid).ntiles;
-                if (nt > 0) lo = std::min(lo, nt);
-                hi = std::max(hi, nt);
-            }
-            if (hi == 0) lo = 1; // nobody has a share (cannot happen for N >= 1)
-            k.ntiles_lo = lo;
-            // shares differ by at most one unit, hence by at most one tile
-            for (int i = 0; i <= MEGA_MAX_SLAB_CK - MEGA_MIN_SLAB_CK; ++i)
-                for (int j = 0; j < 2; ++j) {
-                    k.off[i][j] = -1;
-                    if (lo + j > hi) continue;
-                    k.off[i][j] = (int)table.size();
-                    build_schedule(ph.K, esz, lo + j, MEGA_MIN_SLAB_CK + i, table);
-                }
-            done.push_back(k);
-            hit = &done.back();
-        }
-        ph.ntiles_lo = hit->ntiles_lo;
-        for (int i = 0; i <= MEGA_MAX_SLAB_CK - MEGA_MIN_SLAB_CK; ++i)
-            for (int j = 0; j < 2; ++j) ph.sched_off[i][j] = hit->off[i][j];
-    }
-    if (table.empty()) table.push_back(0u);
-    return table;
 }
 
 constexpr size_t LDS_BYTES = 160 * 1024;
 constexpr size_t ATTN_BYTES = sizeof(AttnSmem<128, MNW>);
 
-// chunks of K per LDS slab for a call of `rows` hidden rows (0: the rows do not fit) and the size of the slab / attention area
-static void smem_plan(int dtype, int rows, int &slab_ck, size_t &u_bytes) {
+// rows the LDS slab can hold (0: use the direct path) and the size of the slab / attention area
+static void smem_plan(int dtype, int rows, int &slab_rows, size_t &u_bytes) {
     const size_t planes = dtype ? 2 : 1;
     const size_t avail = LDS_BYTES - sizeof(MegaSmemTail) - 256;
-    slab_ck = 0;
-    for (int ck = MAX_SLAB_CK; ck >= 1; --ck) {
-        if ((size_t)rows * planes * slab_pitch(ck) <= avail && ck >= MEGA_MIN_SLAB_CK) { // (schedules exist for these sizes)
-            slab_ck = ck;
-            break;
-        }
-    }
-    u_bytes = std::max(ATTN_BYTES, (size_t)rows * planes * slab_pitch(std::max(slab_ck, 1)));
+    const int max_rows = (int)(avail / (planes * SLAB_PITCH));
+    slab_rows = rows <= max_rows ? rows : 0;
+    u_bytes = std::max(ATTN_BYTES, (size_t)slab_rows * planes * SLAB_PITCH);
     u_bytes = (u_bytes + 255) & ~(size_t)255;
 }
 
@@ -1190,11 +1062,11 @@ static hipError_t ensure_smem_attr(int dtype) {
 }
 
 int mega_max_rows(int dtype) {
-    int slab_ck = 0;
+    int slab_rows = 0;
     size_t u_bytes = 0;
     for (int rows = 16; rows >= 1; --rows) {
-        smem_plan(dtype, rows, slab_ck, u_bytes);
-        if (slab_ck > 0) return rows;
+        smem_plan(dtype, rows, slab_rows, u_bytes);
+        if (slab_rows == rows) return rows;
     }
     return 0;
 }
@@ -1214,9 +1086,8 @@ int mega_grid(int dtype, int device) {
 hipError_t launch_mega(const MegaCall &call, int grid, hipStream_t st) {
     MegaCall c = call;
     size_t u_bytes;
-    c.slab_rows = std::max(c.R, c.head_rows);
-    smem_plan(c.dtype, c.slab_rows, c.slab_ck, u_bytes);
-    if (c.slab_ck <= 0) return hipErrorInvalidValue; // the hidden rows must fit the LDS slab (mega_max_rows)
+    smem_plan(c.dtype, std::max(c.R, c.head_rows), c.slab_rows, u_bytes);
+    if (c.slab_rows <= 0) return hipErrorInvalidValue; // the hidden rows must fit the LDS slab (mega_max_rows)
     c.u_bytes = (int)u_bytes;
     void *args[] = {&c};
     const void *fn = call.dtype ? (const void *)verify_persistent_kernel<bf16_t> : (const void *)verify_persistent_kernel<float>;

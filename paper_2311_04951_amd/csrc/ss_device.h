@@ -35,15 +35,6 @@ template <> struct Traits<float> {
     static constexpr int PLANES = 1;
 };
 
-// The thread index through an opaque (volatile, empty) asm statement: values derived from it are not hoisted out of
-// enclosing loops.  For code that is inlined into the persistent kernel's loop over phases, where the compiler would
-// otherwise keep hundreds of thread-dependent addresses and predicates alive across the whole kernel and spill them.
-__device__ __forceinline__ int thread_index() {
-    int t = threadIdx.x;
-    asm volatile("" : "+v"(t));
-    return t;
-}
-
 __device__ __forceinline__ uint32_t f2u(float x) { return __builtin_bit_cast(uint32_t, x); }
 __device__ __forceinline__ float u2f(uint32_t x) { return __builtin_bit_cast(float, x); }
 

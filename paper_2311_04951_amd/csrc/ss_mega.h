@@ -4,7 +4,6 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
-#include <vector>
 
 namespace ss {
 
@@ -36,26 +35,6 @@ struct ActDesc {
     int ld;       // elements between rows
 };
 
-// ---- chunk schedule of a GEMM phase (built on the host, read by the kernel through scalar loads) -------------
-// A workgroup walks its share of a weight matrix in "chunks" (8 loads = 8 KB per wavefront) through a ring of
-// MEGA_RING register slots; one "round" = MEGA_RING consecutive positions, slot s of the ring always holds position
-// s of a round.  The schedule of a phase is a list of rounds of MEGA_ROW_WORDS 32-bit words:
-//   words 0 .. MEGA_RING-1: one position code each
-//       bits 0-7 chunk index inside the tile's K range, bits 8-19 tile index inside the workgroup's share,
-//       bits 20-22 chunk index inside the LDS activation slab, POS_DUMMY: padding (no data, no arithmetic),
-//       POS_FIRST / POS_LAST: first / last chunk of its tile (clear the accumulators / reduce and stash the tile)
-//   word MEGA_RING: what surrounds the round
-//       bits 0-7 K slab to load into LDS before the round (ACT_NO_SLAB: none), ACT_CLEAR: the resets of the phase's
-//       clear_phase follow that load, ACT_SEG_END: a segment (rounds without any other memory operation) ends behind
-//       the round, ACT_FLUSH: the stashed tiles' epilogues run behind it, ACT_PHASE_END: the phase is over.
-// Padding makes every slab group a whole number of rounds.  The schedule depends on the phase's shape, the chunks per
-// LDS slab of the call (MegaCall::slab_ck) and the number of tiles of the workgroup's share, nothing else.
-constexpr int MEGA_RING = 6;
-constexpr int MEGA_ROW_WORDS = 8;
-constexpr uint32_t POS_DUMMY = 1u << 23, POS_FIRST = 1u << 24, POS_LAST = 1u << 25;
-constexpr uint32_t ACT_NO_SLAB = 0xffu, ACT_SEG_END = 1u << 8, ACT_FLUSH = 1u << 9, ACT_PHASE_END = 1u << 10, ACT_CLEAR = 1u << 11;
-constexpr int MEGA_MIN_SLAB_CK = 4, MEGA_MAX_SLAB_CK = 6; // chunks of K per LDS slab a launch may choose from
-
 struct MegaPhase {
     int kind, layer;
     const void *W;     // weights of a GEMM phase, row-major [rows][K]
@@ -66,10 +45,6 @@ struct MegaPhase {
     int act_dst;       // EMBED / RESID: activation planes written (ACT_A or ACT_A1); the norm partials use the same parity
     int sync;          // PhaseSync, honoured when MegaCall::data_sync is set
     int clear_phase;   // index of the later phase whose outputs this phase resets to the "not written yet" pattern (-1: none)
-    // GEMM phases: word offsets into MegaCall::sched of the schedules for slab_ck = MEGA_MIN_SLAB_CK + i and a share of
-    // ntiles_lo + j tiles (-1: no such share)
-    int ntiles_lo;
-    int sched_off[MEGA_MAX_SLAB_CK - MEGA_MIN_SLAB_CK + 1][2];
 };
 
 struct MegaCall {
@@ -108,20 +83,15 @@ struct MegaCall {
     int32_t *status;
     int data_sync;     // 1: phases marked SYNC_DATA* poll their input data instead of waiting at a barrier
     const void *zeros; // >= 64 zero bytes: the target of weight loads that have no data to fetch
-    const uint32_t *sched; // chunk schedules of the GEMM phases (MegaPhase::sched_off)
-    int slab_rows, slab_ck, u_bytes; // set by launch_mega: rows held in the LDS slab, chunks of K per slab, size of the slab area
-    unsigned long long *timeline; // optional [MEGA_TL_SLOTS*n_phases][G] device clock samples of every workgroup (NULL: off)
+    int slab_rows, u_bytes;       // set by launch_mega: rows held in the LDS slab, size of the slab area
+    unsigned long long *timeline; // optional [5*n_phases][G] device clock samples of every workgroup (NULL: off)
 };
 
 constexpr int MEGA_THREADS = 256;
-constexpr int MEGA_TL_SLOTS = 8; // timeline samples per phase and workgroup
 
 // number of workgroups a launch may use (all resident at once), the largest number of hidden rows a
 // launch can take (they must fit the LDS activation slab), and the launch itself
 int mega_grid(int dtype, int device);
-// Builds the chunk schedules of every GEMM phase of `prog` for a grid of `grid` workgroups (fills ntiles_lo and
-// sched_off; phases of the same shape share their schedules) and returns the table to upload as MegaCall::sched.
-std::vector<uint32_t> mega_build_schedules(std::vector<MegaPhase> &prog, int grid, int dtype, int head_dim);
 int mega_max_rows(int dtype);
 hipError_t launch_mega(const MegaCall &call, int grid, hipStream_t st);
 
