@@ -23,7 +23,19 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK = 8.0e12  # B/s, MI355X published peak
-PERSISTENT_7B_TRAFFIC_BYTES = 13.608e9  # 13.472 GB fetched + 0.136 GB written per launch (rocprofv3 --pmc, see profiles/)
+# HBM bytes per launch of the persistent kernel on the default workload: a stored measurement (two rocprofv3 --pmc runs,
+# FETCH_SIZE then WRITE_SIZE, each scaled by what the counter reads for a plain 1 GiB device copy), valid for the kernel
+# source it was taken on; bench.py reports it only on that workload and names the file it comes from
+PERSISTENT_7B_TRAFFIC_BYTES = 13.608e9  # 13.472 GB fetched + 0.136 GB written
+PERSISTENT_7B_TRAFFIC_SOURCE = "profiles/verify_pass_7b_persistent_hbm_traffic.txt"
+
+
+def check_status(sv, *models):
+    """No timing below counts unless the kernels flagged nothing (a clamped token id, a bounded wait that gave up)."""
+    for m in models:
+        st = sv.ss_device_status(m)
+        if st:
+            raise RuntimeError(f"device status {st} after a timed loop (bit 0: token id clamped, bit 1: a wait of the persistent kernel gave up)")
 
 
 def layer_bytes(shape):
@@ -41,46 +53,85 @@ def verify_pass_bytes(shape, L, M):
     return shape.n_layers * layer_bytes(shape) + head + kv_read + kv_write + M * shape.vocab * 4
 
 
-def cpu_baseline(si, torch, shape, packed, io, prompt_len, M, seconds_target=15.0):
-    """The oracle, as it stands, on a bounded sample: the first n layers + LM head of one M-row
-    verify pass against a synthetic context of prompt_len rows; extrapolated by weight bytes."""
+def cpu_baseline(si, torch, shape, packed, io, prompt_len, M, seconds_target=10.0):
+    """The oracle, as it stands, on bounded samples of the workloads (about 25 s of host time in all):
+    whole M-row verify passes of the named model on every host thread (the reported value), the same pass on
+    one thread (first layers + LM head, extrapolated by weight bytes), one layer of the single-layer
+    workload, and a slice of the stand-alone accept workload."""
     import numpy as np
     import oracle
     d, W = shape.d_model, shape.n_heads * shape.head_dim
+    threads = oracle.num_threads()
 
-    def unpack(p):
-        return {"wq": p["wqkv"][:W].cpu(), "wk": p["wqkv"][W:2 * W].cpu(), "wv": p["wqkv"][2 * W:].cpu(),
-                "wo": p["wo"].cpu(), "wg": p["wgu"][:shape.d_ff].cpu(), "wu": p["wgu"][shape.d_ff:].cpu(),
-                "wd": p["wd"].cpu(), "g1": p["g1"].cpu(), "g2": p["g2"].cpu()}
-
-    def run(n_layers):
+    def model(n_layers):
         s = si.DecoderShape(**{**shape.as_dict(), "n_layers": n_layers})
         w = {"embed": io["embed"].cpu(), "gf": io["gf"].cpu(), "lm_head": io["lm_head"].cpu(),
-             "layers": [unpack(packed[l]) for l in range(n_layers)]}
-        om = oracle.Model(s, w)
-        kv = om.new_kv(prompt_len + M + 1)
-        kv.append_raw(si.kv_context(s, 1, "cpu_ctx", prompt_len))
+             "layers": si.unpack_layers(shape, packed[:n_layers])}
+        return s, oracle.Model(s, w)
+
+    def run(n_layers, ctx=prompt_len):
+        s, om = model(n_layers)
+        kv = om.new_kv(ctx + M + 1)
+        kv.append_raw(si.kv_context(s, 1, "cpu_ctx", ctx))
         toks = si.token_ids(1, "cpu_toks", (M,), s.vocab).numpy()
         t0 = time.perf_counter()
         om.forward(kv, toks)
         return time.perf_counter() - t0
 
-    t1 = run(1)
     head_b = shape.vocab * d * 2
-    n = int(max(1, min(shape.n_layers, round(seconds_target / max(t1, 1e-3)))))
-    if n < shape.n_layers:
-        t = run(n) if n > 1 else t1
-        frac = (n * layer_bytes(shape) + head_b) / (shape.n_layers * layer_bytes(shape) + head_b)
-        return {"value": M / (t / frac), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
-                "sample": f"first {n} of {shape.n_layers} layers + LM head of one {M}-row verify pass against "
-                          f"{prompt_len} cached positions ({t:.1f} s), extrapolated by weight bytes to the full pass"}
-    # the host is fast enough for whole passes: repeat the full pass until about seconds_target is spent
-    t_one = run(shape.n_layers)
-    reps = int(max(1, min(20, round(seconds_target / max(t_one, 1e-3)))))
-    t_tot = t_one + sum(run(shape.n_layers) for _ in range(reps - 1))
-    return {"value": M * reps / t_tot, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"{reps} full {M}-row verify passes (all {shape.n_layers} layers + LM head) against {prompt_len} "
-                      f"cached positions, {t_tot:.1f} s in total"}
+    full_b = shape.n_layers * layer_bytes(shape) + head_b
+
+    def sampled(seconds, what):
+        """tokens/s of the full pass from a sample that takes about `seconds`"""
+        t1 = run(1)
+        n = int(max(1, min(shape.n_layers, round(seconds / max(t1, 1e-3)))))
+        if n < shape.n_layers:
+            t = run(n) if n > 1 else t1
+            frac = (n * layer_bytes(shape) + head_b) / full_b
+            return M / (t / frac), (f"first {n} of {shape.n_layers} layers + LM head of one {M}-row verify pass against {prompt_len} cached "
+                                    f"positions ({t:.1f} s {what}), extrapolated by weight bytes to the full pass")
+        t_one = run(shape.n_layers)
+        reps = int(max(1, min(20, round(seconds / max(t_one, 1e-3)))))
+        t_tot = t_one + sum(run(shape.n_layers) for _ in range(reps - 1))
+        return M * reps / t_tot, (f"{reps} full {M}-row verify passes (all {shape.n_layers} layers + LM head) against {prompt_len} cached "
+                                  f"positions, {t_tot:.1f} s {what}")
+
+    value, sample = sampled(seconds_target, f"on {threads} threads")
+    out = {"value": value, "unit": "tokens/s", "cores": threads, "kind": "oracle", "sample": sample}
+    oracle.set_num_threads(1)
+    try:
+        v1, s1 = sampled(5.0, "on 1 thread")
+    finally:
+        oracle.set_num_threads(threads)
+    out["single_thread"] = {"value": v1, "unit": "tokens/s", "cores": 1, "sample": s1}
+    # the single-layer workload: one layer, M rows against 1024 cached positions (layers_forward: no embedding, no head)
+    s1l, om = model(1)
+    kv = om.new_kv(1024 + M + 1)
+    kv.append_raw(si.kv_context(s1l, 1, "cpu_ctx1024", 1024))
+    h = si.normal(7, "cpu_lp_h", (M, d), 1.0).numpy()
+    reps, t0 = 0, time.perf_counter()
+    while reps < 3 or (time.perf_counter() - t0 < 2.0 and reps < 50):
+        kv.set_len(1024)
+        om.layers_forward(kv, h)
+        reps += 1
+    t_layer = (time.perf_counter() - t0) / reps
+    out["layer_pass"] = {"us_per_layer": t_layer * 1e6, "cores": threads,
+                         "sample": f"{reps} passes of one 7B-shaped layer, {M} rows against 1024 cached positions"}
+    # the stand-alone accept workload, a slice of its batch: softmax of every row at the temperature, then the rejection step
+    Bs, K, V, T = 4, 8, 128256, 0.8
+    pl, ql, u, ud = si.accept_workload(41, Bs, K, V)
+    t0 = time.perf_counter()
+    p = oracle.softmax(pl.numpy(), T)
+    q = oracle.softmax(ql.numpy(), T)
+    dtok = np.array([[oracle.sample(q[b, i], float(ud[b, i])) for i in range(K)] for b in range(Bs)], dtype=np.int32)
+    t_q = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    oracle.speculative_accept(p, q, dtok, u.numpy())
+    t_acc = time.perf_counter() - t0
+    out["standalone_accept"] = {"us_per_sequence": (t_q + t_acc) / Bs * 1e6, "cores": threads,
+                                "sample": f"{Bs} of the workload's 64 sequences (K {K}, vocab {V}): softmax of the {2 * K + 1} rows per sequence, "
+                                          f"the draft's samples and the rejection step; {t_q + t_acc:.1f} s"}
+    return out
 
 
 def standalone_accept(si, sv, torch, dev, iters=40):
@@ -280,8 +331,11 @@ def batched_workload(si, sv, torch, dev, shape, packed, io, iters=5, B=8, L=4096
     torch.cuda.synchronize()
     prof = sv.ss_profile_read(m)
     nbytes = shape.n_layers * layer_bytes(shape) + shape.vocab * shape.d_model * 2 + shape.n_layers * B * 2 * (L + M) * W * 2
-    out = {"workload": f"batch {B}, context {L}, K {M - 1} ({B * M} rows per pass), {shape.n_layers} layers", "ms_per_pass": dt * 1e3,
+    check_status(sv, m)
+    out = {"workload": f"batch {B}, context {L}, K {M - 1} ({B * M} rows per pass), {shape.n_layers} layers, one launch per phase", "ms_per_pass": dt * 1e3,
            "rows_per_s": B * M / dt, "algorithmic_bytes": nbytes, "GBps": nbytes / dt / 1e9, "frac_of_hbm_peak": nbytes / dt / HBM_PEAK,
+           "roofline": {"bound": "hbm", "achieved": nbytes / dt / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": nbytes / dt / HBM_PEAK,
+                        "traffic": None, "note": "whole pass (weights once, every sequence's KV context once) over its host-timed duration"},
            "class_ms_per_pass": {k: round(ms / 3, 3) for k, (ms, n) in prof.items() if n}}
     m.close()
     if int8:
@@ -300,6 +354,7 @@ def batched_workload(si, sv, torch, dev, shape, packed, io, iters=5, B=8, L=4096
             run()
         torch.cuda.synchronize()
         prof = sv.ss_profile_read(m)
+        check_status(sv, m)
         nb8 = nbytes - (shape.n_layers * layer_bytes(shape) + shape.vocab * shape.d_model * 2) // 2
         out["int8_weights"] = {"ms_per_pass": dt8 * 1e3, "rows_per_s": B * M / dt8, "algorithmic_bytes": nb8, "GBps": nb8 / dt8 / 1e9,
                                "frac_of_hbm_peak": nb8 / dt8 / HBM_PEAK,
@@ -325,8 +380,8 @@ def main():
     ap.add_argument("--no-int8-leg", action="store_true", help="skip the weight-only int8 and int4 legs")
     ap.add_argument("--no-paper-pair", action="store_true", help="skip the 13B/3B-shaped target/draft pair (the paper's size ratio)")
     ap.add_argument("--no-layer-pass", action="store_true", help="skip the one-layer leg (5 rows, 1024 cached positions)")
-    ap.add_argument("--batched-workload", action="store_true",
-                    help="also time the batched long-context workload (8 x 4096 positions, 72 rows; needs 20 GB more)")
+    ap.add_argument("--no-batched-workload", action="store_true",
+                    help="skip the batched long-context workload (8 x 4096 positions, 72 rows per pass; 20 GB more)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of 1 GiB five times (a kernel of known traffic, for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -434,6 +489,7 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     L_end = int(sv.ss_kv_cache_get_len(tkv)[0])
+    check_status(sv, target, draft)
     ms_per_step = 1e3 * dt / args.steps
     value = M * args.steps / dt
     L_mean = 0.5 * (L_start + L_end)
@@ -446,6 +502,7 @@ def main():
     torch.cuda.synchronize()
     prof = sv.ss_profile_read(target)
     sv.ss_profile_enable(target, False)
+    check_status(sv, target)
     classes = {k: {"avg_us": 1e3 * ms / max(1, n), "launches_per_step": n / args.steps} for k, (ms, n) in prof.items() if n}
     if "verify_persistent" in classes:
         # the whole forward of a verify pass is one launch of the persistent kernel
@@ -464,8 +521,9 @@ def main():
     # it is a measurement of the default workload only
     traffic = PERSISTENT_7B_TRAFFIC_BYTES if ("verify_persistent" in classes and args.layers == 32 and K == 4) else None
     roofline = {"bound": "hbm", "kernel": k_name, "achieved": achieved, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                "frac": achieved / (HBM_PEAK / 1e9), "traffic": traffic, "algorithmic_bytes_per_launch": k_bytes,
-                "avg_launch_us": k_us}
+                "frac": achieved / (HBM_PEAK / 1e9), "traffic": traffic,
+                "traffic_source": (PERSISTENT_7B_TRAFFIC_SOURCE + " (stored counter measurement of this workload, not taken in this run)") if traffic else None,
+                "algorithmic_bytes_per_launch": k_bytes, "avg_launch_us": k_us}
     # what a dependency-free read kernel reaches on this machine over a 2 GiB buffer (beyond the last-level cache):
     # the practical ceiling beside the nominal peak
     probe_buf = torch.empty(1 << 29, dtype=torch.float32, device=dev).fill_(1.0)
@@ -473,6 +531,29 @@ def main():
     del probe_buf
     roofline["read_stream_GBps"] = stream_GBps
     roofline["frac_of_read_stream"] = achieved / stream_GBps
+
+    # The paper's premise (Section 2): the pass is memory-bound, so K + 1 rows cost about what one row costs.  The
+    # forward alone, same cache length, M rows against one row.
+    def forward_ms(rows, iters=20):
+        Lp = int(sv.ss_kv_cache_get_len(tkv)[0])
+        t_in = vt[:, :rows].contiguous()
+        lg = logits[:, :rows]
+        ts = []
+        for it in range(iters + 2):
+            sv.ss_kv_cache_set_len(tkv, [Lp])
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            sv.ss_verify_forward(target, tkv, t_in, rows, lg.contiguous() if rows != M else logits)
+            torch.cuda.synchronize()
+            if it >= 2:
+                ts.append(time.perf_counter() - t1)
+        sv.ss_kv_cache_set_len(tkv, [Lp])
+        ts.sort()
+        return 1e3 * ts[len(ts) // 2]
+    t_m, t_1 = forward_ms(M), forward_ms(1)
+    check_status(sv, target)
+    premise = {"t_verify_ms_rows_K_plus_1": t_m, "t_verify_ms_rows_1": t_1, "premise_ratio": t_m / t_1,
+               "note": f"host-timed ss_verify_forward alone, {M} rows against 1 row, same cache length; 1.0 = K draft tokens verified for the price of one"}
 
     out = {
         "metric": "verify-pass tokens/s", "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -485,6 +566,7 @@ def main():
         "verify_pass": {"algorithmic_bytes": pass_bytes, "hbm_frac_of_peak": pass_bytes / (dt / args.steps) / HBM_PEAK,
                         "hbm_GBps": pass_bytes / (dt / args.steps) / 1e9, "kernel_classes": classes},
         "roofline": roofline,
+        "premise": premise,
         "end_to_end": e2e,
     }
     if not args.no_layer_pass:
@@ -496,7 +578,7 @@ def main():
         out["int4_weights"] = int8_weights_leg(si, sv, torch, gen, dev, target, bool(args.persistent), shape, packed, io, prompt, K, args.steps, bits=4)
     if not args.no_paper_pair:
         out["paper_size_pair"] = paper_pair_leg(si, sv, torch, gen, dev)
-    if args.batched_workload:
+    if not args.no_batched_workload and args.layers == 32:
         out["batched_workload"] = batched_workload(si, sv, torch, dev, shape, packed, io, int8=not args.no_int8_leg)
     for leg in ("layer_pass", "standalone_accept", "batched_workload", "int8_weights", "int4_weights"):
         if leg in out and "GBps" in out[leg]:
@@ -510,11 +592,13 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    check_status(sv, target, draft)
     print(json.dumps(out), flush=True)
-    # release the device objects while the HIP runtime is still up (not at interpreter teardown)
+    # release every device object and the library's own state while the HIP runtime is still up (not at interpreter teardown)
     torch.cuda.synchronize()
     for obj in (tkv, dkv, target, draft):
         obj.close()
+    sv.ss_shutdown()
 
 
 if __name__ == "__main__":

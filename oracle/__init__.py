@@ -38,6 +38,7 @@ def lib():
         L.orc_model_set_layer.argtypes = [vp, i32] + [vp] * 9
         L.orc_model_set_io.argtypes = [vp, vp, vp, vp]
         L.orc_model_free.argtypes = [vp]
+        L.orc_set_num_threads.argtypes = [i32]
         L.orc_kv_new.restype = vp
         L.orc_kv_new.argtypes = [vp, i32]
         L.orc_kv_free.argtypes = [vp]
@@ -76,6 +77,11 @@ def lib():
 
 def num_threads() -> int:
     return lib().orc_num_threads()
+
+
+def set_num_threads(n: int) -> None:
+    """Threads the row loops use from now on (for timing on one core; results do not depend on it)."""
+    lib().orc_set_num_threads(int(n))
 
 
 def _p(a: np.ndarray):

@@ -78,6 +78,15 @@ int orc_num_threads(void) {
     return 1;
 #endif
 }
+/* How many threads the row loops may use from now on (timing on one core; no result depends on it: every output
+ * row is computed by one thread, in the same order). */
+void orc_set_num_threads(int n) {
+#ifdef _OPENMP
+    omp_set_num_threads(n < 1 ? 1 : n);
+#else
+    (void)n;
+#endif
+}
 
 /* ------------------------------------------------------------------ decoder pieces */
 
