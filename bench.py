@@ -26,8 +26,13 @@ HBM_PEAK = 8.0e12  # B/s, MI355X published peak
 # HBM bytes per launch of the persistent kernel on the default workload: a stored measurement (two rocprofv3 --pmc runs,
 # FETCH_SIZE then WRITE_SIZE, each scaled by what the counter reads for a plain 1 GiB device copy), valid for the kernel
 # source it was taken on; bench.py reports it only on that workload and names the file it comes from
-PERSISTENT_7B_TRAFFIC_BYTES = 13.608e9  # 13.472 GB fetched + 0.136 GB written
+PERSISTENT_7B_TRAFFIC_BYTES = 13.609e9  # 13.472 GB fetched + 0.136 GB written
 PERSISTENT_7B_TRAFFIC_SOURCE = "profiles/verify_pass_7b_persistent_hbm_traffic.txt"
+# the same kind of stored measurement for the stand-alone accept workload (the kernels stop reading a sequence's rows at
+# its first rejection, so they fetch less than "every logit once") and for the batched long-context pass
+ACCEPT_TRAFFIC_BYTES, ACCEPT_TRAFFIC_SOURCE = 366.5e6, "profiles/standalone_accept_hbm_traffic.txt"
+BATCHED_TRAFFIC_BYTES, BATCHED_TRAFFIC_SOURCE = 38.686e9, "profiles/batched_long_context_pass_hbm_traffic.txt"
+STORED = " (stored counter measurement of this workload, not taken in this run)"
 
 
 def check_status(sv, *models):
@@ -167,7 +172,9 @@ def standalone_accept(si, sv, torch, dev, iters=40):
     nbytes = (2 * K + 1) * B * V * 4
     return {"workload": f"batch {B}, K {K}, vocab {V}, fp32 logits, temperature {T}", "us_per_call": dt * 1e6,
             "algorithmic_bytes": nbytes, "GBps": nbytes / dt / 1e9, "frac_of_hbm_peak": nbytes / dt / HBM_PEAK,
-            "mean_accepted": float(na.float().mean())}
+            "algorithmic_bytes_note": "every logit of p and q once; the kernels read a sequence's rows only up to its first rejection",
+            "traffic": ACCEPT_TRAFFIC_BYTES, "traffic_source": ACCEPT_TRAFFIC_SOURCE + STORED,
+            "traffic_GBps": ACCEPT_TRAFFIC_BYTES / dt / 1e9, "mean_accepted": float(na.float().mean())}
 
 
 def layer_pass(si, sv, torch, dev, target, shape, iters=20, L=1024, M=5):
@@ -335,7 +342,9 @@ def batched_workload(si, sv, torch, dev, shape, packed, io, iters=5, B=8, L=4096
     out = {"workload": f"batch {B}, context {L}, K {M - 1} ({B * M} rows per pass), {shape.n_layers} layers, one launch per phase", "ms_per_pass": dt * 1e3,
            "rows_per_s": B * M / dt, "algorithmic_bytes": nbytes, "GBps": nbytes / dt / 1e9, "frac_of_hbm_peak": nbytes / dt / HBM_PEAK,
            "roofline": {"bound": "hbm", "achieved": nbytes / dt / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": nbytes / dt / HBM_PEAK,
-                        "traffic": None, "note": "whole pass (weights once, every sequence's KV context once) over its host-timed duration"},
+                        "traffic": BATCHED_TRAFFIC_BYTES if (shape.n_layers == 32 and B == 8 and L == 4096 and M == 9) else None,
+                        "traffic_source": BATCHED_TRAFFIC_SOURCE + STORED,
+                        "note": "whole pass (weights once, every sequence's KV context once) over its host-timed duration"},
            "class_ms_per_pass": {k: round(ms / 3, 3) for k, (ms, n) in prof.items() if n}}
     m.close()
     if int8:
@@ -522,7 +531,7 @@ def main():
     traffic = PERSISTENT_7B_TRAFFIC_BYTES if ("verify_persistent" in classes and args.layers == 32 and K == 4) else None
     roofline = {"bound": "hbm", "kernel": k_name, "achieved": achieved, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                 "frac": achieved / (HBM_PEAK / 1e9), "traffic": traffic,
-                "traffic_source": (PERSISTENT_7B_TRAFFIC_SOURCE + " (stored counter measurement of this workload, not taken in this run)") if traffic else None,
+                "traffic_source": (PERSISTENT_7B_TRAFFIC_SOURCE + STORED) if traffic else None,
                 "algorithmic_bytes_per_launch": k_bytes, "avg_launch_us": k_us}
     # what a dependency-free read kernel reaches on this machine over a 2 GiB buffer (beyond the last-level cache):
     # the practical ceiling beside the nominal peak
