@@ -67,6 +67,7 @@ def lib():
         L.orc_linear_w4.argtypes = [vp, vp, vp, i32, i32, i32, vp]
         L.orc_model_set_wbits.argtypes = [vp, i32]
         L.orc_top_p_filter.argtypes = [vp, i32, f32, vp]
+        L.orc_top_k_filter.argtypes = [vp, i32, i32, vp]
         L.orc_f32_to_bf16.restype = C.c_uint16
         L.orc_f32_to_bf16.argtypes = [f32]
         L.orc_bf16_to_f32.restype = f32
@@ -212,6 +213,24 @@ def top_p_filter(p, top_p):
     return out.reshape(p.shape)
 
 
+def top_k_filter(p, top_k):
+    """Rows of probabilities [..., V] -> the rows restricted to their top_k most probable tokens (ties: lowest
+    index first) and renormalised (top_k >= V or top_k < 1: returned unchanged)."""
+    p = _f32(p)
+    flat = p.reshape(-1, p.shape[-1])
+    out = np.empty_like(flat)
+    for r in range(flat.shape[0]):
+        lib().orc_top_k_filter(_p(flat[r]), flat.shape[1], int(top_k), _p(out[r]))
+    return out.reshape(p.shape)
+
+
+def select(p, top_k=0, top_p=1.0):
+    """The selection rules in the order they apply: top-k (top_k >= 1), then top-p (top_p < 1)."""
+    if top_k and top_k >= 1:
+        p = top_k_filter(p, top_k)
+    return top_p_filter(p, top_p)
+
+
 def speculative_accept(p, q, draft, u):
     """p [B,K+1,V], q [B,K,V] probabilities, draft [B,K] int32, u [B,K+1] -> (n_accepted[B], next[B])."""
     p, q, u = _f32(p), _f32(q), _f32(u)
@@ -354,10 +373,10 @@ class KVCache:
 # ------------------------------------------------------------------ host loops
 
 def autoregressive_generate(target: Model, prompt, n_new: int, temperature: float, u=None,
-                            max_seq=None, top_p=1.0):
+                            max_seq=None, top_p=1.0, top_k=0):
     """Section 3, Eq. (1) with a KV cache (Section 4.2).  temperature == 0 selects argmax;
-    otherwise token ~ softmax(logits / T), restricted to its top-p nucleus when top_p < 1, by the
-    integer inverse CDF with uniforms u[n_new]."""
+    otherwise token ~ softmax(logits / T), restricted to its top_k most probable tokens when top_k >= 1 and
+    then to its top-p nucleus when top_p < 1, by the integer inverse CDF with uniforms u[n_new]."""
     x = [int(t) for t in prompt]
     kv = target.new_kv(max_seq or (len(x) + n_new + 1))
     logits = target.forward(kv, x)[-1]
@@ -366,7 +385,7 @@ def autoregressive_generate(target: Model, prompt, n_new: int, temperature: floa
         if temperature == 0:
             t = argmax(logits)
         else:
-            t = sample(top_p_filter(softmax(logits, temperature), top_p), u[i])
+            t = sample(select(softmax(logits, temperature), top_k, top_p), u[i])
         out.append(t)
         if i + 1 < n_new:
             logits = target.forward(kv, [t])[-1]
@@ -374,7 +393,7 @@ def autoregressive_generate(target: Model, prompt, n_new: int, temperature: floa
 
 
 def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int,
-                         temperature: float, u_draft=None, u_accept=None, max_seq=None, shared_kv=False, top_p=1.0):
+                         temperature: float, u_draft=None, u_accept=None, max_seq=None, shared_kv=False, top_p=1.0, top_k=0):
     """Speculative sampling with two KV caches (Sections 3, 4.3, 4.4).
 
     shared_kv (the other answer to Section 4.4's "do we have two separate caches?", for a draft made of
@@ -387,8 +406,8 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
     Draft phase: K one-token draft calls (after a fully accepted step the first call feeds the two
     tokens the draft cache is missing).  Verify: one target call over [x_n, d_1..d_K].  Accept:
     the modified rejection rule.  Fix-up: both caches are truncated to n + a positions.
-    top_p < 1: the draft's and the target's rows are both restricted to their top-p nucleus before
-    anything is sampled or compared, so the run emits the filtered target distribution.
+    top_k >= 1 / top_p < 1: the draft's and the target's rows are both restricted (top-k first, then top-p)
+    before anything is sampled or compared, so the run emits the filtered target distribution.
     u_draft [steps, K], u_accept [steps, K+1].  Returns (tokens[n_new], stats dict)."""
     x = [int(t) for t in prompt]
     n0 = len(x)
@@ -413,7 +432,7 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
             if greedy:
                 tok = argmax(ql)
             else:
-                q_rows[i] = top_p_filter(softmax(ql, temperature), top_p)
+                q_rows[i] = select(softmax(ql, temperature), top_k, top_p)
                 tok = sample(q_rows[i], u_draft[step][i])
             d.append(tok)
             feed = [tok]
@@ -423,7 +442,7 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
         if greedy:
             na, nx = greedy_accept(pl[None], np.asarray([d], dtype=np.int32))
         else:
-            p_rows = top_p_filter(softmax(pl, temperature), top_p)
+            p_rows = select(softmax(pl, temperature), top_k, top_p)
             na, nx = speculative_accept(p_rows[None], q_rows[None], np.asarray([d], dtype=np.int32),
                                         np.asarray([u_accept[step]], dtype=np.float32))
         a, y = int(na[0]), int(nx[0])

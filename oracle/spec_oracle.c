@@ -564,6 +564,38 @@ int orc_top_p_filter(const float *p, int V, float top_p, float *out) {
     return kept;
 }
 
+/* Top-k selection (Section 3 lists it with top-p among the usual token selection rules): keep the k most probable
+ * tokens, renormalise.  Same arithmetic as top-p: weights w_v as above, tokens ordered by (w descending, index
+ * ascending), kept = the first k of that order (k >= V: the row is returned unchanged, like top_p >= 1);
+ * S' = sum of the kept weights (S' = 0: the row is returned unchanged), Z' = fl32(S') * 2^-32,
+ * out_v = fl32(p_v / Z') for kept v, else 0.  With both rules in force top-k is applied first and top-p works on its
+ * output.  Returns the number of tokens kept. */
+int orc_top_k_filter(const float *p, int V, int k, float *out) {
+    if (k >= V || k < 1) {
+        for (int v = 0; v < V; ++v) out[v] = p[v];
+        return V;
+    }
+    orc_wv *o = (orc_wv *)malloc(sizeof(orc_wv) * (size_t)V);
+    for (int v = 0; v < V; ++v) { o[v].w = fx_weight32(p[v]); o[v].v = v; }
+    qsort(o, (size_t)V, sizeof(orc_wv), cmp_wv);
+    uint64_t C = 0;
+    for (int i = 0; i < k; ++i) C += o[i].w;
+    if (C == 0) {
+        for (int v = 0; v < V; ++v) out[v] = p[v];
+        free(o);
+        return V;
+    }
+    volatile float zs = (float)C;           /* uint64 -> fp32, round to nearest even */
+    float Z = zs * 2.3283064365386963e-10f; /* * 2^-32, exact */
+    for (int v = 0; v < V; ++v) out[v] = 0.0f;
+    for (int i = 0; i < k; ++i) {
+        volatile float r = p[o[i].v] / Z;
+        out[o[i].v] = r;
+    }
+    free(o);
+    return k;
+}
+
 /* The modified rejection step (Sections 3, 4.3) for a batch of sequences.
  * p [B][K+1][V], q [B][K][V] probabilities; draft [B][K]; u [B][K+1]: u[b][i<K] decides draft
  * token i, u[b][K] drives the one sampling that happens (residual resample or bonus).
