@@ -281,9 +281,11 @@ int ss_decoder_layers_forward(ss_model *model, ss_kv_cache *kv, float *h_dev, in
  * top_p < 1 (temperature > 0 only): q is restricted to its top-p nucleus and renormalised before
  * the token is drawn (see ss_top_p_filter), and that filtered row is what q_rows_dev receives;
  * top_p >= 1: no filtering; top_p <= 0: SS_EINVAL.
+ * top_k >= 1 (temperature > 0 only): q is first restricted to its top_k most probable tokens (see
+ * ss_top_k_filter), top-p then works on that row; top_k == 0 or >= vocab: no filtering; < 0: SS_EINVAL.
  * token_out_dev int32 [batch].  Calling it on the target model is an autoregressive decode step. */
 int ss_draft_step(ss_model *draft, ss_kv_cache *draft_kv, const int32_t *tokens_dev, int32_t batch,
-                  int32_t m, float temperature, float top_p, const float *u_dev, float *q_rows_dev,
+                  int32_t m, float temperature, float top_p, int32_t top_k, const float *u_dev, float *q_rows_dev,
                   int64_t ldq, int32_t *token_out_dev, ss_stream stream);
 
 /* ---- top-p ("nucleus") selection (Section 3 names sampling from the top-p set beside argmax) --------
@@ -300,6 +302,16 @@ int ss_draft_step(ss_model *draft, ss_kv_cache *draft_kv, const int32_t *tokens_
  * filtered target distribution.  out_dev may be probs_dev (in place).  top_p >= 1 copies the rows
  * unchanged; top_p <= 0 is SS_EINVAL. */
 int ss_top_p_filter(const float *probs_dev, int32_t rows, int32_t vocab, float top_p, float *out_dev,
+                    ss_stream stream);
+
+/* ---- top-k selection (Section 3 lists top-k with top-p among the usual selection rules) ------------
+ * Every row of probs_dev fp32 [rows][vocab] is restricted to its top_k most probable tokens and
+ * renormalised, in the arithmetic of ss_top_p_filter: weights w_v as there; kept = the first top_k tokens
+ * in the order (w descending, index ascending); S' = the sum of their weights (S' = 0: the row is
+ * returned unchanged); Z' = fl32(S') * 2^-32; out_v = fl32(p_v / Z') for kept v, 0 otherwise.
+ * Where both rules are in force (ss_draft_step, ss_speculative_step) top-k is applied first.
+ * out_dev may be probs_dev.  top_k >= vocab copies the rows unchanged; top_k < 1 is SS_EINVAL. */
+int ss_top_k_filter(const float *probs_dev, int32_t rows, int32_t vocab, int32_t top_k, float *out_dev,
                     ss_stream stream);
 
 /* ---- device workspace of the entry points that take no handle ---------------------------------
@@ -392,8 +404,8 @@ int ss_greedy_accept(const float *p_logits_dev, const int32_t *draft_tokens_dev,
  *     probability rows go to q_rows_dev [K][vocab] (temperature > 0);
  *   ss_verify_forward on (target, target_kv) over verify_tokens_dev [K+1] = [last committed token,
  *     d_1 .. d_K] -> logits_dev [K+1][vocab];
- *   temperature > 0: ss_softmax -> p_dev [K+1][vocab] (top_p < 1: then ss_top_p_filter in place, as
- *     the draft's calls did to their rows), then ss_speculative_accept with
+ *   temperature > 0: ss_softmax -> p_dev [K+1][vocab] (top_k >= 1: then ss_top_k_filter, top_p < 1: then
+ *     ss_top_p_filter, in place, as the draft's calls did to their rows), then ss_speculative_accept with
  *     u_accept_dev [K+1]; temperature == 0: ss_greedy_accept (p_dev, q_rows_dev, u_*_dev unused);
  *   both caches rolled back to their committed length.
  * Outputs: result_dev int32 [2] = (n_accepted a, next token y); out_host int32 [K+2] = (a, y, d_1 ..
@@ -412,7 +424,7 @@ int ss_greedy_accept(const float *p_logits_dev, const int32_t *draft_tokens_dev,
  * synchronisation state of both models has been reset, both cache lengths have been put back to the
  * host-tracked values from before the step, *n_feed and feed_dev are unchanged, the outputs are invalid. */
 int ss_speculative_step(ss_model *target, ss_kv_cache *target_kv, ss_model *draft, ss_kv_cache *draft_kv,
-                        int32_t K, float temperature, float top_p, int32_t *feed_dev, int32_t *n_feed,
+                        int32_t K, float temperature, float top_p, int32_t top_k, int32_t *feed_dev, int32_t *n_feed,
                         const float *u_draft_dev, const float *u_accept_dev, int32_t *verify_tokens_dev,
                         float *q_rows_dev, float *logits_dev, float *p_dev, int32_t *result_dev,
                         int32_t *out_host, ss_stream stream);

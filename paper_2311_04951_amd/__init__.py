@@ -27,7 +27,7 @@ EXPORTS = [
     "ss_kv_cache_get_len", "ss_kv_cache_rollback", "ss_verify_forward", "ss_decoder_layers_forward",
     "ss_draft_step", "ss_softmax", "ss_speculative_accept", "ss_speculative_accept_logits",
     "ss_greedy_accept", "ss_profile_enable", "ss_profile_read", "ss_model_set_persistent", "ss_model_set_persistent_options",
-    "ss_speculative_step", "ss_probe_read_bandwidth", "ss_quantize_rows_int8", "ss_top_p_filter",
+    "ss_speculative_step", "ss_probe_read_bandwidth", "ss_quantize_rows_int8", "ss_top_p_filter", "ss_top_k_filter",
     "ss_model_set_wait_limit", "ss_quantize_rows_int4", "ss_shutdown", "ss_kv_cache_create", "ss_kv_cache_truncate",
     "ss_workspace_bytes", "ss_workspace_init", "ss_workspace_status", "ss_model_set_timeline", "ss_freeze_allocations",
     "ss_speculative_accept_noalloc",
@@ -95,8 +95,9 @@ def lib():
             "ss_kv_cache_rollback": [vp, vp, vp, i32, vp],
             "ss_verify_forward": [vp, vp, vp, i32, i32, vp, vp],
             "ss_decoder_layers_forward": [vp, vp, vp, i32, i32, vp],
-            "ss_draft_step": [vp, vp, vp, i32, i32, f32, f32, vp, vp, i64, vp, vp],
+            "ss_draft_step": [vp, vp, vp, i32, i32, f32, f32, i32, vp, vp, i64, vp, vp],
             "ss_top_p_filter": [vp, i32, i32, f32, vp, vp],
+            "ss_top_k_filter": [vp, i32, i32, i32, vp, vp],
             "ss_softmax": [vp, i32, i32, f32, vp, vp, sz, vp],
             "ss_speculative_accept": [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp],
             "ss_speculative_accept_noalloc": [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp],
@@ -106,7 +107,7 @@ def lib():
             "ss_model_set_persistent": [vp, i32],
             "ss_model_set_persistent_options": [vp, i32, i32],
             "ss_model_set_wait_limit": [vp, C.c_uint32],
-            "ss_speculative_step": [vp, vp, vp, vp, i32, C.c_float, C.c_float, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp],
+            "ss_speculative_step": [vp, vp, vp, vp, i32, C.c_float, C.c_float, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp],
             "ss_profile_read": [vp, i32, vp, vp],
             "ss_probe_read_bandwidth": [vp, C.c_size_t, i32, vp, vp, vp],
             "ss_quantize_rows_int8": [vp, i32, i64, i64, vp, vp, vp],
@@ -368,10 +369,10 @@ def ss_decoder_layers_forward(model: Model, kv: KVCache, h, batch: int, M: int, 
 
 
 def ss_draft_step(draft: Model, kv: KVCache, tokens, m: int, temperature: float, u, q_rows, ldq: int,
-                  token_out, stream=None, top_p: float = 1.0):
+                  token_out, stream=None, top_p: float = 1.0, top_k: int = 0):
     batch = tokens.numel() // m
     qp = C.c_void_p(0) if q_rows is None else C.c_void_p(q_rows.data_ptr())
-    _check(lib().ss_draft_step(draft.handle, kv.handle, _dev(tokens, torch.int32), batch, m, float(temperature), float(top_p),
+    _check(lib().ss_draft_step(draft.handle, kv.handle, _dev(tokens, torch.int32), batch, m, float(temperature), float(top_p), int(top_k),
                                _dev(u, torch.float32 if u is not None else None), qp, int(ldq),
                                _dev(token_out, torch.int32), _stream(stream)))
     return token_out
@@ -393,6 +394,16 @@ def ss_top_p_filter(probs, top_p: float, out=None, stream=None):
     if out is None:
         out = torch.empty_like(probs)
     _check(lib().ss_top_p_filter(_dev(probs, torch.float32), probs.numel() // V, V, float(top_p), _dev(out, torch.float32),
+                                 _stream(stream)))
+    return out
+
+
+def ss_top_k_filter(probs, top_k: int, out=None, stream=None):
+    """Rows [..., V] of probabilities -> restricted to their top_k most probable tokens and renormalised (out may be probs)."""
+    V = probs.shape[-1]
+    if out is None:
+        out = torch.empty_like(probs)
+    _check(lib().ss_top_k_filter(_dev(probs, torch.float32), probs.numel() // V, V, int(top_k), _dev(out, torch.float32),
                                  _stream(stream)))
     return out
 
@@ -464,10 +475,10 @@ class StepBuffers:
 
 
 def ss_speculative_step(target: Model, target_kv: KVCache, draft: Model, draft_kv: KVCache, buf: StepBuffers,
-                        temperature: float, u_draft=None, u_accept=None, stream=None, top_p: float = 1.0):
+                        temperature: float, u_draft=None, u_accept=None, stream=None, top_p: float = 1.0, top_k: int = 0):
     """One speculative step; returns (n_accepted, next_token, [d_1..d_K]) as host integers."""
     _check(lib().ss_speculative_step(
-        target.handle, target_kv.handle, draft.handle, draft_kv.handle, buf.K, float(temperature), float(top_p),
+        target.handle, target_kv.handle, draft.handle, draft_kv.handle, buf.K, float(temperature), float(top_p), int(top_k),
         _dev(buf.feed, torch.int32),
         C.byref(buf.n_feed), _dev(u_draft, torch.float32), _dev(u_accept, torch.float32), _dev(buf.verify_tokens, torch.int32),
         _dev(buf.q), _dev(buf.logits), _dev(buf.p), _dev(buf.result, torch.int32), buf.out, _stream(stream)))

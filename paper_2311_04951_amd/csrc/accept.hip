@@ -591,6 +591,11 @@ __device__ __forceinline__ unsigned long long block_excl_scan(unsigned long long
     return before + incl - mine;
 }
 
+// BY_COUNT = false: top-p, the histograms hold sums of weights and the selection looks for the weight at which the running
+// sum reaches ceil(P24 * S / 2^24).  BY_COUNT = true: top-k (`P24` carries k, 1 <= k < V), the histograms hold counts (tokens
+// without a weight count too: they are the tail of the order) and the selection looks for the weight of the k-th token;
+// the kept weight is then summed in one more pass over the row.
+template <bool BY_COUNT>
 __global__ __launch_bounds__(TP_THREADS) void top_p_filter_kernel(const float *probs, long long ld_in, int V, unsigned P24, float *out, long long ld_out) {
     __shared__ unsigned long long hist[TP_BINS];
     __shared__ unsigned long long sm_wave[TP_WAVES];
@@ -625,14 +630,14 @@ __global__ __launch_bounds__(TP_THREADS) void top_p_filter_kernel(const float *p
             for (int e = 0; e < TP_UNROLL; ++e) {
                 const uint32_t w = fx_weight32(x[e]);
                 // keys inside the range chosen so far (pass 0: every key with a weight)
-                if (w != 0 && (pass == 0 || (w >> (sh + nb)) == prefix)) {
+                if ((BY_COUNT ? v0 + e * TP_THREADS + t < V : w != 0) && (pass == 0 || (w >> (sh + nb)) == prefix)) {
                     const uint32_t bin = (w >> sh) & ((1u << nb) - 1);
                     if (bin != run_bin) {
                         if (run_bin != 0xffffffffu) atomicAdd(&hist[run_bin], run_sum);
                         run_bin = bin;
                         run_sum = 0;
                     }
-                    run_sum += w;
+                    run_sum += BY_COUNT ? 1u : w;
                 }
             }
         }
@@ -642,7 +647,11 @@ __global__ __launch_bounds__(TP_THREADS) void top_p_filter_kernel(const float *p
         const unsigned long long a = hist[TP_BINS - 1 - 2 * t], b = hist[TP_BINS - 2 - 2 * t];
         unsigned long long total;
         const unsigned long long above = block_excl_scan(a + b, sm_wave, total);
-        if (pass == 0) {
+        if (BY_COUNT && pass == 0) {
+            need = P24; // the k-th token of the order
+            target = need;
+        }
+        if (!BY_COUNT && pass == 0) {
             S = total;
             if (S == 0) { // nothing has a weight: the row is returned as it is
                 for (int v = t; v < V; v += TP_THREADS) o[v] = p[v];
@@ -672,7 +681,8 @@ __global__ __launch_bounds__(TP_THREADS) void top_p_filter_kernel(const float *p
     }
     // prefix = threshold weight tau (>= 1); need = what tokens of weight tau must contribute; tie_weight = their total
     const unsigned long long tau = prefix;
-    const unsigned long long n_ties = tie_weight / tau, n_keep = (need + tau - 1) / tau;
+    // (top-k: counts already; tau may be 0 there, when k reaches into the tokens without a weight)
+    const unsigned long long n_ties = BY_COUNT ? tie_weight : tie_weight / tau, n_keep = BY_COUNT ? need : (need + tau - 1) / tau;
     int cut = V; // ties are kept up to and including this index
     if (n_keep < n_ties) {
         // the n_keep-th token of weight tau in index order: contiguous chunks per thread, counts scanned over threads
@@ -694,7 +704,21 @@ __global__ __launch_bounds__(TP_THREADS) void top_p_filter_kernel(const float *p
         cut = sm_cut;
     }
     // weight of the kept set: everything above tau (target - need) plus the kept tokens of weight tau
-    const unsigned long long kept = target - need + n_keep * tau;
+    unsigned long long kept = target - need + n_keep * tau;
+    if (BY_COUNT) { // the weight above tau is not known from counts: one more pass over the row
+        unsigned long long mine = 0;
+        for (int v = t; v < V; v += TP_THREADS) {
+            const uint32_t w = fx_weight32(p[v]);
+            mine += w > prefix ? w : 0u;
+        }
+        unsigned long long total;
+        block_excl_scan(mine, sm_wave, total);
+        kept = total + n_keep * tau;
+        if (kept == 0) { // nothing kept has a weight (then nothing has): the row is returned as it is
+            for (int v = t; v < V; v += TP_THREADS) o[v] = p[v];
+            return;
+        }
+    }
     const float Z = __fmul_rn(__ull2float_rn(kept), 2.3283064365386963e-10f);
     for (int v0 = 0; v0 < V; v0 += TP_UNROLL * TP_THREADS) {
         float x[TP_UNROLL];
@@ -713,7 +737,11 @@ __global__ __launch_bounds__(TP_THREADS) void top_p_filter_kernel(const float *p
 }
 void launch_top_p_filter(const float *probs, long long ld_in, int rows, int V, unsigned P24, float *out, long long ld_out, hipStream_t st) {
     if (rows <= 0) return;
-    hipLaunchKernelGGL(top_p_filter_kernel, dim3(rows), dim3(TP_THREADS), 0, st, probs, ld_in, V, P24, out, ld_out);
+    hipLaunchKernelGGL(top_p_filter_kernel<false>, dim3(rows), dim3(TP_THREADS), 0, st, probs, ld_in, V, P24, out, ld_out);
+}
+void launch_top_k_filter(const float *probs, long long ld_in, int rows, int V, int k, float *out, long long ld_out, hipStream_t st) {
+    if (rows <= 0) return;
+    hipLaunchKernelGGL(top_p_filter_kernel<true>, dim3(rows), dim3(TP_THREADS), 0, st, probs, ld_in, V, (unsigned)k, out, ld_out);
 }
 
 // ------------------------------------------------------------------ sampling / argmax of plain rows

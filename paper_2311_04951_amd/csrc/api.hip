@@ -831,13 +831,37 @@ extern "C" int ss_top_p_filter(const float *probs_dev, int32_t rows, int32_t voc
     return check_launch();
 }
 
+// top_k as the filter takes it: 0 = no filtering (0 and >= vocab switch it off)
+static int top_k_arg(int32_t top_k, int vocab, int *k, const char *who) {
+    if (top_k < 0) return fail(SS_EINVAL, "%s: top_k must be >= 0 (0 and >= vocab switch the filter off)", who);
+    *k = top_k >= vocab ? 0 : top_k;
+    return SS_OK;
+}
+
+extern "C" int ss_top_k_filter(const float *probs_dev, int32_t rows, int32_t vocab, int32_t top_k, float *out_dev, ss_stream stream) {
+    if (!probs_dev || !out_dev) return fail(SS_EINVAL, "ss_top_k_filter: NULL argument");
+    if (rows < 0 || vocab <= 0) return fail(SS_EINVAL, "ss_top_k_filter: bad shape");
+    if (top_k < 1) return fail(SS_EINVAL, "ss_top_k_filter: top_k must be >= 1 (>= vocab copies the rows unchanged)");
+    if (rows == 0) return SS_OK;
+    hipStream_t st = (hipStream_t)stream;
+    if (top_k >= vocab) {
+        if (out_dev != probs_dev) HIP_TRY(hipMemcpyAsync(out_dev, probs_dev, sizeof(float) * (size_t)rows * vocab, hipMemcpyDeviceToDevice, st));
+        return SS_OK;
+    }
+    launch_top_k_filter(probs_dev, vocab, rows, vocab, top_k, out_dev, vocab, st);
+    return check_launch();
+}
+
 extern "C" int ss_draft_step(ss_model *m, ss_kv_cache *kv, const int32_t *tokens_dev, int32_t batch, int32_t mrows,
-                             float temperature, float top_p, const float *u_dev, float *q_rows_dev, int64_t ldq,
+                             float temperature, float top_p, int32_t top_k, const float *u_dev, float *q_rows_dev, int64_t ldq,
                              int32_t *token_out_dev, ss_stream stream) {
     int rc = check_pair(m, kv, batch, mrows, "ss_draft_step");
     if (rc) return rc;
     unsigned P24 = 0;
     rc = top_p_grid(top_p, &P24, "ss_draft_step");
+    if (rc) return rc;
+    int kk = 0;
+    rc = top_k_arg(top_k, m->cfg.vocab, &kk, "ss_draft_step");
     if (rc) return rc;
     if (!tokens_dev || !token_out_dev) return fail(SS_EINVAL, "ss_draft_step: NULL argument");
     if (!m->embed || !m->lm_head || !m->gf) return fail(SS_EINVAL, "ss_draft_step: model has no embedding / LM head");
@@ -857,6 +881,7 @@ extern "C" int ss_draft_step(ss_model *m, ss_kv_cache *kv, const int32_t *tokens
         const float inv_t = 1.0f / temperature;
         launch_row_stats(m->logits_ws, batch, V, inv_t, m->stats_ws, m->stats_cnt, m->stats_part, st);
         launch_softmax_write(m->logits_ws, batch, V, inv_t, m->stats_ws, q_rows_dev, ldq, st);
+        if (kk) launch_top_k_filter(q_rows_dev, ldq, batch, V, kk, q_rows_dev, ldq, st); // top-k first, top-p on its output
         if (P24) launch_top_p_filter(q_rows_dev, ldq, batch, V, P24, q_rows_dev, ldq, st);
         launch_sample_rows(q_rows_dev, ldq, batch, V, u_dev, token_out_dev, st);
     } else {
@@ -1086,7 +1111,7 @@ extern "C" int ss_speculative_accept_noalloc(const float *p_dev, const float *q_
 // ------------------------------------------------------------------------------------------ one speculative step
 
 extern "C" int ss_speculative_step(ss_model *target, ss_kv_cache *tkv, ss_model *draft, ss_kv_cache *dkv, int32_t K,
-                                   float temperature, float top_p, int32_t *feed_dev, int32_t *n_feed, const float *u_draft_dev,
+                                   float temperature, float top_p, int32_t top_k, int32_t *feed_dev, int32_t *n_feed, const float *u_draft_dev,
                                    const float *u_accept_dev, int32_t *vt, float *q_rows_dev, float *logits_dev, float *p_dev,
                                    int32_t *result_dev, int32_t *out_host, ss_stream stream) {
     if (!target || !tkv || !draft || !dkv || !feed_dev || !n_feed || !vt || !logits_dev || !result_dev || !out_host)
@@ -1100,6 +1125,8 @@ extern "C" int ss_speculative_step(ss_model *target, ss_kv_cache *tkv, ss_model 
     if (!(temperature >= 0.f)) return fail(SS_EINVAL, "ss_speculative_step: temperature must be >= 0");
     unsigned P24 = 0;
     if (int rc0 = top_p_grid(top_p, &P24, "ss_speculative_step")) return rc0;
+    int kk = 0;
+    if (int rc0 = top_k_arg(top_k, target->cfg.vocab, &kk, "ss_speculative_step")) return rc0;
     const bool sample = temperature > 0.f;
     if (sample && (!u_draft_dev || !u_accept_dev || !q_rows_dev || !p_dev)) return fail(SS_EINVAL, "ss_speculative_step: sampling needs uniforms, q_rows_dev and p_dev");
     hipStream_t st = (hipStream_t)stream;
@@ -1115,7 +1142,7 @@ extern "C" int ss_speculative_step(ss_model *target, ss_kv_cache *tkv, ss_model 
                     dkv->len_ub[0], draft_rows, dkv->max_seq, draft->cfg.max_pos);
     const int t_len0 = tkv->len_ub[0], d_len0 = dkv->len_ub[0];
     for (int i = 0; i < K; ++i) {
-        rc = ss_draft_step(draft, dkv, i ? vt + i : feed_dev, 1, i ? 1 : *n_feed, temperature, top_p, sample ? u_draft_dev + i : nullptr,
+        rc = ss_draft_step(draft, dkv, i ? vt + i : feed_dev, 1, i ? 1 : *n_feed, temperature, top_p, top_k, sample ? u_draft_dev + i : nullptr,
                            sample ? q_rows_dev + (size_t)i * V : nullptr, V, vt + i + 1, stream);
         if (rc) return rc;
     }
@@ -1130,7 +1157,8 @@ extern "C" int ss_speculative_step(ss_model *target, ss_kv_cache *tkv, ss_model 
     if (sample) {
         rc = ss_softmax(logits_dev, M, V, temperature, p_dev, target->ws, target->ws_bytes, stream);
         if (rc) return rc;
-        if (P24) launch_top_p_filter(p_dev, V, M, V, P24, p_dev, V, st); // the draft's rows were filtered by its own calls
+        if (kk) launch_top_k_filter(p_dev, V, M, V, kk, p_dev, V, st); // the draft's rows were filtered by its own calls
+        if (P24) launch_top_p_filter(p_dev, V, M, V, P24, p_dev, V, st);
         rc = ss_speculative_accept(p_dev, q_rows_dev, vt + 1, u_accept_dev, 1, K, V, result_dev, result_dev + 1, target->ws, target->ws_bytes, stream);
     } else {
         rc = ss_greedy_accept(logits_dev, vt + 1, 1, K, V, result_dev, result_dev + 1, target->ws, target->ws_bytes, stream);

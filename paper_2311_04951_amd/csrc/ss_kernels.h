@@ -118,6 +118,8 @@ void launch_greedy_accept(const float *p_logits, const int32_t *draft, int B, in
 // token ~ row by the integer inverse CDF (rows are probabilities), or argmax when greedy
 // rows of probabilities -> the rows restricted to their top-p nucleus and renormalised (P24 = top_p on a 2^-24 grid); out may alias probs
 void launch_top_p_filter(const float *probs, long long ld_in, int rows, int V, unsigned P24, float *out, long long ld_out, hipStream_t st);
+// rows of probabilities -> the rows restricted to their k heaviest tokens (ties: lowest index first) and renormalised; 1 <= k < V; out may alias probs
+void launch_top_k_filter(const float *probs, long long ld_in, int rows, int V, int k, float *out, long long ld_out, hipStream_t st);
 void launch_sample_rows(const float *probs, int64_t ld, int B, int V, const float *u, int32_t *token_out,
                         hipStream_t st);
 void launch_argmax_rows(const float *logits, int64_t ld, int B, int V, int32_t *token_out, hipStream_t st);

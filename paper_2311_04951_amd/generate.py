@@ -14,7 +14,7 @@ import time
 
 import torch
 
-from . import (KVCache, Model, SpecVerifyError, StepBuffers, ss_device_status, ss_draft_step, ss_greedy_accept, ss_kv_cache_rollback, ss_kv_cache_set_len, ss_softmax, ss_top_p_filter,
+from . import (KVCache, Model, SpecVerifyError, StepBuffers, ss_device_status, ss_draft_step, ss_greedy_accept, ss_kv_cache_rollback, ss_kv_cache_set_len, ss_softmax, ss_top_k_filter, ss_top_p_filter,
                ss_speculative_accept, ss_speculative_step, ss_verify_forward)
 
 
@@ -36,10 +36,11 @@ def prefill(model: Model, kv: KVCache, tokens, chunk: int = 16):
 
 
 def autoregressive_generate(target: Model, prompt, n_new: int, temperature: float, u=None, max_seq=None,
-                            stats=None, top_p: float = 1.0):
+                            stats=None, top_p: float = 1.0, top_k: int = 0):
     """One target call per token; the sampled token never leaves the device between steps.  `stats`
     (a dict, optional) receives loop_seconds: the wall time of the decode loop without the prefill.
-    top_p < 1: tokens are drawn from the top-p nucleus of every row (Section 3)."""
+    top_p < 1: tokens are drawn from the top-p nucleus of every row; top_k >= 1: from its top_k most probable
+    tokens (top-k first when both are set; Section 3)."""
     dev = torch.device("cuda")
     V = target.shape.vocab
     kv = KVCache(target, 1, max_seq or (len(prompt) + n_new + 1))
@@ -54,7 +55,7 @@ def autoregressive_generate(target: Model, prompt, n_new: int, temperature: floa
     t0 = time.perf_counter()
     for i in range(n_new):
         ss_draft_step(target, kv, buf[i:i + 1], 1, temperature, ud[i:i + 1] if ud is not None else None, q, V,
-                      buf[i + 1:i + 2], top_p=top_p)
+                      buf[i + 1:i + 2], top_p=top_p, top_k=top_k)
     torch.cuda.synchronize()
     if stats is not None:
         stats["loop_seconds"] = time.perf_counter() - t0
@@ -65,17 +66,19 @@ def autoregressive_generate(target: Model, prompt, n_new: int, temperature: floa
 
 
 def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int, temperature: float,
-                         u_draft=None, u_accept=None, max_seq=None, observer=None, shared_kv=False, top_p: float = 1.0):
+                         u_draft=None, u_accept=None, max_seq=None, observer=None, shared_kv=False, top_p: float = 1.0,
+                         top_k: int = 0):
     """Returns (tokens[n_new], stats).  u_draft [steps, K], u_accept [steps, K+1] (temperature > 0).
     `observer(dict)` (optional) sees each step's device tensors: draft tokens, q rows, target logits,
     n_accepted, next token; with an observer the step is issued call by call from here, without one
     it is a single ss_speculative_step per step (same calls, same results).
     shared_kv (Section 4.4, for a draft made of the target's first layers): one cache; the draft works in
     its leading layers, the verify pass rewrites the draft's positions, no catch-up call exists.
-    top_p < 1: the draft's and the target's rows are both restricted to their top-p nucleus (Section 3 names
-    top-p selection) before anything is drawn or compared: the run emits the filtered target distribution."""
+    top_p < 1 / top_k >= 1: the draft's and the target's rows are both restricted (top-k first, then the top-p
+    nucleus; Section 3 names both selection rules) before anything is drawn or compared: the run emits the
+    filtered target distribution."""
     if observer is None:
-        return _speculative_generate_native(target, draft, prompt, n_new, K, temperature, u_draft, u_accept, max_seq, shared_kv, top_p)
+        return _speculative_generate_native(target, draft, prompt, n_new, K, temperature, u_draft, u_accept, max_seq, shared_kv, top_p, top_k)
     dev = torch.device("cuda")
     V = target.shape.vocab
     M = K + 1
@@ -107,7 +110,7 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
         for i in range(K):
             ss_draft_step(draft, dkv, feed, feed.shape[1], temperature,
                           None if greedy else ud_all[step, i:i + 1], None if greedy else q[0, i], K * V,
-                          vt[0, i + 1:i + 2], top_p=top_p)
+                          vt[0, i + 1:i + 2], top_p=top_p, top_k=top_k)
             feed = vt[:, i + 1:i + 2]
         vt[0, 0] = x[-1]
         if shared_kv:
@@ -118,6 +121,8 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
             ss_greedy_accept(logits, d, na, nx)
         else:
             ss_softmax(logits, temperature, p)
+            if 1 <= top_k < V:
+                ss_top_k_filter(p, top_k, p)
             if top_p < 1.0:
                 ss_top_p_filter(p, top_p, p)
             ss_speculative_accept(p, q, d, ua_all[step:step + 1].contiguous(), na, nx)
@@ -143,7 +148,7 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
 
 
 def _speculative_generate_native(target, draft, prompt, n_new, K, temperature, u_draft, u_accept, max_seq, shared_kv=False,
-                                 top_p=1.0):
+                                 top_p=1.0, top_k=0):
     dev = torch.device("cuda")
     greedy = temperature == 0
     cap = max_seq or (len(prompt) + n_new + K + 2)
@@ -163,7 +168,7 @@ def _speculative_generate_native(target, draft, prompt, n_new, K, temperature, u
     t0 = time.perf_counter()
     while len(out) < n_new:
         a, y, d = ss_speculative_step(target, tkv, draft, dkv, buf, temperature,
-                                      None if greedy else ud_all[step], None if greedy else ua_all[step], top_p=top_p)
+                                      None if greedy else ud_all[step], None if greedy else ua_all[step], top_p=top_p, top_k=top_k)
         out += d[:a] + [y]
         accepted.append(a)
         step += 1
