@@ -346,6 +346,42 @@ def batched_workload(si, sv, torch, dev, shape, packed, io, iters=5, B=8, L=4096
                         "traffic_source": BATCHED_TRAFFIC_SOURCE + STORED,
                         "note": "whole pass (weights once, every sequence's KV context once) over its host-timed duration"},
            "class_ms_per_pass": {k: round(ms / 3, 3) for k, (ms, n) in prof.items() if n}}
+    # end to end on this workload: speculative steps of all sequences at once (ss_speculative_step_batched), early-exit draft,
+    # T = 1; the sequences start at ragged lengths and accept different numbers of tokens per step
+    K = M - 1
+    dshape = si.DecoderShape(**{**shape.as_dict(), "n_layers": min(2, shape.n_layers)})
+    dm = sv.Model(dshape, io, max_rows=2 * B, max_pos=L + 512, packed_layers=packed[:dshape.n_layers])
+    dkv = sv.KVCache(dm, B, L + 512)
+    for l in range(dshape.n_layers):
+        k = si.normal(5, f"bw_k{l}", (L, W), 1.0, device=dev, dtype=torch.bfloat16)
+        v = si.normal(5, f"bw_v{l}", (L, W), 1.0, device=dev, dtype=torch.bfloat16)
+        for b in range(B):
+            sv.ss_kv_cache_append(dkv, l, b, 0, k, v)
+    lens = [L - 7 * b for b in range(B)]
+    n_steps = 12
+    buf = sv.BatchedStepBuffers(B, K, shape.vocab, si.token_ids(2, "bw_feed", (B, 2), shape.vocab).tolist(), dev)
+    ud = si.uniforms(2, "bw_ud", (n_steps + 2, K, B)).to(dev)
+    ua = si.uniforms(2, "bw_ua", (n_steps + 2, B, K + 1)).to(dev)
+    sv.ss_kv_cache_set_len(kv, lens)
+    sv.ss_kv_cache_set_len(dkv, [x - 1 for x in lens])
+    tokens = accepted = 0
+    for it in range(n_steps + 2):
+        if it == 2:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+        res = sv.ss_speculative_step_batched(m, kv, dm, dkv, buf, 1.0, ud[it], ua[it])
+        if it >= 2:
+            tokens += sum(a + 1 for a, _, _ in res)
+            accepted += sum(a for a, _, _ in res)
+    torch.cuda.synchronize()
+    dts = (time.perf_counter() - t0) / n_steps
+    check_status(sv, m, dm)
+    out["end_to_end"] = {"workload": f"{n_steps} speculative steps of {B} sequences at once (K {K}, T 1, early-exit draft of {dshape.n_layers} layers, ragged lengths from {lens[-1]} to {lens[0]})",
+                         "ms_per_step": dts * 1e3, "accepted_tokens_per_s": tokens / (dts * n_steps),
+                         "mean_accepted_per_step_and_sequence": accepted / (n_steps * B),
+                         "final_lengths": [int(x) for x in sv.ss_kv_cache_get_len(kv).tolist()]}
+    dkv.close()
+    dm.close()
     m.close()
     if int8:
         # the same pass with int8 matrices (the KV cache stays bf16: it is most of this workload's bytes)

@@ -429,6 +429,31 @@ int ss_speculative_step(ss_model *target, ss_kv_cache *target_kv, ss_model *draf
                         float *q_rows_dev, float *logits_dev, float *p_dev, int32_t *result_dev,
                         int32_t *out_host, ss_stream stream);
 
+/* ---- one speculative step for a batch of sequences (Sections 3, 4.3, 4.4; every sequence accepts its own
+ * number of tokens, so the cache lengths grow ragged) -------------------------------------------
+ * The same calls as ss_speculative_step, each over `batch` sequences at once, with two caches of `batch`
+ * sequences.  To keep every call rectangular the draft cache is kept one position shorter than in the
+ * single-sequence step: with n_b committed tokens of sequence b the target cache holds n_b - 1 positions, the
+ * draft cache n_b - 2, and feed_dev int32 [batch][2] holds every sequence's last two committed tokens (a prompt
+ * has at least two; prefill the target with all but the last token, the draft with all but the last two).  The
+ * first draft call feeds both tokens of every sequence (two rows each), the others one; after the rejection
+ * step both caches keep a_b + 1 of the K + 1 positions they gained, and feed_dev is rewritten.  The price of
+ * the rectangle is one draft row per sequence and step that the single-sequence step computes only after a
+ * fully accepted step; the tokens are the same.
+ * u_draft_dev fp32 [K][batch] (call-major), u_accept_dev fp32 [batch][K+1]; draft_tokens_dev int32
+ * [2][K][batch] scratch; verify_tokens_dev int32 [batch][K+1]; q_rows_dev fp32 [batch][K][vocab]; logits_dev
+ * and p_dev fp32 [batch][K+1][vocab]; result_dev int32 [2][batch] = (n_accepted, next token);
+ * out_host int32 [batch][K+2] = (a_b, y_b, d_1 .. d_K) after a stream synchronisation.  temperature, top_p,
+ * top_k as in ss_speculative_step.  The target model must have been created with max_rows >= batch * (K + 1),
+ * the draft with max_rows >= 2 * batch.  Errors as in ss_speculative_step; SS_EABORTED restores both caches'
+ * lengths, the feed is then stale (rebuild it from the caller's token history). */
+int ss_speculative_step_batched(ss_model *target, ss_kv_cache *target_kv, ss_model *draft, ss_kv_cache *draft_kv,
+                                int32_t batch, int32_t K, float temperature, float top_p, int32_t top_k,
+                                int32_t *feed_dev, const float *u_draft_dev, const float *u_accept_dev,
+                                int32_t *draft_tokens_dev, int32_t *verify_tokens_dev, float *q_rows_dev,
+                                float *logits_dev, float *p_dev, int32_t *result_dev, int32_t *out_host,
+                                ss_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,7 +27,7 @@ EXPORTS = [
     "ss_kv_cache_get_len", "ss_kv_cache_rollback", "ss_verify_forward", "ss_decoder_layers_forward",
     "ss_draft_step", "ss_softmax", "ss_speculative_accept", "ss_speculative_accept_logits",
     "ss_greedy_accept", "ss_profile_enable", "ss_profile_read", "ss_model_set_persistent", "ss_model_set_persistent_options",
-    "ss_speculative_step", "ss_probe_read_bandwidth", "ss_quantize_rows_int8", "ss_top_p_filter", "ss_top_k_filter",
+    "ss_speculative_step", "ss_speculative_step_batched", "ss_probe_read_bandwidth", "ss_quantize_rows_int8", "ss_top_p_filter", "ss_top_k_filter",
     "ss_model_set_wait_limit", "ss_quantize_rows_int4", "ss_shutdown", "ss_kv_cache_create", "ss_kv_cache_truncate",
     "ss_workspace_bytes", "ss_workspace_init", "ss_workspace_status", "ss_model_set_timeline", "ss_freeze_allocations",
     "ss_speculative_accept_noalloc",
@@ -108,6 +108,7 @@ def lib():
             "ss_model_set_persistent_options": [vp, i32, i32],
             "ss_model_set_wait_limit": [vp, C.c_uint32],
             "ss_speculative_step": [vp, vp, vp, vp, i32, C.c_float, C.c_float, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp],
+            "ss_speculative_step_batched": [vp, vp, vp, vp, i32, i32, C.c_float, C.c_float, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp],
             "ss_profile_read": [vp, i32, vp, vp],
             "ss_probe_read_bandwidth": [vp, C.c_size_t, i32, vp, vp, vp],
             "ss_quantize_rows_int8": [vp, i32, i64, i64, vp, vp, vp],
@@ -175,6 +176,7 @@ class Model:
     def __init__(self, shape, weights=None, max_rows=16, max_pos=4096, packed_layers=None, int8_weights=False,
                  int4_weights=False):
         self.shape = shape
+        self.max_rows, self.max_pos = int(max_rows), int(max_pos)
         if int8_weights and int4_weights:
             raise ValueError("one quantisation at a time")
         self.int4_weights = bool(int4_weights)
@@ -483,6 +485,36 @@ def ss_speculative_step(target: Model, target_kv: KVCache, draft: Model, draft_k
         C.byref(buf.n_feed), _dev(u_draft, torch.float32), _dev(u_accept, torch.float32), _dev(buf.verify_tokens, torch.int32),
         _dev(buf.q), _dev(buf.logits), _dev(buf.p), _dev(buf.result, torch.int32), buf.out, _stream(stream)))
     return buf.out[0], buf.out[1], list(buf.out[2:2 + buf.K])
+
+
+class BatchedStepBuffers:
+    """Device and host buffers of ss_speculative_step_batched (allocated once per decode loop).
+    last_two: [batch][2], every sequence's last two committed tokens."""
+
+    def __init__(self, batch: int, K: int, vocab: int, last_two, device):
+        self.B, self.K, self.V = batch, K, vocab
+        i32, f32 = torch.int32, torch.float32
+        self.feed = torch.as_tensor(last_two, dtype=i32).reshape(batch, 2).to(device).contiguous()
+        self.draft_tokens = torch.zeros((2, K, batch), dtype=i32, device=device)
+        self.verify_tokens = torch.zeros((batch, K + 1), dtype=i32, device=device)
+        self.q = torch.zeros((batch, K, vocab), dtype=f32, device=device)
+        self.logits = torch.empty((batch, K + 1, vocab), dtype=f32, device=device)
+        self.p = torch.empty((batch, K + 1, vocab), dtype=f32, device=device)
+        self.result = torch.zeros((2, batch), dtype=i32, device=device)
+        self.out = (C.c_int32 * (batch * (K + 2)))()
+
+
+def ss_speculative_step_batched(target: Model, target_kv: KVCache, draft: Model, draft_kv: KVCache, buf: BatchedStepBuffers,
+                                temperature: float, u_draft=None, u_accept=None, stream=None, top_p: float = 1.0, top_k: int = 0):
+    """One speculative step of every sequence; u_draft [K][batch], u_accept [batch][K+1].
+    Returns a list over sequences of (n_accepted, next_token, [d_1..d_K]) as host integers."""
+    _check(lib().ss_speculative_step_batched(
+        target.handle, target_kv.handle, draft.handle, draft_kv.handle, buf.B, buf.K, float(temperature), float(top_p), int(top_k),
+        _dev(buf.feed, torch.int32), _dev(u_draft, torch.float32), _dev(u_accept, torch.float32), _dev(buf.draft_tokens, torch.int32),
+        _dev(buf.verify_tokens, torch.int32), _dev(buf.q), _dev(buf.logits), _dev(buf.p), _dev(buf.result, torch.int32), buf.out,
+        _stream(stream)))
+    w = buf.K + 2
+    return [(buf.out[b * w], buf.out[b * w + 1], list(buf.out[b * w + 2:b * w + w])) for b in range(buf.B)]
 
 
 def ss_device_status(model: Model, stream=None) -> int:

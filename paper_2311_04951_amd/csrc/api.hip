@@ -1198,6 +1198,91 @@ extern "C" int ss_speculative_step(ss_model *target, ss_kv_cache *tkv, ss_model 
     return check_launch();
 }
 
+// ------------------------------------------------------------------------------------------ one speculative step, many sequences
+
+extern "C" int ss_speculative_step_batched(ss_model *target, ss_kv_cache *tkv, ss_model *draft, ss_kv_cache *dkv, int32_t batch, int32_t K,
+                                           float temperature, float top_p, int32_t top_k, int32_t *feed_dev, const float *u_draft_dev,
+                                           const float *u_accept_dev, int32_t *draft_tokens_dev, int32_t *vt, float *q_rows_dev,
+                                           float *logits_dev, float *p_dev, int32_t *result_dev, int32_t *out_host, ss_stream stream) {
+    if (!target || !tkv || !draft || !dkv || !feed_dev || !draft_tokens_dev || !vt || !logits_dev || !result_dev || !out_host)
+        return fail(SS_EINVAL, "ss_speculative_step_batched: NULL argument");
+    if (K < 1 || K > SS_MAX_ROWS_PER_SEQ - 1) return fail(SS_EINVAL, "ss_speculative_step_batched: K must be in [1, %d]", SS_MAX_ROWS_PER_SEQ - 1);
+    if (dkv == tkv) return fail(SS_EINVAL, "ss_speculative_step_batched: two caches (the shared-cache scheme is single-sequence)");
+    if (batch < 1 || tkv->B != batch || dkv->B != batch) return fail(SS_EINVAL, "ss_speculative_step_batched: both caches must hold `batch` sequences");
+    if (target->cfg.vocab != draft->cfg.vocab) return fail(SS_EINVAL, "ss_speculative_step_batched: the two models have different vocabularies");
+    if (!(temperature >= 0.f)) return fail(SS_EINVAL, "ss_speculative_step_batched: temperature must be >= 0");
+    unsigned P24 = 0;
+    if (int rc0 = top_p_grid(top_p, &P24, "ss_speculative_step_batched")) return rc0;
+    int kk = 0;
+    if (int rc0 = top_k_arg(top_k, target->cfg.vocab, &kk, "ss_speculative_step_batched")) return rc0;
+    const bool sample = temperature > 0.f;
+    if (sample && (!u_draft_dev || !u_accept_dev || !q_rows_dev || !p_dev)) return fail(SS_EINVAL, "ss_speculative_step_batched: sampling needs uniforms, q_rows_dev and p_dev");
+    hipStream_t st = (hipStream_t)stream;
+    const int V = target->cfg.vocab, M = K + 1;
+    // everything the calls below would refuse is refused here, before the first of them changes a cache
+    int rc = check_pair(target, tkv, batch, M, "ss_speculative_step_batched (target)");
+    if (rc) return rc;
+    rc = check_pair(draft, dkv, batch, 2, "ss_speculative_step_batched (draft)");
+    if (rc) return rc;
+    for (int b = 0; b < batch; ++b)
+        if (dkv->len_ub[b] + M > dkv->max_seq || dkv->len_ub[b] + M > draft->cfg.max_pos)
+            return fail(SS_ECAPACITY, "ss_speculative_step_batched: the draft cache of sequence %d at length <= %d has no room for %d rows (max_seq %d, max_pos %d)",
+                        b, dkv->len_ub[b], M, dkv->max_seq, draft->cfg.max_pos);
+    if (ss_workspace_bytes((int64_t)batch * (2 * K + 1), V) > target->ws_bytes)
+        return fail(SS_ECAPACITY, "ss_speculative_step_batched: the target model's workspace (sized for max_rows) is too small for %d sequences", batch);
+    const std::vector<int32_t> t_len0 = tkv->len_ub, d_len0 = dkv->len_ub;
+    int32_t *dbk = draft_tokens_dev + (size_t)K * batch; // the draft's tokens, sequence-major
+    for (int i = 0; i < K; ++i) {
+        rc = ss_draft_step(draft, dkv, i ? draft_tokens_dev + (size_t)(i - 1) * batch : feed_dev, batch, i ? 1 : 2, temperature, top_p, top_k,
+                           sample ? u_draft_dev + (size_t)i * batch : nullptr, sample ? q_rows_dev + (size_t)i * V : nullptr, (int64_t)K * V,
+                           draft_tokens_dev + (size_t)i * batch, stream);
+        if (rc) return rc;
+    }
+    launch_step_pack_tokens(feed_dev, draft_tokens_dev, batch, K, vt, dbk, st);
+    rc = ss_verify_forward(target, tkv, vt, batch, M, logits_dev, stream);
+    if (rc) return rc;
+    if (sample) {
+        rc = ss_softmax(logits_dev, batch * M, V, temperature, p_dev, target->ws, target->ws_bytes, stream);
+        if (rc) return rc;
+        if (kk) launch_top_k_filter(p_dev, V, batch * M, V, kk, p_dev, V, st); // the draft's rows were filtered by its own calls
+        if (P24) launch_top_p_filter(p_dev, V, batch * M, V, P24, p_dev, V, st);
+        rc = ss_speculative_accept(p_dev, q_rows_dev, dbk, u_accept_dev, batch, K, V, result_dev, result_dev + batch, target->ws, target->ws_bytes, stream);
+    } else {
+        rc = ss_greedy_accept(logits_dev, dbk, batch, K, V, result_dev, result_dev + batch, target->ws, target->ws_bytes, stream);
+    }
+    if (rc) return rc;
+    // both caches grew by K + 1 rows per sequence and keep a_b + 1 of them: the target then holds n'_b - 1 positions, the draft n'_b - 2
+    launch_len_rollback(tkv->len_dev, result_dev, batch, M, st);
+    launch_len_rollback(dkv->len_dev, result_dev, batch, M, st);
+    launch_step_next_feed(vt, result_dev, result_dev + batch, batch, K, feed_dev, st);
+    std::vector<int32_t> res(2 * (size_t)batch), dt((size_t)batch * K);
+    HIP_TRY(hipMemcpyAsync(res.data(), result_dev, res.size() * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(dt.data(), dbk, dt.size() * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    unsigned ab[2] = {0u, 0u};
+    if (target->abort_flag) HIP_TRY(hipMemcpyAsync(&ab[0], target->abort_flag, sizeof(unsigned), hipMemcpyDeviceToHost, st));
+    if (draft->abort_flag && draft != target) HIP_TRY(hipMemcpyAsync(&ab[1], draft->abort_flag, sizeof(unsigned), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (ab[0] | ab[1]) {
+        int32_t dummy = 0;
+        if (ab[0]) (void)ss_device_status(target, stream, &dummy); // resets the synchronisation state
+        if (ab[1]) (void)ss_device_status(draft, stream, &dummy);
+        (void)ss_kv_cache_set_len(tkv, t_len0.data(), stream);
+        (void)ss_kv_cache_set_len(dkv, d_len0.data(), stream);
+        return fail(SS_EABORTED, "ss_speculative_step_batched: a bounded wait of the persistent kernel gave up (%s model); cache lengths restored, the feed is stale",
+                    ab[0] ? "target" : "draft");
+    }
+    for (int b = 0; b < batch; ++b) {
+        const int a = std::min(std::max(res[b], 0), K);
+        tkv->len_ub[b] -= K - a;
+        dkv->len_ub[b] -= K - a;
+        int32_t *o = out_host + (size_t)b * (K + 2);
+        o[0] = a;
+        o[1] = res[batch + b];
+        for (int i = 0; i < K; ++i) o[2 + i] = dt[(size_t)b * K + i];
+    }
+    return check_launch();
+}
+
 // ------------------------------------------------------------------------------------------ shutdown
 
 extern "C" int ss_shutdown(void) {

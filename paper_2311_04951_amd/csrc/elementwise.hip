@@ -122,6 +122,33 @@ void launch_len_rollback(int32_t *len, const int32_t *n_accepted, int batch, int
     hipLaunchKernelGGL(len_rollback_kernel, dim3((batch + 63) / 64), dim3(64), 0, st, len, n_accepted, batch, M);
 }
 
+// The batched speculative step's token plumbing.  verify rows of sequence b = [its last committed token, d_1 .. d_K]
+// (the draft's tokens arrive call-major, [K][batch]); the same tokens sequence-major for the rejection step.
+__global__ void step_pack_tokens_kernel(const int32_t *feed, const int32_t *dtok, int batch, int K, int32_t *vt, int32_t *dbk) {
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= batch * (K + 1)) return;
+    const int b = idx / (K + 1), j = idx - b * (K + 1);
+    const int32_t v = j == 0 ? feed[2 * b + 1] : dtok[(size_t)(j - 1) * batch + b];
+    vt[idx] = v;
+    if (j > 0) dbk[b * K + j - 1] = v;
+}
+void launch_step_pack_tokens(const int32_t *feed, const int32_t *dtok, int batch, int K, int32_t *vt, int32_t *dbk, hipStream_t st) {
+    const int n = batch * (K + 1);
+    hipLaunchKernelGGL(step_pack_tokens_kernel, dim3((n + 63) / 64), dim3(64), 0, st, feed, dtok, batch, K, vt, dbk);
+}
+// the next step's draft feed of sequence b: its last two committed tokens = [verify row a_b, the token that followed]
+__global__ void step_next_feed_kernel(const int32_t *vt, const int32_t *n_accepted, const int32_t *next, int batch, int K, int32_t *feed) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= batch) return;
+    int a = n_accepted[b];
+    a = a < 0 ? 0 : (a > K ? K : a);
+    feed[2 * b] = vt[b * (K + 1) + a];
+    feed[2 * b + 1] = next[b];
+}
+void launch_step_next_feed(const int32_t *vt, const int32_t *n_accepted, const int32_t *next, int batch, int K, int32_t *feed, hipStream_t st) {
+    hipLaunchKernelGGL(step_next_feed_kernel, dim3((batch + 63) / 64), dim3(64), 0, st, vt, n_accepted, next, batch, K, feed);
+}
+
 // truncation from a device array (Section 4.4: dropping the stale tail of a cache is a length write)
 __global__ void len_truncate_kernel(int32_t *len, const int32_t *new_len, int batch, int32_t *status) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;

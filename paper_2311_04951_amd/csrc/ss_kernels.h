@@ -78,6 +78,10 @@ void launch_quantize_rows_int4(int dtype, const void *W, long long rows, long lo
 void launch_read_probe(const void *buf, size_t bytes, uint32_t *sink, hipStream_t st);
 void launch_len_add(int32_t *len, int batch, int delta, hipStream_t st);
 void launch_len_rollback(int32_t *len, const int32_t *n_accepted, int batch, int M, hipStream_t st);
+// batched speculative step: verify rows [batch][K+1] and draft tokens [batch][K] from feed [batch][2] and call-major draft tokens [K][batch]
+void launch_step_pack_tokens(const int32_t *feed, const int32_t *dtok, int batch, int K, int32_t *vt, int32_t *dbk, hipStream_t st);
+// ... and the next feed [batch][2] = [verify row n_accepted[b], next[b]]
+void launch_step_next_feed(const int32_t *vt, const int32_t *n_accepted, const int32_t *next, int batch, int K, int32_t *feed, hipStream_t st);
 // len[b] = min(len[b], max(new_len[b], 0)); a value above the current length sets bit 2 of *status (may be NULL)
 void launch_len_truncate(int32_t *len, const int32_t *new_len, int batch, int32_t *status, hipStream_t st);
 // fills n 32-bit words with `value` (a kernel, so that it may be recorded into a graph)

@@ -14,8 +14,8 @@ import time
 
 import torch
 
-from . import (KVCache, Model, SpecVerifyError, StepBuffers, ss_device_status, ss_draft_step, ss_greedy_accept, ss_kv_cache_rollback, ss_kv_cache_set_len, ss_softmax, ss_top_k_filter, ss_top_p_filter,
-               ss_speculative_accept, ss_speculative_step, ss_verify_forward)
+from . import (BatchedStepBuffers, KVCache, Model, SpecVerifyError, StepBuffers, ss_device_status, ss_draft_step, ss_greedy_accept, ss_kv_cache_get_len, ss_kv_cache_rollback, ss_kv_cache_set_len, ss_softmax, ss_top_k_filter, ss_top_p_filter,
+               ss_speculative_accept, ss_speculative_step, ss_speculative_step_batched, ss_verify_forward)
 
 
 def _check_status(*models):
@@ -179,3 +179,66 @@ def _speculative_generate_native(target, draft, prompt, n_new, K, temperature, u
     if not shared_kv:
         dkv.close()
     return out[:n_new], {"steps": step, "accepted": accepted, "loop_seconds": loop_s, "generated": len(out)}
+
+
+def speculative_generate_batched(target: Model, draft: Model, prompts, n_new: int, K: int, temperature: float,
+                                 u_draft=None, u_accept=None, max_seq=None, observer=None, top_p: float = 1.0, top_k: int = 0):
+    """Speculative sampling for a batch of sequences that accept different numbers of tokens per step (ragged cache
+    lengths, Section 4.4's bookkeeping per sequence): one ss_speculative_step_batched per step until every sequence
+    has n_new tokens.  prompts: list of token lists (>= 2 tokens each, any lengths).  u_draft [batch][steps][K],
+    u_accept [batch][steps][K+1] (temperature > 0): sequence b consumes row s in its step s, as a single-sequence run
+    would.  Returns (list of token lists, stats).  `observer(step, buf, results)` (optional) sees the step's device
+    buffers after each step."""
+    dev = torch.device("cuda")
+    B = len(prompts)
+    greedy = temperature == 0
+    cap = max_seq or (max(len(p) for p in prompts) + n_new + 2 * K + 20)   # (room for the padding rows of the ragged prefill)
+    tkv, dkv = KVCache(target, B, cap), KVCache(draft, B, cap)
+    # ragged prefill: sequence by sequence into its own slot of the batched caches (one-sequence views share the buffers)
+    for b, pr in enumerate(prompts):
+        if len(pr) < 2:
+            raise ValueError("a prompt needs at least two tokens")
+        for model, kv, upto in ((target, tkv, len(pr) - 1), (draft, dkv, len(pr) - 2)):
+            _prefill_slot(model, kv, b, list(pr[:upto]))
+    buf = BatchedStepBuffers(B, K, target.shape.vocab, [list(p[-2:]) for p in prompts], dev)
+    ud_all = ua_all = None
+    if not greedy:
+        ud_all = torch.as_tensor(u_draft, dtype=torch.float32).to(dev)      # [B][steps][K]
+        ua_all = torch.as_tensor(u_accept, dtype=torch.float32).to(dev)     # [B][steps][K+1]
+    out = [[] for _ in range(B)]
+    accepted = [[] for _ in range(B)]
+    step = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while min(len(o) for o in out) < n_new:
+        ud = None if greedy else ud_all[:, step].transpose(0, 1).contiguous()      # [K][B]
+        ua = None if greedy else ua_all[:, step].contiguous()                      # [B][K+1]
+        res = ss_speculative_step_batched(target, tkv, draft, dkv, buf, temperature, ud, ua, top_p=top_p, top_k=top_k)
+        if observer is not None:
+            observer(step, buf, res)
+        for b, (a, y, d) in enumerate(res):
+            out[b] += d[:a] + [y]
+            accepted[b].append(a)
+        step += 1
+    torch.cuda.synchronize()
+    loop_s = time.perf_counter() - t0
+    _check_status(target, draft)
+    tkv.close()
+    dkv.close()
+    return [o[:n_new] for o in out], {"steps": step, "accepted": accepted, "loop_seconds": loop_s, "generated": [len(o) for o in out]}
+
+
+def _prefill_slot(model: Model, kv: KVCache, b: int, tokens, chunk: int = 16):
+    """Feeds `tokens` of sequence b through the model into slot b of a batched cache: the other sequences take part with
+    a padding token and are set back to their lengths afterwards (a length write; their rows are overwritten later)."""
+    dev = torch.device("cuda")
+    B = kv.batch
+    lens = [int(x) for x in ss_kv_cache_get_len(kv).tolist()]
+    chunk = max(1, min(chunk, model.max_rows // B))       # every sequence takes part in a call
+    for i in range(0, len(tokens), chunk):
+        part = tokens[i:i + chunk]
+        t = torch.zeros((B, len(part)), dtype=torch.int32, device=dev)
+        t[b] = torch.tensor(part, dtype=torch.int32, device=dev)
+        ss_verify_forward(model, kv, t, len(part), logits=False)
+        lens[b] += len(part)
+        ss_kv_cache_set_len(kv, lens)
