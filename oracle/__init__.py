@@ -396,7 +396,7 @@ def speculative_generate(target: Model, draft: Model, prompt, n_new: int, K: int
                          temperature: float, u_draft=None, u_accept=None, max_seq=None, shared_kv=False, top_p=1.0, top_k=0):
     """Speculative sampling with two KV caches (Sections 3, 4.3, 4.4).
 
-    shared_kv (the other answer to Section 4.4's "do we have two separate caches?", for a draft made of
+    shared_kv (the other answer to the question Section 4.4 leaves open, whether the two models need separate caches; for a draft made of
     the target's first layers): the draft reads and writes the leading layers of the target's cache.
     Its K calls leave the cache at n-1+K positions; the length is set back to n-1 and the verify call
     rewrites those positions for every layer, so afterwards the cache is complete up to n+K for both

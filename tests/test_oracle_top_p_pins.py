@@ -1,4 +1,4 @@
-"""Pins of the oracle's top-p filter (Section 3 names "randomly selected from top-p" as a token selection
+"""Pins of the oracle's top-p filter (Section 3 names sampling from the top-p set as a token selection
 rule; the arithmetic is this build's reading: integer weights, ties by index, fp32 renormalisation).
 Brute force over all subsets on tiny rows, hand-made cases with exact arithmetic, the defining properties
 on random rows, and the distribution the rejection step emits when both models are filtered."""
