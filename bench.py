@@ -384,27 +384,30 @@ def batched_workload(si, sv, torch, dev, shape, packed, io, iters=5, B=8, L=4096
     dm.close()
     m.close()
     if int8:
-        # the same pass with int8 matrices (the KV cache stays bf16: it is most of this workload's bytes)
-        m = sv.Model(shape, io, max_rows=B * M, max_pos=L + 512, packed_layers=packed, int8_weights=True)
-        for _ in range(2):
-            run()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(iters):
-            run()
-        torch.cuda.synchronize()
-        dt8 = (time.perf_counter() - t0) / iters
-        sv.ss_profile_enable(m, True)
-        for _ in range(3):
-            run()
-        torch.cuda.synchronize()
-        prof = sv.ss_profile_read(m)
-        check_status(sv, m)
-        nb8 = nbytes - (shape.n_layers * layer_bytes(shape) + shape.vocab * shape.d_model * 2) // 2
-        out["int8_weights"] = {"ms_per_pass": dt8 * 1e3, "rows_per_s": B * M / dt8, "algorithmic_bytes": nb8, "GBps": nb8 / dt8 / 1e9,
-                               "frac_of_hbm_peak": nb8 / dt8 / HBM_PEAK,
-                               "class_ms_per_pass": {k: round(ms / 3, 3) for k, (ms, n) in prof.items() if n}}
-        m.close()
+        # the same pass with quantised matrices (the KV cache stays bf16: it is most of this workload's bytes); int4 streams
+        # its matrices once per 16 rows (five times here)
+        wb16 = shape.n_layers * layer_bytes(shape) + shape.vocab * shape.d_model * 2
+        for name, kw, wbytes in (("int8_weights", {"int8_weights": True}, wb16 // 2), ("int4_weights", {"int4_weights": True}, wb16 // 4 + wb16 // 2 // 128 * 4)):
+            m = sv.Model(shape, io, max_rows=B * M, max_pos=L + 512, packed_layers=packed, **kw)
+            for _ in range(2):
+                run()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(iters):
+                run()
+            torch.cuda.synchronize()
+            dtq = (time.perf_counter() - t0) / iters
+            sv.ss_profile_enable(m, True)
+            for _ in range(3):
+                run()
+            torch.cuda.synchronize()
+            prof = sv.ss_profile_read(m)
+            check_status(sv, m)
+            nbq = nbytes - wb16 + wbytes
+            out[name] = {"ms_per_pass": dtq * 1e3, "rows_per_s": B * M / dtq, "algorithmic_bytes": nbq, "GBps": nbq / dtq / 1e9,
+                         "frac_of_hbm_peak": nbq / dtq / HBM_PEAK,
+                         "class_ms_per_pass": {k: round(ms / 3, 3) for k, (ms, n) in prof.items() if n}}
+            m.close()
     kv.close()
     return out
 

@@ -200,7 +200,6 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
         const int mult = c.weight_quant == SS_QUANT_INT4_G128 ? 128 : 16;
         if (c.d_model % mult || (c.n_heads * c.head_dim) % mult || c.d_ff % mult)
             return fail(SS_EINVAL, "quantised weights: d_model, n_heads*head_dim and d_ff must be multiples of %d", mult);
-        if (c.weight_quant == SS_QUANT_INT4_G128 && c.max_rows > 16) return fail(SS_EINVAL, "int4 weights: calls of at most 16 rows (max_rows %d)", c.max_rows);
         if (w->lm_head && !w->s_head) return fail(SS_EINVAL, "quantised LM head without scales");
     }
     ss_model *m = new ss_model();

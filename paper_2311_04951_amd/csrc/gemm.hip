@@ -358,8 +358,11 @@ __global__ __launch_bounds__(NW * 64) void gemm_w4_kernel(GemmArgs a) {
         for (int v = 0; v < 4; ++v) ncol[t][v] = min(n0[t] + 4 * g + v, nrows_w - 1);
     }
     ActPlanes<T> act{const_cast<T *>(reinterpret_cast<const T *>(a.act)), a.act_plane, a.ld_act};
-    const size_t aoff = (size_t)c * a.ld_act + g * 32;
-    const bool row_live = c < a.R;
+    // calls of more than 16 rows: one workgroup per (column tile, row tile); every row tile streams the (quarter-size)
+    // weights again
+    const int rt = blockIdx.y;
+    const size_t aoff = (size_t)(rt * 16 + c) * a.ld_act + g * 32;
+    const bool row_live = rt * 16 + c < a.R;
 
     f32x4 acc[NT];
 #pragma unroll
@@ -404,7 +407,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_w4_kernel(GemmArgs a) {
         for (int v = 0; v < 4; ++v) red[wave][t][v][lane] = acc[t][v];
     __syncthreads();
     if (wave != 0) return;
-    tile_epilogue<T, EPI, NW>(a, red, n0, 0);
+    tile_epilogue<T, EPI, NW>(a, red, n0, rt);
 }
 
 // More than 16 rows (larger batches, prefill): the waves of a workgroup split the output columns instead
@@ -735,11 +738,11 @@ template <int EPI> static void launch_gemm_w8(const GemmArgs &a, hipStream_t st)
 // already holds 13 to 17 loads per lane: one of weights, eight of activations, the scales)
 template <int EPI> static void launch_gemm_w4(const GemmArgs &a, hipStream_t st) {
     const int tiles = EPI == EPI_QKV ? 3 * a.H * (a.hd / 32) : (a.N + 15) / 16;
-    hipLaunchKernelGGL((gemm_w4_kernel<EPI, 8, 1>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
+    hipLaunchKernelGGL((gemm_w4_kernel<EPI, 8, 1>), dim3(tiles, (a.R + 15) / 16), dim3(8 * 64), 0, st, a);
 }
 
 void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st) {
-    if (a.wscale && a.wbits == 4) { // int4 weights: the caller has checked bf16 planes, at most 16 rows, K % 128 == 0
+    if (a.wscale && a.wbits == 4) { // int4 weights: the caller has checked bf16 planes and K % 128 == 0
         switch (epi) {
         case EPI_STORE: launch_gemm_w4<EPI_STORE>(a, st); break;
         case EPI_RESID: launch_gemm_w4<EPI_RESID>(a, st); break;

@@ -85,12 +85,36 @@ def test_loops_with_int4_models():
     assert s1 == s2 and st1["accepted"] == st2["accepted"]
 
 
+@pytest.mark.parametrize("B,M", [(3, 8), (8, 9)])      # 24 and 72 rows per call: 2 and 5 row tiles
+def test_int4_model_in_launches_of_more_than_16_rows(B, M):
+    """Batched calls of an int4 model (one workgroup per column tile and row tile): whole forward with ragged
+    contexts, every sequence against the oracle's int4 model run on that sequence alone."""
+    shape = si.DecoderShape(2, 256, 4, 64, 768, 1000, dtype="bf16")
+    w = si.decoder_weights(shape, 52)
+    om = oracle.Model(shape, w, int4_weights=True)
+    gm = sv.Model(shape, weights_to_device(w), max_rows=B * M, max_pos=256, int4_weights=True)
+    lens = [37, 1, 150, 64, 9, 200, 77, 128][:B]
+    gkv = sv.KVCache(gm, B, 256)
+    toks = si.token_ids(52, f"t{B}x{M}", (B, M), shape.vocab).numpy().astype(np.int32)
+    refs = []
+    for b in range(B):
+        ctx = si.kv_context(shape, 52, f"ctx{b}", lens[b])
+        okv = om.new_kv(256)
+        okv.append_raw(ctx)
+        for l in range(shape.n_layers):
+            sv.ss_kv_cache_append(gkv, l, b, 0, ctx[l][0].to(dev()), ctx[l][1].to(dev()))
+        refs.append(om.forward(okv, toks[b]))
+    sv.ss_kv_cache_set_len(gkv, lens)
+    got = sv.ss_verify_forward(gm, gkv, torch.from_numpy(toks).to(dev()), M).cpu().numpy()
+    for b in range(B):
+        assert maxabs(got[b], refs[b]) < 2e-2, b
+    assert sv.ss_kv_cache_get_len(gkv).tolist() == [l + M for l in lens]
+    assert sv.ss_device_status(gm) == 0
+
+
 def test_int4_configurations_that_are_refused():
     shape = si.DecoderShape(1, 128, 4, 32, 384, 512, dtype="bf16")
     w = weights_to_device(si.decoder_weights(shape, 5))
-    with pytest.raises(sv.SpecVerifyError) as e:
-        sv.Model(shape, w, max_rows=32, max_pos=64, int4_weights=True)            # launches of more than 16 rows take int8 or storage-type matrices
-    assert e.value.code == sv.SS_EINVAL
     odd = si.DecoderShape(1, 128, 4, 32, 336, 512, dtype="bf16")                   # d_ff = 336: not a multiple of 128
     with pytest.raises(sv.SpecVerifyError):
         sv.Model(odd, weights_to_device(si.decoder_weights(odd, 5)), max_rows=16, max_pos=64, int4_weights=True)
