@@ -133,6 +133,19 @@ def cpu_baseline(si, torch, shape, packed, io, prompt_len, M, seconds_target=10.
     t0 = time.perf_counter()
     oracle.speculative_accept(p, q, dtok, u.numpy())
     t_acc = time.perf_counter() - t0
+    # the tiny fp32 pair end to end: 64 tokens, K = 4, temperature 1 and greedy (the configuration the oracle finishes in seconds)
+    tw = si.decoder_weights(si.TINY_TARGET, 0)
+    ot, od = oracle.Model(si.TINY_TARGET, tw), oracle.Model(si.TINY_DRAFT, si.decoder_weights(si.TINY_DRAFT, 100))
+    tp = si.token_ids(0, "prompt", (32,), si.TINY_TARGET.vocab).numpy().tolist()
+    t0 = time.perf_counter()
+    _, st_s = oracle.speculative_generate(ot, od, tp, 64, 4, 1.0, si.uniforms(0, "ud", (64, 4)).numpy(), si.uniforms(0, "ua", (64, 5)).numpy())
+    t_s = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    oracle.speculative_generate(ot, od, tp, 64, 4, 0.0)
+    t_g = time.perf_counter() - t0
+    out["tiny_pair"] = {"sampled_tokens_per_s": 64 / t_s, "greedy_tokens_per_s": 64 / t_g, "cores": threads,
+                        "sample": f"speculative loop of the tiny fp32 pair, prompt 32, 64 tokens, K 4: {t_s:.2f} s at temperature 1 "
+                                  f"({st_s['steps']} steps), {t_g:.2f} s greedy"}
     out["standalone_accept"] = {"us_per_sequence": (t_q + t_acc) / Bs * 1e6, "cores": threads,
                                 "sample": f"{Bs} of the workload's 64 sequences (K {K}, vocab {V}): softmax of the {2 * K + 1} rows per sequence, "
                                           f"the draft's samples and the rejection step; {t_q + t_acc:.1f} s"}
@@ -300,7 +313,9 @@ def paper_pair_leg(si, sv, torch, gen, dev, prompt_len=128, n_new=96, K=5):
            "draft_ms_per_token": 1e3 * t_draft1,
            "target_GBps": tb / t_target1 / 1e9, "draft_GBps": db / t_draft1 / 1e9,
            # accepted draft tokens per step at which a step (K draft tokens + one verify pass) yields as many tokens per second as one target token per pass
-           "break_even_accepted_per_step": t_step / t_target1 - 1.0}
+           "break_even_accepted_per_step": t_step / t_target1 - 1.0,
+           "parity_note": "timing only at this depth: these two widths are compared with the oracle on one layer each "
+                          "(tests/test_gpu_forward.py, reduced depth), not as 40- and 28-layer models"}
     for obj in (target, draft):
         obj.close()
     return out
