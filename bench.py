@@ -74,14 +74,15 @@ def cpu_baseline(si, torch, shape, packed, io, prompt_len, M, seconds_target=10.
              "layers": si.unpack_layers(shape, packed[:n_layers])}
         return s, oracle.Model(s, w)
 
-    def run(n_layers, ctx=prompt_len):
+    def run(n_layers, ctx=prompt_len, rows=M, reps=1):
         s, om = model(n_layers)
-        kv = om.new_kv(ctx + M + 1)
+        kv = om.new_kv(ctx + rows * reps + 1)
         kv.append_raw(si.kv_context(s, 1, "cpu_ctx", ctx))
-        toks = si.token_ids(1, "cpu_toks", (M,), s.vocab).numpy()
+        toks = si.token_ids(1, "cpu_toks", (rows,), s.vocab).numpy()
         t0 = time.perf_counter()
-        om.forward(kv, toks)
-        return time.perf_counter() - t0
+        for _ in range(reps):
+            om.forward(kv, toks)
+        return (time.perf_counter() - t0) / reps
 
     head_b = shape.vocab * d * 2
     full_b = shape.n_layers * layer_bytes(shape) + head_b
@@ -109,6 +110,9 @@ def cpu_baseline(si, torch, shape, packed, io, prompt_len, M, seconds_target=10.
     finally:
         oracle.set_num_threads(threads)
     out["single_thread"] = {"value": v1, "unit": "tokens/s", "cores": 1, "sample": s1}
+    # a draft step of the early-exit draft (first 2 layers + LM head, one row), the call a speculative step makes K times
+    nd = min(2, shape.n_layers)
+    out["draft_step"] = {"ms": 1e3 * run(nd, rows=1, reps=3), "cores": threads, "sample": f"3 one-row passes of the first {nd} layers + LM head"}
     # the single-layer workload: one layer, M rows against 1024 cached positions (layers_forward: no embedding, no head)
     s1l, om = model(1)
     kv = om.new_kv(1024 + M + 1)
