@@ -8,6 +8,7 @@ no CPU fallback - importing works without a GPU, calling does not.
 from __future__ import annotations
 
 import atexit
+import weakref
 import ctypes as C
 import os
 
@@ -125,10 +126,16 @@ def ss_freeze_allocations(on: bool):
     _check(lib().ss_freeze_allocations(int(bool(on))))
 
 
+_live = weakref.WeakSet()   # Model and KVCache objects that hold a handle
+
+
 def ss_shutdown():
-    """Destroys every live model and cache of the library (handles held by Python objects become no-ops)."""
+    """Destroys every live model and cache of the library.  The Python objects that held them forget their handles:
+    a later close() or garbage collection must not release a handle value that a new object has received since."""
     if _lib is not None:
         _lib.ss_shutdown()
+    for obj in list(_live):
+        obj.handle = None
     _workspaces.clear()
 
 
@@ -227,6 +234,7 @@ class Model:
         h = C.c_void_p()
         _check(lib().ss_model_create(C.byref(cfg), C.byref(w), C.byref(h)))
         self.handle = h
+        _live.add(self)
 
     def close(self):
         if getattr(self, "handle", None) and _lib is not None:
@@ -255,6 +263,7 @@ class KVCache:
         _check(lib().ss_kv_cache_create(model.handle, batch, max_seq, _dev(buf), buf.numel() * buf.element_size(), _stream(stream),
                                         C.byref(h)))
         self.handle = h
+        _live.add(self)
 
     def close(self):
         if getattr(self, "handle", None) and _lib is not None:

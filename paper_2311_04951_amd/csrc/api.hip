@@ -249,6 +249,7 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
         (void)hipGetDevice(&dev);
         m->mega_G = m->mega_G_max = c.weight_quant ? 0 : mega_grid(c.dtype, dev); // the persistent kernel streams storage-type matrices only
         m->mega_rows = mega_max_rows(c.dtype);
+        if (m->mega_G > 0 && mega_warm(c.dtype, nullptr) != hipSuccess) m->mega_G = m->mega_G_max = 0; // (first-launch set-up of both kernel variants happens here, where allocating is allowed)
         if (m->mega_G > 0 && c.n_layers >= 0) {
             std::vector<MegaPhase> prog;
             auto gain_after = [&](int l) { return l + 1 < c.n_layers ? m->layers[l + 1].g1 : m->gf; };
@@ -725,6 +726,7 @@ static int run_persistent(ss_model *m, ss_kv_cache *kv, const int32_t *tokens, f
     P.phases = with_head ? m->prog_full : m->prog_nohead;
     P.n_phases = with_head ? m->n_full : m->n_nohead;
     P.dtype = c.dtype;
+    P.large_slab = mega_wants_large_slab(c.dtype, c.d_model, c.d_ff) ? 1 : 0;
     P.d = c.d_model; P.H = c.n_heads; P.hd = c.head_dim; P.F = c.d_ff; P.V = c.vocab;
     P.R = batch * M; P.B = batch; P.M = M;
     P.eps = c.rms_eps;

@@ -46,7 +46,13 @@ namespace ss {
 
 constexpr int MNW = MEGA_THREADS / 64; // wavefronts per workgroup
 constexpr int CH = 4;                  // 128-byte steps per chunk per wave (8 loads = 8 KB per wave)
-constexpr int SLAB_CK = 8192 / (CH * MNW * 128); // chunks per LDS activation slab (8 KB of K per row)
+// Chunks per LDS activation slab: a template parameter SCK of the kernel, chosen per launch.  4 (8 KB of K per hidden row)
+// always fits the rows the kernel takes; 6 (12 KB) is taken when the host finds that it saves slab trips for the model's
+// shapes (mega_wants_large_slab) and the rows are few enough for LDS (<= 6 rows of a bf16 model): with d_model = 5120 a
+// weight row then fits one slab and a phase stops reloading the slab for every tile.  Every unit of a slab row is
+// requested whether K reaches it or not, so the larger slab costs half as many loads again where K is short: for the 7B
+// shape (K = 4096 in three of four phases) it is 1 % slower, for the 13B shape 24 - 30 % faster.
+constexpr int SCK_SMALL = 4, SCK_LARGE = 6;
 constexpr int RING = 2;                // chunks in flight per wave
 constexpr int CHUNK_ROW_BYTES = CH * MNW * 128; // bytes of a weight row one chunk covers (all waves)
 
@@ -137,13 +143,13 @@ template <typename T> __device__ __forceinline__ void cursor_begin(Cursor &c, co
 
 // Advance to the next position of the phase.  Positions are real chunks or padding: a "slab group"
 // (the chunks that share one LDS activation slab: the workgroup's whole share when K fits one slab, else
-// SLAB_CK chunks of a tile) is padded to a multiple of RING positions, so that rounds of RING steps
+// SCK chunks of a tile) is padded to a multiple of RING positions, so that rounds of RING steps
 // never straddle a slab reload or the end of the phase.  While `dummy` is set, (tile, ck, wp) already
 // describe the next real chunk.  Touches no memory.
-template <typename T> __device__ __forceinline__ void cursor_next(Cursor &c, int hd) {
+template <typename T, int SCK> __device__ __forceinline__ void cursor_next(Cursor &c, int hd) {
     ++c.idx;
     if (!c.dummy) {
-        const bool multi = c.nck > SLAB_CK;
+        const bool multi = c.nck > SCK;
         bool group_end;
         if (++c.ck == c.nck) {
             c.ck = 0;
@@ -151,7 +157,7 @@ template <typename T> __device__ __forceinline__ void cursor_next(Cursor &c, int
             group_end = multi || c.tile == c.r.ntiles;
             if (c.tile < c.r.ntiles) cursor_tile<T>(c, hd);
         } else {
-            group_end = multi && c.ck % SLAB_CK == 0;
+            group_end = multi && c.ck % SCK == 0;
         }
         if (!group_end) return;
         if (c.idx % RING != 0) {
@@ -184,8 +190,8 @@ __device__ __forceinline__ void issue_chunk(const Cursor &c, bool valid, const c
         }
 }
 
-constexpr int SLAB_ROW_BYTES = SLAB_CK * CH * MNW * 128; // 8192: the K range one slab covers, per hidden row
-constexpr int SLAB_PITCH = SLAB_ROW_BYTES + 48; // padded against LDS bank conflicts between rows
+__host__ __device__ constexpr int slab_row_bytes(int sck) { return sck * CH * MNW * 128; } // the K range one slab covers, per hidden row
+__host__ __device__ constexpr int slab_pitch(int sck) { return slab_row_bytes(sck) + 48; }    // padded against LDS bank conflicts between rows
 
 // LDS: [ union: activation slab | attention merge area ][ red ][ small ]
 constexpr int STASH_TILES = 6; // reduced tiles kept in LDS until the epilogue flush
@@ -463,12 +469,12 @@ static_assert(MEGA_THREADS / 32 * 2 >= 16, "two halves of the scale loads cover 
 // bf16_rne and the fp32 arithmetic produce other NaNs at most), so a unit that still shows the pattern
 // has not arrived and is simply loaded again (bounded).  Each element is validated on its own, so no
 // ordering between different stores is assumed.  The resets ride on causality, see clear_outputs().
-constexpr int SLAB_UNITS = SLAB_ROW_BYTES / 16 / MEGA_THREADS; // 16-byte units per thread and slab row
-template <int NPR> struct SlabLoads { // NPR: (plane, row) pairs per batch
-    u32x4 v[NPR][SLAB_UNITS]; // [(plane, row) pair][unit]
+__host__ __device__ constexpr int slab_units(int sck) { return slab_row_bytes(sck) / 16 / MEGA_THREADS; } // 16-byte units per thread and slab row
+template <int NPR, int SCK> struct SlabLoads { // NPR: (plane, row) pairs per batch
+    u32x4 v[NPR][slab_units(SCK)]; // [(plane, row) pair][unit]
     ScaleLoads sl;
 };
-static_assert(10 * SLAB_UNITS < 31, "one mask bit per unit of a batch, bit 31 for the row scales");
+static_assert(slab_row_bytes(SCK_SMALL) % (16 * MEGA_THREADS) == 0 && slab_row_bytes(SCK_LARGE) % (16 * MEGA_THREADS) == 0, "whole units per thread");
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 // running maximum that ends at all ones iff some element seen was the "not written yet" pattern
@@ -489,7 +495,7 @@ __device__ __forceinline__ void store_unset(float *p) { st_coh(p, u2f(0xffffffff
 // Unit (i, h2) of a batch that starts at (plane, row) pair pr0: byte offset of its 16 bytes in the source
 // planes, clamped to a valid address when the unit does not exist (pair beyond the slab rows, row
 // without data, K tail); false: it does not exist and counts as zeros.
-template <typename T>
+template <typename T, int SCK>
 __device__ __forceinline__ bool slab_unit(const MegaCall &P, const MegaPhase &ph, const ActPlanes<T> &src, int slab, int pr, int h2,
                                           uint32_t &byte_off) {
     constexpr int PER16 = 16 / (int)sizeof(T); // elements per 16-byte unit
@@ -500,39 +506,39 @@ __device__ __forceinline__ bool slab_unit(const MegaCall &P, const MegaPhase &ph
     const int r = prc % rows, pl = prc / rows, rc = min(r, nlive - 1);
     const int brow = head ? P.head_row0 + rc * P.head_stride : rc;
     const int x = threadIdx.x + h2 * MEGA_THREADS;
-    const int k = slab * (SLAB_ROW_BYTES / (int)sizeof(T)) + x * PER16; // K is a multiple of the unit
+    const int k = slab * (slab_row_bytes(SCK) / (int)sizeof(T)) + x * PER16; // K is a multiple of the unit
     const bool valid = pr < nrow && r < nlive && k < ph.K;
     byte_off = (uint32_t)((pl * src.plane + (size_t)brow * src.ld + (k < ph.K ? k : 0)) * sizeof(T));
     return valid;
 }
 // All loads of a batch (with_scales: and of the row scales), unconditionally: the number of loads in
 // flight is a compile-time constant, so a later wait for them can leave younger loads in flight.
-template <typename T, int NPR>
+template <typename T, int NPR, int SCK>
 __device__ __forceinline__ void slab_issue(const MegaCall &P, const MegaPhase &ph, int slab, int pr0, int G, bool with_scales,
-                                           SlabLoads<NPR> &L) {
+                                           SlabLoads<NPR, SCK> &L) {
     const ActPlanes<T> src = act_planes<T>(P, ph.act_src);
     if (with_scales) scales_issue(P, nsq_set(P, ph.act_src, G), G, false, L.sl);
 #pragma unroll
     for (int i = 0; i < NPR; ++i)
 #pragma unroll
-        for (int h2 = 0; h2 < SLAB_UNITS; ++h2) {
+        for (int h2 = 0; h2 < slab_units(SCK); ++h2) {
             uint32_t off;
-            slab_unit<T>(P, ph, src, slab, pr0 + i, h2, off);
+            slab_unit<T, SCK>(P, ph, src, slab, pr0 + i, h2, off);
             L.v[i][h2] = ld16_coh_buf(src.base, off);
         }
 }
 // true: something this lane loaded still shows the "not written yet" pattern
-template <typename T, int NPR>
+template <typename T, int NPR, int SCK>
 __device__ __forceinline__ bool slab_unset(const MegaCall &P, const MegaPhase &ph, int slab, int pr0, int G, bool with_scales,
-                                           const SlabLoads<NPR> &L) {
+                                           const SlabLoads<NPR, SCK> &L) {
     const ActPlanes<T> src = act_planes<T>(P, ph.act_src);
     uint32_t m = 0, ms = 0;
 #pragma unroll
     for (int i = 0; i < NPR; ++i)
 #pragma unroll
-        for (int h2 = 0; h2 < SLAB_UNITS; ++h2) {
+        for (int h2 = 0; h2 < slab_units(SCK); ++h2) {
             uint32_t off;
-            const bool valid = slab_unit<T>(P, ph, src, slab, pr0 + i, h2, off);
+            const bool valid = slab_unit<T, SCK>(P, ph, src, slab, pr0 + i, h2, off);
             const uint32_t um = unset_acc<T>(unset_acc<T>(L.v[i][h2][0], L.v[i][h2][1]), unset_acc<T>(L.v[i][h2][2], L.v[i][h2][3]));
             m = unset_acc<T>(m, valid ? um : 0u);
         }
@@ -549,9 +555,9 @@ __device__ __forceinline__ bool slab_unset(const MegaCall &P, const MegaPhase &p
 }
 // After a first slab_unset() found the pattern: wait (bounded) until nothing this wave loaded shows
 // it, loading again what does.  false: gave up (the caller raises the abort flag).
-template <typename T, int NPR>
+template <typename T, int NPR, int SCK>
 __device__ __forceinline__ bool slab_retry(const MegaCall &P, const MegaPhase &ph, int slab, int pr0, int G, bool with_scales,
-                                           SlabLoads<NPR> &L) {
+                                           SlabLoads<NPR, SCK> &L) {
     const ActPlanes<T> src = act_planes<T>(P, ph.act_src);
     for (unsigned spins = 0; spins < P.spin_limit; ++spins) {
         if (__hip_atomic_load(P.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) return false;
@@ -559,17 +565,17 @@ __device__ __forceinline__ bool slab_retry(const MegaCall &P, const MegaPhase &p
 #pragma unroll
         for (int i = 0; i < NPR; ++i)
 #pragma unroll
-            for (int h2 = 0; h2 < SLAB_UNITS; ++h2) {
+            for (int h2 = 0; h2 < slab_units(SCK); ++h2) {
                 uint32_t off;
-                if (slab_unit<T>(P, ph, src, slab, pr0 + i, h2, off) && unit_unset<T>(L.v[i][h2])) L.v[i][h2] = ld16_coh_buf(src.base, off);
+                if (slab_unit<T, SCK>(P, ph, src, slab, pr0 + i, h2, off) && unit_unset<T>(L.v[i][h2])) L.v[i][h2] = ld16_coh_buf(src.base, off);
             }
-        if (!__any(slab_unset<T>(P, ph, slab, pr0, G, with_scales, L))) return true;
+        if (!__any(slab_unset<T, NPR, SCK>(P, ph, slab, pr0, G, with_scales, L))) return true;
     }
     return false;
 }
-template <typename T, int NPR>
+template <typename T, int NPR, int SCK>
 __device__ __forceinline__ void slab_finish(const MegaCall &P, const MegaPhase &ph, int slab, int pr0, int G, bool with_scales,
-                                            const SlabLoads<NPR> &L, MegaSmem &sm) {
+                                            const SlabLoads<NPR, SCK> &L, MegaSmem &sm) {
     const ActPlanes<T> src = act_planes<T>(P, ph.act_src);
     const int nrow = Traits<T>::PLANES * P.slab_rows;
     if (with_scales) scales_finish(P, nsq_set(P, ph.act_src, G), G, L.sl, sm);
@@ -578,11 +584,11 @@ __device__ __forceinline__ void slab_finish(const MegaCall &P, const MegaPhase &
         const int pr = pr0 + i;
         if (pr < nrow) {
 #pragma unroll
-            for (int h2 = 0; h2 < SLAB_UNITS; ++h2) {
+            for (int h2 = 0; h2 < slab_units(SCK); ++h2) {
                 uint32_t off;
-                const bool valid = slab_unit<T>(P, ph, src, slab, pr, h2, off);
+                const bool valid = slab_unit<T, SCK>(P, ph, src, slab, pr, h2, off);
                 const int x = threadIdx.x + h2 * MEGA_THREADS;
-                *reinterpret_cast<u32x4 *>(sm.u + (size_t)pr * SLAB_PITCH + x * 16) = valid ? L.v[i][h2] : zero16();
+                *reinterpret_cast<u32x4 *>(sm.u + (size_t)pr * slab_pitch(SCK) + x * 16) = valid ? L.v[i][h2] : zero16();
             }
         }
     }
@@ -728,7 +734,7 @@ __device__ __forceinline__ void mma2(f32x4 &acc0, f32x4 &acc1, u32x4 w, const Ac
 }
 
 // multiply chunk c (weights in wbuf) into the tile accumulators; the B operand comes from the LDS slab
-template <typename T>
+template <typename T, int SCK>
 __device__ __forceinline__ void mma_chunk(const Cursor &c, const MegaCall &P, const u32x4 (&wbuf)[2 * CH], f32x4 &acc0, f32x4 &acc1,
                                           MegaSmem &sm) {
     constexpr int PL = Traits<T>::PLANES;
@@ -738,8 +744,8 @@ __device__ __forceinline__ void mma_chunk(const Cursor &c, const MegaCall &P, co
         acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
     }
     const bool blive = cc < P.slab_rows;
-    const unsigned char *lb = sm.u + (size_t)cc * SLAB_PITCH + (c.ck % SLAB_CK) * CHUNK_ROW_BYTES + wave * 128 + g * 16;
-    const size_t plane_off = (size_t)P.slab_rows * SLAB_PITCH;
+    const unsigned char *lb = sm.u + (size_t)cc * slab_pitch(SCK) + (c.ck % SCK) * CHUNK_ROW_BYTES + wave * 128 + g * 16;
+    const size_t plane_off = (size_t)P.slab_rows * slab_pitch(SCK);
 #pragma unroll
     for (int i = 0; i < CH; ++i)
 #pragma unroll
@@ -804,8 +810,9 @@ __device__ __forceinline__ void flush_stash(const MegaCall &P, const MegaPhase &
 
 // ---------------------------------------------------------------- the kernel
 
-template <typename T>
+template <typename T, int SCK>
 __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCall P) {
+    static_assert(10 * slab_units(SCK) < 31, "one mask bit per unit of a batch, bit 31 for the row scales");
     extern __shared__ __align__(16) unsigned char smem_raw[];
     MegaSmem sm;
     sm.u = smem_raw;
@@ -849,7 +856,7 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
         asm volatile("" ::: "memory");
         issue_chunk(st.la, true, zeros, slot);
         asm volatile("" ::: "memory");
-        if (st.la.active) cursor_next<T>(st.la, P.hd);
+        if (st.la.active) cursor_next<T, SCK>(st.la, P.hd);
     };
 
     for (int p = 0; p < P.n_phases; ++p) {
@@ -898,8 +905,8 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
         auto run_segment = [&](int n_fill, bool last) {
             auto step = [&](auto fill_c, u32x4(&slot)[2 * CH]) {
                 const Cursor c = st.cc;
-                cursor_next<T>(st.cc, P.hd);
-                if (!c.dummy) mma_chunk<T>(c, P, slot, st.acc0, st.acc1, sm);
+                cursor_next<T, SCK>(st.cc, P.hd);
+                if (!c.dummy) mma_chunk<T, SCK>(c, P, slot, st.acc0, st.acc1, sm);
                 if (decltype(fill_c)::value) fill(slot);
                 if (!c.dummy && c.ck + 1 == c.nck) finish_tile(c.tile, st.acc0, st.acc1, st.tile_seq, nstash, sm);
             };
@@ -916,9 +923,9 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
         // One K slab of the B operand into LDS, in batches of 10 (plane, row) pairs, one memory round trip
         // each (5 rows of a bf16 model: one batch).
         // false: a bounded wait for the data ran out (every wave of the workgroup returns the same).
-        auto load_slab = [&](int slab, bool scales, bool fills, SlabLoads<10> &L) __attribute__((always_inline)) {
+        auto load_slab = [&](int slab, bool scales, bool fills, SlabLoads<10, SCK> &L) __attribute__((always_inline)) {
             bool ok = true;
-            slab_issue<T>(P, ph, slab, 0, G, scales, L);
+            slab_issue<T, 10, SCK>(P, ph, slab, 0, G, scales, L);
             asm volatile("" ::: "memory"); // keeps the compiler from fusing the two loops (load, wait, store per row)
             // The first look at the data is straight-line code behind the loads (once per branch), so it
             // waits for them with an exact count and leaves the younger weight prefetch in flight.
@@ -926,18 +933,18 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
             if (fills) { // the weight prefetch goes out behind the slab: loads return in order, and the slab is needed first
 #pragma unroll
                 for (int sl = 0; sl < RING; ++sl) fill(ring[sl]);
-                dirty = polled && __any(slab_unset<T>(P, ph, slab, 0, G, scales, L));
+                dirty = polled && __any(slab_unset<T, 10, SCK>(P, ph, slab, 0, G, scales, L));
             } else {
-                dirty = polled && __any(slab_unset<T>(P, ph, slab, 0, G, scales, L));
+                dirty = polled && __any(slab_unset<T, 10, SCK>(P, ph, slab, 0, G, scales, L));
             }
-            if (dirty) ok = slab_retry<T>(P, ph, slab, 0, G, scales, L);
+            if (dirty) ok = slab_retry<T, 10, SCK>(P, ph, slab, 0, G, scales, L);
             lds_barrier(); // every wave is done with the previous slab
-            slab_finish<T>(P, ph, slab, 0, G, scales, L, sm);
+            slab_finish<T, 10, SCK>(P, ph, slab, 0, G, scales, L, sm);
             if (Traits<T>::PLANES * P.slab_rows > 10) {
-                slab_issue<T>(P, ph, slab, 10, G, false, L);
+                slab_issue<T, 10, SCK>(P, ph, slab, 10, G, false, L);
                 asm volatile("" ::: "memory");
-                if (polled && ok && __any(slab_unset<T>(P, ph, slab, 10, G, false, L))) ok = slab_retry<T>(P, ph, slab, 10, G, false, L);
-                slab_finish<T>(P, ph, slab, 10, G, false, L, sm);
+                if (polled && ok && __any(slab_unset<T, 10, SCK>(P, ph, slab, 10, G, false, L))) ok = slab_retry<T, 10, SCK>(P, ph, slab, 10, G, false, L);
+                slab_finish<T, 10, SCK>(P, ph, slab, 10, G, false, L, sm);
             }
             if (!ok && lane == 0) {
                 sm.t->ok = 0;
@@ -947,7 +954,7 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
             lds_barrier();
             return sm.t->ok != 0;
         };
-        const bool multi_slab = st.cc.nck > SLAB_CK;
+        const bool multi_slab = st.cc.nck > SCK;
         const bool clears = P.data_sync && ph.clear_phase >= 0;
         st.es.rowsq = 0.f;
         if (st.cc.active) {
@@ -1012,8 +1019,8 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
         while (st.cc.active) {
             // one segment = rounds that share an LDS slab and fit the stash
             const Cursor &cc = st.cc;
-            const bool multi = cc.nck > SLAB_CK;
-            const int grp_end = min((cc.ck / SLAB_CK + 1) * SLAB_CK, cc.nck); // multi: end of the slab group
+            const bool multi = cc.nck > SCK;
+            const int grp_end = min((cc.ck / SCK + 1) * SCK, cc.nck); // multi: end of the slab group
             const int grp_chunks = multi ? grp_end - cc.ck : (cc.r.ntiles - cc.tile) * cc.nck - cc.ck;
             const int grp_rounds = (grp_chunks + RING - 1) / RING;
             const bool last_group = multi ? (cc.tile + 1 == cc.r.ntiles && grp_end == cc.nck) : true;
@@ -1021,10 +1028,10 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
             auto stash_room = [&]() { return multi ? STASH_TILES - nstash : ((STASH_TILES - nstash) * cc.nck - cc.ck) / RING; };
             const int n = min(grp_rounds, stash_room()); // >= 1: the stash is flushed below whenever no round fits
             const bool final_round = last_group && n == grp_rounds; // the phase ends with this segment
-            const int tag = (p << 8) | (cc.ck / SLAB_CK);
+            const int tag = (p << 8) | (cc.ck / SCK);
             if (st.slab_tag != tag) {
-                SlabLoads<10> L;
-                if (!load_slab(cc.ck / SLAB_CK, want_scales && cc.idx == 0, spec && cc.idx == 0, L)) return; // first slab of the phase: with the row scales
+                SlabLoads<10, SCK> L;
+                if (!load_slab(cc.ck / SCK, want_scales && cc.idx == 0, spec && cc.idx == 0, L)) return; // first slab of the phase: with the row scales
                 st.slab_tag = tag;
                 // the whole input has been seen once the first tile's last slab is in; the resets are acknowledged before the rounds start
                 if (clears && cc.tile == 0 && (!multi || grp_end == cc.nck)) clear_outputs<T>(P, P.phases[ph.clear_phase], wg, G);
@@ -1041,31 +1048,36 @@ __global__ __launch_bounds__(MEGA_THREADS) void verify_persistent_kernel(MegaCal
 constexpr size_t LDS_BYTES = 160 * 1024;
 constexpr size_t ATTN_BYTES = sizeof(AttnSmem<128, MNW>);
 
-// rows the LDS slab can hold (0: use the direct path) and the size of the slab / attention area
-static void smem_plan(int dtype, int rows, int &slab_rows, size_t &u_bytes) {
+// rows the LDS slab can hold (0: use the direct path), the chunks per slab and the size of the slab / attention area
+static void smem_plan(int dtype, int rows, bool want_large, int &slab_rows, int &sck, size_t &u_bytes) {
     const size_t planes = dtype ? 2 : 1;
     const size_t avail = LDS_BYTES - sizeof(MegaSmemTail) - 256;
-    const int max_rows = (int)(avail / (planes * SLAB_PITCH));
+    sck = (want_large && (size_t)rows * planes * slab_pitch(SCK_LARGE) <= avail) ? SCK_LARGE : SCK_SMALL;
+    const int max_rows = (int)(avail / (planes * slab_pitch(sck)));
     slab_rows = rows <= max_rows ? rows : 0;
-    u_bytes = std::max(ATTN_BYTES, (size_t)slab_rows * planes * SLAB_PITCH);
+    u_bytes = std::max(ATTN_BYTES, (size_t)slab_rows * planes * slab_pitch(sck));
     u_bytes = (u_bytes + 255) & ~(size_t)255;
 }
 
-static hipError_t ensure_smem_attr(int dtype) {
-    static bool attr_set[2] = {false, false};
-    const int i = dtype ? 1 : 0;
-    if (attr_set[i]) return hipSuccess;
-    const void *fn = dtype ? (const void *)verify_persistent_kernel<bf16_t> : (const void *)verify_persistent_kernel<float>;
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
-    if (e == hipSuccess) attr_set[i] = true;
+static const void *mega_fn(int dtype, int sck) {
+    if (dtype) return sck == SCK_LARGE ? (const void *)verify_persistent_kernel<bf16_t, SCK_LARGE> : (const void *)verify_persistent_kernel<bf16_t, SCK_SMALL>;
+    return sck == SCK_LARGE ? (const void *)verify_persistent_kernel<float, SCK_LARGE> : (const void *)verify_persistent_kernel<float, SCK_SMALL>;
+}
+
+static hipError_t ensure_smem_attr(int dtype, int sck) {
+    static bool attr_set[2][2] = {{false, false}, {false, false}};
+    const int i = dtype ? 1 : 0, j = sck == SCK_LARGE ? 1 : 0;
+    if (attr_set[i][j]) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute(mega_fn(dtype, sck), hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
+    if (e == hipSuccess) attr_set[i][j] = true;
     return e;
 }
 
 int mega_max_rows(int dtype) {
-    int slab_rows = 0;
+    int slab_rows = 0, sck = 0;
     size_t u_bytes = 0;
     for (int rows = 16; rows >= 1; --rows) {
-        smem_plan(dtype, rows, slab_rows, u_bytes);
+        smem_plan(dtype, rows, false, slab_rows, sck, u_bytes);
         if (slab_rows == rows) return rows;
     }
     return 0;
@@ -1074,24 +1086,57 @@ int mega_max_rows(int dtype) {
 int mega_grid(int dtype, int device) {
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) != hipSuccess) return 0;
-    if (ensure_smem_attr(dtype) != hipSuccess) return 0;
-    int per_cu = 0;
     const size_t smem = LDS_BYTES - 1024;
-    hipError_t e = dtype ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, verify_persistent_kernel<bf16_t>, MEGA_THREADS, smem)
-                         : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, verify_persistent_kernel<float>, MEGA_THREADS, smem);
-    if (e != hipSuccess || per_cu < 1) return 0;
+    for (int sck : {SCK_SMALL, SCK_LARGE}) { // both variants must fit one workgroup per compute unit
+        if (ensure_smem_attr(dtype, sck) != hipSuccess) return 0;
+        int per_cu = 0;
+        hipError_t e;
+        if (dtype) e = sck == SCK_LARGE ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, verify_persistent_kernel<bf16_t, SCK_LARGE>, MEGA_THREADS, smem)
+                                        : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, verify_persistent_kernel<bf16_t, SCK_SMALL>, MEGA_THREADS, smem);
+        else e = sck == SCK_LARGE ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, verify_persistent_kernel<float, SCK_LARGE>, MEGA_THREADS, smem)
+                                  : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, verify_persistent_kernel<float, SCK_SMALL>, MEGA_THREADS, smem);
+        if (e != hipSuccess || per_cu < 1) return 0;
+    }
     return prop.multiProcessorCount; // one workgroup per compute unit
+}
+
+// One launch of every variant of the kernel with an empty program (a workgroup that finds no phase touches no memory
+// and leaves): whatever the runtime sets up at a kernel's first launch (code object, per-lane scratch) then exists
+// before a caller freezes allocations, whichever variant its later calls pick.
+// Slab trips of a layer's four GEMM phases with either slab size (K in bytes: d_model three times, d_ff once); the
+// larger slab moves 1.5 times the bytes per trip.
+bool mega_wants_large_slab(int dtype, int d_model, int d_ff) {
+    const long esz = dtype ? 2 : 4;
+    auto trips = [&](int sck) {
+        const long sb = slab_row_bytes(sck);
+        return 3 * ((d_model * esz + sb - 1) / sb) + (d_ff * esz + sb - 1) / sb;
+    };
+    return 3 * trips(SCK_LARGE) < 2 * trips(SCK_SMALL);
+}
+
+hipError_t mega_warm(int dtype, hipStream_t st) {
+    for (int sck : {SCK_SMALL, SCK_LARGE}) {
+        hipError_t e = ensure_smem_attr(dtype, sck);
+        if (e != hipSuccess) return e;
+        MegaCall c{};
+        c.u_bytes = 256;
+        void *args[] = {&c};
+        e = hipLaunchKernel(mega_fn(dtype, sck), dim3(1), dim3(MEGA_THREADS), args, LDS_BYTES / 2 + 1024, st);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_mega(const MegaCall &call, int grid, hipStream_t st) {
     MegaCall c = call;
     size_t u_bytes;
-    smem_plan(c.dtype, std::max(c.R, c.head_rows), c.slab_rows, u_bytes);
+    int sck;
+    smem_plan(c.dtype, std::max(c.R, c.head_rows), c.large_slab != 0, c.slab_rows, sck, u_bytes);
     if (c.slab_rows <= 0) return hipErrorInvalidValue; // the hidden rows must fit the LDS slab (mega_max_rows)
     c.u_bytes = (int)u_bytes;
     void *args[] = {&c};
-    const void *fn = call.dtype ? (const void *)verify_persistent_kernel<bf16_t> : (const void *)verify_persistent_kernel<float>;
-    hipError_t e = ensure_smem_attr(call.dtype);
+    const void *fn = mega_fn(call.dtype, sck);
+    hipError_t e = ensure_smem_attr(call.dtype, sck);
     if (e != hipSuccess) return e;
     // An ordinary launch: the grid never exceeds the compute units (mega_grid) and a workgroup asks for more than half
     // of a compute unit's LDS, so at most one fits per unit and every workgroup becomes resident as soon as units are

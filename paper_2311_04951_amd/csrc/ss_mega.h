@@ -84,6 +84,7 @@ struct MegaCall {
     int data_sync;     // 1: phases marked SYNC_DATA* poll their input data instead of waiting at a barrier
     const void *zeros; // >= 64 zero bytes: the target of weight loads that have no data to fetch
     int slab_rows, u_bytes;       // set by launch_mega: rows held in the LDS slab, size of the slab area
+    int large_slab;               // host to launch_mega only: 12 KB of K per slab row pays for this model's shapes (if the rows fit LDS)
     unsigned long long *timeline; // optional [5*n_phases][G] device clock samples of every workgroup (NULL: off)
 };
 
@@ -94,5 +95,7 @@ constexpr int MEGA_THREADS = 256;
 int mega_grid(int dtype, int device);
 int mega_max_rows(int dtype);
 hipError_t launch_mega(const MegaCall &call, int grid, hipStream_t st);
+hipError_t mega_warm(int dtype, hipStream_t st); // launches every kernel variant once with an empty program
+bool mega_wants_large_slab(int dtype, int d_model, int d_ff); // 12 KB instead of 8 KB of K per slab row saves slab trips for these shapes
 
 } // namespace ss

@@ -368,7 +368,8 @@ def test_read_stream_probe_reports_a_plausible_rate():
 def test_single_layer_of_13b_and_3b_width_matches_oracle(d, H, F, persistent):
     """One bf16 layer at the widths of a 13B-shaped target and a 3B-shaped draft (the size ratio of the
     paper's Section 6 experiment), K = 5 (6 query rows) against 200 cached positions: weight rows of 10 KB
-    and 27 KB (two and four activation slabs in the persistent kernel), 20 and 12 output rows per workgroup."""
+    and 27 KB (at d_model 5120 the persistent kernel takes its 12 KB slabs: one and three slab trips; at 3072
+    its 8 KB slabs), 20 and 12 output rows per workgroup."""
     shape = si.DecoderShape(1, d, H, 128, F, 32000, dtype="bf16")
     lw = si.layer_weights(shape, seed=3, layer=0)
     w = {"embed": None, "gf": None, "lm_head": None, "layers": [lw]}
@@ -387,6 +388,33 @@ def test_single_layer_of_13b_and_3b_width_matches_oracle(d, H, F, persistent):
     ref = om.layers_forward(okv, h.numpy())
     assert maxabs(got, ref) < 2e-2
     assert maxabs(got, ref) < 2e-3
+    assert sv.ss_device_status(gm) == 0
+
+
+@pytest.mark.parametrize("M", [1, 3, 6, 7, 9])
+def test_persistent_kernel_at_13b_width_with_either_slab_size_matches_oracle(M):
+    """Two bf16 layers at d_model 5120 on the persistent kernel: up to 6 rows fit its 12 KB activation slabs (a
+    weight row of 10 KB in one slab), 7 and 9 rows fall back to 8 KB slabs (two slab groups per tile, reloaded for
+    every tile of a workgroup's share); both against the oracle, twice in a row on the same model."""
+    shape = si.DecoderShape(2, 5120, 40, 128, 13824, 32000, dtype="bf16")
+    w = {"embed": None, "gf": None, "lm_head": None, "layers": [si.layer_weights(shape, seed=4, layer=l) for l in range(2)]}
+    om = oracle.Model(shape, w)
+    gm = sv.Model(shape, weights_to_device(w), max_rows=16, max_pos=512)
+    set_path(gm, True)
+    L = 150
+    ctx = si.kv_context(shape, 4, "ctx", L)
+    gkv = sv.KVCache(gm, 1, L + 64)
+    for l in range(2):
+        sv.ss_kv_cache_append(gkv, l, 0, 0, ctx[l][0].to(dev()), ctx[l][1].to(dev()))
+    okv = om.new_kv(L + 64)
+    okv.append_raw(ctx)
+    h = si.normal(4, f"h{M}", (M, shape.d_model), 1.0)
+    ref = om.layers_forward(okv, h.numpy())
+    for _ in range(2):
+        sv.ss_kv_cache_set_len(gkv, [L])
+        got = sv.ss_decoder_layers_forward(gm, gkv, h.to(dev()).clone(), 1, M).cpu().numpy()
+        assert maxabs(got, ref) < 2e-2, M               # the stated bf16 bar; hidden rows reach |h| of about 10 after two layers
+        assert maxabs(got, ref) < 1e-3 * float(np.abs(ref).max()), M
     assert sv.ss_device_status(gm) == 0
 
 
