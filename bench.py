@@ -516,6 +516,31 @@ def main():
                                   "mean_accepted_per_step": sum(s3["accepted"]) / max(1, s3["steps"]),
                                   "ms_per_step": 1e3 * s3["loop_seconds"] / max(1, s3["steps"])}
 
+        # The same loop against a target whose layers behind the draft's two write only a tenth as much into the residual
+        # stream: the early-exit draft then predicts its target about as well as a trained draft does, which random
+        # weights cannot show (same shapes, same kernels, same bytes per pass; only the acceptance changes).
+        damped = si.damp_late_layers(packed, dshape.n_layers, 0.1)
+        t2 = sv.Model(shape, io, max_rows=16, max_pos=max_pos, packed_layers=damped)
+        sv.ss_model_set_persistent(t2, bool(args.persistent))
+        good = {}
+        n_gd = min(128, n_new)
+        ar2 = {}
+        gen.autoregressive_generate(t2, prompt, 48, T, si.uniforms(4, "uar", (48,)), stats=ar2)
+        for k2, t2v in ((4, 1.0), (8, 1.0), (4, 0.0)):
+            _, s5 = gen.speculative_generate(t2, draft, prompt, n_gd, k2, t2v, si.uniforms(4, f"ud{k2}", (n_gd, k2)), si.uniforms(4, f"ua{k2}", (n_gd, k2 + 1)))
+            good[f"K{k2}_{'greedy' if t2v == 0.0 else 'T1'}"] = {
+                "accepted_tokens_per_s": round(s5["generated"] / s5["loop_seconds"], 1),
+                "mean_accepted_per_step": round(sum(s5["accepted"]) / max(1, s5["steps"]), 3),
+                "ms_per_step": round(1e3 * s5["loop_seconds"] / max(1, s5["steps"]), 3),
+                "speedup_vs_autoregressive": round((s5["generated"] / s5["loop_seconds"]) / (48 / ar2["loop_seconds"]), 3)}
+        good["autoregressive_tokens_per_s"] = round(48 / ar2["loop_seconds"], 1)
+        good["workload"] = ("the 7B-shaped target with the O and down projections of layers 2..31 scaled by 0.1 (synthetic stand-in for a "
+                            "draft that predicts its target), same early-exit draft")
+        e2e["good_draft"] = good
+        check_status(sv, t2, draft)
+        t2.close()
+        del damped
+
     # ---- state for the verify-pass legs: prompt in the cache, real draft rows from the draft model
     total_steps = args.warmup + 2 * args.steps + 4
     tkv = sv.KVCache(target, 1, prompt_len + M * total_steps + 16)

@@ -131,6 +131,23 @@ def packed_7b(seed: int, n_layers: int, device="cpu"):
     return packed_decoder(DecoderShape(**{**FULL_7B.as_dict(), "n_layers": n_layers}), seed, device)
 
 
+def damp_late_layers(packed, first: int, factor: float):
+    """A second set of packed layers in which every layer from `first` on writes `factor` times as much into the residual
+    stream (its O and down projections are scaled, rounded to the storage type again); all other tensors are shared.
+    With a small factor the target's first `first` layers + final norm + LM head predict the whole target the way a
+    trained draft predicts its target: a synthetic stand-in for a good draft."""
+    out = []
+    for l, p in enumerate(packed):
+        if l < first:
+            out.append(p)
+        else:
+            q = dict(p)
+            for k in ("wo", "wd"):
+                q[k] = (p[k].float() * factor).to(p[k].dtype)
+            out.append(q)
+    return out
+
+
 def unpack_layers(shape: DecoderShape, packed):
     """Packed layers -> the separate host matrices {wq, wk, wv, wo, wg, wu, wd, g1, g2} (views, same bits)."""
     W = shape.n_heads * shape.head_dim
