@@ -36,7 +36,7 @@
 // tile, so one thread finds both values of a pair in the same stashed tile.  RMSNorm is folded into the GEMMs: the producer packs
 // h * gain and publishes per-workgroup partial sums of squares, the consumer multiplies its outputs by
 // the row scale.  The hidden rows a phase multiplies with (B operand) are copied once per phase (per
-// 8 KB of K per row) into LDS, all loads of the copy in flight together.
+// 8 KB, or in the second instance of the kernel 12 KB, of K per row) into LDS, all loads of the copy in flight together.
 #include "attention_core.h"
 #include "ss_mega.h"
 #include <algorithm>
