@@ -49,7 +49,10 @@ __device__ __forceinline__ void attn_unit(const AttnArgs &a, int split, int h, i
 
     // One step covers KB positions.  The key and value chunks of a step do not depend on anything
     // computed here, so the next step's chunks are requested before the current step's arithmetic:
-    // a wave pays one memory round trip for its whole KV range instead of two per step.
+    // a wave pays one memory round trip for its whole KV range instead of two per step.  Plain loads, not
+    // non-temporal ones: a load instruction covers half of each line it touches (16 rows x 64 bytes), and the
+    // other half, which the next instruction (keys) or the neighbouring wave (values) asks for, should hit
+    // (8 % faster at 4096 cached positions, and 20 % fewer bytes fetched).
     struct Tile {
         u32x4 k[TPB][NKC];
         u32x4 v[NDT];
@@ -60,11 +63,11 @@ __device__ __forceinline__ void attn_unit(const AttnArgs &a, int split, int h, i
             const int pos_i = p0 + (c >> 2) * E + 4 * tt + (c & 3);
             const T *krow = Kb + (size_t)pos_i * HD + g * E;
 #pragma unroll
-            for (int kc = 0; kc < NKC; ++kc) t.k[tt][kc] = ld16_stream(krow + kc * KB);
+            for (int kc = 0; kc < NKC; ++kc) t.k[tt][kc] = ld16_global(krow + kc * KB);
         }
         const T *vrow = Vb + ((size_t)(p0 >> 6) * HD + c) * 64 + (p0 & 63) + g * E;
 #pragma unroll
-        for (int dt = 0; dt < NDT; ++dt) t.v[dt] = ld16_stream(vrow + (size_t)dt * 16 * 64);
+        for (int dt = 0; dt < NDT; ++dt) t.v[dt] = ld16_global(vrow + (size_t)dt * 16 * 64);
     };
     Tile cur, nxt;
     const int p_first = p_begin + wave * KB;

@@ -184,7 +184,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(GemmArgs a) {
                 const int k = (2 * (kp + s * NW) + j) * KB;
                 const bool ok = k + g * E < K; // K is a multiple of E
 #pragma unroll
-                for (int t = 0; t < NT; ++t) w[s][t][j] = ok ? ld16_stream(wrow[t] + k) : zero16();
+                for (int t = 0; t < NT; ++t) w[s][t][j] = ok ? ld16_global(wrow[t] + k) : zero16();
 #pragma unroll
                 for (int r = 0; r < RT; ++r) av[s][j][r] = (ok && row_live[r]) ? load_act(act, aoff[r] + k) : zero_act<T>();
             }
@@ -274,7 +274,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_w8_kernel(GemmArgs a) {
             const int k = (ks + s * NW) * 64;
             const bool ok = k + g * 16 < K; // K is a multiple of 16
 #pragma unroll
-            for (int t = 0; t < NT; ++t) w[s][t] = ok ? ld16_stream(wrow[t] + k) : zero16();
+            for (int t = 0; t < NT; ++t) w[s][t] = ok ? ld16_global(wrow[t] + k) : zero16();
 #pragma unroll
             for (int j = 0; j < 2; ++j) av[s][j] = (ok && row_live) ? load_act(act, aoff + k + 8 * j) : zero_act<T>();
         }
@@ -534,13 +534,13 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
         asm volatile("" ::: "memory");
     };
     auto w_load = [&](int sl, u32x4 (&w)[NT][WLD]) {
-        const int k0 = (s_lo + sl) * WIDE_KS;
+        const int k0 = (s_lo + min(sl, nslab - 1)) * WIDE_KS; // past the end: the last slab again (a cache hit; never multiplied)
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int kb = 0; kb < WLD; ++kb) {
                 const int k = k0 + kb * 4 * WE;
-                w[t][kb] = ld16_stream(wrow[t] + (size_t)min(k, K - (g + 1) * WE) * WB); // zeroed past K when it is used
+                w[t][kb] = ld16_global(wrow[t] + (size_t)min(k, K - (g + 1) * WE) * WB); // zeroed past K when it is used
             }
         asm volatile("" ::: "memory");
     };
@@ -555,26 +555,23 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
 #pragma unroll
             for (int t = 0; t < NT; ++t) acc[h][r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // Activation slabs are requested two steps ahead (three LDS buffers), weight slabs WDW - 1 steps
-    // ahead (registers).  A step issues [slab sl+2 -> LDS, weights sl+WDW-1 -> registers]; buffers and
-    // register sets are compile-time choices, so the step sequence is unrolled over WDW (a multiple of 3) steps.
-    constexpr int WDW = 3; // deeper weight rings (6) were measured and are slower
-    const int nstep = (nslab + WDW - 1) / WDW * WDW;
-    u32x4 wring[WDW][NT][WLD];
-#pragma unroll
-    for (int j = 0; j < WDW - 3; ++j) w_load(j, wring[j]);
+    // Activation slabs are requested two steps ahead (three LDS buffers), and so are the weight slabs (three
+    // register sets; deeper weight rings were measured and are slower).  A step issues [slab sl+2 -> LDS,
+    // weights sl+2 -> registers]; buffers and register sets are compile-time choices, so the loop below is
+    // unrolled over three steps and the last one or two steps of a slab count that is not a multiple of
+    // three are written out after it (no idle step: the projections with K split four ways have 8 steps).
+    u32x4 wring[3][NT][WLD];
     slab_dma(0, slab0);
-    w_load(WDW - 3, wring[WDW - 3]);
+    w_load(0, wring[0]);
     slab_dma(1, slab1);
-    w_load(WDW - 2, wring[WDW - 2]);
+    w_load(1, wring[1]);
     auto step = [&](int sl, const unsigned char *cur, unsigned char *fill, u32x4 (&wcur)[NT][WLD], u32x4 (&wfill)[NT][WLD]) {
         // this wave's part of slab sl and its weight slab sl have landed: the only younger loads are
         // those of the previous step (slab sl+1, weights sl+1)
-        static_assert(WDW == 3, "the wait below counts one step of younger loads");
         wait_vmcnt_at_most<DPW + WN>();
         wide_barrier(); // everybody's part has landed, and everybody is done reading `fill` (slab sl - 1)
         slab_dma(sl + 2, fill);
-        w_load(sl + WDW - 1, wfill);
+        w_load(sl + 2, wfill);
         const unsigned char *base = cur + (size_t)c * WIDE_SLAB_BYTES;
         // the LDS reads of k-block kb+1 are issued before the MFMAs of k-block kb (the scheduling
         // barriers keep the compiler from sinking them next to their uses, which serialises every
@@ -605,14 +602,14 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    for (int s0 = 0; s0 < nstep; s0 += WDW) {
-#pragma unroll
-        for (int j = 0; j < WDW; j += 3) {
-            step(s0 + j, slab0, slab2, wring[j], wring[(j + WDW - 1) % WDW]);
-            step(s0 + j + 1, slab1, slab0, wring[j + 1], wring[j % WDW]);
-            step(s0 + j + 2, slab2, slab1, wring[j + 2], wring[(j + 1) % WDW]);
-        }
+    int s0 = 0;
+    for (; s0 + 3 <= nslab; s0 += 3) {
+        step(s0, slab0, slab2, wring[0], wring[2]);
+        step(s0 + 1, slab1, slab0, wring[1], wring[0]);
+        step(s0 + 2, slab2, slab1, wring[2], wring[1]);
     }
+    if (s0 < nslab) step(s0, slab0, slab2, wring[0], wring[2]);
+    if (s0 + 1 < nslab) step(s0 + 1, slab1, slab0, wring[1], wring[0]);
     wait_vmcnt_at_most<0>(); // nothing may still be landing in LDS when the workgroup ends
     if (!tile_live) return;
     const int row_tiles = (a.R + 15) / 16;

@@ -54,7 +54,11 @@ template <> __device__ __forceinline__ bf16_t to_storage<bf16_t>(float x) { retu
 template <> __device__ __forceinline__ float to_storage<float>(float x) { return x; }
 
 __device__ __forceinline__ u32x4 ld16(const void *p) { return *reinterpret_cast<const u32x4 *>(p); }
-// streamed-once data (weights, cache): keep it from displacing the reusable operands in cache
+// non-temporal load.  Measured on the 7B-shaped layer: where a wave-level load covers half of each 128-byte line
+// it touches (16 rows x 64 bytes: the MFMA operand layout of bf16 and int8 matrices and of the cache) the plain
+// load is the faster one (the other half of the line, asked for by the next instruction or by a neighbouring wave,
+// then hits; the counters showed 20 to 40 % more bytes fetched with the non-temporal form), so only the int4
+// kernel, whose loads cover whole lines, still uses this.
 __device__ __forceinline__ u32x4 ld16_stream(const void *p) {
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
 }
