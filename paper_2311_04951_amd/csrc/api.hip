@@ -597,11 +597,17 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
     nsplit = (Lmax + chunk - 1) / chunk;
 
     const int wbits = c.weight_quant == SS_QUANT_INT4_G128 ? 4 : 8;
+    // the two residual projections name the RMSNorm that follows them: a launcher that has a row-wise last launch
+    // anyway (split K) writes the normalised planes there and says so
+    bool normed = false;
+    auto with_norm = [&](GemmArgs &g, const float *gain) {
+        g.norm_gain = gain; g.norm_act = m->act_a; g.norm_act_plane = pl * d; g.norm_ld = d; g.norm_eps = c.rms_eps;
+    };
     for (int l = 0; l < c.n_layers; ++l) {
         const ss_layer_weights &L = m->layers[l];
         char *kc = (char *)kv->k + kv->layer_elems * l * kv->esz;
         char *vc = (char *)kv->v + kv->layer_elems * l * kv->esz;
-        {
+        if (!normed) {
             ProfScope ps(m, PT_NORM, st);
             launch_rmsnorm_pack(c.dtype, m->h, L.g1, R, d, c.rms_eps, m->act_a, pl * d, d, st);
         }
@@ -635,11 +641,12 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
         o.W = L.wo; o.N = d; o.K = W; o.wscale = c.weight_quant ? L.so : nullptr; o.wbits = wbits;
         o.act = m->act_o; o.act_plane = pl * W; o.ld_act = W; o.R = R;
         o.out = m->h; o.resid = m->h; o.ldo = d;
+        with_norm(o, L.g2);
         {
             ProfScope ps(m, PT_OPROJ, st);
-            launch_gemm(c.dtype, EPI_RESID, o, st);
+            normed = launch_gemm(c.dtype, EPI_RESID, o, st);
         }
-        {
+        if (!normed) {
             ProfScope ps(m, PT_NORM, st);
             launch_rmsnorm_pack(c.dtype, m->h, L.g2, R, d, c.rms_eps, m->act_a, pl * d, d, st);
         }
@@ -658,9 +665,10 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
         dn.W = L.wd; dn.N = d; dn.K = F; dn.wscale = c.weight_quant ? L.sd : nullptr; dn.wbits = wbits;
         dn.act = m->act_z; dn.act_plane = pl * F; dn.ld_act = F; dn.R = R;
         dn.out = m->h; dn.resid = m->h; dn.ldo = d;
+        if (l + 1 < c.n_layers) with_norm(dn, m->layers[l + 1].g1); // (the final norm belongs to the head: it may gather rows)
         {
             ProfScope ps(m, PT_DOWN, st);
-            launch_gemm(c.dtype, EPI_RESID, dn, st);
+            normed = launch_gemm(c.dtype, EPI_RESID, dn, st);
         }
     }
     launch_len_add(kv->len_dev, batch, M, st);

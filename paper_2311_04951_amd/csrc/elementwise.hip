@@ -1,6 +1,7 @@
 // Small row-wise kernels of the verify pass: embedding gather, RMSNorm (+ packing of the result as
 // the activation planes the next GEMM reads), cache-length bookkeeping (Section 4.4: truncation is a
 // length write) and the raw cache append used to build an existing context.
+#include <cstdlib>
 #include "ss_device.h"
 #include "ss_kernels.h"
 #include <algorithm>
@@ -42,15 +43,21 @@ __device__ __forceinline__ void store_act4(const ActPlanes<bf16_t> &a, size_t of
 __device__ __forceinline__ void store_act4(const ActPlanes<float> &a, size_t off, const float (&x)[4]) {
     *reinterpret_cast<float4 *>(a.base + off) = make_float4(x[0], x[1], x[2], x[3]);
 }
-template <typename T>
+// SPLITK: the row is first completed, x = h[r] + (parts[0][r] + parts[1][r] + ...) with the splits added in order, and
+// stored back to h; without a gain that is all (the norm below is the same code either way, so a fused launch and
+// the two separate ones give the same bits).
+constexpr int SPLITK_MAX = 4; // splits the fused form can sum (the wide GEMM never makes more)
+template <typename T, bool SPLITK>
 __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(const float *h, const float *gain, int row0, int row_stride,
-                                                           int d, float eps, ActPlanes<T> act) {
+                                                           int d, float eps, ActPlanes<T> act, const float *parts,
+                                                           int ksplit, size_t part_stride, float *h_out) {
     constexpr int MAXV = 8; // float4 per thread kept in registers
     const int r = blockIdx.x;
     const float *x = h + (size_t)(row0 + r * row_stride) * d;
     const bool vec = d % 4 == 0 && d <= 256 * 4 * MAXV && act.ld % 4 == 0 && act.plane % 4 == 0 &&
                      (reinterpret_cast<uintptr_t>(h) & 15) == 0 && (reinterpret_cast<uintptr_t>(gain) & 15) == 0 &&
-                     (reinterpret_cast<uintptr_t>(act.base) & 15) == 0;
+                     (reinterpret_cast<uintptr_t>(act.base) & 15) == 0 &&
+                     (!SPLITK || ((reinterpret_cast<uintptr_t>(parts) & 15) == 0 && part_stride % 4 == 0));
     float4 v[MAXV];
     float ss = 0.f;
     if (vec) {
@@ -59,9 +66,44 @@ __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(const float *h, const
             const int e4 = threadIdx.x + 256 * j;
             v[j] = e4 * 4 < d ? reinterpret_cast<const float4 *>(x)[e4] : make_float4(0.f, 0.f, 0.f, 0.f);
         }
+        if constexpr (SPLITK) {
+            // every partial is requested before the first one is used (at most SPLITK_MAX splits)
+            float4 p[MAXV][SPLITK_MAX];
+#pragma unroll
+            for (int j = 0; j < MAXV; ++j)
+#pragma unroll
+                for (int z = 0; z < SPLITK_MAX; ++z) {
+                    const int e4 = threadIdx.x + 256 * j;
+                    p[j][z] = (e4 * 4 < d && z < ksplit) ? reinterpret_cast<const float4 *>(parts + z * part_stride + (size_t)r * d)[e4]
+                                                         : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+            for (int j = 0; j < MAXV; ++j) {
+                const int e4 = threadIdx.x + 256 * j;
+                if (e4 * 4 < d) {
+                    float4 s4 = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                    for (int z = 0; z < SPLITK_MAX; ++z)
+                        if (z < ksplit) {
+                            s4.x += p[j][z].x; s4.y += p[j][z].y; s4.z += p[j][z].z; s4.w += p[j][z].w;
+                        }
+                    v[j].x += s4.x; v[j].y += s4.y; v[j].z += s4.z; v[j].w += s4.w;
+                    reinterpret_cast<float4 *>(h_out + (size_t)r * d)[e4] = v[j];
+                }
+            }
+            if (!gain) return;
+        }
 #pragma unroll
         for (int j = 0; j < MAXV; ++j) ss += (v[j].x * v[j].x + v[j].y * v[j].y) + (v[j].z * v[j].z + v[j].w * v[j].w);
     } else {
+        if constexpr (SPLITK) {
+            for (int e = threadIdx.x; e < d; e += 256) {
+                float s1 = 0.f;
+                for (int z = 0; z < ksplit; ++z) s1 += parts[z * part_stride + (size_t)r * d + e];
+                h_out[(size_t)r * d + e] = x[e] + s1; // x is this row of h_out; the same thread reads it back below
+            }
+            if (!gain) return;
+        }
         for (int e = threadIdx.x; e < d; e += 256) ss += x[e] * x[e];
     }
     ss = wave_sum(ss);
@@ -89,16 +131,29 @@ void launch_rmsnorm_pack_rows(int dtype, const float *h, const float *gain, int 
                               int d, float eps, void *act, size_t act_plane, int ld_act, hipStream_t st) {
     if (dtype) {
         ActPlanes<bf16_t> ap{(bf16_t *)act, act_plane, ld_act};
-        hipLaunchKernelGGL((rmsnorm_pack_kernel<bf16_t>), dim3(nrows), dim3(256), 0, st, h, gain, row0, row_stride, d, eps, ap);
+        hipLaunchKernelGGL((rmsnorm_pack_kernel<bf16_t, false>), dim3(nrows), dim3(256), 0, st, h, gain, row0, row_stride, d, eps, ap, nullptr, 0, (size_t)0, nullptr);
     } else {
         ActPlanes<float> ap{(float *)act, act_plane, ld_act};
-        hipLaunchKernelGGL((rmsnorm_pack_kernel<float>), dim3(nrows), dim3(256), 0, st, h, gain, row0, row_stride, d, eps, ap);
+        hipLaunchKernelGGL((rmsnorm_pack_kernel<float, false>), dim3(nrows), dim3(256), 0, st, h, gain, row0, row_stride, d, eps, ap, nullptr, 0, (size_t)0, nullptr);
     }
 }
 
 void launch_rmsnorm_pack(int dtype, const float *h, const float *gain, int R, int d, float eps, void *act,
                          size_t act_plane, int ld_act, hipStream_t st) {
     launch_rmsnorm_pack_rows(dtype, h, gain, R, 0, 1, d, eps, act, act_plane, ld_act, st);
+}
+
+void launch_splitk_resid_norm(int dtype, float *h, const float *parts, int ksplit, const float *gain, int R, int d,
+                              float eps, void *act, size_t act_plane, int ld_act, hipStream_t st) {
+    if (ksplit > SPLITK_MAX) abort(); // the caller's split count is bounded by the same constant
+    const size_t stride = (size_t)R * d;
+    if (dtype) {
+        ActPlanes<bf16_t> ap{(bf16_t *)act, act_plane, ld_act};
+        hipLaunchKernelGGL((rmsnorm_pack_kernel<bf16_t, true>), dim3(R), dim3(256), 0, st, h, gain, 0, 1, d, eps, ap, parts, ksplit, stride, h);
+    } else {
+        ActPlanes<float> ap{(float *)act, act_plane, ld_act};
+        hipLaunchKernelGGL((rmsnorm_pack_kernel<float, true>), dim3(R), dim3(256), 0, st, h, gain, 0, 1, d, eps, ap, parts, ksplit, stride, h);
+    }
 }
 
 __global__ void len_add_kernel(int32_t *len, int batch, int delta) {

@@ -16,6 +16,7 @@
 //   SWIGLU  silu(gate) * up     (gate tile + up tile in one workgroup) -> activation planes
 //   QKV     rotary embedding of q and k (pairs j, j + hd/2 sit in the two tiles), q -> activation
 //           planes, k and v -> KV cache at positions len[b] + i
+#include <type_traits>
 #include "ss_device.h"
 #include "ss_kernels.h"
 
@@ -624,7 +625,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
                 if constexpr (W8) out[t][v] *= a.wscale[min(n0[t] + 4 * g + v, nrows_w - 1)]; // linear: also right for split-K partials
             }
         if (a.ksplit > 1) {
-            if (rt0 + r < row_tiles) {
+            if (EPI == EPI_RESID && a.splitk_rows) { // plain rows [split][R][N]: the launch that follows works row by row
+                const int row = (rt0 + r) * 16 + c;
+                if (row < a.R)
+                    *reinterpret_cast<float4 *>(a.splitk_ws + ((size_t)blockIdx.z * a.R + row) * a.N + n0[0] + 4 * g) =
+                        make_float4(out[0][0], out[0][1], out[0][2], out[0][3]);
+            } else if (rt0 + r < row_tiles) {
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
 #pragma unroll
@@ -660,7 +666,10 @@ __global__ __launch_bounds__(64) void gemm_splitk_finish_kernel(GemmArgs a) {
 // 64 workgroups for a 4096-column projection).  K is then split over up to 4 workgroups whose partial
 // tiles a second small launch sums in a fixed order; the split count is the largest that still fits the
 // chip in one round, so the extra traffic (partials written and read once) stays a fraction of the weights.
-template <typename T, int EPI, int NW, int RT, bool W8 = false> static void launch_wide(const GemmArgs &a0, int tiles, int row_tiles, hipStream_t st) {
+// A residual projection (whole 16-column tiles, dense output rows) leaves its partials as plain rows, and the
+// second launch is the RMSNorm kernel with the sum over the splits in front: it completes h and, when the caller
+// named the norm that follows, writes that too (returns true then).
+template <typename T, int EPI, int NW, int RT, bool W8 = false> static bool launch_wide(const GemmArgs &a0, int tiles, int row_tiles, hipStream_t st) {
     constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
     constexpr int WIDE_KS = WIDE_SLAB_BYTES / (int)sizeof(T);
     GemmArgs a = a0;
@@ -678,35 +687,42 @@ template <typename T, int EPI, int NW, int RT, bool W8 = false> static void laun
             a.kslabs = per;
         }
     }
+    a.splitk_rows = EPI == EPI_RESID && a.ksplit > 1 && a.ksplit <= 4 && a.N % 16 == 0 && a.ldo == a.N && a.out == a.resid;
     hipLaunchKernelGGL((gemm_wide_kernel<T, EPI, NW, RT, W8>), dim3(gx, gy, a.ksplit), dim3(NW * 64), 0, st, a);
+    if (a.splitk_rows) {
+        launch_splitk_resid_norm(std::is_same<T, bf16_t>::value ? 1 : 0, a.out, a.splitk_ws, a.ksplit, a.norm_gain, a.R, a.N, a.norm_eps,
+                                 a.norm_act, a.norm_act_plane, a.norm_ld, st);
+        return a.norm_gain != nullptr;
+    }
     if (a.ksplit > 1) hipLaunchKernelGGL((gemm_splitk_finish_kernel<T, EPI>), dim3(tiles, row_tiles), dim3(64), 0, st, a);
+    return false;
 }
 
-template <typename T, int EPI, bool W8> static void launch_wide_any(const GemmArgs &a, int tiles, int row_tiles, hipStream_t st);
+template <typename T, int EPI, bool W8> static bool launch_wide_any(const GemmArgs &a, int tiles, int row_tiles, hipStream_t st);
 
-template <typename T, int EPI> static void launch_gemm_t(const GemmArgs &a, hipStream_t st) {
+template <typename T, int EPI> static bool launch_gemm_t(const GemmArgs &a, hipStream_t st) {
     int tiles;
     if (EPI == EPI_QKV) tiles = 3 * a.H * (a.hd / 32);
     else tiles = (a.N + 15) / 16;
     const int row_tiles = (a.R + 15) / 16;
     if (row_tiles <= 1) { // the verify pass proper: 8 waves split K, two steps in flight (measured: 3.5 % faster than 16 waves over a 7B-shaped pass)
         hipLaunchKernelGGL((gemm_kernel<T, EPI, 8, 2, 1>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
-        return;
+        return false;
     }
-    launch_wide_any<T, EPI, false>(a, tiles, row_tiles, st);
+    return launch_wide_any<T, EPI, false>(a, tiles, row_tiles, st);
 }
 
-template <typename T, int EPI, bool W8> static void launch_wide_any(const GemmArgs &a, int tiles, int row_tiles, hipStream_t st) {
+template <typename T, int EPI, bool W8> static bool launch_wide_any(const GemmArgs &a, int tiles, int row_tiles, hipStream_t st) {
     // larger batches and prefill chunks: waves split the columns; fewer waves per workgroup when the
     // matrix has few tiles, so that the launch still covers the chip
     constexpr bool FUSED = EPI == EPI_SWIGLU || EPI == EPI_QKV; // two weight tiles per wave: more registers
     const bool small = tiles < 8 * 128;
     if (row_tiles <= 2) {
-        if (small) launch_wide<T, EPI, 4, 2, W8>(a, tiles, row_tiles, st);
-        else launch_wide<T, EPI, 8, 2, W8>(a, tiles, row_tiles, st);
+        if (small) return launch_wide<T, EPI, 4, 2, W8>(a, tiles, row_tiles, st);
+        return launch_wide<T, EPI, 8, 2, W8>(a, tiles, row_tiles, st);
     } else if (row_tiles <= 3) {
-        if (small) launch_wide<T, EPI, 4, 3, W8>(a, tiles, row_tiles, st);
-        else launch_wide<T, EPI, 8, 3, W8>(a, tiles, row_tiles, st);
+        if (small) return launch_wide<T, EPI, 4, 3, W8>(a, tiles, row_tiles, st);
+        return launch_wide<T, EPI, 8, 3, W8>(a, tiles, row_tiles, st);
     } else {
         // one workgroup per compute unit fits: 3 waves per workgroup when that fills more of a 256-unit chip
         // in whole rounds than 4 (688 gate/up tiles: 230 workgroups instead of 172; 384 QKV tiles: 128, split in two)
@@ -715,20 +731,21 @@ template <typename T, int EPI, bool W8> static void launch_wide_any(const GemmAr
             const int ks = std::max(1, std::min(256 / std::max(wgs, 1), 4));
             return (double)(wgs * ks) / (double)((wgs * ks + 255) / 256 * 256);
         };
-        if ((small || FUSED) && fill(3) > fill(4) + 0.1) launch_wide<T, EPI, 3, 5, W8>(a, tiles, row_tiles, st);
-        else if (small || FUSED) launch_wide<T, EPI, 4, 5, W8>(a, tiles, row_tiles, st);
-        else launch_wide<T, EPI, 8, 5, W8>(a, tiles, row_tiles, st);
+        if ((small || FUSED) && fill(3) > fill(4) + 0.1) return launch_wide<T, EPI, 3, 5, W8>(a, tiles, row_tiles, st);
+        if (small || FUSED) return launch_wide<T, EPI, 4, 5, W8>(a, tiles, row_tiles, st);
+        return launch_wide<T, EPI, 8, 5, W8>(a, tiles, row_tiles, st);
     }
 }
 
 // 8 waves per workgroup and two steps in flight per wave: measured best on the 7B-shaped layer among
 // (4 | 8 | 16 waves) x (1..4 steps) - the registers go to the activation operands (four 16-byte loads per
 // weight load), so more steps in flight cost occupancy, and smaller workgroups give more of them per compute unit.
-template <int EPI> static void launch_gemm_w8(const GemmArgs &a, hipStream_t st) {
+template <int EPI> static bool launch_gemm_w8(const GemmArgs &a, hipStream_t st) {
     const int tiles = EPI == EPI_QKV ? 3 * a.H * (a.hd / 32) : (a.N + 15) / 16;
     const int row_tiles = (a.R + 15) / 16;
-    if (row_tiles <= 1) hipLaunchKernelGGL((gemm_w8_kernel<EPI, 8, 2>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
-    else launch_wide_any<bf16_t, EPI, true>(a, tiles, row_tiles, st);
+    if (row_tiles > 1) return launch_wide_any<bf16_t, EPI, true>(a, tiles, row_tiles, st);
+    hipLaunchKernelGGL((gemm_w8_kernel<EPI, 8, 2>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
+    return false;
 }
 
 // 8 waves, one step in flight: measured best of (4 | 8 | 16 waves) x (1 | 2 steps) on the 7B-shaped layer (a step
@@ -738,7 +755,7 @@ template <int EPI> static void launch_gemm_w4(const GemmArgs &a, hipStream_t st)
     hipLaunchKernelGGL((gemm_w4_kernel<EPI, 8, 1>), dim3(tiles, (a.R + 15) / 16), dim3(8 * 64), 0, st, a);
 }
 
-void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st) {
+bool launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st) {
     if (a.wscale && a.wbits == 4) { // int4 weights: the caller has checked bf16 planes and K % 128 == 0
         switch (epi) {
         case EPI_STORE: launch_gemm_w4<EPI_STORE>(a, st); break;
@@ -746,22 +763,20 @@ void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st) {
         case EPI_SWIGLU: launch_gemm_w4<EPI_SWIGLU>(a, st); break;
         case EPI_QKV: launch_gemm_w4<EPI_QKV>(a, st); break;
         }
-        return;
+        return false;
     }
     if (a.wscale) { // int8 weights: the caller has checked bf16 planes and K % 16 == 0
         switch (epi) {
-        case EPI_STORE: launch_gemm_w8<EPI_STORE>(a, st); break;
-        case EPI_RESID: launch_gemm_w8<EPI_RESID>(a, st); break;
-        case EPI_SWIGLU: launch_gemm_w8<EPI_SWIGLU>(a, st); break;
-        case EPI_QKV: launch_gemm_w8<EPI_QKV>(a, st); break;
+        case EPI_STORE: return launch_gemm_w8<EPI_STORE>(a, st);
+        case EPI_RESID: return launch_gemm_w8<EPI_RESID>(a, st);
+        case EPI_SWIGLU: return launch_gemm_w8<EPI_SWIGLU>(a, st);
+        case EPI_QKV: return launch_gemm_w8<EPI_QKV>(a, st);
         }
-        return;
+        return false;
     }
 #define SS_CASE(EP)                                                  \
     case EP:                                                         \
-        if (dtype) launch_gemm_t<bf16_t, EP>(a, st);                 \
-        else launch_gemm_t<float, EP>(a, st);                        \
-        break;
+        return dtype ? launch_gemm_t<bf16_t, EP>(a, st) : launch_gemm_t<float, EP>(a, st);
     switch (epi) {
         SS_CASE(EPI_STORE)
         SS_CASE(EPI_RESID)
@@ -769,6 +784,7 @@ void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st) {
         SS_CASE(EPI_QKV)
     }
 #undef SS_CASE
+    return false;
 }
 
 } // namespace ss

@@ -39,12 +39,21 @@ struct GemmArgs {
     float *splitk_ws;
     size_t splitk_ws_bytes;
     int ksplit, kslabs; // set by the launcher: K splits, K slabs per split
+    int splitk_rows;    // set by the launcher: partials are plain rows [split][R][N] (EPI_RESID), not accumulator tiles
+    // EPI_RESID, optional: the RMSNorm that follows the projection (gain over the N output columns; planes
+    // [planes][R16][norm_ld]).  A launcher that can fold it into its last launch does and returns true.
+    const float *norm_gain;
+    void *norm_act;
+    size_t norm_act_plane;
+    int norm_ld;
+    float norm_eps;
     // weight-only int8: W is int8 [N][K] and output column n is scaled by wscale[n] (NULL: W is in the storage type).
     // bf16 activation planes only; K a multiple of 16.
     const float *wscale;
     int wbits; // with wscale: 8 = int8, one scale per output column; 4 = int4, two entries per byte, scales [K/128][columns] (at most 16 rows, K % 128 == 0)
 };
-void launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st);
+// true: the RMSNorm asked for through norm_gain has been written as well
+bool launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st);
 
 struct AttnArgs {
     const void *q; // activation planes [planes][R16][ldq], rotated queries
@@ -68,6 +77,10 @@ void launch_embed(int dtype, const void *embed, const int32_t *tokens, int R, in
                   int32_t *status, hipStream_t st);
 void launch_rmsnorm_pack(int dtype, const float *h, const float *gain, int R, int d, float eps, void *act,
                          size_t act_plane, int ld_act, hipStream_t st);
+// second pass of a split-K residual projection: h[r][:] += sum over splits (in split order) of parts[z][r][:], then,
+// with a gain, the RMSNorm of the new row exactly as launch_rmsnorm_pack computes it
+void launch_splitk_resid_norm(int dtype, float *h, const float *parts, int ksplit, const float *gain, int R, int d,
+                              float eps, void *act, size_t act_plane, int ld_act, hipStream_t st);
 // gathers the last row of every sequence: rows b*M + M-1 -> compact rows b (norm + pack)
 void launch_rmsnorm_pack_rows(int dtype, const float *h, const float *gain, int nrows, int row0, int row_stride,
                               int d, float eps, void *act, size_t act_plane, int ld_act, hipStream_t st);
