@@ -66,7 +66,7 @@ typedef struct {
                            * SS_QUANT_INT8: int8, one fp32 scale per output row (ss_quantize_rows_int8); d_model,
                            *   n_heads*head_dim and d_ff multiples of 16;
                            * SS_QUANT_INT4_G128: int4, two entries per byte, one fp32 scale per group of 128 entries
-                           *   along K (ss_quantize_rows_int4); those three sizes multiples of 128 (calls of more than 16 rows stream the matrices once per 16 rows).
+                           *   along K (ss_quantize_rows_int4); those three sizes multiples of 128.
                            * Both need dtype bf16.  The embedding, the gains and the KV cache keep the storage type;
                            * such a model runs with one launch per phase (the persistent kernel streams
                            * storage-type matrices only). */

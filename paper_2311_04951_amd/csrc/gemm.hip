@@ -471,12 +471,18 @@ __device__ __forceinline__ size_t splitk_index(int z, int ntiles, int tile, int 
     return (((((size_t)z * ntiles + tile) * row_tiles + rt) * NT + t) * 4 + v) * 64 + lane;
 }
 
-// W8: the matrix is int8 with row scales (bf16 activation planes only).  A lane's 16-byte load then holds 16 K entries,
+// QB = 4: the matrix is int4 with one scale per 128 K entries and output column (bf16 planes, K a multiple of 128, a
+// multiple of 4 weight rows).  A slab is exactly one scale group and a lane's single 16-byte load holds 32 K entries =
+// its four k-blocks (dword j = entries 32g + 8j .., activations in LDS unit 4g + j): a step multiplies into fresh tiles
+// and adds them, times the group's scales of the lane's four columns (one 16-byte load, requested with the weights), to
+// the running sums - the arithmetic of gemm_w4_kernel.
+// QB = 8 (W8): the matrix is int8 with row scales (bf16 activation planes only).  A lane's 16-byte load then holds 16 K entries,
 // two MFMA k-blocks: per slab and tile two loads instead of four, and quarter q = 2h + j of the slab multiplies bytes
 // 8j..8j+7 of load h with the activations of k = 64h + 16g + 8j .., which sit in LDS unit 8h + 2g + j of the row.
-template <typename T, int EPI, int NW, int RT, bool W8 = false>
+template <typename T, int EPI, int NW, int RT, int QB = 0>
 __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
-    static_assert(!W8 || Traits<T>::E == 8, "int8 matrices go with bf16 activation planes");
+    constexpr bool W8 = QB == 8, W4 = QB == 4;
+    static_assert(QB == 0 || Traits<T>::E == 8, "quantised matrices go with bf16 activation planes");
     constexpr int E = Traits<T>::E, KB = 4 * E, PL = Traits<T>::PLANES;
     constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
     constexpr int WIDE_KS = WIDE_SLAB_BYTES / (int)sizeof(T); // elements of K per slab
@@ -486,9 +492,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
     constexpr int BUF = PL * ROWS * WIDE_SLAB_BYTES;          // bytes of one slab buffer
     constexpr int GROUPS = PL * ROWS / 4;                     // 1 KB load instructions per slab (4 rows each)
     constexpr int DPW = (GROUPS + NW - 1) / NW;               // ... per wave
-    constexpr int WLD = W8 ? KBS / 2 : KBS;                   // weight loads per tile and step
-    constexpr int WN = NT * WLD;                              // weight loads per wave and step
-    constexpr int WE = W8 ? 16 : E;                           // K entries per weight load
+    constexpr int WLD = W4 ? 1 : (W8 ? KBS / 2 : KBS);        // weight loads per tile and step
+    constexpr int WN = NT * WLD + (W4 ? NT : 0);              // weight (and int4 scale) loads per wave and step
+    constexpr int WE = W4 ? 32 : (W8 ? 16 : E);               // K entries per weight load
     __shared__ __align__(16) unsigned char slab0[BUF], slab1[BUF], slab2[BUF];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 15, g = lane >> 4;
@@ -501,14 +507,16 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
     const bool tile_live = tile < ntiles; // a dead wave still helps with the slab copies and barriers
     const int nrows_w = (EPI == EPI_SWIGLU) ? 2 * a.N : a.N;
 
-    constexpr size_t WB = W8 ? 1 : sizeof(T); // bytes per matrix entry
+    constexpr size_t WB2 = W4 ? 1 : (W8 ? 2 : 2 * sizeof(T)); // twice the bytes of a matrix entry (an int4 entry is half a byte)
     const char *W = reinterpret_cast<const char *>(a.W);
     const char *wrow[NT]; // byte pointers: this lane's row at its lane group's offset
+    const float *srow[NT]; // int4: the scales of the lane's four output columns in group 0
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         int n = n0[t] + c;
         if (n > nrows_w - 1) n = nrows_w - 1; // ragged last tile: load a valid row, masked at the store
-        wrow[t] = W + ((size_t)n * K + g * WE) * WB;
+        wrow[t] = W + ((size_t)n * K + g * WE) * WB2 / 2;
+        srow[t] = W4 ? a.wscale + min(n0[t] + 4 * g, nrows_w - 4) : nullptr; // (nrows_w % 4 == 0: either all four columns exist or none)
     }
     const T *act = reinterpret_cast<const T *>(a.act);
     // split-K (a.ksplit > 1): workgroup z multiplies K slabs [s_lo, s_hi) only and leaves raw partial tiles
@@ -534,15 +542,19 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
         }
         asm volatile("" ::: "memory");
     };
-    auto w_load = [&](int sl, u32x4 (&w)[NT][WLD]) {
+    auto w_load = [&](int sl, u32x4 (&w)[NT][WLD], u32x4 (&sc)[W4 ? NT : 1]) {
         const int k0 = (s_lo + min(sl, nslab - 1)) * WIDE_KS; // past the end: the last slab again (a cache hit; never multiplied)
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int kb = 0; kb < WLD; ++kb) {
                 const int k = k0 + kb * 4 * WE;
-                w[t][kb] = ld16_global(wrow[t] + (size_t)min(k, K - (g + 1) * WE) * WB); // zeroed past K when it is used
+                w[t][kb] = ld16_global(wrow[t] + (size_t)min(k, K - (g + 1) * WE) * WB2 / 2); // zeroed past K when it is used
             }
+        if constexpr (W4) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t) sc[t] = ld16_global(srow[t] + (size_t)(k0 / WIDE_KS) * nrows_w);
+        }
         asm volatile("" ::: "memory");
     };
 
@@ -562,17 +574,19 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
     // unrolled over three steps and the last one or two steps of a slab count that is not a multiple of
     // three are written out after it (no idle step: the projections with K split four ways have 8 steps).
     u32x4 wring[3][NT][WLD];
+    u32x4 sring[3][W4 ? NT : 1]; // int4: the slab's scales (four floats per tile), travelling with its weights
     slab_dma(0, slab0);
-    w_load(0, wring[0]);
+    w_load(0, wring[0], sring[0]);
     slab_dma(1, slab1);
-    w_load(1, wring[1]);
-    auto step = [&](int sl, const unsigned char *cur, unsigned char *fill, u32x4 (&wcur)[NT][WLD], u32x4 (&wfill)[NT][WLD]) {
+    w_load(1, wring[1], sring[1]);
+    auto step = [&](int sl, const unsigned char *cur, unsigned char *fill, u32x4 (&wcur)[NT][WLD], u32x4 (&wfill)[NT][WLD],
+                    u32x4 (&scur)[W4 ? NT : 1], u32x4 (&sfill)[W4 ? NT : 1]) {
         // this wave's part of slab sl and its weight slab sl have landed: the only younger loads are
         // those of the previous step (slab sl+1, weights sl+1)
         wait_vmcnt_at_most<DPW + WN>();
         wide_barrier(); // everybody's part has landed, and everybody is done reading `fill` (slab sl - 1)
         slab_dma(sl + 2, fill);
-        w_load(sl + 2, wfill);
+        w_load(sl + 2, wfill, sfill);
         const unsigned char *base = cur + (size_t)c * WIDE_SLAB_BYTES;
         // the LDS reads of k-block kb+1 are issued before the MFMAs of k-block kb (the scheduling
         // barriers keep the compiler from sinking them next to their uses, which serialises every
@@ -583,34 +597,59 @@ __global__ __launch_bounds__(NW * 64) void gemm_wide_kernel(GemmArgs a) {
 #pragma unroll
                 for (int pl = 0; pl < PL; ++pl)
                     av[r].p[pl] = *reinterpret_cast<const u32x4 *>(base + (size_t)(pl * ROWS + r * 16) * WIDE_SLAB_BYTES +
-                                                                   (((W8 ? 8 * (kb >> 1) + 2 * g + (kb & 1) : kb * 4 + g) ^ c) * 16));
+                                                                   (((W4 ? 4 * g + kb : (W8 ? 8 * (kb >> 1) + 2 * g + (kb & 1) : kb * 4 + g)) ^ c) * 16));
             __builtin_amdgcn_sched_barrier(0);
         };
         Act<T> av[2][RT];
         read_av(0, av[0]);
+        if constexpr (W4) {
+            f32x4 part[RT][NT]; // this scale group's sums
 #pragma unroll
-        for (int kb = 0; kb < KBS; ++kb) {
-            if (kb + 1 < KBS) read_av(kb + 1, av[(kb + 1) & 1]);
-            const bool in_k = (s_lo + sl) * WIDE_KS + (W8 ? (kb >> 1) * 64 + g * 16 : kb * KB + g * E) < k_end;
+            for (int r = 0; r < RT; ++r)
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                u32x4 wm;
-                if constexpr (W8) wm = in_k ? w8_to_bf16x8(wcur[t][kb >> 1][2 * (kb & 1)], wcur[t][kb >> 1][2 * (kb & 1) + 1]) : zero16();
-                else wm = in_k ? wcur[t][kb] : zero16();
+                for (int t = 0; t < NT; ++t) part[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int r = 0; r < RT; ++r) mma_split(acc[0][r][t], acc[1][r][t], wm, av[kb & 1][r], kb);
+            for (int kb = 0; kb < KBS; ++kb) {
+                if (kb + 1 < KBS) read_av(kb + 1, av[(kb + 1) & 1]);
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const u32x4 wm = w4_to_bf16x8(wcur[t][0][kb]); // a slab of a K that is a multiple of 128 lies inside K
+#pragma unroll
+                    for (int r = 0; r < RT; ++r) part[r][t] = mma(part[r][t], wm, av[kb & 1][r]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int r = 0; r < RT; ++r)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[0][r][t][v] += u2f(scur[t][v]) * part[r][t][v];
+        } else {
+#pragma unroll
+            for (int kb = 0; kb < KBS; ++kb) {
+                if (kb + 1 < KBS) read_av(kb + 1, av[(kb + 1) & 1]);
+                const bool in_k = (s_lo + sl) * WIDE_KS + (W8 ? (kb >> 1) * 64 + g * 16 : kb * KB + g * E) < k_end;
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    u32x4 wm;
+                    if constexpr (W8) wm = in_k ? w8_to_bf16x8(wcur[t][kb >> 1][2 * (kb & 1)], wcur[t][kb >> 1][2 * (kb & 1) + 1]) : zero16();
+                    else wm = in_k ? wcur[t][kb] : zero16();
+#pragma unroll
+                    for (int r = 0; r < RT; ++r) mma_split(acc[0][r][t], acc[1][r][t], wm, av[kb & 1][r], kb);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     };
     int s0 = 0;
     for (; s0 + 3 <= nslab; s0 += 3) {
-        step(s0, slab0, slab2, wring[0], wring[2]);
-        step(s0 + 1, slab1, slab0, wring[1], wring[0]);
-        step(s0 + 2, slab2, slab1, wring[2], wring[1]);
+        step(s0, slab0, slab2, wring[0], wring[2], sring[0], sring[2]);
+        step(s0 + 1, slab1, slab0, wring[1], wring[0], sring[1], sring[0]);
+        step(s0 + 2, slab2, slab1, wring[2], wring[1], sring[2], sring[1]);
     }
-    if (s0 < nslab) step(s0, slab0, slab2, wring[0], wring[2]);
-    if (s0 + 1 < nslab) step(s0 + 1, slab1, slab0, wring[1], wring[0]);
+    if (s0 < nslab) step(s0, slab0, slab2, wring[0], wring[2], sring[0], sring[2]);
+    if (s0 + 1 < nslab) step(s0 + 1, slab1, slab0, wring[1], wring[0], sring[1], sring[0]);
     wait_vmcnt_at_most<0>(); // nothing may still be landing in LDS when the workgroup ends
     if (!tile_live) return;
     const int row_tiles = (a.R + 15) / 16;
@@ -669,7 +708,7 @@ __global__ __launch_bounds__(64) void gemm_splitk_finish_kernel(GemmArgs a) {
 // A residual projection (whole 16-column tiles, dense output rows) leaves its partials as plain rows, and the
 // second launch is the RMSNorm kernel with the sum over the splits in front: it completes h and, when the caller
 // named the norm that follows, writes that too (returns true then).
-template <typename T, int EPI, int NW, int RT, bool W8 = false> static bool launch_wide(const GemmArgs &a0, int tiles, int row_tiles, hipStream_t st) {
+template <typename T, int EPI, int NW, int RT, int QB = 0> static bool launch_wide(const GemmArgs &a0, int tiles, int row_tiles, hipStream_t st) {
     constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
     constexpr int WIDE_KS = WIDE_SLAB_BYTES / (int)sizeof(T);
     GemmArgs a = a0;
@@ -688,7 +727,7 @@ template <typename T, int EPI, int NW, int RT, bool W8 = false> static bool laun
         }
     }
     a.splitk_rows = EPI == EPI_RESID && a.ksplit > 1 && a.ksplit <= 4 && a.N % 16 == 0 && a.ldo == a.N && a.out == a.resid;
-    hipLaunchKernelGGL((gemm_wide_kernel<T, EPI, NW, RT, W8>), dim3(gx, gy, a.ksplit), dim3(NW * 64), 0, st, a);
+    hipLaunchKernelGGL((gemm_wide_kernel<T, EPI, NW, RT, QB>), dim3(gx, gy, a.ksplit), dim3(NW * 64), 0, st, a);
     if (a.splitk_rows) {
         launch_splitk_resid_norm(std::is_same<T, bf16_t>::value ? 1 : 0, a.out, a.splitk_ws, a.ksplit, a.norm_gain, a.R, a.N, a.norm_eps,
                                  a.norm_act, a.norm_act_plane, a.norm_ld, st);
@@ -698,7 +737,7 @@ template <typename T, int EPI, int NW, int RT, bool W8 = false> static bool laun
     return false;
 }
 
-template <typename T, int EPI, bool W8> static bool launch_wide_any(const GemmArgs &a, int tiles, int row_tiles, hipStream_t st);
+template <typename T, int EPI, int QB> static bool launch_wide_any(const GemmArgs &a, int tiles, int row_tiles, hipStream_t st);
 
 template <typename T, int EPI> static bool launch_gemm_t(const GemmArgs &a, hipStream_t st) {
     int tiles;
@@ -709,20 +748,20 @@ template <typename T, int EPI> static bool launch_gemm_t(const GemmArgs &a, hipS
         hipLaunchKernelGGL((gemm_kernel<T, EPI, 8, 2, 1>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
         return false;
     }
-    return launch_wide_any<T, EPI, false>(a, tiles, row_tiles, st);
+    return launch_wide_any<T, EPI, 0>(a, tiles, row_tiles, st);
 }
 
-template <typename T, int EPI, bool W8> static bool launch_wide_any(const GemmArgs &a, int tiles, int row_tiles, hipStream_t st) {
+template <typename T, int EPI, int QB> static bool launch_wide_any(const GemmArgs &a, int tiles, int row_tiles, hipStream_t st) {
     // larger batches and prefill chunks: waves split the columns; fewer waves per workgroup when the
     // matrix has few tiles, so that the launch still covers the chip
     constexpr bool FUSED = EPI == EPI_SWIGLU || EPI == EPI_QKV; // two weight tiles per wave: more registers
     const bool small = tiles < 8 * 128;
     if (row_tiles <= 2) {
-        if (small) return launch_wide<T, EPI, 4, 2, W8>(a, tiles, row_tiles, st);
-        return launch_wide<T, EPI, 8, 2, W8>(a, tiles, row_tiles, st);
+        if (small) return launch_wide<T, EPI, 4, 2, QB>(a, tiles, row_tiles, st);
+        return launch_wide<T, EPI, 8, 2, QB>(a, tiles, row_tiles, st);
     } else if (row_tiles <= 3) {
-        if (small) return launch_wide<T, EPI, 4, 3, W8>(a, tiles, row_tiles, st);
-        return launch_wide<T, EPI, 8, 3, W8>(a, tiles, row_tiles, st);
+        if (small) return launch_wide<T, EPI, 4, 3, QB>(a, tiles, row_tiles, st);
+        return launch_wide<T, EPI, 8, 3, QB>(a, tiles, row_tiles, st);
     } else {
         // one workgroup per compute unit fits: 3 waves per workgroup when that fills more of a 256-unit chip
         // in whole rounds than 4 (688 gate/up tiles: 230 workgroups instead of 172; 384 QKV tiles: 128, split in two)
@@ -731,9 +770,9 @@ template <typename T, int EPI, bool W8> static bool launch_wide_any(const GemmAr
             const int ks = std::max(1, std::min(256 / std::max(wgs, 1), 4));
             return (double)(wgs * ks) / (double)((wgs * ks + 255) / 256 * 256);
         };
-        if ((small || FUSED) && fill(3) > fill(4) + 0.1) return launch_wide<T, EPI, 3, 5, W8>(a, tiles, row_tiles, st);
-        if (small || FUSED) return launch_wide<T, EPI, 4, 5, W8>(a, tiles, row_tiles, st);
-        return launch_wide<T, EPI, 8, 5, W8>(a, tiles, row_tiles, st);
+        if ((small || FUSED) && fill(3) > fill(4) + 0.1) return launch_wide<T, EPI, 3, 5, QB>(a, tiles, row_tiles, st);
+        if (small || FUSED) return launch_wide<T, EPI, 4, 5, QB>(a, tiles, row_tiles, st);
+        return launch_wide<T, EPI, 8, 5, QB>(a, tiles, row_tiles, st);
     }
 }
 
@@ -743,25 +782,31 @@ template <typename T, int EPI, bool W8> static bool launch_wide_any(const GemmAr
 template <int EPI> static bool launch_gemm_w8(const GemmArgs &a, hipStream_t st) {
     const int tiles = EPI == EPI_QKV ? 3 * a.H * (a.hd / 32) : (a.N + 15) / 16;
     const int row_tiles = (a.R + 15) / 16;
-    if (row_tiles > 1) return launch_wide_any<bf16_t, EPI, true>(a, tiles, row_tiles, st);
+    if (row_tiles > 1) return launch_wide_any<bf16_t, EPI, 8>(a, tiles, row_tiles, st);
     hipLaunchKernelGGL((gemm_w8_kernel<EPI, 8, 2>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
     return false;
 }
 
 // 8 waves, one step in flight: measured best of (4 | 8 | 16 waves) x (1 | 2 steps) on the 7B-shaped layer (a step
 // already holds 13 to 17 loads per lane: one of weights, eight of activations, the scales)
-template <int EPI> static void launch_gemm_w4(const GemmArgs &a, hipStream_t st) {
+template <int EPI> static bool launch_gemm_w4(const GemmArgs &a, hipStream_t st) {
     const int tiles = EPI == EPI_QKV ? 3 * a.H * (a.hd / 32) : (a.N + 15) / 16;
-    hipLaunchKernelGGL((gemm_w4_kernel<EPI, 8, 1>), dim3(tiles, (a.R + 15) / 16), dim3(8 * 64), 0, st, a);
+    const int row_tiles = (a.R + 15) / 16;
+    const int nrows_w = EPI == EPI_SWIGLU ? 2 * a.N : a.N;
+    // more than 16 rows: the wide kernel (it reads a lane's four scales as one 16-byte load); otherwise, or with a
+    // row count that is not a multiple of 4, one workgroup per (column tile, row tile)
+    if (row_tiles > 1 && nrows_w % 4 == 0 && (reinterpret_cast<uintptr_t>(a.wscale) & 15) == 0) return launch_wide_any<bf16_t, EPI, 4>(a, tiles, row_tiles, st);
+    hipLaunchKernelGGL((gemm_w4_kernel<EPI, 8, 1>), dim3(tiles, row_tiles), dim3(8 * 64), 0, st, a);
+    return false;
 }
 
 bool launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st) {
     if (a.wscale && a.wbits == 4) { // int4 weights: the caller has checked bf16 planes and K % 128 == 0
         switch (epi) {
-        case EPI_STORE: launch_gemm_w4<EPI_STORE>(a, st); break;
-        case EPI_RESID: launch_gemm_w4<EPI_RESID>(a, st); break;
-        case EPI_SWIGLU: launch_gemm_w4<EPI_SWIGLU>(a, st); break;
-        case EPI_QKV: launch_gemm_w4<EPI_QKV>(a, st); break;
+        case EPI_STORE: return launch_gemm_w4<EPI_STORE>(a, st);
+        case EPI_RESID: return launch_gemm_w4<EPI_RESID>(a, st);
+        case EPI_SWIGLU: return launch_gemm_w4<EPI_SWIGLU>(a, st);
+        case EPI_QKV: return launch_gemm_w4<EPI_QKV>(a, st);
         }
         return false;
     }

@@ -187,18 +187,22 @@ def test_7b_width_data_synchronisation_equals_barriers_over_many_launches():
 
 
 @pytest.mark.timeout(900)
-def test_batched_7b_layer_72_rows_matches_per_sequence_oracle():
+@pytest.mark.parametrize("quant", [None, "int8", "int4"])
+def test_batched_7b_layer_72_rows_matches_per_sequence_oracle(quant):
     """The batched workload's launch shapes at full width: one 7B-shaped bf16 layer, 8 sequences with
-    ragged contexts, K = 8 -> 72 rows in one call (wide GEMMs with split-K, split-KV attention).  Each
-    sequence's hidden rows against the oracle run on that sequence alone (reduced depth and context:
-    the full 32-layer, 4096-position pass is out of the oracle's reach)."""
+    ragged contexts, K = 8 -> 72 rows in one call (wide GEMMs with split-K, split-KV attention), with bf16
+    matrices and with the int8 and int4 matrices the library quantises from them (the wide kernel's two
+    quantised modes at K = 4096 and 11008).  Each sequence's hidden rows against the oracle's model of the
+    same kind run on that sequence alone (reduced depth and context: the full 32-layer, 4096-position pass
+    is out of the oracle's reach)."""
     shape = si.LAYER_7B
     lw = si.layer_weights(shape, seed=0, layer=0)
     w = {"embed": None, "gf": None, "lm_head": None, "layers": [lw]}
-    om = oracle.Model(shape, w)
+    qkw = {} if quant is None else {f"{quant}_weights": True}
+    om = oracle.Model(shape, w, **qkw)
     B, M = 8, 9
     lens = [300, 17, 129, 64, 1, 255, 190, 77]
-    gm = sv.Model(shape, weights_to_device(w), max_rows=B * M, max_pos=512)
+    gm = sv.Model(shape, weights_to_device(w), max_rows=B * M, max_pos=512, **qkw)
     gkv = sv.KVCache(gm, B, 384)
     h = si.normal(9, "h72", (B, M, shape.d_model), 1.0)
     refs = []
