@@ -220,20 +220,23 @@ def test_batched_7b_layer_72_rows_matches_per_sequence_oracle(quant):
 
 
 @pytest.mark.timeout(1200)
-def test_batched_long_context_layer_at_its_real_shape_matches_per_sequence_oracle():
+@pytest.mark.parametrize("B", [8, 2])
+def test_batched_long_context_layer_at_its_real_shape_matches_per_sequence_oracle(B):
     """The batched long-context workload at its real shape, reduced in depth only (the oracle cannot run 32 layers
-    of it): one 7B-shaped bf16 layer, 8 sequences whose caches hold 4096 - jitter(0..63) positions (the KV cache
-    "can be quite large", Section 2), K = 8 -> 72 rows in one call against a cache of 4608 positions per
+    of it): one 7B-shaped bf16 layer, 8 sequences whose caches hold 4096 - jitter(0..63) positions (Section 2: the
+    cache of a long context is a large object), K = 8 -> 72 rows in one call against a cache of 4608 positions per
     sequence: block indices far past the first cache blocks, the transposed value blocks of a long sequence,
-    16-way split-KV attention with partly empty tail splits, split-K wide GEMMs.  Every sequence's hidden rows
-    against the oracle run on that sequence alone; then a ragged roll-back (Section 4.4: sequences accept
-    different numbers of tokens) and a second 72-row pass over the shortened caches, checked the same way."""
+    one workgroup per (sequence, head) walking the whole context, split-K wide GEMMs.  With 2 sequences (18 rows:
+    two row tiles) the same contexts go through 8-way split-KV attention with a partly empty tail split and the
+    merge launch.  Every sequence's hidden rows against the oracle run on that sequence alone; then a ragged
+    roll-back (Section 4.4: sequences accept different numbers of tokens) and a second pass over the shortened
+    caches, checked the same way."""
     shape = si.LAYER_7B
     lw = si.layer_weights(shape, seed=0, layer=0)
     w = {"embed": None, "gf": None, "lm_head": None, "layers": [lw]}
     om = oracle.Model(shape, w)
-    B, M, S = 8, 9, 4608
-    lens = [4096 - j for j in [0, 63, 1, 37, 50, 12, 31, 64 - 41]]
+    M, S = 9, 4608
+    lens = [4096 - j for j in [0, 63, 1, 37, 50, 12, 31, 64 - 41]][:B]
     assert len(set(lens)) == B and min(lens) > 4096 - 64
     gm = sv.Model(shape, weights_to_device(w), max_rows=B * M, max_pos=S)
     gkv = sv.KVCache(gm, B, S)
@@ -255,7 +258,7 @@ def test_batched_long_context_layer_at_its_real_shape_matches_per_sequence_oracl
         assert err < 2e-2, (b, err)
     assert sv.ss_kv_cache_get_len(gkv).tolist() == [l + M for l in lens]
     # ragged roll-back, then the next pass
-    acc = [0, 8, 3, 8, 1, 5, 2, 7]
+    acc = [0, 8, 3, 8, 1, 5, 2, 7][:B]
     sv.ss_kv_cache_rollback(gkv, torch.tensor(acc, dtype=torch.int32, device=dev()), M, n_accepted_host=acc)
     lens2 = [l + a + 1 for l, a in zip(lens, acc)]
     assert sv.ss_kv_cache_get_len(gkv).tolist() == lens2
