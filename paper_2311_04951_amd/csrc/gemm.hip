@@ -22,11 +22,42 @@
 
 namespace ss {
 
+// What an epilogue reads besides the sums (the residual, the sequence's length and the rotary factors): a kernel whose
+// K loop takes many memory round trips asks for them in front of it, so that the epilogue does not add two more.
+struct EpiPre {
+    float resid[4];
+    float2 rope[4];
+    int pos;
+};
+template <typename T, int EPI>
+__device__ __forceinline__ void epi_prefetch(const GemmArgs &a, const int (&n0)[(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1], int rt, EpiPre &pre) {
+    const int lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
+    const int m = min(rt * 16 + c, a.R - 1); // a row past the end asks for the last row's operands and never uses them
+    if constexpr (EPI == EPI_RESID) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) pre.resid[v] = a.resid[(size_t)m * a.ldo + min(n0[0] + 4 * g + v, a.N - 1)];
+    } else if constexpr (EPI == EPI_QKV) {
+        const int d_all = a.H * a.hd;
+        const int region = n0[0] / d_all;
+        const int within = n0[0] - region * d_all;
+        const int j0 = within - (within / a.hd) * a.hd + 4 * g;
+        const int b = m / a.M, i = m - b * a.M;
+        int pos = a.len[b] + i;
+        if (pos > a.max_pos - 1) pos = a.max_pos - 1;
+        if (pos > a.S - 1) pos = a.S - 1;
+        pre.pos = pos;
+        if (region < 2) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) pre.rope[v] = a.rope[(size_t)pos * (a.hd / 2) + j0 + v];
+        }
+    }
+}
+
 // Epilogue of one output tile by one wave: lane (c, g) holds r[t][v] = the value of row m = rt*16 + c,
-// column n0[t] + 4g + v.
+// column n0[t] + 4g + v.  pre: operands fetched ahead by epi_prefetch for this tile and row tile (NULL: read here).
 template <typename T, int EPI>
 __device__ __forceinline__ void apply_epilogue(const GemmArgs &a, const float (&r)[(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1][4],
-                                               const int (&n0)[(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1], int rt) {
+                                               const int (&n0)[(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1], int rt, const EpiPre *pre = nullptr) {
     const int lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
     const int m = rt * 16 + c;
     if (m >= a.R) return;
@@ -37,7 +68,7 @@ __device__ __forceinline__ void apply_epilogue(const GemmArgs &a, const float (&
             const int n = n0[0] + 4 * g + v;
             if (n < a.N) {
                 const size_t o = (size_t)m * a.ldo + n;
-                a.out[o] = (EPI == EPI_RESID) ? a.resid[o] + r[0][v] : r[0][v];
+                a.out[o] = (EPI == EPI_RESID) ? (pre ? pre->resid[v] : a.resid[o]) + r[0][v] : r[0][v];
             }
         }
     } else if constexpr (EPI == EPI_SWIGLU) {
@@ -58,9 +89,14 @@ __device__ __forceinline__ void apply_epilogue(const GemmArgs &a, const float (&
         const int h = within / a.hd;
         const int j0 = within - h * a.hd + 4 * g; // column inside the head (first half)
         const int b = m / a.M, i = m - b * a.M;
-        int pos = a.len[b] + i;
-        if (pos > a.max_pos - 1) pos = a.max_pos - 1; // host validation keeps these from happening
-        if (pos > a.S - 1) pos = a.S - 1;
+        int pos;
+        if (pre) {
+            pos = pre->pos;
+        } else {
+            pos = a.len[b] + i;
+            if (pos > a.max_pos - 1) pos = a.max_pos - 1; // host validation keeps these from happening
+            if (pos > a.S - 1) pos = a.S - 1;
+        }
         float x0[4], x1[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
@@ -70,7 +106,7 @@ __device__ __forceinline__ void apply_epilogue(const GemmArgs &a, const float (&
         if (region < 2) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const float2 cs = a.rope[(size_t)pos * (a.hd / 2) + j0 + v];
+                const float2 cs = pre ? pre->rope[v] : a.rope[(size_t)pos * (a.hd / 2) + j0 + v];
                 const float p0 = x0[v] * cs.x - x1[v] * cs.y;
                 const float p1 = x0[v] * cs.y + x1[v] * cs.x;
                 x0[v] = p0;
@@ -108,7 +144,7 @@ __device__ __forceinline__ void apply_epilogue(const GemmArgs &a, const float (&
 // Sum of the waves' partial tiles of row tile rt (fixed order) and the epilogue, by one wave.
 template <typename T, int EPI, int NW>
 __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, const float (&red)[NW][(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1][4][64],
-                                              const int (&n0)[(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1], int rt) {
+                                              const int (&n0)[(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1], int rt, const EpiPre *pre = nullptr) {
     constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
     const int lane = threadIdx.x & 63;
     float r[NT][4];
@@ -121,7 +157,7 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, const float (&r
             for (int w2 = 1; w2 < NW; ++w2) sum += red[w2][t][v][lane];
             r[t][v] = sum;
         }
-    apply_epilogue<T, EPI>(a, r, n0, rt);
+    apply_epilogue<T, EPI>(a, r, n0, rt, pre);
 }
 
 // NW = wavefronts per workgroup (interleaved over K), U = 128-byte steps in flight per wave,
@@ -171,6 +207,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(GemmArgs a) {
     for (int r = 0; r < RT; ++r)
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    constexpr bool PRE = EPI == EPI_RESID || EPI == EPI_QKV; // the epilogue's own operands, asked for ahead of the K loop
+    EpiPre pre[RT];
+    if (PRE && wave == 0) {
+#pragma unroll
+        for (int r = 0; r < RT; ++r) epi_prefetch<T, EPI>(a, n0, rt0 + r, pre[r]);
+    }
 
     // Each wave takes 128-byte steps (two k-blocks) of every row, interleaved with the other waves,
     // U steps per iteration so that 2*U*NT weight loads are in flight per lane before the first MFMA.
@@ -209,7 +251,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(GemmArgs a) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) red[wave][t][v][lane] = acc[r][t][v];
         __syncthreads();
-        if (wave == 0) tile_epilogue<T, EPI, NW>(a, red, n0, rt0 + r);
+        if (wave == 0) tile_epilogue<T, EPI, NW>(a, red, n0, rt0 + r, PRE ? &pre[r] : nullptr);
     }
 }
 
@@ -265,6 +307,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_w8_kernel(GemmArgs a) {
     f32x4 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    constexpr bool PRE = EPI == EPI_RESID || EPI == EPI_QKV; // the epilogue's own operands, asked for ahead of the K loop
+    EpiPre pre;
+    if (PRE && wave == 0) epi_prefetch<T, EPI>(a, n0, 0, pre);
 
     const int nsteps = (K + 63) / 64; // 64 entries of K (64 bytes of a weight row) per step
     for (int ks = wave; ks < nsteps; ks += U * NW) {
@@ -305,7 +350,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_w8_kernel(GemmArgs a) {
             for (int w2 = 1; w2 < NW; ++w2) sum += red[w2][t][v][lane];
             r[t][v] = sum * a.wscale[min(n0[t] + 4 * g + v, nrows_w - 1)];
         }
-    apply_epilogue<T, EPI>(a, r, n0, 0);
+    apply_epilogue<T, EPI>(a, r, n0, 0, PRE ? &pre : nullptr);
 }
 
 // ---- weight-only int4 matrices with one scale per group of 128 K entries (the coarser reading of the same
@@ -368,6 +413,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_w4_kernel(GemmArgs a) {
     f32x4 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    constexpr bool PRE = EPI == EPI_RESID || EPI == EPI_QKV; // the epilogue's own operands, asked for ahead of the K loop
+    EpiPre pre;
+    if (PRE && wave == 0) epi_prefetch<T, EPI>(a, n0, rt, pre);
 
     const int nsteps = K / 128; // one scale group per step
     for (int ks = wave; ks < nsteps; ks += U * NW) {
@@ -408,7 +456,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_w4_kernel(GemmArgs a) {
         for (int v = 0; v < 4; ++v) red[wave][t][v][lane] = acc[t][v];
     __syncthreads();
     if (wave != 0) return;
-    tile_epilogue<T, EPI, NW>(a, red, n0, rt);
+    tile_epilogue<T, EPI, NW>(a, red, n0, rt, PRE ? &pre : nullptr);
 }
 
 // More than 16 rows (larger batches, prefill): the waves of a workgroup split the output columns instead
