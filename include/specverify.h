@@ -125,7 +125,7 @@ int ss_device_status(ss_model *model, ss_stream stream, int32_t *status_host);
  * the elapsed times up per kernel class and clears the record.  Classes (n_classes >= 9):
  * 0 RMSNorm, 1 QKV GEMM (+rotary, +cache append), 2 attention (+merge), 3 O-projection GEMM,
  * 4 gate/up GEMM (+SwiGLU), 5 down-projection GEMM, 6 LM-head GEMM, 7 other, 8 the persistent
- * verify kernel (the whole forward of a small call is one launch of it, see ss_model_set_persistent).
+ * verify kernel (with ss_model_set_persistent(model, 1) the whole forward of a small call is one launch of it).
  * total_ms_host / launches_host: host arrays [n_classes].  Event recording perturbs the pass a
  * little, so timed throughput runs keep it off. */
 int ss_profile_enable(ss_model *model, int32_t on);
@@ -168,15 +168,18 @@ int ss_probe_read_bandwidth(const void *buf_dev, size_t bytes, int32_t iters, ui
 int ss_model_create(const ss_model_cfg *cfg, const ss_weights *weights, ss_model **out);
 int ss_model_destroy(ss_model *model);
 
-/* Selects how the forward path of `model` is launched.  1 (default wherever the kernel can be
- * co-resident on the device): calls whose rows (batch * M) fit the kernel's LDS activation slab (9
- * rows for bf16 models, 16 for fp32) run as ONE persistent cooperative kernel
- * (one workgroup per compute unit, phases ordered by device-wide barriers or by self-validating
- * activations, RMSNorm folded into the GEMMs, weight loads of the next phase in flight across each
- * phase boundary); larger calls always use one
- * kernel per phase.  0: one kernel per phase (RMSNorm, QKV GEMM, attention, O projection, gate/up
- * GEMM, down projection ...) for every call.  Both paths produce results within the same tolerance
- * of the method; SS_EINVAL if `on` is set and the persistent kernel is not available on this device. */
+/* Selects how the forward path of `model` is launched.  0 (default): one kernel per phase (RMSNorm, QKV
+ * GEMM, attention, O projection, gate/up GEMM, down projection ...) for every call.  1: calls whose rows
+ * (batch * M) fit the kernel's LDS activation slab (9 rows for bf16 models, 16 for fp32) run as ONE
+ * persistent kernel (one workgroup per compute unit, phases ordered by device-wide barriers or by
+ * self-validating activations, RMSNorm folded into the GEMMs, weight loads of the next phase in flight
+ * across each phase boundary); larger calls still use one kernel per phase.  Measured on the 7B-, 13B- and
+ * 3B-shaped models the two are within a few per cent of each other (the per-phase path ahead at 1 - 7 rows
+ * and at every row count of the narrower model, the persistent kernel ahead by under 3 % at 9 rows of the
+ * 7B shape and 5 - 6 rows of the 13B shape), which is why the simpler one is the default.  Both paths
+ * produce results within the same tolerance of the method; SS_EINVAL if `on` is set and the persistent
+ * kernel is not available on this device (it needs every workgroup co-resident, and matrices in the
+ * storage type). */
 int ss_model_set_persistent(ss_model *model, int32_t on);
 
 /* Tuning and test knobs of the persistent kernel (no effect on the per-phase path).

@@ -87,7 +87,7 @@ struct ss_model {
     unsigned *arrive = nullptr, *abort_flag = nullptr, *attn_cnt = nullptr;
     void *zeros = nullptr;
     unsigned epoch = 1;
-    bool persistent = false; // forward path: false = one launch per phase, true = the persistent kernel (default where available)
+    bool persistent = false; // forward path: false = one launch per phase (default), true = the persistent kernel where the rows fit
     // optional per-kernel-class timing (ss_profile_*): event pairs recorded around launches
     bool prof = false;
     std::vector<hipEvent_t> ev;
@@ -329,7 +329,7 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
             return fail(SS_EHIP, "rope table upload: %s", hipGetErrorString(e));
         }
     }
-    m->persistent = m->mega_G > 0; // calls of at most 16 rows use the persistent kernel unless told otherwise
+    m->persistent = false; // one launch per phase unless ss_model_set_persistent asks for the persistent kernel (measured: as fast or faster at most shapes)
     {
         std::lock_guard<std::mutex> lk(g_reg_mu);
         g_models.insert(m);

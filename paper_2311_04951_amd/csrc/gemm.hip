@@ -792,8 +792,12 @@ template <typename T, int EPI> static bool launch_gemm_t(const GemmArgs &a, hipS
     if (EPI == EPI_QKV) tiles = 3 * a.H * (a.hd / 32);
     else tiles = (a.N + 15) / 16;
     const int row_tiles = (a.R + 15) / 16;
-    if (row_tiles <= 1) { // the verify pass proper: 8 waves split K, two steps in flight (measured: 3.5 % faster than 16 waves over a 7B-shaped pass)
-        hipLaunchKernelGGL((gemm_kernel<T, EPI, 8, 2, 1>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
+    if (row_tiles <= 1) { // the verify pass proper: the waves of a workgroup split K, two steps in flight each
+        // fused epilogues (688 gate/up pairs, 384 rotary pairs at the 7B shape: several workgroups per compute unit anyway)
+        // run 2 waves per workgroup, the projections with 256 tiles 8: measured over (1 | 2 | 3 | 4 | 5 | 6 | 8 | 16 waves)
+        // x (1 - 8 steps in flight) per kind of epilogue on the 7B-shaped layer
+        if (EPI == EPI_SWIGLU || EPI == EPI_QKV) hipLaunchKernelGGL((gemm_kernel<T, EPI, 2, 2, 1>), dim3(tiles, 1), dim3(2 * 64), 0, st, a);
+        else hipLaunchKernelGGL((gemm_kernel<T, EPI, 8, 2, 1>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
         return false;
     }
     return launch_wide_any<T, EPI, 0>(a, tiles, row_tiles, st);
@@ -824,19 +828,20 @@ template <typename T, int EPI, int QB> static bool launch_wide_any(const GemmArg
     }
 }
 
-// 8 waves per workgroup and two steps in flight per wave: measured best on the 7B-shaped layer among
-// (4 | 8 | 16 waves) x (1..4 steps) - the registers go to the activation operands (four 16-byte loads per
-// weight load), so more steps in flight cost occupancy, and smaller workgroups give more of them per compute unit.
+// Two steps in flight per wave; 8 waves per workgroup for the projections with few tiles, 4 for the fused epilogues
+// (measured per kind of epilogue on the 7B-shaped layer among (2 | 4 | 8 | 16 waves) x (1..4 steps)) - the registers
+// go to the activation operands (four 16-byte loads per weight load), so more steps in flight cost occupancy.
 template <int EPI> static bool launch_gemm_w8(const GemmArgs &a, hipStream_t st) {
     const int tiles = EPI == EPI_QKV ? 3 * a.H * (a.hd / 32) : (a.N + 15) / 16;
     const int row_tiles = (a.R + 15) / 16;
     if (row_tiles > 1) return launch_wide_any<bf16_t, EPI, 8>(a, tiles, row_tiles, st);
-    hipLaunchKernelGGL((gemm_w8_kernel<EPI, 8, 2>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
+    if (EPI == EPI_SWIGLU || EPI == EPI_QKV) hipLaunchKernelGGL((gemm_w8_kernel<EPI, 4, 2>), dim3(tiles, 1), dim3(4 * 64), 0, st, a);
+    else hipLaunchKernelGGL((gemm_w8_kernel<EPI, 8, 2>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
     return false;
 }
 
-// 8 waves, one step in flight: measured best of (4 | 8 | 16 waves) x (1 | 2 steps) on the 7B-shaped layer (a step
-// already holds 13 to 17 loads per lane: one of weights, eight of activations, the scales)
+// One step in flight, 8 waves (4 for the fused epilogues): measured best of (2 | 4 | 8 | 16 waves) x (1 | 2 steps) on
+// the 7B-shaped layer (a step already holds 13 to 17 loads per lane: one of weights, eight of activations, the scales)
 template <int EPI> static bool launch_gemm_w4(const GemmArgs &a, hipStream_t st) {
     const int tiles = EPI == EPI_QKV ? 3 * a.H * (a.hd / 32) : (a.N + 15) / 16;
     const int row_tiles = (a.R + 15) / 16;
@@ -844,7 +849,8 @@ template <int EPI> static bool launch_gemm_w4(const GemmArgs &a, hipStream_t st)
     // more than 16 rows: the wide kernel (it reads a lane's four scales as one 16-byte load); otherwise, or with a
     // row count that is not a multiple of 4, one workgroup per (column tile, row tile)
     if (row_tiles > 1 && nrows_w % 4 == 0 && (reinterpret_cast<uintptr_t>(a.wscale) & 15) == 0) return launch_wide_any<bf16_t, EPI, 4>(a, tiles, row_tiles, st);
-    hipLaunchKernelGGL((gemm_w4_kernel<EPI, 8, 1>), dim3(tiles, row_tiles), dim3(8 * 64), 0, st, a);
+    if (EPI == EPI_SWIGLU || EPI == EPI_QKV) hipLaunchKernelGGL((gemm_w4_kernel<EPI, 4, 1>), dim3(tiles, row_tiles), dim3(4 * 64), 0, st, a);
+    else hipLaunchKernelGGL((gemm_w4_kernel<EPI, 8, 1>), dim3(tiles, row_tiles), dim3(8 * 64), 0, st, a);
     return false;
 }
 

@@ -26,7 +26,7 @@ def model_pair(shape, seed, max_rows=16, max_pos=256, persistent=False):
     return oracle.Model(shape, w), gm, w
 
 
-# Forward paths under test: per-phase launches; the persistent kernel as it runs by default (on these
+# Forward paths under test: per-phase launches (the default); the persistent kernel on its default grid (on these
 # small shapes a grid of one workgroup per compute unit leaves workgroups without a share of some
 # phase, so every phase boundary is a barrier); the persistent kernel on a grid of 8 workgroups, where
 # every workgroup owns part of every GEMM phase and the activations synchronise themselves.

@@ -72,11 +72,13 @@ def test_device_side_truncation_only_lowers_lengths():
     assert sv.ss_kv_cache_get_len(kv).tolist() == [0, 7, 30]
 
 
-def test_hot_path_runs_with_allocations_frozen():
+@pytest.mark.parametrize("persistent", [False, True])
+def test_hot_path_runs_with_allocations_frozen(persistent):
     """One verify step the way the bench times it (forward, softmax, rejection step, roll-back), a draft step, the
     fused logits entry, the greedy entry and whole speculative steps, with every allocating path of the library
-    switched off and the workspace passed in by the caller; free device memory does not move either."""
-    tw, gt, gd = _tiny()
+    switched off and the workspace passed in by the caller; free device memory does not move either.  On both
+    forward paths (one launch per phase, the default, and the persistent kernel)."""
+    tw, gt, gd = _tiny(persistent=persistent)
     V, K, M = si.TINY_TARGET.vocab, 4, 5
     tkv, dkv = sv.KVCache(gt, 1, 128), sv.KVCache(gd, 1, 128)
     prompt = si.token_ids(31, "prompt", (1, 16), V).to(dev())

@@ -282,6 +282,7 @@ def test_persistent_kernel_at_7b_width_for_every_row_count_and_a_long_context_ma
     inside the kernel)."""
     shape, packed, io = si.packed_7b(5, 3, dev())
     gm = sv.Model(shape, io, max_rows=16, max_pos=4096, packed_layers=packed)
+    sv.ss_model_set_persistent(gm, True)
     om = oracle.Model(shape, {"embed": io["embed"].cpu(), "gf": io["gf"].cpu(), "lm_head": io["lm_head"].cpu(),
                               "layers": si.unpack_layers(shape, packed)})
     Lbig = 4003
@@ -308,17 +309,19 @@ def test_persistent_kernel_at_7b_width_for_every_row_count_and_a_long_context_ma
 
 
 @pytest.mark.timeout(1200)
-@pytest.mark.parametrize("quant", [None, "int8", "int4"])
+@pytest.mark.parametrize("quant", [None, "persistent", "int8", "int4"])
 def test_full_7b_verify_pass_matches_oracle(quant):
-    """The benchmark workload at its full size and in the launch configuration bench.py times (32
-    7B-shaped bf16 layers + LM head, default forward path, 5 query rows, 128 cached positions):
-    every logit of the verify pass against the oracle, max-abs 2e-2; the greedy token of a row must
-    agree wherever the oracle's top-2 margin exceeds twice that tolerance.  Also with the matrices
-    quantised to int8 and to int4 (the bench's int8_weights / int4_weights legs), against the oracle's
-    model quantised the same way."""
-    qkw = {} if quant is None else {f"{quant}_weights": True}
+    """The benchmark workload at its full size and in the launch configurations bench.py times (32
+    7B-shaped bf16 layers + LM head, 5 query rows, 128 cached positions; the default forward path with one
+    launch per phase, and the persistent kernel): every logit of the verify pass against the oracle, max-abs
+    2e-2; the greedy token of a row must agree wherever the oracle's top-2 margin exceeds twice that
+    tolerance.  Also with the matrices quantised to int8 and to int4 (the bench's int8_weights /
+    int4_weights legs), against the oracle's model quantised the same way."""
+    qkw = {} if quant in (None, "persistent") else {f"{quant}_weights": True}
     shape, packed, io = si.packed_7b(0, si.FULL_7B.n_layers, dev())
     gm = sv.Model(shape, io, max_rows=16, max_pos=512, packed_layers=packed, **qkw)
+    if quant == "persistent":
+        sv.ss_model_set_persistent(gm, True)
     om = oracle.Model(shape, {"embed": io["embed"].cpu(), "gf": io["gf"].cpu(), "lm_head": io["lm_head"].cpu(),
                               "layers": si.unpack_layers(shape, packed)}, **qkw)
     L, M = 128, 5
