@@ -26,11 +26,13 @@ HBM_PEAK = 8.0e12  # B/s, MI355X published peak
 # HBM bytes per launch of the persistent kernel on the default workload: a stored measurement (two rocprofv3 --pmc runs,
 # FETCH_SIZE then WRITE_SIZE, each scaled by what the counter reads for a plain 1 GiB device copy), valid for the kernel
 # source it was taken on; bench.py reports it only on that workload and names the file it comes from
-PERSISTENT_7B_TRAFFIC_BYTES = 13.602e9  # 13.466 GB fetched + 0.136 GB written
+PERSISTENT_7B_TRAFFIC_BYTES = 13.601e9  # 13.465 GB fetched + 0.136 GB written
 PERSISTENT_7B_TRAFFIC_SOURCE = "profiles/verify_pass_7b_persistent_hbm_traffic.txt"
 # the same kind of stored measurement for the stand-alone accept workload (the kernels stop reading a sequence's rows at
 # its first rejection, so they fetch less than "every logit once") and for the batched long-context pass
 ACCEPT_TRAFFIC_BYTES, ACCEPT_TRAFFIC_SOURCE = 366.5e6, "profiles/standalone_accept_hbm_traffic.txt"
+GATEUP_TRAFFIC_BYTES, GATEUP_TRAFFIC_SOURCE = 181.4e6, "profiles/verify_pass_7b_per_phase_hbm_traffic.txt"
+PER_PHASE_PASS_TRAFFIC_BYTES = 13.532e9  # 13.494 GB fetched + 0.038 GB written over the launches of one pass (same file)
 BATCHED_TRAFFIC_BYTES, BATCHED_TRAFFIC_SOURCE = 34.001e9, "profiles/batched_long_context_pass_hbm_traffic.txt"
 STORED = " (stored counter measurement of this workload, not taken in this run)"
 
@@ -439,8 +441,8 @@ def main():
     ap.add_argument("--K", type=int, default=4)
     ap.add_argument("--layers", type=int, default=32, help="decoder layers (32 = the named workload)")
     ap.add_argument("--gen-tokens", type=int, default=256)
-    ap.add_argument("--persistent", type=int, default=1,
-                    help="1: run the forward as the persistent single-launch kernel, 0: one launch per phase")
+    ap.add_argument("--persistent", type=int, default=0,
+                    help="0 (the library's default): one launch per phase, 1: the forward as the persistent single-launch kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-e2e", action="store_true")
     ap.add_argument("--no-accept-workload", action="store_true", help="skip the stand-alone accept workload leg")
@@ -609,13 +611,24 @@ def main():
         k_us = gu["avg_us"]
     achieved = k_bytes / (k_us * 1e-6) / 1e9
     # HBM bytes per launch from the FETCH_SIZE and WRITE_SIZE counters of two rocprofv3 --pmc runs, each scaled by
-    # what the same counter reads for a plain 1 GiB device copy (profiles/verify_pass_7b_persistent_hbm_traffic.txt);
-    # it is a measurement of the default workload only
-    traffic = PERSISTENT_7B_TRAFFIC_BYTES if ("verify_persistent" in classes and args.layers == 32 and K == 4) else None
+    # what the same counter reads for a plain 1 GiB device copy (profiles/verify_pass_7b_persistent_hbm_traffic.txt,
+    # profiles/verify_pass_7b_per_phase_hbm_traffic.txt); measurements of the default workload only
+    named = args.layers == 32 and K == 4
+    if "verify_persistent" in classes:
+        traffic, traffic_src = (PERSISTENT_7B_TRAFFIC_BYTES, PERSISTENT_7B_TRAFFIC_SOURCE) if named else (None, None)
+    else:
+        traffic, traffic_src = (GATEUP_TRAFFIC_BYTES, GATEUP_TRAFFIC_SOURCE) if named else (None, None)
     roofline = {"bound": "hbm", "kernel": k_name, "achieved": achieved, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                 "frac": achieved / (HBM_PEAK / 1e9), "traffic": traffic,
-                "traffic_source": (PERSISTENT_7B_TRAFFIC_SOURCE + STORED) if traffic else None,
-                "algorithmic_bytes_per_launch": k_bytes, "avg_launch_us": k_us}
+                "traffic_source": (traffic_src + STORED) if traffic else None,
+                "algorithmic_bytes_per_launch": k_bytes, "avg_launch_us": k_us,
+                # the whole verify pass (every launch of it) over its host-timed duration: the figure to set beside the
+                # dominant kernel's, and the one that compares with a single-launch pass
+                "whole_pass": {"algorithmic_bytes": pass_bytes, "ms": 1e3 * dt / args.steps,
+                               "GBps": pass_bytes / (dt / args.steps) / 1e9, "frac": pass_bytes / (dt / args.steps) / HBM_PEAK,
+                               "traffic": ((PERSISTENT_7B_TRAFFIC_BYTES if "verify_persistent" in classes else PER_PHASE_PASS_TRAFFIC_BYTES) if named else None),
+                               "traffic_source": (((PERSISTENT_7B_TRAFFIC_SOURCE if "verify_persistent" in classes else GATEUP_TRAFFIC_SOURCE) + STORED) if named else None),
+                               "note": "the timed step also holds softmax, the rejection step and the roll-back (about 40 us)"}}
     # what a dependency-free read kernel reaches on this machine over a 2 GiB buffer (beyond the last-level cache):
     # the practical ceiling beside the nominal peak
     probe_buf = torch.empty(1 << 29, dtype=torch.float32, device=dev).fill_(1.0)
@@ -644,6 +657,20 @@ def main():
         return 1e3 * ts[len(ts) // 2]
     t_m, t_1 = forward_ms(M), forward_ms(1)
     check_status(sv, target)
+    # the other forward path on the same model and cache, for comparison (ss_model_set_persistent)
+    other = None
+    try:
+        sv.ss_model_set_persistent(target, not bool(args.persistent))
+        o_m, o_1 = forward_ms(M), forward_ms(1)
+        other = {"forward_path": "one launch per phase" if args.persistent else "persistent kernel",
+                 "t_verify_ms_rows_K_plus_1": o_m, "t_verify_ms_rows_1": o_1,
+                 "hbm_frac_of_peak_rows_K_plus_1": pass_bytes / (o_m * 1e-3) / HBM_PEAK,
+                 "note": "host-timed ss_verify_forward alone, as in `premise`"}
+    except sv.SpecVerifyError as e:            # the persistent kernel is not available on every device
+        other = {"forward_path": "persistent kernel", "unavailable": str(e)}
+    finally:
+        sv.ss_model_set_persistent(target, bool(args.persistent))
+    check_status(sv, target)
     premise = {"t_verify_ms_rows_K_plus_1": t_m, "t_verify_ms_rows_1": t_1, "premise_ratio": t_m / t_1,
                "note": f"host-timed ss_verify_forward alone, {M} rows against 1 row, same cache length; 1.0 = K draft tokens verified for the price of one"}
 
@@ -659,6 +686,7 @@ def main():
                         "hbm_GBps": pass_bytes / (dt / args.steps) / 1e9, "kernel_classes": classes},
         "roofline": roofline,
         "premise": premise,
+        "other_forward_path": other,
         "end_to_end": e2e,
     }
     if not args.no_layer_pass:
