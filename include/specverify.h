@@ -183,7 +183,7 @@ int ss_model_destroy(ss_model *model);
 int ss_model_set_persistent(ss_model *model, int32_t on);
 
 /* Tuning and test knobs of the persistent kernel (no effect on the per-phase path).
- * workgroups: size of the cooperative grid; 0 = default (one per compute unit), at most that.
+ * workgroups: size of the grid (every workgroup must be resident at once); 0 = default (one per compute unit), at most that.
  * data_sync: 1 (default): between GEMM phases the consumers validate the activation data itself
  * (elements not yet written carry a reserved bit pattern) instead of waiting at a device-wide
  * barrier; used for a launch only when every workgroup owns part of every GEMM phase (grid <=
