@@ -62,6 +62,7 @@ struct ss_model {
     float *part_o, *part_m, *part_l;
     float *logits_ws; // [max_rows][vocab] (draft step)
     float2 *stats_ws; // [max_rows]
+    float *nsq_ws = nullptr;       // per-tile sums of squares of a deferred RMSNorm (calls of at most 16 rows): [16][d_model / 16]
     float *splitk_ws = nullptr;    // partial tiles of split-K GEMM launches (models that take more than 16 rows per call)
     size_t splitk_ws_bytes = 0;
     unsigned *stats_cnt = nullptr; // [max_rows] arrival counters of the segmented row statistics (zero between launches)
@@ -234,6 +235,7 @@ extern "C" int ss_model_create(const ss_model_cfg *cfg, const ss_weights *w, ss_
         A((void **)&m->splitk_ws, m->splitk_ws_bytes, false);
     }
     A((void **)&m->stats_cnt, sizeof(unsigned) * (size_t)c.max_rows, true);
+    if (c.d_model % 256 == 0 && c.d_model / 16 <= NSQ_MAX_TILES) A((void **)&m->nsq_ws, sizeof(float) * 16 * (size_t)(c.d_model / 16), true);
     A((void **)&m->stats_part, row_stats_partial_bytes(c.max_rows, c.vocab) + 16, true);
     m->ws_bytes = ss_workspace_bytes(2 * (int64_t)c.max_rows, c.vocab); // target rows + draft rows of a step
     A(&m->ws, m->ws_bytes, true);
@@ -601,11 +603,19 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
     nsplit = (Lmax + chunk - 1) / chunk;
 
     const int wbits = c.weight_quant == SS_QUANT_INT4_G128 ? 4 : 8;
-    // the two residual projections name the RMSNorm that follows them: a launcher that has a row-wise last launch
-    // anyway (split K) writes the normalised planes there and says so
-    bool normed = false;
+    // The two residual projections name the RMSNorm that follows them.  A launcher that has a row-wise last launch
+    // anyway (split K, more than 16 rows) writes the normalised planes there (1); the kernels of at most 16 rows write
+    // h * gain as planes and per-tile sums of squares, and the GEMM that consumes the planes multiplies its sums by the
+    // row scale (2: the norm is deferred; no launch of its own either way).  0: the norm is still to be launched.
+    int normed = 0;
+    const int T = d / 16;
+    const bool defer_ok = R <= 16 && m->nsq_ws != nullptr;
     auto with_norm = [&](GemmArgs &g, const float *gain) {
         g.norm_gain = gain; g.norm_act = m->act_a; g.norm_act_plane = pl * d; g.norm_ld = d; g.norm_eps = c.rms_eps;
+        if (defer_ok) { g.nsq_out = m->nsq_ws; g.nsq_ld = T; }
+    };
+    auto consumes_norm = [&](GemmArgs &g) { // the GEMM reads act_a: tell it when the row scale is still missing
+        if (normed == 2) { g.act_nsq = m->nsq_ws; g.act_nsq_tiles = T; g.act_nsq_ld = T; g.norm_eps = c.rms_eps; }
     };
     for (int l = 0; l < c.n_layers; ++l) {
         const ss_layer_weights &L = m->layers[l];
@@ -622,6 +632,7 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
         g.act_out = m->act_q; g.act_out_plane = pl * W; g.ld_act_out = W;
         g.H = c.n_heads; g.hd = c.head_dim; g.M = M; g.S = kv->S; g.max_pos = c.max_pos;
         g.len = kv->len_dev; g.rope = m->rope; g.kcache = kc; g.vcache = vc;
+        consumes_norm(g);
         {
             ProfScope ps(m, PT_QKV, st);
             launch_gemm(c.dtype, EPI_QKV, g, st);
@@ -659,6 +670,7 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
         u.W = L.wgu; u.N = F; u.K = d; u.wscale = c.weight_quant ? L.sgu : nullptr; u.wbits = wbits;
         u.act = m->act_a; u.act_plane = pl * d; u.ld_act = d; u.R = R;
         u.act_out = m->act_z; u.act_out_plane = pl * F; u.ld_act_out = F;
+        consumes_norm(u);
         {
             ProfScope ps(m, PT_GATEUP, st);
             launch_gemm(c.dtype, EPI_SWIGLU, u, st);

@@ -28,7 +28,32 @@ struct EpiPre {
     float resid[4];
     float2 rope[4];
     int pos;
+    float gain[4]; // deferred norm, producer: the next norm's gains of the lane's four columns
 };
+// Deferred norm, consumer: a lane's quarter of its activation row's per-tile sums of squares (lane group g holds tiles
+// [g * T/4, (g + 1) * T/4) of row c), requested ahead of the K loop like the rest ...
+constexpr int NSQ4 = NSQ_MAX_TILES / 16;
+__device__ __forceinline__ void nsq_prefetch(const GemmArgs &a, int rt, float4 (&nsq)[NSQ4]) {
+    const int lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
+    const int m = min(rt * 16 + c, a.R - 1);
+    const float4 *p = reinterpret_cast<const float4 *>(a.act_nsq + (size_t)m * a.act_nsq_ld + g * (a.act_nsq_tiles / 4));
+    const int n4 = a.act_nsq_tiles / 16;
+#pragma unroll
+    for (int i = 0; i < NSQ4; ++i) nsq[i] = p[min(i, n4 - 1)]; // (surplus slots repeat the last one and are not added)
+}
+// ... and 1 / rms of the row from them: fixed order inside a lane, then over the four lane groups
+__device__ __forceinline__ float deferred_row_scale(const GemmArgs &a, const float4 (&nsq)[NSQ_MAX_TILES / 16]) {
+    const int n4 = a.act_nsq_tiles / 16;
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < NSQ_MAX_TILES / 16; ++i) s += i < n4 ? (nsq[i].x + nsq[i].y) + (nsq[i].z + nsq[i].w) : 0.f;
+    const float s1 = __shfl_xor(s, 16);
+    const float lo = (threadIdx.x & 16) ? s1 : s, hi = (threadIdx.x & 16) ? s : s1; // (g even, g odd) of the pair, in that order
+    const float pair = lo + hi;
+    const float p2 = __shfl_xor(pair, 32);
+    const float tot = (threadIdx.x & 32) ? p2 + pair : pair + p2;                   // (groups 0,1) + (groups 2,3)
+    return 1.0f / sqrtf(tot / (float)a.K + a.norm_eps);
+}
 template <typename T, int EPI>
 __device__ __forceinline__ void epi_prefetch(const GemmArgs &a, const int (&n0)[(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1], int rt, EpiPre &pre) {
     const int lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
@@ -36,6 +61,10 @@ __device__ __forceinline__ void epi_prefetch(const GemmArgs &a, const int (&n0)[
     if constexpr (EPI == EPI_RESID) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) pre.resid[v] = a.resid[(size_t)m * a.ldo + min(n0[0] + 4 * g + v, a.N - 1)];
+        if (a.nsq_out) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) pre.gain[v] = a.norm_gain[min(n0[0] + 4 * g + v, a.N - 1)];
+        }
     } else if constexpr (EPI == EPI_QKV) {
         const int d_all = a.H * a.hd;
         const int region = n0[0] / d_all;
@@ -63,13 +92,31 @@ __device__ __forceinline__ void apply_epilogue(const GemmArgs &a, const float (&
     if (m >= a.R) return;
 
     if constexpr (EPI == EPI_STORE || EPI == EPI_RESID) {
+        float hn[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int n = n0[0] + 4 * g + v;
+            hn[v] = 0.f;
             if (n < a.N) {
                 const size_t o = (size_t)m * a.ldo + n;
-                a.out[o] = (EPI == EPI_RESID) ? (pre ? pre->resid[v] : a.resid[o]) + r[0][v] : r[0][v];
+                hn[v] = (EPI == EPI_RESID) ? (pre ? pre->resid[v] : a.resid[o]) + r[0][v] : r[0][v];
+                a.out[o] = hn[v];
             }
+        }
+        if (EPI == EPI_RESID && a.nsq_out && pre) { // deferred norm: h * gain as planes, the tile's sum of squares per row
+            ActPlanes<T> np{reinterpret_cast<T *>(a.norm_act), a.norm_act_plane, a.norm_ld};
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int n = n0[0] + 4 * g + v;
+                if (n < a.N) store_act(np, (size_t)m * a.norm_ld + n, hn[v] * pre->gain[v]);
+            }
+            float sq = (hn[0] * hn[0] + hn[1] * hn[1]) + (hn[2] * hn[2] + hn[3] * hn[3]);
+            const float s1 = __shfl_xor(sq, 16);
+            const float lo = (lane & 16) ? s1 : sq, hi = (lane & 16) ? sq : s1;
+            const float pair = lo + hi;
+            const float p2 = __shfl_xor(pair, 32);
+            const float tot = (lane & 32) ? p2 + pair : pair + p2;
+            if (g == 0) a.nsq_out[(size_t)m * a.nsq_ld + n0[0] / 16] = tot;
         }
     } else if constexpr (EPI == EPI_SWIGLU) {
         ActPlanes<T> z{reinterpret_cast<T *>(a.act_out), a.act_out_plane, a.ld_act_out};
@@ -144,7 +191,8 @@ __device__ __forceinline__ void apply_epilogue(const GemmArgs &a, const float (&
 // Sum of the waves' partial tiles of row tile rt (fixed order) and the epilogue, by one wave.
 template <typename T, int EPI, int NW>
 __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, const float (&red)[NW][(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1][4][64],
-                                              const int (&n0)[(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1], int rt, const EpiPre *pre = nullptr) {
+                                              const int (&n0)[(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1], int rt, const EpiPre *pre = nullptr,
+                                              float rs = 1.0f) {
     constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
     const int lane = threadIdx.x & 63;
     float r[NT][4];
@@ -155,7 +203,7 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, const float (&r
             float sum = red[0][t][v][lane];
 #pragma unroll 4
             for (int w2 = 1; w2 < NW; ++w2) sum += red[w2][t][v][lane];
-            r[t][v] = sum;
+            r[t][v] = sum * rs; // rs: the row scale of a deferred norm (1 otherwise: exact)
         }
     apply_epilogue<T, EPI>(a, r, n0, rt, pre);
 }
@@ -207,11 +255,23 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(GemmArgs a) {
     for (int r = 0; r < RT; ++r)
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    constexpr bool PRE = EPI == EPI_RESID || EPI == EPI_QKV; // the epilogue's own operands, asked for ahead of the K loop
+    constexpr bool PRE = EPI != EPI_STORE; // the epilogue's own operands, asked for ahead of the K loop
     EpiPre pre[RT];
     if (PRE && wave == 0) {
 #pragma unroll
         for (int r = 0; r < RT; ++r) epi_prefetch<T, EPI>(a, n0, rt0 + r, pre[r]);
+    }
+    // the row scale of a deferred norm on the activations (1 otherwise), worked out by the epilogue's wave up front
+    float rs[RT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r) rs[r] = 1.0f;
+    if (a.act_nsq && wave == 0) {
+#pragma unroll
+        for (int r = 0; r < RT; ++r) {
+            float4 nsq[NSQ4];
+            nsq_prefetch(a, rt0 + r, nsq);
+            rs[r] = deferred_row_scale(a, nsq);
+        }
     }
 
     // Each wave takes 128-byte steps (two k-blocks) of every row, interleaved with the other waves,
@@ -251,7 +311,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(GemmArgs a) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) red[wave][t][v][lane] = acc[r][t][v];
         __syncthreads();
-        if (wave == 0) tile_epilogue<T, EPI, NW>(a, red, n0, rt0 + r, PRE ? &pre[r] : nullptr);
+        if (wave == 0) tile_epilogue<T, EPI, NW>(a, red, n0, rt0 + r, PRE ? &pre[r] : nullptr, rs[r]);
     }
 }
 
@@ -307,9 +367,21 @@ __global__ __launch_bounds__(NW * 64) void gemm_w8_kernel(GemmArgs a) {
     f32x4 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    constexpr bool PRE = EPI == EPI_RESID || EPI == EPI_QKV; // the epilogue's own operands, asked for ahead of the K loop
+    constexpr bool PRE = EPI != EPI_STORE; // the epilogue's own operands, asked for ahead of the K loop
     EpiPre pre;
     if (PRE && wave == 0) epi_prefetch<T, EPI>(a, n0, 0, pre);
+    // the row scale of a deferred norm on the activations (1 otherwise), worked out by the epilogue's wave up front
+    float rs[1];
+#pragma unroll
+    for (int r = 0; r < 1; ++r) rs[r] = 1.0f;
+    if (a.act_nsq && wave == 0) {
+#pragma unroll
+        for (int r = 0; r < 1; ++r) {
+            float4 nsq[NSQ4];
+            nsq_prefetch(a, 0 + r, nsq);
+            rs[r] = deferred_row_scale(a, nsq);
+        }
+    }
 
     const int nsteps = (K + 63) / 64; // 64 entries of K (64 bytes of a weight row) per step
     for (int ks = wave; ks < nsteps; ks += U * NW) {
@@ -348,7 +420,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_w8_kernel(GemmArgs a) {
             float sum = red[0][t][v][lane];
 #pragma unroll 4
             for (int w2 = 1; w2 < NW; ++w2) sum += red[w2][t][v][lane];
-            r[t][v] = sum * a.wscale[min(n0[t] + 4 * g + v, nrows_w - 1)];
+            r[t][v] = sum * a.wscale[min(n0[t] + 4 * g + v, nrows_w - 1)] * rs[0];
         }
     apply_epilogue<T, EPI>(a, r, n0, 0, PRE ? &pre : nullptr);
 }
@@ -413,9 +485,21 @@ __global__ __launch_bounds__(NW * 64) void gemm_w4_kernel(GemmArgs a) {
     f32x4 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    constexpr bool PRE = EPI == EPI_RESID || EPI == EPI_QKV; // the epilogue's own operands, asked for ahead of the K loop
+    constexpr bool PRE = EPI != EPI_STORE; // the epilogue's own operands, asked for ahead of the K loop
     EpiPre pre;
     if (PRE && wave == 0) epi_prefetch<T, EPI>(a, n0, rt, pre);
+    // the row scale of a deferred norm on the activations (1 otherwise), worked out by the epilogue's wave up front
+    float rs[1];
+#pragma unroll
+    for (int r = 0; r < 1; ++r) rs[r] = 1.0f;
+    if (a.act_nsq && wave == 0) {
+#pragma unroll
+        for (int r = 0; r < 1; ++r) {
+            float4 nsq[NSQ4];
+            nsq_prefetch(a, rt + r, nsq);
+            rs[r] = deferred_row_scale(a, nsq);
+        }
+    }
 
     const int nsteps = K / 128; // one scale group per step
     for (int ks = wave; ks < nsteps; ks += U * NW) {
@@ -456,7 +540,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_w4_kernel(GemmArgs a) {
         for (int v = 0; v < 4; ++v) red[wave][t][v][lane] = acc[t][v];
     __syncthreads();
     if (wave != 0) return;
-    tile_epilogue<T, EPI, NW>(a, red, n0, rt, PRE ? &pre : nullptr);
+    tile_epilogue<T, EPI, NW>(a, red, n0, rt, PRE ? &pre : nullptr, rs[0]);
 }
 
 // More than 16 rows (larger batches, prefill): the waves of a workgroup split the output columns instead
@@ -756,7 +840,7 @@ __global__ __launch_bounds__(64) void gemm_splitk_finish_kernel(GemmArgs a) {
 // A residual projection (whole 16-column tiles, dense output rows) leaves its partials as plain rows, and the
 // second launch is the RMSNorm kernel with the sum over the splits in front: it completes h and, when the caller
 // named the norm that follows, writes that too (returns true then).
-template <typename T, int EPI, int NW, int RT, int QB = 0> static bool launch_wide(const GemmArgs &a0, int tiles, int row_tiles, hipStream_t st) {
+template <typename T, int EPI, int NW, int RT, int QB = 0> static int launch_wide(const GemmArgs &a0, int tiles, int row_tiles, hipStream_t st) {
     constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
     constexpr int WIDE_KS = WIDE_SLAB_BYTES / (int)sizeof(T);
     GemmArgs a = a0;
@@ -779,15 +863,15 @@ template <typename T, int EPI, int NW, int RT, int QB = 0> static bool launch_wi
     if (a.splitk_rows) {
         launch_splitk_resid_norm(std::is_same<T, bf16_t>::value ? 1 : 0, a.out, a.splitk_ws, a.ksplit, a.norm_gain, a.R, a.N, a.norm_eps,
                                  a.norm_act, a.norm_act_plane, a.norm_ld, st);
-        return a.norm_gain != nullptr;
+        return a.norm_gain != nullptr ? 1 : 0;
     }
     if (a.ksplit > 1) hipLaunchKernelGGL((gemm_splitk_finish_kernel<T, EPI>), dim3(tiles, row_tiles), dim3(64), 0, st, a);
-    return false;
+    return 0;
 }
 
-template <typename T, int EPI, int QB> static bool launch_wide_any(const GemmArgs &a, int tiles, int row_tiles, hipStream_t st);
+template <typename T, int EPI, int QB> static int launch_wide_any(const GemmArgs &a, int tiles, int row_tiles, hipStream_t st);
 
-template <typename T, int EPI> static bool launch_gemm_t(const GemmArgs &a, hipStream_t st) {
+template <typename T, int EPI> static int launch_gemm_t(const GemmArgs &a, hipStream_t st) {
     int tiles;
     if (EPI == EPI_QKV) tiles = 3 * a.H * (a.hd / 32);
     else tiles = (a.N + 15) / 16;
@@ -798,12 +882,12 @@ template <typename T, int EPI> static bool launch_gemm_t(const GemmArgs &a, hipS
         // x (1 - 8 steps in flight) per kind of epilogue on the 7B-shaped layer
         if (EPI == EPI_SWIGLU || EPI == EPI_QKV) hipLaunchKernelGGL((gemm_kernel<T, EPI, 2, 2, 1>), dim3(tiles, 1), dim3(2 * 64), 0, st, a);
         else hipLaunchKernelGGL((gemm_kernel<T, EPI, 8, 2, 1>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
-        return false;
+        return (EPI == EPI_RESID && a.nsq_out) ? 2 : 0;
     }
     return launch_wide_any<T, EPI, 0>(a, tiles, row_tiles, st);
 }
 
-template <typename T, int EPI, int QB> static bool launch_wide_any(const GemmArgs &a, int tiles, int row_tiles, hipStream_t st) {
+template <typename T, int EPI, int QB> static int launch_wide_any(const GemmArgs &a, int tiles, int row_tiles, hipStream_t st) {
     // larger batches and prefill chunks: waves split the columns; fewer waves per workgroup when the
     // matrix has few tiles, so that the launch still covers the chip
     constexpr bool FUSED = EPI == EPI_SWIGLU || EPI == EPI_QKV; // two weight tiles per wave: more registers
@@ -831,18 +915,18 @@ template <typename T, int EPI, int QB> static bool launch_wide_any(const GemmArg
 // Two steps in flight per wave; 8 waves per workgroup for the projections with few tiles, 4 for the fused epilogues
 // (measured per kind of epilogue on the 7B-shaped layer among (2 | 4 | 8 | 16 waves) x (1..4 steps)) - the registers
 // go to the activation operands (four 16-byte loads per weight load), so more steps in flight cost occupancy.
-template <int EPI> static bool launch_gemm_w8(const GemmArgs &a, hipStream_t st) {
+template <int EPI> static int launch_gemm_w8(const GemmArgs &a, hipStream_t st) {
     const int tiles = EPI == EPI_QKV ? 3 * a.H * (a.hd / 32) : (a.N + 15) / 16;
     const int row_tiles = (a.R + 15) / 16;
     if (row_tiles > 1) return launch_wide_any<bf16_t, EPI, 8>(a, tiles, row_tiles, st);
     if (EPI == EPI_SWIGLU || EPI == EPI_QKV) hipLaunchKernelGGL((gemm_w8_kernel<EPI, 4, 2>), dim3(tiles, 1), dim3(4 * 64), 0, st, a);
     else hipLaunchKernelGGL((gemm_w8_kernel<EPI, 8, 2>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
-    return false;
+    return (EPI == EPI_RESID && a.nsq_out) ? 2 : 0;
 }
 
 // One step in flight, 8 waves (4 for the fused epilogues): measured best of (2 | 4 | 8 | 16 waves) x (1 | 2 steps) on
 // the 7B-shaped layer (a step already holds 13 to 17 loads per lane: one of weights, eight of activations, the scales)
-template <int EPI> static bool launch_gemm_w4(const GemmArgs &a, hipStream_t st) {
+template <int EPI> static int launch_gemm_w4(const GemmArgs &a, hipStream_t st) {
     const int tiles = EPI == EPI_QKV ? 3 * a.H * (a.hd / 32) : (a.N + 15) / 16;
     const int row_tiles = (a.R + 15) / 16;
     const int nrows_w = EPI == EPI_SWIGLU ? 2 * a.N : a.N;
@@ -851,10 +935,10 @@ template <int EPI> static bool launch_gemm_w4(const GemmArgs &a, hipStream_t st)
     if (row_tiles > 1 && nrows_w % 4 == 0 && (reinterpret_cast<uintptr_t>(a.wscale) & 15) == 0) return launch_wide_any<bf16_t, EPI, 4>(a, tiles, row_tiles, st);
     if (EPI == EPI_SWIGLU || EPI == EPI_QKV) hipLaunchKernelGGL((gemm_w4_kernel<EPI, 4, 1>), dim3(tiles, row_tiles), dim3(4 * 64), 0, st, a);
     else hipLaunchKernelGGL((gemm_w4_kernel<EPI, 8, 1>), dim3(tiles, row_tiles), dim3(8 * 64), 0, st, a);
-    return false;
+    return (EPI == EPI_RESID && a.nsq_out && row_tiles == 1) ? 2 : 0;
 }
 
-bool launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st) {
+int launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st) {
     if (a.wscale && a.wbits == 4) { // int4 weights: the caller has checked bf16 planes and K % 128 == 0
         switch (epi) {
         case EPI_STORE: return launch_gemm_w4<EPI_STORE>(a, st);
@@ -862,7 +946,7 @@ bool launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st) {
         case EPI_SWIGLU: return launch_gemm_w4<EPI_SWIGLU>(a, st);
         case EPI_QKV: return launch_gemm_w4<EPI_QKV>(a, st);
         }
-        return false;
+        return 0;
     }
     if (a.wscale) { // int8 weights: the caller has checked bf16 planes and K % 16 == 0
         switch (epi) {
@@ -871,7 +955,7 @@ bool launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st) {
         case EPI_SWIGLU: return launch_gemm_w8<EPI_SWIGLU>(a, st);
         case EPI_QKV: return launch_gemm_w8<EPI_QKV>(a, st);
         }
-        return false;
+        return 0;
     }
 #define SS_CASE(EP)                                                  \
     case EP:                                                         \
@@ -883,7 +967,7 @@ bool launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st) {
         SS_CASE(EPI_QKV)
     }
 #undef SS_CASE
-    return false;
+    return 0;
 }
 
 } // namespace ss

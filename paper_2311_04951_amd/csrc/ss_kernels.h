@@ -47,13 +47,23 @@ struct GemmArgs {
     size_t norm_act_plane;
     int norm_ld;
     float norm_eps;
+    // ... a launcher of at most 16 rows defers it instead (returns 2): the planes receive h * gain without the row
+    // scale, and nsq_out[row * nsq_ld + tile] the sum of squares of the 16 columns of each output tile.  The GEMM that
+    // consumes such planes gets act_nsq / act_nsq_tiles / act_nsq_ld (and norm_eps) and multiplies its sums by
+    // 1 / sqrt(sum over the tiles / K + eps) of the row: the norm is linear in the row scale.
+    float *nsq_out;
+    int nsq_ld;
+    const float *act_nsq;
+    int act_nsq_tiles, act_nsq_ld;
     // weight-only int8: W is int8 [N][K] and output column n is scaled by wscale[n] (NULL: W is in the storage type).
     // bf16 activation planes only; K a multiple of 16.
     const float *wscale;
     int wbits; // with wscale: 8 = int8, one scale per output column; 4 = int4, two entries per byte, scales [K/128][columns] (at most 16 rows, K % 128 == 0)
 };
-// true: the RMSNorm asked for through norm_gain has been written as well
-bool launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st);
+// 0: no norm written; 1: the RMSNorm asked for through norm_gain has been written as well; 2: written in the deferred
+// form (planes without the row scale + per-tile sums of squares in nsq_out)
+int launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st);
+constexpr int NSQ_MAX_TILES = 320; // most 16-column tiles of a deferred norm (d_model <= 5120); a multiple of 16
 
 struct AttnArgs {
     const void *q; // activation planes [planes][R16][ldq], rotated queries
