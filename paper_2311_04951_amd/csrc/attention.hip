@@ -29,10 +29,10 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 }
 
 // a single split: the workgroup normalises and writes the activation planes itself (no partials, no merge launch)
-template <typename T, int HD>
-__global__ __launch_bounds__(256) void attn_direct_kernel(AttnArgs a) {
-    __shared__ AttnSmem<HD, 4> sm;
-    attn_unit<T, HD, 4, false, true>(a, 0, blockIdx.y, blockIdx.z, a.len[blockIdx.z], sm);
+template <typename T, int HD, int NWX = 4>
+__global__ __launch_bounds__(NWX * 64) void attn_direct_kernel(AttnArgs a) {
+    __shared__ AttnSmem<HD, NWX> sm;
+    attn_unit<T, HD, NWX, false, true>(a, 0, blockIdx.y, blockIdx.z, a.len[blockIdx.z], sm);
 }
 
 template <typename T>
@@ -45,6 +45,11 @@ __global__ void attn_merge_kernel(AttnArgs a) {
 template <typename T> static void launch_attention_t(const AttnArgs &a, hipStream_t st) {
     dim3 grid(a.nsplit, a.H, a.B);
     if (a.nsplit == 1) {
+        // few units with a short context (one split by the host's choice): 8 waves, so that a wave has one step
+        if (a.hd == 128 && a.B * a.H < 256) {
+            hipLaunchKernelGGL((attn_direct_kernel<T, 128, 8>), grid, dim3(512), 0, st, a);
+            return;
+        }
         if (a.hd == 128) hipLaunchKernelGGL((attn_direct_kernel<T, 128>), grid, dim3(256), 0, st, a);
         else if (a.hd == 64) hipLaunchKernelGGL((attn_direct_kernel<T, 64>), grid, dim3(256), 0, st, a);
         else hipLaunchKernelGGL((attn_direct_kernel<T, 32>), grid, dim3(256), 0, st, a);
