@@ -598,7 +598,7 @@ static void run_layers(ss_model *m, ss_kv_cache *kv, int batch, int M, hipStream
     // layer against 109 - 112 with two splits and the merge)
     const int units = batch * c.n_heads;
     int want = units >= 256 ? 1 : (512 + units - 1) / units;
-    if (Lmax <= 160) want = 1; // up to here one workgroup per unit beats splits + merge launch (measured at 100, 145, 250 positions: -1.3 %, -0.9 %, +0.4 % of a pass)
+    if (Lmax <= 192) want = 1; // up to about 200 positions one workgroup per unit beats splits + merge launch (measured at 100, 145, 250 positions: -1.3 %, -0.9 %, +0.4 % of a pass)
     int nsplit = std::max(1, std::min(std::min(want, (Lmax + 63) / 64), MAX_SPLITS));
     const int chunk = round_up((Lmax + nsplit - 1) / nsplit, 64);
     nsplit = (Lmax + chunk - 1) / chunk;

@@ -45,7 +45,7 @@ __global__ void attn_merge_kernel(AttnArgs a) {
 template <typename T> static void launch_attention_t(const AttnArgs &a, hipStream_t st) {
     dim3 grid(a.nsplit, a.H, a.B);
     if (a.nsplit == 1) {
-        // few units with a short context (one split by the host's choice): 8 waves, so that a wave has one step
+        // few units with a short context (one split by the host's choice): 8 waves, so that a wave has one step up to 256 positions
         if (a.hd == 128 && a.B * a.H < 256) {
             hipLaunchKernelGGL((attn_direct_kernel<T, 128, 8>), grid, dim3(512), 0, st, a);
             return;
