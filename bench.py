@@ -26,13 +26,13 @@ HBM_PEAK = 8.0e12  # B/s, MI355X published peak
 # HBM bytes per launch of the persistent kernel on the default workload: a stored measurement (two rocprofv3 --pmc runs,
 # FETCH_SIZE then WRITE_SIZE, each scaled by what the counter reads for a plain 1 GiB device copy), valid for the kernel
 # source it was taken on; bench.py reports it only on that workload and names the file it comes from
-PERSISTENT_7B_TRAFFIC_BYTES = 13.602e9  # 13.466 GB fetched + 0.136 GB written
+PERSISTENT_7B_TRAFFIC_BYTES = 13.601e9  # 13.465 GB fetched + 0.136 GB written
 PERSISTENT_7B_TRAFFIC_SOURCE = "profiles/verify_pass_7b_persistent_hbm_traffic.txt"
 # the same kind of stored measurement for the stand-alone accept workload (the kernels stop reading a sequence's rows at
 # its first rejection, so they fetch less than "every logit once") and for the batched long-context pass
 ACCEPT_TRAFFIC_BYTES, ACCEPT_TRAFFIC_SOURCE = 366.5e6, "profiles/standalone_accept_hbm_traffic.txt"
-GATEUP_TRAFFIC_BYTES, GATEUP_TRAFFIC_SOURCE = 181.5e6, "profiles/verify_pass_7b_per_phase_hbm_traffic.txt"
-PER_PHASE_PASS_TRAFFIC_BYTES = 13.523e9  # 13.482 GB fetched + 0.041 GB written over the launches of one pass (same file)
+GATEUP_TRAFFIC_BYTES, GATEUP_TRAFFIC_SOURCE = 181.4e6, "profiles/verify_pass_7b_per_phase_hbm_traffic.txt"
+PER_PHASE_PASS_TRAFFIC_BYTES = 13.493e9  # 13.461 GB fetched + 0.032 GB written over the launches of one pass (same file)
 BATCHED_TRAFFIC_BYTES, BATCHED_TRAFFIC_SOURCE = 34.001e9, "profiles/batched_long_context_pass_hbm_traffic.txt"
 STORED = " (stored counter measurement of this workload, not taken in this run)"
 
