@@ -197,6 +197,58 @@ __device__ __forceinline__ int rotated(int i, int rot, int nst) {
     return i >= nst ? i - nst : i;
 }
 
+// Activations of the kernels for at most 16 rows, through a wave-private piece of LDS.  A step of a wave is UPS units
+// of 16 bytes of K for every row and plane: PL * R * UPS pieces.  Loaded per lane into MFMA operand layout that is
+// 2 * PL * UPS / 8 load instructions with R / 16 of their lanes active; instead ceil(PL * R * UPS / 64) full-width
+// load-to-LDS instructions bring them (lane l of instruction i brings piece 64 i + l; the pieces land in lane order,
+// 16 bytes each) and the operands are read back from LDS.  Piece (plane * R + row) * UPS + (unit xor row) holds unit
+// `unit` of the row, so that the 16 rows a wave reads together fall into different banks.  Lanes of rows that do not
+// exist read a slot that holds zeros.  Measured on the 7B-shaped layer: 5-row pass 3.62 -> 3.37 ms, 1 row 3.29 -> 3.18.
+template <typename T, int UPS> struct ActStage {
+    static constexpr int PL = Traits<T>::PLANES, EPU = 16 / (int)sizeof(T);
+    static constexpr int SLOTS = PL * 16 * UPS; // pieces of a step at 16 rows
+    static constexpr int NDMA = SLOTS / 64;     // ... and the instructions that bring them
+    static constexpr int BYTES = (SLOTS + 1) * 16; // LDS of one step of one wave (the last slot holds zeros)
+    typedef const void __attribute__((address_space(1))) *gptr;
+    typedef void __attribute__((address_space(3))) *lptr;
+    const T *src[NDMA]; // the row (and plane) of this lane's piece of instruction i
+    int ucol[NDMA];     // ... and its first K element inside the step
+    int rows, npiece, kmax;
+
+    // row0: first row of the tile; K: reduction length (a multiple of EPU)
+    __device__ __forceinline__ void init(const GemmArgs &a, int row0, int K, int lane) {
+        rows = min(a.R - row0, 16);
+        npiece = PL * rows * UPS;
+        kmax = K - EPU;
+#pragma unroll
+        for (int i = 0; i < NDMA; ++i) {
+            const int p = min(i * 64 + lane, npiece - 1); // surplus lanes repeat the last piece into slots nobody reads
+            const int plane = p / (rows * UPS), rem = p - plane * rows * UPS, row = rem / UPS, pos = rem % UPS;
+            src[i] = reinterpret_cast<const T *>(a.act) + (size_t)plane * a.act_plane + (size_t)(row0 + row) * a.ld_act;
+            ucol[i] = (pos ^ (row & (UPS - 1))) * EPU;
+        }
+    }
+    __device__ __forceinline__ static void clear(unsigned char *region, int lane) {
+        if (lane == 0) *reinterpret_cast<u32x4 *>(region + SLOTS * 16) = zero16();
+    }
+    // asks for the step that starts at K element k0 (columns past the end are clamped to the row's last unit: the
+    // weights there are zero, so any finite value does)
+    __device__ __forceinline__ void request(unsigned char *region, int k0) const {
+#pragma unroll
+        for (int i = 0; i < NDMA; ++i)
+            if (i * 64 < npiece) __builtin_amdgcn_global_load_lds((gptr)(src[i] + min(k0 + ucol[i], kmax)), (lptr)(region + i * 1024), 16, 0, 0);
+    }
+    // byte offset in a step's region of row c's unit `unit` of plane pl
+    __device__ __forceinline__ int operand_offset(int c, int unit, int pl) const {
+        return c < rows ? ((pl * rows + c) * UPS + (unit ^ (c & (UPS - 1)))) * 16 : SLOTS * 16;
+    }
+};
+// every load of the wave has landed (weights in registers, activations in LDS); the compiler may not move LDS reads above
+__device__ __forceinline__ void act_stage_wait() {
+    __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
+    asm volatile("" ::: "memory");
+}
+
 // Sum of the waves' partial tiles of row tile rt (fixed order) and the epilogue, by one wave.
 template <typename T, int EPI, int NW>
 __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, const float (&red)[NW][(EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1][4][64],
@@ -217,15 +269,14 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, const float (&r
     apply_epilogue<T, EPI>(a, r, n0, rt, pre);
 }
 
-// NW = wavefronts per workgroup (interleaved over K), U = 128-byte steps in flight per wave,
-// RT = row tiles (of 16 rows) per workgroup: blockIdx.y covers row tiles [blockIdx.y*RT, +RT)
-template <typename T, int EPI, int NW, int U, int RT>
+// NW = wavefronts per workgroup (interleaved over K), U = 128-byte steps in flight per wave; blockIdx.y = row tile
+template <typename T, int EPI, int NW, int U>
 __global__ __launch_bounds__(NW * 64) void gemm_kernel(GemmArgs a) {
     constexpr int E = Traits<T>::E, KB = 4 * E;
     constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 15, g = lane >> 4;
-    const int rt0 = blockIdx.y * RT;
+    const int rt = blockIdx.y;
     const int K = a.K;
 
     int n0[NT];
@@ -250,37 +301,19 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(GemmArgs a) {
         if (n > nrows_w - 1) n = nrows_w - 1; // ragged last tile: load a valid row, masked at the store
         wrow[t] = W + (size_t)n * K + g * E;
     }
-    ActPlanes<T> act{const_cast<T *>(reinterpret_cast<const T *>(a.act)), a.act_plane, a.ld_act};
-    size_t aoff[RT];
-    bool row_live[RT]; // rows past R contribute nothing: skip their loads
-#pragma unroll
-    for (int r = 0; r < RT; ++r) {
-        aoff[r] = (size_t)((rt0 + r) * 16 + c) * a.ld_act + g * E;
-        row_live[r] = (rt0 + r) * 16 + c < a.R;
-    }
 
-    f32x4 acc[RT][NT];
+    f32x4 acc[NT];
 #pragma unroll
-    for (int r = 0; r < RT; ++r)
-#pragma unroll
-        for (int t = 0; t < NT; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
     constexpr bool PRE = EPI != EPI_STORE; // the epilogue's own operands, asked for ahead of the K loop
-    EpiPre pre[RT];
-    if (PRE && wave == 0) {
-#pragma unroll
-        for (int r = 0; r < RT; ++r) epi_prefetch<T, EPI>(a, n0, rt0 + r, pre[r]);
-    }
+    EpiPre pre;
+    if (PRE && wave == 0) epi_prefetch<T, EPI>(a, n0, rt, pre);
     // the row scale of a deferred norm on the activations (1 otherwise), worked out by the epilogue's wave up front
-    float rs[RT];
-#pragma unroll
-    for (int r = 0; r < RT; ++r) rs[r] = 1.0f;
+    float rs = 1.0f;
     if (a.act_nsq && wave == 0) {
-#pragma unroll
-        for (int r = 0; r < RT; ++r) {
-            float4 nsq[NSQ4];
-            nsq_prefetch(a, rt0 + r, nsq);
-            rs[r] = deferred_row_scale(a, nsq);
-        }
+        float4 nsq[NSQ4];
+        nsq_prefetch(a, rt, nsq);
+        rs = deferred_row_scale(a, nsq);
     }
 
     // Each wave takes 128-byte steps (two k-blocks) of every row, interleaved with the other waves,
@@ -291,42 +324,56 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(GemmArgs a) {
     const int nkb = (K + KB - 1) / KB;
     const int nst = (nkb + 1) / 2;
     const int rot = k_rotation(nst);
+    typedef ActStage<T, 8> Stage; // a step = 8 units per row and plane; lane (c, g) reads unit 4j + g for k-block j
+    __shared__ __align__(16) unsigned char alds[NW][U][Stage::BYTES];
+    Stage stage;
+    stage.init(a, rt * 16, K, lane);
+    int rdoff[2][Stage::PL];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int pl = 0; pl < Stage::PL; ++pl) rdoff[j][pl] = stage.operand_offset(c, 4 * j + g, pl);
+#pragma unroll
+    for (int s = 0; s < U; ++s) Stage::clear(alds[wave][s], lane);
     for (int kp = wave; 2 * kp < nkb; kp += U * NW) {
         u32x4 w[U][NT][2];
-        Act<T> av[U][2][RT];
+        Act<T> av[U][2];
 #pragma unroll
-        for (int s = 0; s < U; ++s)
+        for (int s = 0; s < U; ++s) {
+            const int k0 = 2 * rotated(kp + s * NW, rot, nst) * KB; // (a step past the end: zero weights)
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                const int k = (2 * rotated(kp + s * NW, rot, nst) + j) * KB;
+                const int k = k0 + j * KB;
                 const bool ok = k + g * E < K; // K is a multiple of E
 #pragma unroll
                 for (int t = 0; t < NT; ++t) w[s][t][j] = ok ? ld16_global(wrow[t] + k) : zero16();
-#pragma unroll
-                for (int r = 0; r < RT; ++r) av[s][j][r] = (ok && row_live[r]) ? load_act(act, aoff[r] + k) : zero_act<T>();
             }
+            stage.request(alds[wave][s], k0);
+        }
+        act_stage_wait();
 #pragma unroll
         for (int s = 0; s < U; ++s)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
-                for (int r = 0; r < RT; ++r)
+                for (int pl = 0; pl < Stage::PL; ++pl) av[s][j].p[pl] = *reinterpret_cast<const u32x4 *>(alds[wave][s] + rdoff[j][pl]);
+        asm volatile("" ::: "memory"); // ... nor below the next requests
 #pragma unroll
-                    for (int t = 0; t < NT; ++t) acc[r][t] = mma(acc[r][t], w[s][t][j], av[s][j][r]);
+        for (int s = 0; s < U; ++s)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int t = 0; t < NT; ++t) acc[t] = mma(acc[t], w[s][t][j], av[s][j]);
     }
 
-    // fixed-order sum of the waves' partial tiles, one row tile at a time; wave 0 applies the epilogue
+    // fixed-order sum of the waves' partial tiles; wave 0 applies the epilogue
     __shared__ float red[NW][NT][4][64];
 #pragma unroll
-    for (int r = 0; r < RT; ++r) {
-        if (r > 0) __syncthreads(); // wave 0 has read the previous row tile's partials
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) red[wave][t][v][lane] = acc[r][t][v];
-        __syncthreads();
-        if (wave == 0) tile_epilogue<T, EPI, NW>(a, red, n0, rt0 + r, PRE ? &pre[r] : nullptr, rs[r]);
-    }
+        for (int v = 0; v < 4; ++v) red[wave][t][v][lane] = acc[t][v];
+    __syncthreads();
+    if (wave == 0) tile_epilogue<T, EPI, NW>(a, red, n0, rt, PRE ? &pre : nullptr, rs);
 }
 
 // ---- weight-only int8 matrices (the quantised model Sections 2 and 3 assume; one fp32 scale per output row)
@@ -374,10 +421,6 @@ __global__ __launch_bounds__(NW * 64) void gemm_w8_kernel(GemmArgs a) {
         if (n > nrows_w - 1) n = nrows_w - 1; // ragged last tile: a valid row, masked at the store
         wrow[t] = W + (size_t)n * K + g * 16;
     }
-    ActPlanes<T> act{const_cast<T *>(reinterpret_cast<const T *>(a.act)), a.act_plane, a.ld_act};
-    const size_t aoff = (size_t)c * a.ld_act + g * 16;
-    const bool row_live = c < a.R;
-
     f32x4 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -399,18 +442,36 @@ __global__ __launch_bounds__(NW * 64) void gemm_w8_kernel(GemmArgs a) {
 
     const int nsteps = (K + 63) / 64; // 64 entries of K (64 bytes of a weight row) per step
     const int rot = k_rotation(nsteps); // (see gemm_kernel)
+    typedef ActStage<T, 8> Stage; // a step = 8 units per row and plane; lane (c, g) reads unit 2g + j for k-block j
+    __shared__ __align__(16) unsigned char alds[NW][U][Stage::BYTES];
+    Stage stage;
+    stage.init(a, 0, K, lane);
+    int rdoff[2][Stage::PL];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int pl = 0; pl < Stage::PL; ++pl) rdoff[j][pl] = stage.operand_offset(c, 2 * g + j, pl);
+#pragma unroll
+    for (int s = 0; s < U; ++s) Stage::clear(alds[wave][s], lane);
     for (int ks = wave; ks < nsteps; ks += U * NW) {
         u32x4 w[U][NT];
         Act<T> av[U][2];
 #pragma unroll
         for (int s = 0; s < U; ++s) {
-            const int k = rotated(ks + s * NW, rot, nsteps) * 64;
+            const int k = rotated(ks + s * NW, rot, nsteps) * 64; // (a step past the end: zero weights)
             const bool ok = k + g * 16 < K; // K is a multiple of 16
 #pragma unroll
             for (int t = 0; t < NT; ++t) w[s][t] = ok ? ld16_global(wrow[t] + k) : zero16();
-#pragma unroll
-            for (int j = 0; j < 2; ++j) av[s][j] = (ok && row_live) ? load_act(act, aoff + k + 8 * j) : zero_act<T>();
+            stage.request(alds[wave][s], k);
         }
+        act_stage_wait();
+#pragma unroll
+        for (int s = 0; s < U; ++s)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int pl = 0; pl < Stage::PL; ++pl) av[s][j].p[pl] = *reinterpret_cast<const u32x4 *>(alds[wave][s] + rdoff[j][pl]);
+        asm volatile("" ::: "memory");
 #pragma unroll
         for (int s = 0; s < U; ++s)
 #pragma unroll
@@ -490,12 +551,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_w4_kernel(GemmArgs a) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) ncol[t][v] = min(n0[t] + 4 * g + v, nrows_w - 1);
     }
-    ActPlanes<T> act{const_cast<T *>(reinterpret_cast<const T *>(a.act)), a.act_plane, a.ld_act};
     // calls of more than 16 rows: one workgroup per (column tile, row tile); every row tile streams the (quarter-size)
     // weights again
     const int rt = blockIdx.y;
-    const size_t aoff = (size_t)(rt * 16 + c) * a.ld_act + g * 32;
-    const bool row_live = rt * 16 + c < a.R;
 
     f32x4 acc[NT];
 #pragma unroll
@@ -518,6 +576,17 @@ __global__ __launch_bounds__(NW * 64) void gemm_w4_kernel(GemmArgs a) {
 
     const int nsteps = K / 128; // one scale group per step
     const int rot = k_rotation(nsteps); // (see gemm_kernel)
+    typedef ActStage<T, 16> Stage; // a step = 16 units per row and plane; lane (c, g) reads unit 4g + j for k-block j
+    __shared__ __align__(16) unsigned char alds[NW][U][Stage::BYTES];
+    Stage stage;
+    stage.init(a, rt * 16, K, lane);
+    int rdoff[4][Stage::PL];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int pl = 0; pl < Stage::PL; ++pl) rdoff[j][pl] = stage.operand_offset(c, 4 * g + j, pl);
+#pragma unroll
+    for (int s = 0; s < U; ++s) Stage::clear(alds[wave][s], lane);
     for (int ks = wave; ks < nsteps; ks += U * NW) {
         u32x4 w[U][NT];
         Act<T> av[U][4];
@@ -533,9 +602,16 @@ __global__ __launch_bounds__(NW * 64) void gemm_w4_kernel(GemmArgs a) {
 #pragma unroll
                 for (int v = 0; v < 4; ++v) sc[s][t][v] = a.wscale[(size_t)st2 * nrows_w + ncol[t][v]];
             }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) av[s][j] = (ok && row_live) ? load_act(act, aoff + (size_t)st2 * 128 + 8 * j) : zero_act<T>();
+            stage.request(alds[wave][s], st2 * 128);
         }
+        act_stage_wait();
+#pragma unroll
+        for (int s = 0; s < U; ++s)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int pl = 0; pl < Stage::PL; ++pl) av[s][j].p[pl] = *reinterpret_cast<const u32x4 *>(alds[wave][s] + rdoff[j][pl]);
+        asm volatile("" ::: "memory");
 #pragma unroll
         for (int s = 0; s < U; ++s)
 #pragma unroll
@@ -900,8 +976,8 @@ template <typename T, int EPI> static int launch_gemm_t(const GemmArgs &a, hipSt
         // fused epilogues (688 gate/up pairs, 384 rotary pairs at the 7B shape: several workgroups per compute unit anyway)
         // run 2 waves per workgroup, the projections with 256 tiles 8: measured over (1 | 2 | 3 | 4 | 5 | 6 | 8 | 16 waves)
         // x (1 - 8 steps in flight) per kind of epilogue on the 7B-shaped layer
-        if (EPI == EPI_SWIGLU || EPI == EPI_QKV) hipLaunchKernelGGL((gemm_kernel<T, EPI, 2, 2, 1>), dim3(tiles, 1), dim3(2 * 64), 0, st, a);
-        else hipLaunchKernelGGL((gemm_kernel<T, EPI, 8, 2, 1>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
+        if (EPI == EPI_SWIGLU || EPI == EPI_QKV) hipLaunchKernelGGL((gemm_kernel<T, EPI, 2, 2>), dim3(tiles, 1), dim3(2 * 64), 0, st, a);
+        else hipLaunchKernelGGL((gemm_kernel<T, EPI, 8, 2>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
         return (EPI == EPI_RESID && a.nsq_out) ? 2 : 0;
     }
     return launch_wide_any<T, EPI, 0>(a, tiles, row_tiles, st);
@@ -933,8 +1009,7 @@ template <typename T, int EPI, int QB> static int launch_wide_any(const GemmArgs
 }
 
 // Two steps in flight per wave; 8 waves per workgroup for the projections with few tiles, 4 for the fused epilogues
-// (measured per kind of epilogue on the 7B-shaped layer among (2 | 4 | 8 | 16 waves) x (1..4 steps)) - the registers
-// go to the activation operands (four 16-byte loads per weight load), so more steps in flight cost occupancy.
+// (measured per kind of epilogue on the 7B-shaped layer among (2 | 3 | 4 | 8 | 16 waves) x (1..4 steps)).
 template <int EPI> static int launch_gemm_w8(const GemmArgs &a, hipStream_t st) {
     const int tiles = EPI == EPI_QKV ? 3 * a.H * (a.hd / 32) : (a.N + 15) / 16;
     const int row_tiles = (a.R + 15) / 16;
@@ -944,8 +1019,9 @@ template <int EPI> static int launch_gemm_w8(const GemmArgs &a, hipStream_t st) 
     return (EPI == EPI_RESID && a.nsq_out) ? 2 : 0;
 }
 
-// One step in flight, 8 waves (4 for the fused epilogues): measured best of (2 | 4 | 8 | 16 waves) x (1 | 2 steps) on
-// the 7B-shaped layer (a step already holds 13 to 17 loads per lane: one of weights, eight of activations, the scales)
+// 4 waves with one step in flight for the fused epilogues, 8 waves with two for the projections: measured best of
+// (2 | 3 | 4 | 8 waves) x (1 | 2 steps) on the 7B-shaped layer (a step holds a weight load, the four scale loads and up
+// to 8 load-to-LDS instructions per tile)
 template <int EPI> static int launch_gemm_w4(const GemmArgs &a, hipStream_t st) {
     const int tiles = EPI == EPI_QKV ? 3 * a.H * (a.hd / 32) : (a.N + 15) / 16;
     const int row_tiles = (a.R + 15) / 16;
@@ -954,7 +1030,7 @@ template <int EPI> static int launch_gemm_w4(const GemmArgs &a, hipStream_t st) 
     // row count that is not a multiple of 4, one workgroup per (column tile, row tile)
     if (row_tiles > 1 && nrows_w % 4 == 0 && (reinterpret_cast<uintptr_t>(a.wscale) & 15) == 0) return launch_wide_any<bf16_t, EPI, 4>(a, tiles, row_tiles, st);
     if (EPI == EPI_SWIGLU || EPI == EPI_QKV) hipLaunchKernelGGL((gemm_w4_kernel<EPI, 4, 1>), dim3(tiles, row_tiles), dim3(4 * 64), 0, st, a);
-    else hipLaunchKernelGGL((gemm_w4_kernel<EPI, 8, 1>), dim3(tiles, row_tiles), dim3(8 * 64), 0, st, a);
+    else hipLaunchKernelGGL((gemm_w4_kernel<EPI, 8, 2>), dim3(tiles, row_tiles), dim3(8 * 64), 0, st, a);
     return (EPI == EPI_RESID && a.nsq_out && row_tiles == 1) ? 2 : 0;
 }
 
