@@ -204,9 +204,9 @@ __device__ __forceinline__ int rotated(int i, int rot, int nst) {
 // 16 bytes each) and the operands are read back from LDS.  Piece (plane * R + row) * UPS + (unit xor row) holds unit
 // `unit` of the row, so that the 16 rows a wave reads together fall into different banks.  Lanes of rows that do not
 // exist read a slot that holds zeros.  Measured on the 7B-shaped layer: 5-row pass 3.62 -> 3.37 ms, 1 row 3.29 -> 3.18.
-template <typename T, int UPS> struct ActStage {
+template <typename T, int UPS, int RCAP = 16> struct ActStage { // RCAP: most rows (8 or 16)
     static constexpr int PL = Traits<T>::PLANES, EPU = 16 / (int)sizeof(T);
-    static constexpr int SLOTS = PL * 16 * UPS; // pieces of a step at 16 rows
+    static constexpr int SLOTS = PL * RCAP * UPS; // pieces of a step at RCAP rows
     static constexpr int NDMA = SLOTS / 64;     // ... and the instructions that bring them
     static constexpr int BYTES = (SLOTS + 1) * 16; // LDS of one step of one wave (the last slot holds zeros)
     typedef const void __attribute__((address_space(1))) *gptr;
@@ -217,7 +217,7 @@ template <typename T, int UPS> struct ActStage {
 
     // row0: first row of the tile; K: reduction length (a multiple of EPU)
     __device__ __forceinline__ void init(const GemmArgs &a, int row0, int K, int lane) {
-        rows = min(a.R - row0, 16);
+        rows = min(a.R - row0, RCAP);
         npiece = PL * rows * UPS;
         kmax = K - EPU;
 #pragma unroll
@@ -243,7 +243,7 @@ template <typename T, int UPS> struct ActStage {
         return c < rows ? ((pl * rows + c) * UPS + (unit ^ (c & (UPS - 1)))) * 16 : SLOTS * 16;
     }
 };
-// every load of the wave has landed (weights in registers, activations in LDS); the compiler may not move LDS reads above
+// every load of the wave has landed (in registers or in LDS); the compiler may not move LDS reads above
 __device__ __forceinline__ void act_stage_wait() {
     __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
     asm volatile("" ::: "memory");
@@ -269,10 +269,18 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &a, const float (&r
     apply_epilogue<T, EPI>(a, r, n0, rt, pre);
 }
 
-// NW = wavefronts per workgroup (interleaved over K), U = 128-byte steps in flight per wave; blockIdx.y = row tile
-template <typename T, int EPI, int NW, int U>
+// The kernel for at most 16 rows: NW = wavefronts per workgroup (interleaved over K), U = 128-byte steps in flight per
+// wave, RCAP = most rows (8 or 16: sizes the LDS); blockIdx.x = column tile (pair), blockIdx.y = row tile.
+// The weights go through LDS like the activations: loaded straight into MFMA operand layout, a load instruction takes
+// 64 bytes of each of 16 weight rows (four lanes per row), i.e. half a cache line per row; a load-to-LDS instruction
+// whose lane l brings unit l & 7 of row l >> 3 takes whole 128-byte lines of 8 rows, and two of them bring a step's
+// 16 x 128 bytes, which the lanes then read from LDS as operands (same xor placement as the activations).  Measured
+// on the 7B-shaped layer: 5-row pass 3.28 -> 3.05 ms, 1 row 3.09 -> 2.99 (requests of whole lines are what counts:
+// timing-only variants with a tile-major weight order gained 6 % with a contiguous kilobyte per instruction and
+// nothing with half lines).
+template <typename T, int EPI, int NW, int U, int RCAP>
 __global__ __launch_bounds__(NW * 64) void gemm_kernel(GemmArgs a) {
-    constexpr int E = Traits<T>::E, KB = 4 * E;
+    constexpr int E = Traits<T>::E, KB = 4 * E, EPU = 16 / (int)sizeof(T);
     constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 15, g = lane >> 4;
@@ -293,14 +301,16 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(GemmArgs a) {
     }
     const int nrows_w = (EPI == EPI_SWIGLU) ? 2 * a.N : a.N;
 
+    // this lane's pieces of a weight step: instruction i brings rows 8i .. 8i + 7 of the tile, lane l unit
+    // (l & 7) xor (row & 7) of row 8i + (l >> 3), into slot 64 i + l = row * 8 + (l & 7)
     const T *W = reinterpret_cast<const T *>(a.W);
-    const T *wrow[NT];
+    const T *wsrc[NT][2];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        int n = n0[t] + c;
-        if (n > nrows_w - 1) n = nrows_w - 1; // ragged last tile: load a valid row, masked at the store
-        wrow[t] = W + (size_t)n * K + g * E;
-    }
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) wsrc[t][i] = W + (size_t)min(n0[t] + 8 * i + (lane >> 3), nrows_w - 1) * K; // ragged last tile: a valid row, masked at the store
+    const int wucol = ((lane & 7) ^ (lane >> 3)) * EPU;
+    const int kmax = K - EPU;
 
     f32x4 acc[NT];
 #pragma unroll
@@ -316,54 +326,74 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(GemmArgs a) {
         rs = deferred_row_scale(a, nsq);
     }
 
-    // Each wave takes 128-byte steps (two k-blocks) of every row, interleaved with the other waves,
-    // U steps per iteration so that 2*U*NT weight loads are in flight per lane before the first MFMA.
+    // Each wave takes 128-byte steps (two k-blocks) of every row, interleaved with the other waves, U steps per
+    // iteration: all their loads are in flight before the first MFMA.
     // Every workgroup starts at another place of K and wraps around (k_rotation): with all of them walking K in step,
     // the loads of a moment differ by multiples of the row stride and meet in the same memory channels, and all ask
     // for the same activation lines (measured on the 7B-shaped layer: 6 % of the 5-row pass, QKV 33.3 -> 29.7 us).
     const int nkb = (K + KB - 1) / KB;
     const int nst = (nkb + 1) / 2;
     const int rot = k_rotation(nst);
-    typedef ActStage<T, 8> Stage; // a step = 8 units per row and plane; lane (c, g) reads unit 4j + g for k-block j
-    __shared__ __align__(16) unsigned char alds[NW][U][Stage::BYTES];
+    const bool ragged = (K % (2 * KB)) != 0; // the last step ends inside its 128 bytes
+    typedef ActStage<T, 8, RCAP> Stage;
+    constexpr int WBYTES = NT * 2048;
+    __shared__ __align__(16) unsigned char lds[NW][U][WBYTES + Stage::BYTES];
+    typedef const void __attribute__((address_space(1))) *gptr;
+    typedef void __attribute__((address_space(3))) *lptr;
     Stage stage;
     stage.init(a, rt * 16, K, lane);
-    int rdoff[2][Stage::PL];
+    int rdw[2], rda[2][Stage::PL];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 2; ++j) {
+        rdw[j] = (c * 8 + ((4 * j + g) ^ (c & 7))) * 16;
 #pragma unroll
-        for (int pl = 0; pl < Stage::PL; ++pl) rdoff[j][pl] = stage.operand_offset(c, 4 * j + g, pl);
+        for (int pl = 0; pl < Stage::PL; ++pl) rda[j][pl] = WBYTES + stage.operand_offset(c, 4 * j + g, pl);
+    }
 #pragma unroll
-    for (int s = 0; s < U; ++s) Stage::clear(alds[wave][s], lane);
-    for (int kp = wave; 2 * kp < nkb; kp += U * NW) {
-        u32x4 w[U][NT][2];
-        Act<T> av[U][2];
+    for (int s = 0; s < U; ++s) Stage::clear(lds[wave][s] + WBYTES, lane);
+    for (int kp = wave; kp < nst; kp += U * NW) {
 #pragma unroll
         for (int s = 0; s < U; ++s) {
-            const int k0 = 2 * rotated(kp + s * NW, rot, nst) * KB; // (a step past the end: zero weights)
+            if (kp + s * NW < nst) { // (the same for the whole wave)
+                const int k0 = 2 * rotated(kp + s * NW, rot, nst) * KB;
+                const int kw = min(k0 + wucol, kmax); // past a ragged end: the row's last unit, zeroed after the read
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int k = k0 + j * KB;
-                const bool ok = k + g * E < K; // K is a multiple of E
+                for (int t = 0; t < NT; ++t)
 #pragma unroll
-                for (int t = 0; t < NT; ++t) w[s][t][j] = ok ? ld16_global(wrow[t] + k) : zero16();
+                    for (int i = 0; i < 2; ++i)
+                        __builtin_amdgcn_global_load_lds((gptr)(wsrc[t][i] + kw), (lptr)(lds[wave][s] + t * 2048 + i * 1024), 16, 0, 0);
+                stage.request(lds[wave][s] + WBYTES, k0);
             }
-            stage.request(alds[wave][s], k0);
         }
         act_stage_wait();
 #pragma unroll
-        for (int s = 0; s < U; ++s)
+        for (int s = 0; s < U; ++s) {
+            if (kp + s * NW < nst) {
+                const int st = rotated(kp + s * NW, rot, nst);
+                u32x4 w[NT][2];
+                Act<T> av[2];
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < 2; ++j) {
 #pragma unroll
-                for (int pl = 0; pl < Stage::PL; ++pl) av[s][j].p[pl] = *reinterpret_cast<const u32x4 *>(alds[wave][s] + rdoff[j][pl]);
-        asm volatile("" ::: "memory"); // ... nor below the next requests
+                    for (int t = 0; t < NT; ++t) w[t][j] = *reinterpret_cast<const u32x4 *>(lds[wave][s] + t * 2048 + rdw[j]);
 #pragma unroll
-        for (int s = 0; s < U; ++s)
+                    for (int pl = 0; pl < Stage::PL; ++pl) av[j].p[pl] = *reinterpret_cast<const u32x4 *>(lds[wave][s] + rda[j][pl]);
+                }
+                if (ragged && st == nst - 1) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+                    for (int j = 0; j < 2; ++j)
+                        if ((2 * st + j) * KB + g * E >= K) {
 #pragma unroll
-                for (int t = 0; t < NT; ++t) acc[t] = mma(acc[t], w[s][t][j], av[s][j]);
+                            for (int t = 0; t < NT; ++t) w[t][j] = zero16();
+                        }
+                }
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) acc[t] = mma(acc[t], w[t][j], av[j]);
+            }
+        }
+        asm volatile("" ::: "memory"); // the reads stay above the next requests
     }
 
     // fixed-order sum of the waves' partial tiles; wave 0 applies the epilogue
@@ -967,6 +997,11 @@ template <typename T, int EPI, int NW, int RT, int QB = 0> static int launch_wid
 
 template <typename T, int EPI, int QB> static int launch_wide_any(const GemmArgs &a, int tiles, int row_tiles, hipStream_t st);
 
+template <typename T, int EPI, int NW, int U> static void launch_narrow(const GemmArgs &a, int tiles, hipStream_t st) {
+    if (a.R <= 8) hipLaunchKernelGGL((gemm_kernel<T, EPI, NW, U, 8>), dim3(tiles, 1), dim3(NW * 64), 0, st, a);
+    else hipLaunchKernelGGL((gemm_kernel<T, EPI, NW, U, 16>), dim3(tiles, 1), dim3(NW * 64), 0, st, a);
+}
+
 template <typename T, int EPI> static int launch_gemm_t(const GemmArgs &a, hipStream_t st) {
     int tiles;
     if (EPI == EPI_QKV) tiles = 3 * a.H * (a.hd / 32);
@@ -974,10 +1009,11 @@ template <typename T, int EPI> static int launch_gemm_t(const GemmArgs &a, hipSt
     const int row_tiles = (a.R + 15) / 16;
     if (row_tiles <= 1) { // the verify pass proper: the waves of a workgroup split K, two steps in flight each
         // fused epilogues (688 gate/up pairs, 384 rotary pairs at the 7B shape: several workgroups per compute unit anyway)
-        // run 2 waves per workgroup, the projections with 256 tiles 8: measured over (1 | 2 | 3 | 4 | 5 | 6 | 8 | 16 waves)
-        // x (1 - 8 steps in flight) per kind of epilogue on the 7B-shaped layer
-        if (EPI == EPI_SWIGLU || EPI == EPI_QKV) hipLaunchKernelGGL((gemm_kernel<T, EPI, 2, 2>), dim3(tiles, 1), dim3(2 * 64), 0, st, a);
-        else hipLaunchKernelGGL((gemm_kernel<T, EPI, 8, 2>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
+        // run 2 (gate/up) and 4 (QKV) waves per workgroup, the projections with 256 tiles 8: measured over
+        // (2 | 3 | 4 | 5 | 6 | 8 | 16 waves) x (1 - 5 steps in flight) per kind of epilogue on the 7B-shaped layer
+        if (EPI == EPI_QKV) launch_narrow<T, EPI, 4, 2>(a, tiles, st);
+        else if (EPI == EPI_SWIGLU) launch_narrow<T, EPI, 2, 2>(a, tiles, st);
+        else launch_narrow<T, EPI, 8, 2>(a, tiles, st);
         return (EPI == EPI_RESID && a.nsq_out) ? 2 : 0;
     }
     return launch_wide_any<T, EPI, 0>(a, tiles, row_tiles, st);
