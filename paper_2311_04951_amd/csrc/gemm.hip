@@ -243,6 +243,10 @@ template <typename T, int UPS, int RCAP = 16> struct ActStage { // RCAP: most ro
         return c < rows ? ((pl * rows + c) * UPS + (unit ^ (c & (UPS - 1)))) * 16 : SLOTS * 16;
     }
 };
+// cache policy of the weight loads (the non-temporal bit of a load-to-LDS instruction): a weight line is used once,
+// the activation lines by every workgroup.  Measured on the 7B-shaped bf16 pass: 3.04 -> 2.85 ms at 5 rows,
+// 2.97 -> 2.75 at 1 row (int8 -3.6 %, int4 -2.5 %); the scope bits on top of it change nothing.
+constexpr int WEIGHT_STREAM = 2;
 // every load of the wave has landed (in registers or in LDS); the compiler may not move LDS reads above
 __device__ __forceinline__ void act_stage_wait() {
     __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
@@ -361,7 +365,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(GemmArgs a) {
                 for (int t = 0; t < NT; ++t)
 #pragma unroll
                     for (int i = 0; i < 2; ++i)
-                        __builtin_amdgcn_global_load_lds((gptr)(wsrc[t][i] + kw), (lptr)(lds[wave][s] + t * 2048 + i * 1024), 16, 0, 0);
+                        __builtin_amdgcn_global_load_lds((gptr)(wsrc[t][i] + kw), (lptr)(lds[wave][s] + t * 2048 + i * 1024), 16, 0, WEIGHT_STREAM);
                 stage.request(lds[wave][s] + WBYTES, k0);
             }
         }
@@ -408,10 +412,11 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(GemmArgs a) {
 
 // ---- weight-only int8 matrices (the quantised model Sections 2 and 3 assume; one fp32 scale per output row)
 //
-// Same decomposition as gemm_kernel for at most 16 rows.  A lane's 16-byte load holds 16 consecutive K
-// entries of its weight row, i.e. two MFMA k-blocks: lane (c, g) supplies k = 64*step + 16*g + 8*j .. +7 to
-// block j, and reads the activations of exactly those k.  An int8 value is exact in bf16, the sum runs
-// in fp32, and the row scale multiplies the finished sum, so the only roundings are those of the sum.
+// Same decomposition as gemm_kernel for at most 16 rows, a step being 128 entries of K (a 128-byte line of a weight
+// row).  A lane's 16-byte unit holds 16 consecutive K entries of its weight row, i.e. two MFMA k-blocks: lane (c, g)
+// supplies k = 128*step + 64*h + 16*g + 8*j .. +7 to block (h, j), and reads the activations of exactly those k.  An
+// int8 value is exact in bf16, the sum runs in fp32, and the row scale multiplies the finished sum, so the only
+// roundings are those of the sum.
 __device__ __forceinline__ uint32_t w8_pair_to_bf16x2(uint32_t x, int first_byte) {
     const float f0 = (float)((int)(x << (24 - 8 * first_byte)) >> 24); // sign-extended bytes
     const float f1 = (float)((int)(x << (16 - 8 * first_byte)) >> 24);
@@ -421,7 +426,7 @@ __device__ __forceinline__ u32x4 w8_to_bf16x8(uint32_t a, uint32_t b) {
     return u32x4{w8_pair_to_bf16x2(a, 0), w8_pair_to_bf16x2(a, 2), w8_pair_to_bf16x2(b, 0), w8_pair_to_bf16x2(b, 2)};
 }
 
-template <int EPI, int NW, int U>
+template <int EPI, int NW, int U, int RCAP>
 __global__ __launch_bounds__(NW * 64) void gemm_w8_kernel(GemmArgs a) {
     typedef bf16_t T;
     constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
@@ -443,14 +448,17 @@ __global__ __launch_bounds__(NW * 64) void gemm_w8_kernel(GemmArgs a) {
     }
     const int nrows_w = (EPI == EPI_SWIGLU) ? 2 * a.N : a.N;
 
+    // a step is 128 entries of K, a whole 128-byte line of every weight row; as in gemm_kernel the tile's 16 x 128 bytes
+    // come through LDS by two load-to-LDS instructions (lane l: unit (l & 7) xor (row & 7) of row 8i + (l >> 3))
     const int8_t *W = reinterpret_cast<const int8_t *>(a.W);
-    const int8_t *wrow[NT];
+    const int8_t *wsrc[NT][2];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        int n = n0[t] + c;
-        if (n > nrows_w - 1) n = nrows_w - 1; // ragged last tile: a valid row, masked at the store
-        wrow[t] = W + (size_t)n * K + g * 16;
-    }
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) wsrc[t][i] = W + (size_t)min(n0[t] + 8 * i + (lane >> 3), nrows_w - 1) * K; // ragged last tile: a valid row, masked at the store
+    const int wucol = ((lane & 7) ^ (lane >> 3)) * 16;
+    const int kmax = K - 16; // K is a multiple of 16
+
     f32x4 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -458,56 +466,77 @@ __global__ __launch_bounds__(NW * 64) void gemm_w8_kernel(GemmArgs a) {
     EpiPre pre;
     if (PRE && wave == 0) epi_prefetch<T, EPI>(a, n0, 0, pre);
     // the row scale of a deferred norm on the activations (1 otherwise), worked out by the epilogue's wave up front
-    float rs[1];
-#pragma unroll
-    for (int r = 0; r < 1; ++r) rs[r] = 1.0f;
+    float rs = 1.0f;
     if (a.act_nsq && wave == 0) {
-#pragma unroll
-        for (int r = 0; r < 1; ++r) {
-            float4 nsq[NSQ4];
-            nsq_prefetch(a, 0 + r, nsq);
-            rs[r] = deferred_row_scale(a, nsq);
-        }
+        float4 nsq[NSQ4];
+        nsq_prefetch(a, 0, nsq);
+        rs = deferred_row_scale(a, nsq);
     }
 
-    const int nsteps = (K + 63) / 64; // 64 entries of K (64 bytes of a weight row) per step
+    const int nsteps = (K + 127) / 128;
     const int rot = k_rotation(nsteps); // (see gemm_kernel)
-    typedef ActStage<T, 8> Stage; // a step = 8 units per row and plane; lane (c, g) reads unit 2g + j for k-block j
-    __shared__ __align__(16) unsigned char alds[NW][U][Stage::BYTES];
+    const bool ragged = (K % 128) != 0;
+    // lane (c, g) reads units g and 4 + g of its weight row: entries 64h + 16g .. + 15, i.e. two k-blocks (j = 0, 1) of 8
+    // entries each, whose activations are unit 8h + 2g + j of the row's 16
+    typedef ActStage<T, 16, RCAP> Stage;
+    constexpr int WBYTES = NT * 2048;
+    __shared__ __align__(16) unsigned char lds[NW][U][WBYTES + Stage::BYTES];
+    typedef const void __attribute__((address_space(1))) *gptr;
+    typedef void __attribute__((address_space(3))) *lptr;
     Stage stage;
     stage.init(a, 0, K, lane);
-    int rdoff[2][Stage::PL];
+    int rdw[2], rda[2][2][Stage::PL];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int h = 0; h < 2; ++h) {
+        rdw[h] = (c * 8 + ((4 * h + g) ^ (c & 7))) * 16;
 #pragma unroll
-        for (int pl = 0; pl < Stage::PL; ++pl) rdoff[j][pl] = stage.operand_offset(c, 2 * g + j, pl);
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-    for (int s = 0; s < U; ++s) Stage::clear(alds[wave][s], lane);
+            for (int pl = 0; pl < Stage::PL; ++pl) rda[h][j][pl] = WBYTES + stage.operand_offset(c, 8 * h + 2 * g + j, pl);
+    }
+#pragma unroll
+    for (int s = 0; s < U; ++s) Stage::clear(lds[wave][s] + WBYTES, lane);
     for (int ks = wave; ks < nsteps; ks += U * NW) {
-        u32x4 w[U][NT];
-        Act<T> av[U][2];
 #pragma unroll
         for (int s = 0; s < U; ++s) {
-            const int k = rotated(ks + s * NW, rot, nsteps) * 64; // (a step past the end: zero weights)
-            const bool ok = k + g * 16 < K; // K is a multiple of 16
+            if (ks + s * NW < nsteps) { // (the same for the whole wave)
+                const int k0 = rotated(ks + s * NW, rot, nsteps) * 128;
+                const int kw = min(k0 + wucol, kmax); // past a ragged end: the row's last unit, zeroed after the read
 #pragma unroll
-            for (int t = 0; t < NT; ++t) w[s][t] = ok ? ld16_global(wrow[t] + k) : zero16();
-            stage.request(alds[wave][s], k);
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+                        __builtin_amdgcn_global_load_lds((gptr)(wsrc[t][i] + kw), (lptr)(lds[wave][s] + t * 2048 + i * 1024), 16, 0, WEIGHT_STREAM);
+                stage.request(lds[wave][s] + WBYTES, k0);
+            }
         }
         act_stage_wait();
 #pragma unroll
-        for (int s = 0; s < U; ++s)
+        for (int s = 0; s < U; ++s) {
+            if (ks + s * NW < nsteps) {
+                const int k0 = rotated(ks + s * NW, rot, nsteps) * 128;
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+                for (int h = 0; h < 2; ++h) {
+                    u32x4 w[NT];
+                    Act<T> av[2];
 #pragma unroll
-                for (int pl = 0; pl < Stage::PL; ++pl) av[s][j].p[pl] = *reinterpret_cast<const u32x4 *>(alds[wave][s] + rdoff[j][pl]);
-        asm volatile("" ::: "memory");
+                    for (int t = 0; t < NT; ++t) w[t] = *reinterpret_cast<const u32x4 *>(lds[wave][s] + t * 2048 + rdw[h]);
 #pragma unroll
-        for (int s = 0; s < U; ++s)
+                    for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+                        for (int pl = 0; pl < Stage::PL; ++pl) av[j].p[pl] = *reinterpret_cast<const u32x4 *>(lds[wave][s] + rda[h][j][pl]);
+                    if (ragged && k0 + 64 * h + 16 * g >= K) {
 #pragma unroll
-                for (int t = 0; t < NT; ++t) acc[t] = mma(acc[t], w8_to_bf16x8(w[s][t][2 * j], w[s][t][2 * j + 1]), av[s][j]);
+                        for (int t = 0; t < NT; ++t) w[t] = zero16();
+                    }
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+#pragma unroll
+                        for (int t = 0; t < NT; ++t) acc[t] = mma(acc[t], w8_to_bf16x8(w[t][2 * j], w[t][2 * j + 1]), av[j]);
+                }
+            }
+        }
+        asm volatile("" ::: "memory"); // the reads stay above the next requests
     }
 
     // fixed-order sum of the waves' partial tiles; wave 0 scales the columns and applies the epilogue
@@ -526,17 +555,17 @@ __global__ __launch_bounds__(NW * 64) void gemm_w8_kernel(GemmArgs a) {
             float sum = red[0][t][v][lane];
 #pragma unroll 4
             for (int w2 = 1; w2 < NW; ++w2) sum += red[w2][t][v][lane];
-            r[t][v] = sum * a.wscale[min(n0[t] + 4 * g + v, nrows_w - 1)] * rs[0];
+            r[t][v] = sum * a.wscale[min(n0[t] + 4 * g + v, nrows_w - 1)] * rs;
         }
     apply_epilogue<T, EPI>(a, r, n0, 0, PRE ? &pre : nullptr);
 }
 
 // ---- weight-only int4 matrices with one scale per group of 128 K entries (the coarser reading of the same
-// quantised model).  A lane's 16-byte load holds 32 consecutive K entries of its weight row, i.e. four MFMA
-// k-blocks (dword j = entries 8j..8j+7, entry e in bits 4e..4e+3, two's complement): a step covers 128 entries
-// of K for the 16 rows, which is exactly one scale group, so a step accumulates into a fresh tile and the
-// tile is added to the running sum times the group's scales of the lane's four output columns
-// (scales are stored group-major, scale[group][column]).  K is a multiple of 128.
+// quantised model).  A lane's 16-byte unit holds 32 consecutive K entries of its weight row, i.e. four MFMA
+// k-blocks (dword j = entries 8j..8j+7, entry e in bits 4e..4e+3, two's complement).  A step is a 128-byte line of
+// every weight row = 256 entries of K = two scale groups, the lane's two units being one of each: a group accumulates
+// into a fresh tile and the tile is added to the running sum times the group's scales of the lane's four output
+// columns (scales are stored group-major, scale[group][column]).  K is a multiple of 128.
 __device__ __forceinline__ u32x4 w4_to_bf16x8(uint32_t x) {
     uint32_t r[4];
 #pragma unroll
@@ -548,7 +577,7 @@ __device__ __forceinline__ u32x4 w4_to_bf16x8(uint32_t x) {
     return u32x4{r[0], r[1], r[2], r[3]};
 }
 
-template <int EPI, int NW, int U>
+template <int EPI, int NW, int U, int RCAP>
 __global__ __launch_bounds__(NW * 64) void gemm_w4_kernel(GemmArgs a) {
     typedef bf16_t T;
     constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
@@ -570,17 +599,20 @@ __global__ __launch_bounds__(NW * 64) void gemm_w4_kernel(GemmArgs a) {
     }
     const int nrows_w = (EPI == EPI_SWIGLU) ? 2 * a.N : a.N;
 
+    // the tile's 16 x 128 bytes of a step come through LDS by two load-to-LDS instructions, as in gemm_kernel
+    // (lane l: unit (l & 7) xor (row & 7) of row 8i + (l >> 3))
     const unsigned char *W = reinterpret_cast<const unsigned char *>(a.W);
-    const unsigned char *wrow[NT];
+    const unsigned char *wsrc[NT][2];
     int ncol[NT][4]; // the lane's four output columns (weight rows 4g + v of the tile), clamped into the matrix
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        int n = n0[t] + c;
-        if (n > nrows_w - 1) n = nrows_w - 1; // ragged last tile: a valid row, masked at the store
-        wrow[t] = W + (size_t)n * (K / 2) + g * 16;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) wsrc[t][i] = W + (size_t)min(n0[t] + 8 * i + (lane >> 3), nrows_w - 1) * (K / 2); // ragged last tile: a valid row, masked at the store
 #pragma unroll
         for (int v = 0; v < 4; ++v) ncol[t][v] = min(n0[t] + 4 * g + v, nrows_w - 1);
     }
+    const int wucol = ((lane & 7) ^ (lane >> 3)) * 16; // bytes
+    const int bmax = K / 2 - 16;
     // calls of more than 16 rows: one workgroup per (column tile, row tile); every row tile streams the (quarter-size)
     // weights again
     const int rt = blockIdx.y;
@@ -592,66 +624,80 @@ __global__ __launch_bounds__(NW * 64) void gemm_w4_kernel(GemmArgs a) {
     EpiPre pre;
     if (PRE && wave == 0) epi_prefetch<T, EPI>(a, n0, rt, pre);
     // the row scale of a deferred norm on the activations (1 otherwise), worked out by the epilogue's wave up front
-    float rs[1];
-#pragma unroll
-    for (int r = 0; r < 1; ++r) rs[r] = 1.0f;
+    float rs = 1.0f;
     if (a.act_nsq && wave == 0) {
-#pragma unroll
-        for (int r = 0; r < 1; ++r) {
-            float4 nsq[NSQ4];
-            nsq_prefetch(a, rt + r, nsq);
-            rs[r] = deferred_row_scale(a, nsq);
-        }
+        float4 nsq[NSQ4];
+        nsq_prefetch(a, rt, nsq);
+        rs = deferred_row_scale(a, nsq);
     }
 
-    const int nsteps = K / 128; // one scale group per step
-    const int rot = k_rotation(nsteps); // (see gemm_kernel)
-    typedef ActStage<T, 16> Stage; // a step = 16 units per row and plane; lane (c, g) reads unit 4g + j for k-block j
-    __shared__ __align__(16) unsigned char alds[NW][U][Stage::BYTES];
+    // lane (c, g) reads units g and 4 + g of its weight row: unit 4h + g is entries 128h + 32g .. + 31 of the step, all in
+    // scale group h, i.e. four k-blocks (j = 0..3) of 8 entries whose activations are unit 16h + 4g + j of the row's 32
+    const int ngroups = K / 128;
+    const int nsteps = (ngroups + 1) / 2; // two scale groups (a 128-byte line of a weight row) per step
+    const int rot = k_rotation(nsteps);   // (see gemm_kernel)
+    typedef ActStage<T, 32, RCAP> Stage;
+    constexpr int WBYTES = NT * 2048;
+    __shared__ __align__(16) unsigned char lds[NW][U][WBYTES + Stage::BYTES];
+    typedef const void __attribute__((address_space(1))) *gptr;
+    typedef void __attribute__((address_space(3))) *lptr;
     Stage stage;
     stage.init(a, rt * 16, K, lane);
-    int rdoff[4][Stage::PL];
+    int rdw[2];
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int h = 0; h < 2; ++h) rdw[h] = (c * 8 + ((4 * h + g) ^ (c & 7))) * 16;
 #pragma unroll
-        for (int pl = 0; pl < Stage::PL; ++pl) rdoff[j][pl] = stage.operand_offset(c, 4 * g + j, pl);
-#pragma unroll
-    for (int s = 0; s < U; ++s) Stage::clear(alds[wave][s], lane);
+    for (int s = 0; s < U; ++s) Stage::clear(lds[wave][s] + WBYTES, lane);
     for (int ks = wave; ks < nsteps; ks += U * NW) {
-        u32x4 w[U][NT];
-        Act<T> av[U][4];
-        float sc[U][NT][4];
+        float sc[U][2][NT][4];
 #pragma unroll
         for (int s = 0; s < U; ++s) {
-            const int step = ks + s * NW;
-            const bool ok = step < nsteps;
-            const int st2 = ok ? rotated(step, rot, nsteps) : nsteps - 1; // (clamped addresses: every lane issues every load)
+            if (ks + s * NW < nsteps) { // (the same for the whole wave)
+                const int st = rotated(ks + s * NW, rot, nsteps);
+                const int kw = min(st * 128 + wucol, bmax); // past the end (a last step of one group): a valid unit, not used
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                w[s][t] = ok ? ld16_stream(wrow[t] + (size_t)st2 * 64) : zero16();
+                for (int t = 0; t < NT; ++t) {
 #pragma unroll
-                for (int v = 0; v < 4; ++v) sc[s][t][v] = a.wscale[(size_t)st2 * nrows_w + ncol[t][v]];
+                    for (int i = 0; i < 2; ++i)
+                        __builtin_amdgcn_global_load_lds((gptr)(wsrc[t][i] + kw), (lptr)(lds[wave][s] + t * 2048 + i * 1024), 16, 0, WEIGHT_STREAM);
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) sc[s][h][t][v] = a.wscale[(size_t)min(2 * st + h, ngroups - 1) * nrows_w + ncol[t][v]];
+                }
+                stage.request(lds[wave][s] + WBYTES, st * 256);
             }
-            stage.request(alds[wave][s], st2 * 128);
         }
         act_stage_wait();
 #pragma unroll
-        for (int s = 0; s < U; ++s)
+        for (int s = 0; s < U; ++s) {
+            if (ks + s * NW < nsteps) {
+                const int st = rotated(ks + s * NW, rot, nsteps);
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+                for (int h = 0; h < 2; ++h) {
+                    if (2 * st + h < ngroups) { // (the same for the whole wave)
+                        u32x4 w[NT];
+                        Act<T> av[4];
 #pragma unroll
-                for (int pl = 0; pl < Stage::PL; ++pl) av[s][j].p[pl] = *reinterpret_cast<const u32x4 *>(alds[wave][s] + rdoff[j][pl]);
-        asm volatile("" ::: "memory");
+                        for (int t = 0; t < NT; ++t) w[t] = *reinterpret_cast<const u32x4 *>(lds[wave][s] + t * 2048 + rdw[h]);
 #pragma unroll
-        for (int s = 0; s < U; ++s)
+                        for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                f32x4 part = f32x4{0.f, 0.f, 0.f, 0.f};
+                            for (int pl = 0; pl < Stage::PL; ++pl)
+                                av[j].p[pl] = *reinterpret_cast<const u32x4 *>(lds[wave][s] + WBYTES + stage.operand_offset(c, 16 * h + 4 * g + j, pl));
 #pragma unroll
-                for (int j = 0; j < 4; ++j) part = mma(part, w4_to_bf16x8(w[s][t][j]), av[s][j]);
+                        for (int t = 0; t < NT; ++t) {
+                            f32x4 part = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int v = 0; v < 4; ++v) acc[t][v] += sc[s][t][v] * part[v];
+                            for (int j = 0; j < 4; ++j) part = mma(part, w4_to_bf16x8(w[t][j]), av[j]);
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) acc[t][v] += sc[s][h][t][v] * part[v];
+                        }
+                    }
+                }
             }
+        }
+        asm volatile("" ::: "memory"); // the reads stay above the next requests
     }
 
     // fixed-order sum of the waves' partial tiles; wave 0 applies the epilogue
@@ -662,7 +708,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_w4_kernel(GemmArgs a) {
         for (int v = 0; v < 4; ++v) red[wave][t][v][lane] = acc[t][v];
     __syncthreads();
     if (wave != 0) return;
-    tile_epilogue<T, EPI, NW>(a, red, n0, rt, PRE ? &pre : nullptr, rs[0]);
+    tile_epilogue<T, EPI, NW>(a, red, n0, rt, PRE ? &pre : nullptr, rs);
 }
 
 // More than 16 rows (larger batches, prefill): the waves of a workgroup split the output columns instead
@@ -1044,20 +1090,51 @@ template <typename T, int EPI, int QB> static int launch_wide_any(const GemmArgs
     }
 }
 
-// Two steps in flight per wave; 8 waves per workgroup for the projections with few tiles, 4 for the fused epilogues
-// (measured per kind of epilogue on the 7B-shaped layer among (2 | 3 | 4 | 8 | 16 waves) x (1..4 steps)).
+// (a shape whose LDS does not fit at this row count runs with 8 waves and one step in flight)
+template <int EPI, int NW, int U> static void launch_w8(const GemmArgs &a, int tiles, hipStream_t st) {
+    constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
+    constexpr int red = NW * NT * 4 * 64 * 4;
+    constexpr bool fit8 = NW * U * (NT * 2048 + ActStage<bf16_t, 16, 8>::BYTES) + red <= 160 * 1024;
+    constexpr bool fit16 = NW * U * (NT * 2048 + ActStage<bf16_t, 16, 16>::BYTES) + red <= 160 * 1024;
+    if (a.R <= 8) {
+        if constexpr (fit8) hipLaunchKernelGGL((gemm_w8_kernel<EPI, NW, U, 8>), dim3(tiles, 1), dim3(NW * 64), 0, st, a);
+        else hipLaunchKernelGGL((gemm_w8_kernel<EPI, 8, 1, 8>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
+    } else {
+        if constexpr (fit16) hipLaunchKernelGGL((gemm_w8_kernel<EPI, NW, U, 16>), dim3(tiles, 1), dim3(NW * 64), 0, st, a);
+        else hipLaunchKernelGGL((gemm_w8_kernel<EPI, 8, 1, 16>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
+    }
+}
+
+// 8 waves per workgroup for the projections with few tiles, 4 for the fused epilogues; one or two steps in flight per
+// wave (measured per kind of epilogue on the 7B-shaped layer among (2 | 3 | 4 | 5 | 6 | 7 | 8 | 16 waves) x (1..3 steps))
 template <int EPI> static int launch_gemm_w8(const GemmArgs &a, hipStream_t st) {
     const int tiles = EPI == EPI_QKV ? 3 * a.H * (a.hd / 32) : (a.N + 15) / 16;
     const int row_tiles = (a.R + 15) / 16;
     if (row_tiles > 1) return launch_wide_any<bf16_t, EPI, 8>(a, tiles, row_tiles, st);
-    if (EPI == EPI_SWIGLU || EPI == EPI_QKV) hipLaunchKernelGGL((gemm_w8_kernel<EPI, 4, 2>), dim3(tiles, 1), dim3(4 * 64), 0, st, a);
-    else hipLaunchKernelGGL((gemm_w8_kernel<EPI, 8, 2>), dim3(tiles, 1), dim3(8 * 64), 0, st, a);
+    if (EPI == EPI_QKV) launch_w8<EPI, 4, 2>(a, tiles, st);
+    else if (EPI == EPI_SWIGLU) launch_w8<EPI, 4, 1>(a, tiles, st);
+    else if (EPI == EPI_RESID) launch_w8<EPI, 8, 2>(a, tiles, st);
+    else launch_w8<EPI, 8, 1>(a, tiles, st);
     return (EPI == EPI_RESID && a.nsq_out) ? 2 : 0;
 }
 
-// 4 waves with one step in flight for the fused epilogues, 8 waves with two for the projections: measured best of
-// (2 | 3 | 4 | 8 waves) x (1 | 2 steps) on the 7B-shaped layer (a step holds a weight load, the four scale loads and up
-// to 8 load-to-LDS instructions per tile)
+// One step in flight; 8 waves for the residual projections, 4 for the fused epilogues and the LM head: measured best of
+// (2 | 3 | 4 | 5 | 6 | 8 waves) x (1 | 2 | 3 steps) on the 7B-shaped layer
+// (a shape whose LDS does not fit at this row count runs with 4 waves and one step in flight)
+template <int EPI, int NW, int U> static void launch_w4(const GemmArgs &a, int tiles, int row_tiles, hipStream_t st) {
+    constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
+    constexpr int red = NW * NT * 4 * 64 * 4;
+    constexpr bool fit8 = NW * U * (NT * 2048 + ActStage<bf16_t, 32, 8>::BYTES) + red <= 160 * 1024;
+    constexpr bool fit16 = NW * U * (NT * 2048 + ActStage<bf16_t, 32, 16>::BYTES) + red <= 160 * 1024;
+    if (a.R <= 8) {
+        if constexpr (fit8) hipLaunchKernelGGL((gemm_w4_kernel<EPI, NW, U, 8>), dim3(tiles, row_tiles), dim3(NW * 64), 0, st, a);
+        else hipLaunchKernelGGL((gemm_w4_kernel<EPI, 4, 1, 8>), dim3(tiles, row_tiles), dim3(4 * 64), 0, st, a);
+    } else {
+        if constexpr (fit16) hipLaunchKernelGGL((gemm_w4_kernel<EPI, NW, U, 16>), dim3(tiles, row_tiles), dim3(NW * 64), 0, st, a);
+        else hipLaunchKernelGGL((gemm_w4_kernel<EPI, 4, 1, 16>), dim3(tiles, row_tiles), dim3(4 * 64), 0, st, a);
+    }
+}
+
 template <int EPI> static int launch_gemm_w4(const GemmArgs &a, hipStream_t st) {
     const int tiles = EPI == EPI_QKV ? 3 * a.H * (a.hd / 32) : (a.N + 15) / 16;
     const int row_tiles = (a.R + 15) / 16;
@@ -1065,8 +1142,8 @@ template <int EPI> static int launch_gemm_w4(const GemmArgs &a, hipStream_t st) 
     // more than 16 rows: the wide kernel (it reads a lane's four scales as one 16-byte load); otherwise, or with a
     // row count that is not a multiple of 4, one workgroup per (column tile, row tile)
     if (row_tiles > 1 && nrows_w % 4 == 0 && (reinterpret_cast<uintptr_t>(a.wscale) & 15) == 0) return launch_wide_any<bf16_t, EPI, 4>(a, tiles, row_tiles, st);
-    if (EPI == EPI_SWIGLU || EPI == EPI_QKV) hipLaunchKernelGGL((gemm_w4_kernel<EPI, 4, 1>), dim3(tiles, row_tiles), dim3(4 * 64), 0, st, a);
-    else hipLaunchKernelGGL((gemm_w4_kernel<EPI, 8, 2>), dim3(tiles, row_tiles), dim3(8 * 64), 0, st, a);
+    if (EPI == EPI_RESID) launch_w4<EPI, 8, 1>(a, tiles, row_tiles, st);
+    else launch_w4<EPI, 4, 1>(a, tiles, row_tiles, st);
     return (EPI == EPI_RESID && a.nsq_out && row_tiles == 1) ? 2 : 0;
 }
 
