@@ -174,9 +174,8 @@ int ss_model_destroy(ss_model *model);
  * persistent kernel (one workgroup per compute unit, phases ordered by device-wide barriers or by
  * self-validating activations, RMSNorm folded into the GEMMs, weight loads of the next phase in flight
  * across each phase boundary); larger calls still use one kernel per phase.  Measured on the 7B-, 13B- and
- * 3B-shaped models the per-phase path is ahead at almost every row count (by 7 - 13 % at 1 - 5 rows of the 7B
- * shape, 10 - 18 % on the narrower model; the persistent kernel by 1 % at 5 rows of the 13B shape), which is
- * why the simpler one is the default.  Both paths
+ * 3B-shaped models the per-phase path is ahead at every row count from 1 to 9 (by 28 - 39 % on the 7B shape,
+ * 35 - 50 % on the other two), which is why the simpler one is the default.  Both paths
  * produce results within the same tolerance of the method; SS_EINVAL if `on` is set and the persistent
  * kernel is not available on this device (it needs every workgroup co-resident, and matrices in the
  * storage type). */
