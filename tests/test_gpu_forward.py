@@ -57,6 +57,29 @@ def test_bf16_verify_logits_match_oracle(shape, persistent):
     assert maxabs(got, ref) < 2e-3
 
 
+@pytest.mark.parametrize("kind,shape", [
+    ("f32", si.DecoderShape(2, 256, 4, 64, 344, 333, dtype="f32")),      # K = 344: the last 128-byte step ends inside
+    ("bf16", si.DecoderShape(2, 256, 4, 64, 688, 333, dtype="bf16")),    # K = 688 likewise; 333 columns: a ragged last tile
+    ("int8", si.DecoderShape(2, 256, 4, 64, 688, 333, dtype="bf16")),    # K = 688: a ragged last 128-entry step
+    ("int4", si.DecoderShape(2, 256, 4, 64, 640, 333, dtype="bf16"))])   # K = 640: a last step of one scale group
+def test_every_row_count_of_the_kernels_for_at_most_16_rows_matches_oracle(kind, shape):
+    """Calls of 1, 2, ... 16 rows one after the other on the per-phase path (both sizes of the kernels' LDS staging,
+    every number of load-to-LDS instructions per step), all logits against one oracle pass over the same tokens."""
+    w = si.decoder_weights(shape, 17)
+    kw = {"int8": {"int8_weights": True}, "int4": {"int4_weights": True}}.get(kind, {})
+    om = oracle.Model(shape, w, **kw)
+    gm = sv.Model(shape, weights_to_device(w), max_rows=16, max_pos=256, **kw)
+    set_path(gm, False)
+    chunks = list(range(1, 17))
+    toks = si.token_ids(17, "toks", (sum(chunks),), shape.vocab).numpy()
+    gkv = sv.KVCache(gm, 1, 160)
+    got = _gpu_forward_chunks(gm, gkv, toks, chunks)
+    ref = om.forward(om.new_kv(160), toks)
+    assert maxabs(got, ref) < (tol(shape) if kind in ("f32", "bf16") else 2e-2)
+    assert sv.ss_kv_cache_get_len(gkv).tolist() == [sum(chunks)]
+    assert sv.ss_device_status(gm) == 0
+
+
 @pytest.mark.parametrize("persistent", PATHS)
 def test_rollback_then_reverify_matches_oracle(persistent):
     """Rejected rows are dropped by a length write and overwritten by the next pass (Section 4.4)."""

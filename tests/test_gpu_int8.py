@@ -34,7 +34,7 @@ def _int8_pair(shape, seed, max_pos=256):
     return om, gm, w
 
 
-@pytest.mark.parametrize("shape", [si.DecoderShape(2, 256, 4, 64, 688, 1000, dtype="bf16"),     # K = 688: a ragged last 64-entry step
+@pytest.mark.parametrize("shape", [si.DecoderShape(2, 256, 4, 64, 688, 1000, dtype="bf16"),     # K = 688: a ragged last 128-entry step
                                    si.DecoderShape(1, 128, 4, 32, 336, 515, dtype="bf16")])     # vocabulary not a multiple of 16
 def test_int8_model_forward_matches_int8_oracle(shape):
     om, gm, _ = _int8_pair(shape, 31)
