@@ -577,6 +577,23 @@ __device__ __forceinline__ u32x4 w4_to_bf16x8(uint32_t x) {
     return u32x4{r[0], r[1], r[2], r[3]};
 }
 
+// The same eight entries as bf16 values q + 136 (0x4300 | (q + 8): 128 + n is exact in bf16 for n < 128), without a
+// conversion instruction: flip the sign bits (two's complement -> q + 8), split the even and the odd nibbles into bytes,
+// and let four byte permutes place a pair of them into the low mantissa bits of 0x4300 4300.  About half the vector
+// instructions of w4_to_bf16x8, which bound the kernel for at most 16 rows (its gate/up launch took longer than the
+// int8 one for half the bytes); the caller takes 136 * (sum of the activations of the k-block) off the product.
+// Measured on the 7B-shaped model: 5-row int4 pass -9 %.
+__device__ __forceinline__ u32x4 w4_to_bf16x8_plus136(uint32_t x) {
+    x ^= 0x88888888u;
+    const uint32_t even = x & 0x0F0F0F0Fu, odd = (x >> 4) & 0x0F0F0F0Fu; // byte i: entry 2i / entry 2i + 1
+    uint32_t r[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) // bytes [even.i, 0, odd.i, 0] (selector bytes 0-3: second operand, 4-7: first, 0x0c: zero)
+        r[i] = __builtin_amdgcn_perm(odd, even, 0x0c000c00u | ((4u + i) << 16) | (uint32_t)i) | 0x43004300u;
+    return u32x4{r[0], r[1], r[2], r[3]};
+}
+constexpr float W4_BIAS = 136.0f;
+
 template <int EPI, int NW, int U, int RCAP>
 __global__ __launch_bounds__(NW * 64) void gemm_w4_kernel(GemmArgs a) {
     typedef bf16_t T;
@@ -685,13 +702,18 @@ __global__ __launch_bounds__(NW * 64) void gemm_w4_kernel(GemmArgs a) {
 #pragma unroll
                             for (int pl = 0; pl < Stage::PL; ++pl)
                                 av[j].p[pl] = *reinterpret_cast<const u32x4 *>(lds[wave][s] + WBYTES + stage.operand_offset(c, 16 * h + 4 * g + j, pl));
+                        // the group's activation sums per row (an all-ones weight tile: every output column gets the sum)
+                        f32x4 asum = f32x4{0.f, 0.f, 0.f, 0.f};
+                        const u32x4 ones = u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) asum = mma(asum, ones, av[j]);
 #pragma unroll
                         for (int t = 0; t < NT; ++t) {
                             f32x4 part = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) part = mma(part, w4_to_bf16x8(w[t][j]), av[j]);
+                            for (int j = 0; j < 4; ++j) part = mma(part, w4_to_bf16x8_plus136(w[t][j]), av[j]);
 #pragma unroll
-                            for (int v = 0; v < 4; ++v) acc[t][v] += sc[s][h][t][v] * part[v];
+                            for (int v = 0; v < 4; ++v) acc[t][v] += sc[s][h][t][v] * (part[v] - W4_BIAS * asum[v]);
                         }
                     }
                 }
