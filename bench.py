@@ -33,7 +33,7 @@ PERSISTENT_7B_TRAFFIC_SOURCE = "profiles/verify_pass_7b_persistent_hbm_traffic.t
 ACCEPT_TRAFFIC_BYTES, ACCEPT_TRAFFIC_SOURCE = 366.5e6, "profiles/standalone_accept_hbm_traffic.txt"
 GATEUP_TRAFFIC_BYTES, GATEUP_TRAFFIC_SOURCE = 181.4e6, "profiles/verify_pass_7b_per_phase_hbm_traffic.txt"
 PER_PHASE_PASS_TRAFFIC_BYTES = 13.495e9  # 13.463 GB fetched + 0.032 GB written over the launches of one pass (same file)
-BATCHED_TRAFFIC_BYTES, BATCHED_TRAFFIC_SOURCE = 37.417e9, "profiles/batched_long_context_pass_hbm_traffic.txt"
+BATCHED_TRAFFIC_BYTES, BATCHED_TRAFFIC_SOURCE = 37.412e9, "profiles/batched_long_context_pass_hbm_traffic.txt"
 STORED = " (stored counter measurement of this workload, not taken in this run)"
 
 
