@@ -204,10 +204,10 @@ __device__ __forceinline__ int rotated(int i, int rot, int nst) {
 // 16 bytes each) and the operands are read back from LDS.  Piece (plane * R + row) * UPS + (unit xor row) holds unit
 // `unit` of the row, so that the 16 rows a wave reads together fall into different banks.  Lanes of rows that do not
 // exist read a slot that holds zeros.  Measured on the 7B-shaped layer: 5-row pass 3.62 -> 3.37 ms, 1 row 3.29 -> 3.18.
-template <typename T, int UPS, int RCAP = 16> struct ActStage { // RCAP: most rows (8 or 16)
+template <typename T, int UPS, int RCAP = 16> struct ActStage { // RCAP: most rows (5, 8 or 16)
     static constexpr int PL = Traits<T>::PLANES, EPU = 16 / (int)sizeof(T);
-    static constexpr int SLOTS = PL * RCAP * UPS; // pieces of a step at RCAP rows
-    static constexpr int NDMA = SLOTS / 64;     // ... and the instructions that bring them
+    static constexpr int NDMA = (PL * RCAP * UPS + 63) / 64; // instructions that bring a step at RCAP rows
+    static constexpr int SLOTS = NDMA * 64;                   // ... and the slots they fill
     static constexpr int BYTES = (SLOTS + 1) * 16; // LDS of one step of one wave (the last slot holds zeros)
     typedef const void __attribute__((address_space(1))) *gptr;
     typedef void __attribute__((address_space(3))) *lptr;
@@ -1146,9 +1146,13 @@ template <int EPI> static int launch_gemm_w8(const GemmArgs &a, hipStream_t st) 
 template <int EPI, int NW, int U> static void launch_w4(const GemmArgs &a, int tiles, int row_tiles, hipStream_t st) {
     constexpr int NT = (EPI == EPI_SWIGLU || EPI == EPI_QKV) ? 2 : 1;
     constexpr int red = NW * NT * 4 * 64 * 4;
+    constexpr bool fit5 = NW * U * (NT * 2048 + ActStage<bf16_t, 32, 5>::BYTES) + red <= 160 * 1024;
     constexpr bool fit8 = NW * U * (NT * 2048 + ActStage<bf16_t, 32, 8>::BYTES) + red <= 160 * 1024;
     constexpr bool fit16 = NW * U * (NT * 2048 + ActStage<bf16_t, 32, 16>::BYTES) + red <= 160 * 1024;
-    if (a.R <= 8) {
+    if (a.R <= 5) { // the K + 1 = 5 rows of the usual verify pass: the smaller staging area lets a compute unit hold a workgroup more
+        if constexpr (fit5) hipLaunchKernelGGL((gemm_w4_kernel<EPI, NW, U, 5>), dim3(tiles, row_tiles), dim3(NW * 64), 0, st, a);
+        else hipLaunchKernelGGL((gemm_w4_kernel<EPI, 4, 1, 5>), dim3(tiles, row_tiles), dim3(4 * 64), 0, st, a);
+    } else if (a.R <= 8) {
         if constexpr (fit8) hipLaunchKernelGGL((gemm_w4_kernel<EPI, NW, U, 8>), dim3(tiles, row_tiles), dim3(NW * 64), 0, st, a);
         else hipLaunchKernelGGL((gemm_w4_kernel<EPI, 4, 1, 8>), dim3(tiles, row_tiles), dim3(4 * 64), 0, st, a);
     } else {
